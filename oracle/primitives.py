@@ -1,0 +1,93 @@
+"""TEST INFRASTRUCTURE ONLY - slow, plain CPU definitions of the primitives.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may use
+anything in this package; the product path never does.
+
+Every function here is the textbook definition written out with NumPy, in the
+floating-point type of its inputs (float64 unless a test asks otherwise).
+The paper (Sec. 3.1, "Speculative Prediction Block") only says that a block is
+self-attention, cross-attention to the condition c and a feed-forward network;
+the concrete choices (RMSNorm, rotary positions, tanh-GELU) come from the
+benchmark configuration list and are listed as readings in the design notes.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+HEAD_DIM = 64
+
+
+def bf16_round(x):
+    """Nearest-even rounding to bfloat16, via float32 (the device rounds float32 values)."""
+    x32 = np.ascontiguousarray(x, dtype=np.float32)
+    u = x32.view(np.uint32)
+    r = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
+    y = ((u + r) & np.uint32(0xFFFF0000)).astype(np.uint32).view(np.float32).reshape(x32.shape)
+    return y.astype(np.asarray(x).dtype, copy=False)
+
+
+def rmsnorm(x, g, eps):
+    """x * g / sqrt(mean(x^2) + eps) over the last axis."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * g
+
+
+def gelu_tanh(x):
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+
+
+def softmax(x):
+    z = x - np.max(x, axis=-1, keepdims=True)
+    e = np.exp(z)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def rope(x, pos, base):
+    """Rotary position embedding on [rows, heads, 64] with half-split pairing (i, i+32).
+
+    Pair i is rotated by the angle pos * base**(-i/32)."""
+    half = HEAD_DIM // 2
+    pos = np.asarray(pos, dtype=np.float64)
+    inv = base ** (-np.arange(half, dtype=np.float64) / half)
+    ang = pos[:, None] * inv[None, :]                     # [rows, 32], always float64
+    c = np.cos(ang).astype(x.dtype)[:, None, :]
+    s = np.sin(ang).astype(x.dtype)[:, None, :]
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def attend(q, K, V, limit):
+    """Scaled dot-product attention, one query row at a time over keys [0, limit[row]].
+
+    q [rows, H, 64]; K, V [L, H, 64]; limit[row] is the last visible key (inclusive).
+    Scores are scaled by 1/sqrt(64); softmax in the working precision."""
+    rows, H, _ = q.shape
+    out = np.zeros_like(q)
+    scale = 1.0 / np.sqrt(HEAD_DIM)
+    lim = np.asarray(limit)
+    if rows and np.all(lim == lim[0]):
+        # all rows see the same keys: one batched product per head
+        n = int(lim[0]) + 1
+        s = np.einsum("rhd,khd->hrk", q, K[:n]) * scale
+        out = np.einsum("hrk,khd->rhd", softmax(s), V[:n])
+        return out
+    for r in range(rows):
+        n = int(lim[r]) + 1
+        s = np.einsum("hd,khd->hk", q[r], K[:n]) * scale
+        out[r] = np.einsum("hk,khd->hd", softmax(s), V[:n])
+    return out
+
+
+def attend_causal(q, K, V, first_pos):
+    """Block-causal attention: row r (absolute position first_pos + r) sees keys [0, first_pos + r].
+
+    Same result as attend(q, K, V, first_pos + arange(rows)) but with one masked
+    matrix product per head, for long teacher-forced blocks."""
+    rows, H, _ = q.shape
+    n = first_pos + rows
+    scale = 1.0 / np.sqrt(HEAD_DIM)
+    s = np.einsum("rhd,khd->hrk", q, K[:n]) * scale
+    kk = np.arange(n)[None, :]
+    rr = (first_pos + np.arange(rows))[:, None]
+    s = np.where((kk <= rr)[None, :, :], s, -np.inf)
+    return np.einsum("hrk,khd->rhd", softmax(s), V[:n])

@@ -1,0 +1,309 @@
+"""Invariants that pin the oracle's backbone and decode loop without any other implementation."""
+import os
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import primitives as P
+from oracle import speculative as sp
+from oracle.hourglass import Model, SeqState, forward_block, forward_full
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _model(name, jitter=0.1, **kw):
+    cfg = si.TEST_CONFIGS[name]
+    if kw:
+        cfg = cfg.replace(**kw)
+    return cfg, Model(cfg, si.make_weights(cfg, 0, jitter)), si.make_memory(cfg, 0)
+
+
+def _tokens(cfg, n, seed=3):
+    r = np.random.default_rng(seed)
+    return [cfg.bos] + [int(t) for t in r.integers(0, cfg.n_bins, n - 1)]
+
+
+# -- T1: incremental decoding equals full-sequence recompute ------------------------------
+@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99"])
+def test_incremental_equals_full(name):
+    cfg, m, mem = _model(name)
+    T = 64
+    toks = _tokens(cfg, T)
+    taps = {}
+    full = forward_full(m, toks, mem, taps)
+    tol = 1e-9 if cfg.dtype == "f32" else 2e-2
+    r = np.random.default_rng(5)
+    for trial in range(6):
+        st = SeqState(m, mem, T)
+        i = 0
+        while i < T:
+            B = int(r.integers(1, 20)) if trial else 1
+            B = min(B, T - i)
+            lg = forward_block(m, st, toks[i:i + B], long_block=bool(trial % 2))
+            assert np.abs(lg - full[i:i + B]).max() < tol, (trial, i, B)
+            i += B
+            st.P = i
+            assert SeqState.level_lengths(i) == (i, (i - 1) // 3 + 1, (i - 1) // 9 + 1)
+        if cfg.dtype == "f32":
+            assert np.abs(st.tap["c"][:T] - taps["tap_c"]).max() < 1e-9
+            nv, nf = (T - 1) // 3 + 1, (T - 1) // 9 + 1
+            assert np.abs(st.tap["v"][:nv] - taps["tap_v"]).max() < 1e-9
+            assert np.abs(st.tap["f"][:nf] - taps["tap_f"]).max() < 1e-9
+            assert np.abs(st.y_f[:nf] - taps["y_f"]).max() < 1e-9
+
+
+def test_every_block_length_and_phase():
+    """All block lengths 1..19 from every start phase mod 9, re-verified after a partial commit."""
+    cfg, m, mem = _model("t_f32_c")
+    T = 48
+    toks = _tokens(cfg, T)
+    full = forward_full(m, toks, mem)
+    for P0 in range(0, 9):
+        st = SeqState(m, mem, T)
+        if P0:
+            forward_block(m, st, toks[:P0])
+            st.P = P0
+        for B in range(1, 20):
+            # a wrong block first (rejected drafts must leave no trace) ...
+            junk = toks[P0:P0 + 1] + [(t + 1) % cfg.n_bins for t in toks[P0 + 1:P0 + B]]
+            forward_block(m, st, junk)
+            # ... then the right one
+            lg = forward_block(m, st, toks[P0:P0 + B])
+            assert np.abs(lg - full[P0:P0 + B]).max() < 1e-9, (P0, B)
+
+
+# -- T3: causality ----------------------------------------------------------------------------
+def test_causality_probe():
+    cfg, m, mem = _model("t_f32_99")
+    T = 30
+    toks = _tokens(cfg, T)
+    base = forward_full(m, toks, mem)
+    for qpos in (1, 3, 8, 9, 10, 17, 18, 26):
+        t2 = list(toks)
+        t2[qpos] = (t2[qpos] + 5) % cfg.n_bins
+        out = forward_full(m, t2, mem)
+        assert np.array_equal(out[:qpos], base[:qpos]), qpos
+        assert not np.allclose(out[qpos], base[qpos])
+
+
+def test_hourglass_collapses_when_shortening_is_zero():
+    """With W_s(coord->vertex) = 0 and the coarse levels' cross-attention outputs zeroed, every coarse
+    feature is exactly zero (RMSNorm(0) = 0, no biases), so the model must equal the flat stack
+    cpre -> cpost: pins that upsample adds nothing else."""
+    cfg, m, mem = _model("t_f32_99")
+    m.w["short_cv"] = np.zeros_like(m.w["short_cv"])
+    for k in list(m.w):
+        if k.split(".")[0] in ("vpre", "face", "vpost") and k.endswith(".co"):
+            m.w[k] = np.zeros_like(m.w[k])
+    T = 20
+    toks = _tokens(cfg, T)
+    got = forward_full(m, toks, mem)
+    h = m.embed(toks)
+    pos = np.arange(T)
+    for stack in ("cpre", "cpost"):
+        for i in range(m.layers[stack]):
+            pfx = f"{stack}.{i}."
+            q, k, v = m.qkv(pfx, h, pos)
+            o = P.attend(q, k, v, pos)
+            h = m.after_self_attention(pfx, h, o, *m.mem_kv(pfx, mem))
+    assert np.abs(got - m.logits(h)).max() < 1e-10
+
+
+def test_single_block_is_textbook_attention():
+    """One block with the cross-attention and FFN outputs zeroed is h + Wo * softmax(QK^T/8) V."""
+    cfg, m, mem = _model("t_f32_c", jitter=0.0)
+    pfx = "cpre.0."
+    m.w[pfx + "co"] = np.zeros_like(m.w[pfx + "co"])
+    m.w[pfx + "w2"] = np.zeros_like(m.w[pfx + "w2"])
+    T = 7
+    h = np.random.default_rng(1).standard_normal((T, cfg.d_model))
+    q, k, v = m.qkv(pfx, h, np.zeros(T))          # position 0 everywhere: rotary is the identity
+    out = m.after_self_attention(pfx, h, P.attend_causal(q, k, v, 0), *m.mem_kv(pfx, mem))
+    x = h / np.sqrt(np.mean(h * h, -1, keepdims=True) + cfg.rms_eps)
+    want = h.copy()
+    for r in range(T):
+        for hd in range(cfg.n_heads):
+            sl = slice(64 * hd, 64 * hd + 64)
+            qq = m.w[pfx + "wq"][sl] @ x[r]
+            sc = np.array([qq @ (m.w[pfx + "wk"][sl] @ x[j]) / 8.0 for j in range(r + 1)])
+            wgt = np.exp(sc - sc.max())
+            wgt /= wgt.sum()
+            o = sum(wgt[j] * (m.w[pfx + "wv"][sl] @ x[j]) for j in range(r + 1))
+            want[r] += m.w[pfx + "wo"][:, sl] @ o
+    assert np.abs(out - want).max() < 1e-10
+
+
+# -- T4: speculative greedy == sequential greedy -------------------------------------------------
+@pytest.mark.parametrize("name", ["t_f32_c", "t_f32_99", "t_f32_1815", "t_bf16_99"])
+def test_speculative_equals_sequential_native_heads(name):
+    cfg, m, mem = _model(name)
+    seq, st0 = sp.generate(m, mem, cfg.faces, speculative=False)
+    trace = []
+    spec, st1 = sp.generate(m, mem, cfg.faces, speculative=True, trace=trace)
+    assert seq == spec and len(seq) == 9 * cfg.faces
+    assert st0.P == st1.P == 9 * cfg.faces
+    assert sum(a for _, _, a in trace) == 9 * cfg.faces
+    assert all(1 <= a <= len(b) <= cfg.block_max for _, b, a in trace)
+
+
+def test_speculative_equals_sequential_adversarial_drafts():
+    cfg, m, mem = _model("t_f32_99")
+    faces = 5
+    truth, _ = sp.generate(m, mem, faces, speculative=False)
+    x = [cfg.bos] + truth                      # x[p] = token index p
+    wrong = lambda t: (t + 1) % cfg.n_bins
+    r = np.random.default_rng(11)
+
+    def source(kind, k=None):
+        def fn(st, budget):
+            B = min(cfg.block_max, budget - st.P)
+            true = [x[st.P + i] for i in range(B)]
+            if kind == "correct":
+                return true
+            if kind == "wrong":
+                return [true[0]] + [wrong(t) for t in true[1:]]
+            if kind == "random":
+                return [true[0]] + [int(t) for t in r.integers(0, cfg.n_bins, B - 1)]
+            blk = list(true)                   # corrupted at index k
+            if k < B:
+                blk[k] = wrong(blk[k])
+            return blk
+        return fn
+
+    for kind in ("correct", "wrong", "random"):
+        trace = []
+        out, _ = sp.generate(m, mem, faces, draft_fn=source(kind), trace=trace)
+        assert out == truth, kind
+        if kind == "correct":
+            assert all(a == len(b) for _, b, a in trace)
+        if kind == "wrong":
+            assert all(a == 1 for _, _, a in trace)
+    for k in range(1, cfg.block_max):
+        trace = []
+        out, _ = sp.generate(m, mem, faces, draft_fn=source("corrupt", k), trace=trace)
+        assert out == truth
+        for _, b, a in trace:
+            assert a == min(k, len(b)), (k, len(b), a)
+
+
+def test_accept_truth_table():
+    """Brute force over every match pattern for D = 1..5 drafts (Sec. 3.3: main accepted outright,
+    then the longest run of drafts that equal the backbone's own predictions)."""
+    for D in range(1, 6):
+        for pattern in range(1 << D):
+            y = list(range(100, 100 + D + 1))
+            block = [7] + [y[i] if (pattern >> i) & 1 else -1 for i in range(D)]
+            lead = 0
+            while lead < D and (pattern >> lead) & 1:
+                lead += 1
+            assert sp.accept_length(block, y) == 1 + lead
+
+
+def test_eos_stops_generation():
+    cfg, m, mem = _model("t_f32_99", ban_specials=0)
+    # bias the LM head so that EOS wins everywhere: the first predicted token ends the mesh
+    m.w["lm"][cfg.eos] = 50.0 * m.w["lm"][cfg.eos] + 0.0
+    m.w["gf"] = np.ones_like(m.w["gf"])
+    out, st = sp.generate(m, mem, 3, speculative=True)
+    assert out[-1] == cfg.eos or len(out) == 27
+    if out[-1] == cfg.eos:
+        assert st.finished and cfg.eos not in out[:-1]
+
+
+# -- T5: schedule against the paper's worked example -----------------------------------------------
+def _walk(cfg, m, mem, n_pos):
+    """Commit one true token at a time and record what each level covers at every position s."""
+    st = SeqState(m, mem, 9 * cfg.faces)
+    rec = {}
+    while st.P < n_pos:
+        block = sp.draft(m, st, 9 * cfg.faces)
+        s = st.P - 1
+        if s >= 0:
+            rec[s] = {l: sorted(st.rows[l]) for l in "cvf"} | {"len": len(block)}
+        _, y, _ = sp.verify(m, st, [st.main])
+        sp.commit(m, st, [st.main], y, 1)
+    return rec
+
+
+def test_schedule_9_9_worked_example():
+    gold = {}
+    for line in open(os.path.join(GOLD, "schedule_9_9.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, main, c, p, total, dbl = line.split()
+        gold[name] = ([int(v) for v in c.split(",")], [int(v) for v in p.split(",")], int(total),
+                      [] if dbl == "none" else [int(v) for v in dbl.split(",")])
+    # the example shows the point and coordinate levels only: switch the face level off
+    cfg, m, mem = _model("t_f32_99", draft_face=0, faces=4)
+    rec = _walk(cfg, m, mem, 18)
+    for s in (3, 6, 12, 15):                      # point split nodes that are not face nodes
+        for name, ss in (("at_point_node", s), ("one_position_later", s + 1)):
+            if ss not in rec:
+                continue
+            c, p, total, dbl = gold[name]
+            main = ss + 1
+            assert [t - main for t in rec[ss]["c"]] == c
+            assert [t - main for t in rec[ss]["v"]] == p
+            assert rec[ss]["len"] == total
+            assert sorted(set(rec[ss]["c"]) & set(rec[ss]["v"])) == [main + v for v in dbl]
+        assert rec[s]["f"] == []
+
+
+def test_step_totals_and_rules():
+    for line in open(os.path.join(GOLD, "step_totals.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        n, mm, dc, at_face, at_point = (int(v) for v in line.split())
+        name = "t_f32_1815" if n == 18 else "t_f32_99"
+        cfg, m, mem = _model(name, faces=8)
+        assert (cfg.draft_face, cfg.draft_point, cfg.draft_coord) == (n, mm, dc)
+        rec = _walk(cfg, m, mem, 40)
+        fired_v_at = []
+        for s in sorted(rec):
+            main = s + 1
+            if s % 9 == 0:
+                # rule (B): the face level leaves the first three future tokens to the coordinate level
+                assert rec[s]["f"] == list(range(main + 3, main + n))
+                assert rec[s]["len"] == at_face
+                # rule (A): no fresh point-level rows at a face node (fresh rows would end at main+mm-1)
+                assert main + mm - 1 not in rec[s]["v"]
+            elif s % 3 == 0:
+                assert rec[s]["v"] == list(range(main + 3, main + mm))
+                assert rec[s]["len"] == at_point
+                fired_v_at.append(s)
+            assert rec[s]["c"] == [main + 1, main + 2]
+        assert fired_v_at == [s for s in sorted(rec) if s % 3 == 0 and s % 9 != 0]
+
+
+# -- T7: residual wiring of the draft heads ------------------------------------------------------
+def test_sp_and_hf_residual_wiring():
+    cfg, m, mem = _model("t_f32_99", faces=3)
+    for k, v in m.w.items():
+        if k.startswith("sp.") and k.endswith(".lin"):
+            m.w[k] = np.zeros_like(v)
+        if k.startswith("hf.") and k.endswith(".w2"):
+            m.w[k] = np.zeros_like(v)
+    st = SeqState(m, mem, 27)
+    toks = _tokens(cfg, 14)
+    forward_block(m, st, toks[:13])
+    st.P = 13
+    st.main = toks[13]
+    sp.draft(m, st, 27)
+    s = 12
+    # Eq. 1 with Linear = 0 leaves h_s: every coordinate head predicts from the tapped feature itself
+    want = P.softmax(m.logits(st.tap["c"][s][None]))[0]
+    for tgt in (s + 2, s + 3):
+        assert np.allclose(st.rows["c"][tgt], want, atol=1e-12)
+    # Eq. 6 with FFN = 0 is the identity on the upsampled feature; Eq. 1 then gives the vertex tap
+    v = s // 3
+    want_v = P.softmax(m.logits(st.tap["v"][v][None]))[0]
+    assert sorted(st.rows["v"]) == list(range(3 * v + 4, 3 * v + 10))
+    for tgt in st.rows["v"]:
+        assert np.allclose(st.rows["v"][tgt], want_v, atol=1e-12)
+    # face level (fired at s = 9): with n = 9 there is no face SP head; the face output repeats down
+    f = 1
+    want_f = P.softmax(m.logits(st.y_f[f][None]))[0]
+    assert st.fired_f == f and sorted(st.rows["f"]) == list(range(9 * f + 4, 9 * f + 10))
+    for tgt in st.rows["f"]:
+        assert np.allclose(st.rows["f"][tgt], want_f, atol=1e-12)
