@@ -1,0 +1,142 @@
+/*
+ * flashmesh.h - C ABI of the MI355X (gfx950) predict / verify / commit decode path of an
+ * hourglass transformer over quantised mesh coordinate tokens.
+ *
+ * Token sequence: x_0 = BOS, then 9 coordinate tokens per face, 3 per vertex (supplement,
+ * "Hourglass Transformer").  Input position n predicts x_{n+1}.  One decode step is
+ *     fm_draft  ->  fm_verify_block  ->  fm_commit
+ * i.e. the predict and verify stages of Sec. 3 ("Predict-Correct-Verify Paradigm"); the
+ * correct stage only edits the draft block and plugs in between fm_draft and fm_verify_block
+ * through the caller-visible block buffer.
+ *
+ * Conventions
+ *  - Every function returns 0 on success or a negative FM_E* code; fm_last_error() gives a
+ *    message for the last failure on that context.  Nothing throws or aborts across the ABI.
+ *  - Pointers named *_dev are DEVICE pointers owned by the caller (the library borrows them for
+ *    the duration of the enqueued work); pointers named host_* / *_host are HOST pointers.
+ *  - All device work is enqueued on the hipStream_t given to fm_create.  Only fm_load_weights,
+ *    fm_generate, fm_read_state and fm_destroy synchronise that stream.
+ *  - Weights, K/V caches at the three hourglass levels, pooling / upsampling carries, tapped
+ *    features and draft distributions are owned by the context.
+ *  - Sequences are independent; `batch` sequences are processed together with ragged block
+ *    lengths and ragged accepted lengths.
+ */
+#ifndef FLASHMESH_H
+#define FLASHMESH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FM_OK 0
+#define FM_EINVAL (-1) /* bad argument or configuration                       */
+#define FM_ESTATE (-2) /* call out of order (e.g. weights not loaded)         */
+#define FM_ENOMEM (-3) /* device or host allocation failed                    */
+#define FM_EHIP (-4)   /* a HIP runtime call failed; see fm_last_error        */
+
+#define FM_DTYPE_F32 0  /* fp32 storage and arithmetic                          */
+#define FM_DTYPE_BF16 1 /* bf16 weights / K,V / GEMM inputs, fp32 accumulation  */
+
+typedef struct fm_ctx fm_ctx; /* opaque, owned by the library */
+
+/* Plain-old-data configuration, copied by fm_create.  head_dim = d_model / n_heads must be 64.
+ * vocabulary = n_bins + 3 with BOS = n_bins, EOS = n_bins + 1, PAD = n_bins + 2. */
+typedef struct {
+  int32_t d_model, n_heads, ffn_mult, n_bins;
+  int32_t l_cpre, l_cpost, l_vpre, l_vpost, l_face; /* transformer blocks per hourglass stack      */
+  int32_t mem_len;                                  /* rows of the condition memory c               */
+  int32_t dtype;                                    /* FM_DTYPE_*                                   */
+  int32_t max_batch;                                /* sequences held by the context                */
+  int32_t max_tokens;                               /* K/V capacity per sequence, coordinate level  */
+  int32_t draft_coord;  /* Dc: coordinate-level SP heads (Eq. 1), one future token each            */
+  int32_t draft_point;  /* m : nominal point-level tokens, multiple of 3, 0 = level off            */
+  int32_t draft_face;   /* n : nominal face-level tokens, multiple of 9, 0 = level off             */
+  int32_t hf_ffn_mult;  /* width multiplier of FFN^(t) in the HF block (Eq. 6)                     */
+  int32_t ban_specials; /* 1: argmax over the coordinate bins only (BOS/EOS/PAD never chosen)      */
+  float rope_base, rms_eps;
+} fm_config;
+
+typedef struct {
+  int64_t steps;             /* decode steps run by fm_generate                                   */
+  int64_t tokens;            /* tokens emitted over all sequences (BOS excluded)                  */
+  int64_t acc_hist[32];      /* histogram of accepted lengths per (step, live sequence)           */
+  double ms_total;           /* device time of the whole loop, hipEvent                            */
+} fm_stats;
+
+/* Create a context for `cfg` bound to `hip_stream` (a hipStream_t; NULL = the null stream).
+ * Allocates every device buffer up front.  FM_EINVAL for an unsupported configuration. */
+int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out);
+int fm_destroy(fm_ctx* ctx);
+const char* fm_last_error(const fm_ctx* ctx);
+
+/* Largest verify block (main token + drafts) = max(1 + Dc, m, n): row stride of the block buffers. */
+int32_t fm_block_max(const fm_ctx* ctx);
+/* Number of float32 values fm_load_weights expects. */
+int64_t fm_blob_elems(const fm_ctx* ctx);
+
+/* Load all parameters from one HOST blob of float32 values in manifest order (embedding; per stack
+ * cpre, vpre, face, vpost, cpost and per block g1,wq,wk,wv,wo,g2,cq,ck,cv,co,g3,w1,w2; shorten
+ * coord->vertex, vertex->face; final gain, LM head; SP heads per level; HF sets per level), linear
+ * weights as [out,in].  Converts to the configured storage type on the device.  Synchronises. */
+int fm_load_weights(fm_ctx* ctx, const float* host_blob, size_t n_floats);
+
+/* Cross-attention keys/values of every block for sequence `seq` from its condition memory
+ * mem_dev [mem_len, d_model] float32 (K_mem = W_k c, V_mem = W_v c; the condition c of Sec. 3.1),
+ * and reset of the sequence to x_0 = BOS with empty caches. */
+int fm_prefill_condition(fm_ctx* ctx, int32_t seq, const float* mem_dev);
+
+/* Predict stage (Sec. 3.1, supplement "Three-Level Speculative Decoding"): from the features tapped
+ * at the last committed position run the coordinate-level SP heads, and the point / face pipelines
+ * (SP heads, draft upsample Eq. 2, HF blocks Eq. 3-6) where a split node was crossed (rules (A) and
+ * (B) of the supplement), average the distributions that cover a position and take the argmax.
+ * Writes block_tok_dev[seq*block_max + i] (i = 0 is the main token) and block_len_dev[seq]
+ * (0 for a finished sequence).  Updates only the context's draft bookkeeping. */
+int fm_draft(fm_ctx* ctx, int32_t* block_tok_dev, int32_t* block_len_dev);
+
+/* Verify stage (Sec. 3.3): one causal backbone forward over each sequence's block at positions
+ * P .. P+len-1 against the K/V caches of all three levels.  logits_dev ([batch, block_max, vocab]
+ * float32) may be NULL.  accepted_len_dev[seq] = 1 + number of leading drafts equal to the
+ * backbone's own greedy prediction (0 for an empty block).  Committed state is not changed;
+ * calling it twice with the same block gives the same result. */
+int fm_verify_block(fm_ctx* ctx, const int32_t* block_tok_dev, const int32_t* block_len_dev,
+                    float* logits_dev, int32_t* accepted_len_dev);
+
+/* Commit the first accepted_len_dev[seq] (1..len) tokens of the last verified block: advances the
+ * committed lengths at all three levels (K/V rollback is implicit: rows past them are scratch), and
+ * makes the backbone's prediction after the last accepted token the next main token. */
+int fm_commit(fm_ctx* ctx, const int32_t* accepted_len_dev);
+
+/* Whole loop, device side: repeat draft -> verify -> commit until every sequence has max_faces faces
+ * or ended with EOS.  speculative = 0 runs plain one-token-per-step greedy decoding of the same
+ * backbone.  out_tok_dev [batch, max_tokens] receives x_1.., out_len_dev [batch] their count.
+ * host_stats may be NULL.  Sequences must have been prefetched with fm_prefill_condition. */
+int fm_generate(fm_ctx* ctx, int32_t max_faces, int32_t speculative, int32_t* out_tok_dev,
+                int32_t* out_len_dev, fm_stats* host_stats);
+
+/* Test / measurement hooks ------------------------------------------------------------------- */
+
+/* HOST out[seq*6 + k]: committed coordinate, vertex, face lengths, pending main token, finished flag,
+ * tokens emitted.  Synchronises. */
+int fm_read_state(fm_ctx* ctx, int32_t* host_out);
+
+/* Synthetic draft source for throughput measurements with a prescribed acceptance pattern: when
+ * stream_dev != NULL, fm_draft still runs every head but then replaces draft token x_p by
+ * stream_dev[seq*stride + p - 1] (the known greedy continuation, x_1 first) when the counter-based
+ * uniform u(seed, seq, p) < keep_prob, else by a wrong id.  NULL switches it off. */
+int fm_set_draft_replay(fm_ctx* ctx, const int32_t* stream_dev, int32_t stride, int32_t n_valid,
+                        float keep_prob, uint64_t seed);
+
+/* Limit on generated tokens per sequence for the step-wise API (default max_tokens). */
+int fm_set_budget(fm_ctx* ctx, int32_t max_faces);
+
+/* Algorithmic HBM bytes of one verify pass at the current committed lengths (weights once, self
+ * and cross K/V once per block and sequence), for roofline reporting.  Synchronises. */
+int fm_verify_bytes(fm_ctx* ctx, double* host_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHMESH_H */

@@ -94,8 +94,10 @@ def _dist(model: Model, h):
     return P.softmax(model.logits(h[None, :]))[0]
 
 
-def draft(model: Model, st: SeqState, budget_tokens: int):
-    """Build the next verify block [main, drafts...] from the state left by the last commit."""
+def draft(model: Model, st: SeqState, budget_tokens: int, merged=None):
+    """Build the next verify block [main, drafts...] from the state left by the last commit.
+
+    If `merged` is a list it receives the averaged distribution behind every draft token."""
     m, cfg = model, model.cfg
     if st.finished:
         return []
@@ -143,6 +145,8 @@ def draft(model: Model, st: SeqState, budget_tokens: int):
         if not have:
             break
         dist = sum(have) / float(len(have))
+        if merged is not None:
+            merged.append(dist)
         block.append(pick(dist, cfg))
         p += 1
     return block

@@ -1,0 +1,174 @@
+"""ctypes binding: argument marshalling only.  Names follow include/flashmesh.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libflashmesh.so")
+
+EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
+           "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
+           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes"]
+
+
+class LibraryMissing(RuntimeError):
+    pass
+
+
+class FmConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "d_model", "n_heads", "ffn_mult", "n_bins", "l_cpre", "l_cpost", "l_vpre", "l_vpost", "l_face", "mem_len",
+        "dtype", "max_batch", "max_tokens", "draft_coord", "draft_point", "draft_face", "hf_ffn_mult",
+        "ban_specials")] + [("rope_base", C.c_float), ("rms_eps", C.c_float)]
+
+
+class FmStats(C.Structure):
+    _fields_ = [("steps", C.c_int64), ("tokens", C.c_int64), ("acc_hist", C.c_int64 * 32), ("ms_total", C.c_double)]
+
+
+_lib = None
+
+
+def load_library():
+    """Load the HIP library; there is no fallback: without it nothing in this package computes."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise LibraryMissing(f"{LIB_PATH} not built: run `python -m paper_2511_15618_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    lib.fm_create.argtypes = [C.POINTER(FmConfig), p, C.POINTER(p)]
+    lib.fm_destroy.argtypes = [p]
+    lib.fm_last_error.argtypes = [p]
+    lib.fm_last_error.restype = C.c_char_p
+    lib.fm_block_max.argtypes = [p]
+    lib.fm_block_max.restype = i32
+    lib.fm_blob_elems.argtypes = [p]
+    lib.fm_blob_elems.restype = i64
+    lib.fm_load_weights.argtypes = [p, p, C.c_size_t]
+    lib.fm_prefill_condition.argtypes = [p, i32, p]
+    lib.fm_draft.argtypes = [p, p, p]
+    lib.fm_verify_block.argtypes = [p, p, p, p, p]
+    lib.fm_commit.argtypes = [p, p]
+    lib.fm_generate.argtypes = [p, i32, i32, p, p, C.POINTER(FmStats)]
+    lib.fm_read_state.argtypes = [p, p]
+    lib.fm_set_draft_replay.argtypes = [p, p, i32, i32, C.c_float, C.c_uint64]
+    lib.fm_set_budget.argtypes = [p, i32]
+    lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
+    for n in EXPORTS:
+        if n not in ("fm_last_error", "fm_block_max", "fm_blob_elems"):
+            getattr(lib, n).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def config_struct(cfg, max_batch=None, max_tokens=None) -> FmConfig:
+    """FmConfig from a synth_inputs.Config-like object (attribute access only)."""
+    return FmConfig(
+        d_model=cfg.d_model, n_heads=cfg.n_heads, ffn_mult=cfg.ffn_mult, n_bins=cfg.n_bins,
+        l_cpre=cfg.l_cpre, l_cpost=cfg.l_cpost, l_vpre=cfg.l_vpre, l_vpost=cfg.l_vpost, l_face=cfg.l_face,
+        mem_len=cfg.mem_len, dtype=1 if cfg.dtype == "bf16" else 0,
+        max_batch=max_batch or cfg.batch, max_tokens=max_tokens or cfg.max_tokens,
+        draft_coord=cfg.draft_coord, draft_point=cfg.draft_point, draft_face=cfg.draft_face,
+        hf_ffn_mult=cfg.hf_ffn_mult, ban_specials=cfg.ban_specials, rope_base=cfg.rope_base, rms_eps=cfg.rms_eps)
+
+
+class FlashMesh:
+    """One library context.  Tensor arguments are torch CUDA tensors (int32 / float32, contiguous)."""
+
+    def __init__(self, fm_config: FmConfig, stream=None):
+        import torch
+        self.lib = load_library()
+        self.torch = torch
+        self.cfgs = fm_config
+        self.stream = stream if stream is not None else torch.cuda.current_stream()
+        h = C.c_void_p()
+        rc = self.lib.fm_create(C.byref(fm_config), C.c_void_p(self.stream.cuda_stream), C.byref(h))
+        if rc != 0:
+            raise RuntimeError(f"fm_create failed with code {rc}")
+        self.h = h
+        self.batch = fm_config.max_batch
+        self.block_max = self.lib.fm_block_max(h)
+        self.vocab = fm_config.n_bins + 3
+        self.max_tokens = fm_config.max_tokens
+
+    def _chk(self, rc, what):
+        if rc != 0:
+            raise RuntimeError(f"{what} failed ({rc}): {self.lib.fm_last_error(self.h).decode()}")
+
+    @staticmethod
+    def _ptr(t):
+        return C.c_void_p(0 if t is None else t.data_ptr())
+
+    def close(self):
+        if self.h:
+            self.lib.fm_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def blob_elems(self) -> int:
+        return int(self.lib.fm_blob_elems(self.h))
+
+    def load_weights(self, blob: np.ndarray):
+        blob = np.ascontiguousarray(blob, dtype=np.float32)
+        self._chk(self.lib.fm_load_weights(self.h, C.c_void_p(blob.ctypes.data), C.c_size_t(blob.size)), "fm_load_weights")
+
+    def prefill_condition(self, seq: int, mem):
+        assert mem.is_cuda and mem.dtype == self.torch.float32 and mem.is_contiguous()
+        assert tuple(mem.shape) == (self.cfgs.mem_len, self.cfgs.d_model)
+        self._chk(self.lib.fm_prefill_condition(self.h, seq, self._ptr(mem)), "fm_prefill_condition")
+
+    def new_block(self):
+        t = self.torch
+        return (t.zeros(self.batch, self.block_max, dtype=t.int32, device="cuda"),
+                t.zeros(self.batch, dtype=t.int32, device="cuda"))
+
+    def draft(self, block_tok, block_len):
+        self._chk(self.lib.fm_draft(self.h, self._ptr(block_tok), self._ptr(block_len)), "fm_draft")
+
+    def verify_block(self, block_tok, block_len, logits, accepted):
+        self._chk(self.lib.fm_verify_block(self.h, self._ptr(block_tok), self._ptr(block_len), self._ptr(logits),
+                                           self._ptr(accepted)), "fm_verify_block")
+
+    def commit(self, accepted):
+        self._chk(self.lib.fm_commit(self.h, self._ptr(accepted)), "fm_commit")
+
+    def generate(self, max_faces: int, speculative: bool = True):
+        t = self.torch
+        out = t.zeros(self.batch, self.max_tokens, dtype=t.int32, device="cuda")
+        n = t.zeros(self.batch, dtype=t.int32, device="cuda")
+        st = FmStats()
+        self._chk(self.lib.fm_generate(self.h, max_faces, 1 if speculative else 0, self._ptr(out), self._ptr(n),
+                                       C.byref(st)), "fm_generate")
+        return out, n, st
+
+    def read_state(self) -> np.ndarray:
+        out = np.zeros((self.batch, 6), np.int32)
+        self._chk(self.lib.fm_read_state(self.h, C.c_void_p(out.ctypes.data)), "fm_read_state")
+        return out
+
+    def set_draft_replay(self, stream, n_valid: int, keep_prob: float, seed: int):
+        if stream is None:
+            self._chk(self.lib.fm_set_draft_replay(self.h, None, 0, 0, 0.0, 0), "fm_set_draft_replay")
+        else:
+            assert stream.dtype == self.torch.int32 and stream.is_cuda and stream.is_contiguous()
+            self._keep = stream
+            self._chk(self.lib.fm_set_draft_replay(self.h, self._ptr(stream), stream.shape[1], n_valid,
+                                                   C.c_float(keep_prob), C.c_uint64(seed)), "fm_set_draft_replay")
+
+    def set_budget(self, max_faces: int):
+        self._chk(self.lib.fm_set_budget(self.h, max_faces), "fm_set_budget")
+
+    def verify_bytes(self) -> float:
+        v = C.c_double()
+        self._chk(self.lib.fm_verify_bytes(self.h, C.byref(v)), "fm_verify_bytes")
+        return v.value

@@ -1,0 +1,727 @@
+// C-ABI library: context, weight loading, and the enqueue logic of draft / verify / commit.
+// See include/flashmesh.h for the contract of every entry point.
+#include "../../include/flashmesh.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "fm_device.h"
+#include "fm_kernels_basic.h"
+#include "fm_kernels_step.h"
+#include "fm_kernels_mfma.h"
+
+#define RS_C 32  // ring sizes (positions kept per sequence) at the coordinate / vertex / face level
+#define RS_V 16
+#define RS_F 8
+
+namespace {
+
+struct Layer {
+  float *g1, *g2, *g3;
+  void *wqkv, *wo, *cq, *ckv, *co, *w1, *w2;  // storage type T, [out, in]
+  void *Kc, *Vc;                               // [S][H][cap][64]
+  void *Km, *Vm;                               // [S][H][M][64]
+  int level;                                   // 0 coordinate, 1 vertex, 2 face
+};
+
+struct SpLevel {  // SP heads of one level, head-major contiguous so that one grouped GEMM serves all heads
+  int cnt;
+  float* g;
+  void *wq, *wo, *cq, *co, *lin;
+};
+struct HfLevel {
+  int cnt;
+  float* g;
+  void *wq, *w1, *w2;
+};
+
+struct LoadItem { size_t blob_off, n; void* dst; bool f32; };
+
+}  // namespace
+
+struct fm_ctx {
+  fm_config cfg;
+  Dims D;
+  InvFreq inv;
+  hipStream_t stream;
+  bool bf16;
+  size_t esz;
+  int ff, hff, Vpad;
+  int Rc, Rv, Rf;  // row slots per level
+  std::string err;
+  std::vector<void*> allocs;
+  std::vector<LoadItem> items;
+  size_t blob_elems;
+  bool weights_loaded;
+  std::vector<bool> prefilled;
+
+  // parameters
+  void* emb;
+  std::vector<Layer> stacks[5];  // cpre, vpre, face, vpost, cpost
+  void *short_cv, *short_vf, *lm;
+  float* gf;
+  SpLevel sp[3];
+  HfLevel hfc, hfv;
+
+  // state
+  StateDev st;
+  // rings (fp32)
+  float *ring_hc, *ring_hv, *ring_yf, *ring_yv, *tap_c, *tap_v, *tap_f;
+  // verify scratch
+  int *pos[3], *limx[3];
+  float2* cs[3];
+  float* h[3];
+  void *xn, *qT, *attT, *mid;
+  float *qkv, *logits;
+  float* attn_ws;     // split-KV partials of the MFMA attention
+  float* stage;       // staging for weight conversion / prefill GEMM output
+  size_t stage_elems;
+  // draft scratch
+  DraftRows dr;
+  DraftBufs db;
+  float *spv_out, *spf_out, *hfv_out, *dh, *dkeep, *dtmp, *dlogits;
+  float *dist_c, *dist_v, *dist_f;
+  void *dxn, *dq, *datt, *dmid;
+  Replay replay;
+  int *gen_tok, *gen_len;  // block buffers used by fm_generate
+  int* gen_acc;
+  int* host_flag;          // pinned
+  double weight_bytes;
+};
+
+namespace {
+
+int fail(fm_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                         \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess) return fail(c, FM_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+template <typename U> int dalloc(fm_ctx* c, U** p, size_t n, bool zero = true) {
+  void* q = nullptr;
+  const size_t bytes = (n ? n : 1) * sizeof(U);
+  if (hipMalloc(&q, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(c, FM_ENOMEM, "hipMalloc of %zu bytes failed", bytes);
+  }
+  if (zero && hipMemset(q, 0, bytes) != hipSuccess) return fail(c, FM_EHIP, "hipMemset failed");
+  c->allocs.push_back(q);
+  *p = (U*)q;
+  return FM_OK;
+}
+int dalloc_t(fm_ctx* c, void** p, size_t n) {  // n elements of the storage type
+  uint8_t* q;
+  int rc = dalloc(c, &q, n * c->esz);
+  *p = q;
+  return rc;
+}
+#define TRY(x) do { int rc_ = (x); if (rc_ != FM_OK) return rc_; } while (0)
+
+int level_cap(const fm_ctx* c, int level) { return level == 0 ? c->D.capc : level == 1 ? c->D.capv : c->D.capf; }
+const int kStackLevel[5] = {0, 1, 2, 1, 0};
+
+// ------------------------------------------------------------------------------------------
+// launch wrappers
+// ------------------------------------------------------------------------------------------
+template <typename T>
+void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, long gsw, void* Y, long ldy, long gsy,
+          const float* R, long ldr, long gsr, int M, int N, int K, int groups, const int* flag) {
+  GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag};
+  if (mfma_gemm_launch<T>(a, epi, groups, c->stream)) return;
+  dim3 grid((N + 3) / 4, groups);
+  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_simple<T, EPI_F32>), grid, dim3(256), 0, c->stream, a);
+  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_simple<T, EPI_GELU_T>), grid, dim3(256), 0, c->stream, a);
+  else hipLaunchKernelGGL((k_gemm_simple<T, EPI_T>), grid, dim3(256), 0, c->stream, a);
+}
+
+template <typename T>
+void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
+               long seq_stride, int cap, void* out, const int* flag) {
+  if (mfma_attn_launch<T>(q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, c->attn_ws, flag, c->stream)) return;
+  hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
+                     (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag);
+}
+
+template <typename T>
+void rmsnorm(fm_ctx* c, const float* src, const float* const* srcptr, const float* gain, int gain_mod, void* out,
+             float* keep, int rows, const int* flag) {
+  hipLaunchKernelGGL((k_rmsnorm<T>), dim3(rows), dim3(256), 0, c->stream, src, srcptr, gain, gain_mod, (T*)out, keep,
+                     c->D.d, c->cfg.rms_eps, flag);
+}
+
+// one transformer block on the row set of `level` (Sec. 3.1: self-attention, cross-attention to c, FFN)
+template <typename T>
+void run_block(fm_ctx* c, const Layer& L, int level) {
+  const Dims& D = c->D;
+  const int d = D.d, rows = level == 0 ? c->Rc : level == 1 ? c->Rv : c->Rf;
+  const int RPS = level == 0 ? D.Bm : level == 1 ? D.VB : D.FB;
+  const int cap = level_cap(c, level);
+  float* h = c->h[level];
+  const int* flag = c->st.alive;
+  rmsnorm<T>(c, h, nullptr, L.g1, 0, c->xn, nullptr, rows, flag);
+  gemm<T>(c, EPI_F32, c->xn, d, 0, L.wqkv, 0, c->qkv, 3 * d, 0, nullptr, 0, 0, rows, 3 * d, d, 1, flag);
+  hipLaunchKernelGGL((k_rope_append<T>), dim3(rows), dim3(256), 0, c->stream, c->qkv, (long)3 * d, c->cs[level],
+                     c->pos[level], RPS, (T*)c->qT, (T*)L.Kc, (T*)L.Vc, D.H, cap, flag);
+  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)D.H * cap * FM_HD, cap, c->attT, flag);
+  gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
+  rmsnorm<T>(c, h, nullptr, L.g2, 0, c->xn, nullptr, rows, flag);
+  gemm<T>(c, EPI_T, c->xn, d, 0, L.cq, 0, c->qT, d, 0, nullptr, 0, 0, rows, d, d, 1, flag);
+  attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)D.H * D.M * FM_HD, D.M, c->attT, flag);
+  gemm<T>(c, EPI_F32, c->attT, d, 0, L.co, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
+  rmsnorm<T>(c, h, nullptr, L.g3, 0, c->xn, nullptr, rows, flag);
+  gemm<T>(c, EPI_GELU_T, c->xn, d, 0, L.w1, 0, c->mid, c->ff, 0, nullptr, 0, 0, rows, c->ff, d, 1, flag);
+  gemm<T>(c, EPI_F32, c->mid, c->ff, 0, L.w2, 0, h, d, 0, h, d, 0, rows, d, c->ff, 1, flag);
+}
+
+void ring_save(fm_ctx* c, const float* src, float* ring, int level, int RS) {
+  const Dims& D = c->D;
+  const int rows = level == 0 ? c->Rc : level == 1 ? c->Rv : c->Rf;
+  const int RPS = level == 0 ? D.Bm : level == 1 ? D.VB : D.FB;
+  hipLaunchKernelGGL(k_ring_save, dim3(rows), dim3(256), 0, c->stream, src, ring, c->pos[level], RPS, RS, D.d);
+}
+
+template <typename T>
+void run_stack(fm_ctx* c, int stack, float* tap_ring, int tap_rs) {
+  const int level = kStackLevel[stack];
+  const size_t n = c->stacks[stack].size();
+  for (size_t i = 0; i < n; i++) {
+    if (tap_ring && i == n - 1) ring_save(c, c->h[level], tap_ring, level, tap_rs);
+    run_block<T>(c, c->stacks[stack][i], level);
+  }
+}
+
+template <typename T>
+int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits_out, int32_t* accepted) {
+  const Dims& D = c->D;
+  const int d = D.d;
+  hipLaunchKernelGGL(k_verify_setup, dim3(1), dim3(256), 0, c->stream, c->st, D, c->inv, block_tok, block_len,
+                     c->pos[0], c->pos[1], c->pos[2], c->limx[0], c->limx[1], c->limx[2], c->cs[0], c->cs[1], c->cs[2]);
+  hipLaunchKernelGGL((k_embed<T>), dim3(c->Rc), dim3(256), 0, c->stream, c->st.vtok, c->pos[0], (const T*)c->emb,
+                     c->h[0], d);
+  const int* flag = c->st.alive;
+  // coordinate level, first half
+  run_stack<T>(c, 0, nullptr, 0);
+  ring_save(c, c->h[0], c->ring_hc, 0, RS_C);
+  // shorten coordinate -> vertex
+  hipLaunchKernelGGL((k_pool3<T>), dim3(c->Rv), dim3(256), 0, c->stream, c->ring_hc, RS_C, c->pos[1], D.VB, (T*)c->xn, d);
+  gemm<T>(c, EPI_F32, c->xn, d, 0, c->short_cv, 0, c->h[1], d, 0, nullptr, 0, 0, c->Rv, d, d, 1, flag);
+  run_stack<T>(c, 1, nullptr, 0);
+  ring_save(c, c->h[1], c->ring_hv, 1, RS_V);
+  // shorten vertex -> face
+  hipLaunchKernelGGL((k_pool3<T>), dim3(c->Rf), dim3(256), 0, c->stream, c->ring_hv, RS_V, c->pos[2], D.FB, (T*)c->xn, d);
+  gemm<T>(c, EPI_F32, c->xn, d, 0, c->short_vf, 0, c->h[2], d, 0, nullptr, 0, 0, c->Rf, d, d, 1, flag);
+  run_stack<T>(c, 2, c->tap_f, RS_F);
+  ring_save(c, c->h[2], c->ring_yf, 2, RS_F);
+  // upsample face -> vertex (repeat + skip), vertex level second half
+  hipLaunchKernelGGL(k_upsample_add, dim3(c->Rv), dim3(256), 0, c->stream, c->h[1], c->pos[1], D.VB, c->ring_yf, RS_F, d);
+  run_stack<T>(c, 3, c->tap_v, RS_V);
+  ring_save(c, c->h[1], c->ring_yv, 1, RS_V);
+  // upsample vertex -> coordinate, coordinate level second half
+  hipLaunchKernelGGL(k_upsample_add, dim3(c->Rc), dim3(256), 0, c->stream, c->h[0], c->pos[0], D.Bm, c->ring_yv, RS_V, d);
+  run_stack<T>(c, 4, c->tap_c, RS_C);
+  // output head, greedy prediction, acceptance
+  float* lg = logits_out ? logits_out : c->logits;
+  rmsnorm<T>(c, c->h[0], nullptr, c->gf, 0, c->xn, nullptr, c->Rc, flag);
+  gemm<T>(c, EPI_F32, c->xn, d, 0, c->lm, 0, lg, D.V, 0, nullptr, 0, 0, c->Rc, D.V, d, 1, flag);
+  hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, lg, D.V, D.ban ? D.nbins : D.V, c->st.y);
+  hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted);
+  HIPCHK(c, hipGetLastError());
+  return FM_OK;
+}
+
+// SP head chain (Eq. 1) for the row set `set` of one level; writes fp32 features to out (row stride ldo)
+template <typename T>
+void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level, float* out, long ldo, long gso,
+            const int* flag) {
+  const Dims& D = c->D;
+  const int d = D.d, G = sp.cnt, rows = D.S * G;
+  if (G == 0) return;
+  const int cap = level_cap(c, level);
+  const long dd = (long)d * d;
+  rmsnorm<T>(c, nullptr, c->dr.src[set], sp.g, G, c->dxn, c->dkeep, rows, flag);
+  gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.wq, dd, c->dtmp, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
+  hipLaunchKernelGGL((k_rope_append<T>), dim3(rows), dim3(256), 0, c->stream, c->dtmp, (long)d, c->dr.cs[set],
+                     c->dr.pos[set], G, (T*)c->dq, (T*)nullptr, (T*)nullptr, D.H, cap, flag);
+  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)D.H * cap * FM_HD, cap, c->datt, flag);
+  gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.wo, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
+  gemm<T>(c, EPI_T, c->dxn, (long)G * d, d, sp.cq, dd, c->dq, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
+  attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)D.H * D.M * FM_HD, D.M, c->datt, flag);
+  gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.co, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
+  gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.lin, dd, out, ldo, gso, c->dkeep, (long)G * d, d, D.S, d, d, G, flag);
+}
+
+// HF block chain (Eq. 3-6) for row set `set`: `per_seq` rows per sequence, `G` parameter sets, `mult`
+// consecutive row groups of G sharing the sets (mult = 2 for the coordinate level: point and face pipelines)
+template <typename T>
+void run_hf(fm_ctx* c, int set, const HfLevel& hf, int mult, const Layer& last, int level, float* out, const int* flag) {
+  const Dims& D = c->D;
+  const int d = D.d, G = hf.cnt, per_seq = G * mult, rows = D.S * per_seq;
+  if (G == 0) return;
+  const int cap = level_cap(c, level);
+  const long dd = (long)d * d, dh = (long)d * c->hff;
+  const int Mg = D.S * mult;           // rows per parameter set
+  const long ld = (long)G * d;         // stride between those rows
+  rmsnorm<T>(c, nullptr, c->dr.src[set], hf.g, G, c->dxn, c->dkeep, rows, flag);
+  gemm<T>(c, EPI_F32, c->dxn, ld, d, hf.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, Mg, d, d, G, flag);
+  hipLaunchKernelGGL((k_rope_append<T>), dim3(rows), dim3(256), 0, c->stream, c->dtmp, (long)d, c->dr.cs[set],
+                     c->dr.pos[set], per_seq, (T*)c->dq, (T*)nullptr, (T*)nullptr, D.H, cap, flag);
+  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)D.H * cap * FM_HD, cap, c->datt, flag);
+  gemm<T>(c, EPI_GELU_T, c->datt, ld, d, hf.w1, dh, c->dmid, (long)G * c->hff, c->hff, nullptr, 0, 0, Mg, c->hff, d, G, flag);
+  gemm<T>(c, EPI_F32, c->dmid, (long)G * c->hff, c->hff, hf.w2, dh, out, ld, d, c->dkeep, ld, d, Mg, d, c->hff, G, flag);
+}
+
+template <typename T>
+int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculative) {
+  const Dims& D = c->D;
+  const int d = D.d;
+  if (speculative) {
+    hipLaunchKernelGGL(k_draft_setup, dim3(1), dim3(256), 0, c->stream, c->st, D, c->inv, c->dr, c->db);
+    const int *f_alive = c->dr.flags, *f_v = c->dr.flags + 1, *f_f = c->dr.flags + 2;
+    const Layer& lastc = c->stacks[4].back();
+    const Layer& lastv = c->stacks[3].back();
+    const Layer& lastf = c->stacks[2].back();
+    const int nLM = D.S * (D.Dc + 2 * D.nhfc);
+    // coordinate level: SP heads straight to the output head
+    run_sp<T>(c, 0, c->sp[0], lastc, 0, c->dh, (long)D.Dc * d, d, f_alive);
+    // point level: SP heads on the vertex feature; their outputs feed the coordinate HF rows of pipe 0
+    run_sp<T>(c, 1, c->sp[1], lastv, 1, c->spv_out, (long)D.nspv * d, d, f_v);
+    // face level: SP heads on the face feature, vertex-level HF, then coordinate HF rows of pipe 1
+    run_sp<T>(c, 2, c->sp[2], lastf, 2, c->spf_out, (long)D.nspf * d, d, f_f);
+    run_hf<T>(c, 3, c->hfv, 1, lastv, 1, c->hfv_out, f_f);
+    run_hf<T>(c, 4, c->hfc, 2, lastc, 0, c->dh + (long)D.S * D.Dc * d, f_alive);
+    if (nLM > 0) {
+      rmsnorm<T>(c, c->dh, nullptr, c->gf, 0, c->dxn, nullptr, nLM, f_alive);
+      gemm<T>(c, EPI_F32, c->dxn, d, 0, c->lm, 0, c->dlogits, D.V, 0, nullptr, 0, 0, nLM, D.V, d, 1, f_alive);
+      hipLaunchKernelGGL(k_dist_store, dim3(nLM), dim3(256), 0, c->stream, c->dlogits, D, c->dr, c->dist_c, c->dist_v,
+                         c->dist_f);
+    }
+  }
+  hipLaunchKernelGGL(k_merge, dim3(D.S), dim3(256), 0, c->stream, c->st, D, c->dr, c->dist_c, c->dist_v, c->dist_f,
+                     c->replay, speculative, block_tok, block_len);
+  HIPCHK(c, hipGetLastError());
+  return FM_OK;
+}
+
+template <typename T>
+int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
+  const Dims& D = c->D;
+  const int d = D.d;
+  // condition memory in the storage type (dmid is large enough: M*d <= checked at create)
+  T* memT = (T*)c->stage;  // reuse staging area: [M*d] T followed by fp32 [M][2d]
+  float* kv = c->stage + (size_t)D.M * d;
+  hipLaunchKernelGGL((k_convert<T>), dim3(512), dim3(256), 0, c->stream, mem_dev, memT, (long)D.M * d);
+  for (int st = 0; st < 5; st++)
+    for (auto& L : c->stacks[st]) {
+      gemm<T>(c, EPI_F32, memT, d, 0, L.ckv, 0, kv, 2 * d, 0, nullptr, 0, 0, D.M, 2 * d, d, 1, nullptr);
+      T* Km = (T*)L.Km + (size_t)seq * D.H * D.M * FM_HD;
+      T* Vm = (T*)L.Vm + (size_t)seq * D.H * D.M * FM_HD;
+      hipLaunchKernelGGL((k_mem_kv_store<T>), dim3(D.M), dim3(256), 0, c->stream, kv, Km, Vm, D.H, D.M);
+    }
+  hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
+  HIPCHK(c, hipGetLastError());
+  return FM_OK;
+}
+
+// Build the parameter tables and the list of (blob range -> device destination) in manifest order.
+int build_params(fm_ctx* c) {
+  const Dims& D = c->D;
+  const size_t d = D.d, ff = c->ff, hff = c->hff, V = D.V;
+  size_t off = 0;
+  auto item = [&](void* dst, size_t n, bool f32) { c->items.push_back({off, n, dst, f32}); off += n; };
+  auto at = [&](void* base, size_t elems) { return (void*)((uint8_t*)base + elems * c->esz); };
+
+  TRY(dalloc_t(c, &c->emb, V * d));
+  item(c->emb, V * d, false);
+  const int counts[5] = {c->cfg.l_cpre, c->cfg.l_vpre, c->cfg.l_face, c->cfg.l_vpost, c->cfg.l_cpost};
+  for (int st = 0; st < 5; st++) {
+    const int level = kStackLevel[st];
+    const size_t cap = level_cap(c, level);
+    for (int i = 0; i < counts[st]; i++) {
+      Layer L{};
+      L.level = level;
+      TRY(dalloc(c, &L.g1, d)); TRY(dalloc(c, &L.g2, d)); TRY(dalloc(c, &L.g3, d));
+      TRY(dalloc_t(c, &L.wqkv, 3 * d * d)); TRY(dalloc_t(c, &L.wo, d * d)); TRY(dalloc_t(c, &L.cq, d * d));
+      TRY(dalloc_t(c, &L.ckv, 2 * d * d)); TRY(dalloc_t(c, &L.co, d * d));
+      TRY(dalloc_t(c, &L.w1, ff * d)); TRY(dalloc_t(c, &L.w2, d * ff));
+      TRY(dalloc_t(c, &L.Kc, (size_t)D.S * D.H * cap * FM_HD)); TRY(dalloc_t(c, &L.Vc, (size_t)D.S * D.H * cap * FM_HD));
+      TRY(dalloc_t(c, &L.Km, (size_t)D.S * D.H * D.M * FM_HD)); TRY(dalloc_t(c, &L.Vm, (size_t)D.S * D.H * D.M * FM_HD));
+      item(L.g1, d, true);
+      item(L.wqkv, 3 * d * d, false);   // wq, wk, wv are consecutive in the blob
+      item(L.wo, d * d, false);
+      item(L.g2, d, true);
+      item(L.cq, d * d, false);
+      item(L.ckv, 2 * d * d, false);    // ck, cv consecutive
+      item(L.co, d * d, false);
+      item(L.g3, d, true);
+      item(L.w1, ff * d, false);
+      item(L.w2, d * ff, false);
+      c->stacks[st].push_back(L);
+    }
+  }
+  TRY(dalloc_t(c, &c->short_cv, d * d)); item(c->short_cv, d * d, false);
+  TRY(dalloc_t(c, &c->short_vf, d * d)); item(c->short_vf, d * d, false);
+  TRY(dalloc(c, &c->gf, d)); item(c->gf, d, true);
+  TRY(dalloc_t(c, &c->lm, (size_t)c->Vpad * d)); item(c->lm, V * d, false);
+  const int spcnt[3] = {D.Dc, D.nspv, D.nspf};
+  for (int l = 0; l < 3; l++) {
+    SpLevel& s = c->sp[l];
+    s.cnt = spcnt[l];
+    const size_t n = s.cnt;
+    TRY(dalloc(c, &s.g, n * d));
+    TRY(dalloc_t(c, &s.wq, n * d * d)); TRY(dalloc_t(c, &s.wo, n * d * d)); TRY(dalloc_t(c, &s.cq, n * d * d));
+    TRY(dalloc_t(c, &s.co, n * d * d)); TRY(dalloc_t(c, &s.lin, n * d * d));
+    for (size_t k = 0; k < n; k++) {
+      item(s.g + k * d, d, true);
+      item(at(s.wq, k * d * d), d * d, false); item(at(s.wo, k * d * d), d * d, false);
+      item(at(s.cq, k * d * d), d * d, false); item(at(s.co, k * d * d), d * d, false);
+      item(at(s.lin, k * d * d), d * d, false);
+    }
+  }
+  HfLevel* hfs[2] = {&c->hfc, &c->hfv};
+  const int hfcnt[2] = {D.nhfc, D.nhfv};
+  for (int l = 0; l < 2; l++) {
+    HfLevel& h = *hfs[l];
+    h.cnt = hfcnt[l];
+    const size_t n = h.cnt;
+    TRY(dalloc(c, &h.g, n * d));
+    TRY(dalloc_t(c, &h.wq, n * d * d)); TRY(dalloc_t(c, &h.w1, n * hff * d)); TRY(dalloc_t(c, &h.w2, n * d * hff));
+    for (size_t k = 0; k < n; k++) {
+      item(h.g + k * d, d, true);
+      item(at(h.wq, k * d * d), d * d, false);
+      item(at(h.w1, k * hff * d), hff * d, false);
+      item(at(h.w2, k * d * hff), d * hff, false);
+    }
+  }
+  c->blob_elems = off;
+  return FM_OK;
+}
+
+int build_buffers(fm_ctx* c) {
+  const Dims& D = c->D;
+  const size_t d = D.d, S = D.S;
+  StateDev& st = c->st;
+  TRY(dalloc(c, &st.P, S)); TRY(dalloc(c, &st.main, S)); TRY(dalloc(c, &st.fin, S));
+  TRY(dalloc(c, &st.firedv, S)); TRY(dalloc(c, &st.firedf, S));
+  TRY(dalloc(c, &st.basec, S)); TRY(dalloc(c, &st.basev, S)); TRY(dalloc(c, &st.basef, S));
+  TRY(dalloc(c, &st.vlen, S)); TRY(dalloc(c, &st.vtok, S * D.Bm)); TRY(dalloc(c, &st.y, S * D.Bm)); TRY(dalloc(c, &st.acc, S));
+  TRY(dalloc(c, &st.hist, S * (D.capc + 1))); TRY(dalloc(c, &st.budget, 1)); TRY(dalloc(c, &st.alive, 1));
+  TRY(dalloc(c, &st.acc_hist, 32)); TRY(dalloc(c, &st.counters, 2));
+  TRY(dalloc(c, &c->ring_hc, S * RS_C * d)); TRY(dalloc(c, &c->tap_c, S * RS_C * d));
+  TRY(dalloc(c, &c->ring_hv, S * RS_V * d)); TRY(dalloc(c, &c->ring_yv, S * RS_V * d)); TRY(dalloc(c, &c->tap_v, S * RS_V * d));
+  TRY(dalloc(c, &c->ring_yf, S * RS_F * d)); TRY(dalloc(c, &c->tap_f, S * RS_F * d));
+  const size_t rows[3] = {(size_t)c->Rc, (size_t)c->Rv, (size_t)c->Rf};
+  for (int l = 0; l < 3; l++) {
+    TRY(dalloc(c, &c->pos[l], rows[l])); TRY(dalloc(c, &c->limx[l], rows[l]));
+    TRY(dalloc(c, &c->cs[l], rows[l] * 32)); TRY(dalloc(c, &c->h[l], rows[l] * d));
+  }
+  TRY(dalloc_t(c, &c->xn, rows[0] * d)); TRY(dalloc_t(c, &c->qT, rows[0] * d)); TRY(dalloc_t(c, &c->attT, rows[0] * d));
+  TRY(dalloc_t(c, &c->mid, rows[0] * c->ff));
+  TRY(dalloc(c, &c->qkv, rows[0] * 3 * d)); TRY(dalloc(c, &c->logits, rows[0] * D.V));
+  // staging: conversion of the largest tensor, or the prefill (memory in T + fp32 K/V of one layer)
+  size_t big = std::max((size_t)c->ff * d, (size_t)c->hff * d);
+  big = std::max(big, 3 * d * d);
+  big = std::max(big, (size_t)D.V * d);
+  c->stage_elems = std::max(big, (size_t)D.M * d + (size_t)D.M * 2 * d);
+  TRY(dalloc(c, &c->stage, c->stage_elems));
+  // draft rows
+  const size_t nset[5] = {S * D.Dc, S * D.nspv, S * D.nspf, S * D.nhfv, S * 2 * D.nhfc};
+  size_t maxset = 1;
+  for (int i = 0; i < 5; i++) {
+    maxset = std::max(maxset, nset[i]);
+    TRY(dalloc(c, (const float***)&c->dr.src[i], nset[i])); TRY(dalloc(c, &c->dr.pos[i], nset[i]));
+    TRY(dalloc(c, &c->dr.lim[i], nset[i])); TRY(dalloc(c, &c->dr.limx[i], nset[i]));
+    TRY(dalloc(c, &c->dr.cs[i], nset[i] * 32));
+  }
+  TRY(dalloc(c, &c->dr.alive, S)); TRY(dalloc(c, &c->dr.firev, S)); TRY(dalloc(c, &c->dr.firef, S)); TRY(dalloc(c, &c->dr.flags, 4));
+  TRY(dalloc(c, &c->spv_out, nset[1] * d)); TRY(dalloc(c, &c->spf_out, nset[2] * d)); TRY(dalloc(c, &c->hfv_out, nset[3] * d));
+  const size_t nLM = S * (D.Dc + 2 * D.nhfc);
+  TRY(dalloc(c, &c->dh, nLM * d)); TRY(dalloc(c, &c->dlogits, nLM * D.V));
+  const size_t rmax = std::max(maxset, nLM);
+  TRY(dalloc(c, &c->dkeep, rmax * d)); TRY(dalloc(c, &c->dtmp, rmax * d));
+  TRY(dalloc_t(c, &c->dxn, rmax * d)); TRY(dalloc_t(c, &c->dq, rmax * d)); TRY(dalloc_t(c, &c->datt, rmax * d));
+  TRY(dalloc_t(c, &c->dmid, rmax * c->hff));
+  TRY(dalloc(c, &c->dist_c, S * std::max(D.Dc, 1) * D.V));
+  TRY(dalloc(c, &c->dist_v, S * std::max(D.nhfc, 1) * D.V)); TRY(dalloc(c, &c->dist_f, S * std::max(D.nhfc, 1) * D.V));
+  c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
+  TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
+  TRY(dalloc(c, &c->attn_ws, mfma_attn_ws_floats(D.S, D.H, std::max((int)rmax, c->Rc))));
+  if (hipHostMalloc((void**)&c->host_flag, 64) != hipSuccess) return fail(c, FM_ENOMEM, "hipHostMalloc failed");
+  return FM_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
+  if (!cfg || !out) return FM_EINVAL;
+  *out = nullptr;
+  const fm_config& g = *cfg;
+  if (g.d_model <= 0 || g.n_heads <= 0 || g.d_model != g.n_heads * FM_HD) return FM_EINVAL;
+  if (g.ffn_mult < 1 || g.hf_ffn_mult < 1 || g.n_bins < 1 || g.mem_len < 1) return FM_EINVAL;
+  if (g.l_cpre < 1 || g.l_cpost < 1 || g.l_vpre < 1 || g.l_vpost < 1 || g.l_face < 1) return FM_EINVAL;
+  if (g.dtype != FM_DTYPE_F32 && g.dtype != FM_DTYPE_BF16) return FM_EINVAL;
+  if (g.max_batch < 1 || g.max_batch > 64 || g.max_tokens < 9 || g.max_tokens % 9 != 0) return FM_EINVAL;
+  if (g.draft_coord < 0 || g.draft_point < 0 || g.draft_face < 0) return FM_EINVAL;
+  if (g.draft_point % 3 != 0 || g.draft_face % 9 != 0) return FM_EINVAL;
+  if ((g.draft_point > 0 || g.draft_face > 0) && g.draft_coord < 2) return FM_EINVAL;  // rule (B) leaves 3 tokens to the coordinate level
+  const int Bm = std::max(std::max(1 + g.draft_coord, g.draft_point), std::max(g.draft_face, 1));
+  if (Bm > 27) return FM_EINVAL;  // rings hold 32 coordinate positions: block + 2 carried rows
+  if (!(g.rope_base > 1.f) || !(g.rms_eps > 0.f)) return FM_EINVAL;
+
+  fm_ctx* c = new (std::nothrow) fm_ctx();
+  if (!c) return FM_ENOMEM;
+  c->cfg = g;
+  c->stream = (hipStream_t)hip_stream;
+  c->bf16 = g.dtype == FM_DTYPE_BF16;
+  c->esz = c->bf16 ? 2 : 4;
+  c->ff = g.ffn_mult * g.d_model;
+  c->hff = g.hf_ffn_mult * g.d_model;
+  Dims& D = c->D;
+  D.d = g.d_model; D.H = g.n_heads; D.V = g.n_bins + 3; D.S = g.max_batch; D.Bm = Bm;
+  D.VB = (Bm + 2) / 3; D.FB = (Bm + 8) / 9; D.M = g.mem_len;
+  D.capc = g.max_tokens; D.capv = (g.max_tokens + 2) / 3 + 1; D.capf = (g.max_tokens + 8) / 9 + 1;
+  D.Dc = g.draft_coord; D.m = g.draft_point; D.n = g.draft_face;
+  D.nspv = std::max(D.m / 3 - 1, 0); D.nspf = std::max(D.n / 9 - 1, 0);
+  D.nhfc = std::max(std::max(D.m, D.n) - 3, 0); D.nhfv = std::max(D.n / 3 - 1, 0);
+  D.nbins = g.n_bins; D.ban = g.ban_specials ? 1 : 0; D.eos = g.n_bins + 1; D.pad = g.n_bins + 2;
+  c->Vpad = (D.V + 63) / 64 * 64;
+  c->Rc = D.S * D.Bm; c->Rv = D.S * D.VB; c->Rf = D.S * D.FB;
+  for (int i = 0; i < 32; i++) c->inv.v[i] = std::pow((double)g.rope_base, -(double)i / 32.0);
+  c->weights_loaded = false;
+  c->prefilled.assign(D.S, false);
+  c->replay = Replay{nullptr, 0, 0, 0.f, 0ull};
+  c->host_flag = nullptr;
+  int rc = build_params(c);
+  if (rc == FM_OK) rc = build_buffers(c);
+  if (rc == FM_OK) {
+    const int budget = g.max_tokens;
+    if (hipMemcpy(c->st.budget, &budget, sizeof(int), hipMemcpyHostToDevice) != hipSuccess) rc = FM_EHIP;
+    // all sequences start finished until they are prefilled
+    std::vector<int> ones(D.S, 1);
+    if (hipMemcpy(c->st.fin, ones.data(), sizeof(int) * D.S, hipMemcpyHostToDevice) != hipSuccess) rc = FM_EHIP;
+  }
+  if (rc != FM_OK) {
+    fprintf(stderr, "fm_create: %s\n", c->err.c_str());
+    for (void* p : c->allocs) (void)hipFree(p);
+    if (c->host_flag) (void)hipHostFree(c->host_flag);
+    delete c;
+    return rc;
+  }
+  // algorithmic weight bytes of one verify pass
+  const double d2 = (double)D.d * D.d;
+  const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
+  c->weight_bytes = c->esz * (nl * (6.0 + 2.0 * g.ffn_mult) * d2 + 2.0 * d2 + (double)D.V * D.d);
+  *out = c;
+  return FM_OK;
+}
+
+int fm_destroy(fm_ctx* c) {
+  if (!c) return FM_EINVAL;
+  (void)hipStreamSynchronize(c->stream);
+  for (void* p : c->allocs) (void)hipFree(p);
+  if (c->host_flag) (void)hipHostFree(c->host_flag);
+  delete c;
+  return FM_OK;
+}
+
+const char* fm_last_error(const fm_ctx* c) { return c ? c->err.c_str() : "null context"; }
+int32_t fm_block_max(const fm_ctx* c) { return c ? c->D.Bm : FM_EINVAL; }
+int64_t fm_blob_elems(const fm_ctx* c) { return c ? (int64_t)c->blob_elems : FM_EINVAL; }
+
+int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
+  if (!c) return FM_EINVAL;
+  if (!blob) return fail(c, FM_EINVAL, "null blob");
+  if (n_floats != c->blob_elems) return fail(c, FM_EINVAL, "blob has %zu floats, expected %zu", n_floats, c->blob_elems);
+  for (const LoadItem& it : c->items) {
+    size_t done = 0;
+    while (done < it.n) {
+      const size_t n = std::min(it.n - done, c->stage_elems);
+      if (it.f32) {
+        HIPCHK(c, hipMemcpyAsync((float*)it.dst + done, blob + it.blob_off + done, n * 4, hipMemcpyHostToDevice, c->stream));
+      } else {
+        HIPCHK(c, hipMemcpyAsync(c->stage, blob + it.blob_off + done, n * 4, hipMemcpyHostToDevice, c->stream));
+        if (c->bf16)
+          hipLaunchKernelGGL((k_convert<bf16_t>), dim3(1024), dim3(256), 0, c->stream, c->stage, (bf16_t*)it.dst + done, (long)n);
+        else
+          hipLaunchKernelGGL((k_convert<float>), dim3(1024), dim3(256), 0, c->stream, c->stage, (float*)it.dst + done, (long)n);
+      }
+      HIPCHK(c, hipStreamSynchronize(c->stream));  // the staging buffer is reused
+      done += n;
+    }
+  }
+  HIPCHK(c, hipGetLastError());
+  c->weights_loaded = true;
+  return FM_OK;
+}
+
+int fm_prefill_condition(fm_ctx* c, int32_t seq, const float* mem_dev) {
+  if (!c) return FM_EINVAL;
+  if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
+  if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range [0,%d)", seq, c->D.S);
+  if (!mem_dev) return fail(c, FM_EINVAL, "null condition memory");
+  int rc = c->bf16 ? prefill_impl<bf16_t>(c, seq, mem_dev) : prefill_impl<float>(c, seq, mem_dev);
+  if (rc == FM_OK) c->prefilled[seq] = true;
+  return rc;
+}
+
+int fm_draft(fm_ctx* c, int32_t* block_tok, int32_t* block_len) {
+  if (!c) return FM_EINVAL;
+  if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
+  if (!block_tok || !block_len) return fail(c, FM_EINVAL, "null block buffer");
+  return c->bf16 ? draft_impl<bf16_t>(c, block_tok, block_len, 1) : draft_impl<float>(c, block_tok, block_len, 1);
+}
+
+int fm_verify_block(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits, int32_t* accepted) {
+  if (!c) return FM_EINVAL;
+  if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
+  if (!block_tok || !block_len || !accepted) return fail(c, FM_EINVAL, "null block / accepted buffer");
+  return c->bf16 ? verify_impl<bf16_t>(c, block_tok, block_len, logits, accepted)
+                 : verify_impl<float>(c, block_tok, block_len, logits, accepted);
+}
+
+int fm_commit(fm_ctx* c, const int32_t* accepted) {
+  if (!c) return FM_EINVAL;
+  if (!accepted) return fail(c, FM_EINVAL, "null accepted buffer");
+  hipLaunchKernelGGL(k_commit, dim3(1), dim3(64), 0, c->stream, c->st, c->D, accepted);
+  HIPCHK(c, hipGetLastError());
+  return FM_OK;
+}
+
+int fm_set_budget(fm_ctx* c, int32_t max_faces) {
+  if (!c) return FM_EINVAL;
+  if (max_faces < 1 || 9 * max_faces > c->D.capc) return fail(c, FM_EINVAL, "max_faces %d outside [1,%d]", max_faces, c->D.capc / 9);
+  const int budget = 9 * max_faces;
+  HIPCHK(c, hipMemcpyAsync(c->st.budget, &budget, sizeof(int), hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  return FM_OK;
+}
+
+int fm_set_draft_replay(fm_ctx* c, const int32_t* stream_dev, int32_t stride, int32_t n_valid, float keep_prob, uint64_t seed) {
+  if (!c) return FM_EINVAL;
+  if (stream_dev && (stride < n_valid || n_valid < 0 || !(keep_prob >= 0.f && keep_prob <= 1.f)))
+    return fail(c, FM_EINVAL, "bad replay arguments");
+  c->replay = Replay{stream_dev, stride, n_valid, keep_prob, (unsigned long long)seed};
+  return FM_OK;
+}
+
+int fm_read_state(fm_ctx* c, int32_t* host_out) {
+  if (!c || !host_out) return FM_EINVAL;
+  const int S = c->D.S;
+  std::vector<int> P(S), mn(S), fin(S);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(P.data(), c->st.P, S * 4, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(mn.data(), c->st.main, S * 4, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(fin.data(), c->st.fin, S * 4, hipMemcpyDeviceToHost));
+  for (int s = 0; s < S; s++) {
+    host_out[s * 6 + 0] = P[s];
+    host_out[s * 6 + 1] = (P[s] + 2) / 3;
+    host_out[s * 6 + 2] = (P[s] + 8) / 9;
+    host_out[s * 6 + 3] = mn[s];
+    host_out[s * 6 + 4] = fin[s];
+    host_out[s * 6 + 5] = P[s];
+  }
+  return FM_OK;
+}
+
+int fm_verify_bytes(fm_ctx* c, double* host_bytes) {
+  if (!c || !host_bytes) return FM_EINVAL;
+  const int S = c->D.S;
+  std::vector<int> P(S), fin(S);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(P.data(), c->st.P, S * 4, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(fin.data(), c->st.fin, S * 4, hipMemcpyDeviceToHost));
+  double bytes = c->weight_bytes;
+  const fm_config& g = c->cfg;
+  for (int s = 0; s < S; s++) {
+    if (fin[s]) continue;
+    const double Lc = P[s], Lv = (P[s] + 2) / 3, Lf = (P[s] + 8) / 9, M = c->D.M;
+    bytes += c->esz * 2.0 * c->D.d *
+             ((g.l_cpre + g.l_cpost) * (Lc + M) + (g.l_vpre + g.l_vpost) * (Lv + M) + g.l_face * (Lf + M));
+  }
+  *host_bytes = bytes;
+  return FM_OK;
+}
+
+int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_tok, int32_t* out_len, fm_stats* stats) {
+  if (!c) return FM_EINVAL;
+  if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
+  if (!out_tok || !out_len) return fail(c, FM_EINVAL, "null output buffer");
+  for (int s = 0; s < c->D.S; s++)
+    if (!c->prefilled[s]) return fail(c, FM_ESTATE, "sequence %d has no condition memory", s);
+  TRY(fm_set_budget(c, max_faces));
+  const Dims& D = c->D;
+  HIPCHK(c, hipMemsetAsync(c->st.acc_hist, 0, 32 * sizeof(unsigned long long), c->stream));
+  HIPCHK(c, hipMemsetAsync(c->st.counters, 0, 2 * sizeof(unsigned long long), c->stream));
+  hipEvent_t e0, e1, eflag;
+  HIPCHK(c, hipEventCreate(&e0)); HIPCHK(c, hipEventCreate(&e1)); HIPCHK(c, hipEventCreate(&eflag));
+  HIPCHK(c, hipEventRecord(e0, c->stream));
+  const long max_steps = 9L * max_faces + 1;
+  const int check_every = 32;
+  bool pending = false, done = false;
+  int rc = FM_OK;
+  for (long step = 0; step < max_steps && !done && rc == FM_OK; step++) {
+    rc = c->bf16 ? draft_impl<bf16_t>(c, c->gen_tok, c->gen_len, speculative) : draft_impl<float>(c, c->gen_tok, c->gen_len, speculative);
+    if (rc == FM_OK)
+      rc = c->bf16 ? verify_impl<bf16_t>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc)
+                   : verify_impl<float>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc);
+    if (rc == FM_OK) rc = fm_commit(c, c->gen_acc);
+    if (rc != FM_OK) break;
+    if ((step + 1) % check_every == 0) {
+      // look at the flag copied one interval ago, then queue the next copy: the device never waits for the host
+      if (pending) {
+        HIPCHK(c, hipEventSynchronize(eflag));
+        if (c->host_flag[0] == 0) done = true;
+      }
+      if (!done) {
+        HIPCHK(c, hipMemcpyAsync(c->host_flag, c->st.alive, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipEventRecord(eflag, c->stream));
+        pending = true;
+      }
+    }
+  }
+  if (rc == FM_OK) {
+    HIPCHK(c, hipEventRecord(e1, c->stream));
+    // outputs: x_1 .. x_P per sequence
+    for (int s = 0; s < D.S; s++)
+      HIPCHK(c, hipMemcpyAsync(out_tok + (size_t)s * D.capc, c->st.hist + (size_t)s * (D.capc + 1) + 1, (size_t)D.capc * 4,
+                               hipMemcpyDeviceToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(out_len, c->st.P, (size_t)D.S * 4, hipMemcpyDeviceToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    if (stats) {
+      unsigned long long cnt[2], hist[32];
+      HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));
+      HIPCHK(c, hipMemcpy(hist, c->st.acc_hist, sizeof hist, hipMemcpyDeviceToHost));
+      float ms = 0.f;
+      HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+      stats->tokens = (int64_t)cnt[1];
+      stats->steps = 0;
+      for (int i = 0; i < 32; i++) { stats->acc_hist[i] = (int64_t)hist[i]; }
+      stats->steps = (int64_t)cnt[0];
+      stats->ms_total = ms;
+    }
+  }
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(eflag);
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,354 @@
+// Control kernels of one decode step: row bookkeeping for the verify pass, acceptance, commit,
+// draft-row set-up, distribution store and the merge that builds the next block.  Integer work
+// and a little fp32; every kernel is a single small launch.
+#pragma once
+#include "fm_device.h"
+#include "fm_kernels_basic.h"
+
+struct InvFreq { double v[32]; };  // base^(-i/32), computed in double on the host
+
+struct Dims {
+  int d, H, V, S, Bm, VB, FB, M;
+  int capc, capv, capf;
+  int Dc, m, n;          // draft configuration
+  int nspv, nspf;        // SP heads at the point / face level
+  int nhfc, nhfv;        // HF parameter sets at the coordinate / vertex level
+  int nbins, ban, eos, pad;
+};
+
+struct StateDev {
+  int *P, *main, *fin, *firedv, *firedf, *basec, *basev, *basef;
+  int *vlen, *vtok, *y, *acc;
+  int* hist;          // [S][capc + 1], hist[p] = x_p
+  int* budget;        // [1]
+  int* alive;         // [1] unfinished sequences; doubles as the run flag of the step
+  unsigned long long* acc_hist;  // [32]
+  unsigned long long* counters;  // [0] steps, [1] tokens
+};
+
+__device__ __forceinline__ int eff_block_len(const StateDev& st, const Dims& D, int s, const int* block_len) {
+  if (st.fin[s]) return 0;
+  int len = block_len[s];
+  len = min(len, D.Bm);
+  len = min(len, st.budget[0] - st.P[s]);
+  return max(len, 0);
+}
+
+__global__ __launch_bounds__(256) void k_verify_setup(StateDev st, Dims D, InvFreq inv, const int* __restrict__ block_tok,
+                                                       const int* __restrict__ block_len, int* pos_c, int* pos_v, int* pos_f,
+                                                       int* limx_c, int* limx_v, int* limx_f, float2* cs_c, float2* cs_v,
+                                                       float2* cs_f) {
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < D.S * D.Bm; idx += 256) {
+    const int s = idx / D.Bm, i = idx % D.Bm;
+    const int len = eff_block_len(st, D, s, block_len);
+    const bool on = i < len;
+    pos_c[idx] = on ? st.P[s] + i : -1;
+    limx_c[idx] = on ? D.M - 1 : -1;
+    int t = on ? block_tok[idx] : D.pad;
+    if (t < 0 || t >= D.V) t = D.pad;
+    st.vtok[idx] = t;
+    if (i == 0) st.vlen[s] = len;
+  }
+  for (int idx = tid; idx < D.S * D.VB; idx += 256) {
+    const int s = idx / D.VB, k = idx % D.VB;
+    const int len = eff_block_len(st, D, s, block_len), P = st.P[s];
+    const int j = (P + 2) / 3 + k;
+    const bool on = 3 * j < P + len;
+    pos_v[idx] = on ? j : -1;
+    limx_v[idx] = on ? D.M - 1 : -1;
+  }
+  for (int idx = tid; idx < D.S * D.FB; idx += 256) {
+    const int s = idx / D.FB, k = idx % D.FB;
+    const int len = eff_block_len(st, D, s, block_len), P = st.P[s];
+    const int f = (P + 8) / 9 + k;
+    const bool on = 9 * f < P + len;
+    pos_f[idx] = on ? f : -1;
+    limx_f[idx] = on ? D.M - 1 : -1;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < D.S * D.Bm * 32; idx += 256) {
+    const int p = pos_c[idx >> 5];
+    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx & 31];
+    cs_c[idx] = make_float2((float)cos(a), (float)sin(a));
+  }
+  for (int idx = tid; idx < D.S * D.VB * 32; idx += 256) {
+    const int p = pos_v[idx >> 5];
+    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx & 31];
+    cs_v[idx] = make_float2((float)cos(a), (float)sin(a));
+  }
+  for (int idx = tid; idx < D.S * D.FB * 32; idx += 256) {
+    const int p = pos_f[idx >> 5];
+    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx & 31];
+    cs_f[idx] = make_float2((float)cos(a), (float)sin(a));
+  }
+}
+
+// accepted = 1 + number of leading drafts that equal the backbone's greedy prediction
+__global__ void k_accept(StateDev st, Dims D, int* __restrict__ accepted_out) {
+  const int s = threadIdx.x;
+  if (s >= D.S) return;
+  const int len = st.vlen[s];
+  int a = 0;
+  if (len > 0) {
+    a = 1;
+    while (a < len && st.vtok[s * D.Bm + a] == st.y[s * D.Bm + a - 1]) a++;
+  }
+  st.acc[s] = a;
+  if (accepted_out) accepted_out[s] = a;
+}
+
+__global__ void k_commit(StateDev st, Dims D, const int* __restrict__ accepted) {
+  const int s = threadIdx.x;
+  __shared__ int any_live;
+  if (s == 0) any_live = 0;
+  __syncthreads();
+  if (s < D.S) {
+    const int len = st.vlen[s];
+    if (len > 0) {
+      any_live = 1;
+      int a = accepted[s];
+      a = max(1, min(a, len));
+      for (int i = 1; i < a; i++)
+        if (st.vtok[s * D.Bm + i] == D.eos) { a = i; break; }   // an accepted EOS draft is not fed: it becomes the main token
+      int P = st.P[s];
+      int* h = st.hist + (long)s * (D.capc + 1);
+      for (int i = 0; i < a; i++) h[P + i] = st.vtok[s * D.Bm + i];
+      P += a;
+      const int mainTok = st.y[s * D.Bm + a - 1];
+      h[P] = mainTok;
+      st.P[s] = P;
+      st.main[s] = mainTok;
+      st.fin[s] = (mainTok == D.eos || P >= st.budget[0]) ? 1 : 0;
+      st.vlen[s] = 0;
+      atomicAdd(&st.acc_hist[min(a, 31)], 1ull);
+      atomicAdd(&st.counters[1], (unsigned long long)a);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int alive = 0;
+    for (int i = 0; i < D.S; i++) alive += st.fin[i] ? 0 : 1;
+    st.alive[0] = alive;
+    if (any_live) st.counters[0] += 1;
+  }
+}
+
+// Reset one sequence to x_0 = BOS with empty caches and no draft rows.
+__global__ void k_reset_seq(StateDev st, Dims D, int s, int bos) {
+  if (threadIdx.x != 0) return;
+  st.P[s] = 0; st.main[s] = bos; st.fin[s] = 0;
+  st.firedv[s] = -1; st.firedf[s] = -1;
+  st.basec[s] = -1000000; st.basev[s] = -1; st.basef[s] = -1;
+  st.vlen[s] = 0; st.acc[s] = 0;
+  st.hist[(long)s * (D.capc + 1)] = bos;
+  int alive = 0;
+  for (int i = 0; i < D.S; i++) alive += st.fin[i] ? 0 : 1;
+  st.alive[0] = alive;
+}
+
+// ------------------------------------------------------------------------------------------
+// Draft stage
+// ------------------------------------------------------------------------------------------
+struct DraftRows {
+  // five row sets: 0 SP coordinate, 1 SP point, 2 SP face, 3 HF vertex, 4 HF coordinate
+  const float** src[5];
+  int* pos[5];
+  int* lim[5];
+  int* limx[5];
+  float2* cs[5];
+  int *alive, *firev, *firef;   // [S]
+  int* flags;                   // [0] any alive with P > 0, [1] any point firing, [2] any face firing
+};
+
+struct DraftBufs {
+  const float *tap_c, *tap_v, *tap_f, *ring_yf;   // rings
+  const float *spv_out, *spf_out, *hfv_out;        // head outputs feeding the HF blocks
+};
+
+__device__ __forceinline__ void set_row(const DraftRows& R, int set, int r, const float* src, int pos, int lim, int M,
+                                        const InvFreq& inv, int lane32) {
+  if (lane32 == 0) {
+    R.src[set][r] = src;
+    R.pos[set][r] = lim >= 0 ? pos : -1;
+    R.lim[set][r] = lim;
+    R.limx[set][r] = lim >= 0 ? M - 1 : -1;
+  }
+  const double a = (lim >= 0 ? (double)pos : 0.0) * inv.v[lane32];
+  R.cs[set][(long)r * 32 + lane32] = make_float2((float)cos(a), (float)sin(a));
+}
+
+// one workgroup, 32 threads per row at a time
+__global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFreq inv, DraftRows R, DraftBufs B) {
+  const int lane32 = threadIdx.x & 31, grp = threadIdx.x >> 5;  // 8 groups of 32
+  __shared__ int f_any[3];
+  if (threadIdx.x < 3) f_any[threadIdx.x] = 0;
+  __syncthreads();
+  const int d = D.d;
+  for (int s = 0; s < D.S; s++) {
+    const int P = st.P[s];
+    const bool alive = !st.fin[s] && P > 0;
+    const int spos = P - 1;
+    const int v = alive ? spos / 3 : 0, f = alive ? spos / 9 : 0;
+    const bool firev = alive && D.m > 0 && (v % 3) != 0 && st.firedv[s] != v;
+    const bool firef = alive && D.n > 0 && st.firedf[s] != f;
+    if (threadIdx.x == 0) {
+      R.alive[s] = alive; R.firev[s] = firev; R.firef[s] = firef;
+      if (alive) f_any[0] = 1;
+      if (firev) f_any[1] = 1;
+      if (firef) f_any[2] = 1;
+    }
+    const float* tapc = B.tap_c + ((long)s * 32 + (spos & 31)) * d;
+    const float* tapv = B.tap_v + ((long)s * 16 + (v & 15)) * d;
+    const float* tapf = B.tap_f + ((long)s * 8 + (f & 7)) * d;
+    const float* yf = B.ring_yf + ((long)s * 8 + (f & 7)) * d;
+    // set 0: coordinate SP heads k = 1..Dc on the coordinate tap at s
+    for (int k = grp; k < D.Dc; k += 8) set_row(R, 0, s * D.Dc + k, tapc, spos, alive ? spos : -1, D.M, inv, lane32);
+    // set 1: point SP heads on the vertex tap of v
+    for (int k = grp; k < D.nspv; k += 8) set_row(R, 1, s * D.nspv + k, tapv, v, firev ? v : -1, D.M, inv, lane32);
+    // set 2: face SP heads on the face tap of f
+    for (int k = grp; k < D.nspf; k += 8) set_row(R, 2, s * D.nspf + k, tapf, f, firef ? f : -1, D.M, inv, lane32);
+    // set 3: vertex-level HF, vertex offsets j = 1..n/3-1 from vertex token 3f; input = face feature j/3
+    for (int q = grp; q < D.nhfv; q += 8) {
+      const int j = q + 1;
+      const float* src = (j < 3) ? yf : B.spf_out + ((long)s * D.nspf + (j / 3 - 1)) * d;
+      set_row(R, 3, s * D.nhfv + q, src, 3 * f + j, firef ? 3 * f : -1, D.M, inv, lane32);
+    }
+    // set 4: coordinate-level HF, offsets t = 3..; pipe 0 = point pipeline, pipe 1 = face pipeline
+    for (int q = grp; q < 2 * D.nhfc; q += 8) {
+      const int pipe = q / D.nhfc, t = q % D.nhfc + 3;
+      const int r = s * 2 * D.nhfc + q;
+      if (pipe == 0) {
+        const bool on = firev && t < D.m;
+        const float* src = B.spv_out + ((long)s * max(D.nspv, 1) + min(t / 3 - 1, max(D.nspv - 1, 0))) * d;
+        set_row(R, 4, r, src, 3 * v + t, on ? 3 * v : -1, D.M, inv, lane32);
+      } else {
+        const bool on = firef && t < D.n;
+        const float* src = B.hfv_out + ((long)s * max(D.nhfv, 1) + min(t / 3 - 1, max(D.nhfv - 1, 0))) * d;
+        set_row(R, 4, r, src, 9 * f + t, on ? 9 * f : -1, D.M, inv, lane32);
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < 3) R.flags[threadIdx.x] = f_any[threadIdx.x];
+}
+
+// softmax of one LM row of the draft heads into the distribution store of its level
+__global__ __launch_bounds__(256) void k_dist_store(const float* __restrict__ logits, Dims D, DraftRows R, float* dist_c,
+                                                     float* dist_v, float* dist_f) {
+  const int r = blockIdx.x;
+  float* dst = nullptr;
+  if (r < D.S * D.Dc) {
+    const int s = r / D.Dc, k = r % D.Dc;
+    if (R.alive[s]) dst = dist_c + ((long)s * D.Dc + k) * D.V;
+  } else {
+    const int rr = r - D.S * D.Dc;
+    const int s = rr / (2 * D.nhfc), q = rr % (2 * D.nhfc);
+    const int pipe = q / D.nhfc, t = q % D.nhfc + 3;
+    if (pipe == 0 && R.firev[s] && t < D.m) dst = dist_v + ((long)s * D.nhfc + (t - 3)) * D.V;
+    if (pipe == 1 && R.firef[s] && t < D.n) dst = dist_f + ((long)s * D.nhfc + (t - 3)) * D.V;
+  }
+  if (!dst) return;
+  const float* x = logits + (long)r * D.V;
+  __shared__ float red[4];
+  float mx = -INFINITY;
+  for (int i = threadIdx.x; i < D.V; i += 256) mx = fmaxf(mx, x[i]);
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < D.V; i += 256) sum += expf(x[i] - mx);
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  sum = red[0] + red[1] + red[2] + red[3];
+  const float inv = 1.0f / sum;
+  for (int i = threadIdx.x; i < D.V; i += 256) dst[i] = expf(x[i] - mx) * inv;
+}
+
+struct Replay {
+  const int* stream;  // [S][stride], stream[p - 1] = x_p
+  int stride, n_valid;
+  float keep;
+  unsigned long long seed;
+};
+
+__device__ __forceinline__ float replay_uniform(unsigned long long seed, unsigned long long seq, unsigned long long pos) {
+  unsigned long long z = seed * 0x9E3779B97F4A7C15ull + seq * 0xBF58476D1CE4E5B9ull + pos * 0x94D049BB133111EBull +
+                         0x2545F4914F6CDD1Dull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z = z ^ (z >> 31);
+  return (float)(z >> 40) * (1.0f / 16777216.0f);
+}
+
+// One workgroup per sequence: update the draft bookkeeping, average the distributions that cover
+// each future position, take the greedy token, stop at the first uncovered position.
+__global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R, const float* __restrict__ dist_c,
+                                                const float* __restrict__ dist_v, const float* __restrict__ dist_f,
+                                                Replay rp, int speculative, int* __restrict__ block_tok,
+                                                int* __restrict__ block_len) {
+  __shared__ float sv[4];
+  __shared__ int si[4];
+  const int s = blockIdx.x;
+  int* tok = block_tok + (long)s * D.Bm;
+  if (st.fin[s]) {
+    if (threadIdx.x == 0) block_len[s] = 0;
+    return;
+  }
+  const int P = st.P[s], budget = st.budget[0];
+  if (threadIdx.x == 0) tok[0] = st.main[s];
+  if (P == 0 || !speculative) {
+    if (threadIdx.x == 0) block_len[s] = 1;
+    return;
+  }
+  const int spos = P - 1;
+  const int basec = spos;
+  const int basev = R.firev[s] ? 3 * (spos / 3) : st.basev[s];
+  const int basef = R.firef[s] ? 9 * (spos / 9) : st.basef[s];
+  __syncthreads();   // every thread has read the old state
+  if (threadIdx.x == 0) {
+    st.basec[s] = basec; st.basev[s] = basev; st.basef[s] = basef;
+    if (R.firev[s]) st.firedv[s] = spos / 3;
+    if (R.firef[s]) st.firedf[s] = spos / 9;
+  }
+  const int nlim = D.ban ? D.nbins : D.V;
+  int len = 1;
+  for (int p = spos + 2; len < D.Bm && p < budget; p++) {
+    const float* rows[3];
+    int cnt = 0;
+    const int kc = p - (basec + 2);
+    if (kc >= 0 && kc < D.Dc) rows[cnt++] = dist_c + ((long)s * D.Dc + kc) * D.V;
+    const int tv = p - 1 - basev;
+    if (basev >= 0 && tv >= 3 && tv < D.m) rows[cnt++] = dist_v + ((long)s * D.nhfc + (tv - 3)) * D.V;
+    const int tf = p - 1 - basef;
+    if (basef >= 0 && tf >= 3 && tf < D.n) rows[cnt++] = dist_f + ((long)s * D.nhfc + (tf - 3)) * D.V;
+    if (cnt == 0) break;
+    const float inv = 1.0f / (float)cnt;
+    float bv = -INFINITY;
+    int bi = 0x7fffffff;
+    for (int i = threadIdx.x; i < nlim; i += 256) {
+      float a = rows[0][i];
+      if (cnt > 1) a += rows[1][i];
+      if (cnt > 2) a += rows[2][i];
+      argmax_merge(bv, bi, a * inv, i);
+    }
+    const int b = block_argmax(bv, bi, sv, si);
+    if (threadIdx.x == 0) tok[len] = b;
+    len++;
+  }
+  if (rp.stream) {
+    // synthetic draft source: the known continuation, each token kept with probability `keep`
+    len = 1;
+    for (int p = P + 1; len < D.Bm && p < budget && p <= rp.n_valid; p++, len++) {
+      if (threadIdx.x == 0) {
+        const int truth = rp.stream[(long)s * rp.stride + p - 1];
+        const bool keep = replay_uniform(rp.seed, (unsigned long long)s, (unsigned long long)p) < rp.keep;
+        tok[len] = keep ? truth : (truth + 1) % D.nbins;
+      }
+    }
+  }
+  if (threadIdx.x == 0) block_len[s] = len;
+}

@@ -1,0 +1,125 @@
+"""Drives the HIP path (through the C-ABI binding) and the CPU oracle in lock step.
+
+Protocol: both start from the same seeded blob and condition memories.  Every step compares the
+draft block, the verify logits (max-abs), the greedy predictions, the accepted length and the
+committed lengths.  Where a token differs, the oracle's own scores decide: if the margin between
+its choice and the device's choice is below the tolerance the flip is allowed and the oracle is
+forced onto the device's token; anything else is a failure.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import synth_inputs as si
+from oracle import speculative as osp
+from oracle.hourglass import Model, SeqState, forward_block
+from paper_2511_15618_amd import FlashMesh
+from paper_2511_15618_amd.binding import config_struct
+
+
+class Report:
+    def __init__(self):
+        self.steps = 0
+        self.max_logit_err = 0.0
+        self.token_flips = 0
+        self.draft_flips = 0
+        self.accepted = []
+        self.block_lens = []
+
+    def __repr__(self):
+        return (f"steps={self.steps} max|dlogit|={self.max_logit_err:.3e} token_flips={self.token_flips} "
+                f"draft_flips={self.draft_flips} mean_acc={np.mean(self.accepted) if self.accepted else 0:.2f}")
+
+
+def make_pair(cfg, work=np.float64, max_tokens=None):
+    w = si.make_weights(cfg, 0)
+    model = Model(cfg, w, work=work)
+    fm = FlashMesh(config_struct(cfg, max_tokens=max_tokens))
+    assert fm.blob_elems() == si.blob_size(cfg)
+    fm.load_weights(si.pack_blob(cfg, w))
+    mems = [si.make_memory(cfg, s) for s in range(cfg.batch)]
+    for s, m in enumerate(mems):
+        fm.prefill_condition(s, torch.from_numpy(m).cuda())
+    states = [SeqState(model, mems[s], max_tokens or cfg.max_tokens) for s in range(cfg.batch)]
+    return model, fm, states
+
+
+def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work=np.float64, check_logits=True):
+    """Run the decode loop on both sides; returns (Report, device token streams)."""
+    model, fm, states = make_pair(cfg, work=work)
+    fm.set_budget(faces)
+    budget = 9 * faces
+    if replay is not None:
+        fm.set_draft_replay(*replay)
+    S, Bm, V = cfg.batch, fm.block_max, cfg.vocab
+    tok, ln = fm.new_block()
+    logits = torch.zeros(S, Bm, V, dtype=torch.float32, device="cuda")
+    acc = torch.zeros(S, dtype=torch.int32, device="cuda")
+    rep = Report()
+    nlim = cfg.n_bins if cfg.ban_specials else cfg.vocab
+    while True:
+        st_dev = fm.read_state()
+        if all(st_dev[s, 4] for s in range(S)):
+            break
+        if max_steps is not None and rep.steps >= max_steps:
+            break
+        if drafts == "none":
+            tok.zero_()
+            tok[:, 0] = torch.from_numpy(st_dev[:, 3].copy()).cuda()
+            ln[:] = torch.from_numpy((1 - st_dev[:, 4]).astype(np.int32)).cuda()
+        else:
+            fm.draft(tok, ln)
+        fm.verify_block(tok, ln, logits, acc)
+        torch.cuda.synchronize()
+        h_tok, h_len = tok.cpu().numpy(), ln.cpu().numpy()
+        h_logits, h_acc = logits.cpu().numpy(), acc.cpu().numpy()
+        fm.commit(acc)
+        for s in range(S):
+            st = states[s]
+            if st.finished or st.P >= budget:
+                assert h_len[s] == 0 and h_acc[s] == 0, (s, h_len[s], h_acc[s])
+                continue
+            block_dev = [int(t) for t in h_tok[s, :h_len[s]]]
+            if drafts == "native" and replay is None:
+                merged = []
+                block_ref = osp.draft(model, st, budget, merged)
+                assert len(block_ref) == len(block_dev), (rep.steps, s, block_ref, block_dev)
+                assert block_ref[0] == block_dev[0]
+                for i in range(1, len(block_ref)):
+                    if block_ref[i] != block_dev[i]:
+                        dist = merged[i - 1]
+                        gap = dist[block_ref[i]] - dist[block_dev[i]]
+                        assert gap <= tol, ("draft token beyond tolerance", rep.steps, s, i, gap)
+                        rep.draft_flips += 1
+            else:
+                assert block_dev[0] == st.main and 1 <= len(block_dev) <= min(Bm, budget - st.P)
+            lg = forward_block(model, st, block_dev)
+            B = len(block_dev)
+            if check_logits:
+                err = float(np.abs(lg - h_logits[s, :B]).max())
+                rep.max_logit_err = max(rep.max_logit_err, err)
+                assert err <= tol, ("logits beyond tolerance", rep.steps, s, err)
+            y_dev = [int(np.argmax(h_logits[s, i, :nlim])) for i in range(B)]
+            y_ref = [osp.pick(lg[i], cfg) for i in range(B)]
+            for i in range(B):
+                if y_ref[i] != y_dev[i]:
+                    gap = lg[i, y_ref[i]] - lg[i, y_dev[i]]
+                    assert gap <= tol, ("greedy token beyond tolerance", rep.steps, s, i, gap)
+                    rep.token_flips += 1
+                    y_ref[i] = y_dev[i]
+            a = osp.accept_length(block_dev, y_ref)
+            assert a == h_acc[s], ("accepted length", rep.steps, s, a, h_acc[s])
+            osp.commit(model, st, block_dev, y_ref, a)
+            if st.P >= budget:
+                st.finished = True
+            rep.accepted.append(a)
+            rep.block_lens.append(B)
+        rep.steps += 1
+        st_dev = fm.read_state()
+        for s in range(S):
+            st = states[s]
+            assert tuple(st_dev[s, :4]) == (st.P, (st.P + 2) // 3, (st.P + 8) // 9, st.main), (rep.steps, s, st_dev[s], st.P, st.main)
+            assert bool(st_dev[s, 4]) == bool(st.finished)
+    streams = [st.tokens[1:] + [st.main] for st in states]
+    return rep, streams, fm
