@@ -38,7 +38,7 @@ extern "C" {
 #define FM_EHIP (-4)   /* a HIP runtime call failed; see fm_last_error        */
 
 #define FM_DTYPE_F32 0  /* fp32 storage and arithmetic                          */
-#define FM_DTYPE_BF16 1 /* bf16 weights / K,V / GEMM inputs, fp32 accumulation  */
+#define FM_DTYPE_BF16 1 /* bf16-valued weights held as IEEE half (exact), half K/V and GEMM inputs, fp32 accumulation */
 
 typedef struct fm_ctx fm_ctx; /* opaque, owned by the library */
 

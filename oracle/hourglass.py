@@ -16,11 +16,12 @@ token f pools vertex tokens 3f-2..3f and is upsampled onto vertex tokens
 3f..3f+2.  Upsampling is repeat plus the skip connection from before the
 shortening.  Everything is causal.
 
-bf16 configurations: weights arrive already rounded; `rnd` rounds every GEMM
-input, q/k/v and the condition memory to bf16 (the configuration list asks for
-bf16 weights/activations with wider accumulation).  For f32 configurations rnd
-is the identity.  Accumulation, softmax, the residual stream, norms and logits
-stay in the working precision (float64 by default).
+bf16 configurations: the weights arrive already rounded to bf16 values and all
+arithmetic on them is done in the working precision (float64 by default) with
+no further rounding: the oracle is the exact forward function of the
+bf16-valued parameters.  `act_round=True` additionally rounds every GEMM
+input, q/k/v and the condition memory to bf16, which is only used to study how
+reduced-precision activations perturb the logits.
 """
 from __future__ import annotations
 
@@ -35,7 +36,7 @@ LEVEL_OF = {"cpre": "c", "cpost": "c", "vpre": "v", "vpost": "v", "face": "f"}
 class Model:
     """Holds the parameters (cast to the working precision) and the hyper-parameters."""
 
-    def __init__(self, cfg, weights: dict, work=np.float64, act_round=True):
+    def __init__(self, cfg, weights: dict, work=np.float64, act_round=False):
         self.cfg = cfg
         self.work = work
         self.w = {k: np.asarray(v, dtype=work) for k, v in weights.items()}

@@ -561,7 +561,7 @@ int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
       } else {
         HIPCHK(c, hipMemcpyAsync(c->stage, blob + it.blob_off + done, n * 4, hipMemcpyHostToDevice, c->stream));
         if (c->bf16)
-          hipLaunchKernelGGL((k_convert<bf16_t>), dim3(1024), dim3(256), 0, c->stream, c->stage, (bf16_t*)it.dst + done, (long)n);
+          hipLaunchKernelGGL((k_convert<f16_t>), dim3(1024), dim3(256), 0, c->stream, c->stage, (f16_t*)it.dst + done, (long)n);
         else
           hipLaunchKernelGGL((k_convert<float>), dim3(1024), dim3(256), 0, c->stream, c->stage, (float*)it.dst + done, (long)n);
       }
@@ -579,7 +579,7 @@ int fm_prefill_condition(fm_ctx* c, int32_t seq, const float* mem_dev) {
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
   if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range [0,%d)", seq, c->D.S);
   if (!mem_dev) return fail(c, FM_EINVAL, "null condition memory");
-  int rc = c->bf16 ? prefill_impl<bf16_t>(c, seq, mem_dev) : prefill_impl<float>(c, seq, mem_dev);
+  int rc = c->bf16 ? prefill_impl<f16_t>(c, seq, mem_dev) : prefill_impl<float>(c, seq, mem_dev);
   if (rc == FM_OK) c->prefilled[seq] = true;
   return rc;
 }
@@ -588,14 +588,14 @@ int fm_draft(fm_ctx* c, int32_t* block_tok, int32_t* block_len) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
   if (!block_tok || !block_len) return fail(c, FM_EINVAL, "null block buffer");
-  return c->bf16 ? draft_impl<bf16_t>(c, block_tok, block_len, 1) : draft_impl<float>(c, block_tok, block_len, 1);
+  return c->bf16 ? draft_impl<f16_t>(c, block_tok, block_len, 1) : draft_impl<float>(c, block_tok, block_len, 1);
 }
 
 int fm_verify_block(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits, int32_t* accepted) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
   if (!block_tok || !block_len || !accepted) return fail(c, FM_EINVAL, "null block / accepted buffer");
-  return c->bf16 ? verify_impl<bf16_t>(c, block_tok, block_len, logits, accepted)
+  return c->bf16 ? verify_impl<f16_t>(c, block_tok, block_len, logits, accepted)
                  : verify_impl<float>(c, block_tok, block_len, logits, accepted);
 }
 
@@ -680,9 +680,9 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
   bool pending = false, done = false;
   int rc = FM_OK;
   for (long step = 0; step < max_steps && !done && rc == FM_OK; step++) {
-    rc = c->bf16 ? draft_impl<bf16_t>(c, c->gen_tok, c->gen_len, speculative) : draft_impl<float>(c, c->gen_tok, c->gen_len, speculative);
+    rc = c->bf16 ? draft_impl<f16_t>(c, c->gen_tok, c->gen_len, speculative) : draft_impl<float>(c, c->gen_tok, c->gen_len, speculative);
     if (rc == FM_OK)
-      rc = c->bf16 ? verify_impl<bf16_t>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc)
+      rc = c->bf16 ? verify_impl<f16_t>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc)
                    : verify_impl<float>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc);
     if (rc == FM_OK) rc = fm_commit(c, c->gen_acc);
     if (rc != FM_OK) break;

@@ -1,5 +1,5 @@
-// Generic kernels (fp32 arithmetic, storage type T = float or bf16).  They are the whole path for
-// fp32 configurations and the small/irregular pieces of the bf16 path; the bf16 hot kernels (MFMA
+// Generic kernels (fp32 arithmetic, storage type T = float or half).  They are the whole path for
+// fp32 configurations and the small/irregular pieces of the half-precision path; its hot kernels (MFMA
 // GEMM and attention) live in fm_kernels_mfma.h.
 //
 // Row convention: a "row set" has S * RPS slots, slot r belongs to sequence r / RPS.  Each set has
