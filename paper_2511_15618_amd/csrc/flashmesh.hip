@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "fm_device.h"
@@ -41,7 +42,7 @@ struct HfLevel {
   void *wq, *w1, *w2;
 };
 
-struct LoadItem { size_t blob_off, n; void* dst; bool f32; };
+struct LoadItem { size_t blob_off, n; void* dst; bool f32; int N, K; };  // N, K > 0: linear weight [N, K]
 
 }  // namespace
 
@@ -79,7 +80,7 @@ struct fm_ctx {
   float* h[3];
   void *xn, *qT, *attT, *mid;
   float *qkv, *logits;
-  float* attn_ws;     // split-KV partials of the MFMA attention
+  MfmaRes mres;       // workspaces of the MFMA kernels (half-precision path)
   float* stage;       // staging for weight conversion / prefill GEMM output
   size_t stage_elems;
   // draft scratch
@@ -143,7 +144,7 @@ template <typename T>
 void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, long gsw, void* Y, long ldy, long gsy,
           const float* R, long ldr, long gsr, int M, int N, int K, int groups, const int* flag) {
   GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag};
-  if (mfma_gemm_launch<T>(a, epi, groups, c->stream)) return;
+  if (mfma_gemm_launch<T>(c->mres, a, epi, groups, c->stream)) return;
   dim3 grid((N + 3) / 4, groups);
   if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_simple<T, EPI_F32>), grid, dim3(256), 0, c->stream, a);
   else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_simple<T, EPI_GELU_T>), grid, dim3(256), 0, c->stream, a);
@@ -153,7 +154,7 @@ void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, 
 template <typename T>
 void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
                long seq_stride, int cap, void* out, const int* flag) {
-  if (mfma_attn_launch<T>(q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, c->attn_ws, flag, c->stream)) return;
+  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, c->stream)) return;
   hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
                      (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag);
 }
@@ -163,6 +164,23 @@ void rmsnorm(fm_ctx* c, const float* src, const float* const* srcptr, const floa
              float* keep, int rows, const int* flag) {
   hipLaunchKernelGGL((k_rmsnorm<T>), dim3(rows), dim3(256), 0, c->stream, src, srcptr, gain, gain_mod, (T*)out, keep,
                      c->D.d, c->cfg.rms_eps, flag);
+}
+
+// rotary position on q (and k), conversion to the storage type, optional append to a K/V cache
+template <typename T>
+void rope_append(fm_ctx* c, const float* qkv, long ldq, const float2* cs, const int* pos, int rows, int RPS, void* q,
+                 void* Kc, void* Vc, int cap, const int* flag) {
+  if (std::is_same<T, f16_t>::value)
+    hipLaunchKernelGGL(k_rope_append_h, dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (f16_t*)q, (f16_t*)Kc,
+                       (f16_t*)Vc, c->D.H, (cap + 31) / 32, flag);
+  else
+    hipLaunchKernelGGL((k_rope_append<float>), dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (float*)q,
+                       (float*)Kc, (float*)Vc, c->D.H, cap, flag);
+}
+
+// elements of one (sequence) slice of a K or V cache with `cap` key positions
+size_t cache_seq_elems(const fm_ctx* c, int cap) {
+  return c->bf16 ? (size_t)c->D.H * ((cap + 31) / 32) * 2048 : (size_t)c->D.H * cap * FM_HD;
 }
 
 // one transformer block on the row set of `level` (Sec. 3.1: self-attention, cross-attention to c, FFN)
@@ -176,13 +194,12 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
   const int* flag = c->st.alive;
   rmsnorm<T>(c, h, nullptr, L.g1, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_F32, c->xn, d, 0, L.wqkv, 0, c->qkv, 3 * d, 0, nullptr, 0, 0, rows, 3 * d, d, 1, flag);
-  hipLaunchKernelGGL((k_rope_append<T>), dim3(rows), dim3(256), 0, c->stream, c->qkv, (long)3 * d, c->cs[level],
-                     c->pos[level], RPS, (T*)c->qT, (T*)L.Kc, (T*)L.Vc, D.H, cap, flag);
-  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)D.H * cap * FM_HD, cap, c->attT, flag);
+  rope_append<T>(c, c->qkv, (long)3 * d, c->cs[level], c->pos[level], rows, RPS, c->qT, L.Kc, L.Vc, cap, flag);
+  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag);
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   rmsnorm<T>(c, h, nullptr, L.g2, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_T, c->xn, d, 0, L.cq, 0, c->qT, d, 0, nullptr, 0, 0, rows, d, d, 1, flag);
-  attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)D.H * D.M * FM_HD, D.M, c->attT, flag);
+  attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)cache_seq_elems(c, D.M), D.M, c->attT, flag);
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.co, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   rmsnorm<T>(c, h, nullptr, L.g3, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_GELU_T, c->xn, d, 0, L.w1, 0, c->mid, c->ff, 0, nullptr, 0, 0, rows, c->ff, d, 1, flag);
@@ -256,12 +273,11 @@ void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level,
   const long dd = (long)d * d;
   rmsnorm<T>(c, nullptr, c->dr.src[set], sp.g, G, c->dxn, c->dkeep, rows, flag);
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.wq, dd, c->dtmp, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
-  hipLaunchKernelGGL((k_rope_append<T>), dim3(rows), dim3(256), 0, c->stream, c->dtmp, (long)d, c->dr.cs[set],
-                     c->dr.pos[set], G, (T*)c->dq, (T*)nullptr, (T*)nullptr, D.H, cap, flag);
-  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)D.H * cap * FM_HD, cap, c->datt, flag);
+  rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[set], c->dr.pos[set], rows, G, c->dq, nullptr, nullptr, cap, flag);
+  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag);
   gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.wo, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   gemm<T>(c, EPI_T, c->dxn, (long)G * d, d, sp.cq, dd, c->dq, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
-  attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)D.H * D.M * FM_HD, D.M, c->datt, flag);
+  attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)cache_seq_elems(c, D.M), D.M, c->datt, flag);
   gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.co, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.lin, dd, out, ldo, gso, c->dkeep, (long)G * d, d, D.S, d, d, G, flag);
 }
@@ -279,9 +295,8 @@ void run_hf(fm_ctx* c, int set, const HfLevel& hf, int mult, const Layer& last, 
   const long ld = (long)G * d;         // stride between those rows
   rmsnorm<T>(c, nullptr, c->dr.src[set], hf.g, G, c->dxn, c->dkeep, rows, flag);
   gemm<T>(c, EPI_F32, c->dxn, ld, d, hf.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, Mg, d, d, G, flag);
-  hipLaunchKernelGGL((k_rope_append<T>), dim3(rows), dim3(256), 0, c->stream, c->dtmp, (long)d, c->dr.cs[set],
-                     c->dr.pos[set], per_seq, (T*)c->dq, (T*)nullptr, (T*)nullptr, D.H, cap, flag);
-  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)D.H * cap * FM_HD, cap, c->datt, flag);
+  rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[set], c->dr.pos[set], rows, per_seq, c->dq, nullptr, nullptr, cap, flag);
+  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag);
   gemm<T>(c, EPI_GELU_T, c->datt, ld, d, hf.w1, dh, c->dmid, (long)G * c->hff, c->hff, nullptr, 0, 0, Mg, c->hff, d, G, flag);
   gemm<T>(c, EPI_F32, c->dmid, (long)G * c->hff, c->hff, hf.w2, dh, out, ld, d, c->dkeep, ld, d, Mg, d, c->hff, G, flag);
 }
@@ -329,9 +344,13 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
   for (int st = 0; st < 5; st++)
     for (auto& L : c->stacks[st]) {
       gemm<T>(c, EPI_F32, memT, d, 0, L.ckv, 0, kv, 2 * d, 0, nullptr, 0, 0, D.M, 2 * d, d, 1, nullptr);
-      T* Km = (T*)L.Km + (size_t)seq * D.H * D.M * FM_HD;
-      T* Vm = (T*)L.Vm + (size_t)seq * D.H * D.M * FM_HD;
-      hipLaunchKernelGGL((k_mem_kv_store<T>), dim3(D.M), dim3(256), 0, c->stream, kv, Km, Vm, D.H, D.M);
+      T* Km = (T*)L.Km + (size_t)seq * cache_seq_elems(c, D.M);
+      T* Vm = (T*)L.Vm + (size_t)seq * cache_seq_elems(c, D.M);
+      if (std::is_same<T, f16_t>::value)
+        hipLaunchKernelGGL(k_mem_kv_store_h, dim3(D.M), dim3(256), 0, c->stream, kv, (f16_t*)Km, (f16_t*)Vm, D.H, D.M,
+                           (D.M + 31) / 32);
+      else
+        hipLaunchKernelGGL((k_mem_kv_store<float>), dim3(D.M), dim3(256), 0, c->stream, kv, (float*)Km, (float*)Vm, D.H, D.M);
     }
   hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
   HIPCHK(c, hipGetLastError());
@@ -343,7 +362,8 @@ int build_params(fm_ctx* c) {
   const Dims& D = c->D;
   const size_t d = D.d, ff = c->ff, hff = c->hff, V = D.V;
   size_t off = 0;
-  auto item = [&](void* dst, size_t n, bool f32) { c->items.push_back({off, n, dst, f32}); off += n; };
+  auto item = [&](void* dst, size_t n, bool f32) { c->items.push_back({off, n, dst, f32, 0, 0}); off += n; };
+  auto lin = [&](void* dst, size_t N, size_t K) { c->items.push_back({off, N * K, dst, false, (int)N, (int)K}); off += N * K; };
   auto at = [&](void* base, size_t elems) { return (void*)((uint8_t*)base + elems * c->esz); };
 
   TRY(dalloc_t(c, &c->emb, V * d));
@@ -359,25 +379,25 @@ int build_params(fm_ctx* c) {
       TRY(dalloc_t(c, &L.wqkv, 3 * d * d)); TRY(dalloc_t(c, &L.wo, d * d)); TRY(dalloc_t(c, &L.cq, d * d));
       TRY(dalloc_t(c, &L.ckv, 2 * d * d)); TRY(dalloc_t(c, &L.co, d * d));
       TRY(dalloc_t(c, &L.w1, ff * d)); TRY(dalloc_t(c, &L.w2, d * ff));
-      TRY(dalloc_t(c, &L.Kc, (size_t)D.S * D.H * cap * FM_HD)); TRY(dalloc_t(c, &L.Vc, (size_t)D.S * D.H * cap * FM_HD));
-      TRY(dalloc_t(c, &L.Km, (size_t)D.S * D.H * D.M * FM_HD)); TRY(dalloc_t(c, &L.Vm, (size_t)D.S * D.H * D.M * FM_HD));
+      TRY(dalloc_t(c, &L.Kc, D.S * cache_seq_elems(c, cap))); TRY(dalloc_t(c, &L.Vc, D.S * cache_seq_elems(c, cap)));
+      TRY(dalloc_t(c, &L.Km, D.S * cache_seq_elems(c, D.M))); TRY(dalloc_t(c, &L.Vm, D.S * cache_seq_elems(c, D.M)));
       item(L.g1, d, true);
-      item(L.wqkv, 3 * d * d, false);   // wq, wk, wv are consecutive in the blob
-      item(L.wo, d * d, false);
+      lin(L.wqkv, 3 * d, d);   // wq, wk, wv are consecutive in the blob
+      lin(L.wo, d, d);
       item(L.g2, d, true);
-      item(L.cq, d * d, false);
-      item(L.ckv, 2 * d * d, false);    // ck, cv consecutive
-      item(L.co, d * d, false);
+      lin(L.cq, d, d);
+      lin(L.ckv, 2 * d, d);    // ck, cv consecutive
+      lin(L.co, d, d);
       item(L.g3, d, true);
-      item(L.w1, ff * d, false);
-      item(L.w2, d * ff, false);
+      lin(L.w1, ff, d);
+      lin(L.w2, d, ff);
       c->stacks[st].push_back(L);
     }
   }
-  TRY(dalloc_t(c, &c->short_cv, d * d)); item(c->short_cv, d * d, false);
-  TRY(dalloc_t(c, &c->short_vf, d * d)); item(c->short_vf, d * d, false);
+  TRY(dalloc_t(c, &c->short_cv, d * d)); lin(c->short_cv, d, d);
+  TRY(dalloc_t(c, &c->short_vf, d * d)); lin(c->short_vf, d, d);
   TRY(dalloc(c, &c->gf, d)); item(c->gf, d, true);
-  TRY(dalloc_t(c, &c->lm, (size_t)c->Vpad * d)); item(c->lm, V * d, false);
+  TRY(dalloc_t(c, &c->lm, (size_t)c->Vpad * d)); lin(c->lm, V, d);
   const int spcnt[3] = {D.Dc, D.nspv, D.nspf};
   for (int l = 0; l < 3; l++) {
     SpLevel& s = c->sp[l];
@@ -388,9 +408,9 @@ int build_params(fm_ctx* c) {
     TRY(dalloc_t(c, &s.co, n * d * d)); TRY(dalloc_t(c, &s.lin, n * d * d));
     for (size_t k = 0; k < n; k++) {
       item(s.g + k * d, d, true);
-      item(at(s.wq, k * d * d), d * d, false); item(at(s.wo, k * d * d), d * d, false);
-      item(at(s.cq, k * d * d), d * d, false); item(at(s.co, k * d * d), d * d, false);
-      item(at(s.lin, k * d * d), d * d, false);
+      lin(at(s.wq, k * d * d), d, d); lin(at(s.wo, k * d * d), d, d);
+      lin(at(s.cq, k * d * d), d, d); lin(at(s.co, k * d * d), d, d);
+      lin(at(s.lin, k * d * d), d, d);
     }
   }
   HfLevel* hfs[2] = {&c->hfc, &c->hfv};
@@ -403,9 +423,9 @@ int build_params(fm_ctx* c) {
     TRY(dalloc_t(c, &h.wq, n * d * d)); TRY(dalloc_t(c, &h.w1, n * hff * d)); TRY(dalloc_t(c, &h.w2, n * d * hff));
     for (size_t k = 0; k < n; k++) {
       item(h.g + k * d, d, true);
-      item(at(h.wq, k * d * d), d * d, false);
-      item(at(h.w1, k * hff * d), hff * d, false);
-      item(at(h.w2, k * d * hff), d * hff, false);
+      lin(at(h.wq, k * d * d), d, d);
+      lin(at(h.w1, k * hff * d), hff, d);
+      lin(at(h.w2, k * d * hff), d, hff);
     }
   }
   c->blob_elems = off;
@@ -460,7 +480,14 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &c->dist_v, S * std::max(D.nhfc, 1) * D.V)); TRY(dalloc(c, &c->dist_f, S * std::max(D.nhfc, 1) * D.V));
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
-  TRY(dalloc(c, &c->attn_ws, mfma_attn_ws_floats(D.S, D.H, std::max((int)rmax, c->Rc))));
+  c->mres = MfmaRes{nullptr, nullptr, nullptr, nullptr, 0};
+  if (c->bf16) {
+    TRY(dalloc(c, &c->mres.gemm_ws, (size_t)FM_GEMM_WS_FLOATS, false));
+    TRY(dalloc(c, &c->mres.gemm_counters, (size_t)FM_GEMM_COUNTERS));
+    c->mres.attn_ws_floats = mfma_attn_ws_floats(D.S, D.H);
+    TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
+    TRY(dalloc(c, &c->mres.attn_counters, (size_t)D.S * D.H));
+  }
   if (hipHostMalloc((void**)&c->host_flag, 64) != hipSuccess) return fail(c, FM_ENOMEM, "hipHostMalloc failed");
   return FM_OK;
 }
@@ -560,7 +587,11 @@ int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
         HIPCHK(c, hipMemcpyAsync((float*)it.dst + done, blob + it.blob_off + done, n * 4, hipMemcpyHostToDevice, c->stream));
       } else {
         HIPCHK(c, hipMemcpyAsync(c->stage, blob + it.blob_off + done, n * 4, hipMemcpyHostToDevice, c->stream));
-        if (c->bf16)
+        if (c->bf16 && it.N > 0) {
+          if (n != it.n) return fail(c, FM_EINVAL, "staging buffer smaller than a weight matrix");
+          hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, c->stage, (f16_t*)it.dst, it.N, it.K,
+                             (it.N + 15) / 16 * 16);
+        } else if (c->bf16)
           hipLaunchKernelGGL((k_convert<f16_t>), dim3(1024), dim3(256), 0, c->stream, c->stage, (f16_t*)it.dst + done, (long)n);
         else
           hipLaunchKernelGGL((k_convert<float>), dim3(1024), dim3(256), 0, c->stream, c->stage, (float*)it.dst + done, (long)n);

@@ -1,14 +1,453 @@
-// bf16 MFMA kernels for gfx950 (placeholder launchers: the generic kernels serve every type until
-// the MFMA versions take over for T = bf16).
+// Half-precision MFMA kernels for gfx950 (64-wide wavefronts, v_mfma_f32_16x16x32_f16).
+//
+//  * k_gemm_mfma : skinny weight-streaming GEMM.  Weights are pre-tiled at load time into MFMA
+//                  B-operand order so that every wave load is one contiguous 1 KiB burst; the four
+//                  waves of a workgroup split K, reduce through LDS, and K is further split across
+//                  workgroups with a deterministic last-arriver reduction (fixed summation order).
+//  * k_attn_mfma : block attention over a K/V cache (flash-decoding): keys split across workgroups
+//                  and waves, online softmax in fp32, P kept in registers between the two MFMAs by
+//                  storing V in a blocked, slot-permuted transposed layout.
+//
+// MFMA 16x16x32 operand layout (lane l of 64):
+//   A[16 x 32]: row l%16, k = (l/16)*8 .. +8      B[32 x 16]: col l%16, k = (l/16)*8 .. +8
+//   C[16 x 16]: col l%16, rows (l/16)*4 + i, i = 0..3
 #pragma once
 #include "fm_device.h"
 #include "fm_kernels_basic.h"
 
-template <typename T>
-bool mfma_gemm_launch(const GemmArgs&, int /*epi*/, int /*groups*/, hipStream_t) { return false; }
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define FM_GEMM_WS_FLOATS (48u << 20)   // split-K partials (192 MiB)
+#define FM_GEMM_COUNTERS 65536
+#define FM_ATTN_MAX_SPLIT 64
+
+// ------------------------------------------------------------------------------------------
+// Cache layouts of the half-precision path (one 32-key block = 2048 halves = 4 KiB per head)
+// ------------------------------------------------------------------------------------------
+// K: four A-fragments per block, fragment f = (key/16)*2 + dim/32, lane = key%16 + 16*((dim%32)/8)
+__device__ __forceinline__ long kblk_off(int key, int dim) {
+  const int r = key & 31;
+  const int f = (r >> 4) * 2 + (dim >> 5);
+  const int lane = (r & 15) + 16 * ((dim & 31) >> 3);
+  return (long)(key >> 5) * 2048 + (f * 64 + lane) * 8 + (dim & 7);
+}
+// V: transposed inside the block, [dim][slot]; slot order matches the C-layout of the score tile so
+// that the probabilities never leave registers: key r -> g = (r%16)/4, slot = g*8 + (r/16)*4 + r%4
+__device__ __forceinline__ long vblk_off(int key, int dim) {
+  const int r = key & 31;
+  const int slot = ((r & 15) >> 2) * 8 + (r >> 4) * 4 + (r & 3);
+  return (long)(key >> 5) * 2048 + dim * 32 + slot;
+}
+
+// rotary + append for the half-precision caches (same contract as k_rope_append)
+__global__ void k_rope_append_h(const float* __restrict__ qkv, long ldq, const float2* __restrict__ cs,
+                                const int* __restrict__ pos, int RPS, f16_t* __restrict__ q, f16_t* __restrict__ Kc,
+                                f16_t* __restrict__ Vc, int H, int capb, const int* run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  const int r = blockIdx.x;
+  const int p = pos[r];
+  const int d = H * FM_HD;
+  const int s = r / RPS;
+  for (int idx = threadIdx.x; idx < H * 32; idx += blockDim.x) {
+    const int hh = idx >> 5, i = idx & 31;
+    const float2 c = cs[(long)r * 32 + i];
+    const float* row = qkv + (long)r * ldq;
+    const float qa = row[hh * 64 + i], qb = row[hh * 64 + 32 + i];
+    q[(long)r * d + hh * 64 + i] = (f16_t)(qa * c.x - qb * c.y);
+    q[(long)r * d + hh * 64 + 32 + i] = (f16_t)(qb * c.x + qa * c.y);
+    if (Kc && p >= 0) {
+      const float ka = row[d + hh * 64 + i], kb = row[d + hh * 64 + 32 + i];
+      const long base = ((long)s * H + hh) * capb * 2048;
+      Kc[base + kblk_off(p, i)] = (f16_t)(ka * c.x - kb * c.y);
+      Kc[base + kblk_off(p, i + 32)] = (f16_t)(kb * c.x + ka * c.y);
+      Vc[base + vblk_off(p, i)] = (f16_t)row[2 * d + hh * 64 + i];
+      Vc[base + vblk_off(p, i + 32)] = (f16_t)row[2 * d + hh * 64 + 32 + i];
+    }
+  }
+}
+
+__global__ void k_mem_kv_store_h(const float* __restrict__ kv, f16_t* __restrict__ Kc, f16_t* __restrict__ Vc, int H,
+                                 int M, int capb) {
+  const int m = blockIdx.x;
+  const int d = H * FM_HD;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    const int hh = i >> 6, e = i & 63;
+    const long base = (long)hh * capb * 2048;
+    Kc[base + kblk_off(m, e)] = (f16_t)kv[(long)m * 2 * d + i];
+    Vc[base + vblk_off(m, e)] = (f16_t)kv[(long)m * 2 * d + d + i];
+  }
+}
+
+// weights [N][K] fp32 (bf16-valued) -> half, tiled: fragment (nt, kt) holds W[nt*16 + l%16][kt*32 + (l/16)*8 + j]
+__global__ void k_tile_weight(const float* __restrict__ src, f16_t* __restrict__ dst, int N, int K, int Npad) {
+  const long total = (long)Npad * K / 8;
+  for (long v = blockIdx.x * (long)blockDim.x + threadIdx.x; v < total; v += (long)gridDim.x * blockDim.x) {
+    const int lane = (int)(v & 63);
+    const long frag = v >> 6;
+    const int KT = K / 32;
+    const int kt = (int)(frag % KT), nt = (int)(frag / KT);
+    const int n = nt * 16 + (lane & 15), k = kt * 32 + (lane >> 4) * 8;
+    f16x8 o;
+#pragma unroll
+    for (int j = 0; j < 8; j++) o[j] = n < N ? (f16_t)src[(long)n * K + k + j] : (f16_t)0.f;
+    *reinterpret_cast<f16x8*>(dst + v * 8) = o;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// GEMM
+// ------------------------------------------------------------------------------------------
+struct GemmSplit {
+  int kt_per_wave;   // K fragments (of 32) each wave walks
+  int ksplit;        // workgroups along K (each covers 4 * kt_per_wave fragments)
+  float* ws;         // [group*mblocks][ksplit][MT*16][Npad]
+  unsigned* counters;
+  int Npad;
+};
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
+  if (a.run_flag && *a.run_flag == 0) return;
+  __shared__ f32x4 red[4][MT][64];
+  __shared__ int s_last;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nt = blockIdx.x, ks = blockIdx.y;
+  const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
+  const int g = blockIdx.z / nmb, mb = blockIdx.z % nmb;
+  const int KT = a.K / 32;
+  const f16_t* X = (const f16_t*)a.X + (long)g * a.gsx;
+  const f16_t* W = (const f16_t*)a.W + (long)g * a.gsw + ((long)nt * KT) * 512;
+  const int m0 = mb * MT * 16;
+  // A-fragment row pointers (rows past M are clamped: computed, never stored)
+  const f16_t* xrow[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) {
+    int m = m0 + mt * 16 + (lane & 15);
+    m = m < a.M ? m : a.M - 1;
+    xrow[mt] = X + (long)m * a.ldx + (lane >> 4) * 8;
+  }
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int kt0 = (ks * 4 + wave) * sp.kt_per_wave;
+  const int kt1 = min(kt0 + sp.kt_per_wave, KT);
+
+  for (int kt = kt0; kt < kt1; kt++) {
+    const f16x8 b = *reinterpret_cast<const f16x8*>(W + ((long)kt * 64 + lane) * 8);
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) {
+      const f16x8 av = *reinterpret_cast<const f16x8*>(xrow[mt] + kt * 32);
+      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b, acc[mt], 0, 0, 0);
+    }
+  }
+  // reduce the four K-quarters of the workgroup through LDS
+#pragma unroll
+  for (int mt = 0; mt < MT; mt++) red[wave][mt][lane] = acc[mt];
+  __syncthreads();
+  const int n = nt * 16 + (lane & 15);
+  const long tile = (long)blockIdx.z * gridDim.x + nt;
+  bool last = true;
+  if (sp.ksplit > 1) {
+    // publish this workgroup's partial, then find out whether it is the last one for the tile
+    for (int mt = wave; mt < MT; mt += 4) {
+      f32x4 v = red[0][mt][lane];
+#pragma unroll
+      for (int w = 1; w < 4; w++) v += red[w][mt][lane];
+      float* p = sp.ws + ((tile * sp.ksplit + ks) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
+#pragma unroll
+      for (int i = 0; i < 4; i++) p[i * 16] = v[i];
+    }
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const unsigned old = atomicAdd(&sp.counters[tile], 1u);
+      s_last = (old == (unsigned)sp.ksplit - 1);
+      if (s_last) sp.counters[tile] = 0;   // nobody else touches it until the next launch
+    }
+    __syncthreads();
+    last = s_last != 0;
+    if (last) __threadfence();
+  }
+  if (!last) return;
+  for (int mt = wave; mt < MT; mt += 4) {
+    f32x4 v;
+    if (sp.ksplit > 1) {
+      v = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int k2 = 0; k2 < sp.ksplit; k2++) {   // fixed order: deterministic sums
+        const float* p = sp.ws + ((tile * sp.ksplit + k2) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
+#pragma unroll
+        for (int i = 0; i < 4; i++) v[i] += __builtin_nontemporal_load(p + i * 16);
+      }
+    } else {
+      v = red[0][mt][lane];
+#pragma unroll
+      for (int w = 1; w < 4; w++) v += red[w][mt][lane];
+    }
+    if (n < a.N) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const long m = m0 + mt * 16 + (lane >> 4) * 4 + i;
+        if (m < a.M) {
+          float val = v[i];
+          if (EPI == EPI_F32) {
+            if (a.R) val += a.R[(long)g * a.gsr + m * a.ldr + n];
+            ((float*)a.Y)[(long)g * a.gsy + m * a.ldy + n] = val;
+          } else {
+            ((f16_t*)a.Y)[(long)g * a.gsy + m * a.ldy + n] = (f16_t)(EPI == EPI_GELU_T ? gelu_tanh_f(val) : val);
+          }
+        }
+      }
+    }
+  }
+}
+
+struct MfmaRes {      // per-context resources of the MFMA kernels
+  float* gemm_ws;
+  unsigned* gemm_counters;
+  float* attn_ws;
+  unsigned* attn_counters;
+  size_t attn_ws_floats;
+};
+
+template <int MT>
+void gemm_mfma_dispatch(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
+  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32>), grid, dim3(256), 0, st, a, sp);
+  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T>), grid, dim3(256), 0, st, a, sp);
+  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T>), grid, dim3(256), 0, st, a, sp);
+}
 
 template <typename T>
-bool mfma_attn_launch(const void*, const int*, int, int, const void*, const void*, long, int, void*, int, float*,
+bool mfma_gemm_launch(const MfmaRes&, const GemmArgs&, int, int, hipStream_t) { return false; }
+
+template <>
+inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int epi, int groups, hipStream_t st) {
+  if (a.K % 32 != 0 || a.M < 1) return false;
+  const int KT = a.K / 32, Npad = (a.N + 15) / 16 * 16, NT = Npad / 16;
+  const int mtiles = (a.M + 15) / 16;
+  const int MT = mtiles <= 1 ? 1 : mtiles <= 2 ? 2 : mtiles <= 3 ? 3 : mtiles <= 5 ? 5 : 8;
+  const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
+  // K split: aim for >= ~1024 waves in flight, at least 2 fragments (2 KiB of weights) per wave
+  int kt_per_wave = (KT + 3) / 4, ksplit = 1;
+  if (nmb == 1) {
+    const long base_wgs = (long)NT * groups;
+    while (base_wgs * ksplit < 512 && kt_per_wave > 2 && kt_per_wave % 2 == 0 && ksplit < 16) {
+      kt_per_wave /= 2;
+      ksplit *= 2;
+    }
+  }
+  const long tiles = (long)NT * groups * nmb;
+  if (ksplit > 1 && (tiles > FM_GEMM_COUNTERS || tiles * ksplit * MT * 256 > (long)FM_GEMM_WS_FLOATS)) {
+    ksplit = 1;
+    kt_per_wave = (KT + 3) / 4;
+  }
+  GemmSplit sp{kt_per_wave, ksplit, res.gemm_ws, res.gemm_counters, Npad};
+  dim3 grid(NT, ksplit, groups * nmb);
+  switch (MT) {
+    case 1: gemm_mfma_dispatch<1>(a, sp, epi, grid, st); break;
+    case 2: gemm_mfma_dispatch<2>(a, sp, epi, grid, st); break;
+    case 3: gemm_mfma_dispatch<3>(a, sp, epi, grid, st); break;
+    case 5: gemm_mfma_dispatch<5>(a, sp, epi, grid, st); break;
+    default: gemm_mfma_dispatch<8>(a, sp, epi, grid, st); break;
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention
+// ------------------------------------------------------------------------------------------
+// Workspace per (sequence, head): [nsplit][QT*16*64 unnormalised O | QT*16 running max (log2 units) | QT*16 sums]
+template <int QT>
+__global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS,
+                                                    const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
+                                                    long seq_stride, int capb, f16_t* __restrict__ out, int H,
+                                                    float* __restrict__ ws, unsigned* __restrict__ counters,
+                                                    const int* run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  constexpr int NQ = QT * 16;
+  constexpr int PSZ = NQ * 64 + 2 * NQ;
+  __shared__ float lo[4][NQ][65];
+  __shared__ float lm[4][NQ], ll[4][NQ];
+  __shared__ int s_last;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int split = blockIdx.x, nsplit = gridDim.x, hh = blockIdx.y, s = blockIdx.z;
+  const int d = H * FM_HD;
+  const int g = lane >> 4, ql = lane & 15;
+  const float kScale = 0.125f * 1.4426950408889634f;   // 1/sqrt(64) * log2(e)
+
+  // this lane's query rows (one per q-tile), their visibility limits and B-operand fragments
+  int lim[QT];
+  f16x8 qf[QT][2];
+  int maxlim = -1;
+#pragma unroll
+  for (int t = 0; t < QT; t++) {
+    const int qi = t * 16 + ql;
+    const bool on = qi < RPS;
+    const long row = (long)s * RPS + (on ? qi : 0);
+    lim[t] = on ? limit[row] : -1;
+    maxlim = max(maxlim, lim[t]);
+    const f16_t* qp = q + row * d + hh * FM_HD + g * 8;
+    qf[t][0] = *reinterpret_cast<const f16x8*>(qp);
+    qf[t][1] = *reinterpret_cast<const f16x8*>(qp + 32);
+  }
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, o, 64));
+  const int nblk = (maxlim + 32) >> 5;                // blocks that hold a visible key (0 if none)
+  const int per = (nblk + nsplit - 1) / nsplit;
+  const int b0 = split * per, b1 = min(b0 + per, nblk);
+
+  float mrun[QT], lrun[QT];
+  f32x4 o[QT][4];
+#pragma unroll
+  for (int t = 0; t < QT; t++) {
+    mrun[t] = -INFINITY;
+    lrun[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  const f16_t* Kb = Kc + (long)s * seq_stride + (long)hh * capb * 2048;
+  const f16_t* Vb = Vc + (long)s * seq_stride + (long)hh * capb * 2048;
+  for (int b = b0 + wave; b < b1; b += 4) {
+    const f16_t* kp = Kb + (long)b * 2048 + lane * 8;
+    const f16_t* vp = Vb + (long)b * 2048 + (lane & 15) * 32 + g * 8;
+    f16x8 kf[4], vf[4];
+#pragma unroll
+    for (int f = 0; f < 4; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+      // scores, transposed: sT[hb][i] = <K[key], Q[q]> for key = b*32 + hb*16 + g*4 + i, q = this lane's row
+      f32x4 sT[2];
+#pragma unroll
+      for (int hb = 0; hb < 2; hb++) {
+        f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+        z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2], qf[t][0], z, 0, 0, 0);
+        z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2 + 1], qf[t][1], z, 0, 0, 0);
+        sT[hb] = z;
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int hb = 0; hb < 2; hb++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const int key = b * 32 + hb * 16 + g * 4 + i;
+          const float v = key <= lim[t] ? sT[hb][i] * kScale : -INFINITY;
+          sT[hb][i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(mrun[t], mx);
+      const float msafe = mnew == -INFINITY ? 0.f : mnew;
+      const float alpha = __builtin_amdgcn_exp2f(mrun[t] - msafe);   // exp2(-inf) = 0 on the first block
+      mrun[t] = mnew;
+      f16x8 pf;
+      float psum = 0.f;
+#pragma unroll
+      for (int hb = 0; hb < 2; hb++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const float p = __builtin_amdgcn_exp2f(sT[hb][i] - msafe);
+          psum += p;
+          pf[hb * 4 + i] = (f16_t)p;
+        }
+      lrun[t] = lrun[t] * alpha + psum;
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        o[t][dt] *= alpha;
+        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[t][dt], 0, 0, 0);   // O^T[dim][q]
+      }
+    }
+  }
+  // combine the four waves of the workgroup
+#pragma unroll
+  for (int t = 0; t < QT; t++) {
+    float l = lrun[t];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (g == 0) { lm[wave][t * 16 + ql] = mrun[t]; ll[wave][t * 16 + ql] = l; }
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) lo[wave][t * 16 + ql][dt * 16 + g * 4 + i] = o[t][dt][i];
+  }
+  __syncthreads();
+  const long sh = (long)s * H + hh;
+  float* part = ws + (sh * nsplit + split) * PSZ;
+  for (int e = threadIdx.x; e < NQ * 64; e += 256) {
+    const int qi = e >> 6, dim = e & 63;
+    const float M = fmaxf(fmaxf(lm[0][qi], lm[1][qi]), fmaxf(lm[2][qi], lm[3][qi]));
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+      const float f = __builtin_amdgcn_exp2f(lm[w][qi] - Ms);
+      num += lo[w][qi][dim] * f;
+      den += ll[w][qi] * f;
+    }
+    if (nsplit == 1) {
+      if (qi < RPS) out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
+    } else {
+      part[e] = num;
+      if (dim == 0) { part[NQ * 64 + qi] = M; part[NQ * 64 + NQ + qi] = den; }
+    }
+  }
+  if (nsplit == 1) return;
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned old = atomicAdd(&counters[sh], 1u);
+    s_last = (old == (unsigned)nsplit - 1);
+    if (s_last) counters[sh] = 0;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  const float* base = ws + sh * nsplit * PSZ;
+  for (int e = threadIdx.x; e < NQ * 64; e += 256) {
+    const int qi = e >> 6, dim = e & 63;
+    if (qi >= RPS) continue;
+    float M = -INFINITY;
+    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, __builtin_nontemporal_load(base + (long)k2 * PSZ + NQ * 64 + qi));
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float num = 0.f, den = 0.f;
+    for (int k2 = 0; k2 < nsplit; k2++) {   // fixed order
+      const float* p = base + (long)k2 * PSZ;
+      const float f = __builtin_amdgcn_exp2f(__builtin_nontemporal_load(p + NQ * 64 + qi) - Ms);
+      num += __builtin_nontemporal_load(p + e) * f;
+      den += __builtin_nontemporal_load(p + NQ * 64 + NQ + qi) * f;
+    }
+    out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
+  }
+}
+
+inline size_t mfma_attn_ws_floats(int S, int H) {
+  return (size_t)S * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64);
+}
+
+template <typename T>
+bool mfma_attn_launch(const MfmaRes&, const void*, const int*, int, int, const void*, const void*, long, int, void*, int,
                       const int*, hipStream_t) { return false; }
 
-inline size_t mfma_attn_ws_floats(int /*S*/, int /*H*/, int /*rows*/) { return 1; }
+// `cap` = key capacity of the cache (positions); caches are laid out in 32-key blocks
+template <>
+inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int* limit, int rows, int RPS, const void* Kc,
+                                    const void* Vc, long seq_stride, int cap, void* out, int H, const int* flag,
+                                    hipStream_t st) {
+  if (RPS > 32 || rows % RPS != 0) return false;
+  const int S = rows / RPS;
+  const int capb = (cap + 31) / 32;
+  int nsplit = capb / 8;   // about 8 blocks (two per wave) per workgroup at full length
+  const int want = 1024 / (H * S) > 0 ? 1024 / (H * S) : 1;
+  nsplit = nsplit < 1 ? 1 : nsplit;
+  nsplit = nsplit > want ? want : nsplit;
+  nsplit = nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
+  dim3 grid(nsplit, H, S);
+  if (RPS <= 16)
+    hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
+                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, flag);
+  else
+    hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
+                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, flag);
+  return true;
+}
