@@ -129,7 +129,9 @@ int fm_read_state(fm_ctx* ctx, int32_t* host_out);
 int fm_set_draft_replay(fm_ctx* ctx, const int32_t* stream_dev, int32_t stride, int32_t n_valid,
                         float keep_prob, uint64_t seed);
 
-/* Limit on generated tokens per sequence for the step-wise API (default max_tokens). */
+/* Budget of 9*max_faces generated tokens per sequence for the step-wise API (default max_tokens):
+ * blocks are clipped to it and a sequence that reaches it is finished; prefilled sequences below the
+ * new budget that did not end with EOS become live again.  FM_EINVAL outside [1, max_tokens/9]. */
 int fm_set_budget(fm_ctx* ctx, int32_t max_faces);
 
 /* Algorithmic HBM bytes of one verify pass at the current committed lengths (weights once, self

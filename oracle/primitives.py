@@ -68,9 +68,8 @@ def attend(q, K, V, limit):
     if rows and np.all(lim == lim[0]):
         # all rows see the same keys: one batched product per head
         n = int(lim[0]) + 1
-        s = np.einsum("rhd,khd->hrk", q, K[:n]) * scale
-        out = np.einsum("hrk,khd->rhd", softmax(s), V[:n])
-        return out
+        s = np.matmul(q.transpose(1, 0, 2), K[:n].transpose(1, 2, 0)) * scale    # [H, rows, n]
+        return np.matmul(softmax(s), V[:n].transpose(1, 0, 2)).transpose(1, 0, 2)
     for r in range(rows):
         n = int(lim[r]) + 1
         s = np.einsum("hd,khd->hk", q[r], K[:n]) * scale
@@ -86,8 +85,8 @@ def attend_causal(q, K, V, first_pos):
     rows, H, _ = q.shape
     n = first_pos + rows
     scale = 1.0 / np.sqrt(HEAD_DIM)
-    s = np.einsum("rhd,khd->hrk", q, K[:n]) * scale
+    s = np.matmul(q.transpose(1, 0, 2), K[:n].transpose(1, 2, 0)) * scale        # [H, rows, n]
     kk = np.arange(n)[None, :]
     rr = (first_pos + np.arange(rows))[:, None]
     s = np.where((kk <= rr)[None, :, :], s, -np.inf)
-    return np.einsum("hrk,khd->rhd", softmax(s), V[:n])
+    return np.matmul(softmax(s), V[:n].transpose(1, 0, 2)).transpose(1, 0, 2)

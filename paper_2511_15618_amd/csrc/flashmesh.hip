@@ -641,9 +641,8 @@ int fm_commit(fm_ctx* c, const int32_t* accepted) {
 int fm_set_budget(fm_ctx* c, int32_t max_faces) {
   if (!c) return FM_EINVAL;
   if (max_faces < 1 || 9 * max_faces > c->D.capc) return fail(c, FM_EINVAL, "max_faces %d outside [1,%d]", max_faces, c->D.capc / 9);
-  const int budget = 9 * max_faces;
-  HIPCHK(c, hipMemcpyAsync(c->st.budget, &budget, sizeof(int), hipMemcpyHostToDevice, c->stream));
-  HIPCHK(c, hipStreamSynchronize(c->stream));
+  hipLaunchKernelGGL(k_set_budget, dim3(1), dim3(64), 0, c->stream, c->st, c->D, 9 * max_faces);
+  HIPCHK(c, hipGetLastError());
   return FM_OK;
 }
 

@@ -17,6 +17,18 @@
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Cross-workgroup exchange inside one launch (split-K / split-KV partials): values are written and read
+// with agent-scope atomics, which go through to the level of the memory hierarchy that all XCDs share,
+// so no cache-wide write-back / invalidate (what a full __threadfence costs on this chip) is needed.
+// publish_fence() only waits until this wave's own stores have been acknowledged.
+__device__ __forceinline__ void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+
 #define FM_GEMM_WS_FLOATS (48u << 20)   // split-K partials (192 MiB)
 #define FM_GEMM_COUNTERS 65536
 #define FM_ATTN_MAX_SPLIT 64
@@ -155,18 +167,17 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
       for (int w = 1; w < 4; w++) v += red[w][mt][lane];
       float* p = sp.ws + ((tile * sp.ksplit + ks) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
 #pragma unroll
-      for (int i = 0; i < 4; i++) p[i * 16] = v[i];
+      for (int i = 0; i < 4; i++) st_agent(p + i * 16, v[i]);
     }
-    __threadfence();
+    publish_fence();
     __syncthreads();
     if (threadIdx.x == 0) {
-      const unsigned old = atomicAdd(&sp.counters[tile], 1u);
+      const unsigned old = __hip_atomic_fetch_add(&sp.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = (old == (unsigned)sp.ksplit - 1);
-      if (s_last) sp.counters[tile] = 0;   // nobody else touches it until the next launch
+      if (s_last) __hip_atomic_store(&sp.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else touches it until the next launch
     }
     __syncthreads();
     last = s_last != 0;
-    if (last) __threadfence();
   }
   if (!last) return;
   for (int mt = wave; mt < MT; mt += 4) {
@@ -176,7 +187,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
       for (int k2 = 0; k2 < sp.ksplit; k2++) {   // fixed order: deterministic sums
         const float* p = sp.ws + ((tile * sp.ksplit + k2) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
 #pragma unroll
-        for (int i = 0; i < 4; i++) v[i] += __builtin_nontemporal_load(p + i * 16);
+        for (int i = 0; i < 4; i++) v[i] += ld_agent(p + i * 16);
       }
     } else {
       v = red[0][mt][lane];
@@ -230,7 +241,7 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   int kt_per_wave = (KT + 3) / 4, ksplit = 1;
   if (nmb == 1) {
     const long base_wgs = (long)NT * groups;
-    while (base_wgs * ksplit < 512 && kt_per_wave > 2 && kt_per_wave % 2 == 0 && ksplit < 16) {
+    while (base_wgs * ksplit < 256 && kt_per_wave > 2 && kt_per_wave % 2 == 0 && ksplit < 16) {
       kt_per_wave /= 2;
       ksplit *= 2;
     }
@@ -267,9 +278,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   constexpr int PSZ = NQ * 64 + 2 * NQ;
   __shared__ float lo[4][NQ][65];
   __shared__ float lm[4][NQ], ll[4][NQ];
+  __shared__ float cf[FM_ATTN_MAX_SPLIT][NQ], cden[NQ];
   __shared__ int s_last;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int split = blockIdx.x, nsplit = gridDim.x, hh = blockIdx.y, s = blockIdx.z;
+  const int split = blockIdx.x, hh = blockIdx.y, s = blockIdx.z;
   const int d = H * FM_HD;
   const int g = lane >> 4, ql = lane & 15;
   const float kScale = 0.125f * 1.4426950408889634f;   // 1/sqrt(64) * log2(e)
@@ -292,7 +304,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
 #pragma unroll
   for (int o = 1; o < 16; o <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, o, 64));
   const int nblk = (maxlim + 32) >> 5;                // blocks that hold a visible key (0 if none)
-  const int per = (nblk + nsplit - 1) / nsplit;
+  // Fixed partition of the key axis: split k owns blocks [k*per, (k+1)*per) whatever the current length,
+  // so the arithmetic for one query position never depends on what else is in the block or on how far
+  // the sequence has grown (speculative and one-token decoding then agree bit for bit).  Splits with no
+  // visible key leave at once; every workgroup of this (sequence, head) derives the same count.
+  const int per = (capb + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int nsplit = max(1, (nblk + per - 1) / per);
+  if (split >= nsplit) return;
   const int b0 = split * per, b1 = min(b0 + per, nblk);
 
   float mrun[QT], lrun[QT];
@@ -373,7 +391,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   }
   __syncthreads();
   const long sh = (long)s * H + hh;
-  float* part = ws + (sh * nsplit + split) * PSZ;
+  float* part = ws + (sh * gridDim.x + split) * PSZ;   // slots are laid out for the launched split count
   for (int e = threadIdx.x; e < NQ * 64; e += 256) {
     const int qi = e >> 6, dim = e & 63;
     const float M = fmaxf(fmaxf(lm[0][qi], lm[1][qi]), fmaxf(lm[2][qi], lm[3][qi]));
@@ -388,35 +406,45 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
     if (nsplit == 1) {
       if (qi < RPS) out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
     } else {
-      part[e] = num;
-      if (dim == 0) { part[NQ * 64 + qi] = M; part[NQ * 64 + NQ + qi] = den; }
+      st_agent(part + e, num);
+      if (dim == 0) { st_agent(part + NQ * 64 + qi, M); st_agent(part + NQ * 64 + NQ + qi, den); }
     }
   }
   if (nsplit == 1) return;
-  __threadfence();
+  publish_fence();
   __syncthreads();
   if (threadIdx.x == 0) {
-    const unsigned old = atomicAdd(&counters[sh], 1u);
+    const unsigned old = __hip_atomic_fetch_add(&counters[sh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (old == (unsigned)nsplit - 1);
-    if (s_last) counters[sh] = 0;
+    if (s_last) __hip_atomic_store(&counters[sh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
   if (!s_last) return;
-  __threadfence();
-  const float* base = ws + sh * nsplit * PSZ;
+  // last workgroup of this (sequence, head): merge the splits in a fixed order
+  const float* base = ws + sh * gridDim.x * PSZ;
+  for (int e = threadIdx.x; e < nsplit * NQ; e += 256) cf[e / NQ][e % NQ] = ld_agent(base + (long)(e / NQ) * PSZ + NQ * 64 + (e % NQ));
+  __syncthreads();
+  if (threadIdx.x < NQ) {
+    const int qi = threadIdx.x;
+    float M = -INFINITY;
+    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, cf[k2][qi]);
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float den = 0.f;
+    for (int k2 = 0; k2 < nsplit; k2++) {
+      const float f = __builtin_amdgcn_exp2f(cf[k2][qi] - Ms);
+      cf[k2][qi] = f;
+      den += ld_agent(base + (long)k2 * PSZ + NQ * 64 + NQ + qi) * f;
+    }
+    cden[qi] = den;
+  }
+  __syncthreads();
   for (int e = threadIdx.x; e < NQ * 64; e += 256) {
     const int qi = e >> 6, dim = e & 63;
     if (qi >= RPS) continue;
-    float M = -INFINITY;
-    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, __builtin_nontemporal_load(base + (long)k2 * PSZ + NQ * 64 + qi));
-    const float Ms = M == -INFINITY ? 0.f : M;
-    float num = 0.f, den = 0.f;
-    for (int k2 = 0; k2 < nsplit; k2++) {   // fixed order
-      const float* p = base + (long)k2 * PSZ;
-      const float f = __builtin_amdgcn_exp2f(__builtin_nontemporal_load(p + NQ * 64 + qi) - Ms);
-      num += __builtin_nontemporal_load(p + e) * f;
-      den += __builtin_nontemporal_load(p + NQ * 64 + NQ + qi) * f;
-    }
+    float num = 0.f;
+#pragma unroll 8
+    for (int k2 = 0; k2 < nsplit; k2++) num += ld_agent(base + (long)k2 * PSZ + e) * cf[k2][qi];
+    const float den = cden[qi];
     out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
   }
 }

@@ -134,6 +134,19 @@ __global__ void k_commit(StateDev st, Dims D, const int* __restrict__ accepted) 
   }
 }
 
+// New token budget: sequences that have not ended with EOS become live again if they are below it.
+__global__ void k_set_budget(StateDev st, Dims D, int budget) {
+  if (threadIdx.x != 0) return;
+  st.budget[0] = budget;
+  int alive = 0;
+  for (int i = 0; i < D.S; i++) {
+    if (st.P[i] >= 0 && st.hist[(long)i * (D.capc + 1)] == D.nbins)   // sequence has been prefilled
+      st.fin[i] = (st.main[i] == D.eos || st.P[i] >= budget) ? 1 : 0;
+    alive += st.fin[i] ? 0 : 1;
+  }
+  st.alive[0] = alive;
+}
+
 // Reset one sequence to x_0 = BOS with empty caches and no draft rows.
 __global__ void k_reset_seq(StateDev st, Dims D, int s, int bos) {
   if (threadIdx.x != 0) return;

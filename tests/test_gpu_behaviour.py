@@ -1,0 +1,227 @@
+"""GPU tests of the decode-step contract: idempotent verify, rollback, replay accounting, error paths,
+and the full-size runs with teacher-forced oracle checks."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+
+
+def _ctx(cfg, max_tokens=None):
+    from paper_2511_15618_amd import FlashMesh
+    from paper_2511_15618_amd.binding import config_struct
+    w = si.make_weights(cfg, 0)
+    fm = FlashMesh(config_struct(cfg, max_tokens=max_tokens))
+    fm.load_weights(si.pack_blob(cfg, w))
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    return fm, w
+
+
+def test_verify_is_idempotent_and_commit_is_the_only_transition():
+    _need_gpu()
+    cfg = si.TEST_CONFIGS["t_bf16_99"]
+    print("case idempotent", flush=True)
+    fm, _ = _ctx(cfg)
+    tok, ln = fm.new_block()
+    S, Bm, V = cfg.batch, fm.block_max, cfg.vocab
+    lg1 = torch.zeros(S, Bm, V, device="cuda")
+    lg2 = torch.zeros(S, Bm, V, device="cuda")
+    a1 = torch.zeros(S, dtype=torch.int32, device="cuda")
+    a2 = torch.zeros(S, dtype=torch.int32, device="cuda")
+    for step in range(12):
+        fm.draft(tok, ln)
+        before = fm.read_state().copy()
+        fm.verify_block(tok, ln, lg1, a1)
+        # a different (wrong) block in between must leave no trace
+        junk = (tok + 1) % cfg.n_bins
+        junk[:, 0] = tok[:, 0]
+        fm.verify_block(junk, ln, lg2, a2)
+        fm.verify_block(tok, ln, lg2, a2)
+        torch.cuda.synchronize()
+        assert np.array_equal(fm.read_state(), before)
+        L = ln.cpu().numpy()
+        for s in range(S):
+            assert torch.equal(lg1[s, :L[s]], lg2[s, :L[s]])
+        assert torch.equal(a1, a2)
+        fm.commit(a1)
+        after = fm.read_state()
+        assert np.array_equal(after[:, 0], before[:, 0] + a1.cpu().numpy())
+
+
+def test_rollback_with_corrupted_drafts_ragged_batch():
+    """Drafts = the known continuation corrupted at a per-sequence index k: accepted must equal k exactly
+    and the emitted streams must not change."""
+    _need_gpu()
+    cfg = si.TEST_CONFIGS["t_bf16_99"]
+    print("case rollback", flush=True)
+    fm, _ = _ctx(cfg)
+    out, n, _ = fm.generate(cfg.faces, False)
+    truth = out.cpu().numpy()
+    budget = 9 * cfg.faces
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    fm.set_budget(cfg.faces)
+    S, Bm = cfg.batch, fm.block_max
+    tok, ln = fm.new_block()
+    acc = torch.zeros(S, dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(3)
+    P = np.zeros(S, int)
+    while (P < budget).any():
+        ks = rng.integers(1, Bm + 1, S)
+        blk = np.zeros((S, Bm), np.int32)
+        lens = np.zeros(S, np.int32)
+        for s in range(S):
+            if P[s] >= budget:
+                continue
+            L = min(Bm, budget - P[s])
+            x = [cfg.bos] + list(truth[s])
+            blk[s, :L] = x[P[s]:P[s] + L]
+            if ks[s] < L:
+                blk[s, ks[s]] = (blk[s, ks[s]] + 1) % cfg.n_bins
+            lens[s] = L
+        tok.copy_(torch.from_numpy(blk))
+        ln.copy_(torch.from_numpy(lens))
+        fm.verify_block(tok, ln, None, acc)
+        fm.commit(acc)
+        a = acc.cpu().numpy()
+        for s in range(S):
+            if lens[s]:
+                assert a[s] == min(ks[s], lens[s]), (s, P[s], ks[s], lens[s], a[s])
+        P += a
+        st = fm.read_state()
+        assert np.array_equal(st[:, 0], P)
+        assert np.array_equal(st[:, 1], (P + 2) // 3) and np.array_equal(st[:, 2], (P + 8) // 9)
+    assert all(fm.read_state()[:, 4] == 1)
+
+
+def test_replay_accounting_matches_host_prediction():
+    """With the replay draft source the whole step sequence is predictable on the host from the
+    counter-based uniforms: accepted = 1 + leading kept drafts."""
+    _need_gpu()
+    cfg = si.TEST_CONFIGS["t_bf16_1815"]
+    print("case replay", flush=True)
+    fm, _ = _ctx(cfg)
+    out, n, st0 = fm.generate(cfg.faces, True)
+    budget = 9 * cfg.faces
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    keep, seed = 0.8, 77
+    fm.set_draft_replay(out.clone(), budget, keep, seed)
+    out2, n2, st = fm.generate(cfg.faces, True)
+    assert torch.equal(out, out2)
+    hist = np.zeros(32, int)
+    steps = 0
+    for s in range(cfg.batch):
+        P, k = 0, 0
+        while P < budget:
+            L = 1 if P == 0 else min(fm.block_max, budget - P)
+            a = 1
+            while a < L and si.replay_uniform(seed, s, P + a) < keep:
+                a += 1
+            hist[a] += 1
+            P += a
+            k += 1
+        steps = max(steps, k)
+    assert [int(v) for v in st.acc_hist] == list(hist)
+    assert st.steps == steps and st.tokens == budget * cfg.batch
+
+
+def test_error_paths():
+    _need_gpu()
+    import ctypes as C
+    from paper_2511_15618_amd import FlashMesh
+    from paper_2511_15618_amd.binding import config_struct
+    cfg = si.TEST_CONFIGS["t_f32_99"]
+    fm = FlashMesh(config_struct(cfg))
+    tok, ln = fm.new_block()
+    acc = torch.zeros(cfg.batch, dtype=torch.int32, device="cuda")
+    lib, h = fm.lib, fm.h
+    assert lib.fm_verify_block(h, tok.data_ptr(), ln.data_ptr(), None, acc.data_ptr()) == -2      # no weights
+    assert b"weights" in lib.fm_last_error(h)
+    blob = si.pack_blob(cfg, si.make_weights(cfg, 0))
+    assert lib.fm_load_weights(h, blob.ctypes.data, blob.size - 1) == -1
+    fm.load_weights(blob)
+    mem = torch.from_numpy(si.make_memory(cfg, 0)).cuda()
+    assert lib.fm_prefill_condition(h, cfg.batch, mem.data_ptr()) == -1
+    assert lib.fm_prefill_condition(h, -1, mem.data_ptr()) == -1
+    assert lib.fm_prefill_condition(h, 0, None) == -1
+    out = torch.zeros(cfg.batch, cfg.max_tokens, dtype=torch.int32, device="cuda")
+    assert lib.fm_generate(h, cfg.faces, 1, out.data_ptr(), ln.data_ptr(), None) == -2            # not prefilled
+    assert lib.fm_set_budget(h, 0) == -1 and lib.fm_set_budget(h, cfg.faces + 1) == -1
+    assert lib.fm_verify_block(h, None, ln.data_ptr(), None, acc.data_ptr()) == -1
+    # an unprefilled sequence is simply not live; over-long and out-of-range block entries are clipped
+    fm.prefill_condition(0, mem)
+    tok.fill_(10 ** 6)
+    tok[:, 0] = cfg.bos
+    ln.fill_(1000)
+    fm.verify_block(tok, ln, None, acc)
+    torch.cuda.synchronize()
+    a = acc.cpu().numpy()
+    assert 1 <= a[0] <= fm.block_max and a[1] == 0
+
+
+def _teacher_forced_check(cfg, stream, tol, work, chunk=600):
+    """Replays a device stream through the oracle in long blocks and applies the margin rule at every position."""
+    from oracle.hourglass import Model, SeqState, forward_block
+    model = Model(cfg, si.make_weights(cfg, 0), work=work)
+    flips = 0
+    worst = 0.0
+    for s, toks in enumerate(stream):
+        st = SeqState(model, si.make_memory(cfg, s), len(toks))
+        x = [cfg.bos] + [int(t) for t in toks]
+        nlim = cfg.n_bins if cfg.ban_specials else cfg.vocab
+        while st.P < len(toks):
+            B = min(chunk, len(toks) - st.P)
+            lg = forward_block(model, st, x[st.P:st.P + B], long_block=True)
+            ref = np.argmax(lg[:, :nlim], axis=1)
+            dev = np.array(x[st.P + 1:st.P + B + 1])
+            for i in np.nonzero(ref != dev)[0]:
+                gap = lg[i, ref[i]] - lg[i, dev[i]]
+                worst = max(worst, float(gap))
+                assert gap <= tol, ("device token beyond tolerance", s, st.P + i, gap)
+                flips += 1
+            st.P += B
+            print("  teacher-forced", s, st.P, flush=True)
+    return flips, worst
+
+
+def test_config1_full_size_stream():
+    """configs[1] at its full size (500 faces, 4500 tokens): replay run == native run == what the oracle
+    picks at every position (teacher-forced, margin rule)."""
+    _need_gpu()
+    cfg = si.CONFIGS[1]
+    print("case config1 full", flush=True)
+    fm, _ = _ctx(cfg)
+    out, n, st = fm.generate(cfg.faces, True)
+    assert int(n[0]) == 4500 and st.tokens == 4500
+    fm.prefill_condition(0, torch.from_numpy(si.make_memory(cfg, 0)).cuda())
+    fm.set_draft_replay(out.clone(), 4500, 0.93, 5)
+    out2, n2, st2 = fm.generate(cfg.faces, True)
+    assert torch.equal(out, out2)
+    assert st2.steps < st.steps and st2.tokens == 4500
+    flips, worst = _teacher_forced_check(cfg, out.cpu().numpy(), TOL["bf16"], np.float64)
+    print("config1 full: allowed flips", flips, "worst margin", worst, "steps native/replay", st.steps, st2.steps, flush=True)
+
+
+@pytest.mark.skipif(os.environ.get("FM_LONG") != "1", reason="several minutes of CPU oracle time; set FM_LONG=1")
+def test_config2_full_size_stream():
+    _need_gpu()
+    cfg = si.CONFIGS[2]
+    print("case config2 full", flush=True)
+    fm, _ = _ctx(cfg)
+    out, n, st = fm.generate(cfg.faces, True)
+    assert int(n[0]) == 18000
+    flips, worst = _teacher_forced_check(cfg, out.cpu().numpy(), TOL["bf16"], np.float32, chunk=1500)
+    print("config2 full: allowed flips", flips, "worst margin", worst, flush=True)
