@@ -17,17 +17,19 @@
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Cross-workgroup exchange inside one launch (split-K / split-KV partials): values are written and read
-// with agent-scope atomics, which go through to the level of the memory hierarchy that all XCDs share,
-// so no cache-wide write-back / invalidate (what a full __threadfence costs on this chip) is needed.
-// publish_fence() only waits until this wave's own stores have been acknowledged.
+// Cross-workgroup exchange inside one launch (split-KV partials): values are written and read with
+// agent-scope atomics and published with an agent-scope RELEASE fence before the arrival counter is
+// bumped.  A workgroup-scope fence is not enough on this chip: the write-through of an agent-scope store
+// can still be in flight when the counter increment lands, and the last arriver then reads the previous
+// launch's data (seen as run-to-run differences in one token per ~10^4 steps).  The consumer side needs
+// no invalidate because it reads the partials with agent-scope loads.
 __device__ __forceinline__ void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ float ld_agent(const float* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void publish_fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); }
+__device__ __forceinline__ void publish_fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 
 #define FM_GEMM_WS_FLOATS (48u << 20)   // split-K partials (192 MiB)
 #define FM_GEMM_COUNTERS 65536
@@ -237,15 +239,9 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   const int mtiles = (a.M + 15) / 16;
   const int MT = mtiles <= 1 ? 1 : mtiles <= 2 ? 2 : mtiles <= 3 ? 3 : mtiles <= 5 ? 5 : 8;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
-  // K split: aim for >= ~1024 waves in flight, at least 2 fragments (2 KiB of weights) per wave
+  // The four waves of a workgroup split K; K is NOT split across workgroups (the kernel supports it, but
+  // the publication fence it needs costs more than the extra parallelism gains at these sizes).
   int kt_per_wave = (KT + 3) / 4, ksplit = 1;
-  if (nmb == 1) {
-    const long base_wgs = (long)NT * groups;
-    while (base_wgs * ksplit < 256 && kt_per_wave > 2 && kt_per_wave % 2 == 0 && ksplit < 16) {
-      kt_per_wave /= 2;
-      ksplit *= 2;
-    }
-  }
   const long tiles = (long)NT * groups * nmb;
   if (ksplit > 1 && (tiles > FM_GEMM_COUNTERS || tiles * ksplit * MT * 256 > (long)FM_GEMM_WS_FLOATS)) {
     ksplit = 1;

@@ -225,3 +225,32 @@ def test_config2_full_size_stream():
     assert int(n[0]) == 18000
     flips, worst = _teacher_forced_check(cfg, out.cpu().numpy(), TOL["bf16"], np.float32, chunk=1500)
     print("config2 full: allowed flips", flips, "worst margin", worst, flush=True)
+
+
+def test_streams_are_bit_reproducible_across_runs_and_modes():
+    """Same seeds => same stream, run after run, and for speculative, replay and one-token decoding alike
+    (the kernels never let the arithmetic of a position depend on what it is batched with)."""
+    _need_gpu()
+    cfg = si.CONFIGS[1]
+    faces = 160
+    print("case reproducible", flush=True)
+    fm, _ = _ctx(cfg)
+    mem = torch.from_numpy(si.make_memory(cfg, 0)).cuda()
+
+    def run(spec, replay=None):
+        fm.prefill_condition(0, mem)
+        if replay is None:
+            fm.set_draft_replay(None, 0, 0.0, 0)
+        else:
+            fm.set_draft_replay(replay, 9 * faces, 0.9, 3)
+        out, n, st = fm.generate(faces, spec)
+        return out.clone(), st
+
+    ref, st = run(True)
+    for _ in range(3):
+        o, _ = run(True)
+        assert torch.equal(o, ref)
+    o, st_seq = run(False)
+    assert torch.equal(o, ref) and st_seq.steps == 9 * faces
+    o, st_rep = run(True, ref)
+    assert torch.equal(o, ref) and st_rep.steps < st.steps
