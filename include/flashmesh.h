@@ -134,6 +134,12 @@ int fm_set_draft_replay(fm_ctx* ctx, const int32_t* stream_dev, int32_t stride, 
  * new budget that did not end with EOS become live again.  FM_EINVAL outside [1, max_tokens/9]. */
 int fm_set_budget(fm_ctx* ctx, int32_t max_faces);
 
+/* HOST copy of one of the position-indexed carry rings, [batch][ring][d_model] float32; which: 0 coordinate
+ * pre-stack outputs (32 entries), 1 vertex pre-stack outputs (16), 2 face outputs (8), 3 vertex outputs (16),
+ * 4/5/6 tapped features of the coordinate (32) / vertex (16) / face (8) level.  Entry = position mod ring size.
+ * Synchronises. */
+int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
+
 /* Algorithmic HBM bytes of one verify pass at the current committed lengths (weights once, self
  * and cross K/V once per block and sequence), for roofline reporting.  Synchronises. */
 int fm_verify_bytes(fm_ctx* ctx, double* host_bytes);

@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
-           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes"]
+           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes", "fm_debug_ring"]
 
 
 class LibraryMissing(RuntimeError):
@@ -59,6 +59,7 @@ def load_library():
     lib.fm_set_draft_replay.argtypes = [p, p, i32, i32, C.c_float, C.c_uint64]
     lib.fm_set_budget.argtypes = [p, i32]
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
+    lib.fm_debug_ring.argtypes = [p, i32, p]
     for n in EXPORTS:
         if n not in ("fm_last_error", "fm_block_max", "fm_blob_elems"):
             getattr(lib, n).restype = C.c_int
@@ -167,6 +168,12 @@ class FlashMesh:
 
     def set_budget(self, max_faces: int):
         self._chk(self.lib.fm_set_budget(self.h, max_faces), "fm_set_budget")
+
+    def debug_ring(self, which: int) -> np.ndarray:
+        size = (32, 16, 8, 16, 32, 16, 8)[which]
+        out = np.zeros((self.batch, size, self.cfgs.d_model), np.float32)
+        self._chk(self.lib.fm_debug_ring(self.h, which, C.c_void_p(out.ctypes.data)), "fm_debug_ring")
+        return out
 
     def verify_bytes(self) -> float:
         v = C.c_double()

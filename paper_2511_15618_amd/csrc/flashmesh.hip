@@ -17,6 +17,7 @@
 #include "fm_kernels_basic.h"
 #include "fm_kernels_step.h"
 #include "fm_kernels_mfma.h"
+#include "fm_kernels_persist.h"
 
 #define RS_C 32  // ring sizes (positions kept per sequence) at the coordinate / vertex / face level
 #define RS_V 16
@@ -27,6 +28,7 @@ namespace {
 struct Layer {
   float *g1, *g2, *g3;
   void *wqkv, *wo, *cq, *ckv, *co, *w1, *w2;  // storage type T, [out, in]
+  void* wqkv_rp;                               // persistent path: q/k tiles hold whole rotary pairs
   void *Kc, *Vc;                               // [S][H][cap][64]
   void *Km, *Vm;                               // [S][H][M][64]
   int level;                                   // 0 coordinate, 1 vertex, 2 face
@@ -43,7 +45,7 @@ struct HfLevel {
   void *wq, *w1, *w2;
 };
 
-struct LoadItem { size_t blob_off, n; void* dst; bool f32; int N, K; };  // N, K > 0: linear weight [N, K]
+struct LoadItem { size_t blob_off, n; void* dst; bool f32; int N, K, perm; };  // N, K > 0: linear weight [N, K]
 
 }  // namespace
 
@@ -94,6 +96,10 @@ struct fm_ctx {
   int *gen_tok, *gen_len;  // block buffers used by fm_generate
   int* gen_acc;
   int* host_flag;          // pinned
+  // persistent verify kernel (one sequence, block <= 16, half-precision path)
+  bool persist;
+  PkArgs pk;
+  unsigned pk_epoch;
   double weight_bytes;
 };
 
@@ -230,6 +236,17 @@ int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, f
   const int d = D.d;
   hipLaunchKernelGGL(k_verify_setup, dim3(1), dim3(256), 0, c->stream, c->st, D, c->inv, block_tok, block_len,
                      c->pos[0], c->pos[1], c->pos[2], c->limx[0], c->limx[1], c->limx[2], c->cs[0], c->cs[1], c->cs[2]);
+  if (c->persist) {
+    // the whole backbone forward in one launch (see fm_kernels_persist.h), then greedy choice and acceptance
+    float* lgp = logits_out ? logits_out : c->logits;
+    c->pk.logits = lgp;
+    c->pk.epoch = ++c->pk_epoch;
+    hipLaunchKernelGGL(k_verify_persist, dim3(PK_NWG), dim3(256), 0, c->stream, c->pk);
+    hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, lgp, D.V, D.ban ? D.nbins : D.V, c->st.y);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted);
+    HIPCHK(c, hipGetLastError());
+    return FM_OK;
+  }
   hipLaunchKernelGGL((k_embed<T>), dim3(c->Rc), dim3(256), 0, c->stream, c->st.vtok, c->pos[0], (const T*)c->emb,
                      c->h[0], d);
   const int* flag = c->st.alive;
@@ -358,13 +375,25 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
   return FM_OK;
 }
 
+// After a synchronisation: did the persistent kernel give up waiting (it never hangs, it reports)?
+int check_persist(fm_ctx* c) {
+  if (!c->persist) return FM_OK;
+  unsigned w[9] = {0};
+  HIPCHK(c, hipMemcpy(w, c->pk.abort_word, sizeof w, hipMemcpyDeviceToHost));
+  if (w[0])
+    return fail(c, FM_EHIP, "persistent verify kernel timed out: earliest stuck stage %u; first missing element: stage %u "
+                "workgroup %u thread %u index %u expected tag %u saw %u (epoch %u)", w[1], w[5], w[6], w[7], w[8], w[3], w[4],
+                c->pk_epoch);
+  return FM_OK;
+}
+
 // Build the parameter tables and the list of (blob range -> device destination) in manifest order.
 int build_params(fm_ctx* c) {
   const Dims& D = c->D;
   const size_t d = D.d, ff = c->ff, hff = c->hff, V = D.V;
   size_t off = 0;
-  auto item = [&](void* dst, size_t n, bool f32) { c->items.push_back({off, n, dst, f32, 0, 0}); off += n; };
-  auto lin = [&](void* dst, size_t N, size_t K) { c->items.push_back({off, N * K, dst, false, (int)N, (int)K}); off += N * K; };
+  auto item = [&](void* dst, size_t n, bool f32) { c->items.push_back({off, n, dst, f32, 0, 0, 0}); off += n; };
+  auto lin = [&](void* dst, size_t N, size_t K) { c->items.push_back({off, N * K, dst, false, (int)N, (int)K, 0}); off += N * K; };
   auto at = [&](void* base, size_t elems) { return (void*)((uint8_t*)base + elems * c->esz); };
 
   TRY(dalloc_t(c, &c->emb, V * d));
@@ -383,6 +412,10 @@ int build_params(fm_ctx* c) {
       TRY(dalloc_t(c, &L.Kc, D.S * cache_seq_elems(c, cap))); TRY(dalloc_t(c, &L.Vc, D.S * cache_seq_elems(c, cap)));
       TRY(dalloc_t(c, &L.Km, D.S * cache_seq_elems(c, D.M))); TRY(dalloc_t(c, &L.Vm, D.S * cache_seq_elems(c, D.M)));
       item(L.g1, d, true);
+      if (c->persist) {
+        TRY(dalloc_t(c, &L.wqkv_rp, 3 * d * d));
+        c->items.push_back({off, 3 * d * d, L.wqkv_rp, false, (int)(3 * d), (int)d, (int)d});
+      }
       lin(L.wqkv, 3 * d, d);   // wq, wk, wv are consecutive in the blob
       lin(L.wo, d, d);
       item(L.g2, d, true);
@@ -430,6 +463,72 @@ int build_params(fm_ctx* c) {
     }
   }
   c->blob_elems = off;
+  return FM_OK;
+}
+
+// exchange buffers, layer table and argument block of the persistent verify kernel
+int build_persist(fm_ctx* c) {
+  const Dims& D = c->D;
+  const size_t d = D.d;
+  PkArgs& a = c->pk;
+  memset(&a, 0, sizeof a);
+  std::vector<PkLayer> hl;
+  for (int st = 0; st < 5; st++) {
+    a.first[st] = (int)hl.size();
+    a.count[st] = (int)c->stacks[st].size();
+    for (size_t i = 0; i < c->stacks[st].size(); i++) {
+      const Layer& L = c->stacks[st][i];
+      PkLayer p{};
+      p.g1 = L.g1; p.g2 = L.g2; p.g3 = L.g3;
+      p.wqkv = (const f16_t*)L.wqkv_rp; p.wo = (const f16_t*)L.wo; p.cq = (const f16_t*)L.cq; p.co = (const f16_t*)L.co;
+      p.w1 = (const f16_t*)L.w1; p.w2 = (const f16_t*)L.w2;
+      p.Kc = (f16_t*)L.Kc; p.Vc = (f16_t*)L.Vc; p.Km = (const f16_t*)L.Km; p.Vm = (const f16_t*)L.Vm;
+      p.level = L.level;
+      p.last = i + 1 == c->stacks[st].size();
+      p.tap = p.last && (st == 2 || st == 3 || st == 4);
+      p.stack = st;
+      hl.push_back(p);
+    }
+  }
+  a.n_layers = (int)hl.size();
+  PkLayer* dl;
+  TRY(dalloc(c, &dl, hl.size()));
+  if (hipMemcpy(dl, hl.data(), hl.size() * sizeof(PkLayer), hipMemcpyHostToDevice) != hipSuccess) return fail(c, FM_EHIP, "layer table copy failed");
+  a.layers = dl;
+  a.D = D; a.ff = c->ff; a.eps = c->cfg.rms_eps;
+  a.R[0] = D.Bm; a.R[1] = D.VB; a.R[2] = D.FB;
+  const int caps[3] = {D.capc, D.capv, D.capf};
+  for (int l = 0; l < 3; l++) {
+    a.capb[l] = (caps[l] + 31) / 32;
+    int ns = PK_NWG / D.H;                       // about one attention unit per workgroup
+    ns = std::min(ns, std::max(1, a.capb[l] / 2));
+    a.nsplit[l] = std::max(1, std::min(ns, PK_MAXSPLIT));
+    a.pos[l] = c->pos[l]; a.limx[l] = c->limx[l]; a.cs[l] = c->cs[l];
+  }
+  a.capbM = (D.M + 31) / 32;
+  a.nsplitM = std::max(1, std::min(std::min(PK_NWG / D.H, std::max(1, a.capbM / 2)), PK_MAXSPLIT));
+  a.vtok = c->st.vtok;
+  a.ring_hc = c->ring_hc; a.ring_hv = c->ring_hv; a.ring_yf = c->ring_yf; a.ring_yv = c->ring_yv;
+  a.tap[0] = c->tap_c; a.tap[1] = c->tap_v; a.tap[2] = c->tap_f;
+  a.emb = (const f16_t*)c->emb; a.short_cv = (const f16_t*)c->short_cv; a.short_vf = (const f16_t*)c->short_vf;
+  a.lm = (const f16_t*)c->lm; a.gf = c->gf; a.logits = c->logits;
+  TRY(dalloc(c, &a.hA, 16 * d)); TRY(dalloc(c, &a.hB, 16 * d)); TRY(dalloc(c, &a.hC, 16 * d));
+  for (int i = 0; i < 4; i++) TRY(dalloc(c, &a.hT[i], 16 * d));
+  TRY(dalloc(c, &a.q, 8 * d)); TRY(dalloc(c, &a.att, 8 * d)); TRY(dalloc(c, &a.q2, 8 * d)); TRY(dalloc(c, &a.att2, 8 * d));
+  TRY(dalloc(c, &a.pool, 8 * d)); TRY(dalloc(c, &a.mid, (size_t)8 * c->ff));
+  TRY(dalloc(c, &a.newK, (size_t)D.H * 16 * 32)); TRY(dalloc(c, &a.newV, (size_t)D.H * 16 * 32));
+  TRY(dalloc(c, &a.partS, (size_t)D.H * PK_MAXSPLIT * PK_PART)); TRY(dalloc(c, &a.partX, (size_t)D.H * PK_MAXSPLIT * PK_PART));
+  TRY(dalloc(c, &a.abort_word, 16));
+  if (hipMemset(a.abort_word + 1, 0xFF, 4) != hipSuccess) return fail(c, FM_EHIP, "hipMemset failed");
+  a.run_flag = c->st.alive;
+  c->pk_epoch = 0;
+  // all 256 workgroups must be resident at once: they wait for each other's results
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist, 256, 0) != hipSuccess || (long)cus * per_cu < PK_NWG) {
+    (void)hipGetLastError();
+    c->persist = false;   // fall back to the per-launch path
+  }
   return FM_OK;
 }
 
@@ -481,6 +580,7 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &c->dist_v, S * std::max(D.nhfc, 1) * D.V)); TRY(dalloc(c, &c->dist_f, S * std::max(D.nhfc, 1) * D.V));
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
+  if (c->persist) TRY(build_persist(c));
   c->mres = MfmaRes{nullptr, nullptr, nullptr, nullptr, 0};
   if (c->bf16) {
     TRY(dalloc(c, &c->mres.gemm_ws, (size_t)FM_GEMM_WS_FLOATS, false));
@@ -539,6 +639,12 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   c->prefilled.assign(D.S, false);
   c->replay = Replay{nullptr, 0, 0, 0.f, 0ull};
   c->host_flag = nullptr;
+  {
+    const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
+    const char* env = getenv("FM_PERSIST");
+    c->persist = c->bf16 && D.S == 1 && D.Bm <= 16 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 128 == 0 && nl < 62 &&
+                 !(env && env[0] == '0');
+  }
   int rc = build_params(c);
   if (rc == FM_OK) rc = build_buffers(c);
   if (rc == FM_OK) {
@@ -591,7 +697,7 @@ int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
         if (c->bf16 && it.N > 0) {
           if (n != it.n) return fail(c, FM_EINVAL, "staging buffer smaller than a weight matrix");
           hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, c->stage, (f16_t*)it.dst, it.N, it.K,
-                             (it.N + 15) / 16 * 16);
+                             (it.N + 15) / 16 * 16, it.perm);
         } else if (c->bf16)
           hipLaunchKernelGGL((k_convert<f16_t>), dim3(1024), dim3(256), 0, c->stream, c->stage, (f16_t*)it.dst + done, (long)n);
         else
@@ -663,6 +769,7 @@ int fm_read_state(fm_ctx* c, int32_t* host_out) {
   HIPCHK(c, hipMemcpy(P.data(), c->st.P, S * 4, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(mn.data(), c->st.main, S * 4, hipMemcpyDeviceToHost));
   HIPCHK(c, hipMemcpy(fin.data(), c->st.fin, S * 4, hipMemcpyDeviceToHost));
+  TRY(check_persist(c));
   for (int s = 0; s < S; s++) {
     host_out[s * 6 + 0] = P[s];
     host_out[s * 6 + 1] = (P[s] + 2) / 3;
@@ -671,6 +778,16 @@ int fm_read_state(fm_ctx* c, int32_t* host_out) {
     host_out[s * 6 + 4] = fin[s];
     host_out[s * 6 + 5] = P[s];
   }
+  return FM_OK;
+}
+
+int fm_debug_ring(fm_ctx* c, int32_t which, float* host_out) {
+  if (!c || !host_out) return FM_EINVAL;
+  float* src[7] = {c->ring_hc, c->ring_hv, c->ring_yf, c->ring_yv, c->tap_c, c->tap_v, c->tap_f};
+  const int rs[7] = {RS_C, RS_V, RS_F, RS_V, RS_C, RS_V, RS_F};
+  if (which < 0 || which >= 7) return fail(c, FM_EINVAL, "ring %d out of range", which);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(host_out, src[which], (size_t)c->D.S * rs[which] * c->D.d * sizeof(float), hipMemcpyDeviceToHost));
   return FM_OK;
 }
 
@@ -738,6 +855,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
                                hipMemcpyDeviceToDevice, c->stream));
     HIPCHK(c, hipMemcpyAsync(out_len, c->st.P, (size_t)D.S * 4, hipMemcpyDeviceToDevice, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));
+    TRY(check_persist(c));
     if (stats) {
       unsigned long long cnt[2], hist[32];
       HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));

@@ -93,14 +93,22 @@ __global__ void k_mem_kv_store_h(const float* __restrict__ kv, f16_t* __restrict
 }
 
 // weights [N][K] fp32 (bf16-valued) -> half, tiled: fragment (nt, kt) holds W[nt*16 + l%16][kt*32 + (l/16)*8 + j]
-__global__ void k_tile_weight(const float* __restrict__ src, f16_t* __restrict__ dst, int N, int K, int Npad) {
+// perm_d > 0 (fused q,k,v projection of width perm_d each): the q and k tiles are re-ordered so that tile
+// (head, quarter) holds dims quarter*8..+8 and the same dims + 32, i.e. both halves of 8 rotary pairs.
+__global__ void k_tile_weight(const float* __restrict__ src, f16_t* __restrict__ dst, int N, int K, int Npad, int perm_d) {
   const long total = (long)Npad * K / 8;
   for (long v = blockIdx.x * (long)blockDim.x + threadIdx.x; v < total; v += (long)gridDim.x * blockDim.x) {
     const int lane = (int)(v & 63);
     const long frag = v >> 6;
     const int KT = K / 32;
     const int kt = (int)(frag % KT), nt = (int)(frag / KT);
-    const int n = nt * 16 + (lane & 15), k = kt * 32 + (lane >> 4) * 8;
+    int n = nt * 16 + (lane & 15);
+    const int k = kt * 32 + (lane >> 4) * 8;
+    if (perm_d > 0 && n < 2 * perm_d) {
+      const int part = n / perm_d, cp = n % perm_d;
+      const int hh = cp >> 6, qd = (cp & 63) >> 4, c = cp & 15;
+      n = part * perm_d + hh * 64 + (c < 8 ? qd * 8 + c : 32 + qd * 8 + (c - 8));
+    }
     f16x8 o;
 #pragma unroll
     for (int j = 0; j < 8; j++) o[j] = n < N ? (f16_t)src[(long)n * K + k + j] : (f16_t)0.f;

@@ -1,0 +1,737 @@
+// Persistent verify kernel for the half-precision path with at most 16 rows per hourglass level
+// (one sequence, block <= 16): the whole backbone forward of one verify pass is ONE launch.
+//
+// Why: at batch 1 a transformer block is ~10 dependent operations of 0.3-1 us of HBM time each; as
+// separate launches every one costs ~4 us.  Here 256 resident workgroups walk a static schedule of
+// stages (GEMM tiles, attention splits, merges, level transitions) and hand activations to each other
+// through "tagged" exchange buffers: every 8-byte element carries 4 bytes of payload and a 4-byte tag
+// (launch epoch, layer).  A consumer simply re-reads an element until its tag is the one it expects, so
+// correctness never depends on the order in which stores become visible across XCDs, and there is no
+// grid barrier.  Payloads are written / read with agent-scope 8-byte atomics (single-copy atomic, and
+// they bypass the per-XCD L2, which is not coherent across XCDs inside a launch).
+// A workgroup that is not needed in a stage runs ahead and issues the weight loads of its next tile
+// before it starts waiting, which is what keeps HBM busy across the dependency chain.
+//
+// Every wait is bounded (wall clock); on a time-out the kernel raises an abort word that every waiter
+// polls, so all workgroups leave and the host reports an error instead of hanging.
+//
+// Arithmetic is kept batch-invariant exactly like the per-launch kernels: fixed 32-key blocks, fixed
+// split ranges, fixed merge order, rows never mixed in a GEMM.
+#pragma once
+#include "fm_device.h"
+#include "fm_kernels_mfma.h"
+#include "fm_kernels_step.h"
+
+typedef unsigned long long u64;
+
+#define PK_NWG 256
+#define PK_MAXSPLIT 64
+#define PK_PART (16 * 64 + 32)            // per (head, split): 16x64 unnormalised O, 16 running maxima, 16 sums
+#define PK_TIMEOUT_TICKS 20000000ull      // 200 ms of the 100 MHz wall clock
+
+struct PkLayer {
+  const float *g1, *g2, *g3;
+  const f16_t *wqkv, *wo, *cq, *co, *w1, *w2;   // tiled; wqkv with rotary pairs inside one tile
+  f16_t *Kc, *Vc;
+  const f16_t *Km, *Vm;
+  int level;      // 0 coordinate, 1 vertex, 2 face
+  int tap;        // store the layer input to the level's tap ring (input of the last layer of a stack)
+  int last;       // last layer of its stack: output goes to hT[stack] and to the stack's ring
+  int stack;      // 0 cpre, 1 vpre, 2 face, 3 vpost, 4 cpost
+};
+
+struct PkArgs {
+  const PkLayer* layers;
+  int n_layers;
+  int first[5], count[5];
+  Dims D;
+  int ff;
+  float eps;
+  int R[3];                 // row slots per level (<= 16)
+  int capb[3], capbM;       // cache capacity in 32-key blocks per level / of the condition memory
+  int nsplit[3], nsplitM;   // launch-time split counts (fixed partition of the key axis)
+  const int* pos[3];
+  const int* limx[3];
+  const float2* cs[3];
+  const int* vtok;
+  float *ring_hc, *ring_hv, *ring_yf, *ring_yv;
+  float* tap[3];
+  const f16_t *emb, *short_cv, *short_vf, *lm;
+  const float* gf;
+  float* logits;
+  // exchange buffers (u64 = payload | tag << 32)
+  u64 *hA, *hB, *hC;        // [16][d]
+  u64* hT[4];               // outputs of cpre, vpre, face, vpost  [16][d]
+  u64 *q, *att, *q2, *att2, *pool;   // [16][d/2]
+  u64* mid;                 // [16][ff/2]
+  u64 *newK, *newV;         // [H][16][32]
+  u64 *partS, *partX;       // [H][PK_MAXSPLIT][PK_PART]
+  unsigned epoch;
+  unsigned* abort_word;     // [0] abort flag, [1] first failing stage (diagnostic)
+  const int* run_flag;
+};
+
+struct PkShared {
+  f32x4 red[4][64];
+  float ssq[4][16];
+  float lo[4][16][65];
+  float lm[4][16], ll[4][16];
+  float cf[PK_MAXSPLIT][16];
+  float cl[PK_MAXSPLIT][16];
+  float cden[16];
+};
+
+__device__ __forceinline__ u64 pk_ld(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void pk_st(u64* p, unsigned payload, unsigned tag) {
+  __hip_atomic_store(p, ((u64)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void pk_stf(u64* p, float v, unsigned tag) { pk_st(p, __float_as_uint(v), tag); }
+__device__ __forceinline__ unsigned pk_pack(float lo, float hi) {
+  const f16_t a = (f16_t)lo, b = (f16_t)hi;
+  return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
+}
+__device__ __forceinline__ bool pk_expired(const PkArgs& a, u64 t0, int stage) {
+  // every waiter that gives up records its stage; the smallest one is where the chain broke
+  if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+    atomicMin(a.abort_word + 1, (unsigned)stage);
+    return true;
+  }
+  if (wall_clock64() - t0 > PK_TIMEOUT_TICKS) {
+    __hip_atomic_store(a.abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    atomicMin(a.abort_word + 1, (unsigned)stage);
+    return true;
+  }
+  return false;
+}
+
+// Wave-wide fetch of N tagged elements per lane (addresses from `addr(i)`, i < n <= N); inactive lanes get 0.
+// All loads are issued before any is checked; the whole set is re-read until every tag matches.
+template <int N, class F>
+__device__ __forceinline__ bool pk_fetch(unsigned (&out)[N], int n, bool active, unsigned tag, F addr, const PkArgs& a, int stage) {
+  const u64 t0 = wall_clock64();
+  int it = 0;
+  while (true) {
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      out[i] = 0u;
+      if (active && i < n) {
+        const u64 v = pk_ld(addr(i));
+        out[i] = (unsigned)v;
+        ok = ok && ((unsigned)(v >> 32) == tag);
+      }
+    }
+    if (__all(ok)) return true;
+    if ((++it & 3) == 0 && pk_expired(a, t0, stage)) {
+      // diagnostics of the first element found missing: expected tag, tag seen, stage, workgroup, thread
+      if (!ok && atomicCAS(a.abort_word + 2, 0u, 1u) == 0u) {
+        unsigned seen = 0, idx = 0;
+        for (int i = 0; i < N; i++)
+          if (active && i < n) { const u64 v = pk_ld(addr(i)); if ((unsigned)(v >> 32) != tag) { seen = (unsigned)(v >> 32); idx = i; break; } }
+        a.abort_word[3] = tag; a.abort_word[4] = seen; a.abort_word[5] = (unsigned)stage;
+        a.abort_word[6] = blockIdx.x; a.abort_word[7] = threadIdx.x; a.abort_word[8] = idx;
+      }
+      return false;
+    }
+    __builtin_amdgcn_s_sleep(2);
+  }
+}
+
+// A level transition must not publish anything before the stack below it has finished with the shared
+// exchange buffers, even when its own rows are inactive or only need data of earlier passes: it first
+// waits for row 0 of the stack output from EVERY tile (a tile stores only after its last read).
+__device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, unsigned tag, int stage);
+
+#define PK_TAG(a, l) ((a).epoch * 64u + (unsigned)(l) + 1u)
+
+__device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, unsigned tag, int stage) {
+  unsigned s4[4];
+  const int d = a.D.d;
+  const int n = (d - (int)threadIdx.x + 255) / 256;     // columns threadIdx.x, +256, ... below d (d <= 1024)
+  return pk_fetch<4>(s4, n, n > 0, tag, [&](int i) { return hT + threadIdx.x + 256 * i; }, a, stage);
+}
+
+// ------------------------------------------------------------------------------------------
+// GEMM tile: C[16 rows x 16 cols] = A[16 x K] * W_tile^T, four waves split K, result in wave 0.
+// ASRC 0: A is a half-pair exchange buffer [16][K/2];  ASRC 1: A is an fp32 exchange buffer [16][K] that is
+// RMS-normalised (gain g) on the fly - K/128 <= 8 fragments per wave, i.e. K <= 1024.
+// ------------------------------------------------------------------------------------------
+template <int ASRC>
+__device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, const f16_t* Wt, int KT, const u64* A,
+                                             unsigned tagA, const float* gain, int R, f32x4& result, int stage) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, g = lane >> 4;
+  const bool on = r < R;
+  const int FW = KT >> 2;                  // fragments per wave (host guarantees KT % 4 == 0)
+  const int K = KT * 32;
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  bool ok = true;
+  if (ASRC == 1) {
+    // weights first (they do not depend on anything), then wait for the activations
+    f16x8 wf[8];
+#pragma unroll
+    for (int f = 0; f < 8; f++)
+      if (f < FW) wf[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
+    unsigned raw[64];
+    const u64* base = A + (long)r * K + (long)(wave * FW) * 32 + g * 8;
+    ok = pk_fetch<64>(raw, FW * 8, on, tagA, [&](int i) { return base + (i >> 3) * 32 + (i & 7); }, a, stage);
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 64; i++) { const float v = __uint_as_float(raw[i]); ss += v * v; }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (lane < 16) sh.ssq[wave][lane] = ss;
+    if (__syncthreads_or(!ok)) return false;
+    const float tot = sh.ssq[0][r] + sh.ssq[1][r] + sh.ssq[2][r] + sh.ssq[3][r];
+    const float inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+#pragma unroll
+    for (int f = 0; f < 8; f++) {
+      if (f < FW) {
+        const float* gp = gain + (wave * FW + f) * 32 + g * 8;
+        f16x8 av;
+#pragma unroll
+        for (int j = 0; j < 8; j++) av[j] = (f16_t)(__uint_as_float(raw[f * 8 + j]) * inv * gp[j]);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
+      }
+    }
+  } else {
+    for (int f0 = 0; f0 < FW; f0 += 8) {
+      f16x8 wf[8];
+#pragma unroll
+      for (int f = 0; f < 8; f++)
+        if (f0 + f < FW) wf[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f0 + f) * 64 + lane) * 8);
+      unsigned raw[32];
+      const u64* base = A + (long)r * (K >> 1) + (long)(wave * FW + f0) * 16 + g * 4;
+      const int nf = min(8, FW - f0);
+      ok = ok && pk_fetch<32>(raw, nf * 4, on, tagA, [&](int i) { return base + (i >> 2) * 16 + (i & 3); }, a, stage);
+#pragma unroll
+      for (int f = 0; f < 8; f++) {
+        if (f < nf) {
+          typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+          const u32x4 pk = u32x4{raw[f * 4], raw[f * 4 + 1], raw[f * 4 + 2], raw[f * 4 + 3]};
+          const f16x8 av = __builtin_bit_cast(f16x8, pk);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
+        }
+      }
+    }
+  }
+  sh.red[wave][lane] = acc;
+  if (__syncthreads_or(!ok)) return false;
+  if (wave == 0) result = sh.red[0][lane] + sh.red[1][lane] + sh.red[2][lane] + sh.red[3][lane];
+  return true;
+}
+
+// residual epilogue (wave 0): out[r][n] = old[r][n] + c; optional copies into position-indexed rings
+__device__ __forceinline__ bool pk_epi_residual(const PkArgs& a, const f32x4& c, int nt, const u64* hold, unsigned tag_old,
+                                                u64* hout, unsigned tag_out, int R, const int* pos, float* tap_ring,
+                                                float* out_ring, int ring_size, int stage) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
+  const int d = a.D.d;
+  unsigned old[4];
+  const bool ok = pk_fetch<4>(old, 4, true, tag_old, [&](int i) { return hold + (long)min(g * 4 + i, R - 1) * d + n; }, a, stage);
+  if (!ok) return false;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int r = g * 4 + i;
+    if (r < R) {
+      const float ho = __uint_as_float(old[i]);
+      const float v = ho + c[i];
+      pk_stf(hout + (long)r * d + n, v, tag_out);
+      const int p = pos[r];
+      if (p >= 0) {
+        if (tap_ring) tap_ring[(long)(p & (ring_size - 1)) * d + n] = ho;
+        if (out_ring) out_ring[(long)(p & (ring_size - 1)) * d + n] = v;
+      }
+    }
+  }
+  return true;
+}
+
+// half-pair epilogue (wave 0): dst[r][n/2] = (c[n], c[n+1]) as halves, optional GELU
+__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const float v = gelu ? gelu_tanh_f(c[i]) : c[i];
+    const float w = __shfl_xor(v, 1, 64);
+    const int r = g * 4 + i;
+    if ((lane & 1) == 0 && r < R) pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag);
+  }
+}
+
+// QKV epilogue (wave 0).  Tiles of the q and k parts hold 8 rotary pairs: columns 0..7 = dims qd*8.., columns
+// 8..15 = the same dims + 32.  q -> exchange buffer; k, v -> cache (for later passes) and exchange buffers.
+__device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, const f32x4& c, int nt, unsigned tag, int R,
+                                           const int* pos, const float2* cs, int capb) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
+  const int d = a.D.d;
+  const int part = (nt * 16) / d, cp = (nt * 16) % d;
+  const int hh = cp >> 6, qd = (cp & 63) >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int r = g * 4 + i;
+    const int rr = min(r, R - 1);
+    float v = c[i];
+    int dim;
+    if (part < 2) {
+      const int j = qd * 8 + (col & 7);
+      const float2 t = cs[(long)rr * 32 + j];
+      const float o = __shfl_xor(v, 8, 64);
+      v = col < 8 ? v * t.x - o * t.y : v * t.x + o * t.y;
+      dim = col < 8 ? j : j + 32;
+    } else {
+      dim = qd * 16 + col;
+    }
+    const float w = __shfl_xor(v, 1, 64);       // neighbour dim (dim ^ 1 sits in lane ^ 1 in every layout above)
+    const int p = pos[rr];
+    if (r < R) {
+      if (part == 0) {
+        if ((lane & 1) == 0) pk_st(a.q + (long)r * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
+      } else {
+        u64* nb = (part == 1 ? a.newK : a.newV) + ((long)hh * 16 + r) * 32;
+        if ((lane & 1) == 0) pk_st(nb + (dim >> 1), pk_pack(v, w), tag);
+        if (p >= 0) {
+          const long base = (long)hh * capb * 2048;
+          if (part == 1) L.Kc[base + kblk_off(p, dim)] = (f16_t)v;
+          else L.Vc[base + vblk_off(p, dim)] = (f16_t)v;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Attention over one key range of one head (flash-decoding split), same arithmetic as k_attn_mfma<1>.
+// Keys of this pass (positions >= P0) are taken from the exchange buffers, older keys from the cache.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, const int* limit, int R,
+                                             const f16_t* Kc, const f16_t* Vc, int capb, int nsplit_cfg, int hh, int split,
+                                             bool overlay, int P0, u64* part, unsigned tag, int stage) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int g = lane >> 4, ql = lane & 15;
+  const int d = a.D.d;
+  const float kScale = 0.125f * 1.4426950408889634f;
+  const bool on = ql < R;
+  const int lim = on ? limit[ql] : -1;
+  int maxlim = lim;
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, o, 64));
+  const int nblk = (maxlim + 32) >> 5;
+  const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
+  const int nsplit = max(1, (nblk + per - 1) / per);
+  if (split >= nsplit) return true;      // nothing visible in this range: the merge knows the same count
+  const int b0 = split * per, b1 = min(b0 + per, nblk);
+
+  unsigned qraw[8];
+  const u64* qp = qbuf + (long)ql * (d >> 1) + ((hh * 64 + g * 8) >> 1);
+  bool ok = pk_fetch<8>(qraw, 8, on, tag, [&](int i) { return qp + (i >> 2) * 16 + (i & 3); }, a, stage);
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const f16x8 qf0 = __builtin_bit_cast(f16x8, (u32x4{qraw[0], qraw[1], qraw[2], qraw[3]}));
+  const f16x8 qf1 = __builtin_bit_cast(f16x8, (u32x4{qraw[4], qraw[5], qraw[6], qraw[7]}));
+
+  float mrun = -INFINITY, lrun = 0.f;
+  f32x4 o[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const f16_t* Kb = Kc + (long)hh * capb * 2048;
+  const f16_t* Vb = Vc + (long)hh * capb * 2048;
+  for (int b = b0 + wave; b < b1; b += 4) {
+    const f16_t* kp = Kb + (long)b * 2048 + lane * 8;
+    const f16_t* vp = Vb + (long)b * 2048 + (lane & 15) * 32 + g * 8;
+    f16x8 kf[4], vf[4];
+#pragma unroll
+    for (int f = 0; f < 4; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+    if (overlay && b * 32 + 31 >= P0) {
+      // rows written by this pass: K fragment f = (hb, dh) holds key b*32 + hb*16 + lane%16, dims dh*32 + g*8..+8
+#pragma unroll
+      for (int f = 0; f < 4; f++) {
+        const int key = b * 32 + (f >> 1) * 16 + (lane & 15);
+        const int nr = key - P0;
+        const bool fresh = nr >= 0 && nr < R;
+        unsigned raw[4];
+        const u64* np = a.newK + ((long)hh * 16 + (fresh ? nr : 0)) * 32 + (((f & 1) * 32 + g * 8) >> 1);
+        ok = ok && pk_fetch<4>(raw, 4, fresh, tag, [&](int i) { return np + i; }, a, stage);
+        if (fresh) kf[f] = __builtin_bit_cast(f16x8, (u32x4{raw[0], raw[1], raw[2], raw[3]}));
+      }
+      // V fragment dt holds dim dt*16 + lane%16 and the 8 slots g*8 + j <-> key b*32 + (j/4)*16 + g*4 + j%4
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        const int dim = dt * 16 + (lane & 15);
+        unsigned raw[8];
+        bool any = false;
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+          any = any || (nr >= 0 && nr < R);
+        }
+        ok = ok && pk_fetch<8>(raw, 8, any, tag, [&](int j) {
+          int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+          nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
+          return a.newV + ((long)hh * 16 + nr) * 32 + (dim >> 1);
+        }, a, stage);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+          const int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+          if (nr >= 0 && nr < R) {
+            const unsigned short hbits = (dim & 1) ? (unsigned short)(raw[j] >> 16) : (unsigned short)(raw[j] & 0xFFFFu);
+            vf[dt][j] = __builtin_bit_cast(f16_t, hbits);
+          }
+        }
+      }
+    }
+    f32x4 sT[2];
+#pragma unroll
+    for (int hb = 0; hb < 2; hb++) {
+      f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+      z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2], qf0, z, 0, 0, 0);
+      z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2 + 1], qf1, z, 0, 0, 0);
+      sT[hb] = z;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int hb = 0; hb < 2; hb++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int key = b * 32 + hb * 16 + g * 4 + i;
+        const float v = key <= lim ? sT[hb][i] * kScale : -INFINITY;
+        sT[hb][i] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mnew = fmaxf(mrun, mx);
+    const float msafe = mnew == -INFINITY ? 0.f : mnew;
+    const float alpha = __builtin_amdgcn_exp2f(mrun - msafe);
+    mrun = mnew;
+    f16x8 pf;
+    float psum = 0.f;
+#pragma unroll
+    for (int hb = 0; hb < 2; hb++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const float p = __builtin_amdgcn_exp2f(sT[hb][i] - msafe);
+        psum += p;
+        pf[hb * 4 + i] = (f16_t)p;
+      }
+    lrun = lrun * alpha + psum;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) {
+      o[dt] *= alpha;
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[dt], 0, 0, 0);
+    }
+  }
+  float l = lrun;
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (g == 0) { sh.lm[wave][ql] = mrun; sh.ll[wave][ql] = l; }
+#pragma unroll
+  for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+    for (int i = 0; i < 4; i++) sh.lo[wave][ql][dt * 16 + g * 4 + i] = o[dt][i];
+  if (__syncthreads_or(!ok)) return false;
+  for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+    const int qi = e >> 6, dim = e & 63;
+    const float M = fmaxf(fmaxf(sh.lm[0][qi], sh.lm[1][qi]), fmaxf(sh.lm[2][qi], sh.lm[3][qi]));
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+      const float f = __builtin_amdgcn_exp2f(sh.lm[w][qi] - Ms);
+      num += sh.lo[w][qi][dim] * f;
+      den += sh.ll[w][qi] * f;
+    }
+    if (qi < R) {
+      pk_stf(part + e, num, tag);
+      if (dim == 0) { pk_stf(part + 16 * 64 + qi, M, tag); pk_stf(part + 16 * 64 + 16 + qi, den, tag); }
+    }
+  }
+  __syncthreads();
+  return true;
+}
+
+// merge of the splits of one head into the half-pair attention output
+__device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, const int* limit, int R, int capb, int nsplit_cfg,
+                                              int hh, const u64* parts, u64* att, unsigned tag, int stage) {
+  const int d = a.D.d;
+  int maxlim = -1;
+  for (int r = 0; r < R; r++) maxlim = max(maxlim, limit[r]);
+  const int nblk = (maxlim + 32) >> 5;
+  const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
+  const int nsplit = max(1, (nblk + per - 1) / per);
+  const u64* base = parts + (long)hh * PK_MAXSPLIT * PK_PART;
+  bool ok = true;
+  // running maxima and sums: nsplit * R values each
+  for (int e0 = 0; e0 < nsplit * 16; e0 += 256) {
+    const int e = e0 + threadIdx.x;
+    const int k2 = e >> 4, qi = e & 15;
+    const bool on = k2 < nsplit && qi < R;
+    unsigned raw[2];
+    const u64* p = base + (long)(on ? k2 : 0) * PK_PART + 16 * 64 + qi;
+    ok = pk_fetch<2>(raw, 2, on, tag, [&](int i) { return p + i * 16; }, a, stage) && ok;
+    if (k2 < nsplit) {
+      sh.cf[k2][qi] = on ? __uint_as_float(raw[0]) : -INFINITY;
+      sh.cl[k2][qi] = on ? __uint_as_float(raw[1]) : 0.f;
+    }
+  }
+  if (__syncthreads_or(!ok)) return false;
+  if (threadIdx.x < 16) {
+    const int qi = threadIdx.x;
+    float M = -INFINITY;
+    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, sh.cf[k2][qi]);
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float den = 0.f;
+    for (int k2 = 0; k2 < nsplit; k2++) {
+      const float f = __builtin_amdgcn_exp2f(sh.cf[k2][qi] - Ms);
+      sh.cf[k2][qi] = f;
+      den += sh.cl[k2][qi] * f;
+    }
+    sh.cden[qi] = den;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+    const int qi = e >> 6, dim = e & 63;
+    const bool on = qi < R;
+    float num = 0.f;
+    for (int k0 = 0; k0 < nsplit; k0 += 8) {
+      unsigned raw[8];
+      const int n = min(8, nsplit - k0);
+      ok = pk_fetch<8>(raw, n, on, tag, [&](int i) { return base + (long)(k0 + i) * PK_PART + e; }, a, stage) && ok;
+#pragma unroll
+      for (int i = 0; i < 8; i++)
+        if (i < n) num += __uint_as_float(raw[i]) * sh.cf[k0 + i][qi];     // fixed order
+    }
+    const float den = sh.cden[qi];
+    const float v = den > 0.f ? num / den : 0.f;
+    const float w = __shfl_xor(v, 1, 64);
+    if (on && (dim & 1) == 0) pk_st(att + (long)qi * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
+  }
+  if (__syncthreads_or(!ok)) return false;
+  return true;
+}
+
+// ------------------------------------------------------------------------------------------
+// The kernel
+// ------------------------------------------------------------------------------------------
+#define PK_MINE(units) for (int u = (int)((blockIdx.x + PK_NWG - (rr % PK_NWG)) % PK_NWG); u < (units); u += PK_NWG)
+#define PK_NEXT(units) do { rr += (units); stage++; } while (0)
+
+__global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
+  if (*a.run_flag == 0) return;
+  __shared__ PkShared sh;
+  const int d = a.D.d, H = a.D.H, ff = a.ff;
+  const int wave = threadIdx.x >> 6;
+  unsigned rr = 0;     // round-robin origin of the current stage (same in every workgroup)
+  int stage = 0;
+
+  // ---- embedding: one unit per coordinate row -> hA of layer 0
+  PK_MINE(a.R[0]) {
+    const int r = u;
+    const bool onr = a.pos[0][r] >= 0;
+    const f16_t* e = a.emb + (long)a.vtok[r] * d;
+    for (int i = threadIdx.x; i < d; i += 256) pk_stf(a.hA + (long)r * d + i, onr ? (float)e[i] : 0.f, PK_TAG(a, 0));
+  }
+  PK_NEXT(a.R[0]);
+
+  for (int st = 0; st < 5; st++) {
+    for (int li = 0; li < a.count[st]; li++) {
+      const int l = a.first[st] + li;
+      const PkLayer& L = a.layers[l];
+      const int lev = L.level, R = a.R[lev];
+      const unsigned tag = PK_TAG(a, l);
+      const int* pos = a.pos[lev];
+      const int capb = a.capb[lev];
+      // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append)
+      PK_MINE(3 * d / 16) {
+        f32x4 c;
+        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, a.hA, tag, L.g1, R, c, stage)) return;
+        if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pos, a.cs[lev], capb);
+        __syncthreads();
+      }
+      PK_NEXT(3 * d / 16);
+      // ---- self-attention splits
+      {
+        const int ns = a.nsplit[lev];
+        int P0 = 0x3fffffff;
+        for (int r = 0; r < R; r++) if (pos[r] >= 0) P0 = min(P0, pos[r]);
+        PK_MINE(H * ns) {
+          const int hh = u / ns, sp = u % ns;
+          if (!pk_attn_unit(a, sh, a.q, pos, R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
+                            a.partS + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
+        }
+        PK_NEXT(H * ns);
+        PK_MINE(H) {
+          if (!pk_merge_unit(a, sh, pos, R, capb, ns, u, a.partS, a.att, tag, stage)) return;
+        }
+        PK_NEXT(H);
+      }
+      // ---- Wo + residual -> hB (tap: the layer input is what the draft heads of this level start from)
+      PK_MINE(d / 16) {
+        f32x4 c;
+        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, a.att, tag, nullptr, R, c, stage)) return;
+        if (wave == 0) {
+          float* tapr = L.tap ? a.tap[lev] : nullptr;
+          if (!pk_epi_residual(a, c, u, a.hA, tag, a.hB, tag, R, pos, tapr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8, stage)) {
+            // wave 0 failed alone: raise the abort word so that the other waves and workgroups leave too
+          }
+        }
+        __syncthreads();
+        if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+      }
+      PK_NEXT(d / 16);
+      // ---- cross-attention query (norm2 on the fly)
+      PK_MINE(d / 16) {
+        f32x4 c;
+        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, a.hB, tag, L.g2, R, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false);
+        __syncthreads();
+      }
+      PK_NEXT(d / 16);
+      // ---- cross-attention over the condition memory
+      {
+        const int ns = a.nsplitM;
+        PK_MINE(H * ns) {
+          const int hh = u / ns, sp = u % ns;
+          if (!pk_attn_unit(a, sh, a.q2, a.limx[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
+                            a.partX + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
+        }
+        PK_NEXT(H * ns);
+        PK_MINE(H) {
+          if (!pk_merge_unit(a, sh, a.limx[lev], R, a.capbM, ns, u, a.partX, a.att2, tag, stage)) return;
+        }
+        PK_NEXT(H);
+      }
+      // ---- cross output projection + residual -> hC
+      PK_MINE(d / 16) {
+        f32x4 c;
+        if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, a.att2, tag, nullptr, R, c, stage)) return;
+        if (wave == 0) pk_epi_residual(a, c, u, a.hB, tag, a.hC, tag, R, pos, nullptr, nullptr, 8, stage);
+        __syncthreads();
+        if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+      }
+      PK_NEXT(d / 16);
+      // ---- FFN up (norm3 on the fly, GELU)
+      PK_MINE(ff / 16) {
+        f32x4 c;
+        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, a.hC, tag, L.g3, R, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, u, a.mid, ff >> 1, tag, R, true);
+        __syncthreads();
+      }
+      PK_NEXT(ff / 16);
+      // ---- FFN down + residual -> next layer input, or the stack output (+ its ring for later passes)
+      PK_MINE(d / 16) {
+        f32x4 c;
+        if (!pk_gemm_tile<0>(a, sh, L.w2 + (long)u * (ff / 32) * 512, ff / 32, a.mid, tag, nullptr, R, c, stage)) return;
+        if (wave == 0) {
+          u64* dst = a.hA;
+          float* ring = nullptr;
+          int rs = 8;
+          if (L.last && st < 4) {
+            dst = a.hT[st];
+            ring = st == 0 ? a.ring_hc : st == 1 ? a.ring_hv : st == 2 ? a.ring_yf : a.ring_yv;
+            rs = st == 0 ? 32 : st == 2 ? 8 : 16;
+          }
+          pk_epi_residual(a, c, u, a.hC, tag, dst, PK_TAG(a, l + 1), R, pos, nullptr, ring, rs, stage);
+        }
+        __syncthreads();
+        if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+      }
+      PK_NEXT(d / 16);
+    }
+    // ---- level transition after stack st; everything it produces carries the tag of the next layer
+    const int ln = a.first[st] + a.count[st];
+    const unsigned tagn = PK_TAG(a, ln);
+    if (st == 0 || st == 1) {
+      // shorten: coarse slot k pools fine positions 3j-2..3j (this pass: stack output; older: ring; before the start: 0)
+      const int fl = st, cl = st + 1;
+      const float* ring = st == 0 ? a.ring_hc : a.ring_hv;
+      const int rs = st == 0 ? 32 : 16;
+      const int Rf_ = a.R[fl], Rc_ = a.R[cl];
+      int F0 = 0x3fffffff;   // first fine position of this pass
+      for (int r = 0; r < Rf_; r++) if (a.pos[fl][r] >= 0) F0 = min(F0, a.pos[fl][r]);
+      PK_MINE(Rc_) {
+        const int j = a.pos[cl][u];
+        bool ok = pk_wait_stack(a, a.hT[st], tagn, stage);
+        for (int i0 = 0; i0 < d; i0 += 512) {
+          const int i = i0 + 2 * threadIdx.x;       // two adjacent columns per thread
+          float s0 = 0.f, s1 = 0.f;
+          if (j >= 0 && i < d) {
+            for (int p = 3 * j - 2; p <= 3 * j; p++) {
+              if (p < 0) continue;
+              if (p >= F0) {
+                unsigned raw[2];
+                const u64* src = a.hT[st] + (long)(p - F0) * d + i;
+                ok = pk_fetch<2>(raw, 2, true, tagn, [&](int t) { return src + t; }, a, stage) && ok;
+                s0 += __uint_as_float(raw[0]); s1 += __uint_as_float(raw[1]);
+              } else {
+                s0 += ring[(long)(p & (rs - 1)) * d + i]; s1 += ring[(long)(p & (rs - 1)) * d + i + 1];
+              }
+            }
+          }
+          if (i < d) pk_st(a.pool + (long)u * (d >> 1) + (i >> 1), pk_pack(s0 / 3.0f, s1 / 3.0f), tagn);
+        }
+        if (__syncthreads_or(!ok)) return;
+      }
+      PK_NEXT(Rc_);
+      PK_MINE(d / 16) {
+        f32x4 c;
+        const f16_t* W = (st == 0 ? a.short_cv : a.short_vf) + (long)u * (d / 32) * 512;
+        if (!pk_gemm_tile<0>(a, sh, W, d / 32, a.pool, tagn, nullptr, Rc_, c, stage)) return;
+        if (wave == 0) {
+          const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
+#pragma unroll
+          for (int i = 0; i < 4; i++) if (g * 4 + i < Rc_) pk_stf(a.hA + (long)(g * 4 + i) * d + n, c[i], tagn);
+        }
+        __syncthreads();
+      }
+      PK_NEXT(d / 16);
+    } else if (st == 2 || st == 3) {
+      // upsample: fine row = skip (output of the level's first half) + coarse output of slot floor(pos/3)
+      const int fl = st == 2 ? 1 : 0, cl = fl + 1;
+      const u64* skip = a.hT[st == 2 ? 1 : 0];
+      const unsigned tag_skip = PK_TAG(a, a.first[st == 2 ? 1 : 0] + a.count[st == 2 ? 1 : 0]);
+      const float* ring = st == 2 ? a.ring_yf : a.ring_yv;
+      const int rs = st == 2 ? 8 : 16;
+      const int Rf_ = a.R[fl], Rc_ = a.R[cl];
+      PK_MINE(Rf_) {
+        const int p = a.pos[fl][u];
+        int slot = -1;
+        if (p >= 0) for (int r = 0; r < Rc_; r++) if (a.pos[cl][r] == p / 3) slot = r;
+        bool ok = pk_wait_stack(a, a.hT[st], tagn, stage);
+        for (int i = threadIdx.x; i < d; i += 256) {
+          unsigned r0[1], r1[1];
+          ok = pk_fetch<1>(r0, 1, true, tag_skip, [&](int) { return skip + (long)u * d + i; }, a, stage) && ok;
+          float v = __uint_as_float(r0[0]);
+          if (p >= 0) {
+            if (slot >= 0) {
+              ok = pk_fetch<1>(r1, 1, true, tagn, [&](int) { return a.hT[st] + (long)slot * d + i; }, a, stage) && ok;
+              v += __uint_as_float(r1[0]);
+            } else {
+              v += ring[(long)((p / 3) & (rs - 1)) * d + i];
+            }
+          }
+          pk_stf(a.hA + (long)u * d + i, v, tagn);
+        }
+        if (__syncthreads_or(!ok)) return;
+      }
+      PK_NEXT(Rf_);
+    }
+  }
+  // ---- output head: final norm on the fly, logits to plain memory (later launches read them)
+  {
+    const int l = a.n_layers, R = a.R[0];
+    const int NT = (a.D.V + 15) / 16;
+    PK_MINE(NT) {
+      f32x4 c;
+      if (!pk_gemm_tile<1>(a, sh, a.lm + (long)u * (d / 32) * 512, d / 32, a.hA, PK_TAG(a, l), a.gf, R, c, stage)) return;
+      if (wave == 0) {
+        const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+          if (g * 4 + i < R && n < a.D.V) a.logits[(long)(g * 4 + i) * a.D.V + n] = c[i];
+      }
+      __syncthreads();
+    }
+  }
+}
