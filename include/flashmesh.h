@@ -134,6 +134,11 @@ int fm_set_draft_replay(fm_ctx* ctx, const int32_t* stream_dev, int32_t stride, 
  * new budget that did not end with EOS become live again.  FM_EINVAL outside [1, max_tokens/9]. */
 int fm_set_budget(fm_ctx* ctx, int32_t max_faces);
 
+/* Stage timing of the persistent verify kernel (only when the context was created with the environment
+ * variable FM_PROFILE=1): HOST out[0] = earliest workgroup start, out[1 + s] = latest completion of stage s of
+ * the passes since the last call, in ticks of the 100 MHz wall clock; then re-arms.  Synchronises. */
+int fm_debug_profile(fm_ctx* ctx, uint64_t* host_out, int32_t n);
+
 /* HOST copy of one of the position-indexed carry rings, [batch][ring][d_model] float32; which: 0 coordinate
  * pre-stack outputs (32 entries), 1 vertex pre-stack outputs (16), 2 face outputs (8), 3 vertex outputs (16),
  * 4/5/6 tapped features of the coordinate (32) / vertex (16) / face (8) level.  Entry = position mod ring size.

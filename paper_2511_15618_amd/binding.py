@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
-           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes", "fm_debug_ring"]
+           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile"]
 
 
 class LibraryMissing(RuntimeError):
@@ -60,6 +60,7 @@ def load_library():
     lib.fm_set_budget.argtypes = [p, i32]
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_debug_ring.argtypes = [p, i32, p]
+    lib.fm_debug_profile.argtypes = [p, p, i32]
     for n in EXPORTS:
         if n not in ("fm_last_error", "fm_block_max", "fm_blob_elems"):
             getattr(lib, n).restype = C.c_int
@@ -173,6 +174,11 @@ class FlashMesh:
         size = (32, 16, 8, 16, 32, 16, 8)[which]
         out = np.zeros((self.batch, size, self.cfgs.d_model), np.float32)
         self._chk(self.lib.fm_debug_ring(self.h, which, C.c_void_p(out.ctypes.data)), "fm_debug_ring")
+        return out
+
+    def debug_profile(self, n: int = 1024) -> np.ndarray:
+        out = np.zeros(n, np.uint64)
+        self._chk(self.lib.fm_debug_profile(self.h, C.c_void_p(out.ctypes.data), n), "fm_debug_profile")
         return out
 
     def verify_bytes(self) -> float:

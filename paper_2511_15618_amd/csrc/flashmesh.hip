@@ -100,6 +100,7 @@ struct fm_ctx {
   bool persist;
   PkArgs pk;
   unsigned pk_epoch;
+  size_t pk_lds;           // dynamic LDS of the persistent kernel: the activation panel
   double weight_bytes;
 };
 
@@ -241,7 +242,7 @@ int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, f
     float* lgp = logits_out ? logits_out : c->logits;
     c->pk.logits = lgp;
     c->pk.epoch = ++c->pk_epoch;
-    hipLaunchKernelGGL(k_verify_persist, dim3(PK_NWG), dim3(256), 0, c->stream, c->pk);
+    hipLaunchKernelGGL(k_verify_persist, dim3(PK_NWG), dim3(256), c->pk_lds, c->stream, c->pk);
     hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, lgp, D.V, D.ban ? D.nbins : D.V, c->st.y);
     hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted);
     HIPCHK(c, hipGetLastError());
@@ -512,20 +513,33 @@ int build_persist(fm_ctx* c) {
   a.tap[0] = c->tap_c; a.tap[1] = c->tap_v; a.tap[2] = c->tap_f;
   a.emb = (const f16_t*)c->emb; a.short_cv = (const f16_t*)c->short_cv; a.short_vf = (const f16_t*)c->short_vf;
   a.lm = (const f16_t*)c->lm; a.gf = c->gf; a.logits = c->logits;
-  TRY(dalloc(c, &a.hA, 16 * d)); TRY(dalloc(c, &a.hB, 16 * d)); TRY(dalloc(c, &a.hC, 16 * d));
+  // panels that every workgroup reads are kept in PK_NREP copies (see fm_kernels_persist.h)
+  const size_t nl = hl.size();
+  // GEMM input panels: one region per layer, so that no address is written twice within a launch
+  TRY(dalloc(c, &a.hA, (nl + 1) * 16 * d)); TRY(dalloc(c, &a.hB, nl * 16 * d)); TRY(dalloc(c, &a.hC, nl * 16 * d));
   for (int i = 0; i < 4; i++) TRY(dalloc(c, &a.hT[i], 16 * d));
-  TRY(dalloc(c, &a.q, 8 * d)); TRY(dalloc(c, &a.att, 8 * d)); TRY(dalloc(c, &a.q2, 8 * d)); TRY(dalloc(c, &a.att2, 8 * d));
-  TRY(dalloc(c, &a.pool, 8 * d)); TRY(dalloc(c, &a.mid, (size_t)8 * c->ff));
+  TRY(dalloc(c, &a.q, 8 * d)); TRY(dalloc(c, &a.att, nl * 8 * d)); TRY(dalloc(c, &a.q2, 8 * d));
+  TRY(dalloc(c, &a.att2, nl * 8 * d));
+  TRY(dalloc(c, &a.pool, 2 * 8 * d)); TRY(dalloc(c, &a.mid, nl * 8 * c->ff));
   TRY(dalloc(c, &a.newK, (size_t)D.H * 16 * 32)); TRY(dalloc(c, &a.newV, (size_t)D.H * 16 * 32));
   TRY(dalloc(c, &a.partS, (size_t)D.H * PK_MAXSPLIT * PK_PART)); TRY(dalloc(c, &a.partX, (size_t)D.H * PK_MAXSPLIT * PK_PART));
+  TRY(dalloc(c, &a.w2part, (d / 16) * 3 * 256));
   TRY(dalloc(c, &a.abort_word, 16));
   if (hipMemset(a.abort_word + 1, 0xFF, 4) != hipSuccess) return fail(c, FM_EHIP, "hipMemset failed");
   a.run_flag = c->st.alive;
+  if (const char* e = getenv("FM_PROFILE")) {
+    if (e[0] == '1') TRY(dalloc(c, &a.prof, 1024));
+    if (const char* ps = getenv("FM_PROFILE_STAGE")) a.prof_stage = atoi(ps); else a.prof_stage = -1;
+  }
   c->pk_epoch = 0;
   // all 256 workgroups must be resident at once: they wait for each other's results
   int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist, 256, 0) != hipSuccess || (long)cus * per_cu < PK_NWG) {
+  // panel: R rows of the widest exchange row (fp32 d words, or half pairs of the FFN width), +4 words of padding each
+  c->pk_lds = (size_t)D.Bm * (std::max((size_t)d, (size_t)c->ff / 8) + 4) * 4;
+  if (c->pk_lds > 120 * 1024 ||
+      hipFuncSetAttribute((const void*)k_verify_persist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->pk_lds) != hipSuccess ||
+      hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist, 256, c->pk_lds) != hipSuccess || (long)cus * per_cu < PK_NWG) {
     (void)hipGetLastError();
     c->persist = false;   // fall back to the per-launch path
   }
@@ -642,7 +656,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   {
     const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
     const char* env = getenv("FM_PERSIST");
-    c->persist = c->bf16 && D.S == 1 && D.Bm <= 16 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 128 == 0 && nl < 62 &&
+    c->persist = c->bf16 && D.S == 1 && D.Bm <= 16 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
                  !(env && env[0] == '0');
   }
   int rc = build_params(c);
@@ -778,6 +792,17 @@ int fm_read_state(fm_ctx* c, int32_t* host_out) {
     host_out[s * 6 + 4] = fin[s];
     host_out[s * 6 + 5] = P[s];
   }
+  return FM_OK;
+}
+
+int fm_debug_profile(fm_ctx* c, uint64_t* host_out, int32_t n) {
+  if (!c || !host_out || n < 1 || n > 1024) return FM_EINVAL;
+  if (!c->persist || !c->pk.prof) return fail(c, FM_ESTATE, "stage profiling is off (FM_PROFILE=1 at fm_create, persistent path only)");
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(host_out, c->pk.prof, (size_t)n * 8, hipMemcpyDeviceToHost));
+  std::vector<unsigned long long> init(1024, 0ull);
+  init[0] = ~0ull;
+  HIPCHK(c, hipMemcpy(c->pk.prof, init.data(), 1024 * 8, hipMemcpyHostToDevice));   // re-arm
   return FM_OK;
 }
 

@@ -60,25 +60,26 @@ struct PkArgs {
   const float* gf;
   float* logits;
   // exchange buffers (u64 = payload | tag << 32)
-  u64 *hA, *hB, *hC;        // [16][d]
+  u64 *hA, *hB, *hC;        // [layers + 1][16][d]: one region per layer, written once per launch
   u64* hT[4];               // outputs of cpre, vpre, face, vpost  [16][d]
-  u64 *q, *att, *q2, *att2, *pool;   // [16][d/2]
-  u64* mid;                 // [16][ff/2]
+  u64 *q, *att, *q2, *att2, *pool;   // [16][d/2]; att, att2: [layers][16][d/2]; pool: [2][16][d/2]
+  u64* mid;                 // [layers][16][ff/2]
   u64 *newK, *newV;         // [H][16][32]
   u64 *partS, *partX;       // [H][PK_MAXSPLIT][PK_PART]
+  u64* w2part;              // [d/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
   unsigned epoch;
   unsigned* abort_word;     // [0] abort flag, [1] first failing stage (diagnostic)
   const int* run_flag;
+  int prof_stage;           // stage whose inner phases are timed into prof[600..]
+  u64* prof;                // optional [1 + stages]: earliest start, latest completion per stage (wall clock ticks)
 };
 
 struct PkShared {
   f32x4 red[4][64];
   float ssq[4][16];
+  float gain[1024];
   float lo[4][16][65];
   float lm[4][16], ll[4][16];
-  float cf[PK_MAXSPLIT][16];
-  float cl[PK_MAXSPLIT][16];
-  float cden[16];
 };
 
 __device__ __forceinline__ u64 pk_ld(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -86,6 +87,15 @@ __device__ __forceinline__ void pk_st(u64* p, unsigned payload, unsigned tag) {
   __hip_atomic_store(p, ((u64)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void pk_stf(u64* p, float v, unsigned tag) { pk_st(p, __float_as_uint(v), tag); }
+// Buffers that every workgroup reads in full (GEMM input panels) are kept in PK_NREP copies, `rs` elements
+// apart, and a reader takes copy blockIdx.x % PK_NREP: agent-scope loads bypass L2, so hundreds of
+// workgroups reading one 72 KB buffer would otherwise all queue on the same few memory channels.
+#define PK_NREP 1
+__device__ __forceinline__ void pk_st_r(u64* p, long rs, unsigned payload, unsigned tag) {
+#pragma unroll
+  for (int k = 0; k < PK_NREP; k++) pk_st(p + k * rs, payload, tag);
+}
+__device__ __forceinline__ void pk_stf_r(u64* p, long rs, float v, unsigned tag) { pk_st_r(p, rs, __float_as_uint(v), tag); }
 __device__ __forceinline__ unsigned pk_pack(float lo, float hi) {
   const f16_t a = (f16_t)lo, b = (f16_t)hi;
   return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
@@ -110,16 +120,31 @@ template <int N, class F>
 __device__ __forceinline__ bool pk_fetch(unsigned (&out)[N], int n, bool active, unsigned tag, F addr, const PkArgs& a, int stage) {
   const u64 t0 = wall_clock64();
   int it = 0;
+  // phase 1: watch one element per lane until it shows up (cheap while the producers are still far away)
+  if (N > 1) {
+    while (true) {
+      bool ok = true;
+      if (active && n > 0) ok = (unsigned)(pk_ld(addr(0)) >> 32) == tag;
+      if (__all(ok)) break;
+      if ((++it & 7) == 0 && pk_expired(a, t0, stage)) return false;
+      __builtin_amdgcn_s_sleep(4);
+    }
+  }
+  // phase 2: read everything, again until complete
   while (true) {
+    // all loads are issued back to back (the compiler keeps agent-scope loads in program order and would
+    // otherwise wait for each one before the next), only then are the tags looked at
+    u64 v[N];
+#pragma unroll
+    for (int i = 0; i < N; i++) {
+      v[i] = 0;
+      if (active && i < n) v[i] = pk_ld(addr(i));
+    }
     bool ok = true;
 #pragma unroll
     for (int i = 0; i < N; i++) {
-      out[i] = 0u;
-      if (active && i < n) {
-        const u64 v = pk_ld(addr(i));
-        out[i] = (unsigned)v;
-        ok = ok && ((unsigned)(v >> 32) == tag);
-      }
+      out[i] = (unsigned)v[i];
+      if (active && i < n) ok = ok && ((unsigned)(v[i] >> 32) == tag);
     }
     if (__all(ok)) return true;
     if ((++it & 3) == 0 && pk_expired(a, t0, stage)) {
@@ -151,92 +176,203 @@ __device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, un
   return pk_fetch<4>(s4, n, n > 0, tag, [&](int i) { return hT + threadIdx.x + 256 * i; }, a, stage);
 }
 
+// phase timing inside the units of one chosen stage (debug): latest time each phase was reached
+#define PK_MARK(k) do { if (a.prof && stage == a.prof_stage && threadIdx.x == 0) atomicMax(a.prof + 600 + (k), (u64)wall_clock64()); } while (0)
+
+// ------------------------------------------------------------------------------------------
+// Activation panel: the first R rows of a tagged exchange buffer (KE elements per row) are read by the whole
+// workgroup with coalesced 8-byte loads (re-read until every tag matches) and kept, payload only, in LDS
+// as [R][KE + 4] words (the +4 staggers the rows over the banks for the 16-byte fragment reads).
+// ------------------------------------------------------------------------------------------
+extern __shared__ unsigned pk_panel[];
+
+__device__ __forceinline__ bool pk_panel_load(const PkArgs& a, const u64* A, int lda, int R, int KE, unsigned tag, int stage) {
+  const int total = R * KE, ldp = KE + 4;
+  const u64 t0 = wall_clock64();
+  int it = 0;
+  bool good = true;
+  // phase 1: one cheap load per thread, spread over the columns of the LAST row (every producer tile owns
+  // 16 or 8 of them), until all of them show the tag
+  const int scol = KE >= 256 ? (int)((threadIdx.x * (unsigned)KE) >> 8) : (int)(threadIdx.x % KE);
+  const u64* sent = A + (long)(R - 1) * lda + scol;
+  if (a.prof && stage == a.prof_stage && threadIdx.x == 0) atomicMin(a.prof + 599, (u64)wall_clock64());
+  PK_MARK(0);
+  while (true) {
+    const bool ok = (unsigned)(pk_ld(sent) >> 32) == tag;
+    if (__all(ok)) break;
+    if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
+    __builtin_amdgcn_s_sleep(4);
+  }
+  // phase 2: everything, as 16-byte agent-scope loads (two tagged elements each; measured 5x the throughput
+  // of 8-byte ones), up to 32 per thread in flight.  The loads are inline asm, so the wait for them is
+  // explicit and every destination is passed through an empty asm afterwards to pin its uses behind the wait.
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  PK_MARK(1);
+  const int units = total >> 1;            // KE is even, rows are contiguous
+  for (int base = 0; good && base < units; base += 256 * 32) {
+    u32x4 v[32];
+    while (true) {
+#pragma unroll
+      for (int i = 0; i < 32; i++) {
+        const int idx = base + i * 256 + threadIdx.x;
+        v[i] = u32x4{0u, 0u, 0u, 0u};
+        if (idx < units) {
+          const int e = 2 * idx, row = e / KE;
+          const u64* p = A + (long)row * lda + (e - row * KE);
+          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[i]) : "v"(p) : "memory");
+        }
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      bool ok = true;
+#pragma unroll
+      for (int i = 0; i < 32; i++) {
+        asm volatile("" : "+v"(v[i]));
+        const int idx = base + i * 256 + threadIdx.x;
+        if (idx < units) ok = ok && v[i][1] == tag && v[i][3] == tag;
+      }
+      if (__all(ok)) break;
+      if ((++it & 3) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
+      __builtin_amdgcn_s_sleep(2);
+    }
+    if (good) {
+#pragma unroll
+      for (int i = 0; i < 32; i++) {
+        const int idx = base + i * 256 + threadIdx.x;
+        if (idx < units) {
+          const int e = 2 * idx, row = e / KE;
+          unsigned* dst = &pk_panel[row * ldp + (e - row * KE)];
+          dst[0] = v[i][0];
+          dst[1] = v[i][2];
+        }
+      }
+    }
+  }
+  return !__syncthreads_or(!good);
+}
+
 // ------------------------------------------------------------------------------------------
 // GEMM tile: C[16 rows x 16 cols] = A[16 x K] * W_tile^T, four waves split K, result in wave 0.
 // ASRC 0: A is a half-pair exchange buffer [16][K/2];  ASRC 1: A is an fp32 exchange buffer [16][K] that is
-// RMS-normalised (gain g) on the fly - K/128 <= 8 fragments per wave, i.e. K <= 1024.
+// RMS-normalised (gain g) on the fly (K/128 <= 8 fragments per wave, i.e. K <= 1024).
 // ------------------------------------------------------------------------------------------
 template <int ASRC>
 __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, const f16_t* Wt, int KT, const u64* A,
-                                             unsigned tagA, const float* gain, int R, f32x4& result, int stage) {
+                                             unsigned tagA, const float* gain, int R, f32x4& result, int stage,
+                                             int lda = 0) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 15, g = lane >> 4;
   const bool on = r < R;
   const int FW = KT >> 2;                  // fragments per wave (host guarantees KT % 4 == 0)
   const int K = KT * 32;
+  const int KE = ASRC == 1 ? K : (K >> 1), ldp = KE + 4;
   f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-  bool ok = true;
+  // weights of the first chunk go out before the wait for the activations: they depend on nothing
+  f16x8 wf[8];
+#pragma unroll
+  for (int f = 0; f < 8; f++)
+    if (f < FW) wf[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
+  float gcol[4] = {0.f, 0.f, 0.f, 0.f};     // gains of this thread's columns, requested before the wait
   if (ASRC == 1) {
-    // weights first (they do not depend on anything), then wait for the activations
-    f16x8 wf[8];
 #pragma unroll
-    for (int f = 0; f < 8; f++)
-      if (f < FW) wf[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
-    unsigned raw[64];
-    const u64* base = A + (long)r * K + (long)(wave * FW) * 32 + g * 8;
-    ok = pk_fetch<64>(raw, FW * 8, on, tagA, [&](int i) { return base + (i >> 3) * 32 + (i & 7); }, a, stage);
-    float ss = 0.f;
+    for (int j = 0; j < 4; j++)
+      if (j * 256 + (int)threadIdx.x < K) gcol[j] = gain[j * 256 + threadIdx.x];
+  }
+  if (!pk_panel_load(a, A, lda ? lda : KE, R, KE, tagA, stage)) return false;
+  PK_MARK(2);
+  if (ASRC == 1) {
+    {
+      // gains into LDS (requested before the wait), row sums of squares with 16 threads per row
 #pragma unroll
-    for (int i = 0; i < 64; i++) { const float v = __uint_as_float(raw[i]); ss += v * v; }
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
-    if (lane < 16) sh.ssq[wave][lane] = ss;
-    if (__syncthreads_or(!ok)) return false;
-    const float tot = sh.ssq[0][r] + sh.ssq[1][r] + sh.ssq[2][r] + sh.ssq[3][r];
-    const float inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+      for (int j = 0; j < 4; j++)
+        if (j * 256 + (int)threadIdx.x < K) sh.gain[j * 256 + threadIdx.x] = gcol[j];
+      const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
+      float ss = 0.f;
+      if (row < R) {
+#pragma unroll 4
+        for (int k = sub * 4; k < K; k += 64) {
+          const u32x4 x = *reinterpret_cast<const u32x4*>(&pk_panel[row * ldp + k]);
+#pragma unroll
+          for (int j = 0; j < 4; j++) { const float v = __uint_as_float(x[j]); ss += v * v; }
+        }
+      }
+      ss += __shfl_xor(ss, 1, 64); ss += __shfl_xor(ss, 2, 64); ss += __shfl_xor(ss, 4, 64); ss += __shfl_xor(ss, 8, 64);
+      if (sub == 0) sh.ssq[0][row] = ss;
+    }
+    __syncthreads();
+    const float inv = on ? 1.0f / sqrtf(sh.ssq[0][r] / (float)K + a.eps) : 0.f;
 #pragma unroll
     for (int f = 0; f < 8; f++) {
       if (f < FW) {
-        const float* gp = gain + (wave * FW + f) * 32 + g * 8;
+        const int k0 = (wave * FW + f) * 32 + g * 8;
         f16x8 av;
+        if (on) {
+          const u32x4 x0 = *reinterpret_cast<const u32x4*>(&pk_panel[r * ldp + k0]);
+          const u32x4 x1 = *reinterpret_cast<const u32x4*>(&pk_panel[r * ldp + k0 + 4]);
+          const f32x4 g0 = *reinterpret_cast<const f32x4*>(&sh.gain[k0]);
+          const f32x4 g1 = *reinterpret_cast<const f32x4*>(&sh.gain[k0 + 4]);
 #pragma unroll
-        for (int j = 0; j < 8; j++) av[j] = (f16_t)(__uint_as_float(raw[f * 8 + j]) * inv * gp[j]);
+          for (int j = 0; j < 4; j++) {
+            av[j] = (f16_t)(__uint_as_float(x0[j]) * inv * g0[j]);
+            av[4 + j] = (f16_t)(__uint_as_float(x1[j]) * inv * g1[j]);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; j++) av[j] = (f16_t)0.f;
+        }
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
       }
     }
   } else {
     for (int f0 = 0; f0 < FW; f0 += 8) {
-      f16x8 wf[8];
+      f16x8 wn[8];     // next chunk of weights is in flight while this one is multiplied
 #pragma unroll
       for (int f = 0; f < 8; f++)
-        if (f0 + f < FW) wf[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f0 + f) * 64 + lane) * 8);
-      unsigned raw[32];
-      const u64* base = A + (long)r * (K >> 1) + (long)(wave * FW + f0) * 16 + g * 4;
-      const int nf = min(8, FW - f0);
-      ok = ok && pk_fetch<32>(raw, nf * 4, on, tagA, [&](int i) { return base + (i >> 2) * 16 + (i & 3); }, a, stage);
+        if (f0 + 8 + f < FW) wn[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f0 + 8 + f) * 64 + lane) * 8);
 #pragma unroll
       for (int f = 0; f < 8; f++) {
-        if (f < nf) {
-          typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-          const u32x4 pk = u32x4{raw[f * 4], raw[f * 4 + 1], raw[f * 4 + 2], raw[f * 4 + 3]};
-          const f16x8 av = __builtin_bit_cast(f16x8, pk);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
+        if (f0 + f < FW) {
+          const int k0 = (wave * FW + f0 + f) * 32 + g * 8;
+          u32x4 pk = u32x4{0u, 0u, 0u, 0u};
+          if (on) pk = *reinterpret_cast<const u32x4*>(&pk_panel[r * ldp + (k0 >> 1)]);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, pk), wf[f], acc, 0, 0, 0);
         }
       }
+#pragma unroll
+      for (int f = 0; f < 8; f++) wf[f] = wn[f];
     }
   }
   sh.red[wave][lane] = acc;
-  if (__syncthreads_or(!ok)) return false;
+  __syncthreads();
+  PK_MARK(3);
   if (wave == 0) result = sh.red[0][lane] + sh.red[1][lane] + sh.red[2][lane] + sh.red[3][lane];
   return true;
 }
 
 // residual epilogue (wave 0): out[r][n] = old[r][n] + c; optional copies into position-indexed rings
-__device__ __forceinline__ bool pk_epi_residual(const PkArgs& a, const f32x4& c, int nt, const u64* hold, unsigned tag_old,
-                                                u64* hout, unsigned tag_out, int R, const int* pos, float* tap_ring,
-                                                float* out_ring, int ring_size, int stage) {
+// The residual operand of a tile (complete long before the tile's GEMM input is) is fetched by wave 0 at the
+// start of the unit, so that its latency hides behind the wait for the input panel.
+__device__ __forceinline__ bool pk_res_prefetch(const PkArgs& a, int nt, const u64* hold, unsigned tag_old, int R,
+                                                unsigned (&old)[4], int stage) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
-  unsigned old[4];
-  const bool ok = pk_fetch<4>(old, 4, true, tag_old, [&](int i) { return hold + (long)min(g * 4 + i, R - 1) * d + n; }, a, stage);
-  if (!ok) return false;
+  hold += (blockIdx.x & (PK_NREP - 1)) * 16L * d;
+  return pk_fetch<4>(old, 4, true, tag_old, [&](int i) { return hold + (long)min(g * 4 + i, R - 1) * d + n; }, a, stage);
+}
+
+__device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c, int nt, const unsigned (&old)[4],
+                                                u64* hout, unsigned tag_out, int R, const int* pos, float* tap_ring,
+                                                float* out_ring, int ring_size) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
+  const int d = a.D.d;
+  const long rs = 16L * d;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int r = g * 4 + i;
     if (r < R) {
       const float ho = __uint_as_float(old[i]);
       const float v = ho + c[i];
-      pk_stf(hout + (long)r * d + n, v, tag_out);
+      pk_stf_r(hout + (long)r * d + n, rs, v, tag_out);
       const int p = pos[r];
       if (p >= 0) {
         if (tap_ring) tap_ring[(long)(p & (ring_size - 1)) * d + n] = ho;
@@ -244,18 +380,20 @@ __device__ __forceinline__ bool pk_epi_residual(const PkArgs& a, const f32x4& c,
       }
     }
   }
-  return true;
 }
 
 // half-pair epilogue (wave 0): dst[r][n/2] = (c[n], c[n+1]) as halves, optional GELU
-__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu) {
+__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu, long rs) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const float v = gelu ? gelu_tanh_f(c[i]) : c[i];
     const float w = __shfl_xor(v, 1, 64);
     const int r = g * 4 + i;
-    if ((lane & 1) == 0 && r < R) pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag);
+    if ((lane & 1) == 0 && r < R) {
+      if (rs) pk_st_r(dst + (long)r * ld2 + (n >> 1), rs, pk_pack(v, w), tag);
+      else pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag);
+    }
   }
 }
 
@@ -322,9 +460,39 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   if (split >= nsplit) return true;      // nothing visible in this range: the merge knows the same count
   const int b0 = split * per, b1 = min(b0 + per, nblk);
 
-  unsigned qraw[8];
-  const u64* qp = qbuf + (long)ql * (d >> 1) + ((hh * 64 + g * 8) >> 1);
-  bool ok = pk_fetch<8>(qraw, 8, on, tag, [&](int i) { return qp + (i >> 2) * 16 + (i & 3); }, a, stage);
+  // The wave's query fragments and, if one of its blocks holds rows written by this pass, those rows, in ONE
+  // batch.  K fragment f = (hb, dh) holds key b*32 + hb*16 + lane%16, dims dh*32 + g*8..+8 (4 elements);
+  // V fragment dt holds dim dt*16 + lane%16 and the 8 slots g*8 + j <-> key b*32 + (j/4)*16 + g*4 + j%4.
+  int bov = -1;
+  if (overlay) {
+    const int cand[2] = {P0 >> 5, (P0 + R - 1) >> 5};
+#pragma unroll
+    for (int k = 0; k < 2; k++) {
+      const int b = cand[k];
+      if (b >= b0 + wave && b < b1 && ((b - b0 - wave) & 3) == 0) bov = b;
+    }
+  }
+  unsigned qraw[56];
+  const u64* qp = qbuf + (long)(on ? ql : 0) * (d >> 1) + ((hh * 64 + g * 8) >> 1);
+  bool ok = pk_fetch<56>(qraw, bov >= 0 ? 56 : 8, true, tag, [&](int ii) {
+    if (ii < 8) return qp + (ii >> 2) * 16 + (ii & 3);
+    const int i = ii - 8;
+    if (i < 16) {
+      const int f = i >> 2;
+      int nr = bov * 32 + (f >> 1) * 16 + (lane & 15) - P0;
+      nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
+      return (const u64*)(a.newK + ((long)hh * 16 + nr) * 32 + (((f & 1) * 32 + g * 8) >> 1) + (i & 3));
+    }
+    const int j = (i - 16) & 7, dt = (i - 16) >> 3;
+    int nr = bov * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+    nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
+    return (const u64*)(a.newV + ((long)hh * 16 + nr) * 32 + ((dt * 16 + (lane & 15)) >> 1));
+  }, a, stage);
+  if (!on) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) qraw[i] = 0u;
+  }
+  const unsigned* raw = qraw + 8;
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   const f16x8 qf0 = __builtin_bit_cast(f16x8, (u32x4{qraw[0], qraw[1], qraw[2], qraw[3]}));
   const f16x8 qf1 = __builtin_bit_cast(f16x8, (u32x4{qraw[4], qraw[5], qraw[6], qraw[7]}));
@@ -343,39 +511,21 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
     for (int f = 0; f < 4; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
 #pragma unroll
     for (int dt = 0; dt < 4; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
-    if (overlay && b * 32 + 31 >= P0) {
-      // rows written by this pass: K fragment f = (hb, dh) holds key b*32 + hb*16 + lane%16, dims dh*32 + g*8..+8
+    if (b == bov) {
 #pragma unroll
       for (int f = 0; f < 4; f++) {
-        const int key = b * 32 + (f >> 1) * 16 + (lane & 15);
-        const int nr = key - P0;
-        const bool fresh = nr >= 0 && nr < R;
-        unsigned raw[4];
-        const u64* np = a.newK + ((long)hh * 16 + (fresh ? nr : 0)) * 32 + (((f & 1) * 32 + g * 8) >> 1);
-        ok = ok && pk_fetch<4>(raw, 4, fresh, tag, [&](int i) { return np + i; }, a, stage);
-        if (fresh) kf[f] = __builtin_bit_cast(f16x8, (u32x4{raw[0], raw[1], raw[2], raw[3]}));
+        const int nr = b * 32 + (f >> 1) * 16 + (lane & 15) - P0;
+        if (nr >= 0 && nr < R) kf[f] = __builtin_bit_cast(f16x8, (u32x4{raw[f * 4], raw[f * 4 + 1], raw[f * 4 + 2], raw[f * 4 + 3]}));
       }
-      // V fragment dt holds dim dt*16 + lane%16 and the 8 slots g*8 + j <-> key b*32 + (j/4)*16 + g*4 + j%4
 #pragma unroll
       for (int dt = 0; dt < 4; dt++) {
         const int dim = dt * 16 + (lane & 15);
-        unsigned raw[8];
-        bool any = false;
-#pragma unroll
-        for (int j = 0; j < 8; j++) {
-          const int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
-          any = any || (nr >= 0 && nr < R);
-        }
-        ok = ok && pk_fetch<8>(raw, 8, any, tag, [&](int j) {
-          int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
-          nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
-          return a.newV + ((long)hh * 16 + nr) * 32 + (dim >> 1);
-        }, a, stage);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
           const int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
           if (nr >= 0 && nr < R) {
-            const unsigned short hbits = (dim & 1) ? (unsigned short)(raw[j] >> 16) : (unsigned short)(raw[j] & 0xFFFFu);
+            const unsigned w = raw[16 + dt * 8 + j];
+            const unsigned short hbits = (dim & 1) ? (unsigned short)(w >> 16) : (unsigned short)(w & 0xFFFFu);
             vf[dt][j] = __builtin_bit_cast(f16_t, hbits);
           }
         }
@@ -451,9 +601,10 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   return true;
 }
 
-// merge of the splits of one head into the half-pair attention output
+// merge of the splits of one head (one quarter of its dims per unit) into the half-pair attention output;
+// thread = (row, dim), splits summed in a fixed order
 __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, const int* limit, int R, int capb, int nsplit_cfg,
-                                              int hh, const u64* parts, u64* att, unsigned tag, int stage) {
+                                              int hh, int dq, const u64* parts, u64* att, unsigned tag, int stage) {
   const int d = a.D.d;
   int maxlim = -1;
   for (int r = 0; r < R; r++) maxlim = max(maxlim, limit[r]);
@@ -461,52 +612,39 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, con
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   const u64* base = parts + (long)hh * PK_MAXSPLIT * PK_PART;
+  const int qi = threadIdx.x >> 4, dim = dq * 16 + (threadIdx.x & 15);
+  const bool on = qi < R;
   bool ok = true;
-  // running maxima and sums: nsplit * R values each
-  for (int e0 = 0; e0 < nsplit * 16; e0 += 256) {
-    const int e = e0 + threadIdx.x;
-    const int k2 = e >> 4, qi = e & 15;
-    const bool on = k2 < nsplit && qi < R;
-    unsigned raw[2];
-    const u64* p = base + (long)(on ? k2 : 0) * PK_PART + 16 * 64 + qi;
-    ok = pk_fetch<2>(raw, 2, on, tag, [&](int i) { return p + i * 16; }, a, stage) && ok;
-    if (k2 < nsplit) {
-      sh.cf[k2][qi] = on ? __uint_as_float(raw[0]) : -INFINITY;
-      sh.cl[k2][qi] = on ? __uint_as_float(raw[1]) : 0.f;
-    }
-  }
-  if (__syncthreads_or(!ok)) return false;
-  if (threadIdx.x < 16) {
-    const int qi = threadIdx.x;
-    float M = -INFINITY;
-    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, sh.cf[k2][qi]);
-    const float Ms = M == -INFINITY ? 0.f : M;
-    float den = 0.f;
-    for (int k2 = 0; k2 < nsplit; k2++) {
-      const float f = __builtin_amdgcn_exp2f(sh.cf[k2][qi] - Ms);
-      sh.cf[k2][qi] = f;
-      den += sh.cl[k2][qi] * f;
-    }
-    sh.cden[qi] = den;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < 16 * 64; e += 256) {
-    const int qi = e >> 6, dim = e & 63;
-    const bool on = qi < R;
-    float num = 0.f;
-    for (int k0 = 0; k0 < nsplit; k0 += 8) {
-      unsigned raw[8];
-      const int n = min(8, nsplit - k0);
-      ok = pk_fetch<8>(raw, n, on, tag, [&](int i) { return base + (long)(k0 + i) * PK_PART + e; }, a, stage) && ok;
+  // splits are folded in a fixed order, 16 at a time, with the usual running-maximum rescale
+  float M = -INFINITY, num = 0.f, den = 0.f;
+  for (int k0 = 0; k0 < nsplit; k0 += 16) {
+    unsigned raw[48];
+    const int n = min(16, nsplit - k0);
+    ok = pk_fetch<48>(raw, 3 * n, on, tag, [&](int i) {
+      const u64* p = base + (long)(k0 + i / 3) * PK_PART;
+      const int w = i % 3;
+      return w == 0 ? p + 16 * 64 + qi : w == 1 ? p + 16 * 64 + 16 + qi : p + qi * 64 + dim;
+    }, a, stage) && ok;
+    float Mc = M;
 #pragma unroll
-      for (int i = 0; i < 8; i++)
-        if (i < n) num += __uint_as_float(raw[i]) * sh.cf[k0 + i][qi];     // fixed order
+    for (int i = 0; i < 16; i++) if (i < n && on) Mc = fmaxf(Mc, __uint_as_float(raw[3 * i]));
+    const float Ms = Mc == -INFINITY ? 0.f : Mc;
+    const float scale = __builtin_amdgcn_exp2f(M - Ms);     // exp2(-inf) = 0 for the first chunk
+    num *= scale;
+    den *= scale;
+    M = Mc;
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      if (i < n && on) {
+        const float f = __builtin_amdgcn_exp2f(__uint_as_float(raw[3 * i]) - Ms);
+        den += __uint_as_float(raw[3 * i + 1]) * f;
+        num += __uint_as_float(raw[3 * i + 2]) * f;
+      }
     }
-    const float den = sh.cden[qi];
-    const float v = den > 0.f ? num / den : 0.f;
-    const float w = __shfl_xor(v, 1, 64);
-    if (on && (dim & 1) == 0) pk_st(att + (long)qi * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
   }
+  const float v = den > 0.f ? num / den : 0.f;
+  const float w = __shfl_xor(v, 1, 64);
+  if (on && (dim & 1) == 0) pk_st_r(att + (long)qi * (d >> 1) + ((hh * 64 + dim) >> 1), 8L * d, pk_pack(v, w), tag);
   if (__syncthreads_or(!ok)) return false;
   return true;
 }
@@ -514,8 +652,14 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, con
 // ------------------------------------------------------------------------------------------
 // The kernel
 // ------------------------------------------------------------------------------------------
-#define PK_MINE(units) for (int u = (int)((blockIdx.x + PK_NWG - (rr % PK_NWG)) % PK_NWG); u < (units); u += PK_NWG)
-#define PK_NEXT(units) do { rr += (units); stage++; } while (0)
+#define PK_MINE(units) for (int u = (int)((blockIdx.x + PK_NWG - (rr % PK_NWG)) % PK_NWG); u < (units) && (worked = true); u += PK_NWG)
+#define PK_NEXT(units)                                                                              \
+  do {                                                                                              \
+    if (a.prof && worked && threadIdx.x == 0) atomicMax(a.prof + 1 + stage, (u64)wall_clock64());   \
+    worked = false;                                                                                 \
+    rr += (units);                                                                                  \
+    stage++;                                                                                        \
+  } while (0)
 
 __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   if (*a.run_flag == 0) return;
@@ -524,13 +668,17 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   const int wave = threadIdx.x >> 6;
   unsigned rr = 0;     // round-robin origin of the current stage (same in every workgroup)
   int stage = 0;
+  bool worked = false;
+  const long rep = blockIdx.x & (PK_NREP - 1);
+  const long rh = rep * 16L * d, rh2 = rep * 8L * d, rmid = rep * 8L * ff;   // this workgroup's copy of the panels
+  if (a.prof && threadIdx.x == 0) atomicMin(a.prof, (u64)wall_clock64());
 
   // ---- embedding: one unit per coordinate row -> hA of layer 0
   PK_MINE(a.R[0]) {
     const int r = u;
     const bool onr = a.pos[0][r] >= 0;
     const f16_t* e = a.emb + (long)a.vtok[r] * d;
-    for (int i = threadIdx.x; i < d; i += 256) pk_stf(a.hA + (long)r * d + i, onr ? (float)e[i] : 0.f, PK_TAG(a, 0));
+    for (int i = threadIdx.x; i < d; i += 256) pk_stf_r(a.hA + (long)r * d + i, 16L * d, onr ? (float)e[i] : 0.f, PK_TAG(a, 0));   // region of layer 0
   }
   PK_NEXT(a.R[0]);
 
@@ -542,10 +690,18 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       const unsigned tag = PK_TAG(a, l);
       const int* pos = a.pos[lev];
       const int capb = a.capb[lev];
+      // this layer's own regions of the panel buffers
+      u64* const hA_l = a.hA + (long)l * 16 * d;
+      u64* const hA_n = a.hA + (long)(l + 1) * 16 * d;
+      u64* const hB_l = a.hB + (long)l * 16 * d;
+      u64* const hC_l = a.hC + (long)l * 16 * d;
+      u64* const att_l = a.att + (long)l * 8 * d;
+      u64* const att2_l = a.att2 + (long)l * 8 * d;
+      u64* const mid_l = a.mid + (long)l * 8 * ff;
       // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append)
       PK_MINE(3 * d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, a.hA, tag, L.g1, R, c, stage)) return;
+        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, hA_l + rh, tag, L.g1, R, c, stage)) return;
         if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pos, a.cs[lev], capb);
         __syncthreads();
       }
@@ -561,30 +717,28 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
                             a.partS + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
         }
         PK_NEXT(H * ns);
-        PK_MINE(H) {
-          if (!pk_merge_unit(a, sh, pos, R, capb, ns, u, a.partS, a.att, tag, stage)) return;
+        PK_MINE(4 * H) {
+          if (!pk_merge_unit(a, sh, pos, R, capb, ns, u >> 2, u & 3, a.partS, att_l, tag, stage)) return;
         }
-        PK_NEXT(H);
+        PK_NEXT(4 * H);
       }
       // ---- Wo + residual -> hB (tap: the layer input is what the draft heads of this level start from)
       PK_MINE(d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, a.att, tag, nullptr, R, c, stage)) return;
-        if (wave == 0) {
-          float* tapr = L.tap ? a.tap[lev] : nullptr;
-          if (!pk_epi_residual(a, c, u, a.hA, tag, a.hB, tag, R, pos, tapr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8, stage)) {
-            // wave 0 failed alone: raise the abort word so that the other waves and workgroups leave too
-          }
-        }
-        __syncthreads();
-        if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+        unsigned old[4];
+        bool okr = true;
+        if (wave == 0) okr = pk_res_prefetch(a, u, hA_l, tag, R, old, stage);
+        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, att_l + rh2, tag, nullptr, R, c, stage)) return;
+        if (wave == 0 && okr)
+          pk_epi_residual(a, c, u, old, hB_l, tag, R, pos, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
+        if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16);
       // ---- cross-attention query (norm2 on the fly)
       PK_MINE(d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, a.hB, tag, L.g2, R, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false);
+        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, hB_l + rh, tag, L.g2, R, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false, 0);
         __syncthreads();
       }
       PK_NEXT(d / 16);
@@ -597,47 +751,71 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
                             a.partX + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
         }
         PK_NEXT(H * ns);
-        PK_MINE(H) {
-          if (!pk_merge_unit(a, sh, a.limx[lev], R, a.capbM, ns, u, a.partX, a.att2, tag, stage)) return;
+        PK_MINE(4 * H) {
+          if (!pk_merge_unit(a, sh, a.limx[lev], R, a.capbM, ns, u >> 2, u & 3, a.partX, att2_l, tag, stage)) return;
         }
-        PK_NEXT(H);
+        PK_NEXT(4 * H);
       }
       // ---- cross output projection + residual -> hC
       PK_MINE(d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, a.att2, tag, nullptr, R, c, stage)) return;
-        if (wave == 0) pk_epi_residual(a, c, u, a.hB, tag, a.hC, tag, R, pos, nullptr, nullptr, 8, stage);
-        __syncthreads();
-        if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+        unsigned old[4];
+        bool okr = true;
+        if (wave == 0) okr = pk_res_prefetch(a, u, hB_l, tag, R, old, stage);
+        if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, att2_l + rh2, tag, nullptr, R, c, stage)) return;
+        if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, tag, R, pos, nullptr, nullptr, 8);
+        if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16);
       // ---- FFN up (norm3 on the fly, GELU)
       PK_MINE(ff / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, a.hC, tag, L.g3, R, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, u, a.mid, ff >> 1, tag, R, true);
+        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, hC_l + rh, tag, L.g3, R, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, u, mid_l, ff >> 1, tag, R, true, 8L * ff);
         __syncthreads();
       }
       PK_NEXT(ff / 16);
-      // ---- FFN down + residual -> next layer input, or the stack output (+ its ring for later passes)
-      PK_MINE(d / 16) {
+      // ---- FFN down + residual -> next layer input, or the stack output (+ its ring for later passes).
+      // K = ff is four times longer than in the other GEMMs, so a tile is computed by four units, one per
+      // K-quarter; quarters 1..3 hand their partial tile to quarter 0, which adds them in a fixed order.
+      PK_MINE(4 * (d / 16)) {
+        const int nt = u >> 2, kq = u & 3;
+        const int KTq = ff / 128;                       // fragments of one K-quarter
         f32x4 c;
-        if (!pk_gemm_tile<0>(a, sh, L.w2 + (long)u * (ff / 32) * 512, ff / 32, a.mid, tag, nullptr, R, c, stage)) return;
+        unsigned old[4];
+        bool okr = true;
+        if (wave == 0 && kq == 0) okr = pk_res_prefetch(a, nt, hC_l, tag, R, old, stage);
+        if (!pk_gemm_tile<0>(a, sh, L.w2 + ((long)nt * (ff / 32) + (long)kq * KTq) * 512, KTq, mid_l + (long)kq * (ff / 8), tag,
+                             nullptr, R, c, stage, ff >> 1)) return;
         if (wave == 0) {
-          u64* dst = a.hA;
-          float* ring = nullptr;
-          int rs = 8;
-          if (L.last && st < 4) {
-            dst = a.hT[st];
-            ring = st == 0 ? a.ring_hc : st == 1 ? a.ring_hv : st == 2 ? a.ring_yf : a.ring_yv;
-            rs = st == 0 ? 32 : st == 2 ? 8 : 16;
+          const int lane = threadIdx.x & 63;
+          if (kq > 0) {
+#pragma unroll
+            for (int i = 0; i < 4; i++) pk_stf(a.w2part + ((long)nt * 3 + (kq - 1)) * 256 + i * 64 + lane, c[i], tag);
+          } else {
+            unsigned pr[12];
+            okr = pk_fetch<12>(pr, 12, true, tag, [&](int i) { return a.w2part + ((long)nt * 3 + (i >> 2)) * 256 + (i & 3) * 64 + lane; },
+                               a, stage) && okr;
+            if (okr) {
+#pragma unroll
+              for (int k = 0; k < 3; k++)
+#pragma unroll
+                for (int i = 0; i < 4; i++) c[i] += __uint_as_float(pr[k * 4 + i]);
+              u64* dst = hA_n;
+              float* ring = nullptr;
+              int rs = 8;
+              if (L.last && st < 4) {
+                dst = a.hT[st];
+                ring = st == 0 ? a.ring_hc : st == 1 ? a.ring_hv : st == 2 ? a.ring_yf : a.ring_yv;
+                rs = st == 0 ? 32 : st == 2 ? 8 : 16;
+              }
+              pk_epi_residual(a, c, nt, old, dst, PK_TAG(a, l + 1), R, pos, nullptr, ring, rs);
+            }
           }
-          pk_epi_residual(a, c, u, a.hC, tag, dst, PK_TAG(a, l + 1), R, pos, nullptr, ring, rs, stage);
         }
-        __syncthreads();
-        if (__hip_atomic_load(a.abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+        if (__syncthreads_or(!okr)) return;
       }
-      PK_NEXT(d / 16);
+      PK_NEXT(4 * (d / 16));
     }
     // ---- level transition after stack st; everything it produces carries the tag of the next layer
     const int ln = a.first[st] + a.count[st];
@@ -669,7 +847,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
               }
             }
           }
-          if (i < d) pk_st(a.pool + (long)u * (d >> 1) + (i >> 1), pk_pack(s0 / 3.0f, s1 / 3.0f), tagn);
+          if (i < d) pk_st_r(a.pool + (long)st * 8 * d + (long)u * (d >> 1) + (i >> 1), 8L * d, pk_pack(s0 / 3.0f, s1 / 3.0f), tagn);
         }
         if (__syncthreads_or(!ok)) return;
       }
@@ -677,11 +855,11 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       PK_MINE(d / 16) {
         f32x4 c;
         const f16_t* W = (st == 0 ? a.short_cv : a.short_vf) + (long)u * (d / 32) * 512;
-        if (!pk_gemm_tile<0>(a, sh, W, d / 32, a.pool, tagn, nullptr, Rc_, c, stage)) return;
+        if (!pk_gemm_tile<0>(a, sh, W, d / 32, a.pool + (long)st * 8 * d + rh2, tagn, nullptr, Rc_, c, stage)) return;
         if (wave == 0) {
           const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll
-          for (int i = 0; i < 4; i++) if (g * 4 + i < Rc_) pk_stf(a.hA + (long)(g * 4 + i) * d + n, c[i], tagn);
+          for (int i = 0; i < 4; i++) if (g * 4 + i < Rc_) pk_stf_r(a.hA + (long)ln * 16 * d + (long)(g * 4 + i) * d + n, 16L * d, c[i], tagn);
         }
         __syncthreads();
       }
@@ -711,7 +889,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
               v += ring[(long)((p / 3) & (rs - 1)) * d + i];
             }
           }
-          pk_stf(a.hA + (long)u * d + i, v, tagn);
+          pk_stf_r(a.hA + (long)ln * 16 * d + (long)u * d + i, 16L * d, v, tagn);
         }
         if (__syncthreads_or(!ok)) return;
       }
@@ -724,7 +902,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const int NT = (a.D.V + 15) / 16;
     PK_MINE(NT) {
       f32x4 c;
-      if (!pk_gemm_tile<1>(a, sh, a.lm + (long)u * (d / 32) * 512, d / 32, a.hA, PK_TAG(a, l), a.gf, R, c, stage)) return;
+      if (!pk_gemm_tile<1>(a, sh, a.lm + (long)u * (d / 32) * 512, d / 32, a.hA + (long)l * 16 * d + rh, PK_TAG(a, l), a.gf, R, c, stage)) return;
       if (wave == 0) {
         const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll
