@@ -158,6 +158,11 @@ def main():
     torch.cuda.synchronize()
     ms_verify = ev0.elapsed_time(ev1) / iters
     achieved = bytes_mid / (ms_verify * 1e-3) / 1e9
+    if fm.verify_path() == 1:
+        kernel = ("k_verify_persist (whole backbone forward of the block in one launch) at half context; the timed "
+                  "region is fm_verify_block = that kernel plus the block set-up, row argmax and accept kernels")
+    else:
+        kernel = "verify pass at half context (all launches of fm_verify_block, one per operator)"
 
     result = {
         "metric": "mesh tokens/sec, batch 1 (replay drafts p=0.93, all heads executed)",
@@ -180,7 +185,7 @@ def main():
                    "native_heads_ms_per_step": st_native.ms_total / max(st_native.steps, 1),
                    "sequential_tokens_per_s": st_seq.tokens / st_seq.ms_total * 1e3,
                    "sequential_prefix_faces": seq_faces, "host_wall_s": wall},
-        "roofline": {"bound": "hbm", "kernel": "verify pass at half context (all launches of fm_verify_block)",
+        "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "algorithmic_bytes": bytes_mid, "ms": ms_verify},
     }

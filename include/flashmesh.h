@@ -145,6 +145,10 @@ int fm_debug_profile(fm_ctx* ctx, uint64_t* host_out, int32_t n);
  * Synchronises. */
 int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
 
+/* Which implementation fm_verify_block runs for this context: 1 = the single persistent kernel (half-precision
+ * storage, one sequence, block <= 16), 0 = one launch per operator.  Both compute the same values. */
+int32_t fm_verify_path(const fm_ctx* ctx);
+
 /* Algorithmic HBM bytes of one verify pass at the current committed lengths (weights once, self
  * and cross K/V once per block and sequence), for roofline reporting.  Synchronises. */
 int fm_verify_bytes(fm_ctx* ctx, double* host_bytes);

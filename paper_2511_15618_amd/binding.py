@@ -11,7 +11,8 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
-           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile"]
+           "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile",
+           "fm_verify_path"]
 
 
 class LibraryMissing(RuntimeError):
@@ -61,8 +62,10 @@ def load_library():
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_debug_ring.argtypes = [p, i32, p]
     lib.fm_debug_profile.argtypes = [p, p, i32]
+    lib.fm_verify_path.argtypes = [p]
+    lib.fm_verify_path.restype = i32
     for n in EXPORTS:
-        if n not in ("fm_last_error", "fm_block_max", "fm_blob_elems"):
+        if n not in ("fm_last_error", "fm_block_max", "fm_blob_elems", "fm_verify_path"):
             getattr(lib, n).restype = C.c_int
     _lib = lib
     return lib
@@ -180,6 +183,9 @@ class FlashMesh:
         out = np.zeros(n, np.uint64)
         self._chk(self.lib.fm_debug_profile(self.h, C.c_void_p(out.ctypes.data), n), "fm_debug_profile")
         return out
+
+    def verify_path(self) -> int:
+        return int(self.lib.fm_verify_path(self.h))
 
     def verify_bytes(self) -> float:
         v = C.c_double()

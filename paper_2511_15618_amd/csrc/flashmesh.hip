@@ -694,6 +694,7 @@ int fm_destroy(fm_ctx* c) {
 
 const char* fm_last_error(const fm_ctx* c) { return c ? c->err.c_str() : "null context"; }
 int32_t fm_block_max(const fm_ctx* c) { return c ? c->D.Bm : FM_EINVAL; }
+int32_t fm_verify_path(const fm_ctx* c) { return c ? (c->persist ? 1 : 0) : FM_EINVAL; }
 int64_t fm_blob_elems(const fm_ctx* c) { return c ? (int64_t)c->blob_elems : FM_EINVAL; }
 
 int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
