@@ -213,7 +213,7 @@ def main():
         kernel = "verify pass at half context (all launches of fm_verify_block, one per operator)"
 
     result = {
-        "metric": "mesh tokens/sec, batch 1 (replay drafts p=0.93, all heads executed)",
+        "metric": f"mesh tokens/sec, batch {cfg.batch} (replay drafts p={REPLAY_P}, all heads executed)",
         "value": tokens / ms * 1e3,
         "unit": "tokens/s",
         "n_gpus": 1,

@@ -31,11 +31,6 @@ __device__ __forceinline__ float ld_agent(const float* p) {
 }
 __device__ __forceinline__ void publish_fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 
-#ifndef FM_XCHG_TEST
-#define FM_XCHG_TEST 0
-#endif
-static constexpr bool g_xchg_test = FM_XCHG_TEST != 0;   // experiment: publish split-K partials with returning atomics
-static constexpr bool g_xchg_host = FM_XCHG_TEST != 0;
 #define FM_GEMM_WS_FLOATS (48u << 20)   // split-K partials (192 MiB)
 #define FM_GEMM_COUNTERS 65536
 #define FM_ATTN_MAX_SPLIT 64
@@ -181,15 +176,8 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
 #pragma unroll
       for (int w = 1; w < 4; w++) v += red[w][mt][lane];
       float* p = sp.ws + ((tile * sp.ksplit + ks) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
-      if (g_xchg_test) {
-        float dummy = 0.f;
-        for (int i = 0; i < 4; i++) dummy += __hip_atomic_exchange(p + i * 16, v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (dummy == 1.2345e30f) sp.ws[0] = dummy;
-      } else {
-        for (int i = 0; i < 4; i++) st_agent(p + i * 16, v[i]);
-      }
+      for (int i = 0; i < 4; i++) st_agent(p + i * 16, v[i]);
     }
-    if (g_xchg_test) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup"); else
     publish_fence();
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -260,16 +248,7 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
   // The four waves of a workgroup split K; K is NOT split across workgroups (the kernel supports it, but
   // the publication fence it needs costs more than the extra parallelism gains at these sizes).
-  int kt_per_wave = (KT + 3) / 4, ksplit = 1;
-  if (g_xchg_host && nmb == 1) {
-    const long base_wgs = (long)NT * groups;
-    while (base_wgs * ksplit < 256 && kt_per_wave > 2 && kt_per_wave % 2 == 0 && ksplit < 16) { kt_per_wave /= 2; ksplit *= 2; }
-  }
-  const long tiles = (long)NT * groups * nmb;
-  if (ksplit > 1 && (tiles > FM_GEMM_COUNTERS || tiles * ksplit * MT * 256 > (long)FM_GEMM_WS_FLOATS)) {
-    ksplit = 1;
-    kt_per_wave = (KT + 3) / 4;
-  }
+  const int kt_per_wave = (KT + 3) / 4, ksplit = 1;
   GemmSplit sp{kt_per_wave, ksplit, res.gemm_ws, res.gemm_counters, Npad};
   dim3 grid(NT, ksplit, groups * nmb);
   switch (MT) {

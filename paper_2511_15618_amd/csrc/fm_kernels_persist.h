@@ -62,13 +62,16 @@ struct PkArgs {
   // exchange buffers (u64 = payload | tag << 32)
   u64 *hA, *hB, *hC;        // [layers + 1][16][d]: one region per layer, written once per launch
   u64* hT[4];               // outputs of cpre, vpre, face, vpost  [16][d]
-  u64 *q, *att, *q2, *att2, *pool;   // [16][d/2]; att, att2: [layers][16][d/2]; pool: [2][16][d/2]
+  u64 *q, *q2;              // [16][d/2] rotated queries of the self- / cross-attention (half pairs)
+  u64 *att, *att2;          // [layers][16][d/2] attention outputs
+  u64* pool;                // [2][16][d/2] pooled groups before the two shortening projections
   u64* mid;                 // [layers][16][ff/2]
   u64 *newK, *newV;         // [H][16][32]
   u64 *partS, *partX;       // [H][PK_MAXSPLIT][PK_PART]
   u64* w2part;              // [d/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
   unsigned epoch;
-  unsigned* abort_word;     // [0] abort flag, [1] first failing stage (diagnostic)
+  unsigned* abort_word;     // [0] abort flag, [1] earliest stage that gave up, [2] claim, [3..8] expected tag, tag seen,
+                            // stage, workgroup, thread, element of the first missing value
   const int* run_flag;
   int prof_stage;           // stage whose inner phases are timed into prof[600..]
   u64* prof;                // optional [1 + stages]: earliest start, latest completion per stage (wall clock ticks)
@@ -87,15 +90,6 @@ __device__ __forceinline__ void pk_st(u64* p, unsigned payload, unsigned tag) {
   __hip_atomic_store(p, ((u64)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void pk_stf(u64* p, float v, unsigned tag) { pk_st(p, __float_as_uint(v), tag); }
-// Buffers that every workgroup reads in full (GEMM input panels) are kept in PK_NREP copies, `rs` elements
-// apart, and a reader takes copy blockIdx.x % PK_NREP: agent-scope loads bypass L2, so hundreds of
-// workgroups reading one 72 KB buffer would otherwise all queue on the same few memory channels.
-#define PK_NREP 1
-__device__ __forceinline__ void pk_st_r(u64* p, long rs, unsigned payload, unsigned tag) {
-#pragma unroll
-  for (int k = 0; k < PK_NREP; k++) pk_st(p + k * rs, payload, tag);
-}
-__device__ __forceinline__ void pk_stf_r(u64* p, long rs, float v, unsigned tag) { pk_st_r(p, rs, __float_as_uint(v), tag); }
 __device__ __forceinline__ unsigned pk_pack(float lo, float hi) {
   const f16_t a = (f16_t)lo, b = (f16_t)hi;
   return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
@@ -356,7 +350,6 @@ __device__ __forceinline__ bool pk_res_prefetch(const PkArgs& a, int nt, const u
                                                 unsigned (&old)[4], int stage) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
-  hold += (blockIdx.x & (PK_NREP - 1)) * 16L * d;
   return pk_fetch<4>(old, 4, true, tag_old, [&](int i) { return hold + (long)min(g * 4 + i, R - 1) * d + n; }, a, stage);
 }
 
@@ -365,14 +358,13 @@ __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c,
                                                 float* out_ring, int ring_size) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
-  const long rs = 16L * d;
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int r = g * 4 + i;
     if (r < R) {
       const float ho = __uint_as_float(old[i]);
       const float v = ho + c[i];
-      pk_stf_r(hout + (long)r * d + n, rs, v, tag_out);
+      pk_stf(hout + (long)r * d + n, v, tag_out);
       const int p = pos[r];
       if (p >= 0) {
         if (tap_ring) tap_ring[(long)(p & (ring_size - 1)) * d + n] = ho;
@@ -383,7 +375,7 @@ __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c,
 }
 
 // half-pair epilogue (wave 0): dst[r][n/2] = (c[n], c[n+1]) as halves, optional GELU
-__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu, long rs) {
+__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
 #pragma unroll
   for (int i = 0; i < 4; i++) {
@@ -391,8 +383,7 @@ __device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, in
     const float w = __shfl_xor(v, 1, 64);
     const int r = g * 4 + i;
     if ((lane & 1) == 0 && r < R) {
-      if (rs) pk_st_r(dst + (long)r * ld2 + (n >> 1), rs, pk_pack(v, w), tag);
-      else pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag);
+      pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag);
     }
   }
 }
@@ -644,7 +635,7 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, con
   }
   const float v = den > 0.f ? num / den : 0.f;
   const float w = __shfl_xor(v, 1, 64);
-  if (on && (dim & 1) == 0) pk_st_r(att + (long)qi * (d >> 1) + ((hh * 64 + dim) >> 1), 8L * d, pk_pack(v, w), tag);
+  if (on && (dim & 1) == 0) pk_st(att + (long)qi * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
   if (__syncthreads_or(!ok)) return false;
   return true;
 }
@@ -669,8 +660,6 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   unsigned rr = 0;     // round-robin origin of the current stage (same in every workgroup)
   int stage = 0;
   bool worked = false;
-  const long rep = blockIdx.x & (PK_NREP - 1);
-  const long rh = rep * 16L * d, rh2 = rep * 8L * d, rmid = rep * 8L * ff;   // this workgroup's copy of the panels
   if (a.prof && threadIdx.x == 0) atomicMin(a.prof, (u64)wall_clock64());
 
   // ---- embedding: one unit per coordinate row -> hA of layer 0
@@ -678,7 +667,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const int r = u;
     const bool onr = a.pos[0][r] >= 0;
     const f16_t* e = a.emb + (long)a.vtok[r] * d;
-    for (int i = threadIdx.x; i < d; i += 256) pk_stf_r(a.hA + (long)r * d + i, 16L * d, onr ? (float)e[i] : 0.f, PK_TAG(a, 0));   // region of layer 0
+    for (int i = threadIdx.x; i < d; i += 256) pk_stf(a.hA + (long)r * d + i, onr ? (float)e[i] : 0.f, PK_TAG(a, 0));   // region of layer 0
   }
   PK_NEXT(a.R[0]);
 
@@ -701,7 +690,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append)
       PK_MINE(3 * d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, hA_l + rh, tag, L.g1, R, c, stage)) return;
+        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, hA_l, tag, L.g1, R, c, stage)) return;
         if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pos, a.cs[lev], capb);
         __syncthreads();
       }
@@ -728,7 +717,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         unsigned old[4];
         bool okr = true;
         if (wave == 0) okr = pk_res_prefetch(a, u, hA_l, tag, R, old, stage);
-        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, att_l + rh2, tag, nullptr, R, c, stage)) return;
+        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, att_l, tag, nullptr, R, c, stage)) return;
         if (wave == 0 && okr)
           pk_epi_residual(a, c, u, old, hB_l, tag, R, pos, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
         if (__syncthreads_or(!okr)) return;
@@ -737,8 +726,8 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // ---- cross-attention query (norm2 on the fly)
       PK_MINE(d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, hB_l + rh, tag, L.g2, R, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false, 0);
+        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, hB_l, tag, L.g2, R, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false);
         __syncthreads();
       }
       PK_NEXT(d / 16);
@@ -762,7 +751,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         unsigned old[4];
         bool okr = true;
         if (wave == 0) okr = pk_res_prefetch(a, u, hB_l, tag, R, old, stage);
-        if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, att2_l + rh2, tag, nullptr, R, c, stage)) return;
+        if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, att2_l, tag, nullptr, R, c, stage)) return;
         if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, tag, R, pos, nullptr, nullptr, 8);
         if (__syncthreads_or(!okr)) return;
       }
@@ -770,8 +759,8 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // ---- FFN up (norm3 on the fly, GELU)
       PK_MINE(ff / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, hC_l + rh, tag, L.g3, R, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, u, mid_l, ff >> 1, tag, R, true, 8L * ff);
+        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, hC_l, tag, L.g3, R, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, u, mid_l, ff >> 1, tag, R, true);
         __syncthreads();
       }
       PK_NEXT(ff / 16);
@@ -847,7 +836,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
               }
             }
           }
-          if (i < d) pk_st_r(a.pool + (long)st * 8 * d + (long)u * (d >> 1) + (i >> 1), 8L * d, pk_pack(s0 / 3.0f, s1 / 3.0f), tagn);
+          if (i < d) pk_st(a.pool + (long)st * 8 * d + (long)u * (d >> 1) + (i >> 1), pk_pack(s0 / 3.0f, s1 / 3.0f), tagn);
         }
         if (__syncthreads_or(!ok)) return;
       }
@@ -855,11 +844,11 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       PK_MINE(d / 16) {
         f32x4 c;
         const f16_t* W = (st == 0 ? a.short_cv : a.short_vf) + (long)u * (d / 32) * 512;
-        if (!pk_gemm_tile<0>(a, sh, W, d / 32, a.pool + (long)st * 8 * d + rh2, tagn, nullptr, Rc_, c, stage)) return;
+        if (!pk_gemm_tile<0>(a, sh, W, d / 32, a.pool + (long)st * 8 * d, tagn, nullptr, Rc_, c, stage)) return;
         if (wave == 0) {
           const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll
-          for (int i = 0; i < 4; i++) if (g * 4 + i < Rc_) pk_stf_r(a.hA + (long)ln * 16 * d + (long)(g * 4 + i) * d + n, 16L * d, c[i], tagn);
+          for (int i = 0; i < 4; i++) if (g * 4 + i < Rc_) pk_stf(a.hA + (long)ln * 16 * d + (long)(g * 4 + i) * d + n, c[i], tagn);
         }
         __syncthreads();
       }
@@ -889,7 +878,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
               v += ring[(long)((p / 3) & (rs - 1)) * d + i];
             }
           }
-          pk_stf_r(a.hA + (long)ln * 16 * d + (long)u * d + i, 16L * d, v, tagn);
+          pk_stf(a.hA + (long)ln * 16 * d + (long)u * d + i, v, tagn);
         }
         if (__syncthreads_or(!ok)) return;
       }
@@ -902,7 +891,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const int NT = (a.D.V + 15) / 16;
     PK_MINE(NT) {
       f32x4 c;
-      if (!pk_gemm_tile<1>(a, sh, a.lm + (long)u * (d / 32) * 512, d / 32, a.hA + (long)l * 16 * d + rh, PK_TAG(a, l), a.gf, R, c, stage)) return;
+      if (!pk_gemm_tile<1>(a, sh, a.lm + (long)u * (d / 32) * 512, d / 32, a.hA + (long)l * 16 * d, PK_TAG(a, l), a.gf, R, c, stage)) return;
       if (wave == 0) {
         const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll

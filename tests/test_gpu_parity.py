@@ -1,4 +1,6 @@
 """GPU parity: the HIP path through the C-ABI against the CPU oracle, step by step."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -51,3 +53,27 @@ def test_config0_tiny_full_run():
     rep, streams, fm = lockstep(cfg, cfg.faces, TOL["f32"])
     print(rep, flush=True)
     assert len(streams[0]) == 90
+
+
+def test_config3_shape_short_lockstep():
+    """configs[3] at its real widths (d=1024, 40 blocks, 8 sequences with ragged progress) for a few steps of
+    lock-step decoding: draft blocks, logits, greedy tokens, accepted and committed lengths."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.CONFIGS[3].replace(faces=40)
+    print("case config3 short", flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL["bf16"], max_steps=5)
+    print(rep, flush=True)
+    assert rep.steps == 5 and len(rep.accepted) == 5 * cfg.batch
+
+
+@pytest.mark.skipif(os.environ.get("FM_LONG") != "1", reason="tens of GB of host memory and minutes of CPU oracle time; set FM_LONG=1")
+def test_config4_shape_short_lockstep():
+    """configs[4] at its real widths (d=1536, 48 blocks, 4 sequences, block 18) for a few lock-step steps."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.CONFIGS[4].replace(faces=40)
+    print("case config4 short", flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL["bf16"], max_steps=4)
+    print(rep, flush=True)
+    assert rep.steps == 4 and len(rep.accepted) == 4 * cfg.batch
