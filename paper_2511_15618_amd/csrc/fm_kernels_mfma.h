@@ -264,19 +264,101 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
 // ------------------------------------------------------------------------------------------
 // Attention
 // ------------------------------------------------------------------------------------------
+// Merge of the split-KV partials of one (sequence, head) by one workgroup, splits in ascending order.
+// AGENT: the partials were written by other workgroups of the SAME launch (agent-scope loads; the compiler
+// keeps those in program order, so each batch is requested in full before its first value is used);
+// otherwise they come from an earlier launch and plain loads do.
+template <int QT>
+struct AttnMergeShared {
+  float cf[FM_ATTN_MAX_SPLIT][QT * 16], cl[FM_ATTN_MAX_SPLIT][QT * 16], cden[QT * 16];
+};
+
+template <int QT, bool AGENT>
+__device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float* base, int nsplit, int RPS, f16_t* orow0, int d) {
+  constexpr int NQ = QT * 16;
+  constexpr int PSZ = NQ * 64 + 2 * NQ;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  for (int e0 = 0; e0 < nsplit * NQ; e0 += 256 * 4) {
+    float tm[4], tl[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int e = e0 + j * 256 + threadIdx.x;
+      tm[j] = tl[j] = 0.f;
+      if (e < nsplit * NQ) {
+        const float* pp = base + (long)(e / NQ) * PSZ + NQ * 64 + (e % NQ);
+        tm[j] = AGENT ? ld_agent(pp) : *pp;
+        tl[j] = AGENT ? ld_agent(pp + NQ) : pp[NQ];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+      const int e = e0 + j * 256 + threadIdx.x;
+      if (e < nsplit * NQ) { ms.cf[e / NQ][e % NQ] = tm[j]; ms.cl[e / NQ][e % NQ] = tl[j]; }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < NQ) {
+    const int qi = threadIdx.x;
+    float M = -INFINITY;
+    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, ms.cf[k2][qi]);
+    const float Ms = M == -INFINITY ? 0.f : M;
+    float den = 0.f;
+    for (int k2 = 0; k2 < nsplit; k2++) {
+      const float f = __builtin_amdgcn_exp2f(ms.cf[k2][qi] - Ms);
+      ms.cf[k2][qi] = f;
+      den += ms.cl[k2][qi] * f;
+    }
+    ms.cden[qi] = den;
+  }
+  __syncthreads();
+  // numerators: 16-byte loads (four dims of one query row), eight splits in flight per thread
+  for (int v4 = threadIdx.x; v4 < NQ * 16; v4 += 256) {
+    const int e = v4 * 4, qi = e >> 6, dim = e & 63;
+    float num[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < nsplit; c0 += 8) {
+      u32x4 v[8];
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        v[j] = u32x4{0u, 0u, 0u, 0u};
+        if (c0 + j < nsplit) {
+          const float* pp = base + (long)(c0 + j) * PSZ + e;
+          if (AGENT) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[j]) : "v"(pp) : "memory");
+          else v[j] = *reinterpret_cast<const u32x4*>(pp);
+        }
+      }
+      if (AGENT) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < 8; j++) {
+        if (AGENT) asm volatile("" : "+v"(v[j]));
+        if (c0 + j < nsplit) {
+          const float f = ms.cf[c0 + j][qi];
+#pragma unroll
+          for (int i = 0; i < 4; i++) num[i] += __uint_as_float(v[j][i]) * f;
+        }
+      }
+    }
+    if (qi < RPS) {
+      const float den = ms.cden[qi];
+      f16_t* op = orow0 + (long)qi * d + dim;
+#pragma unroll
+      for (int i = 0; i < 4; i++) op[i] = (f16_t)(den > 0.f ? num[i] / den : 0.f);
+    }
+  }
+}
+
 // Workspace per (sequence, head): [nsplit][QT*16*64 unnormalised O | QT*16 running max (log2 units) | QT*16 sums]
 template <int QT>
 __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS,
                                                     const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
                                                     long seq_stride, int capb, f16_t* __restrict__ out, int H,
                                                     float* __restrict__ ws, unsigned* __restrict__ counters,
-                                                    const int* run_flag) {
+                                                    int defer_merge, const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
   constexpr int NQ = QT * 16;
   constexpr int PSZ = NQ * 64 + 2 * NQ;
   __shared__ float lo[4][NQ][65];
   __shared__ float lm[4][NQ], ll[4][NQ];
-  __shared__ float cf[FM_ATTN_MAX_SPLIT][NQ], cden[NQ];
+  __shared__ AttnMergeShared<QT> ms;
   __shared__ int s_last;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int split = blockIdx.x, hh = blockIdx.y, s = blockIdx.z;
@@ -322,14 +404,26 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   }
   const f16_t* Kb = Kc + (long)s * seq_stride + (long)hh * capb * 2048;
   const f16_t* Vb = Vc + (long)s * seq_stride + (long)hh * capb * 2048;
-  for (int b = b0 + wave; b < b1; b += 4) {
-    const f16_t* kp = Kb + (long)b * 2048 + lane * 8;
-    const f16_t* vp = Vb + (long)b * 2048 + (lane & 15) * 32 + g * 8;
-    f16x8 kf[4], vf[4];
+  // the next block of this wave is requested before the current one is multiplied
+  f16x8 kf[4], vf[4];
+  if (b0 + wave < b1) {
+    const f16_t* kp = Kb + (long)(b0 + wave) * 2048 + lane * 8;
+    const f16_t* vp = Vb + (long)(b0 + wave) * 2048 + (lane & 15) * 32 + g * 8;
 #pragma unroll
     for (int f = 0; f < 4; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
 #pragma unroll
     for (int dt = 0; dt < 4; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+  }
+  for (int b = b0 + wave; b < b1; b += 4) {
+    f16x8 kn[4], vn[4];
+    if (b + 4 < b1) {
+      const f16_t* kp = Kb + (long)(b + 4) * 2048 + lane * 8;
+      const f16_t* vp = Vb + (long)(b + 4) * 2048 + (lane & 15) * 32 + g * 8;
+#pragma unroll
+      for (int f = 0; f < 4; f++) kn[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) vn[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+    }
 #pragma unroll
     for (int t = 0; t < QT; t++) {
       // scores, transposed: sT[hb][i] = <K[key], Q[q]> for key = b*32 + hb*16 + g*4 + i, q = this lane's row
@@ -374,6 +468,10 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
         o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[t][dt], 0, 0, 0);   // O^T[dim][q]
       }
     }
+    if (b + 4 < b1) {
+#pragma unroll
+      for (int f = 0; f < 4; f++) { kf[f] = kn[f]; vf[f] = vn[f]; }
+    }
   }
   // combine the four waves of the workgroup
 #pragma unroll
@@ -403,12 +501,15 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
     }
     if (nsplit == 1) {
       if (qi < RPS) out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
+    } else if (defer_merge) {
+      part[e] = num;
+      if (dim == 0) { part[NQ * 64 + qi] = M; part[NQ * 64 + NQ + qi] = den; }
     } else {
       st_agent(part + e, num);
       if (dim == 0) { st_agent(part + NQ * 64 + qi, M); st_agent(part + NQ * 64 + NQ + qi, den); }
     }
   }
-  if (nsplit == 1) return;
+  if (nsplit == 1 || defer_merge) return;     // deferred: k_attn_merge runs behind this launch
   publish_fence();
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -418,33 +519,30 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   }
   __syncthreads();
   if (!s_last) return;
-  // last workgroup of this (sequence, head): merge the splits in a fixed order
-  const float* base = ws + sh * gridDim.x * PSZ;
-  for (int e = threadIdx.x; e < nsplit * NQ; e += 256) cf[e / NQ][e % NQ] = ld_agent(base + (long)(e / NQ) * PSZ + NQ * 64 + (e % NQ));
-  __syncthreads();
-  if (threadIdx.x < NQ) {
-    const int qi = threadIdx.x;
-    float M = -INFINITY;
-    for (int k2 = 0; k2 < nsplit; k2++) M = fmaxf(M, cf[k2][qi]);
-    const float Ms = M == -INFINITY ? 0.f : M;
-    float den = 0.f;
-    for (int k2 = 0; k2 < nsplit; k2++) {
-      const float f = __builtin_amdgcn_exp2f(cf[k2][qi] - Ms);
-      cf[k2][qi] = f;
-      den += ld_agent(base + (long)k2 * PSZ + NQ * 64 + NQ + qi) * f;
-    }
-    cden[qi] = den;
-  }
-  __syncthreads();
-  for (int e = threadIdx.x; e < NQ * 64; e += 256) {
-    const int qi = e >> 6, dim = e & 63;
-    if (qi >= RPS) continue;
-    float num = 0.f;
-#pragma unroll 8
-    for (int k2 = 0; k2 < nsplit; k2++) num += ld_agent(base + (long)k2 * PSZ + e) * cf[k2][qi];
-    const float den = cden[qi];
-    out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
-  }
+  // last workgroup of this (sequence, head)
+  attn_merge<QT, true>(ms, ws + sh * gridDim.x * PSZ, nsplit, RPS, out + (long)s * RPS * d + hh * FM_HD, d);
+}
+
+// Second launch of the deferred form: one workgroup per (head, sequence) derives the split count exactly as the
+// first launch did and merges; (sequence, head) pairs that fitted one split were already written there.
+template <int QT>
+__global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limit, int RPS, int capb, int nsplit_cfg,
+                                                     f16_t* __restrict__ out, int H, const float* __restrict__ ws,
+                                                     const int* run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  constexpr int NQ = QT * 16;
+  constexpr int PSZ = NQ * 64 + 2 * NQ;
+  __shared__ AttnMergeShared<QT> ms;
+  const int hh = blockIdx.x, s = blockIdx.y;
+  const int d = H * FM_HD;
+  int maxlim = -1;
+  for (int qi = 0; qi < RPS; qi++) maxlim = max(maxlim, limit[(long)s * RPS + qi]);
+  const int nblk = (maxlim + 32) >> 5;
+  const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
+  const int nsplit = max(1, (nblk + per - 1) / per);
+  if (nsplit == 1) return;
+  const long sh = (long)s * H + hh;
+  attn_merge<QT, false>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RPS * d + hh * FM_HD, d);
 }
 
 inline size_t mfma_attn_ws_floats(int S, int H) {
@@ -469,11 +567,18 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
   nsplit = nsplit > want ? want : nsplit;
   nsplit = nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
   dim3 grid(nsplit, H, S);
-  if (RPS <= 16)
+  // With many workgroups the in-kernel merge loses: every workgroup pays an agent-scope release fence (an L2
+  // write-back, and those queue up per XCD).  Then the partials go out as plain stores and a second, tiny
+  // launch merges them; the arithmetic is the same either way.
+  const int defer = (nsplit > 1 && (long)nsplit * H * S > 256) ? 1 : 0;
+  if (RPS <= 16) {
     hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
-                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, flag);
-  else
+                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, defer, flag);
+    if (defer) hipLaunchKernelGGL((k_attn_merge<1>), dim3(H, S), dim3(256), 0, st, limit, RPS, capb, nsplit, (f16_t*)out, H, res.attn_ws, flag);
+  } else {
     hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
-                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, flag);
+                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, defer, flag);
+    if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, limit, RPS, capb, nsplit, (f16_t*)out, H, res.attn_ws, flag);
+  }
   return true;
 }
