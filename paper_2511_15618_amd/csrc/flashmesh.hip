@@ -161,8 +161,8 @@ void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, 
 
 template <typename T>
 void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
-               long seq_stride, int cap, void* out, const int* flag) {
-  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, c->stream)) return;
+               long seq_stride, int cap, void* out, const int* flag, bool dense = false) {
+  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, c->stream)) return;
   hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
                      (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag);
 }
@@ -207,7 +207,7 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   rmsnorm<T>(c, h, nullptr, L.g2, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_T, c->xn, d, 0, L.cq, 0, c->qT, d, 0, nullptr, 0, 0, rows, d, d, 1, flag);
-  attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)cache_seq_elems(c, D.M), D.M, c->attT, flag);
+  attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)cache_seq_elems(c, D.M), D.M, c->attT, flag, true);
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.co, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   rmsnorm<T>(c, h, nullptr, L.g3, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_GELU_T, c->xn, d, 0, L.w1, 0, c->mid, c->ff, 0, nullptr, 0, 0, rows, c->ff, d, 1, flag);
@@ -296,7 +296,7 @@ void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level,
   attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag);
   gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.wo, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   gemm<T>(c, EPI_T, c->dxn, (long)G * d, d, sp.cq, dd, c->dq, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
-  attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)cache_seq_elems(c, D.M), D.M, c->datt, flag);
+  attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)cache_seq_elems(c, D.M), D.M, c->datt, flag, true);
   gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.co, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.lin, dd, out, ldo, gso, c->dkeep, (long)G * d, d, D.S, d, d, G, flag);
 }

@@ -119,6 +119,8 @@ __global__ void k_tile_weight(const float* __restrict__ src, f16_t* __restrict__
 // ------------------------------------------------------------------------------------------
 // GEMM
 // ------------------------------------------------------------------------------------------
+// The wave index is made provably wave-uniform (readfirstlane) in every MFMA kernel: MFMA ignores the EXEC mask,
+// so an MFMA guarded by a condition the compiler takes for divergent would run on a false guard as well.
 struct GemmSplit {
   int kt_per_wave;   // K fragments (of 32) each wave walks
   int ksplit;        // workgroups along K (each covers 4 * kt_per_wave fragments)
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   if (a.run_flag && *a.run_flag == 0) return;
   __shared__ f32x4 red[4][MT][64];
   __shared__ int s_last;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nt = blockIdx.x, ks = blockIdx.y;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
   const int g = blockIdx.z / nmb, mb = blockIdx.z % nmb;
@@ -154,12 +156,40 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   const int kt0 = (ks * 4 + wave) * sp.kt_per_wave;
   const int kt1 = min(kt0 + sp.kt_per_wave, KT);
 
-  for (int kt = kt0; kt < kt1; kt++) {
-    const f16x8 b = *reinterpret_cast<const f16x8*>(W + ((long)kt * 64 + lane) * 8);
+  // K is walked in chunks of U fragments; the loads of the next chunk are in flight while this one is
+  // multiplied (a workgroup is often alone on its CU, so nothing else would hide the latency)
+  constexpr int U = MT <= 2 ? 8 : MT <= 5 ? 4 : 2;
+  f16x8 bc[U], ac[MT][U];
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-      const f16x8 av = *reinterpret_cast<const f16x8*>(xrow[mt] + kt * 32);
-      acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, b, acc[mt], 0, 0, 0);
+  for (int u = 0; u < U; u++) {
+    if (kt0 + u < kt1) {
+      bc[u] = *reinterpret_cast<const f16x8*>(W + ((long)(kt0 + u) * 64 + lane) * 8);
+#pragma unroll
+      for (int mt = 0; mt < MT; mt++) ac[mt][u] = *reinterpret_cast<const f16x8*>(xrow[mt] + (kt0 + u) * 32);
+    }
+  }
+  for (int kt = kt0; kt < kt1; kt += U) {
+    f16x8 bn[U], an[MT][U];
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      if (kt + U + u < kt1) {
+        bn[u] = *reinterpret_cast<const f16x8*>(W + ((long)(kt + U + u) * 64 + lane) * 8);
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) an[mt][u] = *reinterpret_cast<const f16x8*>(xrow[mt] + (kt + U + u) * 32);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      if (kt + u < kt1) {
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac[mt][u], bc[u], acc[mt], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; u++) {
+      bc[u] = bn[u];
+#pragma unroll
+      for (int mt = 0; mt < MT; mt++) ac[mt][u] = an[mt][u];
     }
   }
   // reduce the four K-quarters of the workgroup through LDS
@@ -360,7 +390,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   __shared__ float lm[4][NQ], ll[4][NQ];
   __shared__ AttnMergeShared<QT> ms;
   __shared__ int s_last;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int split = blockIdx.x, hh = blockIdx.y, s = blockIdx.z;
   const int d = H * FM_HD;
   const int g = lane >> 4, ql = lane & 15;
@@ -551,21 +581,26 @@ inline size_t mfma_attn_ws_floats(int S, int H) {
 
 template <typename T>
 bool mfma_attn_launch(const MfmaRes&, const void*, const int*, int, int, const void*, const void*, long, int, void*, int,
-                      const int*, hipStream_t) { return false; }
+                      const int*, bool, hipStream_t) { return false; }
 
 // `cap` = key capacity of the cache (positions); caches are laid out in 32-key blocks
 template <>
 inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int* limit, int rows, int RPS, const void* Kc,
                                     const void* Vc, long seq_stride, int cap, void* out, int H, const int* flag,
-                                    hipStream_t st) {
+                                    bool dense, hipStream_t st) {
   if (RPS > 32 || rows % RPS != 0) return false;
   const int S = rows / RPS;
   const int capb = (cap + 31) / 32;
-  int nsplit = capb / 8;   // about 8 blocks (two per wave) per workgroup at full length
-  const int want = 1024 / (H * S) > 0 ? 1024 / (H * S) : 1;
+  // The key axis is cut into fixed ranges of at least 8 blocks (two per wave).  A growing cache is far below
+  // its capacity most of the time, so its ranges stay that short (up to 64 of them); a cache that is always
+  // full (`dense`: the condition memory) gets as few ranges as fill the chip in one round of workgroups.
+  int nsplit = capb / 8;
   nsplit = nsplit < 1 ? 1 : nsplit;
-  nsplit = nsplit > want ? want : nsplit;
   nsplit = nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
+  if (dense) {
+    const int want = 768 / (H * S) > 0 ? 768 / (H * S) : 1;
+    nsplit = nsplit > want ? want : nsplit;
+  }
   dim3 grid(nsplit, H, S);
   // With many workgroups the in-kernel merge loses: every workgroup pays an agent-scope release fence (an L2
   // write-back, and those queue up per XCD).  Then the partials go out as plain stores and a second, tiny

@@ -254,7 +254,7 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, cons
                                              unsigned tagA, const float* gain, int R, f32x4& result, int stage,
                                              int lda = 0) {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int r = lane & 15, g = lane >> 4;
   const bool on = r < R;
   const int FW = KT >> 2;                  // fragments per wave (host guarantees KT % 4 == 0)
@@ -436,7 +436,7 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, const int* limit, int R,
                                              const f16_t* Kc, const f16_t* Vc, int capb, int nsplit_cfg, int hh, int split,
                                              bool overlay, int P0, u64* part, unsigned tag, int stage) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int g = lane >> 4, ql = lane & 15;
   const int d = a.D.d;
   const float kScale = 0.125f * 1.4426950408889634f;
@@ -656,7 +656,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   if (*a.run_flag == 0) return;
   __shared__ PkShared sh;
   const int d = a.D.d, H = a.D.H, ff = a.ff;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   unsigned rr = 0;     // round-robin origin of the current stage (same in every workgroup)
   int stage = 0;
   bool worked = false;
