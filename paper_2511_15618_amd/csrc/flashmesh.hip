@@ -95,7 +95,9 @@ struct fm_ctx {
   Replay replay;
   int *gen_tok, *gen_len;  // block buffers used by fm_generate
   int* gen_acc;
-  int* host_flag;          // pinned
+  int* host_flag;          // pinned: [0] alive flag, [1..S] lagged copy of the committed lengths
+  std::vector<int> len_bound;   // host upper bound on each sequence's committed coordinate length
+  long commits = 0;             // fm_commit calls so far
   // persistent verify kernel (one sequence, block <= 16, half-precision path)
   bool persist;
   PkArgs pk;
@@ -143,6 +145,15 @@ int dalloc_t(fm_ctx* c, void** p, size_t n) {  // n elements of the storage type
 #define TRY(x) do { int rc_ = (x); if (rc_ != FM_OK) return rc_; } while (0)
 
 int level_cap(const fm_ctx* c, int level) { return level == 0 ? c->D.capc : level == 1 ? c->D.capv : c->D.capf; }
+// Upper bound on the keys any row of the next pass can see at `level`, from the host's bound on the committed
+// lengths (a commit adds at most block_max tokens; fm_read_state and the generate loop tighten it).
+int level_key_bound(const fm_ctx* c, int level) {
+  int b = 0;
+  for (int s = 0; s < c->D.S; s++) b = std::max(b, c->len_bound[s]);
+  const long keys = (long)b + c->D.Bm;                  // positions P .. P + block_max - 1 are in the pass
+  const long k = level == 0 ? keys : level == 1 ? (keys + 2) / 3 + 1 : (keys + 8) / 9 + 1;
+  return (int)std::min<long>(k, level_cap(c, level));
+}
 const int kStackLevel[5] = {0, 1, 2, 1, 0};
 
 // ------------------------------------------------------------------------------------------
@@ -161,8 +172,8 @@ void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, 
 
 template <typename T>
 void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
-               long seq_stride, int cap, void* out, const int* flag, bool dense = false) {
-  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, c->stream)) return;
+               long seq_stride, int cap, void* out, const int* flag, bool dense = false, int key_bound = 1 << 30) {
+  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, c->stream)) return;
   hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
                      (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag);
 }
@@ -203,7 +214,7 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
   rmsnorm<T>(c, h, nullptr, L.g1, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_F32, c->xn, d, 0, L.wqkv, 0, c->qkv, 3 * d, 0, nullptr, 0, 0, rows, 3 * d, d, 1, flag);
   rope_append<T>(c, c->qkv, (long)3 * d, c->cs[level], c->pos[level], rows, RPS, c->qT, L.Kc, L.Vc, cap, flag);
-  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag);
+  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag, false, level_key_bound(c, level));
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   rmsnorm<T>(c, h, nullptr, L.g2, 0, c->xn, nullptr, rows, flag);
   gemm<T>(c, EPI_T, c->xn, d, 0, L.cq, 0, c->qT, d, 0, nullptr, 0, 0, rows, d, d, 1, flag);
@@ -293,7 +304,7 @@ void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level,
   rmsnorm<T>(c, nullptr, c->dr.src[set], sp.g, G, c->dxn, c->dkeep, rows, flag);
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.wq, dd, c->dtmp, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[set], c->dr.pos[set], rows, G, c->dq, nullptr, nullptr, cap, flag);
-  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag);
+  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag, false, level_key_bound(c, level));
   gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.wo, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   gemm<T>(c, EPI_T, c->dxn, (long)G * d, d, sp.cq, dd, c->dq, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)cache_seq_elems(c, D.M), D.M, c->datt, flag, true);
@@ -315,7 +326,7 @@ void run_hf(fm_ctx* c, int set, const HfLevel& hf, int mult, const Layer& last, 
   rmsnorm<T>(c, nullptr, c->dr.src[set], hf.g, G, c->dxn, c->dkeep, rows, flag);
   gemm<T>(c, EPI_F32, c->dxn, ld, d, hf.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, Mg, d, d, G, flag);
   rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[set], c->dr.pos[set], rows, per_seq, c->dq, nullptr, nullptr, cap, flag);
-  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag);
+  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag, false, level_key_bound(c, level));
   gemm<T>(c, EPI_GELU_T, c->datt, ld, d, hf.w1, dh, c->dmid, (long)G * c->hff, c->hff, nullptr, 0, 0, Mg, c->hff, d, G, flag);
   gemm<T>(c, EPI_F32, c->dmid, (long)G * c->hff, c->hff, hf.w2, dh, out, ld, d, c->dkeep, ld, d, Mg, d, c->hff, G, flag);
 }
@@ -603,7 +614,7 @@ int build_buffers(fm_ctx* c) {
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
     TRY(dalloc(c, &c->mres.attn_counters, (size_t)D.S * D.H));
   }
-  if (hipHostMalloc((void**)&c->host_flag, 64) != hipSuccess) return fail(c, FM_ENOMEM, "hipHostMalloc failed");
+  if (hipHostMalloc((void**)&c->host_flag, 64 + sizeof(int) * (size_t)c->D.S) != hipSuccess) return fail(c, FM_ENOMEM, "hipHostMalloc failed");
   return FM_OK;
 }
 
@@ -651,6 +662,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   for (int i = 0; i < 32; i++) c->inv.v[i] = std::pow((double)g.rope_base, -(double)i / 32.0);
   c->weights_loaded = false;
   c->prefilled.assign(D.S, false);
+  c->len_bound.assign(D.S, D.capc);
   c->replay = Replay{nullptr, 0, 0, 0.f, 0ull};
   c->host_flag = nullptr;
   {
@@ -733,7 +745,7 @@ int fm_prefill_condition(fm_ctx* c, int32_t seq, const float* mem_dev) {
   if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range [0,%d)", seq, c->D.S);
   if (!mem_dev) return fail(c, FM_EINVAL, "null condition memory");
   int rc = c->bf16 ? prefill_impl<f16_t>(c, seq, mem_dev) : prefill_impl<float>(c, seq, mem_dev);
-  if (rc == FM_OK) c->prefilled[seq] = true;
+  if (rc == FM_OK) { c->prefilled[seq] = true; c->len_bound[seq] = 0; }
   return rc;
 }
 
@@ -757,6 +769,8 @@ int fm_commit(fm_ctx* c, const int32_t* accepted) {
   if (!accepted) return fail(c, FM_EINVAL, "null accepted buffer");
   hipLaunchKernelGGL(k_commit, dim3(1), dim3(64), 0, c->stream, c->st, c->D, accepted);
   HIPCHK(c, hipGetLastError());
+  for (int s = 0; s < c->D.S; s++) c->len_bound[s] = std::min(c->len_bound[s] + c->D.Bm, c->D.capc);
+  c->commits++;
   return FM_OK;
 }
 
@@ -786,6 +800,7 @@ int fm_read_state(fm_ctx* c, int32_t* host_out) {
   HIPCHK(c, hipMemcpy(fin.data(), c->st.fin, S * 4, hipMemcpyDeviceToHost));
   TRY(check_persist(c));
   for (int s = 0; s < S; s++) {
+    c->len_bound[s] = P[s];
     host_out[s * 6 + 0] = P[s];
     host_out[s * 6 + 1] = (P[s] + 2) / 3;
     host_out[s * 6 + 2] = (P[s] + 8) / 9;
@@ -852,6 +867,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
   const long max_steps = 9L * max_faces + 1;
   const int check_every = 32;
   bool pending = false, done = false;
+  long commits_at_copy = 0;
   int rc = FM_OK;
   for (long step = 0; step < max_steps && !done && rc == FM_OK; step++) {
     rc = c->bf16 ? draft_impl<f16_t>(c, c->gen_tok, c->gen_len, speculative) : draft_impl<float>(c, c->gen_tok, c->gen_len, speculative);
@@ -865,9 +881,15 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
       if (pending) {
         HIPCHK(c, hipEventSynchronize(eflag));
         if (c->host_flag[0] == 0) done = true;
+        // the lengths of one interval ago bound today's: every commit since then added at most block_max
+        const long since = c->commits - commits_at_copy;
+        for (int s = 0; s < D.S; s++)
+          c->len_bound[s] = (int)std::min<long>(c->len_bound[s], c->host_flag[16 + s] + since * D.Bm);
       }
       if (!done) {
         HIPCHK(c, hipMemcpyAsync(c->host_flag, c->st.alive, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipMemcpyAsync(c->host_flag + 16, c->st.P, sizeof(int) * (size_t)D.S, hipMemcpyDeviceToHost, c->stream));
+        commits_at_copy = c->commits;
         HIPCHK(c, hipEventRecord(eflag, c->stream));
         pending = true;
       }

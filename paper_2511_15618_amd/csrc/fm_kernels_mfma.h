@@ -382,7 +382,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
                                                     const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
                                                     long seq_stride, int capb, f16_t* __restrict__ out, int H,
                                                     float* __restrict__ ws, unsigned* __restrict__ counters,
-                                                    int defer_merge, const int* run_flag) {
+                                                    int nsplit_cfg, int defer_merge, const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
   constexpr int NQ = QT * 16;
   constexpr int PSZ = NQ * 64 + 2 * NQ;
@@ -418,7 +418,8 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   // so the arithmetic for one query position never depends on what else is in the block or on how far
   // the sequence has grown (speculative and one-token decoding then agree bit for bit).  Splits with no
   // visible key leave at once; every workgroup of this (sequence, head) derives the same count.
-  const int per = (capb + (int)gridDim.x - 1) / (int)gridDim.x;
+  // (the launch may hold fewer than nsplit_cfg workgroups per head when the host knows the cache is short)
+  const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   if (split >= nsplit) return;
   const int b0 = split * per, b1 = min(b0 + per, nblk);
@@ -517,7 +518,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   }
   __syncthreads();
   const long sh = (long)s * H + hh;
-  float* part = ws + (sh * gridDim.x + split) * PSZ;   // slots are laid out for the launched split count
+  float* part = ws + (sh * nsplit_cfg + split) * PSZ;   // slots are laid out for the configured split count
   for (int e = threadIdx.x; e < NQ * 64; e += 256) {
     const int qi = e >> 6, dim = e & 63;
     const float M = fmaxf(fmaxf(lm[0][qi], lm[1][qi]), fmaxf(lm[2][qi], lm[3][qi]));
@@ -550,7 +551,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   __syncthreads();
   if (!s_last) return;
   // last workgroup of this (sequence, head)
-  attn_merge<QT, true>(ms, ws + sh * gridDim.x * PSZ, nsplit, RPS, out + (long)s * RPS * d + hh * FM_HD, d);
+  attn_merge<QT, true>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RPS * d + hh * FM_HD, d);
 }
 
 // Second launch of the deferred form: one workgroup per (head, sequence) derives the split count exactly as the
@@ -581,13 +582,13 @@ inline size_t mfma_attn_ws_floats(int S, int H) {
 
 template <typename T>
 bool mfma_attn_launch(const MfmaRes&, const void*, const int*, int, int, const void*, const void*, long, int, void*, int,
-                      const int*, bool, hipStream_t) { return false; }
+                      const int*, bool, int, hipStream_t) { return false; }
 
 // `cap` = key capacity of the cache (positions); caches are laid out in 32-key blocks
 template <>
 inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int* limit, int rows, int RPS, const void* Kc,
                                     const void* Vc, long seq_stride, int cap, void* out, int H, const int* flag,
-                                    bool dense, hipStream_t st) {
+                                    bool dense, int key_bound, hipStream_t st) {
   if (RPS > 32 || rows % RPS != 0) return false;
   const int S = rows / RPS;
   const int capb = (cap + 31) / 32;
@@ -601,18 +602,23 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
     const int want = 768 / (H * S) > 0 ? 768 / (H * S) : 1;
     nsplit = nsplit > want ? want : nsplit;
   }
-  dim3 grid(nsplit, H, S);
+  // `key_bound` is the host's upper bound on the visible keys: ranges past it hold nothing and are not launched
+  const int per = (capb + nsplit - 1) / nsplit;
+  const int bound_blocks = ((key_bound < cap ? key_bound : cap) + 31) / 32;
+  int launched = (bound_blocks + per - 1) / per;
+  launched = launched < 1 ? 1 : launched > nsplit ? nsplit : launched;
+  dim3 grid(launched, H, S);
   // With many workgroups the in-kernel merge loses: every workgroup pays an agent-scope release fence (an L2
   // write-back, and those queue up per XCD).  Then the partials go out as plain stores and a second, tiny
   // launch merges them; the arithmetic is the same either way.
-  const int defer = (nsplit > 1 && (long)nsplit * H * S > 256) ? 1 : 0;
+  const int defer = (launched > 1 && (long)launched * H * S > 256) ? 1 : 0;
   if (RPS <= 16) {
     hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
-                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, defer, flag);
+                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
     if (defer) hipLaunchKernelGGL((k_attn_merge<1>), dim3(H, S), dim3(256), 0, st, limit, RPS, capb, nsplit, (f16_t*)out, H, res.attn_ws, flag);
   } else {
     hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
-                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, defer, flag);
+                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
     if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, limit, RPS, capb, nsplit, (f16_t*)out, H, res.attn_ws, flag);
   }
   return true;
