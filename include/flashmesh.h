@@ -146,7 +146,9 @@ int fm_debug_profile(fm_ctx* ctx, uint64_t* host_out, int32_t n);
 int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
 
 /* Which implementation fm_verify_block runs for this context: 1 = the single persistent kernel (half-precision
- * storage, one sequence, block <= 16), 0 = one launch per operator.  Both compute the same values. */
+ * storage, one sequence, block <= 16), 0 = one launch per operator.  Both compute the same function with the same
+ * arithmetic per operator; they cut the key axis of the attention differently, so results agree to rounding, and
+ * each is bit-reproducible in itself. */
 int32_t fm_verify_path(const fm_ctx* ctx);
 
 /* Algorithmic HBM bytes of one verify pass at the current committed lengths (weights once, self

@@ -97,6 +97,7 @@ TEST_CONFIGS = {
     "t_bf16_99": Config("t_bf16_99", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 3, 12, 2, 9, 9),
     "t_bf16_99_b1": Config("t_bf16_99_b1", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9),
     "t_bf16_99_b1w": Config("t_bf16_99_b1w", 256, 4, 64, 2, 1, 2, 2, 3, 100, "bf16", 1, 30, 2, 9, 9),
+    "t_bf16_99_b8long": Config("t_bf16_99_b8long", 256, 4, 64, 2, 1, 2, 2, 3, 100, "bf16", 8, 256, 2, 9, 9),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
 }
 

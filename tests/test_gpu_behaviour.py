@@ -215,6 +215,27 @@ def test_config1_full_size_stream():
     print("config1 full: allowed flips", flips, "worst margin", worst, "steps native/replay", st.steps, st2.steps, flush=True)
 
 
+def test_batched_long_context_stream():
+    """Eight ragged sequences of 2304 tokens at a small width: the key axis of the self-attention is cut into
+    nine ranges whose partial results are merged by the second launch, and the host-side bound on the
+    committed lengths decides how many of them are launched.  Native run == replay run == the oracle's
+    choice at every position (teacher-forced, margin rule)."""
+    _need_gpu()
+    cfg = si.TEST_CONFIGS["t_bf16_99_b8long"]
+    print("case batched long", flush=True)
+    fm, _ = _ctx(cfg)
+    assert fm.verify_path() == 0
+    out, n, st = fm.generate(cfg.faces, True)
+    assert [int(v) for v in n] == [cfg.max_tokens] * cfg.batch
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    fm.set_draft_replay(out.clone(), cfg.max_tokens, 0.8, 11)
+    out2, n2, st2 = fm.generate(cfg.faces, True)
+    assert torch.equal(out, out2) and st2.steps < st.steps
+    flips, worst = _teacher_forced_check(cfg, out.cpu().numpy(), TOL["bf16"], np.float64)
+    print("batched long: allowed flips", flips, "worst margin", worst, "steps native/replay", st.steps, st2.steps, flush=True)
+
+
 @pytest.mark.skipif(os.environ.get("FM_LONG") != "1", reason="several minutes of CPU oracle time; set FM_LONG=1")
 def test_config2_full_size_stream():
     _need_gpu()
