@@ -26,6 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0   # dense fp16 / bf16
 REPLAY_P = 0.93
 REPLAY_SEED = 20251115
 
@@ -187,6 +188,21 @@ def main():
     seq_faces = min(faces, 100)
     _, _, st_seq = fm.generate(seq_faces, False)
 
+    # the one MFMA-bound piece: cross-attention K/V of all blocks from the condition memory (once per sequence)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fm.prefill_condition(0, mems_dev[0])
+    ev0.record(fm.stream)
+    for _ in range(5):
+        fm.prefill_condition(0, mems_dev[0])
+    ev1.record(fm.stream)
+    torch.cuda.synchronize()
+    ms_prefill = ev0.elapsed_time(ev1) / 5
+    prefill_flop = 2.0 * cfg.mem_len * 2 * cfg.d_model * cfg.d_model * cfg.n_layers
+    prefill = {"ms": ms_prefill, "tflops": prefill_flop / (ms_prefill * 1e-3) / 1e12,
+               "frac_of_mfma_peak": prefill_flop / (ms_prefill * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+               "what": "fm_prefill_condition of one sequence: K_mem, V_mem of every block (includes the memory "
+                       "re-tiling and the sequence reset launches)"}
+
     # roofline of the verify pass: algorithmic HBM bytes (weights once, self and cross K/V once per block)
     # over its measured duration, at the half-way point of the run, HIP events on the library's stream
     reset()
@@ -232,7 +248,7 @@ def main():
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,
                    "native_heads_ms_per_step": st_native.ms_total / max(st_native.steps, 1),
                    "sequential_tokens_per_s": st_seq.tokens / st_seq.ms_total * 1e3,
-                   "sequential_prefix_faces": seq_faces, "host_wall_s": wall},
+                   "sequential_prefix_faces": seq_faces, "host_wall_s": wall, "prefill": prefill},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": counter_traffic(args.config, fm.verify_path() == 1) if faces == cfg.faces else None,

@@ -18,6 +18,7 @@
 #include "fm_kernels_step.h"
 #include "fm_kernels_mfma.h"
 #include "fm_kernels_persist.h"
+#include "fm_kernels_prefill.h"
 
 #define RS_C 32  // ring sizes (positions kept per sequence) at the coordinate / vertex / face level
 #define RS_V 16
@@ -101,6 +102,8 @@ struct fm_ctx {
   // persistent verify kernel (one sequence, block <= 16, half-precision path)
   bool persist;
   PkArgs pk;
+  PrefillLayer* pf_layers = nullptr;   // per-block table of the tiled prefill GEMM (null: per-block launches)
+  int pf_n = 0;
   unsigned pk_epoch;
   size_t pk_lds;           // dynamic LDS of the persistent kernel: the activation panel
   double weight_bytes;
@@ -368,6 +371,16 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
   const Dims& D = c->D;
   const int d = D.d;
   // condition memory in the storage type (dmid is large enough: M*d <= checked at create)
+  if (std::is_same<T, f16_t>::value && c->pf_layers) {
+    // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
+    f16_t* Xt = (f16_t*)c->stage;
+    hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
+    hipLaunchKernelGGL(k_prefill_kv, dim3(D.M / 256, 2 * d / 256, c->pf_n), dim3(256), 65536, c->stream, (const f16_t*)Xt,
+                       (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, (D.M + 31) / 32);
+    hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
+    HIPCHK(c, hipGetLastError());
+    return FM_OK;
+  }
   T* memT = (T*)c->stage;  // reuse staging area: [M*d] T followed by fp32 [M][2d]
   float* kv = c->stage + (size_t)D.M * d;
   hipLaunchKernelGGL((k_convert<T>), dim3(512), dim3(256), 0, c->stream, mem_dev, memT, (long)D.M * d);
@@ -613,6 +626,19 @@ int build_buffers(fm_ctx* c) {
     c->mres.attn_ws_floats = mfma_attn_ws_floats(D.S, D.H);
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
     TRY(dalloc(c, &c->mres.attn_counters, (size_t)D.S * D.H));
+    // tiled prefill GEMM: whole 256 x 256 output tiles only
+    const char* pt = getenv("FM_PREFILL_TILED");     // "0" forces the per-block GEMM + scatter launches
+    if (D.M % 256 == 0 && d % 256 == 0 && !(pt && pt[0] == '0')) {
+      std::vector<PrefillLayer> tab;
+      for (int st = 0; st < 5; st++)
+        for (auto& L : c->stacks[st]) tab.push_back(PrefillLayer{(const f16_t*)L.ckv, (f16_t*)L.Km, (f16_t*)L.Vm});
+      uint8_t* raw = nullptr;
+      TRY(dalloc(c, &raw, tab.size() * sizeof(PrefillLayer)));
+      c->pf_layers = (PrefillLayer*)raw;
+      HIPCHK(c, hipMemcpy(c->pf_layers, tab.data(), tab.size() * sizeof(PrefillLayer), hipMemcpyHostToDevice));
+      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv, hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
+      c->pf_n = (int)tab.size();
+    }
   }
   if (hipHostMalloc((void**)&c->host_flag, 64 + sizeof(int) * (size_t)c->D.S) != hipSuccess) return fail(c, FM_ENOMEM, "hipHostMalloc failed");
   return FM_OK;
