@@ -375,7 +375,7 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
     // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
     f16_t* Xt = (f16_t*)c->stage;
     hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
-    hipLaunchKernelGGL(k_prefill_kv, dim3(D.M / 256, 2 * d / 256, c->pf_n), dim3(256), 65536, c->stream, (const f16_t*)Xt,
+    hipLaunchKernelGGL(k_prefill_kv, dim3(D.M / 256, 2 * d / 256, c->pf_n), dim3(256), 131072, c->stream, (const f16_t*)Xt,
                        (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, (D.M + 31) / 32);
     hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
     HIPCHK(c, hipGetLastError());
@@ -504,10 +504,10 @@ int build_persist(fm_ctx* c) {
     for (size_t i = 0; i < c->stacks[st].size(); i++) {
       const Layer& L = c->stacks[st][i];
       PkLayer p{};
-      p.g1 = L.g1; p.g2 = L.g2; p.g3 = L.g3;
-      p.wqkv = (const f16_t*)L.wqkv_rp; p.wo = (const f16_t*)L.wo; p.cq = (const f16_t*)L.cq; p.co = (const f16_t*)L.co;
-      p.w1 = (const f16_t*)L.w1; p.w2 = (const f16_t*)L.w2;
-      p.Kc = (f16_t*)L.Kc; p.Vc = (f16_t*)L.Vc; p.Km = (const f16_t*)L.Km; p.Vm = (const f16_t*)L.Vm;
+      p.g1 = (pk_cf_t)L.g1; p.g2 = (pk_cf_t)L.g2; p.g3 = (pk_cf_t)L.g3;
+      p.wqkv = (pk_cw_t)L.wqkv_rp; p.wo = (pk_cw_t)L.wo; p.cq = (pk_cw_t)L.cq; p.co = (pk_cw_t)L.co;
+      p.w1 = (pk_cw_t)L.w1; p.w2 = (pk_cw_t)L.w2;
+      p.Kc = (pk_w_t)L.Kc; p.Vc = (pk_w_t)L.Vc; p.Km = (pk_cw_t)L.Km; p.Vm = (pk_cw_t)L.Vm;
       p.level = L.level;
       p.last = i + 1 == c->stacks[st].size();
       p.tap = p.last && (st == 2 || st == 3 || st == 4);
@@ -636,7 +636,7 @@ int build_buffers(fm_ctx* c) {
       TRY(dalloc(c, &raw, tab.size() * sizeof(PrefillLayer)));
       c->pf_layers = (PrefillLayer*)raw;
       HIPCHK(c, hipMemcpy(c->pf_layers, tab.data(), tab.size() * sizeof(PrefillLayer), hipMemcpyHostToDevice));
-      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv, hipFuncAttributeMaxDynamicSharedMemorySize, 65536));
+      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
       c->pf_n = (int)tab.size();
     }
   }

@@ -29,11 +29,19 @@ typedef unsigned long long u64;
 #define PK_PART (16 * 64 + 32)            // per (head, split): 16x64 unnormalised O, 16 running maxima, 16 sums
 #define PK_TIMEOUT_TICKS 20000000ull      // 200 ms of the 100 MHz wall clock
 
+// A pointer read from a table in memory is generic to the compiler, and loads through it become FLAT instructions,
+// which count against the LDS counter as well: every wait for an LDS read would then also wait for the weight
+// or cache loads in flight.  The table therefore holds pointers that are typed as global.
+#define PK_GLOBAL __attribute__((address_space(1)))
+typedef const PK_GLOBAL f16_t* pk_cw_t;     // weights, condition-memory caches
+typedef PK_GLOBAL f16_t* pk_w_t;            // self-attention caches (appended to by this kernel)
+typedef const PK_GLOBAL float* pk_cf_t;     // gains
+
 struct PkLayer {
-  const float *g1, *g2, *g3;
-  const f16_t *wqkv, *wo, *cq, *co, *w1, *w2;   // tiled; wqkv with rotary pairs inside one tile
-  f16_t *Kc, *Vc;
-  const f16_t *Km, *Vm;
+  pk_cf_t g1, g2, g3;
+  pk_cw_t wqkv, wo, cq, co, w1, w2;   // tiled; wqkv with rotary pairs inside one tile
+  pk_w_t Kc, Vc;
+  pk_cw_t Km, Vm;
   int level;      // 0 coordinate, 1 vertex, 2 face
   int tap;        // store the layer input to the level's tap ring (input of the last layer of a stack)
   int last;       // last layer of its stack: output goes to hT[stack] and to the stack's ring
@@ -250,8 +258,8 @@ __device__ __forceinline__ bool pk_panel_load(const PkArgs& a, const u64* A, int
 // RMS-normalised (gain g) on the fly (K/128 <= 8 fragments per wave, i.e. K <= 1024).
 // ------------------------------------------------------------------------------------------
 template <int ASRC>
-__device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, const f16_t* Wt, int KT, const u64* A,
-                                             unsigned tagA, const float* gain, int R, f32x4& result, int stage,
+__device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_cw_t Wt, int KT, const u64* A,
+                                             unsigned tagA, pk_cf_t gain, int R, f32x4& result, int stage,
                                              int lda = 0) {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -265,7 +273,7 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, cons
   f16x8 wf[8];
 #pragma unroll
   for (int f = 0; f < 8; f++)
-    if (f < FW) wf[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
+    if (f < FW) wf[f] = *(const PK_GLOBAL f16x8*)(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
   float gcol[4] = {0.f, 0.f, 0.f, 0.f};     // gains of this thread's columns, requested before the wait
   if (ASRC == 1) {
 #pragma unroll
@@ -322,7 +330,7 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, cons
       f16x8 wn[8];     // next chunk of weights is in flight while this one is multiplied
 #pragma unroll
       for (int f = 0; f < 8; f++)
-        if (f0 + 8 + f < FW) wn[f] = *reinterpret_cast<const f16x8*>(Wt + ((long)(wave * FW + f0 + 8 + f) * 64 + lane) * 8);
+        if (f0 + 8 + f < FW) wn[f] = *(const PK_GLOBAL f16x8*)(Wt + ((long)(wave * FW + f0 + 8 + f) * 64 + lane) * 8);
 #pragma unroll
       for (int f = 0; f < 8; f++) {
         if (f0 + f < FW) {
@@ -434,7 +442,7 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 // Keys of this pass (positions >= P0) are taken from the exchange buffers, older keys from the cache.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, const int* limit, int R,
-                                             const f16_t* Kc, const f16_t* Vc, int capb, int nsplit_cfg, int hh, int split,
+                                             pk_cw_t Kc, pk_cw_t Vc, int capb, int nsplit_cfg, int hh, int split,
                                              bool overlay, int P0, u64* part, unsigned tag, int stage) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int g = lane >> 4, ql = lane & 15;
@@ -492,16 +500,16 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   f32x4 o[4];
 #pragma unroll
   for (int dt = 0; dt < 4; dt++) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const f16_t* Kb = Kc + (long)hh * capb * 2048;
-  const f16_t* Vb = Vc + (long)hh * capb * 2048;
+  pk_cw_t Kb = Kc + (long)hh * capb * 2048;
+  pk_cw_t Vb = Vc + (long)hh * capb * 2048;
   for (int b = b0 + wave; b < b1; b += 4) {
-    const f16_t* kp = Kb + (long)b * 2048 + lane * 8;
-    const f16_t* vp = Vb + (long)b * 2048 + (lane & 15) * 32 + g * 8;
+    pk_cw_t kp = Kb + (long)b * 2048 + lane * 8;
+    pk_cw_t vp = Vb + (long)b * 2048 + (lane & 15) * 32 + g * 8;
     f16x8 kf[4], vf[4];
 #pragma unroll
-    for (int f = 0; f < 4; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
+    for (int f = 0; f < 4; f++) kf[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+    for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
     if (b == bov) {
 #pragma unroll
       for (int f = 0; f < 4; f++) {
@@ -843,7 +851,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       PK_NEXT(Rc_);
       PK_MINE(d / 16) {
         f32x4 c;
-        const f16_t* W = (st == 0 ? a.short_cv : a.short_vf) + (long)u * (d / 32) * 512;
+        pk_cw_t W = (pk_cw_t)(st == 0 ? a.short_cv : a.short_vf) + (long)u * (d / 32) * 512;
         if (!pk_gemm_tile<0>(a, sh, W, d / 32, a.pool + (long)st * 8 * d, tagn, nullptr, Rc_, c, stage)) return;
         if (wave == 0) {
           const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
@@ -891,7 +899,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const int NT = (a.D.V + 15) / 16;
     PK_MINE(NT) {
       f32x4 c;
-      if (!pk_gemm_tile<1>(a, sh, a.lm + (long)u * (d / 32) * 512, d / 32, a.hA + (long)l * 16 * d, PK_TAG(a, l), a.gf, R, c, stage)) return;
+      if (!pk_gemm_tile<1>(a, sh, (pk_cw_t)a.lm + (long)u * (d / 32) * 512, d / 32, a.hA + (long)l * 16 * d, PK_TAG(a, l), (pk_cf_t)a.gf, R, c, stage)) return;
       if (wave == 0) {
         const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll
