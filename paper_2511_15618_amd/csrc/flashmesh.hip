@@ -375,8 +375,8 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
     // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
     f16_t* Xt = (f16_t*)c->stage;
     hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
-    hipLaunchKernelGGL(k_prefill_kv, dim3(D.M / 256, 2 * d / 256, c->pf_n), dim3(256), 131072, c->stream, (const f16_t*)Xt,
-                       (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, (D.M + 31) / 32);
+    hipLaunchKernelGGL(k_prefill_kv, dim3((D.M / 256) * (d / 128) + (d / 256) * (D.M / 128), c->pf_n), dim3(256), 0, c->stream,
+                       (const f16_t*)Xt, (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M);
     hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
     HIPCHK(c, hipGetLastError());
     return FM_OK;
@@ -626,7 +626,7 @@ int build_buffers(fm_ctx* c) {
     c->mres.attn_ws_floats = mfma_attn_ws_floats(D.S, D.H);
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
     TRY(dalloc(c, &c->mres.attn_counters, (size_t)D.S * D.H));
-    // tiled prefill GEMM: whole 256 x 256 output tiles only
+    // tiled prefill GEMM: whole 256 x 128 output tiles only (keys x dims for V, dims x keys for K)
     const char* pt = getenv("FM_PREFILL_TILED");     // "0" forces the per-block GEMM + scatter launches
     if (D.M % 256 == 0 && d % 256 == 0 && !(pt && pt[0] == '0')) {
       std::vector<PrefillLayer> tab;
@@ -636,7 +636,6 @@ int build_buffers(fm_ctx* c) {
       TRY(dalloc(c, &raw, tab.size() * sizeof(PrefillLayer)));
       c->pf_layers = (PrefillLayer*)raw;
       HIPCHK(c, hipMemcpy(c->pf_layers, tab.data(), tab.size() * sizeof(PrefillLayer), hipMemcpyHostToDevice));
-      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
       c->pf_n = (int)tab.size();
     }
   }

@@ -1,8 +1,9 @@
 // Cross-attention keys/values of the condition memory for every transformer block in one launch:
 // K_mem = W_k c, V_mem = W_v c (the condition c enters every block through cross-attention, Sec. 3.1).
 // This is the one dense, MFMA-bound contraction of the path (M = mem_len rows, N = 2 d_model, K = d_model
-// per block), so it is a classic LDS-tiled GEMM: 256 x 256 output tile per workgroup, 128 x 128 per wave
-// (16 accumulators of 32x32), K walked 64 at a time through a two-buffer LDS ring, global loads one stage ahead.
+// per block), so it is a classic LDS-tiled GEMM: 256 x 128 output tile per workgroup, 128 x 64 per wave
+// (8 accumulators of 32x32), K walked 32 at a time through a two-buffer LDS ring, global loads one step ahead,
+// two workgroups per CU.
 //
 // Both operands are already in MFMA fragment order in global memory ([rows/16][K/32][64 lanes][8 halves]:
 // the weights from load time, the memory from k_tile_weight), so a fragment is one contiguous 1 KiB burst
@@ -21,78 +22,91 @@ struct PrefillLayer {
 typedef unsigned pf_u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-__global__ __launch_bounds__(256) void k_prefill_kv(const f16_t* __restrict__ Xt, const PrefillLayer* __restrict__ layers,
-                                                    long seq_off, int KT, int d, int capb) {
-  extern __shared__ pf_u32x4 pf_smem[];   // [2 buffers][2 K-steps][X: 16 fragments x 64 lanes | W: 16 fragments x 64 lanes]
+__global__ __launch_bounds__(256, 2) void k_prefill_kv(const f16_t* __restrict__ Xt, const PrefillLayer* __restrict__ layers,
+                                                       long seq_off, int KT, int d, int M) {
+  // [2 buffers][A: 16 fragments x 64 lanes | B: 8 fragments x 64 lanes], one K-step of 32 each (24 KiB)
+  __shared__ pf_u32x4 pf_smem[2 * 1536];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.x * 256, n0 = blockIdx.y * 256;
-  const PrefillLayer L = layers[blockIdx.z];
-  const bool is_v = n0 >= d;
+  const PrefillLayer L = layers[blockIdx.y];
+  // The result tile of a workgroup is 256 rows of operand A by 128 rows of operand B.  V tiles are c W_v^T
+  // (A = memory rows = keys, B = W_v rows = dims), K tiles are W_k c^T (A = W_k rows = dims, B = keys): the
+  // two kinds differ only in where A and B come from and in the epilogue.
+  const int tiles_v = (M >> 8) * (d >> 7);
+  const bool is_v = (int)blockIdx.x < tiles_v;
+  int a0, b0;                                   // first row of the A / B operand of this tile
   // Pointers read from the table are generic to the compiler; as FLAT accesses they would count against the LDS
   // counter and every wait for an LDS read would also wait for HBM.  Say that they are global.
   typedef const __attribute__((address_space(1))) pf_u32x4* gptr_t;
-  gptr_t Xg = (gptr_t)(reinterpret_cast<const pf_u32x4*>(Xt) + (long)(m0 / 16) * KT * 64 + lane);
-  gptr_t Wg = (gptr_t)(reinterpret_cast<const pf_u32x4*>(L.W) + (long)(n0 / 16) * KT * 64 + lane);
+  gptr_t Ag, Bg;
+  if (is_v) {
+    const int t = blockIdx.x;
+    a0 = (t % (M >> 8)) * 256;
+    b0 = (t / (M >> 8)) * 128;
+    Ag = (gptr_t)(reinterpret_cast<const pf_u32x4*>(Xt) + (long)(a0 / 16) * KT * 64 + lane);
+    Bg = (gptr_t)(reinterpret_cast<const pf_u32x4*>(L.W) + (long)((d + b0) / 16) * KT * 64 + lane);
+  } else {
+    const int t = blockIdx.x - tiles_v;
+    a0 = (t % (d >> 8)) * 256;
+    b0 = (t / (d >> 8)) * 128;
+    Ag = (gptr_t)(reinterpret_cast<const pf_u32x4*>(L.W) + (long)(a0 / 16) * KT * 64 + lane);
+    Bg = (gptr_t)(reinterpret_cast<const pf_u32x4*>(Xt) + (long)(b0 / 16) * KT * 64 + lane);
+  }
+  const int capb = M >> 5;
 
-  // 4 x 4 tiles of 32 x 32 per wave (v_mfma_f32_32x32x16_f16: one wave per SIMD keeps the matrix pipe full with
-  // this shape, which it does not with back-to-back 16x16x32 issues: measured 1.85 against 1.26 PFLOP/s)
-  f32x16 acc[4][4];
+  // Per wave 128 rows of A by 64 rows of B: 4 x 2 tiles of 32 x 32 (v_mfma_f32_32x32x16_f16), 128 accumulator
+  // registers, so that two workgroups share a CU: one multiplies while the other waits at a barrier, for LDS or
+  // for its result stores (with one workgroup per CU all of them store at the same time and the matrix pipes idle).
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int a = 0; a < 4; a++)
+  for (int x = 0; x < 4; x++)
 #pragma unroll
-    for (int b = 0; b < 4; b++)
+    for (int w = 0; w < 2; w++)
 #pragma unroll
-      for (int j = 0; j < 16; j++) acc[a][b][j] = 0.f;
+      for (int j = 0; j < 16; j++) acc[x][w][j] = 0.f;
 
-  // One pipeline stage = two K-steps of 32 (64 KiB of LDS: X and W fragments of both).  The registers `rx`, `rw`
-  // carry the stage after the one in LDS: they are written to the other LDS buffer right after the barrier and
-  // refilled from global memory at once, so a load has a whole compute phase (128 MFMAs per wave) to land.
-  pf_u32x4 rx[8], rw[8];     // this thread's share: fragments wave, wave+4, wave+8, wave+12 of both K-steps
-#define PF_GLOAD(S)                                                             \
-  _Pragma("unroll") for (int j = 0; j < 8; j++) {                               \
-    const long f = (long)(wave + 4 * (j & 3)) * KT + 2 * (S) + (j >> 2);        \
-    rx[j] = Xg[f * 64];                                                         \
-    rw[j] = Wg[f * 64];                                                         \
+  // The registers carry the K-step after the one in LDS: written to the other LDS buffer right after the
+  // barrier and refilled from global memory at once.  This thread's share: X fragments wave, +4, +8, +12 and
+  // W fragments wave, +4.
+  pf_u32x4 rx[4], rw[2];
+#define PF_GLOAD(KTI)                                                           \
+  {                                                                             \
+    _Pragma("unroll") for (int j = 0; j < 4; j++) rx[j] = Ag[((long)(wave + 4 * j) * KT + (KTI)) * 64]; \
+    _Pragma("unroll") for (int j = 0; j < 2; j++) rw[j] = Bg[((long)(wave + 4 * j) * KT + (KTI)) * 64]; \
   }
 #define PF_SWRITE(ST)                                                           \
-  _Pragma("unroll") for (int j = 0; j < 8; j++) {                               \
-    pf_smem[(ST) * 4096 + (j >> 2) * 2048 + (wave + 4 * (j & 3)) * 64 + lane] = rx[j];        \
-    pf_smem[(ST) * 4096 + (j >> 2) * 2048 + 1024 + (wave + 4 * (j & 3)) * 64 + lane] = rw[j]; \
+  {                                                                             \
+    _Pragma("unroll") for (int j = 0; j < 4; j++) pf_smem[(ST) * 1536 + (wave + 4 * j) * 64 + lane] = rx[j];        \
+    _Pragma("unroll") for (int j = 0; j < 2; j++) pf_smem[(ST) * 1536 + 1024 + (wave + 4 * j) * 64 + lane] = rw[j]; \
   }
-  // P = the operand whose rows become the rows of the MFMA result, Q = the one whose rows become its columns
-  const int pbase = is_v ? wm * 512 : 1024 + wn * 512;
-  const int qbase = is_v ? 1024 + wn * 512 : wm * 512;
   // A 32-row x 16-k operand of the 32x32x16 MFMA (lane l: row l%32, k (l/32)*8..+8) is gathered from two of the
   // stored 16-row x 32-k fragments: half h of the K-step, row group (l%32)/16 -> stored lane (2h + l/32)*16 + l%16.
   const int lrow = ((lane & 31) >> 4) * 64 + (lane >> 5) * 16 + (lane & 15);
+  const int xbase = wm * 512 + lrow, wbase = 1024 + wn * 256 + lrow;
 #define PF_COMPUTE(ST)                                                          \
-  _Pragma("unroll") for (int ks = 0; ks < 2; ks++) {                            \
-    _Pragma("unroll") for (int h = 0; h < 2; h++) {                             \
-      f16x8 pf[4], qf[4];                                                       \
-      _Pragma("unroll") for (int a = 0; a < 4; a++)                             \
-        pf[a] = __builtin_bit_cast(f16x8, pf_smem[(ST) * 4096 + ks * 2048 + pbase + a * 128 + h * 32 + lrow]); \
-      _Pragma("unroll") for (int b = 0; b < 4; b++)                             \
-        qf[b] = __builtin_bit_cast(f16x8, pf_smem[(ST) * 4096 + ks * 2048 + qbase + b * 128 + h * 32 + lrow]); \
-      _Pragma("unroll") for (int a = 0; a < 4; a++)                             \
-        _Pragma("unroll") for (int b = 0; b < 4; b++)                           \
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(pf[a], qf[b], acc[a][b], 0, 0, 0); \
-    }                                                                           \
+  _Pragma("unroll") for (int h = 0; h < 2; h++) {                               \
+    f16x8 xf[4], wf[2];                                                         \
+    _Pragma("unroll") for (int x = 0; x < 4; x++)                               \
+      xf[x] = __builtin_bit_cast(f16x8, pf_smem[(ST) * 1536 + xbase + x * 128 + h * 32]); \
+    _Pragma("unroll") for (int w = 0; w < 2; w++)                               \
+      wf[w] = __builtin_bit_cast(f16x8, pf_smem[(ST) * 1536 + wbase + w * 128 + h * 32]); \
+    _Pragma("unroll") for (int x = 0; x < 4; x++)                               \
+      _Pragma("unroll") for (int w = 0; w < 2; w++)                             \
+        acc[x][w] = __builtin_amdgcn_mfma_f32_32x32x16_f16(xf[x], wf[w], acc[x][w], 0, 0, 0); \
   }
 
-  const int NS = KT >> 1;      // KT is a multiple of 8
   PF_GLOAD(0);
   PF_SWRITE(0);
   PF_GLOAD(1);
-  for (int s = 0; s < NS; s += 2) {
-    __syncthreads();           // everyone is done with LDS buffer 1; buffer 0 (stage s) is complete
-    PF_SWRITE(1);              // stage s+1 (NS is even)
-    if (s + 2 < NS) { PF_GLOAD(s + 2); }
+  for (int kt = 0; kt < KT; kt += 2) {     // KT is a multiple of 8
+    __syncthreads();           // everyone is done with LDS buffer 1; buffer 0 (step kt) is complete
+    PF_SWRITE(1);              // step kt+1
+    if (kt + 2 < KT) { PF_GLOAD(kt + 2); }
     PF_COMPUTE(0);
     __syncthreads();
-    if (s + 2 < NS) {
+    if (kt + 2 < KT) {
       PF_SWRITE(0);
-      if (s + 3 < NS) { PF_GLOAD(s + 3); }
+      if (kt + 3 < KT) { PF_GLOAD(kt + 3); }
     }
     PF_COMPUTE(1);
   }
@@ -100,36 +114,37 @@ __global__ __launch_bounds__(256) void k_prefill_kv(const f16_t* __restrict__ Xt
 #undef PF_SWRITE
 #undef PF_COMPUTE
 
-  // epilogue: halves into the blocked cache layouts.  Result tile (a, b): lane l owns column l%32 (a row of Q) and
-  // the P rows (j/4)*8 + (l/32)*4 + j%4, j = 0..15, i.e. four runs of four consecutive rows.
+  // epilogue: halves into the blocked cache layouts.  In a result tile lane l owns column l%32 (a row of B) and
+  // the A rows (j/4)*8 + (l/32)*4 + j%4, j = 0..15, i.e. four runs of four consecutive rows.
   const int hl4 = (lane >> 5) * 4, c32 = lane & 31;
   typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
   typedef _Float16 f16x8o __attribute__((ext_vector_type(8)));
 #pragma unroll
-  for (int a = 0; a < 4; a++) {
+  for (int x = 0; x < 4; x++) {
 #pragma unroll
-    for (int b = 0; b < 4; b++) {
+    for (int w = 0; w < 2; w++) {
+      const int col = b0 + wn * 64 + w * 32 + c32;
+      const int row0 = a0 + wm * 128 + x * 32 + hl4;
       if (is_v) {
-        // keys r..r+3 and r+16..r+19 of a block sit next to each other in the V layout: runs j/4 = q and q+2
-        const int e = n0 - d + wn * 128 + b * 32 + c32;               // dim within the V projection
-        f16_t* base = L.Vm + seq_off + (long)(e >> 6) * capb * 2048;
+        // rows = keys, column = dim.  Keys r..r+3 and r+16..r+19 of a block sit next to each other in the V
+        // layout: runs j/4 = q and q+2 make one 16-byte store
+        f16_t* base = L.Vm + seq_off + (long)(col >> 6) * capb * 2048;
 #pragma unroll
         for (int q = 0; q < 2; q++) {
-          const int key0 = m0 + wm * 128 + a * 32 + q * 8 + hl4;
           f16x8o o;
 #pragma unroll
-          for (int i = 0; i < 4; i++) { o[i] = (f16_t)acc[a][b][q * 4 + i]; o[4 + i] = (f16_t)acc[a][b][(q + 2) * 4 + i]; }
-          *(__attribute__((address_space(1))) f16x8o*)(base + vblk_off(key0, e & 63)) = o;
+          for (int i = 0; i < 4; i++) { o[i] = (f16_t)acc[x][w][q * 4 + i]; o[4 + i] = (f16_t)acc[x][w][(q + 2) * 4 + i]; }
+          *(__attribute__((address_space(1))) f16x8o*)(base + vblk_off(row0 + q * 8, col & 63)) = o;
         }
       } else {
-        const int key = m0 + wm * 128 + b * 32 + c32;
+        // rows = dims (four consecutive ones = one 8-byte store), column = key
 #pragma unroll
         for (int q = 0; q < 4; q++) {
-          const int e0 = n0 + wn * 128 + a * 32 + q * 8 + hl4;        // dims e0 .. e0+3 of the K projection
+          const int e0 = row0 + q * 8;
           f16x4 o;
 #pragma unroll
-          for (int i = 0; i < 4; i++) o[i] = (f16_t)acc[a][b][q * 4 + i];
-          *(__attribute__((address_space(1))) f16x4*)(L.Km + seq_off + (long)(e0 >> 6) * capb * 2048 + kblk_off(key, e0 & 63)) = o;
+          for (int i = 0; i < 4; i++) o[i] = (f16_t)acc[x][w][q * 4 + i];
+          *(__attribute__((address_space(1))) f16x4*)(L.Km + seq_off + (long)(e0 >> 6) * capb * 2048 + kblk_off(col, e0 & 63)) = o;
         }
       }
     }
