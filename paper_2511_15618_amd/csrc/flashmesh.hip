@@ -375,8 +375,8 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
     // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
     f16_t* Xt = (f16_t*)c->stage;
     hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
-    hipLaunchKernelGGL(k_prefill_kv, dim3((D.M / 256) * (d / 128) + (d / 256) * (D.M / 128), c->pf_n), dim3(256), 0, c->stream,
-                       (const f16_t*)Xt, (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M);
+    hipLaunchKernelGGL(k_prefill_kv, dim3(512), dim3(256), 0, c->stream,
+                       (const f16_t*)Xt, (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M, c->pf_n);
     hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
     HIPCHK(c, hipGetLastError());
     return FM_OK;

@@ -23,30 +23,38 @@ typedef unsigned pf_u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __global__ __launch_bounds__(256, 2) void k_prefill_kv(const f16_t* __restrict__ Xt, const PrefillLayer* __restrict__ layers,
-                                                       long seq_off, int KT, int d, int M) {
+                                                       long seq_off, int KT, int d, int M, int n_layers) {
   // [2 buffers][A: 16 fragments x 64 lanes | B: 8 fragments x 64 lanes], one K-step of 32 each (24 KiB)
   __shared__ pf_u32x4 pf_smem[2 * 1536];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
-  const PrefillLayer L = layers[blockIdx.y];
+  const int tiles_layer = (M >> 8) * (d >> 7) + (d >> 8) * (M >> 7);
+  // lrow: see PF_COMPUTE below
+  const int lrow = ((lane & 31) >> 4) * 64 + (lane >> 5) * 16 + (lane & 15);
+  const int xbase = wm * 512 + lrow, wbase = 1024 + wn * 256 + lrow;
+  // A workgroup walks over tiles (two workgroups per CU are launched): the result stores of one tile are only
+  // issued, not waited for, so they drain while the next tile is multiplied.
+  for (int tile = blockIdx.x; tile < tiles_layer * n_layers; tile += gridDim.x) {
+  const PrefillLayer L = layers[tile / tiles_layer];
+  const int tl = tile % tiles_layer;
   // The result tile of a workgroup is 256 rows of operand A by 128 rows of operand B.  V tiles are c W_v^T
   // (A = memory rows = keys, B = W_v rows = dims), K tiles are W_k c^T (A = W_k rows = dims, B = keys): the
   // two kinds differ only in where A and B come from and in the epilogue.
   const int tiles_v = (M >> 8) * (d >> 7);
-  const bool is_v = (int)blockIdx.x < tiles_v;
+  const bool is_v = tl < tiles_v;
   int a0, b0;                                   // first row of the A / B operand of this tile
   // Pointers read from the table are generic to the compiler; as FLAT accesses they would count against the LDS
   // counter and every wait for an LDS read would also wait for HBM.  Say that they are global.
   typedef const __attribute__((address_space(1))) pf_u32x4* gptr_t;
   gptr_t Ag, Bg;
   if (is_v) {
-    const int t = blockIdx.x;
+    const int t = tl;
     a0 = (t % (M >> 8)) * 256;
     b0 = (t / (M >> 8)) * 128;
     Ag = (gptr_t)(reinterpret_cast<const pf_u32x4*>(Xt) + (long)(a0 / 16) * KT * 64 + lane);
     Bg = (gptr_t)(reinterpret_cast<const pf_u32x4*>(L.W) + (long)((d + b0) / 16) * KT * 64 + lane);
   } else {
-    const int t = blockIdx.x - tiles_v;
+    const int t = tl - tiles_v;
     a0 = (t % (d >> 8)) * 256;
     b0 = (t / (d >> 8)) * 128;
     Ag = (gptr_t)(reinterpret_cast<const pf_u32x4*>(L.W) + (long)(a0 / 16) * KT * 64 + lane);
@@ -81,8 +89,6 @@ __global__ __launch_bounds__(256, 2) void k_prefill_kv(const f16_t* __restrict__
   }
   // A 32-row x 16-k operand of the 32x32x16 MFMA (lane l: row l%32, k (l/32)*8..+8) is gathered from two of the
   // stored 16-row x 32-k fragments: half h of the K-step, row group (l%32)/16 -> stored lane (2h + l/32)*16 + l%16.
-  const int lrow = ((lane & 31) >> 4) * 64 + (lane >> 5) * 16 + (lane & 15);
-  const int xbase = wm * 512 + lrow, wbase = 1024 + wn * 256 + lrow;
 #define PF_COMPUTE(ST)                                                          \
   _Pragma("unroll") for (int h = 0; h < 2; h++) {                               \
     f16x8 xf[4], wf[2];                                                         \
@@ -149,4 +155,5 @@ __global__ __launch_bounds__(256, 2) void k_prefill_kv(const f16_t* __restrict__
       }
     }
   }
+  }   // tile loop
 }
