@@ -228,6 +228,8 @@ def main():
     else:
         kernel = "verify pass at half context (all launches of fm_verify_block, one per operator)"
 
+    measured = fm.measure_peaks()
+
     result = {
         "metric": f"mesh tokens/sec, batch {cfg.batch} (replay drafts p={REPLAY_P}, all heads executed)",
         "value": tokens / ms * 1e3,
@@ -248,11 +250,13 @@ def main():
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,
                    "native_heads_ms_per_step": st_native.ms_total / max(st_native.steps, 1),
                    "sequential_tokens_per_s": st_seq.tokens / st_seq.ms_total * 1e3,
-                   "sequential_prefix_faces": seq_faces, "host_wall_s": wall, "prefill": prefill},
+                   "sequential_prefix_faces": seq_faces, "host_wall_s": wall, "prefill": prefill,
+                   "measured_on_this_gpu": measured},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": counter_traffic(args.config, fm.verify_path() == 1) if faces == cfg.faces else None,
-                     "algorithmic_bytes": bytes_mid, "ms": ms_verify},
+                     "algorithmic_bytes": bytes_mid, "ms": ms_verify,
+                     "frac_of_measured_read_rate": achieved / measured["hbm_read_GBs"]},
     }
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(cfg, weights, mems[0], args.cpu_seconds)

@@ -145,6 +145,11 @@ int fm_debug_profile(fm_ctx* ctx, uint64_t* host_out, int32_t n);
  * Synchronises. */
 int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
 
+/* What this GPU sustains, for reporting next to the published peaks: HOST out[0] = streaming read GB/s, out[1] =
+ * streaming copy GB/s (read + write bytes), out[2] = register-only MFMA loop TFLOP/s (fp16, 32x32x16).  Allocates
+ * and frees 2 GiB of device memory for the duration of the call.  Synchronises. */
+int fm_measure_peaks(fm_ctx* ctx, double* host_out);
+
 /* Which implementation fm_verify_block runs for this context: 1 = the single persistent kernel (half-precision
  * storage, one sequence, block <= 16), 0 = one launch per operator.  Both compute the same function with the same
  * arithmetic per operator; they cut the key axis of the attention differently, so results agree to rounding, and

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
            "fm_set_draft_replay", "fm_set_budget", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile",
-           "fm_verify_path"]
+           "fm_verify_path", "fm_measure_peaks"]
 
 
 class LibraryMissing(RuntimeError):
@@ -62,6 +62,7 @@ def load_library():
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_debug_ring.argtypes = [p, i32, p]
     lib.fm_debug_profile.argtypes = [p, p, i32]
+    lib.fm_measure_peaks.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_verify_path.argtypes = [p]
     lib.fm_verify_path.restype = i32
     for n in EXPORTS:
@@ -183,6 +184,11 @@ class FlashMesh:
         out = np.zeros(n, np.uint64)
         self._chk(self.lib.fm_debug_profile(self.h, C.c_void_p(out.ctypes.data), n), "fm_debug_profile")
         return out
+
+    def measure_peaks(self) -> dict:
+        v = (C.c_double * 3)()
+        self._chk(self.lib.fm_measure_peaks(self.h, v), "fm_measure_peaks")
+        return {"hbm_read_GBs": v[0], "hbm_copy_GBs": v[1], "mfma_f16_TFLOPs": v[2]}
 
     def verify_path(self) -> int:
         return int(self.lib.fm_verify_path(self.h))

@@ -876,6 +876,51 @@ int fm_verify_bytes(fm_ctx* c, double* host_bytes) {
   return FM_OK;
 }
 
+int fm_measure_peaks(fm_ctx* c, double* host_out) {
+  if (!c || !host_out) return FM_EINVAL;
+  const size_t bytes = (size_t)1 << 30;
+  float4 *a = nullptr, *b = nullptr;
+  float* sink = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  int rc = FM_OK;
+  auto cleanup = [&]() {
+    if (a) (void)hipFree(a);
+    if (b) (void)hipFree(b);
+    if (sink) (void)hipFree(sink);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+#define PK_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(c, FM_EHIP, "peak probe: %s failed", #x); } } while (0)
+  PK_TRY(hipStreamSynchronize(c->stream));
+  PK_TRY(hipMalloc((void**)&a, bytes)); PK_TRY(hipMalloc((void**)&b, bytes)); PK_TRY(hipMalloc((void**)&sink, 1024 * 256 * 4));
+  PK_TRY(hipMemsetAsync(a, 0, bytes, c->stream)); PK_TRY(hipMemsetAsync(b, 0, bytes, c->stream));
+  PK_TRY(hipEventCreate(&e0)); PK_TRY(hipEventCreate(&e1));
+  const long n16 = (long)(bytes / 16);
+  const int reps = 5, iters = 4000, wgs = 1024;
+  float ms = 0.f;
+  // streaming read
+  hipLaunchKernelGGL(k_probe_read, dim3(2048), dim3(256), 0, c->stream, a, sink, n16);
+  PK_TRY(hipEventRecord(e0, c->stream));
+  for (int i = 0; i < reps; i++) hipLaunchKernelGGL(k_probe_read, dim3(2048), dim3(256), 0, c->stream, a, sink, n16);
+  PK_TRY(hipEventRecord(e1, c->stream)); PK_TRY(hipEventSynchronize(e1)); PK_TRY(hipEventElapsedTime(&ms, e0, e1));
+  host_out[0] = (double)bytes * reps / (ms * 1e-3) / 1e9;
+  // streaming copy (read + write bytes)
+  hipLaunchKernelGGL(k_probe_copy, dim3(32768), dim3(256), 0, c->stream, a, b, n16);
+  PK_TRY(hipEventRecord(e0, c->stream));
+  for (int i = 0; i < reps; i++) hipLaunchKernelGGL(k_probe_copy, dim3(32768), dim3(256), 0, c->stream, a, b, n16);
+  PK_TRY(hipEventRecord(e1, c->stream)); PK_TRY(hipEventSynchronize(e1)); PK_TRY(hipEventElapsedTime(&ms, e0, e1));
+  host_out[1] = 2.0 * (double)bytes * reps / (ms * 1e-3) / 1e9;
+  // MFMA loop
+  hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, c->stream, sink, 100);
+  PK_TRY(hipEventRecord(e0, c->stream));
+  hipLaunchKernelGGL(k_probe_mfma, dim3(wgs), dim3(256), 0, c->stream, sink, iters);
+  PK_TRY(hipEventRecord(e1, c->stream)); PK_TRY(hipEventSynchronize(e1)); PK_TRY(hipEventElapsedTime(&ms, e0, e1));
+  host_out[2] = 2.0 * 32 * 32 * 16 * 8.0 * iters * 4.0 * wgs / (ms * 1e-3) / 1e12;
+#undef PK_TRY
+  cleanup();
+  return rc;
+}
+
 int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_tok, int32_t* out_len, fm_stats* stats) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");

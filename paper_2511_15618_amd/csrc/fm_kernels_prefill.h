@@ -157,3 +157,39 @@ __global__ __launch_bounds__(256, 2) void k_prefill_kv(const f16_t* __restrict__
   }
   }   // tile loop
 }
+
+// ------------------------------------------------------------------------------------------
+// Probes of what this chip sustains, to put next to the published peaks: a streaming read, a streaming copy and
+// a register-only MFMA loop (32x32x16 f16, 8 independent accumulators per wave, 4 waves per workgroup).
+// ------------------------------------------------------------------------------------------
+__global__ void k_probe_read(const float4* __restrict__ src, float* __restrict__ sink, long n) {
+  float s = 0.f;
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) {
+    const float4 v = src[i];
+    s += v.x + v.y + v.z + v.w;
+  }
+  if (s == 1.2345e30f) sink[0] = s;    // keeps the loads alive; never true for the zero-filled buffer
+}
+__global__ void k_probe_copy(const float4* __restrict__ src, float4* __restrict__ dst, long n) {
+  for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+__global__ __launch_bounds__(256) void k_probe_mfma(float* __restrict__ sink, int iters) {
+  f32x16 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+#pragma unroll
+    for (int j = 0; j < 16; j++) acc[i][j] = 0.f;
+  f16x8 a, b;
+#pragma unroll
+  for (int j = 0; j < 8; j++) { a[j] = (f16_t)(threadIdx.x * 0.001f + j); b[j] = (f16_t)(j * 0.5f - threadIdx.x * 0.002f); }
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; i++)
+#pragma unroll
+    for (int j = 0; j < 16; j++) s += acc[i][j];
+  sink[blockIdx.x * 256 + threadIdx.x] = s;
+}
