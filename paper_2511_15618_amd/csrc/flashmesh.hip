@@ -99,6 +99,7 @@ struct fm_ctx {
   int* host_flag;          // pinned: [0] alive flag, [1..S] lagged copy of the committed lengths
   std::vector<int> len_bound;   // host upper bound on each sequence's committed coordinate length
   long commits = 0;             // fm_commit calls so far
+  bool sticky_error = false;    // a launch wrapper refused its arguments (message in err); reported by the entry point
   // persistent verify kernel (one sequence, block <= 16, half-precision path)
   bool persist;
   PkArgs pk;
@@ -167,6 +168,8 @@ void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, 
           const float* R, long ldr, long gsr, int M, int N, int K, int groups, const int* flag) {
   GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag};
   if (mfma_gemm_launch<T>(c->mres, a, epi, groups, c->stream)) return;
+  // the plain kernel reads row-major weights: only the fp32 path has those
+  if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "gemm: unsupported shape M=%d N=%d K=%d", M, N, K); c->sticky_error = true; return; }
   dim3 grid((N + 3) / 4, groups);
   if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_simple<T, EPI_F32>), grid, dim3(256), 0, c->stream, a);
   else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_simple<T, EPI_GELU_T>), grid, dim3(256), 0, c->stream, a);
@@ -177,6 +180,8 @@ template <typename T>
 void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
                long seq_stride, int cap, void* out, const int* flag, bool dense = false, int key_bound = 1 << 30) {
   if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, c->stream)) return;
+  // the plain kernel reads row-major caches: only the fp32 path has those
+  if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "attention: unsupported row set (%d rows, %d per sequence)", rows, RPS); c->sticky_error = true; return; }
   hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
                      (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag);
 }
@@ -778,15 +783,17 @@ int fm_draft(fm_ctx* c, int32_t* block_tok, int32_t* block_len) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
   if (!block_tok || !block_len) return fail(c, FM_EINVAL, "null block buffer");
-  return c->bf16 ? draft_impl<f16_t>(c, block_tok, block_len, 1) : draft_impl<float>(c, block_tok, block_len, 1);
+  const int rc = c->bf16 ? draft_impl<f16_t>(c, block_tok, block_len, 1) : draft_impl<float>(c, block_tok, block_len, 1);
+  return rc == FM_OK && c->sticky_error ? FM_EINVAL : rc;
 }
 
 int fm_verify_block(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits, int32_t* accepted) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
   if (!block_tok || !block_len || !accepted) return fail(c, FM_EINVAL, "null block / accepted buffer");
-  return c->bf16 ? verify_impl<f16_t>(c, block_tok, block_len, logits, accepted)
-                 : verify_impl<float>(c, block_tok, block_len, logits, accepted);
+  const int rc = c->bf16 ? verify_impl<f16_t>(c, block_tok, block_len, logits, accepted)
+                         : verify_impl<float>(c, block_tok, block_len, logits, accepted);
+  return rc == FM_OK && c->sticky_error ? FM_EINVAL : rc;
 }
 
 int fm_commit(fm_ctx* c, const int32_t* accepted) {
@@ -945,6 +952,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
       rc = c->bf16 ? verify_impl<f16_t>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc)
                    : verify_impl<float>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc);
     if (rc == FM_OK) rc = fm_commit(c, c->gen_acc);
+    if (rc == FM_OK && c->sticky_error) rc = FM_EINVAL;
     if (rc != FM_OK) break;
     if ((step + 1) % check_every == 0) {
       // look at the flag copied one interval ago, then queue the next copy: the device never waits for the host

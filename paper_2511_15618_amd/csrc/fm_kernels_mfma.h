@@ -378,7 +378,7 @@ __device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float*
 
 // Workspace per (sequence, head): [nsplit][QT*16*64 unnormalised O | QT*16 running max (log2 units) | QT*16 sums]
 template <int QT>
-__global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS,
+__global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS, int RS,
                                                     const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
                                                     long seq_stride, int capb, f16_t* __restrict__ out, int H,
                                                     float* __restrict__ ws, unsigned* __restrict__ counters,
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   for (int t = 0; t < QT; t++) {
     const int qi = t * 16 + ql;
     const bool on = qi < RPS;
-    const long row = (long)s * RPS + (on ? qi : 0);
+    const long row = (long)s * RS + (on ? qi : 0);     // RS = rows per sequence in the buffers (>= RPS)
     lim[t] = on ? limit[row] : -1;
     maxlim = max(maxlim, lim[t]);
     const f16_t* qp = q + row * d + hh * FM_HD + g * 8;
@@ -531,7 +531,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
       den += ll[w][qi] * f;
     }
     if (nsplit == 1) {
-      if (qi < RPS) out[((long)s * RPS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
+      if (qi < RPS) out[((long)s * RS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
     } else if (defer_merge) {
       part[e] = num;
       if (dim == 0) { part[NQ * 64 + qi] = M; part[NQ * 64 + NQ + qi] = den; }
@@ -551,13 +551,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   __syncthreads();
   if (!s_last) return;
   // last workgroup of this (sequence, head)
-  attn_merge<QT, true>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RPS * d + hh * FM_HD, d);
+  attn_merge<QT, true>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * FM_HD, d);
 }
 
 // Second launch of the deferred form: one workgroup per (head, sequence) derives the split count exactly as the
 // first launch did and merges; (sequence, head) pairs that fitted one split were already written there.
 template <int QT>
-__global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limit, int RPS, int capb, int nsplit_cfg,
+__global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limit, int RPS, int RS, int capb, int nsplit_cfg,
                                                      f16_t* __restrict__ out, int H, const float* __restrict__ ws,
                                                      const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
@@ -567,13 +567,13 @@ __global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limi
   const int hh = blockIdx.x, s = blockIdx.y;
   const int d = H * FM_HD;
   int maxlim = -1;
-  for (int qi = 0; qi < RPS; qi++) maxlim = max(maxlim, limit[(long)s * RPS + qi]);
+  for (int qi = 0; qi < RPS; qi++) maxlim = max(maxlim, limit[(long)s * RS + qi]);
   const int nblk = (maxlim + 32) >> 5;
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   if (nsplit == 1) return;
   const long sh = (long)s * H + hh;
-  attn_merge<QT, false>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RPS * d + hh * FM_HD, d);
+  attn_merge<QT, false>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * FM_HD, d);
 }
 
 inline size_t mfma_attn_ws_floats(int S, int H) {
@@ -589,7 +589,7 @@ template <>
 inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int* limit, int rows, int RPS, const void* Kc,
                                     const void* Vc, long seq_stride, int cap, void* out, int H, const int* flag,
                                     bool dense, int key_bound, hipStream_t st) {
-  if (RPS > 32 || rows % RPS != 0) return false;
+  if (RPS < 1 || rows % RPS != 0) return false;
   const int S = rows / RPS;
   const int capb = (cap + 31) / 32;
   // The key axis is cut into fixed ranges of at least 8 blocks (two per wave).  A growing cache is far below
@@ -612,14 +612,22 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
   // write-back, and those queue up per XCD).  Then the partials go out as plain stores and a second, tiny
   // launch merges them; the arithmetic is the same either way.
   const int defer = (launched > 1 && (long)launched * H * S > 256) ? 1 : 0;
-  if (RPS <= 16) {
-    hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
-                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
-    if (defer) hipLaunchKernelGGL((k_attn_merge<1>), dim3(H, S), dim3(256), 0, st, limit, RPS, capb, nsplit, (f16_t*)out, H, res.attn_ws, flag);
-  } else {
-    hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, (const f16_t*)q, limit, RPS, (const f16_t*)Kc,
-                       (const f16_t*)Vc, seq_stride, capb, (f16_t*)out, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
-    if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, limit, RPS, capb, nsplit, (f16_t*)out, H, res.attn_ws, flag);
+  // at most 32 query rows of a sequence per launch; longer row sets go out in chunks
+  const int d = H * FM_HD;
+  for (int r0 = 0; r0 < RPS; r0 += 32) {
+    const int rc = RPS - r0 < 32 ? RPS - r0 : 32;
+    const f16_t* qc = (const f16_t*)q + (long)r0 * d;
+    const int* lc = limit + r0;
+    f16_t* oc = (f16_t*)out + (long)r0 * d;
+    if (rc <= 16) {
+      hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc,
+                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
+      if (defer) hipLaunchKernelGGL((k_attn_merge<1>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
+    } else {
+      hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc,
+                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
+      if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
+    }
   }
   return true;
 }

@@ -98,6 +98,12 @@ TEST_CONFIGS = {
     "t_bf16_99_b1": Config("t_bf16_99_b1", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9),
     "t_bf16_99_b1w": Config("t_bf16_99_b1w", 256, 4, 64, 2, 1, 2, 2, 3, 100, "bf16", 1, 30, 2, 9, 9),
     "t_bf16_99_b8long": Config("t_bf16_99_b8long", 256, 4, 64, 2, 1, 2, 2, 3, 100, "bf16", 8, 256, 2, 9, 9),
+    # draft-count variants of the paper's sweep (face-point counts 18-18, 18-12, 27-9, 27-27) and coordinate-only heads
+    "t_f32_1818": Config("t_f32_1818", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 10, 2, 18, 18),
+    "t_bf16_1812": Config("t_bf16_1812", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 2, 10, 2, 12, 18),
+    "t_bf16_279": Config("t_bf16_279", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 27),
+    "t_f32_2727": Config("t_f32_2727", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 12, 2, 27, 27),
+    "t_bf16_c17": Config("t_bf16_c17", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 2, 8, 17, 0, 0),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
 }
 
