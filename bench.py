@@ -80,6 +80,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--faces", type=int, default=0, help="override the face budget (0 = the configuration's)")
+    ap.add_argument("--draft", default="", help="override the draft counts: Dc,m,n (coordinate heads, point tokens, face tokens)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--counter-pass", action="store_true",
@@ -97,6 +98,9 @@ def main():
     from paper_2511_15618_amd.binding import config_struct
 
     cfg = si.CONFIGS[args.config]
+    if args.draft:
+        dc, m, n = (int(v) for v in args.draft.split(","))
+        cfg = cfg.replace(draft_coord=dc, draft_point=m, draft_face=n)
     faces = args.faces or cfg.faces
     weights = si.make_weights(cfg, 0)
     fm = FlashMesh(config_struct(cfg))
@@ -244,7 +248,7 @@ def main():
         "dtype": "f16 (bf16-valued weights held as half, fp32 accumulate)",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: d={cfg.d_model}, {cfg.n_layers} blocks, batch {cfg.batch}, "
-                               f"{faces} faces ({9 * faces} tokens), block {cfg.block_max}",
+                               f"{faces} faces ({9 * faces} tokens), block {cfg.block_max}, draft counts Dc={cfg.draft_coord} m={cfg.draft_point} n={cfg.draft_face}",
                    "draft_source": f"replay p={REPLAY_P}", "tokens": tokens, "mean_accepted": tokens / max(steps, 1),
                    "accepted_hist": hist, "stream_equals_native_run": same,
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,

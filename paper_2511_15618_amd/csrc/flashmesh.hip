@@ -624,10 +624,8 @@ int build_buffers(fm_ctx* c) {
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
-  c->mres = MfmaRes{nullptr, nullptr, nullptr, nullptr, 0};
+  c->mres = MfmaRes{nullptr, nullptr, 0};
   if (c->bf16) {
-    TRY(dalloc(c, &c->mres.gemm_ws, (size_t)FM_GEMM_WS_FLOATS, false));
-    TRY(dalloc(c, &c->mres.gemm_counters, (size_t)FM_GEMM_COUNTERS));
     c->mres.attn_ws_floats = mfma_attn_ws_floats(D.S, D.H);
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
     TRY(dalloc(c, &c->mres.attn_counters, (size_t)D.S * D.H));

@@ -2,11 +2,13 @@
 //
 //  * k_gemm_mfma : skinny weight-streaming GEMM.  Weights are pre-tiled at load time into MFMA
 //                  B-operand order so that every wave load is one contiguous 1 KiB burst; the four
-//                  waves of a workgroup split K, reduce through LDS, and K is further split across
-//                  workgroups with a deterministic last-arriver reduction (fixed summation order).
-//  * k_attn_mfma : block attention over a K/V cache (flash-decoding): keys split across workgroups
-//                  and waves, online softmax in fp32, P kept in registers between the two MFMAs by
-//                  storing V in a blocked, slot-permuted transposed layout.
+//                  waves of a workgroup split K and reduce through LDS in a fixed order.  K is not
+//                  split across workgroups: publishing partial sums inside a launch needs an
+//                  agent-scope release fence, which costs more than the parallelism gains here.
+//  * k_attn_mfma : block attention over a K/V cache (flash-decoding): fixed key ranges split across
+//                  workgroups and waves, online softmax in fp32, P kept in registers between the two
+//                  MFMAs by storing V in a blocked, slot-permuted transposed layout; partial results
+//                  merged in range order (in the launch, or by k_attn_merge when there are many).
 //
 // MFMA 16x16x32 operand layout (lane l of 64):
 //   A[16 x 32]: row l%16, k = (l/16)*8 .. +8      B[32 x 16]: col l%16, k = (l/16)*8 .. +8
@@ -31,8 +33,6 @@ __device__ __forceinline__ float ld_agent(const float* p) {
 }
 __device__ __forceinline__ void publish_fence() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 
-#define FM_GEMM_WS_FLOATS (48u << 20)   // split-K partials (192 MiB)
-#define FM_GEMM_COUNTERS 65536
 #define FM_ATTN_MAX_SPLIT 64
 
 // ------------------------------------------------------------------------------------------
@@ -123,19 +123,14 @@ __global__ void k_tile_weight(const float* __restrict__ src, f16_t* __restrict__
 // so an MFMA guarded by a condition the compiler takes for divergent would run on a false guard as well.
 struct GemmSplit {
   int kt_per_wave;   // K fragments (of 32) each wave walks
-  int ksplit;        // workgroups along K (each covers 4 * kt_per_wave fragments)
-  float* ws;         // [group*mblocks][ksplit][MT*16][Npad]
-  unsigned* counters;
-  int Npad;
 };
 
 template <int MT, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   if (a.run_flag && *a.run_flag == 0) return;
   __shared__ f32x4 red[4][MT][64];
-  __shared__ int s_last;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int nt = blockIdx.x, ks = blockIdx.y;
+  const int nt = blockIdx.x;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
   const int g = blockIdx.z / nmb, mb = blockIdx.z % nmb;
   const int KT = a.K / 32;
@@ -153,7 +148,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   f32x4 acc[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  const int kt0 = (ks * 4 + wave) * sp.kt_per_wave;
+  const int kt0 = wave * sp.kt_per_wave;
   const int kt1 = min(kt0 + sp.kt_per_wave, KT);
 
   // K is walked in chunks of U fragments; the loads of the next chunk are in flight while this one is
@@ -197,42 +192,10 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   for (int mt = 0; mt < MT; mt++) red[wave][mt][lane] = acc[mt];
   __syncthreads();
   const int n = nt * 16 + (lane & 15);
-  const long tile = (long)blockIdx.z * gridDim.x + nt;
-  bool last = true;
-  if (sp.ksplit > 1) {
-    // publish this workgroup's partial, then find out whether it is the last one for the tile
-    for (int mt = wave; mt < MT; mt += 4) {
-      f32x4 v = red[0][mt][lane];
-#pragma unroll
-      for (int w = 1; w < 4; w++) v += red[w][mt][lane];
-      float* p = sp.ws + ((tile * sp.ksplit + ks) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
-      for (int i = 0; i < 4; i++) st_agent(p + i * 16, v[i]);
-    }
-    publish_fence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const unsigned old = __hip_atomic_fetch_add(&sp.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_last = (old == (unsigned)sp.ksplit - 1);
-      if (s_last) __hip_atomic_store(&sp.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // nobody else touches it until the next launch
-    }
-    __syncthreads();
-    last = s_last != 0;
-  }
-  if (!last) return;
   for (int mt = wave; mt < MT; mt += 4) {
-    f32x4 v;
-    if (sp.ksplit > 1) {
-      v = f32x4{0.f, 0.f, 0.f, 0.f};
-      for (int k2 = 0; k2 < sp.ksplit; k2++) {   // fixed order: deterministic sums
-        const float* p = sp.ws + ((tile * sp.ksplit + k2) * (MT * 16) + mt * 16 + (lane >> 4) * 4) * 16 + (lane & 15);
+    f32x4 v = red[0][mt][lane];
 #pragma unroll
-        for (int i = 0; i < 4; i++) v[i] += ld_agent(p + i * 16);
-      }
-    } else {
-      v = red[0][mt][lane];
-#pragma unroll
-      for (int w = 1; w < 4; w++) v += red[w][mt][lane];
-    }
+    for (int w = 1; w < 4; w++) v += red[w][mt][lane];
     if (n < a.N) {
 #pragma unroll
       for (int i = 0; i < 4; i++) {
@@ -252,8 +215,6 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
 }
 
 struct MfmaRes {      // per-context resources of the MFMA kernels
-  float* gemm_ws;
-  unsigned* gemm_counters;
   float* attn_ws;
   unsigned* attn_counters;
   size_t attn_ws_floats;
@@ -276,11 +237,8 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   const int mtiles = (a.M + 15) / 16;
   const int MT = mtiles <= 1 ? 1 : mtiles <= 2 ? 2 : mtiles <= 3 ? 3 : mtiles <= 5 ? 5 : 8;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
-  // The four waves of a workgroup split K; K is NOT split across workgroups (the kernel supports it, but
-  // the publication fence it needs costs more than the extra parallelism gains at these sizes).
-  const int kt_per_wave = (KT + 3) / 4, ksplit = 1;
-  GemmSplit sp{kt_per_wave, ksplit, res.gemm_ws, res.gemm_counters, Npad};
-  dim3 grid(NT, ksplit, groups * nmb);
+  GemmSplit sp{(KT + 3) / 4};      // the four waves of a workgroup split K
+  dim3 grid(NT, 1, groups * nmb);
   switch (MT) {
     case 1: gemm_mfma_dispatch<1>(a, sp, epi, grid, st); break;
     case 2: gemm_mfma_dispatch<2>(a, sp, epi, grid, st); break;
