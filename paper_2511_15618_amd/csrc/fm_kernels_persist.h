@@ -189,7 +189,7 @@ __device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, un
 extern __shared__ unsigned pk_panel[];
 
 __device__ __forceinline__ bool pk_panel_load(const PkArgs& a, const u64* A, int lda, int R, int KE, unsigned tag, int stage) {
-  const int total = R * KE, ldp = KE + 4;
+  const int ldp = KE + 4;
   const u64 t0 = wall_clock64();
   int it = 0;
   bool good = true;
@@ -206,32 +206,34 @@ __device__ __forceinline__ bool pk_panel_load(const PkArgs& a, const u64* A, int
     __builtin_amdgcn_s_sleep(4);
   }
   // phase 2: everything, as 16-byte agent-scope loads (two tagged elements each; measured 5x the throughput
-  // of 8-byte ones), up to 32 per thread in flight.  The loads are inline asm, so the wait for them is
-  // explicit and every destination is passed through an empty asm afterwards to pin its uses behind the wait.
+  // of 8-byte ones).  Slot i of a thread is row i/2, columns 2*(threadIdx.x + 256*(i%2)) and the next one: all
+  // index arithmetic is compile-time or a shift (a division per load here once cost more than the loads).  The
+  // loads are inline asm, so the wait for them is explicit and every destination is passed through an empty asm
+  // afterwards to pin its uses behind the wait.  Host side guarantees R <= 16 and KE <= 1024.
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   PK_MARK(1);
-  const int units = total >> 1;            // KE is even, rows are contiguous
-  for (int base = 0; good && base < units; base += 256 * 32) {
+  if (good) {
     u32x4 v[32];
     while (true) {
 #pragma unroll
       for (int i = 0; i < 32; i++) {
-        const int idx = base + i * 256 + threadIdx.x;
-        v[i] = u32x4{0u, 0u, 0u, 0u};
-        if (idx < units) {
-          const int e = 2 * idx, row = e / KE;
-          const u64* p = A + (long)row * lda + (e - row * KE);
+        const int r = i >> 1, c = ((int)threadIdx.x + 256 * (i & 1)) * 2;
+        v[i] = u32x4{tag, tag, tag, tag};
+        if (r < R && c < KE) {
+          const u64* p = A + (long)r * lda + c;
           asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[i]) : "v"(p) : "memory");
         }
       }
+      PK_MARK(4);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      PK_MARK(5);
       bool ok = true;
 #pragma unroll
       for (int i = 0; i < 32; i++) {
         asm volatile("" : "+v"(v[i]));
-        const int idx = base + i * 256 + threadIdx.x;
-        if (idx < units) ok = ok && v[i][1] == tag && v[i][3] == tag;
+        ok = ok && v[i][1] == tag && v[i][3] == tag;      // unused slots were preset to the tag
       }
+      if (a.prof && (threadIdx.x & 63) == 0) atomicAdd(a.prof + (__all(ok) ? 701 : 700), 1ull);   // complete / incomplete reads
       if (__all(ok)) break;
       if ((++it & 3) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
       __builtin_amdgcn_s_sleep(2);
@@ -239,16 +241,12 @@ __device__ __forceinline__ bool pk_panel_load(const PkArgs& a, const u64* A, int
     if (good) {
 #pragma unroll
       for (int i = 0; i < 32; i++) {
-        const int idx = base + i * 256 + threadIdx.x;
-        if (idx < units) {
-          const int e = 2 * idx, row = e / KE;
-          unsigned* dst = &pk_panel[row * ldp + (e - row * KE)];
-          dst[0] = v[i][0];
-          dst[1] = v[i][2];
-        }
+        const int r = i >> 1, c = ((int)threadIdx.x + 256 * (i & 1)) * 2;
+        if (r < R && c < KE) *reinterpret_cast<uint2*>(&pk_panel[r * ldp + c]) = uint2{v[i][0], v[i][2]};
       }
     }
   }
+  PK_MARK(6);
   return !__syncthreads_or(!good);
 }
 
