@@ -182,141 +182,119 @@ __device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, un
 #define PK_MARK(k) do { if (a.prof && stage == a.prof_stage && threadIdx.x == 0) atomicMax(a.prof + 600 + (k), (u64)wall_clock64()); } while (0)
 
 // ------------------------------------------------------------------------------------------
-// Activation panel: the first R rows of a tagged exchange buffer (KE elements per row) are read by the whole
-// workgroup with coalesced 8-byte loads (re-read until every tag matches) and kept, payload only, in LDS
-// as [R][KE + 4] words (the +4 staggers the rows over the banks for the 16-byte fragment reads).
-// ------------------------------------------------------------------------------------------
-extern __shared__ unsigned pk_panel[];
-
-__device__ __forceinline__ bool pk_panel_load(const PkArgs& a, const u64* A, int lda, int R, int KE, unsigned tag, int stage) {
-  const int ldp = KE + 4;
-  const u64 t0 = wall_clock64();
-  int it = 0;
-  bool good = true;
-  // phase 1: one cheap load per thread, spread over the columns of the LAST row (every producer tile owns
-  // 16 or 8 of them), until all of them show the tag
-  const int scol = KE >= 256 ? (int)((threadIdx.x * (unsigned)KE) >> 8) : (int)(threadIdx.x % KE);
-  const u64* sent = A + (long)(R - 1) * lda + scol;
-  if (a.prof && stage == a.prof_stage && threadIdx.x == 0) atomicMin(a.prof + 599, (u64)wall_clock64());
-  PK_MARK(0);
-  while (true) {
-    const bool ok = (unsigned)(pk_ld(sent) >> 32) == tag;
-    if (__all(ok)) break;
-    if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
-    __builtin_amdgcn_s_sleep(4);
-  }
-  // phase 2: everything, as 16-byte agent-scope loads (two tagged elements each; measured 5x the throughput
-  // of 8-byte ones).  Slot i of a thread is row i/2, columns 2*(threadIdx.x + 256*(i%2)) and the next one: all
-  // index arithmetic is compile-time or a shift (a division per load here once cost more than the loads).  The
-  // loads are inline asm, so the wait for them is explicit and every destination is passed through an empty asm
-  // afterwards to pin its uses behind the wait.  Host side guarantees R <= 16 and KE <= 1024.
-  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  PK_MARK(1);
-  if (good) {
-    u32x4 v[32];
-    while (true) {
-#pragma unroll
-      for (int i = 0; i < 32; i++) {
-        const int r = i >> 1, c = ((int)threadIdx.x + 256 * (i & 1)) * 2;
-        v[i] = u32x4{tag, tag, tag, tag};
-        if (r < R && c < KE) {
-          const u64* p = A + (long)r * lda + c;
-          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[i]) : "v"(p) : "memory");
-        }
-      }
-      PK_MARK(4);
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      PK_MARK(5);
-      bool ok = true;
-#pragma unroll
-      for (int i = 0; i < 32; i++) {
-        asm volatile("" : "+v"(v[i]));
-        ok = ok && v[i][1] == tag && v[i][3] == tag;      // unused slots were preset to the tag
-      }
-      if (a.prof && (threadIdx.x & 63) == 0) atomicAdd(a.prof + (__all(ok) ? 701 : 700), 1ull);   // complete / incomplete reads
-      if (__all(ok)) break;
-      if ((++it & 3) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
-      __builtin_amdgcn_s_sleep(2);
-    }
-    if (good) {
-#pragma unroll
-      for (int i = 0; i < 32; i++) {
-        const int r = i >> 1, c = ((int)threadIdx.x + 256 * (i & 1)) * 2;
-        if (r < R && c < KE) *reinterpret_cast<uint2*>(&pk_panel[r * ldp + c]) = uint2{v[i][0], v[i][2]};
-      }
-    }
-  }
-  PK_MARK(6);
-  return !__syncthreads_or(!good);
-}
-
-// ------------------------------------------------------------------------------------------
-// GEMM tile: C[16 rows x 16 cols] = A[16 x K] * W_tile^T, four waves split K, result in wave 0.
+// GEMM tile: C[16 rows x 16 cols] = A[16 x K] * W_tile^T, four waves split K (K <= 1024), result in wave 0.
 // ASRC 0: A is a half-pair exchange buffer [16][K/2];  ASRC 1: A is an fp32 exchange buffer [16][K] that is
-// RMS-normalised (gain g) on the fly (K/128 <= 8 fragments per wave, i.e. K <= 1024).
+// RMS-normalised (gain g) on the fly.
+// Every wave takes the MFMA A-fragments of its K-quarter straight from the exchange buffer: lane (r, g) of
+// fragment f needs the 8 consecutive values k0 = f*32 + g*8 .. +8 of row r, which are 32 (half pairs) or 64
+// (fp32) contiguous bytes of tagged elements, i.e. two or four 16-byte agent-scope loads.  No LDS staging, no
+// barrier before the multiplication; the tags are checked per lane and the whole set is re-read until complete.
 // ------------------------------------------------------------------------------------------
 template <int ASRC>
 __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_cw_t Wt, int KT, const u64* A,
                                              unsigned tagA, pk_cf_t gain, int R, f32x4& result, int stage,
                                              int lda = 0) {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  constexpr int NL = ASRC == 1 ? 4 : 2;      // 16-byte loads per fragment and lane
+  constexpr int EF = ASRC == 1 ? 32 : 16;    // tagged elements per fragment row
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int r = lane & 15, g = lane >> 4;
   const bool on = r < R;
-  const int FW = KT >> 2;                  // fragments per wave (host guarantees KT % 4 == 0)
+  const int FW = KT >> 2;                  // fragments per wave (host guarantees KT % 4 == 0, KT <= 32)
   const int K = KT * 32;
-  const int KE = ASRC == 1 ? K : (K >> 1), ldp = KE + 4;
+  if (lda == 0) lda = ASRC == 1 ? K : (K >> 1);
   f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
-  // weights of the first chunk go out before the wait for the activations: they depend on nothing
+  // weights and gains go out before the wait for the activations: they depend on nothing
   f16x8 wf[8];
 #pragma unroll
   for (int f = 0; f < 8; f++)
     if (f < FW) wf[f] = *(const PK_GLOBAL f16x8*)(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
-  float gcol[4] = {0.f, 0.f, 0.f, 0.f};     // gains of this thread's columns, requested before the wait
+  f32x4 gl[ASRC == 1 ? 16 : 1];
   if (ASRC == 1) {
 #pragma unroll
-    for (int j = 0; j < 4; j++)
-      if (j * 256 + (int)threadIdx.x < K) gcol[j] = gain[j * 256 + threadIdx.x];
+    for (int f = 0; f < 8; f++)
+      if (f < FW) {
+        const pk_cf_t gp = gain + (wave * FW + f) * 32 + g * 8;
+        gl[2 * f] = *(const PK_GLOBAL f32x4*)gp;
+        gl[2 * f + 1] = *(const PK_GLOBAL f32x4*)(gp + 4);
+      }
   }
-  if (!pk_panel_load(a, A, lda ? lda : KE, R, KE, tagA, stage)) return false;
-  PK_MARK(2);
-  if (ASRC == 1) {
-    {
-      // gains into LDS (requested before the wait), row sums of squares with 16 threads per row
+  // this wave's part of the rows: element (wave*FW + f)*EF + g*(EF/4) of row r is where fragment f starts
+  const u64* Aw = A + (long)(wave * FW) * EF;
+  const u64* mine = Aw + (long)min(r, R - 1) * lda + g * (EF / 4);
+  const u64 t0 = wall_clock64();
+  int it = 0;
+  bool good = true;
+  // phase 1: one cheap load per lane until it shows the tag.  Lane l watches fragment l/8, its first or second
+  // half (a producer tile owns half a fragment row), in one of the last four rows.
+  {
+    const int fs = min(lane >> 3, FW - 1), hs = (lane >> 2) & 1, rs = max(R - 1 - (lane & 3), 0);
+    const u64* sent = Aw + (long)rs * lda + fs * EF + hs * (EF / 2);
+    PK_MARK(0);
+    while (true) {
+      const bool ok = (unsigned)(pk_ld(sent) >> 32) == tagA;
+      if (__all(ok)) break;
+      if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
+      __builtin_amdgcn_s_sleep(4);
+    }
+  }
+  PK_MARK(1);
+  // phase 2: the fragments (inline asm loads: the wait is explicit, and every destination is passed through
+  // an empty asm afterwards to pin its uses behind the wait)
+  u32x4 v[8 * NL];
+  while (good) {
 #pragma unroll
-      for (int j = 0; j < 4; j++)
-        if (j * 256 + (int)threadIdx.x < K) sh.gain[j * 256 + threadIdx.x] = gcol[j];
-      const int row = threadIdx.x >> 4, sub = threadIdx.x & 15;
-      float ss = 0.f;
-      if (row < R) {
-#pragma unroll 4
-        for (int k = sub * 4; k < K; k += 64) {
-          const u32x4 x = *reinterpret_cast<const u32x4*>(&pk_panel[row * ldp + k]);
+    for (int f = 0; f < 8; f++) {
 #pragma unroll
-          for (int j = 0; j < 4; j++) { const float v = __uint_as_float(x[j]); ss += v * v; }
+      for (int j = 0; j < NL; j++) {
+        v[f * NL + j] = u32x4{tagA, tagA, tagA, tagA};
+        if (f < FW && on) {
+          const u64* p = mine + f * EF + 2 * j;
+          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[f * NL + j]) : "v"(p) : "memory");
         }
       }
-      ss += __shfl_xor(ss, 1, 64); ss += __shfl_xor(ss, 2, 64); ss += __shfl_xor(ss, 4, 64); ss += __shfl_xor(ss, 8, 64);
-      if (sub == 0) sh.ssq[0][row] = ss;
     }
-    __syncthreads();
-    const float inv = on ? 1.0f / sqrtf(sh.ssq[0][r] / (float)K + a.eps) : 0.f;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    bool ok = true;
+#pragma unroll
+    for (int i = 0; i < 8 * NL; i++) {
+      asm volatile("" : "+v"(v[i]));
+      ok = ok && v[i][1] == tagA && v[i][3] == tagA;      // unused slots were preset to the tag
+    }
+    if (__all(ok)) break;
+    if ((++it & 3) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
+    __builtin_amdgcn_s_sleep(2);
+  }
+  PK_MARK(2);
+  if (ASRC == 1) {
+    // row sums of squares: this lane's 8*FW values, then the four k-groups of the wave, then the four waves
+    float ss = 0.f;
+    if (on && good) {
+#pragma unroll
+      for (int i = 0; i < 8 * NL; i++) {
+        if (i < FW * NL) {
+          const float x0 = __uint_as_float(v[i][0]), x1 = __uint_as_float(v[i][2]);
+          ss += x0 * x0 + x1 * x1;
+        }
+      }
+    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g == 0) sh.ssq[wave][r] = ss;
+    if (__syncthreads_or(!good)) return false;
+    const float tot = sh.ssq[0][r] + sh.ssq[1][r] + sh.ssq[2][r] + sh.ssq[3][r];
+    const float inv = on ? 1.0f / sqrtf(tot / (float)K + a.eps) : 0.f;
 #pragma unroll
     for (int f = 0; f < 8; f++) {
       if (f < FW) {
-        const int k0 = (wave * FW + f) * 32 + g * 8;
         f16x8 av;
-        if (on) {
-          const u32x4 x0 = *reinterpret_cast<const u32x4*>(&pk_panel[r * ldp + k0]);
-          const u32x4 x1 = *reinterpret_cast<const u32x4*>(&pk_panel[r * ldp + k0 + 4]);
-          const f32x4 g0 = *reinterpret_cast<const f32x4*>(&sh.gain[k0]);
-          const f32x4 g1 = *reinterpret_cast<const f32x4*>(&sh.gain[k0 + 4]);
 #pragma unroll
-          for (int j = 0; j < 4; j++) {
-            av[j] = (f16_t)(__uint_as_float(x0[j]) * inv * g0[j]);
-            av[4 + j] = (f16_t)(__uint_as_float(x1[j]) * inv * g1[j]);
-          }
-        } else {
+        for (int j = 0; j < 4; j++) {
+          const f32x4 gg = gl[2 * f + (j >> 1)];
+          av[2 * j] = (f16_t)(__uint_as_float(v[f * 4 + j][0]) * inv * gg[(j & 1) * 2]);
+          av[2 * j + 1] = (f16_t)(__uint_as_float(v[f * 4 + j][2]) * inv * gg[(j & 1) * 2 + 1]);
+        }
+        if (!on) {
 #pragma unroll
           for (int j = 0; j < 8; j++) av[j] = (f16_t)0.f;
         }
@@ -324,26 +302,17 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
       }
     }
   } else {
-    for (int f0 = 0; f0 < FW; f0 += 8) {
-      f16x8 wn[8];     // next chunk of weights is in flight while this one is multiplied
 #pragma unroll
-      for (int f = 0; f < 8; f++)
-        if (f0 + 8 + f < FW) wn[f] = *(const PK_GLOBAL f16x8*)(Wt + ((long)(wave * FW + f0 + 8 + f) * 64 + lane) * 8);
-#pragma unroll
-      for (int f = 0; f < 8; f++) {
-        if (f0 + f < FW) {
-          const int k0 = (wave * FW + f0 + f) * 32 + g * 8;
-          u32x4 pk = u32x4{0u, 0u, 0u, 0u};
-          if (on) pk = *reinterpret_cast<const u32x4*>(&pk_panel[r * ldp + (k0 >> 1)]);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, pk), wf[f], acc, 0, 0, 0);
-        }
+    for (int f = 0; f < 8; f++) {
+      if (f < FW) {
+        u32x4 pk = u32x4{0u, 0u, 0u, 0u};
+        if (on && good) pk = u32x4{v[2 * f][0], v[2 * f][2], v[2 * f + 1][0], v[2 * f + 1][2]};
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, pk), wf[f], acc, 0, 0, 0);
       }
-#pragma unroll
-      for (int f = 0; f < 8; f++) wf[f] = wn[f];
     }
   }
   sh.red[wave][lane] = acc;
-  __syncthreads();
+  if (__syncthreads_or(!good)) return false;
   PK_MARK(3);
   if (wave == 0) result = sh.red[0][lane] + sh.red[1][lane] + sh.red[2][lane] + sh.red[3][lane];
   return true;
