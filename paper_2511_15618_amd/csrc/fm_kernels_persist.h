@@ -438,6 +438,18 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
       if (b >= b0 + wave && b < b1 && ((b - b0 - wave) & 3) == 0) bov = b;
     }
   }
+  // the first K/V block of this wave depends on nothing from this pass: request it before waiting for q
+  pk_cw_t Kb = Kc + (long)hh * capb * 2048;
+  pk_cw_t Vb = Vc + (long)hh * capb * 2048;
+  f16x8 kf[4], vf[4];
+  if (b0 + wave < b1) {
+    pk_cw_t kp = Kb + (long)(b0 + wave) * 2048 + lane * 8;
+    pk_cw_t vp = Vb + (long)(b0 + wave) * 2048 + (lane & 15) * 32 + g * 8;
+#pragma unroll
+    for (int f = 0; f < 4; f++) kf[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
+  }
   unsigned qraw[56];
   const u64* qp = qbuf + (long)(on ? ql : 0) * (d >> 1) + ((hh * 64 + g * 8) >> 1);
   bool ok = pk_fetch<56>(qraw, bov >= 0 ? 56 : 8, true, tag, [&](int ii) {
@@ -467,16 +479,17 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   f32x4 o[4];
 #pragma unroll
   for (int dt = 0; dt < 4; dt++) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  pk_cw_t Kb = Kc + (long)hh * capb * 2048;
-  pk_cw_t Vb = Vc + (long)hh * capb * 2048;
   for (int b = b0 + wave; b < b1; b += 4) {
-    pk_cw_t kp = Kb + (long)b * 2048 + lane * 8;
-    pk_cw_t vp = Vb + (long)b * 2048 + (lane & 15) * 32 + g * 8;
-    f16x8 kf[4], vf[4];
+    // the next block of this wave is requested before the current one is multiplied
+    f16x8 kn[4], vn[4];
+    if (b + 4 < b1) {
+      pk_cw_t kp = Kb + (long)(b + 4) * 2048 + lane * 8;
+      pk_cw_t vp = Vb + (long)(b + 4) * 2048 + (lane & 15) * 32 + g * 8;
 #pragma unroll
-    for (int f = 0; f < 4; f++) kf[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
+      for (int f = 0; f < 4; f++) kn[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
+      for (int dt = 0; dt < 4; dt++) vn[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
+    }
     if (b == bov) {
 #pragma unroll
       for (int f = 0; f < 4; f++) {
@@ -536,6 +549,10 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
     for (int dt = 0; dt < 4; dt++) {
       o[dt] *= alpha;
       o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[dt], 0, 0, 0);
+    }
+    if (b + 4 < b1) {
+#pragma unroll
+      for (int f = 0; f < 4; f++) { kf[f] = kn[f]; vf[f] = vn[f]; }
     }
   }
   float l = lrun;
