@@ -322,14 +322,16 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
 // The residual operand of a tile (complete long before the tile's GEMM input is) is fetched by wave 0 at the
 // start of the unit, so that its latency hides behind the wait for the input panel.
 __device__ __forceinline__ bool pk_res_prefetch(const PkArgs& a, int nt, const u64* hold, unsigned tag_old, int R,
-                                                unsigned (&old)[4], int stage) {
+                                                const int* pos, unsigned (&old)[4], int (&prow)[4], int stage) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
+#pragma unroll
+  for (int i = 0; i < 4; i++) prow[i] = pos[min(g * 4 + i, R - 1)];    // positions of the lane's rows, for the ring copies
   return pk_fetch<4>(old, 4, true, tag_old, [&](int i) { return hold + (long)min(g * 4 + i, R - 1) * d + n; }, a, stage);
 }
 
 __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c, int nt, const unsigned (&old)[4],
-                                                u64* hout, unsigned tag_out, int R, const int* pos, float* tap_ring,
+                                                u64* hout, unsigned tag_out, int R, const int (&prow)[4], float* tap_ring,
                                                 float* out_ring, int ring_size) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
@@ -340,7 +342,7 @@ __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c,
       const float ho = __uint_as_float(old[i]);
       const float v = ho + c[i];
       pk_stf(hout + (long)r * d + n, v, tag_out);
-      const int p = pos[r];
+      const int p = prow[i];
       if (p >= 0) {
         if (tap_ring) tap_ring[(long)(p & (ring_size - 1)) * d + n] = ho;
         if (out_ring) out_ring[(long)(p & (ring_size - 1)) * d + n] = v;
@@ -365,8 +367,23 @@ __device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, in
 
 // QKV epilogue (wave 0).  Tiles of the q and k parts hold 8 rotary pairs: columns 0..7 = dims qd*8.., columns
 // 8..15 = the same dims + 32.  q -> exchange buffer; k, v -> cache (for later passes) and exchange buffers.
+struct PkQkvPre {     // what the QKV epilogue needs besides the tile: requested before the tile's input arrives
+  float2 t[4];        // rotary (cos, sin) of the lane's pair for its four rows
+  int p[4];           // positions of those rows
+};
+__device__ __forceinline__ void pk_qkv_prefetch(int nt, int d, int R, const int* pos, const float2* cs, PkQkvPre& pre) {
+  const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
+  const int part = (nt * 16) / d, cp = (nt * 16) % d;
+  const int qd = (cp & 63) >> 4;
+#pragma unroll
+  for (int i = 0; i < 4; i++) {
+    const int rr = min(g * 4 + i, R - 1);
+    pre.p[i] = pos[rr];
+    pre.t[i] = part < 2 ? cs[(long)rr * 32 + qd * 8 + (col & 7)] : float2{1.f, 0.f};
+  }
+}
 __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, const f32x4& c, int nt, unsigned tag, int R,
-                                           const int* pos, const float2* cs, int capb) {
+                                           const PkQkvPre& pre, int capb) {
   const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
   const int d = a.D.d;
   const int part = (nt * 16) / d, cp = (nt * 16) % d;
@@ -374,12 +391,11 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 #pragma unroll
   for (int i = 0; i < 4; i++) {
     const int r = g * 4 + i;
-    const int rr = min(r, R - 1);
     float v = c[i];
     int dim;
     if (part < 2) {
       const int j = qd * 8 + (col & 7);
-      const float2 t = cs[(long)rr * 32 + j];
+      const float2 t = pre.t[i];
       const float o = __shfl_xor(v, 8, 64);
       v = col < 8 ? v * t.x - o * t.y : v * t.x + o * t.y;
       dim = col < 8 ? j : j + 32;
@@ -387,7 +403,7 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
       dim = qd * 16 + col;
     }
     const float w = __shfl_xor(v, 1, 64);       // neighbour dim (dim ^ 1 sits in lane ^ 1 in every layout above)
-    const int p = pos[rr];
+    const int p = pre.p[i];
     if (r < R) {
       if (part == 0) {
         if ((lane & 1) == 0) pk_st(a.q + (long)r * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
@@ -450,28 +466,56 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
 #pragma unroll
     for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
   }
+  // q of this lane: dims g*8..+8 and 32 + g*8..+8 of the head = two runs of four tagged elements = four 16-byte
+  // agent-scope loads, simply repeated until every tag matches (small enough to poll with the data itself)
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   unsigned qraw[56];
   const u64* qp = qbuf + (long)(on ? ql : 0) * (d >> 1) + ((hh * 64 + g * 8) >> 1);
-  bool ok = pk_fetch<56>(qraw, bov >= 0 ? 56 : 8, true, tag, [&](int ii) {
-    if (ii < 8) return qp + (ii >> 2) * 16 + (ii & 3);
-    const int i = ii - 8;
-    if (i < 16) {
-      const int f = i >> 2;
-      int nr = bov * 32 + (f >> 1) * 16 + (lane & 15) - P0;
-      nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
-      return (const u64*)(a.newK + ((long)hh * 16 + nr) * 32 + (((f & 1) * 32 + g * 8) >> 1) + (i & 3));
+  bool ok = true;
+  {
+    const u64 t0 = wall_clock64();
+    int it = 0;
+    u32x4 qv[4];
+    while (true) {
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        const u64* p = qp + (j >> 1) * 16 + (j & 1) * 2;
+        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(qv[j]) : "v"(p) : "memory");
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      bool okq = true;
+#pragma unroll
+      for (int j = 0; j < 4; j++) {
+        asm volatile("" : "+v"(qv[j]));
+        okq = okq && qv[j][1] == tag && qv[j][3] == tag;
+      }
+      if (__all(okq)) break;
+      if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { ok = false; break; }
+      __builtin_amdgcn_s_sleep(2);
     }
-    const int j = (i - 16) & 7, dt = (i - 16) >> 3;
-    int nr = bov * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
-    nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
-    return (const u64*)(a.newV + ((long)hh * 16 + nr) * 32 + ((dt * 16 + (lane & 15)) >> 1));
-  }, a, stage);
+#pragma unroll
+    for (int j = 0; j < 4; j++) { qraw[2 * j] = qv[j][0]; qraw[2 * j + 1] = qv[j][2]; }
+  }
+  // rows written by this pass that fall into one of this wave's blocks (at most one block)
+  if (bov >= 0) {
+    ok = pk_fetch<48>(*reinterpret_cast<unsigned(*)[48]>(qraw + 8), 48, true, tag, [&](int i) {
+      if (i < 16) {
+        const int f = i >> 2;
+        int nr = bov * 32 + (f >> 1) * 16 + (lane & 15) - P0;
+        nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
+        return (const u64*)(a.newK + ((long)hh * 16 + nr) * 32 + (((f & 1) * 32 + g * 8) >> 1) + (i & 3));
+      }
+      const int j = (i - 16) & 7, dt = (i - 16) >> 3;
+      int nr = bov * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+      nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
+      return (const u64*)(a.newV + ((long)hh * 16 + nr) * 32 + ((dt * 16 + (lane & 15)) >> 1));
+    }, a, stage) && ok;
+  }
   if (!on) {
 #pragma unroll
     for (int i = 0; i < 8; i++) qraw[i] = 0u;
   }
   const unsigned* raw = qraw + 8;
-  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   const f16x8 qf0 = __builtin_bit_cast(f16x8, (u32x4{qraw[0], qraw[1], qraw[2], qraw[3]}));
   const f16x8 qf1 = __builtin_bit_cast(f16x8, (u32x4{qraw[4], qraw[5], qraw[6], qraw[7]}));
 
@@ -682,8 +726,10 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append)
       PK_MINE(3 * d / 16) {
         f32x4 c;
+        PkQkvPre pre;
+        if (wave == 0) pk_qkv_prefetch(u, d, R, pos, a.cs[lev], pre);
         if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, hA_l, tag, L.g1, R, c, stage)) return;
-        if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pos, a.cs[lev], capb);
+        if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pre, capb);
         __syncthreads();
       }
       PK_NEXT(3 * d / 16);
@@ -707,11 +753,12 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       PK_MINE(d / 16) {
         f32x4 c;
         unsigned old[4];
+        int prow[4];
         bool okr = true;
-        if (wave == 0) okr = pk_res_prefetch(a, u, hA_l, tag, R, old, stage);
+        if (wave == 0) okr = pk_res_prefetch(a, u, hA_l, tag, R, pos, old, prow, stage);
         if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, att_l, tag, nullptr, R, c, stage)) return;
         if (wave == 0 && okr)
-          pk_epi_residual(a, c, u, old, hB_l, tag, R, pos, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
+          pk_epi_residual(a, c, u, old, hB_l, tag, R, prow, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
         if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16);
@@ -741,10 +788,11 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       PK_MINE(d / 16) {
         f32x4 c;
         unsigned old[4];
+        int prow[4];
         bool okr = true;
-        if (wave == 0) okr = pk_res_prefetch(a, u, hB_l, tag, R, old, stage);
+        if (wave == 0) okr = pk_res_prefetch(a, u, hB_l, tag, R, pos, old, prow, stage);
         if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, att2_l, tag, nullptr, R, c, stage)) return;
-        if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, tag, R, pos, nullptr, nullptr, 8);
+        if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, tag, R, prow, nullptr, nullptr, 8);
         if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16);
@@ -764,8 +812,9 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         const int KTq = ff / 128;                       // fragments of one K-quarter
         f32x4 c;
         unsigned old[4];
+        int prow[4];
         bool okr = true;
-        if (wave == 0 && kq == 0) okr = pk_res_prefetch(a, nt, hC_l, tag, R, old, stage);
+        if (wave == 0 && kq == 0) okr = pk_res_prefetch(a, nt, hC_l, tag, R, pos, old, prow, stage);
         if (!pk_gemm_tile<0>(a, sh, L.w2 + ((long)nt * (ff / 32) + (long)kq * KTq) * 512, KTq, mid_l + (long)kq * (ff / 8), tag,
                              nullptr, R, c, stage, ff >> 1)) return;
         if (wave == 0) {
@@ -790,7 +839,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
                 ring = st == 0 ? a.ring_hc : st == 1 ? a.ring_hv : st == 2 ? a.ring_yf : a.ring_yv;
                 rs = st == 0 ? 32 : st == 2 ? 8 : 16;
               }
-              pk_epi_residual(a, c, nt, old, dst, PK_TAG(a, l + 1), R, pos, nullptr, ring, rs);
+              pk_epi_residual(a, c, nt, old, dst, PK_TAG(a, l + 1), R, prow, nullptr, ring, rs);
             }
           }
         }
