@@ -267,23 +267,10 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
   }
   PK_MARK(2);
   if (ASRC == 1) {
-    // row sums of squares: this lane's 8*FW values, then the four k-groups of the wave, then the four waves
+    // RMSNorm without a barrier in front of the multiplication: the MFMA runs on half(x * gain) and the per-row
+    // factor 1/rms, a scalar per output row, is applied to the accumulated tile afterwards.  Row sums of
+    // squares: this lane's 8*FW values, then the four k-groups of the wave; the four waves meet in LDS below.
     float ss = 0.f;
-    if (on && good) {
-#pragma unroll
-      for (int i = 0; i < 8 * NL; i++) {
-        if (i < FW * NL) {
-          const float x0 = __uint_as_float(v[i][0]), x1 = __uint_as_float(v[i][2]);
-          ss += x0 * x0 + x1 * x1;
-        }
-      }
-    }
-    ss += __shfl_xor(ss, 16, 64);
-    ss += __shfl_xor(ss, 32, 64);
-    if (g == 0) sh.ssq[wave][r] = ss;
-    if (__syncthreads_or(!good)) return false;
-    const float tot = sh.ssq[0][r] + sh.ssq[1][r] + sh.ssq[2][r] + sh.ssq[3][r];
-    const float inv = on ? 1.0f / sqrtf(tot / (float)K + a.eps) : 0.f;
 #pragma unroll
     for (int f = 0; f < 8; f++) {
       if (f < FW) {
@@ -291,16 +278,18 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
 #pragma unroll
         for (int j = 0; j < 4; j++) {
           const f32x4 gg = gl[2 * f + (j >> 1)];
-          av[2 * j] = (f16_t)(__uint_as_float(v[f * 4 + j][0]) * inv * gg[(j & 1) * 2]);
-          av[2 * j + 1] = (f16_t)(__uint_as_float(v[f * 4 + j][2]) * inv * gg[(j & 1) * 2 + 1]);
-        }
-        if (!on) {
-#pragma unroll
-          for (int j = 0; j < 8; j++) av[j] = (f16_t)0.f;
+          const float x0 = on && good ? __uint_as_float(v[f * 4 + j][0]) : 0.f;
+          const float x1 = on && good ? __uint_as_float(v[f * 4 + j][2]) : 0.f;
+          ss += x0 * x0 + x1 * x1;
+          av[2 * j] = (f16_t)(x0 * gg[(j & 1) * 2]);
+          av[2 * j + 1] = (f16_t)(x1 * gg[(j & 1) * 2 + 1]);
         }
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
       }
     }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g == 0) sh.ssq[wave][r] = ss;
   } else {
 #pragma unroll
     for (int f = 0; f < 8; f++) {
@@ -314,7 +303,17 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
   sh.red[wave][lane] = acc;
   if (__syncthreads_or(!good)) return false;
   PK_MARK(3);
-  if (wave == 0) result = sh.red[0][lane] + sh.red[1][lane] + sh.red[2][lane] + sh.red[3][lane];
+  if (wave == 0) {
+    result = sh.red[0][lane] + sh.red[1][lane] + sh.red[2][lane] + sh.red[3][lane];
+    if (ASRC == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) {      // result[i] belongs to row g*4 + i
+        const int row = g * 4 + i;
+        const float tot = sh.ssq[0][row] + sh.ssq[1][row] + sh.ssq[2][row] + sh.ssq[3][row];
+        result[i] *= 1.0f / sqrtf(tot / (float)K + a.eps);
+      }
+    }
+  }
   return true;
 }
 
