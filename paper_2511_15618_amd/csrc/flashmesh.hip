@@ -547,6 +547,7 @@ int build_persist(fm_ctx* c) {
   // GEMM input panels: one region per layer, so that no address is written twice within a launch
   TRY(dalloc(c, &a.hA, (nl + 1) * 16 * d)); TRY(dalloc(c, &a.hB, nl * 16 * d)); TRY(dalloc(c, &a.hC, nl * 16 * d));
   for (int i = 0; i < 4; i++) TRY(dalloc(c, &a.hT[i], 16 * d));
+  TRY(dalloc(c, &a.xA, (nl + 1) * 8 * d)); TRY(dalloc(c, &a.xB, nl * 8 * d)); TRY(dalloc(c, &a.xC, nl * 8 * d));
   TRY(dalloc(c, &a.q, 8 * d)); TRY(dalloc(c, &a.att, nl * 8 * d)); TRY(dalloc(c, &a.q2, 8 * d));
   TRY(dalloc(c, &a.att2, nl * 8 * d));
   TRY(dalloc(c, &a.pool, 2 * 8 * d)); TRY(dalloc(c, &a.mid, nl * 8 * c->ff));

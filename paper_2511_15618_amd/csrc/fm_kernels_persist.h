@@ -70,6 +70,7 @@ struct PkArgs {
   // exchange buffers (u64 = payload | tag << 32)
   u64 *hA, *hB, *hC;        // [layers + 1][16][d]: one region per layer, written once per launch
   u64* hT[4];               // outputs of cpre, vpre, face, vpost  [16][d]
+  u64 *xA, *xB, *xC;        // [layers (+ 1)][16][d/2]: the same activations as hA, hB, hC rounded to half pairs, for the GEMMs
   u64 *q, *q2;              // [16][d/2] rotated queries of the self- / cross-attention (half pairs)
   u64 *att, *att2;          // [layers][16][d/2] attention outputs
   u64* pool;                // [2][16][d/2] pooled groups before the two shortening projections
@@ -183,26 +184,26 @@ __device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, un
 
 // ------------------------------------------------------------------------------------------
 // GEMM tile: C[16 rows x 16 cols] = A[16 x K] * W_tile^T, four waves split K (K <= 1024), result in wave 0.
-// ASRC 0: A is a half-pair exchange buffer [16][K/2];  ASRC 1: A is an fp32 exchange buffer [16][K] that is
-// RMS-normalised (gain g) on the fly.
+// A is a half-pair exchange buffer [16][K/2].  ASRC 1: the rows are RMS-normalised (gain g) on the fly; they are
+// the half-rounded copy that the producers of the fp32 residual stream write next to it.
 // Every wave takes the MFMA A-fragments of its K-quarter straight from the exchange buffer: lane (r, g) of
-// fragment f needs the 8 consecutive values k0 = f*32 + g*8 .. +8 of row r, which are 32 (half pairs) or 64
-// (fp32) contiguous bytes of tagged elements, i.e. two or four 16-byte agent-scope loads.  No LDS staging, no
-// barrier before the multiplication; the tags are checked per lane and the whole set is re-read until complete.
+// fragment f needs the 8 consecutive values k0 = f*32 + g*8 .. +8 of row r, which are 32 contiguous bytes of
+// tagged half pairs, i.e. two 16-byte agent-scope loads.  No LDS staging, no barrier before the multiplication;
+// the tags are checked per lane and the whole set is re-read until complete.
 // ------------------------------------------------------------------------------------------
 template <int ASRC>
 __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_cw_t Wt, int KT, const u64* A,
                                              unsigned tagA, pk_cf_t gain, int R, f32x4& result, int stage,
                                              int lda = 0) {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  constexpr int NL = ASRC == 1 ? 4 : 2;      // 16-byte loads per fragment and lane
-  constexpr int EF = ASRC == 1 ? 32 : 16;    // tagged elements per fragment row
+  constexpr int NL = 2;       // 16-byte loads per fragment and lane
+  constexpr int EF = 16;      // tagged elements (half pairs) per fragment row
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int r = lane & 15, g = lane >> 4;
   const bool on = r < R;
   const int FW = KT >> 2;                  // fragments per wave (host guarantees KT % 4 == 0, KT <= 32)
   const int K = KT * 32;
-  if (lda == 0) lda = ASRC == 1 ? K : (K >> 1);
+  if (lda == 0) lda = K >> 1;
   f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
   // weights and gains go out before the wait for the activations: they depend on nothing
   f16x8 wf[8];
@@ -274,15 +275,15 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
 #pragma unroll
     for (int f = 0; f < 8; f++) {
       if (f < FW) {
+        u32x4 pk = u32x4{0u, 0u, 0u, 0u};
+        if (on && good) pk = u32x4{v[2 * f][0], v[2 * f][2], v[2 * f + 1][0], v[2 * f + 1][2]};
+        const f16x8 xh = __builtin_bit_cast(f16x8, pk);
         f16x8 av;
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-          const f32x4 gg = gl[2 * f + (j >> 1)];
-          const float x0 = on && good ? __uint_as_float(v[f * 4 + j][0]) : 0.f;
-          const float x1 = on && good ? __uint_as_float(v[f * 4 + j][2]) : 0.f;
-          ss += x0 * x0 + x1 * x1;
-          av[2 * j] = (f16_t)(x0 * gg[(j & 1) * 2]);
-          av[2 * j + 1] = (f16_t)(x1 * gg[(j & 1) * 2 + 1]);
+        for (int j = 0; j < 8; j++) {
+          const float x = (float)xh[j];
+          ss += x * x;
+          av[j] = (f16_t)(x * gl[2 * f + (j >> 2)][j & 3]);
         }
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
       }
@@ -330,8 +331,8 @@ __device__ __forceinline__ bool pk_res_prefetch(const PkArgs& a, int nt, const u
 }
 
 __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c, int nt, const unsigned (&old)[4],
-                                                u64* hout, unsigned tag_out, int R, const int (&prow)[4], float* tap_ring,
-                                                float* out_ring, int ring_size) {
+                                                u64* hout, u64* xout, unsigned tag_out, int R, const int (&prow)[4],
+                                                float* tap_ring, float* out_ring, int ring_size) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
 #pragma unroll
@@ -341,6 +342,10 @@ __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c,
       const float ho = __uint_as_float(old[i]);
       const float v = ho + c[i];
       pk_stf(hout + (long)r * d + n, v, tag_out);
+      if (xout) {        // half-pair copy for the GEMM that normalises this row next (r < R holds for the lane pair alike)
+        const float w = __shfl_xor(v, 1, 64);
+        if ((lane & 1) == 0) pk_st(xout + (long)r * (d >> 1) + (n >> 1), pk_pack(v, w), tag_out);
+      }
       const int p = prow[i];
       if (p >= 0) {
         if (tap_ring) tap_ring[(long)(p & (ring_size - 1)) * d + n] = ho;
@@ -702,7 +707,12 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const int r = u;
     const bool onr = a.pos[0][r] >= 0;
     const f16_t* e = a.emb + (long)a.vtok[r] * d;
-    for (int i = threadIdx.x; i < d; i += 256) pk_stf(a.hA + (long)r * d + i, onr ? (float)e[i] : 0.f, PK_TAG(a, 0));   // region of layer 0
+    for (int i = threadIdx.x; i < d; i += 256) {     // region of layer 0, and its half-pair copy (d is a multiple of 128)
+      const float v = onr ? (float)e[i] : 0.f;
+      pk_stf(a.hA + (long)r * d + i, v, PK_TAG(a, 0));
+      const float w = __shfl_xor(v, 1, 64);
+      if ((i & 1) == 0) pk_st(a.xA + (long)r * (d >> 1) + (i >> 1), pk_pack(v, w), PK_TAG(a, 0));
+    }
   }
   PK_NEXT(a.R[0]);
 
@@ -719,6 +729,10 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       u64* const hA_n = a.hA + (long)(l + 1) * 16 * d;
       u64* const hB_l = a.hB + (long)l * 16 * d;
       u64* const hC_l = a.hC + (long)l * 16 * d;
+      u64* const xA_l = a.xA + (long)l * 8 * d;
+      u64* const xA_n = a.xA + (long)(l + 1) * 8 * d;
+      u64* const xB_l = a.xB + (long)l * 8 * d;
+      u64* const xC_l = a.xC + (long)l * 8 * d;
       u64* const att_l = a.att + (long)l * 8 * d;
       u64* const att2_l = a.att2 + (long)l * 8 * d;
       u64* const mid_l = a.mid + (long)l * 8 * ff;
@@ -727,7 +741,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         f32x4 c;
         PkQkvPre pre;
         if (wave == 0) pk_qkv_prefetch(u, d, R, pos, a.cs[lev], pre);
-        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, hA_l, tag, L.g1, R, c, stage)) return;
+        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, xA_l, tag, L.g1, R, c, stage)) return;
         if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pre, capb);
         __syncthreads();
       }
@@ -757,14 +771,14 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         if (wave == 0) okr = pk_res_prefetch(a, u, hA_l, tag, R, pos, old, prow, stage);
         if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, att_l, tag, nullptr, R, c, stage)) return;
         if (wave == 0 && okr)
-          pk_epi_residual(a, c, u, old, hB_l, tag, R, prow, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
+          pk_epi_residual(a, c, u, old, hB_l, xB_l, tag, R, prow, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
         if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16);
       // ---- cross-attention query (norm2 on the fly)
       PK_MINE(d / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, hB_l, tag, L.g2, R, c, stage)) return;
+        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, xB_l, tag, L.g2, R, c, stage)) return;
         if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false);
         __syncthreads();
       }
@@ -791,14 +805,14 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         bool okr = true;
         if (wave == 0) okr = pk_res_prefetch(a, u, hB_l, tag, R, pos, old, prow, stage);
         if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, att2_l, tag, nullptr, R, c, stage)) return;
-        if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, tag, R, prow, nullptr, nullptr, 8);
+        if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, xC_l, tag, R, prow, nullptr, nullptr, 8);
         if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16);
       // ---- FFN up (norm3 on the fly, GELU)
       PK_MINE(ff / 16) {
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, hC_l, tag, L.g3, R, c, stage)) return;
+        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, xC_l, tag, L.g3, R, c, stage)) return;
         if (wave == 0) pk_epi_half(c, u, mid_l, ff >> 1, tag, R, true);
         __syncthreads();
       }
@@ -831,14 +845,16 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
 #pragma unroll
                 for (int i = 0; i < 4; i++) c[i] += __uint_as_float(pr[k * 4 + i]);
               u64* dst = hA_n;
+              u64* xdst = xA_n;
               float* ring = nullptr;
               int rs = 8;
               if (L.last && st < 4) {
                 dst = a.hT[st];
+                xdst = nullptr;        // a stack output feeds a level transition, not a GEMM
                 ring = st == 0 ? a.ring_hc : st == 1 ? a.ring_hv : st == 2 ? a.ring_yf : a.ring_yv;
                 rs = st == 0 ? 32 : st == 2 ? 8 : 16;
               }
-              pk_epi_residual(a, c, nt, old, dst, PK_TAG(a, l + 1), R, prow, nullptr, ring, rs);
+              pk_epi_residual(a, c, nt, old, dst, xdst, PK_TAG(a, l + 1), R, prow, nullptr, ring, rs);
             }
           }
         }
@@ -888,7 +904,13 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         if (wave == 0) {
           const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll
-          for (int i = 0; i < 4; i++) if (g * 4 + i < Rc_) pk_stf(a.hA + (long)ln * 16 * d + (long)(g * 4 + i) * d + n, c[i], tagn);
+          for (int i = 0; i < 4; i++) {
+            const float w = __shfl_xor(c[i], 1, 64);
+            if (g * 4 + i < Rc_) {
+              pk_stf(a.hA + (long)ln * 16 * d + (long)(g * 4 + i) * d + n, c[i], tagn);
+              if ((lane & 1) == 0) pk_st(a.xA + (long)ln * 8 * d + (long)(g * 4 + i) * (d >> 1) + (n >> 1), pk_pack(c[i], w), tagn);
+            }
+          }
         }
         __syncthreads();
       }
@@ -919,6 +941,8 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
             }
           }
           pk_stf(a.hA + (long)ln * 16 * d + (long)u * d + i, v, tagn);
+          const float w = __shfl_xor(v, 1, 64);
+          if ((i & 1) == 0) pk_st(a.xA + (long)ln * 8 * d + (long)u * (d >> 1) + (i >> 1), pk_pack(v, w), tagn);
         }
         if (__syncthreads_or(!ok)) return;
       }
@@ -931,7 +955,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const int NT = (a.D.V + 15) / 16;
     PK_MINE(NT) {
       f32x4 c;
-      if (!pk_gemm_tile<1>(a, sh, (pk_cw_t)a.lm + (long)u * (d / 32) * 512, d / 32, a.hA + (long)l * 16 * d, PK_TAG(a, l), (pk_cf_t)a.gf, R, c, stage)) return;
+      if (!pk_gemm_tile<1>(a, sh, (pk_cw_t)a.lm + (long)u * (d / 32) * 512, d / 32, a.xA + (long)l * 8 * d, PK_TAG(a, l), (pk_cf_t)a.gf, R, c, stage)) return;
       if (wave == 0) {
         const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
 #pragma unroll
