@@ -428,7 +428,7 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 // Attention over one key range of one head (flash-decoding split), same arithmetic as k_attn_mfma<1>.
 // Keys of this pass (positions >= P0) are taken from the exchange buffers, older keys from the cache.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, const int* limit, int R,
+__device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, int lim, int maxlim, int R,
                                              pk_cw_t Kc, pk_cw_t Vc, int capb, int nsplit_cfg, int hh, int split,
                                              bool overlay, int P0, u64* part, unsigned tag, int stage) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -436,10 +436,8 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   const int d = a.D.d;
   const float kScale = 0.125f * 1.4426950408889634f;
   const bool on = ql < R;
-  const int lim = on ? limit[ql] : -1;
-  int maxlim = lim;
-#pragma unroll
-  for (int o = 1; o < 16; o <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, o, 64));
+  // lim: last key this lane's query row may see (-1 for an unused row slot), maxlim: the largest of the block;
+  // both are the same for every layer of a level and come from the caller
   const int nblk = (maxlim + 32) >> 5;
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
@@ -634,11 +632,9 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
 
 // merge of the splits of one head (one quarter of its dims per unit) into the half-pair attention output;
 // thread = (row, dim), splits summed in a fixed order
-__device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, const int* limit, int R, int capb, int nsplit_cfg,
+__device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, int maxlim, int R, int capb, int nsplit_cfg,
                                               int hh, int dq, const u64* parts, u64* att, unsigned tag, int stage) {
   const int d = a.D.d;
-  int maxlim = -1;
-  for (int r = 0; r < R; r++) maxlim = max(maxlim, limit[r]);
   const int nblk = (maxlim + 32) >> 5;
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
@@ -702,6 +698,25 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   bool worked = false;
   if (a.prof && threadIdx.x == 0) atomicMin(a.prof, (u64)wall_clock64());
 
+  // Per level and the same for all of its layers: the last visible key of this lane's query row in the
+  // self-attention (its own position) and in the cross-attention, the block maxima, the first position of the pass.
+  int limS[3], limX[3], maxS[3], maxX[3], firstP[3];
+#pragma unroll
+  for (int lv = 0; lv < 3; lv++) {
+    const int ql = threadIdx.x & 15;
+    const bool onl = ql < a.R[lv];
+    limS[lv] = onl ? a.pos[lv][ql] : -1;
+    limX[lv] = onl ? a.limx[lv][ql] : -1;
+    int ms = limS[lv], mx = limX[lv], fp = limS[lv] >= 0 ? limS[lv] : 0x3fffffff;
+#pragma unroll
+    for (int o = 1; o < 16; o <<= 1) {
+      ms = max(ms, __shfl_xor(ms, o, 64));
+      mx = max(mx, __shfl_xor(mx, o, 64));
+      fp = min(fp, __shfl_xor(fp, o, 64));
+    }
+    maxS[lv] = ms; maxX[lv] = mx; firstP[lv] = fp;
+  }
+
   // ---- embedding: one unit per coordinate row -> hA of layer 0
   PK_MINE(a.R[0]) {
     const int r = u;
@@ -749,16 +764,15 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // ---- self-attention splits
       {
         const int ns = a.nsplit[lev];
-        int P0 = 0x3fffffff;
-        for (int r = 0; r < R; r++) if (pos[r] >= 0) P0 = min(P0, pos[r]);
+        const int P0 = firstP[lev];
         PK_MINE(H * ns) {
           const int hh = u / ns, sp = u % ns;
-          if (!pk_attn_unit(a, sh, a.q, pos, R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
+          if (!pk_attn_unit(a, sh, a.q, limS[lev], maxS[lev], R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
                             a.partS + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
         }
         PK_NEXT(H * ns);
         PK_MINE(4 * H) {
-          if (!pk_merge_unit(a, sh, pos, R, capb, ns, u >> 2, u & 3, a.partS, att_l, tag, stage)) return;
+          if (!pk_merge_unit(a, sh, maxS[lev], R, capb, ns, u >> 2, u & 3, a.partS, att_l, tag, stage)) return;
         }
         PK_NEXT(4 * H);
       }
@@ -788,12 +802,12 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         const int ns = a.nsplitM;
         PK_MINE(H * ns) {
           const int hh = u / ns, sp = u % ns;
-          if (!pk_attn_unit(a, sh, a.q2, a.limx[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
+          if (!pk_attn_unit(a, sh, a.q2, limX[lev], maxX[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
                             a.partX + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
         }
         PK_NEXT(H * ns);
         PK_MINE(4 * H) {
-          if (!pk_merge_unit(a, sh, a.limx[lev], R, a.capbM, ns, u >> 2, u & 3, a.partX, att2_l, tag, stage)) return;
+          if (!pk_merge_unit(a, sh, maxX[lev], R, a.capbM, ns, u >> 2, u & 3, a.partX, att2_l, tag, stage)) return;
         }
         PK_NEXT(4 * H);
       }
