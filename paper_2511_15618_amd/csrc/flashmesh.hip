@@ -106,7 +106,7 @@ struct fm_ctx {
   PrefillLayer* pf_layers = nullptr;   // per-block table of the tiled prefill GEMM (null: per-block launches)
   int pf_n = 0;
   unsigned pk_epoch;
-  size_t pk_lds;           // dynamic LDS of the persistent kernel: the activation panel
+  size_t pk_lds;           // dynamic LDS of the persistent kernel (none at present)
   double weight_bytes;
 };
 
@@ -564,11 +564,8 @@ int build_persist(fm_ctx* c) {
   c->pk_epoch = 0;
   // all 256 workgroups must be resident at once: they wait for each other's results
   int dev = 0, cus = 0, per_cu = 0;
-  // panel: R rows of the widest exchange row (fp32 d words, or half pairs of the FFN width), +4 words of padding each
-  c->pk_lds = (size_t)D.Bm * (std::max((size_t)d, (size_t)c->ff / 8) + 4) * 4;
-  if (c->pk_lds > 120 * 1024 ||
-      hipFuncSetAttribute((const void*)k_verify_persist, hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->pk_lds) != hipSuccess ||
-      hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+  c->pk_lds = 0;   // the kernel uses static LDS only
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
       hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist, 256, c->pk_lds) != hipSuccess || (long)cus * per_cu < PK_NWG) {
     (void)hipGetLastError();
     c->persist = false;   // fall back to the per-launch path

@@ -89,7 +89,6 @@ struct PkArgs {
 struct PkShared {
   f32x4 red[4][64];
   float ssq[4][16];
-  float gain[1024];
   float lo[4][16][65];
   float lm[4][16], ll[4][16];
 };
