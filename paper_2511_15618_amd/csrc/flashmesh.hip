@@ -562,6 +562,11 @@ int build_persist(fm_ctx* c) {
     if (const char* ps = getenv("FM_PROFILE_STAGE")) a.prof_stage = atoi(ps); else a.prof_stage = -1;
   }
   c->pk_epoch = 0;
+  // test hooks for the bounded waits: a shorter bound, and an embedding that publishes under the wrong tag
+  a.timeout_ticks = PK_TIMEOUT_TICKS;
+  a.test_skew = 0;
+  if (const char* e = getenv("FM_PK_TIMEOUT_TICKS")) a.timeout_ticks = strtoull(e, nullptr, 10);
+  if (const char* e = getenv("FM_PK_TEST_SKEW")) a.test_skew = (unsigned)atoi(e);
   // all 256 workgroups must be resident at once: they wait for each other's results
   int dev = 0, cus = 0, per_cu = 0;
   c->pk_lds = 0;   // the kernel uses static LDS only

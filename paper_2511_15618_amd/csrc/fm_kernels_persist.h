@@ -27,7 +27,7 @@ typedef unsigned long long u64;
 #define PK_NWG 256
 #define PK_MAXSPLIT 64
 #define PK_PART (16 * 64 + 32)            // per (head, split): 16x64 unnormalised O, 16 running maxima, 16 sums
-#define PK_TIMEOUT_TICKS 20000000ull      // 200 ms of the 100 MHz wall clock
+#define PK_TIMEOUT_TICKS 20000000ull      // default bound of every wait: 200 ms of the 100 MHz wall clock
 
 // A pointer read from a table in memory is generic to the compiler, and loads through it become FLAT instructions,
 // which count against the LDS counter as well: every wait for an LDS read would then also wait for the weight
@@ -79,6 +79,8 @@ struct PkArgs {
   u64 *partS, *partX;       // [H][PK_MAXSPLIT][PK_PART]
   u64* w2part;              // [d/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
   unsigned epoch;
+  u64 timeout_ticks;        // bound of every wait (100 MHz wall clock)
+  unsigned test_skew;       // test hook: added to the tag the embedding publishes, so that nothing downstream ever arrives
   unsigned* abort_word;     // [0] abort flag, [1] earliest stage that gave up, [2] claim, [3..8] expected tag, tag seen,
                             // stage, workgroup, thread, element of the first missing value
   const int* run_flag;
@@ -108,7 +110,7 @@ __device__ __forceinline__ bool pk_expired(const PkArgs& a, u64 t0, int stage) {
     atomicMin(a.abort_word + 1, (unsigned)stage);
     return true;
   }
-  if (wall_clock64() - t0 > PK_TIMEOUT_TICKS) {
+  if (wall_clock64() - t0 > a.timeout_ticks) {
     __hip_atomic_store(a.abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     atomicMin(a.abort_word + 1, (unsigned)stage);
     return true;
@@ -723,9 +725,9 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
     const f16_t* e = a.emb + (long)a.vtok[r] * d;
     for (int i = threadIdx.x; i < d; i += 256) {     // region of layer 0, and its half-pair copy (d is a multiple of 128)
       const float v = onr ? (float)e[i] : 0.f;
-      pk_stf(a.hA + (long)r * d + i, v, PK_TAG(a, 0));
+      pk_stf(a.hA + (long)r * d + i, v, PK_TAG(a, 0) + a.test_skew);
       const float w = __shfl_xor(v, 1, 64);
-      if ((i & 1) == 0) pk_st(a.xA + (long)r * (d >> 1) + (i >> 1), pk_pack(v, w), PK_TAG(a, 0));
+      if ((i & 1) == 0) pk_st(a.xA + (long)r * (d >> 1) + (i >> 1), pk_pack(v, w), PK_TAG(a, 0) + a.test_skew);
     }
   }
   PK_NEXT(a.R[0]);

@@ -1,6 +1,7 @@
 """GPU tests of the decode-step contract: idempotent verify, rollback, replay accounting, error paths,
 and the full-size runs with teacher-forced oracle checks."""
 import os
+import time
 
 import numpy as np
 import pytest
@@ -170,6 +171,27 @@ def test_error_paths():
     torch.cuda.synchronize()
     a = acc.cpu().numpy()
     assert 1 <= a[0] <= fm.block_max and a[1] == 0
+
+
+def test_persistent_kernel_gives_up_instead_of_hanging(monkeypatch):
+    """Every wait inside the single-launch verify kernel is bounded.  With the test hook that makes the embedding
+    publish under a wrong tag nothing downstream can ever arrive: all workgroups must leave after the (shortened)
+    bound and the host must report which stage was stuck; the kernel itself finishes normally."""
+    _need_gpu()
+    monkeypatch.setenv("FM_PK_TIMEOUT_TICKS", "200000")     # 2 ms
+    monkeypatch.setenv("FM_PK_TEST_SKEW", "1")
+    cfg = si.TEST_CONFIGS["t_bf16_99_b1"]
+    print("case bounded waits", flush=True)
+    fm, _ = _ctx(cfg)
+    assert fm.verify_path() == 1
+    tok, ln = fm.new_block()
+    acc = torch.zeros(1, dtype=torch.int32, device="cuda")
+    fm.draft(tok, ln)
+    t0 = time.time()
+    fm.verify_block(tok, ln, None, acc)
+    with pytest.raises(RuntimeError, match="timed out"):
+        fm.read_state()
+    assert time.time() - t0 < 5.0
 
 
 def _teacher_forced_check(cfg, stream, tol, work, chunk=600):
