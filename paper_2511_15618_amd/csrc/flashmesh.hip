@@ -166,7 +166,7 @@ const int kStackLevel[5] = {0, 1, 2, 1, 0};
 template <typename T>
 void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, long gsw, void* Y, long ldy, long gsy,
           const float* R, long ldr, long gsr, int M, int N, int K, int groups, const int* flag) {
-  GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag};
+  GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag, nullptr, 0.f};
   if (mfma_gemm_launch<T>(c->mres, a, epi, groups, c->stream)) return;
   // the plain kernel reads row-major weights: only the fp32 path has those
   if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "gemm: unsupported shape M=%d N=%d K=%d", M, N, K); c->sticky_error = true; return; }
@@ -191,6 +191,23 @@ void rmsnorm(fm_ctx* c, const float* src, const float* const* srcptr, const floa
              float* keep, int rows, const int* flag) {
   hipLaunchKernelGGL((k_rmsnorm<T>), dim3(rows), dim3(256), 0, c->stream, src, srcptr, gain, gain_mod, (T*)out, keep,
                      c->D.d, c->cfg.rms_eps, flag);
+}
+
+// Y = RMSNorm(h; gain) W^T for the rows of the fp32 residual stream h [rows, d].  Half-precision path: one fused
+// launch (the GEMM normalises on the fly); fp32 path: norm into `xn`, then the plain GEMM.
+template <typename T>
+void gemm_norm(fm_ctx* c, int epi, const float* h, const float* gain, const void* W, void* Y, long ldy, int rows, int N,
+               const int* flag) {
+  const int d = c->D.d;
+  if (std::is_same<T, f16_t>::value) {
+    GemmArgs a{h, d, 0, W, 0, Y, ldy, 0, nullptr, 0, 0, rows, N, d, flag, gain, c->cfg.rms_eps};
+    if (mfma_gemm_launch<T>(c->mres, a, epi, 1, c->stream)) return;
+    fail(c, FM_EINVAL, "gemm_norm: unsupported shape M=%d N=%d K=%d", rows, N, d);
+    c->sticky_error = true;
+    return;
+  }
+  rmsnorm<T>(c, h, nullptr, gain, 0, c->xn, nullptr, rows, flag);
+  gemm<T>(c, epi, c->xn, d, 0, W, 0, Y, ldy, 0, nullptr, 0, 0, rows, N, d, 1, flag);
 }
 
 // rotary position on q (and k), conversion to the storage type, optional append to a K/V cache
@@ -219,17 +236,14 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
   const int cap = level_cap(c, level);
   float* h = c->h[level];
   const int* flag = c->st.alive;
-  rmsnorm<T>(c, h, nullptr, L.g1, 0, c->xn, nullptr, rows, flag);
-  gemm<T>(c, EPI_F32, c->xn, d, 0, L.wqkv, 0, c->qkv, 3 * d, 0, nullptr, 0, 0, rows, 3 * d, d, 1, flag);
+  gemm_norm<T>(c, EPI_F32, h, L.g1, L.wqkv, c->qkv, 3 * d, rows, 3 * d, flag);
   rope_append<T>(c, c->qkv, (long)3 * d, c->cs[level], c->pos[level], rows, RPS, c->qT, L.Kc, L.Vc, cap, flag);
   attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag, false, level_key_bound(c, level));
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
-  rmsnorm<T>(c, h, nullptr, L.g2, 0, c->xn, nullptr, rows, flag);
-  gemm<T>(c, EPI_T, c->xn, d, 0, L.cq, 0, c->qT, d, 0, nullptr, 0, 0, rows, d, d, 1, flag);
+  gemm_norm<T>(c, EPI_T, h, L.g2, L.cq, c->qT, d, rows, d, flag);
   attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)cache_seq_elems(c, D.M), D.M, c->attT, flag, true);
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.co, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
-  rmsnorm<T>(c, h, nullptr, L.g3, 0, c->xn, nullptr, rows, flag);
-  gemm<T>(c, EPI_GELU_T, c->xn, d, 0, L.w1, 0, c->mid, c->ff, 0, nullptr, 0, 0, rows, c->ff, d, 1, flag);
+  gemm_norm<T>(c, EPI_GELU_T, h, L.g3, L.w1, c->mid, c->ff, rows, c->ff, flag);
   gemm<T>(c, EPI_F32, c->mid, c->ff, 0, L.w2, 0, h, d, 0, h, d, 0, rows, d, c->ff, 1, flag);
 }
 
@@ -292,8 +306,7 @@ int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, f
   run_stack<T>(c, 4, c->tap_c, RS_C);
   // output head, greedy prediction, acceptance
   float* lg = logits_out ? logits_out : c->logits;
-  rmsnorm<T>(c, c->h[0], nullptr, c->gf, 0, c->xn, nullptr, c->Rc, flag);
-  gemm<T>(c, EPI_F32, c->xn, d, 0, c->lm, 0, lg, D.V, 0, nullptr, 0, 0, c->Rc, D.V, d, 1, flag);
+  gemm_norm<T>(c, EPI_F32, c->h[0], c->gf, c->lm, lg, D.V, c->Rc, D.V, flag);
   hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, lg, D.V, D.ban ? D.nbins : D.V, c->st.y);
   hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted);
   HIPCHK(c, hipGetLastError());

@@ -18,6 +18,8 @@ struct GemmArgs {
   const float* R; long ldr, gsr;  // optional residual added in EPI_F32 (may alias Y)
   int M, N, K;
   const int* run_flag;            // optional: whole launch is skipped when *run_flag == 0
+  const float* gain;              // MFMA path only: when set, X is the fp32 residual stream and the GEMM applies
+  float eps;                      // RMSNorm(gain, eps) to its rows on the fly
 };
 enum { EPI_F32 = 0, EPI_GELU_T = 2, EPI_T = 3 };
 

@@ -14,6 +14,7 @@
 //   A[16 x 32]: row l%16, k = (l/16)*8 .. +8      B[32 x 16]: col l%16, k = (l/16)*8 .. +8
 //   C[16 x 16]: col l%16, rows (l/16)*4 + i, i = 0..3
 #pragma once
+#include <type_traits>
 #include "fm_device.h"
 #include "fm_kernels_basic.h"
 
@@ -125,20 +126,25 @@ struct GemmSplit {
   int kt_per_wave;   // K fragments (of 32) each wave walks
 };
 
-template <int MT, int EPI>
+// NORM: X is fp32 and each row is RMS-normalised on the fly: the MFMA runs on half(x * gain) and the per-row factor
+// 1/rms is applied to the accumulated tile (every workgroup walks the whole K of its rows, so it has the row sums
+// of squares itself; partial sums per wave meet in LDS next to the partial tiles, in a fixed order).
+template <int MT, int EPI, bool NORM>
 __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   if (a.run_flag && *a.run_flag == 0) return;
   __shared__ f32x4 red[4][MT][64];
+  __shared__ float sq[NORM ? 4 : 1][MT][16];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nt = blockIdx.x;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
   const int g = blockIdx.z / nmb, mb = blockIdx.z % nmb;
   const int KT = a.K / 32;
-  const f16_t* X = (const f16_t*)a.X + (long)g * a.gsx;
+  typedef typename std::conditional<NORM, float, f16_t>::type XT;
+  const XT* X = (const XT*)a.X + (long)g * a.gsx;
   const f16_t* W = (const f16_t*)a.W + (long)g * a.gsw + ((long)nt * KT) * 512;
   const int m0 = mb * MT * 16;
   // A-fragment row pointers (rows past M are clamped: computed, never stored)
-  const f16_t* xrow[MT];
+  const XT* xrow[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; mt++) {
     int m = m0 + mt * 16 + (lane & 15);
@@ -146,56 +152,101 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
     xrow[mt] = X + (long)m * a.ldx + (lane >> 4) * 8;
   }
   f32x4 acc[MT];
+  float ss[MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int mt = 0; mt < MT; mt++) { acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; ss[mt] = 0.f; }
   const int kt0 = wave * sp.kt_per_wave;
   const int kt1 = min(kt0 + sp.kt_per_wave, KT);
 
   // K is walked in chunks of U fragments; the loads of the next chunk are in flight while this one is
   // multiplied (a workgroup is often alone on its CU, so nothing else would hide the latency)
-  constexpr int U = MT <= 2 ? 8 : MT <= 5 ? 4 : 2;
-  f16x8 bc[U], ac[MT][U];
-#pragma unroll
-  for (int u = 0; u < U; u++) {
-    if (kt0 + u < kt1) {
-      bc[u] = *reinterpret_cast<const f16x8*>(W + ((long)(kt0 + u) * 64 + lane) * 8);
-#pragma unroll
-      for (int mt = 0; mt < MT; mt++) ac[mt][u] = *reinterpret_cast<const f16x8*>(xrow[mt] + (kt0 + u) * 32);
-    }
-  }
-  for (int kt = kt0; kt < kt1; kt += U) {
-    f16x8 bn[U], an[MT][U];
+  constexpr int U = NORM ? (MT <= 2 ? 4 : MT <= 5 ? 2 : 1) : (MT <= 2 ? 8 : MT <= 5 ? 4 : 2);
+  struct AFrag { typename std::conditional<NORM, f32x4, f16x8>::type lo; f32x4 hi; };   // hi only used when NORM
+  f16x8 bc[U];
+  AFrag ac[MT][U];
+  f32x4 gc[NORM ? U : 1][2];
+  auto load_chunk = [&](f16x8 (&b)[U], AFrag (&af)[MT][U], f32x4 (&gg)[NORM ? U : 1][2], int kt) {
 #pragma unroll
     for (int u = 0; u < U; u++) {
-      if (kt + U + u < kt1) {
-        bn[u] = *reinterpret_cast<const f16x8*>(W + ((long)(kt + U + u) * 64 + lane) * 8);
+      if (kt + u < kt1) {
+        b[u] = *reinterpret_cast<const f16x8*>(W + ((long)(kt + u) * 64 + lane) * 8);
+        if constexpr (NORM) {
+          const float* gp = a.gain + (kt + u) * 32 + (lane >> 4) * 8;
+          gg[u][0] = *reinterpret_cast<const f32x4*>(gp);
+          gg[u][1] = *reinterpret_cast<const f32x4*>(gp + 4);
+        }
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++) an[mt][u] = *reinterpret_cast<const f16x8*>(xrow[mt] + (kt + U + u) * 32);
+        for (int mt = 0; mt < MT; mt++) {
+          if constexpr (NORM) {
+            af[mt][u].lo = *reinterpret_cast<const f32x4*>(xrow[mt] + (kt + u) * 32);
+            af[mt][u].hi = *reinterpret_cast<const f32x4*>(xrow[mt] + (kt + u) * 32 + 4);
+          } else {
+            af[mt][u].lo = *reinterpret_cast<const f16x8*>(xrow[mt] + (kt + u) * 32);
+          }
+        }
       }
     }
+  };
+  load_chunk(bc, ac, gc, kt0);
+  for (int kt = kt0; kt < kt1; kt += U) {
+    f16x8 bn[U];
+    AFrag an[MT][U];
+    f32x4 gn[NORM ? U : 1][2];
+    load_chunk(bn, an, gn, kt + U);
 #pragma unroll
     for (int u = 0; u < U; u++) {
       if (kt + u < kt1) {
 #pragma unroll
-        for (int mt = 0; mt < MT; mt++) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ac[mt][u], bc[u], acc[mt], 0, 0, 0);
+        for (int mt = 0; mt < MT; mt++) {
+          f16x8 av;
+          if constexpr (NORM) {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+              const float x0 = ac[mt][u].lo[j], x1 = ac[mt][u].hi[j];
+              ss[mt] += x0 * x0 + x1 * x1;
+              av[j] = (f16_t)(x0 * gc[u][0][j]);
+              av[4 + j] = (f16_t)(x1 * gc[u][1][j]);
+            }
+          } else {
+            av = ac[mt][u].lo;
+          }
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bc[u], acc[mt], 0, 0, 0);
+        }
       }
     }
 #pragma unroll
     for (int u = 0; u < U; u++) {
       bc[u] = bn[u];
+      if constexpr (NORM) { gc[u][0] = gn[u][0]; gc[u][1] = gn[u][1]; }
 #pragma unroll
       for (int mt = 0; mt < MT; mt++) ac[mt][u] = an[mt][u];
     }
   }
   // reduce the four K-quarters of the workgroup through LDS
 #pragma unroll
-  for (int mt = 0; mt < MT; mt++) red[wave][mt][lane] = acc[mt];
+  for (int mt = 0; mt < MT; mt++) {
+    red[wave][mt][lane] = acc[mt];
+    if constexpr (NORM) {
+      float t = ss[mt];
+      t += __shfl_xor(t, 16, 64);
+      t += __shfl_xor(t, 32, 64);
+      if ((lane >> 4) == 0) sq[wave][mt][lane & 15] = t;
+    }
+  }
   __syncthreads();
   const int n = nt * 16 + (lane & 15);
   for (int mt = wave; mt < MT; mt += 4) {
     f32x4 v = red[0][mt][lane];
 #pragma unroll
     for (int w = 1; w < 4; w++) v += red[w][mt][lane];
+    if constexpr (NORM) {
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const int row = (lane >> 4) * 4 + i;
+        const float tot = sq[0][mt][row] + sq[1][mt][row] + sq[2][mt][row] + sq[3][mt][row];
+        v[i] *= 1.0f / sqrtf(tot / (float)a.K + a.eps);
+      }
+    }
     if (n < a.N) {
 #pragma unroll
       for (int i = 0; i < 4; i++) {
@@ -220,11 +271,16 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
   size_t attn_ws_floats;
 };
 
+template <int MT, bool NORM>
+void gemm_mfma_dispatch2(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
+  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32, NORM>), grid, dim3(256), 0, st, a, sp);
+  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T, NORM>), grid, dim3(256), 0, st, a, sp);
+  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T, NORM>), grid, dim3(256), 0, st, a, sp);
+}
 template <int MT>
 void gemm_mfma_dispatch(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
-  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32>), grid, dim3(256), 0, st, a, sp);
-  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T>), grid, dim3(256), 0, st, a, sp);
-  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T>), grid, dim3(256), 0, st, a, sp);
+  if (a.gain) gemm_mfma_dispatch2<MT, true>(a, sp, epi, grid, st);
+  else gemm_mfma_dispatch2<MT, false>(a, sp, epi, grid, st);
 }
 
 template <typename T>
