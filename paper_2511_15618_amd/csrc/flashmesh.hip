@@ -166,7 +166,7 @@ const int kStackLevel[5] = {0, 1, 2, 1, 0};
 template <typename T>
 void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, long gsw, void* Y, long ldy, long gsy,
           const float* R, long ldr, long gsr, int M, int N, int K, int groups, const int* flag) {
-  GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag, nullptr, 0.f};
+  GemmArgs a{X, ldx, gsx, W, gsw, Y, ldy, gsy, R, ldr, gsr, M, N, K, flag, nullptr, 0.f, nullptr, nullptr, 0, nullptr, nullptr, 0, 0, 0};
   if (mfma_gemm_launch<T>(c->mres, a, epi, groups, c->stream)) return;
   // the plain kernel reads row-major weights: only the fp32 path has those
   if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "gemm: unsupported shape M=%d N=%d K=%d", M, N, K); c->sticky_error = true; return; }
@@ -200,7 +200,7 @@ void gemm_norm(fm_ctx* c, int epi, const float* h, const float* gain, const void
                const int* flag) {
   const int d = c->D.d;
   if (std::is_same<T, f16_t>::value) {
-    GemmArgs a{h, d, 0, W, 0, Y, ldy, 0, nullptr, 0, 0, rows, N, d, flag, gain, c->cfg.rms_eps};
+    GemmArgs a{h, d, 0, W, 0, Y, ldy, 0, nullptr, 0, 0, rows, N, d, flag, gain, c->cfg.rms_eps, nullptr, nullptr, 0, nullptr, nullptr, 0, 0, 0};
     if (mfma_gemm_launch<T>(c->mres, a, epi, 1, c->stream)) return;
     fail(c, FM_EINVAL, "gemm_norm: unsupported shape M=%d N=%d K=%d", rows, N, d);
     c->sticky_error = true;
@@ -236,8 +236,15 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
   const int cap = level_cap(c, level);
   float* h = c->h[level];
   const int* flag = c->st.alive;
-  gemm_norm<T>(c, EPI_F32, h, L.g1, L.wqkv, c->qkv, 3 * d, rows, 3 * d, flag);
-  rope_append<T>(c, c->qkv, (long)3 * d, c->cs[level], c->pos[level], rows, RPS, c->qT, L.Kc, L.Vc, cap, flag);
+  if (std::is_same<T, f16_t>::value) {
+    // norm1, fused q,k,v projection, rotary, q out and cache append in one launch
+    GemmArgs a{h, d, 0, L.wqkv, 0, c->qT, d, 0, nullptr, 0, 0, rows, 3 * d, d, flag, L.g1, c->cfg.rms_eps,
+               c->cs[level], c->pos[level], RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), (cap + 31) / 32, D.H};
+    if (!mfma_gemm_launch<T>(c->mres, a, EPI_QKV, 1, c->stream)) { fail(c, FM_EINVAL, "qkv: unsupported shape"); c->sticky_error = true; }
+  } else {
+    gemm_norm<T>(c, EPI_F32, h, L.g1, L.wqkv, c->qkv, 3 * d, rows, 3 * d, flag);
+    rope_append<T>(c, c->qkv, (long)3 * d, c->cs[level], c->pos[level], rows, RPS, c->qT, L.Kc, L.Vc, cap, flag);
+  }
   attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag, false, level_key_bound(c, level));
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   gemm_norm<T>(c, EPI_T, h, L.g2, L.cq, c->qT, d, rows, d, flag);
@@ -455,11 +462,15 @@ int build_params(fm_ctx* c) {
       TRY(dalloc_t(c, &L.Kc, D.S * cache_seq_elems(c, cap))); TRY(dalloc_t(c, &L.Vc, D.S * cache_seq_elems(c, cap)));
       TRY(dalloc_t(c, &L.Km, D.S * cache_seq_elems(c, D.M))); TRY(dalloc_t(c, &L.Vm, D.S * cache_seq_elems(c, D.M)));
       item(L.g1, d, true);
-      if (c->persist) {
-        TRY(dalloc_t(c, &L.wqkv_rp, 3 * d * d));
-        c->items.push_back({off, 3 * d * d, L.wqkv_rp, false, (int)(3 * d), (int)d, (int)d});
+      if (c->bf16) {
+        // half path: the q and k tiles of the fused projection hold whole rotary pairs (both verify paths apply
+        // the rotation in the GEMM epilogue), so only the permuted tiling is kept
+        c->items.push_back({off, 3 * d * d, L.wqkv, false, (int)(3 * d), (int)d, (int)d});
+        L.wqkv_rp = L.wqkv;
+        off += 3 * d * d;
+      } else {
+        lin(L.wqkv, 3 * d, d);   // wq, wk, wv are consecutive in the blob
       }
-      lin(L.wqkv, 3 * d, d);   // wq, wk, wv are consecutive in the blob
       lin(L.wo, d, d);
       item(L.g2, d, true);
       lin(L.cq, d, d);

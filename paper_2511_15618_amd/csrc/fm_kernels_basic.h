@@ -20,8 +20,16 @@ struct GemmArgs {
   const int* run_flag;            // optional: whole launch is skipped when *run_flag == 0
   const float* gain;              // MFMA path only: when set, X is the fp32 residual stream and the GEMM applies
   float eps;                      // RMSNorm(gain, eps) to its rows on the fly
+  // EPI_QKV (MFMA path, fused q,k,v projection whose q and k tiles hold whole rotary pairs): rotary on q and k,
+  // q -> Y as half [M, d]; k, v -> the blocked caches at the rows' positions (rows with position < 0 are not cached)
+  const float2* cs;               // [M][32] (cos, sin) of each row's position
+  const int* pos;                 // [M] positions
+  int RPS;                        // rows per sequence
+  void *Kc, *Vc;                  // caches, `seq_stride` elements per sequence, `capb` 32-key blocks per head
+  long seq_stride;
+  int capb, H;
 };
-enum { EPI_F32 = 0, EPI_GELU_T = 2, EPI_T = 3 };
+enum { EPI_F32 = 0, EPI_GELU_T = 2, EPI_T = 3, EPI_QKV = 4 };
 
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_simple(GemmArgs a) {

@@ -247,7 +247,41 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
         v[i] *= 1.0f / sqrtf(tot / (float)a.K + a.eps);
       }
     }
-    if (n < a.N) {
+    if constexpr (EPI == EPI_QKV) {
+      // tile nt of the fused projection: part 0/1/2 = q/k/v, head hh, and for q and k the rotary pairs
+      // qd*8 .. +8 (columns 0..7 = first halves, 8..15 = second halves), for v the dims qd*16 .. +16
+      const int d = a.H * FM_HD, col = lane & 15;
+      const int part = (nt * 16) / d, cp = (nt * 16) % d;
+      const int hh = cp >> 6, qd = (cp & 63) >> 4;
+#pragma unroll
+      for (int i = 0; i < 4; i++) {
+        const long m = m0 + mt * 16 + (lane >> 4) * 4 + i;
+        const long mc = m < a.M ? m : a.M - 1;
+        float val = v[i];
+        int dim;
+        if (part < 2) {
+          const int j = qd * 8 + (col & 7);
+          const float2 t = a.cs[mc * 32 + j];
+          const float o = __shfl_xor(val, 8, 64);
+          val = col < 8 ? val * t.x - o * t.y : val * t.x + o * t.y;
+          dim = col < 8 ? j : j + 32;
+        } else {
+          dim = qd * 16 + col;
+        }
+        if (m < a.M) {
+          if (part == 0) {
+            ((f16_t*)a.Y)[m * a.ldy + hh * FM_HD + dim] = (f16_t)val;
+          } else {
+            const int p = a.pos[m];
+            if (p >= 0) {
+              const long base = (m / a.RPS) * a.seq_stride + (long)hh * a.capb * 2048;
+              if (part == 1) ((f16_t*)a.Kc)[base + kblk_off(p, dim)] = (f16_t)val;
+              else ((f16_t*)a.Vc)[base + vblk_off(p, dim)] = (f16_t)val;
+            }
+          }
+        }
+      }
+    } else if (n < a.N) {
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const long m = m0 + mt * 16 + (lane >> 4) * 4 + i;
@@ -273,6 +307,10 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
 
 template <int MT, bool NORM>
 void gemm_mfma_dispatch2(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
+  if (epi == EPI_QKV) {
+    if constexpr (NORM) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_QKV, true>), grid, dim3(256), 0, st, a, sp);
+    return;
+  }
   if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32, NORM>), grid, dim3(256), 0, st, a, sp);
   else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T, NORM>), grid, dim3(256), 0, st, a, sp);
   else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T, NORM>), grid, dim3(256), 0, st, a, sp);
