@@ -129,8 +129,10 @@ struct GemmSplit {
 // NORM: X is fp32 and each row is RMS-normalised on the fly: the MFMA runs on half(x * gain) and the per-row factor
 // 1/rms is applied to the accumulated tile (every workgroup walks the whole K of its rows, so it has the row sums
 // of squares itself; partial sums per wave meet in LDS next to the partial tiles, in a fixed order).
+// (two workgroups per CU: launches of 257..512 workgroups, e.g. the 288 and 384 tiles of d = 1536, then take one
+// round instead of two)
 template <int MT, int EPI, bool NORM>
-__global__ __launch_bounds__(256) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
+__global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   if (a.run_flag && *a.run_flag == 0) return;
   __shared__ f32x4 red[4][MT][64];
   __shared__ float sq[NORM ? 4 : 1][MT][16];
