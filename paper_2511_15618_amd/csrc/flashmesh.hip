@@ -566,9 +566,9 @@ int build_persist(fm_ctx* c) {
   a.tap[0] = c->tap_c; a.tap[1] = c->tap_v; a.tap[2] = c->tap_f;
   a.emb = (const f16_t*)c->emb; a.short_cv = (const f16_t*)c->short_cv; a.short_vf = (const f16_t*)c->short_vf;
   a.lm = (const f16_t*)c->lm; a.gf = c->gf; a.logits = c->logits;
-  // panels that every workgroup reads are kept in PK_NREP copies (see fm_kernels_persist.h)
   const size_t nl = hl.size();
-  // GEMM input panels: one region per layer, so that no address is written twice within a launch
+  // GEMM inputs (fp32 residual stream and its half-pair copy, attention outputs, FFN hidden): one region per layer,
+  // so that no address is written twice within a launch
   TRY(dalloc(c, &a.hA, (nl + 1) * 16 * d)); TRY(dalloc(c, &a.hB, nl * 16 * d)); TRY(dalloc(c, &a.hC, nl * 16 * d));
   for (int i = 0; i < 4; i++) TRY(dalloc(c, &a.hT[i], 16 * d));
   TRY(dalloc(c, &a.xA, (nl + 1) * 8 * d)); TRY(dalloc(c, &a.xB, nl * 8 * d)); TRY(dalloc(c, &a.xC, nl * 8 * d));

@@ -7,8 +7,9 @@
 // through "tagged" exchange buffers: every 8-byte element carries 4 bytes of payload and a 4-byte tag
 // (launch epoch, layer).  A consumer simply re-reads an element until its tag is the one it expects, so
 // correctness never depends on the order in which stores become visible across XCDs, and there is no
-// grid barrier.  Payloads are written / read with agent-scope 8-byte atomics (single-copy atomic, and
-// they bypass the per-XCD L2, which is not coherent across XCDs inside a launch).
+// grid barrier.  Elements are written with agent-scope 8-byte atomic stores and read with agent-scope loads
+// (8-byte atomics for single elements, 16-byte loads of two elements for bulk reads: each element still
+// arrives whole), which bypass the per-XCD L2, not coherent across XCDs inside a launch.
 // A workgroup that is not needed in a stage runs ahead and issues the weight loads of its next tile
 // before it starts waiting, which is what keeps HBM busy across the dependency chain.
 //
@@ -321,7 +322,7 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_c
 
 // residual epilogue (wave 0): out[r][n] = old[r][n] + c; optional copies into position-indexed rings
 // The residual operand of a tile (complete long before the tile's GEMM input is) is fetched by wave 0 at the
-// start of the unit, so that its latency hides behind the wait for the input panel.
+// start of the unit, so that its latency hides behind the wait for the GEMM input.
 __device__ __forceinline__ bool pk_res_prefetch(const PkArgs& a, int nt, const u64* hold, unsigned tag_old, int R,
                                                 const int* pos, unsigned (&old)[4], int (&prow)[4], int stage) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
@@ -740,7 +741,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       const unsigned tag = PK_TAG(a, l);
       const int* pos = a.pos[lev];
       const int capb = a.capb[lev];
-      // this layer's own regions of the panel buffers
+      // this layer's own regions of the exchange buffers
       u64* const hA_l = a.hA + (long)l * 16 * d;
       u64* const hA_n = a.hA + (long)(l + 1) * 16 * d;
       u64* const hB_l = a.hB + (long)l * 16 * d;
