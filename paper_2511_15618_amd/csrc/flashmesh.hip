@@ -651,7 +651,8 @@ int build_buffers(fm_ctx* c) {
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
-  c->mres = MfmaRes{nullptr, nullptr, 0};
+  c->mres = MfmaRes{nullptr, nullptr, 0, 0};
+  if (const char* e = getenv("FM_GEMM_WAVES")) c->mres.gemm_waves = atoi(e);   // measurement switch: 4, 8 or 16
   if (c->bf16) {
     c->mres.attn_ws_floats = mfma_attn_ws_floats(D.S, D.H);
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));

@@ -131,11 +131,14 @@ struct GemmSplit {
 // of squares itself; partial sums per wave meet in LDS next to the partial tiles, in a fixed order).
 // (two workgroups per CU: launches of 257..512 workgroups, e.g. the 288 and 384 tiles of d = 1536, then take one
 // round instead of two)
-template <int MT, int EPI, bool NORM>
-__global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
+// NW waves per workgroup (4, 8 or 16) split K: launches with few column tiles (N = d gives 64 to 96 of them)
+// take more waves per workgroup so that enough loads are in flight and each wave's K walk stays short.
+template <int MT, int EPI, bool NORM, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   if (a.run_flag && *a.run_flag == 0) return;
-  __shared__ f32x4 red[4][MT][64];
-  __shared__ float sq[NORM ? 4 : 1][MT][16];
+  static_assert(NW * MT <= 60, "partial tiles of all waves must fit the static LDS limit");
+  __shared__ f32x4 red[NW][MT][64];
+  __shared__ float sq[NORM ? NW : 1][MT][16];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nt = blockIdx.x;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
@@ -162,42 +165,46 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmArgs a, GemmSplit sp) 
 
   // K is walked in chunks of U fragments; the loads of the next chunk are in flight while this one is
   // multiplied (a workgroup is often alone on its CU, so nothing else would hide the latency)
-  constexpr int U = NORM ? (MT <= 2 ? 4 : MT <= 5 ? 2 : 1) : (MT <= 2 ? 8 : MT <= 5 ? 4 : 2);
+  constexpr int U4 = NORM ? (MT <= 2 ? 4 : MT <= 5 ? 2 : 1) : (MT <= 2 ? 8 : MT <= 5 ? 4 : 2);
+  constexpr int U = NW == 16 ? (U4 >= 4 ? U4 / 4 : 1) : NW == 8 ? (U4 >= 2 ? U4 / 2 : 1) : U4;
   struct AFrag { typename std::conditional<NORM, f32x4, f16x8>::type lo; f32x4 hi; };   // hi only used when NORM
   f16x8 bc[U];
   AFrag ac[MT][U];
   f32x4 gc[NORM ? U : 1][2];
-  auto load_chunk = [&](f16x8 (&b)[U], AFrag (&af)[MT][U], f32x4 (&gg)[NORM ? U : 1][2], int kt) {
+  const int nk = kt1 - kt0;
+  auto kmap = [&](int i) { return kt0 + i; };
+  auto load_chunk = [&](f16x8 (&b)[U], AFrag (&af)[MT][U], f32x4 (&gg)[NORM ? U : 1][2], int i0) {
 #pragma unroll
     for (int u = 0; u < U; u++) {
-      if (kt + u < kt1) {
-        b[u] = *reinterpret_cast<const f16x8*>(W + ((long)(kt + u) * 64 + lane) * 8);
+      if (i0 + u < nk) {
+        const int kt = kmap(i0 + u);
+        b[u] = *reinterpret_cast<const f16x8*>(W + ((long)kt * 64 + lane) * 8);
         if constexpr (NORM) {
-          const float* gp = a.gain + (kt + u) * 32 + (lane >> 4) * 8;
+          const float* gp = a.gain + kt * 32 + (lane >> 4) * 8;
           gg[u][0] = *reinterpret_cast<const f32x4*>(gp);
           gg[u][1] = *reinterpret_cast<const f32x4*>(gp + 4);
         }
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
           if constexpr (NORM) {
-            af[mt][u].lo = *reinterpret_cast<const f32x4*>(xrow[mt] + (kt + u) * 32);
-            af[mt][u].hi = *reinterpret_cast<const f32x4*>(xrow[mt] + (kt + u) * 32 + 4);
+            af[mt][u].lo = *reinterpret_cast<const f32x4*>(xrow[mt] + kt * 32);
+            af[mt][u].hi = *reinterpret_cast<const f32x4*>(xrow[mt] + kt * 32 + 4);
           } else {
-            af[mt][u].lo = *reinterpret_cast<const f16x8*>(xrow[mt] + (kt + u) * 32);
+            af[mt][u].lo = *reinterpret_cast<const f16x8*>(xrow[mt] + kt * 32);
           }
         }
       }
     }
   };
-  load_chunk(bc, ac, gc, kt0);
-  for (int kt = kt0; kt < kt1; kt += U) {
+  load_chunk(bc, ac, gc, 0);
+  for (int i0 = 0; i0 < nk; i0 += U) {
     f16x8 bn[U];
     AFrag an[MT][U];
     f32x4 gn[NORM ? U : 1][2];
-    load_chunk(bn, an, gn, kt + U);
+    load_chunk(bn, an, gn, i0 + U);
 #pragma unroll
     for (int u = 0; u < U; u++) {
-      if (kt + u < kt1) {
+      if (i0 + u < nk) {
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
           f16x8 av;
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmArgs a, GemmSplit sp) 
       for (int mt = 0; mt < MT; mt++) ac[mt][u] = an[mt][u];
     }
   }
-  // reduce the four K-quarters of the workgroup through LDS
+  // reduce the K-slices of the waves through LDS, in wave order
 #pragma unroll
   for (int mt = 0; mt < MT; mt++) {
     red[wave][mt][lane] = acc[mt];
@@ -237,15 +244,17 @@ __global__ __launch_bounds__(256, 2) void k_gemm_mfma(GemmArgs a, GemmSplit sp) 
   }
   __syncthreads();
   const int n = nt * 16 + (lane & 15);
-  for (int mt = wave; mt < MT; mt += 4) {
+  for (int mt = wave; mt < MT; mt += NW) {
     f32x4 v = red[0][mt][lane];
 #pragma unroll
-    for (int w = 1; w < 4; w++) v += red[w][mt][lane];
+    for (int w = 1; w < NW; w++) v += red[w][mt][lane];
     if constexpr (NORM) {
 #pragma unroll
       for (int i = 0; i < 4; i++) {
         const int row = (lane >> 4) * 4 + i;
-        const float tot = sq[0][mt][row] + sq[1][mt][row] + sq[2][mt][row] + sq[3][mt][row];
+        float tot = sq[0][mt][row];
+#pragma unroll
+        for (int w = 1; w < NW; w++) tot += sq[w][mt][row];
         v[i] *= 1.0f / sqrtf(tot / (float)a.K + a.eps);
       }
     }
@@ -305,22 +314,29 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
   float* attn_ws;
   unsigned* attn_counters;
   size_t attn_ws_floats;
+  int gemm_waves;     // 0 = choose per launch; 4, 8, 16 = forced (measurement switch)
 };
 
-template <int MT, bool NORM>
-void gemm_mfma_dispatch2(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
+template <int MT, bool NORM, int NW>
+void gemm_mfma_dispatch3(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
   if (epi == EPI_QKV) {
-    if constexpr (NORM) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_QKV, true>), grid, dim3(256), 0, st, a, sp);
+    if constexpr (NORM) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_QKV, true, NW>), grid, dim3(NW * 64), 0, st, a, sp);
     return;
   }
-  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32, NORM>), grid, dim3(256), 0, st, a, sp);
-  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T, NORM>), grid, dim3(256), 0, st, a, sp);
-  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T, NORM>), grid, dim3(256), 0, st, a, sp);
+  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32, NORM, NW>), grid, dim3(NW * 64), 0, st, a, sp);
+  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T, NORM, NW>), grid, dim3(NW * 64), 0, st, a, sp);
+  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T, NORM, NW>), grid, dim3(NW * 64), 0, st, a, sp);
+}
+template <int MT, bool NORM>
+void gemm_mfma_dispatch2(const GemmArgs& a, const GemmSplit& sp, int nw, int epi, dim3 grid, hipStream_t st) {
+  if constexpr (MT <= 3) { if (nw == 16) { gemm_mfma_dispatch3<MT, NORM, 16>(a, sp, epi, grid, st); return; } }
+  if constexpr (MT <= 5) { if (nw >= 8) { gemm_mfma_dispatch3<MT, NORM, 8>(a, sp, epi, grid, st); return; } }
+  gemm_mfma_dispatch3<MT, NORM, 4>(a, sp, epi, grid, st);
 }
 template <int MT>
-void gemm_mfma_dispatch(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
-  if (a.gain) gemm_mfma_dispatch2<MT, true>(a, sp, epi, grid, st);
-  else gemm_mfma_dispatch2<MT, false>(a, sp, epi, grid, st);
+void gemm_mfma_dispatch(const GemmArgs& a, const GemmSplit& sp, int nw, int epi, dim3 grid, hipStream_t st) {
+  if (a.gain) gemm_mfma_dispatch2<MT, true>(a, sp, nw, epi, grid, st);
+  else gemm_mfma_dispatch2<MT, false>(a, sp, nw, epi, grid, st);
 }
 
 template <typename T>
@@ -333,14 +349,21 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   const int mtiles = (a.M + 15) / 16;
   const int MT = mtiles <= 1 ? 1 : mtiles <= 2 ? 2 : mtiles <= 3 ? 3 : mtiles <= 5 ? 5 : 8;
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
-  GemmSplit sp{(KT + 3) / 4};      // the four waves of a workgroup split K
+  // waves per workgroup: enough for about 2048 waves in the launch, at least two K fragments per wave, and the
+  // partial tiles of all waves within the static LDS limit
+  const long wgs = (long)NT * groups * nmb;
+  const int nw_max = MT <= 3 ? 16 : MT <= 5 ? 8 : 4;
+  int nw = 4;
+  while (nw < nw_max && wgs * nw < 2048 && KT / (nw * 2) >= 2) nw *= 2;
+  if (res.gemm_waves == 4 || res.gemm_waves == 8 || res.gemm_waves == 16) nw = res.gemm_waves < nw_max ? res.gemm_waves : nw_max;
+  GemmSplit sp{(KT + nw - 1) / nw};   // the waves of a workgroup split K
   dim3 grid(NT, 1, groups * nmb);
   switch (MT) {
-    case 1: gemm_mfma_dispatch<1>(a, sp, epi, grid, st); break;
-    case 2: gemm_mfma_dispatch<2>(a, sp, epi, grid, st); break;
-    case 3: gemm_mfma_dispatch<3>(a, sp, epi, grid, st); break;
-    case 5: gemm_mfma_dispatch<5>(a, sp, epi, grid, st); break;
-    default: gemm_mfma_dispatch<8>(a, sp, epi, grid, st); break;
+    case 1: gemm_mfma_dispatch<1>(a, sp, nw, epi, grid, st); break;
+    case 2: gemm_mfma_dispatch<2>(a, sp, nw, epi, grid, st); break;
+    case 3: gemm_mfma_dispatch<3>(a, sp, nw, epi, grid, st); break;
+    case 5: gemm_mfma_dispatch<5>(a, sp, nw, epi, grid, st); break;
+    default: gemm_mfma_dispatch<8>(a, sp, nw, epi, grid, st); break;
   }
   return true;
 }
