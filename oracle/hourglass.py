@@ -16,6 +16,14 @@ token f pools vertex tokens 3f-2..3f and is upsampled onto vertex tokens
 3f..3f+2.  Upsampling is repeat plus the skip connection from before the
 shortening.  Everything is causal.
 
+Sliding window (Sec. 5.1 names a window size of 18K / 36K tokens and nothing
+else; a reading): with cfg.window = W > 0 a self-attention row at position p of
+the coordinate level sees keys [p - W + 1, p]; the vertex and face levels use
+W/3 and W/9 of their own positions, i.e. the same span of the mesh.  Rotary
+positions stay absolute; cross-attention to the condition is not windowed.
+The oracle keeps every key and masks, which is the definition; a ring buffer is
+an implementation of it.
+
 bf16 configurations: the weights arrive already rounded to bf16 values and all
 arithmetic on them is done in the working precision (float64 by default) with
 no further rounding: the oracle is the exact forward function of the
@@ -124,7 +132,7 @@ def forward_full(model: Model, tokens, mem, taps=None):
             if taps is not None and i == m.layers[st] - 1 and st in ("cpost", "vpost", "face"):
                 taps["tap_" + LEVEL_OF[st]] = h.copy()
             q, k, v = m.qkv(pfx, h, pos)
-            o = P.attend_causal(q, k, v, 0)
+            o = P.attend_causal(q, k, v, 0, m.cfg.level_window(LEVEL_OF[st]))
             if pfx not in mem_cache:
                 mem_cache[pfx] = m.mem_kv(pfx, mem)
             h = m.after_self_attention(pfx, h, o, *mem_cache[pfx])
@@ -203,10 +211,11 @@ def forward_block(model: Model, st: SeqState, tokens, long_block=False):
             q, k, v = m.qkv(pfx, h, pos)
             st.K[pfx][pos] = k
             st.V[pfx][pos] = v
+            win = m.cfg.level_window(lvl)
             if long_block:
-                o = P.attend_causal(q, st.K[pfx], st.V[pfx], first)
+                o = P.attend_causal(q, st.K[pfx], st.V[pfx], first, win)
             else:
-                o = P.attend(q, st.K[pfx], st.V[pfx], pos)
+                o = P.attend(q, st.K[pfx], st.V[pfx], pos, win)
             h = m.after_self_attention(pfx, h, o, st.Kmem[pfx], st.Vmem[pfx])
         return h
 

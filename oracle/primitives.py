@@ -56,10 +56,12 @@ def rope(x, pos, base):
     return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
 
 
-def attend(q, K, V, limit):
-    """Scaled dot-product attention, one query row at a time over keys [0, limit[row]].
+def attend(q, K, V, limit, window=0):
+    """Scaled dot-product attention, one query row at a time over keys [first, limit[row]].
 
     q [rows, H, 64]; K, V [L, H, 64]; limit[row] is the last visible key (inclusive).
+    window = 0: first = 0.  window = W > 0 (sliding window, Sec. 5.1 "window size"): a row sees the
+    W keys that end at its limit, first = max(0, limit[row] - W + 1).
     Scores are scaled by 1/sqrt(64); softmax in the working precision."""
     rows, H, _ = q.shape
     out = np.zeros_like(q)
@@ -68,19 +70,22 @@ def attend(q, K, V, limit):
     if rows and np.all(lim == lim[0]):
         # all rows see the same keys: one batched product per head
         n = int(lim[0]) + 1
-        s = np.matmul(q.transpose(1, 0, 2), K[:n].transpose(1, 2, 0)) * scale    # [H, rows, n]
-        return np.matmul(softmax(s), V[:n].transpose(1, 0, 2)).transpose(1, 0, 2)
+        a = max(0, n - window) if window > 0 else 0
+        s = np.matmul(q.transpose(1, 0, 2), K[a:n].transpose(1, 2, 0)) * scale    # [H, rows, n - a]
+        return np.matmul(softmax(s), V[a:n].transpose(1, 0, 2)).transpose(1, 0, 2)
     for r in range(rows):
         n = int(lim[r]) + 1
-        s = np.einsum("hd,khd->hk", q[r], K[:n]) * scale
-        out[r] = np.einsum("hk,khd->hd", softmax(s), V[:n])
+        a = max(0, n - window) if window > 0 else 0
+        s = np.einsum("hd,khd->hk", q[r], K[a:n]) * scale
+        out[r] = np.einsum("hk,khd->hd", softmax(s), V[a:n])
     return out
 
 
-def attend_causal(q, K, V, first_pos):
-    """Block-causal attention: row r (absolute position first_pos + r) sees keys [0, first_pos + r].
+def attend_causal(q, K, V, first_pos, window=0):
+    """Block-causal attention: row r (absolute position p = first_pos + r) sees keys [0, p], or with a
+    window W > 0 the keys [max(0, p - W + 1), p].
 
-    Same result as attend(q, K, V, first_pos + arange(rows)) but with one masked
+    Same result as attend(q, K, V, first_pos + arange(rows), window) but with one masked
     matrix product per head, for long teacher-forced blocks."""
     rows, H, _ = q.shape
     n = first_pos + rows
@@ -88,5 +93,8 @@ def attend_causal(q, K, V, first_pos):
     s = np.matmul(q.transpose(1, 0, 2), K[:n].transpose(1, 2, 0)) * scale        # [H, rows, n]
     kk = np.arange(n)[None, :]
     rr = (first_pos + np.arange(rows))[:, None]
-    s = np.where((kk <= rr)[None, :, :], s, -np.inf)
+    seen = kk <= rr
+    if window > 0:
+        seen = seen & (kk > rr - window)
+    s = np.where(seen[None, :, :], s, -np.inf)
     return np.matmul(softmax(s), V[:n].transpose(1, 0, 2)).transpose(1, 0, 2)

@@ -67,7 +67,7 @@ def sp_head(model: Model, st: SeqState, lvl: str, k: int, h_s, s_l: int):
     pfx = _last_prefix(m, lvl)
     x = rnd(P.rmsnorm(h_s[None, :], m.w[p + "g"], cfg.rms_eps))
     q = rnd(P.rope(m.heads(m.lin(x, p + "wq")), [s_l], cfg.rope_base))
-    a = P.attend(q, st.K[pfx], st.V[pfx], [s_l]).reshape(1, m.d)
+    a = P.attend(q, st.K[pfx], st.V[pfx], [s_l], cfg.level_window(lvl)).reshape(1, m.d)
     a = m.lin(rnd(a), p + "wo")
     q2 = rnd(m.heads(m.lin(rnd(a), p + "cq")))
     c = P.attend(q2, st.Kmem[pfx], st.Vmem[pfx], [st.Kmem[pfx].shape[0] - 1]).reshape(1, m.d)
@@ -85,7 +85,7 @@ def hf_block(model: Model, st: SeqState, lvl: str, t: int, h_up, pos: int, limit
     pfx = _last_prefix(m, lvl)
     x = rnd(P.rmsnorm(h_up[None, :], m.w[p + "g"], cfg.rms_eps))
     q = rnd(P.rope(m.heads(m.lin(x, p + "wq")), [pos], cfg.rope_base))
-    a = P.attend(q, st.K[pfx], st.V[pfx], [limit]).reshape(1, m.d)
+    a = P.attend(q, st.K[pfx], st.V[pfx], [limit], cfg.level_window(lvl)).reshape(1, m.d)
     z = rnd(P.gelu_tanh(m.lin(rnd(a), p + "w1")))
     return (h_up[None, :] + m.lin(z, p + "w2"))[0]
 

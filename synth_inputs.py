@@ -46,6 +46,7 @@ class Config:
     ban_specials: int = 1
     rope_base: float = 10000.0
     rms_eps: float = 1e-6
+    window: int = 0       # self-attention window in coordinate tokens (multiple of 9); 0 = the whole context
 
     @property
     def vocab(self) -> int:
@@ -66,6 +67,11 @@ class Config:
     @property
     def max_tokens(self) -> int:
         return 9 * self.faces
+
+    def level_window(self, lvl: str) -> int:
+        """Window at level "c" / "v" / "f" in that level's own positions (0 = unbounded): the same span of the
+        mesh at every level."""
+        return self.window // {"c": 1, "v": 3, "f": 9}[lvl]
 
     @property
     def block_max(self) -> int:

@@ -53,6 +53,64 @@ def test_incremental_equals_full(name):
             assert np.abs(st.y_f[:nf] - taps["y_f"]).max() < 1e-9
 
 
+@pytest.mark.parametrize("window", [9, 18, 27])
+def test_incremental_equals_full_with_sliding_window(window):
+    """With a window shorter than the sequence the cached block forward still equals the full recompute,
+    and the logits differ from the unwindowed model once the window has started to drop keys."""
+    cfg, m, mem = _model("t_f32_99", window=window)
+    _, m_all, _ = _model("t_f32_99")
+    T = 64
+    toks = _tokens(cfg, T)
+    full = forward_full(m, toks, mem)
+    full_all = forward_full(m_all, toks, mem)
+    # the face level sees window/9 faces: position p is unaffected while p < window/9 * 9 - 8 at least
+    assert np.abs(full[:window // 9] - full_all[:window // 9]).max() < 1e-12
+    assert np.abs(full[window + 9:] - full_all[window + 9:]).max() > 1e-6
+    r = np.random.default_rng(11)
+    for trial in range(4):
+        st = SeqState(m, mem, T)
+        i = 0
+        while i < T:
+            B = min(int(r.integers(1, 20)) if trial else 1, T - i)
+            lg = forward_block(m, st, toks[i:i + B], long_block=bool(trial % 2))
+            assert np.abs(lg - full[i:i + B]).max() < 1e-9, (trial, i, B)
+            i += B
+            st.P = i
+
+
+def test_sliding_window_forgets_old_tokens():
+    """Changing a token that has left the window of every level cannot change a later logit row; changing one
+    inside the window does (the window is measured in the level's own positions: W, W/3, W/9)."""
+    cfg, m, mem = _model("t_f32_99", window=9)
+    T = 118
+    toks = _tokens(cfg, T)
+    base = forward_full(m, toks, mem)
+    # Information from position 3 travels at most one window per layer and level; the chain is finite, so far
+    # enough downstream the logits are untouched.  Windows 9 / 3 / 1: per coordinate layer 8 positions (3 layers),
+    # per vertex layer 2 vertices = 6 positions (3 layers), the face layers see their own face only; the two
+    # poolings and upsamplings add at most 2 + 8 + 8 positions: under 70 in all.
+    other = list(toks)
+    other[3] = (other[3] + 1) % cfg.n_bins
+    alt = forward_full(m, other, mem)
+    assert np.abs(alt[4] - base[4]).max() > 1e-9
+    _, m_all, _ = _model("t_f32_99")
+    reach_all = np.abs(forward_full(m_all, other, mem) - forward_full(m_all, toks, mem)).max(axis=1)
+    reach = np.abs(alt - base).max(axis=1)
+    assert reach_all[-1] > 1e-9            # without a window the change is visible to the end
+    last = np.nonzero(reach > 0)[0].max()
+    assert last < 3 + 70 and reach[-1] == 0.0, last
+
+
+def test_speculative_equals_sequential_with_sliding_window():
+    cfg, m, mem = _model("t_f32_99", window=18, faces=8)
+    seq, _ = sp.generate(m, mem, cfg.faces, speculative=False)
+    spec, _ = sp.generate(m, mem, cfg.faces, speculative=True)
+    assert seq == spec and len(seq) == 9 * cfg.faces
+    _, m_all, _ = _model("t_f32_99", faces=8)
+    seq_all, _ = sp.generate(m_all, mem, cfg.faces, speculative=False)
+    assert seq_all[:18] == seq[:18]
+
+
 def test_every_block_length_and_phase():
     """All block lengths 1..19 from every start phase mod 9, re-verified after a partial commit."""
     cfg, m, mem = _model("t_f32_c")

@@ -105,6 +105,40 @@ def test_attend_matches_triple_loop():
     assert np.allclose(got, _attend_loops(q, K, V, [5, 6, 7, 8]), atol=1e-12)
 
 
+def test_windowed_attention_closed_forms_and_brute_force():
+    """Sliding window (Sec. 5.1 "window size"): a row with limit p sees the W keys [p - W + 1, p]."""
+    q = rng.standard_normal((4, 2, 64))
+    K = rng.standard_normal((12, 2, 64))
+    V = rng.standard_normal((12, 2, 64))
+    lim = [0, 5, 11, 3]
+    # W = 1: softmax over a single key, the result is that key's value row
+    got = P.attend(q, K, V, lim, window=1)
+    for r, p_ in enumerate(lim):
+        assert np.allclose(got[r], V[p_], atol=1e-13)
+    assert np.allclose(P.attend_causal(q, K, V, 8, window=1), V[8:12], atol=1e-13)
+    # identical keys: uniform weights, the result is the mean of exactly the visible values
+    Kc = np.broadcast_to(K[:1], K.shape)
+    for W in (2, 3, 5):
+        got = P.attend(q, Kc, V, lim, window=W)
+        for r, p_ in enumerate(lim):
+            assert np.allclose(got[r], V[max(0, p_ - W + 1):p_ + 1].mean(axis=0), atol=1e-12), (W, r)
+        got = P.attend_causal(q, Kc, V, 8, window=W)
+        for r in range(4):
+            assert np.allclose(got[r], V[8 + r - W + 1:8 + r + 1].mean(axis=0), atol=1e-12), (W, r)
+    # brute force: plain attention over the slice of visible keys
+    for W in (1, 4, 7, 50):
+        got = P.attend(q, K, V, lim, window=W)
+        for r, p_ in enumerate(lim):
+            a = max(0, p_ - W + 1)
+            want = _attend_loops(q[r:r + 1], K[a:p_ + 1], V[a:p_ + 1], [p_ - a])
+            assert np.allclose(got[r], want[0], atol=1e-12), (W, r)
+        assert np.allclose(P.attend_causal(q, K, V, 8, window=W), P.attend(q, K, V, [8, 9, 10, 11], window=W), atol=1e-12)
+        assert np.allclose(P.attend(q, K, V, [9] * 4, window=W), _attend_loops(q, K[max(0, 10 - W):10], V[max(0, 10 - W):10], [min(W, 10) - 1] * 4), atol=1e-12)
+    # a window that covers everything changes nothing
+    assert np.array_equal(P.attend(q, K, V, lim, window=12), P.attend(q, K, V, lim))
+    assert np.array_equal(P.attend_causal(q, K, V, 8, window=12), P.attend_causal(q, K, V, 8))
+
+
 def test_attend_matches_torch_sdpa():
     q = torch.randn(5, 3, 64, dtype=torch.float64)
     K = torch.randn(5, 3, 64, dtype=torch.float64)
