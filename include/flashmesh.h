@@ -57,6 +57,11 @@ typedef struct {
   int32_t hf_ffn_mult;  /* width multiplier of FFN^(t) in the HF block (Eq. 6)                     */
   int32_t ban_specials; /* 1: argmax over the coordinate bins only (BOS/EOS/PAD never chosen)      */
   float rope_base, rms_eps;
+  int32_t window;       /* sliding-window self-attention (Sec. 5.1 "window size"): 0 = a position sees the whole
+                           context and max_tokens is also the K/V capacity; W > 0 (multiple of 9) = a position p
+                           of the coordinate level sees keys [p-W+1, p], the vertex and face levels W/3 and W/9
+                           of their own positions, the K/V caches are rings of W + block_max positions (rounded
+                           up to 32) and max_tokens only bounds the length of the emitted stream                 */
 } fm_config;
 
 typedef struct {

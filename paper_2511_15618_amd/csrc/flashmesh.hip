@@ -149,6 +149,7 @@ int dalloc_t(fm_ctx* c, void** p, size_t n) {  // n elements of the storage type
 #define TRY(x) do { int rc_ = (x); if (rc_ != FM_OK) return rc_; } while (0)
 
 int level_cap(const fm_ctx* c, int level) { return level == 0 ? c->D.capc : level == 1 ? c->D.capv : c->D.capf; }
+int level_window(const fm_ctx* c, int level) { return level == 0 ? c->D.wc : level == 1 ? c->D.wv : c->D.wf; }
 // Upper bound on the keys any row of the next pass can see at `level`, from the host's bound on the committed
 // lengths (a commit adds at most block_max tokens; fm_read_state and the generate loop tighten it).
 int level_key_bound(const fm_ctx* c, int level) {
@@ -178,12 +179,13 @@ void gemm(fm_ctx* c, int epi, const void* X, long ldx, long gsx, const void* W, 
 
 template <typename T>
 void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
-               long seq_stride, int cap, void* out, const int* flag, bool dense = false, int key_bound = 1 << 30) {
-  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, c->stream)) return;
+               long seq_stride, int cap, void* out, const int* flag, bool dense = false, int key_bound = 1 << 30,
+               int window = 0) {
+  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, window, c->stream)) return;
   // the plain kernel reads row-major caches: only the fp32 path has those
   if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "attention: unsupported row set (%d rows, %d per sequence)", rows, RPS); c->sticky_error = true; return; }
   hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
-                     (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag);
+                     (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag, window);
 }
 
 template <typename T>
@@ -245,7 +247,8 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
     gemm_norm<T>(c, EPI_F32, h, L.g1, L.wqkv, c->qkv, 3 * d, rows, 3 * d, flag);
     rope_append<T>(c, c->qkv, (long)3 * d, c->cs[level], c->pos[level], rows, RPS, c->qT, L.Kc, L.Vc, cap, flag);
   }
-  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag, false, level_key_bound(c, level));
+  attention<T>(c, c->qT, c->pos[level], rows, RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), cap, c->attT, flag, false,
+               level_key_bound(c, level), level_window(c, level));
   gemm<T>(c, EPI_F32, c->attT, d, 0, L.wo, 0, h, d, 0, h, d, 0, rows, d, d, 1, flag);
   gemm_norm<T>(c, EPI_T, h, L.g2, L.cq, c->qT, d, rows, d, flag);
   attention<T>(c, c->qT, c->limx[level], rows, RPS, L.Km, L.Vm, (long)cache_seq_elems(c, D.M), D.M, c->attT, flag, true);
@@ -332,7 +335,8 @@ void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level,
   rmsnorm<T>(c, nullptr, c->dr.src[set], sp.g, G, c->dxn, c->dkeep, rows, flag);
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.wq, dd, c->dtmp, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[set], c->dr.pos[set], rows, G, c->dq, nullptr, nullptr, cap, flag);
-  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag, false, level_key_bound(c, level));
+  attention<T>(c, c->dq, c->dr.lim[set], rows, G, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag, false,
+               level_key_bound(c, level), level_window(c, level));
   gemm<T>(c, EPI_T, c->datt, (long)G * d, d, sp.wo, dd, c->dxn, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   gemm<T>(c, EPI_T, c->dxn, (long)G * d, d, sp.cq, dd, c->dq, (long)G * d, d, nullptr, 0, 0, D.S, d, d, G, flag);
   attention<T>(c, c->dq, c->dr.limx[set], rows, G, last.Km, last.Vm, (long)cache_seq_elems(c, D.M), D.M, c->datt, flag, true);
@@ -354,7 +358,8 @@ void run_hf(fm_ctx* c, int set, const HfLevel& hf, int mult, const Layer& last, 
   rmsnorm<T>(c, nullptr, c->dr.src[set], hf.g, G, c->dxn, c->dkeep, rows, flag);
   gemm<T>(c, EPI_F32, c->dxn, ld, d, hf.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, Mg, d, d, G, flag);
   rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[set], c->dr.pos[set], rows, per_seq, c->dq, nullptr, nullptr, cap, flag);
-  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag, false, level_key_bound(c, level));
+  attention<T>(c, c->dq, c->dr.lim[set], rows, per_seq, last.Kc, last.Vc, (long)cache_seq_elems(c, cap), cap, c->datt, flag, false,
+               level_key_bound(c, level), level_window(c, level));
   gemm<T>(c, EPI_GELU_T, c->datt, ld, d, hf.w1, dh, c->dmid, (long)G * c->hff, c->hff, nullptr, 0, 0, Mg, c->hff, d, G, flag);
   gemm<T>(c, EPI_F32, c->dmid, (long)G * c->hff, c->hff, hf.w2, dh, out, ld, d, c->dkeep, ld, d, Mg, d, c->hff, G, flag);
 }
@@ -610,7 +615,7 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &st.firedv, S)); TRY(dalloc(c, &st.firedf, S));
   TRY(dalloc(c, &st.basec, S)); TRY(dalloc(c, &st.basev, S)); TRY(dalloc(c, &st.basef, S));
   TRY(dalloc(c, &st.vlen, S)); TRY(dalloc(c, &st.vtok, S * D.Bm)); TRY(dalloc(c, &st.y, S * D.Bm)); TRY(dalloc(c, &st.acc, S));
-  TRY(dalloc(c, &st.hist, S * (D.capc + 1))); TRY(dalloc(c, &st.budget, 1)); TRY(dalloc(c, &st.alive, 1));
+  TRY(dalloc(c, &st.hist, S * (D.maxtok + 1))); TRY(dalloc(c, &st.budget, 1)); TRY(dalloc(c, &st.alive, 1));
   TRY(dalloc(c, &st.acc_hist, 32)); TRY(dalloc(c, &st.counters, 2));
   TRY(dalloc(c, &c->ring_hc, S * RS_C * d)); TRY(dalloc(c, &c->tap_c, S * RS_C * d));
   TRY(dalloc(c, &c->ring_hv, S * RS_V * d)); TRY(dalloc(c, &c->ring_yv, S * RS_V * d)); TRY(dalloc(c, &c->tap_v, S * RS_V * d));
@@ -696,6 +701,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   const int Bm = std::max(std::max(1 + g.draft_coord, g.draft_point), std::max(g.draft_face, 1));
   if (Bm > 27) return FM_EINVAL;  // rings hold 32 coordinate positions: block + 2 carried rows
   if (!(g.rope_base > 1.f) || !(g.rms_eps > 0.f)) return FM_EINVAL;
+  if (g.window < 0 || g.window % 9 != 0) return FM_EINVAL;
 
   fm_ctx* c = new (std::nothrow) fm_ctx();
   if (!c) return FM_ENOMEM;
@@ -708,7 +714,16 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   Dims& D = c->D;
   D.d = g.d_model; D.H = g.n_heads; D.V = g.n_bins + 3; D.S = g.max_batch; D.Bm = Bm;
   D.VB = (Bm + 2) / 3; D.FB = (Bm + 8) / 9; D.M = g.mem_len;
+  D.maxtok = g.max_tokens;
   D.capc = g.max_tokens; D.capv = (g.max_tokens + 2) / 3 + 1; D.capf = (g.max_tokens + 8) / 9 + 1;
+  D.wc = D.wv = D.wf = 0;
+  if (g.window > 0 && g.window < g.max_tokens) {
+    // rings: the window plus the rows of one pass (a rejected block leaves stale rows behind the committed
+    // length; they must only ever overwrite positions that no later query can see), in whole 32-key blocks
+    D.wc = g.window; D.wv = g.window / 3; D.wf = g.window / 9;
+    auto ring = [](int w, int rows) { return (w + rows + 2 + 31) / 32 * 32; };
+    D.capc = ring(D.wc, D.Bm); D.capv = ring(D.wv, D.VB); D.capf = ring(D.wf, D.FB);
+  }
   D.Dc = g.draft_coord; D.m = g.draft_point; D.n = g.draft_face;
   D.nspv = std::max(D.m / 3 - 1, 0); D.nspf = std::max(D.n / 9 - 1, 0);
   D.nhfc = std::max(std::max(D.m, D.n) - 3, 0); D.nhfv = std::max(D.n / 3 - 1, 0);
@@ -718,14 +733,15 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   for (int i = 0; i < 32; i++) c->inv.v[i] = std::pow((double)g.rope_base, -(double)i / 32.0);
   c->weights_loaded = false;
   c->prefilled.assign(D.S, false);
-  c->len_bound.assign(D.S, D.capc);
+  c->len_bound.assign(D.S, D.maxtok);
   c->replay = Replay{nullptr, 0, 0, 0.f, 0ull};
   c->host_flag = nullptr;
   {
     const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
     const char* env = getenv("FM_PERSIST");
+    // (the single-launch kernel reads caches that never wrap: a sliding window takes the per-operator path)
     c->persist = c->bf16 && D.S == 1 && D.Bm <= 16 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
-                 !(env && env[0] == '0');
+                 D.wc == 0 && !(env && env[0] == '0');
   }
   int rc = build_params(c);
   if (rc == FM_OK) rc = build_buffers(c);
@@ -827,14 +843,14 @@ int fm_commit(fm_ctx* c, const int32_t* accepted) {
   if (!accepted) return fail(c, FM_EINVAL, "null accepted buffer");
   hipLaunchKernelGGL(k_commit, dim3(1), dim3(64), 0, c->stream, c->st, c->D, accepted);
   HIPCHK(c, hipGetLastError());
-  for (int s = 0; s < c->D.S; s++) c->len_bound[s] = std::min(c->len_bound[s] + c->D.Bm, c->D.capc);
+  for (int s = 0; s < c->D.S; s++) c->len_bound[s] = std::min(c->len_bound[s] + c->D.Bm, c->D.maxtok);
   c->commits++;
   return FM_OK;
 }
 
 int fm_set_budget(fm_ctx* c, int32_t max_faces) {
   if (!c) return FM_EINVAL;
-  if (max_faces < 1 || 9 * max_faces > c->D.capc) return fail(c, FM_EINVAL, "max_faces %d outside [1,%d]", max_faces, c->D.capc / 9);
+  if (max_faces < 1 || 9 * max_faces > c->D.maxtok) return fail(c, FM_EINVAL, "max_faces %d outside [1,%d]", max_faces, c->D.maxtok / 9);
   hipLaunchKernelGGL(k_set_budget, dim3(1), dim3(64), 0, c->stream, c->st, c->D, 9 * max_faces);
   HIPCHK(c, hipGetLastError());
   return FM_OK;
@@ -901,7 +917,9 @@ int fm_verify_bytes(fm_ctx* c, double* host_bytes) {
   const fm_config& g = c->cfg;
   for (int s = 0; s < S; s++) {
     if (fin[s]) continue;
-    const double Lc = P[s], Lv = (P[s] + 2) / 3, Lf = (P[s] + 8) / 9, M = c->D.M;
+    double Lc = P[s], Lv = (P[s] + 2) / 3, Lf = (P[s] + 8) / 9;
+    const double M = c->D.M;
+    if (c->D.wc > 0) { Lc = std::min<double>(Lc, c->D.wc); Lv = std::min<double>(Lv, c->D.wv); Lf = std::min<double>(Lf, c->D.wf); }
     bytes += c->esz * 2.0 * c->D.d *
              ((g.l_cpre + g.l_cpost) * (Lc + M) + (g.l_vpre + g.l_vpost) * (Lv + M) + g.l_face * (Lf + M));
   }
@@ -1003,7 +1021,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
     HIPCHK(c, hipEventRecord(e1, c->stream));
     // outputs: x_1 .. x_P per sequence
     for (int s = 0; s < D.S; s++)
-      HIPCHK(c, hipMemcpyAsync(out_tok + (size_t)s * D.capc, c->st.hist + (size_t)s * (D.capc + 1) + 1, (size_t)D.capc * 4,
+      HIPCHK(c, hipMemcpyAsync(out_tok + (size_t)s * D.maxtok, c->st.hist + (size_t)s * (D.maxtok + 1) + 1, (size_t)D.maxtok * 4,
                                hipMemcpyDeviceToDevice, c->stream));
     HIPCHK(c, hipMemcpyAsync(out_len, c->st.P, (size_t)D.S * 4, hipMemcpyDeviceToDevice, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));

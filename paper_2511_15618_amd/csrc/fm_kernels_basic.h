@@ -138,7 +138,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, long ldq, const flo
     Store<T>::st(q + (long)r * d + hh * 64 + 32 + i, qb * c.x + qa * c.y);
     if (Kc && p >= 0) {
       const float ka = row[d + hh * 64 + i], kb = row[d + hh * 64 + 32 + i];
-      const long o = (((long)s * H + hh) * cap + p) * FM_HD;
+      const long o = (((long)s * H + hh) * cap + p % cap) * FM_HD;     // the cache is a ring when a window is set
       Store<T>::st(Kc + o + i, ka * c.x - kb * c.y);
       Store<T>::st(Kc + o + 32 + i, kb * c.x + ka * c.y);
       Store<T>::st(Vc + o + i, row[2 * d + hh * 64 + i]);
@@ -174,7 +174,7 @@ __global__ void k_convert(const float* __restrict__ src, T* __restrict__ dst, lo
 template <typename T>
 __global__ __launch_bounds__(256) void k_attn_simple(const T* __restrict__ q, const int* __restrict__ limit, int RPS,
                                                       const T* __restrict__ Kc, const T* __restrict__ Vc, long seq_stride,
-                                                      int cap, T* __restrict__ out, int H, const int* run_flag) {
+                                                      int cap, T* __restrict__ out, int H, const int* run_flag, int window) {
   if (run_flag && *run_flag == 0) return;
   const int r = blockIdx.x, hh = blockIdx.y;
   const int d = H * FM_HD;
@@ -193,7 +193,10 @@ __global__ __launch_bounds__(256) void k_attn_simple(const T* __restrict__ q, co
   float m = -INFINITY, l = 0.f, acc[FM_HD];
 #pragma unroll
   for (int i = 0; i < FM_HD; i++) acc[i] = 0.f;
-  for (int j = threadIdx.x; j <= lim; j += 256) {
+  // window > 0: keys lim - window + 1 .. lim, stored at slot (position mod cap)
+  const int first = window > 0 ? max(lim - window + 1, 0) : 0;
+  for (int ka = first + threadIdx.x; ka <= lim; ka += 256) {
+    const int j = window > 0 ? ka % cap : ka;
     float kv[FM_HD];
 #pragma unroll
     for (int i = 0; i < FM_HD; i += 8) Store<T>::ld8(K + (long)j * FM_HD + i, kv + i);

@@ -60,7 +60,7 @@ __global__ void k_rope_append_h(const float* __restrict__ qkv, long ldq, const f
                                 f16_t* __restrict__ Vc, int H, int capb, const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
   const int r = blockIdx.x;
-  const int p = pos[r];
+  const int p = pos[r] >= 0 ? pos[r] % (capb * 32) : -1;     // the cache is a ring when a window is set
   const int d = H * FM_HD;
   const int s = r / RPS;
   for (int idx = threadIdx.x; idx < H * 32; idx += blockDim.x) {
@@ -283,8 +283,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
           if (part == 0) {
             ((f16_t*)a.Y)[m * a.ldy + hh * FM_HD + dim] = (f16_t)val;
           } else {
-            const int p = a.pos[m];
-            if (p >= 0) {
+            const int pa = a.pos[m];
+            if (pa >= 0) {
+              const int p = pa % (a.capb * 32);      // the cache is a ring when a window is set
               const long base = (m / a.RPS) * a.seq_stride + (long)hh * a.capb * 2048;
               if (part == 1) ((f16_t*)a.Kc)[base + kblk_off(p, dim)] = (f16_t)val;
               else ((f16_t*)a.Vc)[base + vblk_off(p, dim)] = (f16_t)val;
@@ -459,7 +460,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
                                                     const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
                                                     long seq_stride, int capb, f16_t* __restrict__ out, int H,
                                                     float* __restrict__ ws, unsigned* __restrict__ counters,
-                                                    int nsplit_cfg, int defer_merge, const int* run_flag) {
+                                                    int nsplit_cfg, int defer_merge, const int* run_flag, int window) {
   if (run_flag && *run_flag == 0) return;
   constexpr int NQ = QT * 16;
   constexpr int PSZ = NQ * 64 + 2 * NQ;
@@ -474,7 +475,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   const float kScale = 0.125f * 1.4426950408889634f;   // 1/sqrt(64) * log2(e)
 
   // this lane's query rows (one per q-tile), their visibility limits and B-operand fragments
-  int lim[QT];
+  int lim[QT], first[QT];
   f16x8 qf[QT][2];
   int maxlim = -1;
 #pragma unroll
@@ -483,6 +484,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
     const bool on = qi < RPS;
     const long row = (long)s * RS + (on ? qi : 0);     // RS = rows per sequence in the buffers (>= RPS)
     lim[t] = on ? limit[row] : -1;
+    first[t] = window > 0 ? max(lim[t] - window + 1, 0) : 0;     // sliding window: keys first .. lim
     maxlim = max(maxlim, lim[t]);
     const f16_t* qp = q + row * d + hh * FM_HD + g * 8;
     qf[t][0] = *reinterpret_cast<const f16x8*>(qp);
@@ -490,7 +492,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   }
 #pragma unroll
   for (int o = 1; o < 16; o <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, o, 64));
-  const int nblk = (maxlim + 32) >> 5;                // blocks that hold a visible key (0 if none)
+  // With a window the cache is a ring of capb blocks: position p lives in slot p mod (32 capb), and a slot holds
+  // the latest position written to it.  Seen from the newest visible position `maxlim`, slot j holds
+  // lapbase + j if that is <= maxlim, else the position one lap earlier (anything newer in the ring is a stale
+  // row of a rejected block: it maps below the window and is masked).  Without a window lapbase = 0.
+  const int nblk = min((maxlim + 32) >> 5, capb);     // slot blocks that can hold a visible key (0 if none)
+  const int ringn = capb * 32;
+  const int lapbase = max(maxlim, 0) / ringn * ringn;
   // Fixed partition of the key axis: split k owns blocks [k*per, (k+1)*per) whatever the current length,
   // so the arithmetic for one query position never depends on what else is in the block or on how far
   // the sequence has grown (speculative and one-token decoding then agree bit for bit).  Splits with no
@@ -548,8 +556,9 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
       for (int hb = 0; hb < 2; hb++)
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-          const int key = b * 32 + hb * 16 + g * 4 + i;
-          const float v = key <= lim[t] ? sT[hb][i] * kScale : -INFINITY;
+          int key = lapbase + b * 32 + hb * 16 + g * 4 + i;     // absolute position held by this slot
+          key = key > maxlim ? key - ringn : key;
+          const float v = (key <= lim[t] && key >= first[t]) ? sT[hb][i] * kScale : -INFINITY;
           sT[hb][i] = v;
           mx = fmaxf(mx, v);
         }
@@ -645,7 +654,7 @@ __global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limi
   const int d = H * FM_HD;
   int maxlim = -1;
   for (int qi = 0; qi < RPS; qi++) maxlim = max(maxlim, limit[(long)s * RS + qi]);
-  const int nblk = (maxlim + 32) >> 5;
+  const int nblk = min((maxlim + 32) >> 5, capb);
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   if (nsplit == 1) return;
@@ -659,14 +668,15 @@ inline size_t mfma_attn_ws_floats(int S, int H) {
 
 template <typename T>
 bool mfma_attn_launch(const MfmaRes&, const void*, const int*, int, int, const void*, const void*, long, int, void*, int,
-                      const int*, bool, int, hipStream_t) { return false; }
+                      const int*, bool, int, int, hipStream_t) { return false; }
 
 // `cap` = key capacity of the cache (positions); caches are laid out in 32-key blocks
 template <>
 inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int* limit, int rows, int RPS, const void* Kc,
                                     const void* Vc, long seq_stride, int cap, void* out, int H, const int* flag,
-                                    bool dense, int key_bound, hipStream_t st) {
+                                    bool dense, int key_bound, int window, hipStream_t st) {
   if (RPS < 1 || rows % RPS != 0) return false;
+  if (window > 0 && (cap % 32 != 0 || window > cap)) return false;     // a ring is a whole number of blocks
   const int S = rows / RPS;
   const int capb = (cap + 31) / 32;
   // The key axis is cut into fixed ranges of at least 8 blocks (two per wave).  A growing cache is far below
@@ -698,11 +708,11 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
     f16_t* oc = (f16_t*)out + (long)r0 * d;
     if (rc <= 16) {
       hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc,
-                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
+                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag, window);
       if (defer) hipLaunchKernelGGL((k_attn_merge<1>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
     } else {
       hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc,
-                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag);
+                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag, window);
       if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
     }
   }

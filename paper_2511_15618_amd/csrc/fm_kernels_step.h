@@ -9,7 +9,9 @@ struct InvFreq { double v[32]; };  // base^(-i/32), computed in double on the ho
 
 struct Dims {
   int d, H, V, S, Bm, VB, FB, M;
-  int capc, capv, capf;
+  int capc, capv, capf;  // K/V cache slots per level (rings when a window is set)
+  int maxtok;            // longest stream (positions 1 .. maxtok)
+  int wc, wv, wf;        // attention window per level in its own positions, 0 = unbounded
   int Dc, m, n;          // draft configuration
   int nspv, nspf;        // SP heads at the point / face level
   int nhfc, nhfv;        // HF parameter sets at the coordinate / vertex level
@@ -19,7 +21,7 @@ struct Dims {
 struct StateDev {
   int *P, *main, *fin, *firedv, *firedf, *basec, *basev, *basef;
   int *vlen, *vtok, *y, *acc;
-  int* hist;          // [S][capc + 1], hist[p] = x_p
+  int* hist;          // [S][maxtok + 1], hist[p] = x_p
   int* budget;        // [1]
   int* alive;         // [1] unfinished sequences; doubles as the run flag of the step
   unsigned long long* acc_hist;  // [32]
@@ -112,7 +114,7 @@ __global__ void k_commit(StateDev st, Dims D, const int* __restrict__ accepted) 
       for (int i = 1; i < a; i++)
         if (st.vtok[s * D.Bm + i] == D.eos) { a = i; break; }   // an accepted EOS draft is not fed: it becomes the main token
       int P = st.P[s];
-      int* h = st.hist + (long)s * (D.capc + 1);
+      int* h = st.hist + (long)s * (D.maxtok + 1);
       for (int i = 0; i < a; i++) h[P + i] = st.vtok[s * D.Bm + i];
       P += a;
       const int mainTok = st.y[s * D.Bm + a - 1];
@@ -140,7 +142,7 @@ __global__ void k_set_budget(StateDev st, Dims D, int budget) {
   st.budget[0] = budget;
   int alive = 0;
   for (int i = 0; i < D.S; i++) {
-    if (st.P[i] >= 0 && st.hist[(long)i * (D.capc + 1)] == D.nbins)   // sequence has been prefilled
+    if (st.P[i] >= 0 && st.hist[(long)i * (D.maxtok + 1)] == D.nbins)   // sequence has been prefilled
       st.fin[i] = (st.main[i] == D.eos || st.P[i] >= budget) ? 1 : 0;
     alive += st.fin[i] ? 0 : 1;
   }
@@ -154,7 +156,7 @@ __global__ void k_reset_seq(StateDev st, Dims D, int s, int bos) {
   st.firedv[s] = -1; st.firedf[s] = -1;
   st.basec[s] = -1000000; st.basev[s] = -1; st.basef[s] = -1;
   st.vlen[s] = 0; st.acc[s] = 0;
-  st.hist[(long)s * (D.capc + 1)] = bos;
+  st.hist[(long)s * (D.maxtok + 1)] = bos;
   int alive = 0;
   for (int i = 0; i < D.S; i++) alive += st.fin[i] ? 0 : 1;
   st.alive[0] = alive;
