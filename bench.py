@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--faces", type=int, default=0, help="override the face budget (0 = the configuration's)")
     ap.add_argument("--draft", default="", help="override the draft counts: Dc,m,n (coordinate heads, point tokens, face tokens)")
+    ap.add_argument("--window", type=int, default=0,
+                    help="sliding-window self-attention: window in coordinate tokens (multiple of 9); with --faces beyond "
+                         "the configuration's budget the stream runs past one window over ring K/V caches")
     ap.add_argument("--b8-faces", type=int, default=150,
                     help="faces per sequence of the extra batch-8 leg (configs[3], same model as configs[2]); 0 = skip")
     ap.add_argument("--no-cpu", action="store_true")
@@ -104,6 +107,8 @@ def main():
         dc, m, n = (int(v) for v in args.draft.split(","))
         cfg = cfg.replace(draft_coord=dc, draft_point=m, draft_face=n)
     faces = args.faces or cfg.faces
+    if args.window:
+        cfg = cfg.replace(window=args.window, faces=max(faces, cfg.faces))
     weights = si.make_weights(cfg, 0)
     fm = FlashMesh(config_struct(cfg))
     fm.load_weights(si.pack_blob(cfg, weights))
@@ -240,7 +245,7 @@ def main():
     # batch-8 leg: the same model with 8 independent sequences (configs[3]) on a shortened budget, so that the
     # default run stays within minutes; ragged accepted lengths come from the per-sequence replay draws
     batch8 = None
-    if args.config == 2 and args.b8_faces > 0 and not args.draft:
+    if args.config == 2 and args.b8_faces > 0 and not args.draft and not args.window:
         cfg8 = si.CONFIGS[3]
         f8 = min(args.b8_faces, cfg8.faces)
         fm.close()
@@ -301,7 +306,8 @@ def main():
         "dtype": "f16 (bf16-valued weights held as half, fp32 accumulate)",
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: d={cfg.d_model}, {cfg.n_layers} blocks, batch {cfg.batch}, "
-                               f"{faces} faces ({9 * faces} tokens), block {cfg.block_max}, draft counts Dc={cfg.draft_coord} m={cfg.draft_point} n={cfg.draft_face}",
+                               f"{faces} faces ({9 * faces} tokens), block {cfg.block_max}, draft counts Dc={cfg.draft_coord} m={cfg.draft_point} n={cfg.draft_face}"
+                               + (f", sliding window {cfg.window} tokens" if cfg.window else ""),
                    "draft_source": f"replay p={REPLAY_P}", "tokens": tokens, "mean_accepted": tokens / max(steps, 1),
                    "accepted_hist": hist, "stream_equals_native_run": same,
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,
@@ -311,7 +317,7 @@ def main():
                    "measured_on_this_gpu": measured, "batch8": batch8},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": counter_traffic(args.config, persistent) if faces == cfg.faces else None,
+                     "traffic": counter_traffic(args.config, persistent) if (faces == si.CONFIGS[args.config].faces and not args.window and not args.draft) else None,
                      "algorithmic_bytes": bytes_mid, "ms": ms_verify,
                      "frac_of_measured_read_rate": achieved / measured["hbm_read_GBs"]},
     }

@@ -563,6 +563,7 @@ int build_persist(fm_ctx* c) {
     ns = std::min(ns, std::max(1, a.capb[l] / 2));
     a.nsplit[l] = std::max(1, std::min(ns, PK_MAXSPLIT));
     a.pos[l] = c->pos[l]; a.limx[l] = c->limx[l]; a.cs[l] = c->cs[l];
+    a.win[l] = level_window(c, l);
   }
   a.capbM = (D.M + 31) / 32;
   a.nsplitM = std::max(1, std::min(std::min(PK_NWG / D.H, std::max(1, a.capbM / 2)), PK_MAXSPLIT));
@@ -719,9 +720,10 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   D.wc = D.wv = D.wf = 0;
   if (g.window > 0 && g.window < g.max_tokens) {
     // rings: the window plus the rows of one pass (a rejected block leaves stale rows behind the committed
-    // length; they must only ever overwrite positions that no later query can see), in whole 32-key blocks
+    // length; they must only ever overwrite positions that no later query can see), in groups of four 32-key
+    // blocks (the rows of one pass then never meet twice in the blocks one wave of an attention range walks)
     D.wc = g.window; D.wv = g.window / 3; D.wf = g.window / 9;
-    auto ring = [](int w, int rows) { return (w + rows + 2 + 31) / 32 * 32; };
+    auto ring = [](int w, int rows) { return (w + rows + 2 + 127) / 128 * 128; };
     D.capc = ring(D.wc, D.Bm); D.capv = ring(D.wv, D.VB); D.capf = ring(D.wf, D.FB);
   }
   D.Dc = g.draft_coord; D.m = g.draft_point; D.n = g.draft_face;
@@ -739,9 +741,8 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   {
     const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
     const char* env = getenv("FM_PERSIST");
-    // (the single-launch kernel reads caches that never wrap: a sliding window takes the per-operator path)
     c->persist = c->bf16 && D.S == 1 && D.Bm <= 16 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
-                 D.wc == 0 && !(env && env[0] == '0');
+                 !(env && env[0] == '0');
   }
   int rc = build_params(c);
   if (rc == FM_OK) rc = build_buffers(c);

@@ -59,6 +59,7 @@ struct PkArgs {
   int R[3];                 // row slots per level (<= 16)
   int capb[3], capbM;       // cache capacity in 32-key blocks per level / of the condition memory
   int nsplit[3], nsplitM;   // launch-time split counts (fixed partition of the key axis)
+  int win[3];               // sliding window per level (0 = none); the self-attention caches are then rings of capb blocks
   const int* pos[3];
   const int* limx[3];
   const float2* cs[3];
@@ -417,9 +418,10 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
         u64* nb = (part == 1 ? a.newK : a.newV) + ((long)hh * 16 + r) * 32;
         if ((lane & 1) == 0) pk_st(nb + (dim >> 1), pk_pack(v, w), tag);
         if (p >= 0) {
+          const int ps = p % (capb * 32);      // the cache is a ring when a window is set
           const long base = (long)hh * capb * 2048;
-          if (part == 1) L.Kc[base + kblk_off(p, dim)] = (f16_t)v;
-          else L.Vc[base + vblk_off(p, dim)] = (f16_t)v;
+          if (part == 1) L.Kc[base + kblk_off(ps, dim)] = (f16_t)v;
+          else L.Vc[base + vblk_off(ps, dim)] = (f16_t)v;
         }
       }
     }
@@ -432,7 +434,7 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, int lim, int maxlim, int R,
                                              pk_cw_t Kc, pk_cw_t Vc, int capb, int nsplit_cfg, int hh, int split,
-                                             bool overlay, int P0, u64* part, unsigned tag, int stage) {
+                                             bool overlay, int P0, u64* part, unsigned tag, int stage, int window) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int g = lane >> 4, ql = lane & 15;
   const int d = a.D.d;
@@ -440,7 +442,14 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   const bool on = ql < R;
   // lim: last key this lane's query row may see (-1 for an unused row slot), maxlim: the largest of the block;
   // both are the same for every layer of a level and come from the caller
-  const int nblk = (maxlim + 32) >> 5;
+  // With a window the cache is a ring of capb blocks (a multiple of four): position p lives in slot p mod (32 capb);
+  // seen from the newest visible position, slot j holds lapbase + j if that is <= maxlim, else the position one
+  // lap earlier.  Without a window lapbase = 0 and nothing wraps.
+  const int nblk = min((maxlim + 32) >> 5, capb);
+  const int ringn = capb * 32;
+  const int lapbase = max(maxlim, 0) / ringn * ringn;
+  auto held = [&](int slot) { const int k = lapbase + slot; return k > maxlim ? k - ringn : k; };
+  const int first = window > 0 ? max(lim - window + 1, 0) : 0;
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   if (split >= nsplit) return true;      // nothing visible in this range: the merge knows the same count
@@ -451,7 +460,7 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   // V fragment dt holds dim dt*16 + lane%16 and the 8 slots g*8 + j <-> key b*32 + (j/4)*16 + g*4 + j%4.
   int bov = -1;
   if (overlay) {
-    const int cand[2] = {P0 >> 5, (P0 + R - 1) >> 5};
+    const int cand[2] = {(P0 % ringn) >> 5, ((P0 + R - 1) % ringn) >> 5};     // slot blocks of the rows of this pass
 #pragma unroll
     for (int k = 0; k < 2; k++) {
       const int b = cand[k];
@@ -505,12 +514,12 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
     ok = pk_fetch<48>(*reinterpret_cast<unsigned(*)[48]>(qraw + 8), 48, true, tag, [&](int i) {
       if (i < 16) {
         const int f = i >> 2;
-        int nr = bov * 32 + (f >> 1) * 16 + (lane & 15) - P0;
+        int nr = held(bov * 32 + (f >> 1) * 16 + (lane & 15)) - P0;
         nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
         return (const u64*)(a.newK + ((long)hh * 16 + nr) * 32 + (((f & 1) * 32 + g * 8) >> 1) + (i & 3));
       }
       const int j = (i - 16) & 7, dt = (i - 16) >> 3;
-      int nr = bov * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+      int nr = held(bov * 32 + (j >> 2) * 16 + g * 4 + (j & 3)) - P0;
       nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
       return (const u64*)(a.newV + ((long)hh * 16 + nr) * 32 + ((dt * 16 + (lane & 15)) >> 1));
     }, a, stage) && ok;
@@ -541,7 +550,7 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
     if (b == bov) {
 #pragma unroll
       for (int f = 0; f < 4; f++) {
-        const int nr = b * 32 + (f >> 1) * 16 + (lane & 15) - P0;
+        const int nr = held(b * 32 + (f >> 1) * 16 + (lane & 15)) - P0;
         if (nr >= 0 && nr < R) kf[f] = __builtin_bit_cast(f16x8, (u32x4{raw[f * 4], raw[f * 4 + 1], raw[f * 4 + 2], raw[f * 4 + 3]}));
       }
 #pragma unroll
@@ -549,7 +558,7 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
         const int dim = dt * 16 + (lane & 15);
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-          const int nr = b * 32 + (j >> 2) * 16 + g * 4 + (j & 3) - P0;
+          const int nr = held(b * 32 + (j >> 2) * 16 + g * 4 + (j & 3)) - P0;
           if (nr >= 0 && nr < R) {
             const unsigned w = raw[16 + dt * 8 + j];
             const unsigned short hbits = (dim & 1) ? (unsigned short)(w >> 16) : (unsigned short)(w & 0xFFFFu);
@@ -571,8 +580,8 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
     for (int hb = 0; hb < 2; hb++)
 #pragma unroll
       for (int i = 0; i < 4; i++) {
-        const int key = b * 32 + hb * 16 + g * 4 + i;
-        const float v = key <= lim ? sT[hb][i] * kScale : -INFINITY;
+        const int key = held(b * 32 + hb * 16 + g * 4 + i);      // absolute position
+        const float v = (key <= lim && key >= first) ? sT[hb][i] * kScale : -INFINITY;
         sT[hb][i] = v;
         mx = fmaxf(mx, v);
       }
@@ -637,7 +646,7 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
 __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, int maxlim, int R, int capb, int nsplit_cfg,
                                               int hh, int dq, const u64* parts, u64* att, unsigned tag, int stage) {
   const int d = a.D.d;
-  const int nblk = (maxlim + 32) >> 5;
+  const int nblk = min((maxlim + 32) >> 5, capb);
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   const u64* base = parts + (long)hh * PK_MAXSPLIT * PK_PART;
@@ -770,7 +779,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         PK_MINE(H * ns) {
           const int hh = u / ns, sp = u % ns;
           if (!pk_attn_unit(a, sh, a.q, limS[lev], maxS[lev], R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
-                            a.partS + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
+                            a.partS + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage, a.win[lev])) return;
         }
         PK_NEXT(H * ns);
         PK_MINE(4 * H) {
@@ -805,7 +814,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         PK_MINE(H * ns) {
           const int hh = u / ns, sp = u % ns;
           if (!pk_attn_unit(a, sh, a.q2, limX[lev], maxX[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
-                            a.partX + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage)) return;
+                            a.partX + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage, 0)) return;
         }
         PK_NEXT(H * ns);
         PK_MINE(4 * H) {

@@ -111,10 +111,11 @@ TEST_CONFIGS = {
     "t_f32_2727": Config("t_f32_2727", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 12, 2, 27, 27),
     "t_bf16_c17": Config("t_bf16_c17", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 2, 8, 17, 0, 0),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
-    # sliding window: streams several times longer than the window, so that the K/V rings of all three levels wrap
-    "t_f32_99_w36": Config("t_f32_99_w36", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 40, 2, 9, 9, window=36),
-    "t_bf16_99_w36": Config("t_bf16_99_w36", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 3, 40, 2, 9, 9, window=36),
-    "t_bf16_1815_w72": Config("t_bf16_1815_w72", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 44, 2, 15, 18, window=72),
+    # sliding window: streams long enough that the K/V rings (multiples of 128 positions) wrap at all three levels
+    "t_f32_99_w36": Config("t_f32_99_w36", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 150, 2, 9, 9, window=36),
+    "t_bf16_99_w36": Config("t_bf16_99_w36", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 3, 150, 2, 9, 9, window=36),
+    "t_bf16_99_b1_w36": Config("t_bf16_99_b1_w36", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 150, 2, 9, 9, window=36),
+    "t_bf16_1815_w72": Config("t_bf16_1815_w72", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 150, 2, 15, 18, window=72),
 }
 
 STACKS = ("cpre", "vpre", "face", "vpost", "cpost")

@@ -19,7 +19,7 @@ def _need_gpu():
 
 @pytest.mark.parametrize("name", ["t_f32_c", "t_f32_99", "t_f32_1815", "t_bf16_99", "t_bf16_1815", "t_bf16_99_b1", "t_bf16_99_b1w",
                                   "t_f32_1818", "t_bf16_1812", "t_bf16_279", "t_f32_2727", "t_bf16_c17",
-                                  "t_f32_99_w36", "t_bf16_99_w36", "t_bf16_1815_w72"])
+                                  "t_f32_99_w36", "t_bf16_99_w36", "t_bf16_99_b1_w36", "t_bf16_1815_w72"])
 def test_lockstep_small_native_heads(name):
     _need_gpu()
     from parity_harness import lockstep
