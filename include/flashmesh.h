@@ -50,7 +50,8 @@ typedef struct {
   int32_t mem_len;                                  /* rows of the condition memory c               */
   int32_t dtype;                                    /* FM_DTYPE_*                                   */
   int32_t max_batch;                                /* sequences held by the context                */
-  int32_t max_tokens;                               /* K/V capacity per sequence, coordinate level  */
+  int32_t max_tokens;                               /* longest stream per sequence (multiple of 9); also the
+                                                       coordinate-level K/V capacity unless `window` is set */
   int32_t draft_coord;  /* Dc: coordinate-level SP heads (Eq. 1), one future token each            */
   int32_t draft_point;  /* m : nominal point-level tokens, multiple of 3, 0 = level off            */
   int32_t draft_face;   /* n : nominal face-level tokens, multiple of 9, 0 = level off             */
@@ -60,8 +61,8 @@ typedef struct {
   int32_t window;       /* sliding-window self-attention (Sec. 5.1 "window size"): 0 = a position sees the whole
                            context and max_tokens is also the K/V capacity; W > 0 (multiple of 9) = a position p
                            of the coordinate level sees keys [p-W+1, p], the vertex and face levels W/3 and W/9
-                           of their own positions, the K/V caches are rings of W + block_max positions (rounded
-                           up to 32) and max_tokens only bounds the length of the emitted stream                 */
+                           of their own positions, the K/V caches are rings of W + block_max + 2 positions (rounded
+                           up to 128) and max_tokens only bounds the length of the emitted stream                 */
 } fm_config;
 
 typedef struct {

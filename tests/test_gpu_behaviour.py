@@ -237,6 +237,36 @@ def test_config1_full_size_stream():
     print("config1 full: allowed flips", flips, "worst margin", worst, "steps native/replay", st.steps, st2.steps, flush=True)
 
 
+def test_config1_sliding_window_stream():
+    """configs[1] (4500 tokens) with a sliding window of 900 tokens (Sec. 5.1 "window size"): the stream is five
+    windows long, the K/V rings of all three levels wrap (1024 / 384 / 128 positions), and the run is the
+    single-launch verify kernel.  Native run == replay run == what the oracle, which keeps every key and masks,
+    picks at every position (teacher-forced, margin rule)."""
+    _need_gpu()
+    cfg = si.CONFIGS[1].replace(window=900)
+    print("case config1 window 900", flush=True)
+    fm, _ = _ctx(cfg)
+    assert fm.verify_path() == 1
+    out, n, st = fm.generate(cfg.faces, True)
+    assert int(n[0]) == 4500 and st.tokens == 4500
+    fm.prefill_condition(0, torch.from_numpy(si.make_memory(cfg, 0)).cuda())
+    fm.set_draft_replay(out.clone(), 4500, 0.93, 5)
+    out2, n2, st2 = fm.generate(cfg.faces, True)
+    assert torch.equal(out, out2)
+    assert st2.steps < st.steps and st2.tokens == 4500
+    fm.prefill_condition(0, torch.from_numpy(si.make_memory(cfg, 0)).cuda())
+    fm.set_draft_replay(None, 0, 0.0, 0)
+    out3, n3, st3 = fm.generate(cfg.faces, False)          # one token per step through the same kernels
+    assert torch.equal(out, out3) and st3.steps == 4500
+    flips, worst = _teacher_forced_check(cfg, out.cpu().numpy(), TOL["bf16"], np.float64)
+    print("config1 window: allowed flips", flips, "worst margin", worst, "steps native/replay", st.steps, st2.steps, flush=True)
+    # the window changes the model: its stream leaves the unwindowed one after the first window
+    fm_all, _ = _ctx(si.CONFIGS[1])
+    out_all, _, _ = fm_all.generate(cfg.faces, True)
+    a, b = out.cpu().numpy()[0], out_all.cpu().numpy()[0]
+    assert np.array_equal(a[:100], b[:100]) and not np.array_equal(a, b)
+
+
 def test_batched_long_context_stream():
     """Eight ragged sequences of 2304 tokens at a small width: the key axis of the self-attention is cut into
     nine ranges whose partial results are merged by the second launch, and the host-side bound on the
