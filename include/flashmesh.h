@@ -85,7 +85,7 @@ int64_t fm_blob_elems(const fm_ctx* ctx);
 
 /* Load all parameters from one HOST blob of float32 values in manifest order (embedding; per stack
  * cpre, vpre, face, vpost, cpost and per block g1,wq,wk,wv,wo,g2,cq,ck,cv,co,g3,w1,w2; shorten
- * coord->vertex, vertex->face; final gain, LM head; SP heads per level; HF sets per level), linear
+ * coord->vertex, vertex->face; final gain, LM head; SP heads per level; HF sets per level; label head), linear
  * weights as [out,in].  Converts to the configured storage type on the device.  Synchronises. */
 int fm_load_weights(fm_ctx* ctx, const float* host_blob, size_t n_floats);
 

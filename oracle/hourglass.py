@@ -184,6 +184,7 @@ class SeqState:
         self.tap = {"c": z(cap_c, m.d), "v": z(cap_v, m.d), "f": z(cap_f, m.d)}
         # draft bookkeeping (used by oracle.speculative)
         self.rows = {"c": {}, "v": {}, "f": {}}
+        self.labels = {"v": {}, "f": {}}      # label distributions per vertex (oracle.correct)
         self.fired_v = -1
         self.fired_f = -1
 

@@ -14,6 +14,7 @@ from __future__ import annotations
 import numpy as np
 
 from . import primitives as P
+from .correct import correct_block, draft_vertex_range, label_row, point_labels
 from .hourglass import Model, SeqState, forward_block
 
 
@@ -117,11 +118,14 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None):
     if point_fires(s, st.fired_v, mm):
         v = s // 3
         rows = {}
+        labels = {}
         for k in range(1, mm // 3):
             u = sp_head(m, st, "v", k, st.tap["v"][v], v)
+            labels[v + k] = label_row(m, u)          # point-level feature of vertex v + k (Sec. 3.2)
             for t in (3 * k, 3 * k + 1, 3 * k + 2):
                 rows[3 * v + t + 1] = _dist(m, hf_block(m, st, "c", t, u, 3 * v + t, 3 * v))
         st.rows["v"] = rows
+        st.labels["v"] = labels
         st.fired_v = v
 
     # face level: the current face feature plus SP heads for later faces, repeat x3 to vertex
@@ -130,11 +134,14 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None):
         f = s // 9
         g = [st.y_f[f]] + [sp_head(m, st, "f", k, st.tap["f"][f], f) for k in range(1, nn // 9)]
         rows = {}
+        labels = {}
         for j in range(1, nn // 3):
             hv = hf_block(m, st, "v", j, g[j // 3], 3 * f + j, 3 * f)
+            labels[3 * f + j] = label_row(m, hv)     # point-level feature of vertex 3f + j
             for t in (3 * j, 3 * j + 1, 3 * j + 2):
                 rows[9 * f + t + 1] = _dist(m, hf_block(m, st, "c", t, hv, 9 * f + t, 9 * f))
         st.rows["f"] = rows
+        st.labels["f"] = labels
         st.fired_f = f
 
     # merge: mean of the distributions that cover a position; stop at the first gap
@@ -193,11 +200,21 @@ def commit(model: Model, st: SeqState, block, y, a: int):
     return a
 
 
-def generate(model: Model, mem, faces: int, speculative=True, draft_fn=None, trace=None):
+def corrected(model: Model, st: SeqState, block, hist_vertices: int):
+    """The draft block after the correct stage (Sec. 3.2), from the label rows the draft left in the state."""
+    if len(block) < 4:
+        return list(block)
+    u0, u1 = draft_vertex_range(st.P, len(block))
+    labels = {u: lab for u, (lab, _) in point_labels(st, u0, u1).items()}
+    return correct_block(model.cfg, st.P, block, labels, st.tokens + [st.main], hist_vertices)
+
+
+def generate(model: Model, mem, faces: int, speculative=True, draft_fn=None, trace=None, correct_hist=0):
     """Greedy generation of up to `faces` faces.  Returns (x_1 .., final state); BOS excluded, the pending main token included.
 
     speculative=False is plain one-token-at-a-time decoding of the same backbone.
-    draft_fn(st, budget) overrides the draft source (tests feed adversarial drafts)."""
+    draft_fn(st, budget) overrides the draft source (tests feed adversarial drafts).
+    correct_hist > 0 runs the correct stage on every draft block with that many historical vertices."""
     budget = 9 * faces
     st = SeqState(model, mem, budget)
     while not st.finished and st.P < budget:
@@ -207,6 +224,8 @@ def generate(model: Model, mem, faces: int, speculative=True, draft_fn=None, tra
             block = draft_fn(st, budget)
         else:
             block = draft(model, st, budget)
+        if speculative and correct_hist > 0:
+            block = corrected(model, st, block, correct_hist)
         _, y, a = verify(model, st, block)
         a = commit(model, st, block, y, a)
         if trace is not None:

@@ -73,6 +73,7 @@ struct fm_ctx {
   float* gf;
   SpLevel sp[3];
   HfLevel hfc, hfv;
+  float* label_w;     // label head of the correct stage [3][d]
 
   // state
   StateDev st;
@@ -521,6 +522,9 @@ int build_params(fm_ctx* c) {
       lin(at(h.w2, k * d * hff), d, hff);
     }
   }
+  // label head of the correct stage (Sec. 3.2): [3][d], kept in fp32 (three dot products per point)
+  TRY(dalloc(c, &c->label_w, 3 * d));
+  item(c->label_w, 3 * d, true);
   c->blob_elems = off;
   return FM_OK;
 }

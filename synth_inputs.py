@@ -169,6 +169,7 @@ def manifest(cfg: Config):
             p = f"hf.{lvl}.{t}."
             out += [(p + "g", (d,), "gain", 0), (p + "wq", (d, d), "lin", d),
                     (p + "w1", (hf, d), "lin", d), (p + "w2", (d, hf), "lin", hf)]
+    out += [("label", (3, d), "lin", d)]     # label head of the correct stage: historical / new / intra-batch
     return out
 
 

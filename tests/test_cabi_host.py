@@ -76,7 +76,7 @@ def test_manifest_matches_blob_size():
         per_block = 3 * d + 8 * d * d + 2 * ff * d
         sp = sum(si.sp_head_counts(cfg).values()) * (d + 5 * d * d)
         hfn = (len(si.hf_coord_offsets(cfg)) + len(si.hf_vertex_offsets(cfg))) * (d + d * d + 2 * hf * d)
-        assert n == V * d + cfg.n_layers * per_block + 2 * d * d + d + V * d + sp + hfn
+        assert n == V * d + cfg.n_layers * per_block + 2 * d * d + d + V * d + sp + hfn + 3 * d   # + label head
 
 
 def test_replay_uniform_is_uniform_and_keyed():

@@ -6,6 +6,7 @@ import pytest
 
 import synth_inputs as si
 from oracle import primitives as P
+from oracle import correct as oc
 from oracle import speculative as sp
 from oracle.hourglass import Model, SeqState, forward_block, forward_full
 
@@ -365,3 +366,98 @@ def test_sp_and_hf_residual_wiring():
     assert st.fired_f == f and sorted(st.rows["f"]) == list(range(9 * f + 4, 9 * f + 10))
     for tgt in st.rows["f"]:
         assert np.allclose(st.rows["f"][tgt], want_f, atol=1e-12)
+
+
+# -- correct stage (Sec. 3.2) ---------------------------------------------------------------
+def _correct_cases():
+    for line in open(os.path.join(GOLD, "correct_cases.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = [x.strip() for x in line.split("|")]
+        labels = {int(a): int(b) for a, b in (kv.split(":") for kv in f[3].split())}
+        yield int(f[0]), [int(t) for t in f[1].split()], [int(t) for t in f[2].split()], labels, int(f[4]), [int(t) for t in f[5].split()]
+
+
+def test_correct_stage_worked_examples():
+    cfg = si.TEST_CONFIGS["t_f32_99"]
+    n = 0
+    for Pc, known, block, labels, hv, want in _correct_cases():
+        assert len(known) == Pc + 1 and known[-1] == block[0]
+        assert oc.correct_block(cfg, Pc, block, labels, known, hv) == want, (Pc, block)
+        n += 1
+    assert n == 6
+
+
+def test_correct_stage_properties_random_blocks():
+    """Random blocks and labels: the main token and every token outside the block's own points never change;
+    points labelled new only move within their face; whole draft faces come out sorted; all-new labels on
+    sorted faces change nothing; the nearest rule agrees with a brute-force search."""
+    cfg = si.TEST_CONFIGS["t_f32_99"]
+    r = np.random.default_rng(12)
+    for trial in range(300):
+        Pc = int(r.integers(0, 40))
+        B = int(r.integers(1, 28))
+        known = [cfg.bos] + [int(t) for t in r.integers(0, 6, Pc)]
+        block = [known[-1]] + [int(t) for t in r.integers(0, 6, B - 1)]
+        if trial % 7 == 0 and B > 3:
+            block[int(r.integers(1, B))] = cfg.eos
+        u0, u1 = oc.draft_vertex_range(Pc, B)
+        labels = {u: int(r.integers(0, 3)) for u in range(u0, u1 + 1) if r.random() < 0.8}
+        hv = int(r.integers(0, 8))
+        out = oc.correct_block(cfg, Pc, block, labels, known, hv)
+        assert len(out) == B and out[0] == block[0]
+        lo, hi = 3 * u0 + 1 - Pc, 3 * u1 + 4 - Pc      # block indices of the complete draft vertices
+        for i in range(B):
+            if not (lo <= i < hi):
+                assert out[i] == block[i], (trial, i)
+        tri = lambda b, u: tuple(b[3 * u + 1 - Pc:3 * u + 4 - Pc])
+        ok = lambda c: all(t < cfg.n_bins for t in c)
+        for f in range((u0 + 2) // 3, (u1 + 1) // 3):
+            vs = [3 * f, 3 * f + 1, 3 * f + 2]
+            if all(ok(tri(out, u)) for u in vs):
+                assert [tri(out, u) for u in vs] == sorted(tri(out, u) for u in vs)
+        # brute force of the two move rules on the first point that qualifies, before any other move can interfere
+        pts = [u for u in range(u0, u1 + 1) if ok(tri(block, u))]
+        hist = [(h, tuple(known[3 * h + 1:3 * h + 4])) for h in range(max(0, Pc // 3 - hv), Pc // 3)]
+        if pts:
+            u = pts[0]
+            c = np.array(tri(block, u))
+            moved = None
+            if labels.get(u, oc.NEW) == oc.HIST and hist and all(tuple(c) != hc for _, hc in hist):
+                dd = np.array([((c - np.array(hc)) ** 2).sum() for _, hc in hist])
+                moved = hist[int(np.argmin(dd))][1]
+            if labels.get(u, oc.NEW) == oc.INTRA and all(tri(block, w) != tuple(c) for w in pts[1:]):
+                cand = [w for w in pts[1:] if labels.get(w, oc.NEW) == oc.NEW and w // 3 != u // 3]
+                if cand:
+                    dd = np.array([((c - np.array(tri(block, w))) ** 2).sum() for w in cand])
+                    moved = tri(block, cand[int(np.argmin(dd))])
+            if moved is not None:
+                # the point now holds `moved` (possibly at another slot of its face after the re-sort)
+                f = u // 3
+                face = [tri(out, w) for w in range(max(3 * f, u0), min(3 * f + 2, u1) + 1)]
+                assert tuple(moved) in face, (trial, u, moved, face)
+        # all-new labels: only the sort acts
+        out2 = oc.correct_block(cfg, Pc, out, {}, known, hv)
+        out3 = oc.correct_block(cfg, Pc, out2, {}, known, hv)
+        assert out2 == out3
+
+
+def test_correct_stage_keeps_the_stream():
+    """The correct stage edits drafts only, so the emitted stream is still plain greedy decoding (Sec. 3.2, 3.3),
+    while the blocks that are verified do change."""
+    cfg, m, mem = _model("t_f32_1815")
+    seq, _ = sp.generate(m, mem, cfg.faces, speculative=False)
+    t0, t1 = [], []
+    plain, _ = sp.generate(m, mem, cfg.faces, speculative=True, trace=t0)
+    fixed, _ = sp.generate(m, mem, cfg.faces, speculative=True, trace=t1, correct_hist=6)
+    assert seq == plain == fixed
+    assert [b for _, b, _ in t0] != [b for _, b, _ in t1]
+    assert all(b0[0] == b1[0] for (_, b0, _), (_, b1, _) in zip(t0[:3], t1[:3]))
+
+
+def test_label_rows_are_softmax_of_the_linear_head():
+    cfg, m, mem = _model("t_f32_99")
+    f = np.random.default_rng(2).standard_normal(cfg.d_model)
+    row = oc.label_row(m, f)
+    z = np.array([float(np.dot(m.w["label"][i], f)) for i in range(3)])
+    assert np.allclose(row, np.exp(z) / np.exp(z).sum(), atol=1e-14) and abs(row.sum() - 1.0) < 1e-14
