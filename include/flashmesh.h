@@ -102,6 +102,21 @@ int fm_prefill_condition(fm_ctx* ctx, int32_t seq, const float* mem_dev);
  * (0 for a finished sequence).  Updates only the context's draft bookkeeping. */
 int fm_draft(fm_ctx* ctx, int32_t* block_tok_dev, int32_t* block_len_dev);
 
+/* Correct stage (Sec. 3.2 "Correction Mechanism"), between fm_draft and fm_verify_block; it edits draft tokens only,
+ * never block_tok_dev[seq*block_max + 0], so the emitted stream is unchanged and only acceptance can move.
+ * fm_set_correct(hist_vertices > 0) switches it on: fm_draft then also keeps, per point-level feature of the point and
+ * face pipelines, the softmax of the linear label head (historical / new / intra-batch), and fm_generate runs the
+ * stage in every speculative step; 0 switches it off.
+ * fm_correct: the points of a block are the vertices whose three tokens (z, y, x) are all drafts and all coordinate
+ * bins; a point's label is the arg max of the mean of the label rows held for it (new if none).  A historical point
+ * that equals none of the last hist_vertices known vertices moves onto the nearest of them; an intra-batch point
+ * that equals no other point of the block moves onto the nearest point labelled new in another face (squared
+ * distance in bins, lowest vertex index on ties, no candidate: unchanged); faces made of draft tokens only are
+ * re-sorted ascending in (z, y, x).  labels_out_dev ([batch, block_max] int32, may be NULL) receives the label of
+ * the i-th point of each block, -1 beyond.  FM_ESTATE when the stage is off. */
+int fm_set_correct(fm_ctx* ctx, int32_t hist_vertices);
+int fm_correct(fm_ctx* ctx, int32_t* block_tok_dev, const int32_t* block_len_dev, int32_t* labels_out_dev);
+
 /* Verify stage (Sec. 3.3): one causal backbone forward over each sequence's block at positions
  * P .. P+len-1 against the K/V caches of all three levels.  logits_dev ([batch, block_max, vocab]
  * float32) may be NULL.  accepted_len_dev[seq] = 1 + number of leading drafts equal to the

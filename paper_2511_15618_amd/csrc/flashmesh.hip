@@ -74,6 +74,8 @@ struct fm_ctx {
   SpLevel sp[3];
   HfLevel hfc, hfv;
   float* label_w;     // label head of the correct stage [3][d]
+  float *lab_v, *lab_f;   // label distributions of the point pipeline [S][nspv][3] and the face pipeline [S][nhfv][3]
+  int correct_hist = 0;   // historical vertices the correct stage looks at; 0 = stage off (no label rows are computed)
 
   // state
   StateDev st;
@@ -383,6 +385,9 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
     // face level: SP heads on the face feature, vertex-level HF, then coordinate HF rows of pipe 1
     run_sp<T>(c, 2, c->sp[2], lastf, 2, c->spf_out, (long)D.nspf * d, d, f_f);
     run_hf<T>(c, 3, c->hfv, 1, lastv, 1, c->hfv_out, f_f);
+    if (c->correct_hist > 0 && D.nspv + D.nhfv > 0)     // label rows of the point-level features (Sec. 3.2)
+      hipLaunchKernelGGL(k_label_rows, dim3(D.S * (D.nspv + D.nhfv)), dim3(64), 0, c->stream, D, c->dr, c->spv_out, c->hfv_out,
+                         c->label_w, c->lab_v, c->lab_f);
     run_hf<T>(c, 4, c->hfc, 2, lastc, 0, c->dh + (long)D.S * D.Dc * d, f_alive);
     if (nLM > 0) {
       rmsnorm<T>(c, c->dh, nullptr, c->gf, 0, c->dxn, nullptr, nLM, f_alive);
@@ -658,6 +663,7 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc_t(c, &c->dmid, rmax * c->hff));
   TRY(dalloc(c, &c->dist_c, S * std::max(D.Dc, 1) * D.V));
   TRY(dalloc(c, &c->dist_v, S * std::max(D.nhfc, 1) * D.V)); TRY(dalloc(c, &c->dist_f, S * std::max(D.nhfc, 1) * D.V));
+  TRY(dalloc(c, &c->lab_v, S * std::max(D.nspv, 1) * 3)); TRY(dalloc(c, &c->lab_f, S * std::max(D.nhfv, 1) * 3));
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
@@ -834,6 +840,24 @@ int fm_draft(fm_ctx* c, int32_t* block_tok, int32_t* block_len) {
   return rc == FM_OK && c->sticky_error ? FM_EINVAL : rc;
 }
 
+int fm_set_correct(fm_ctx* c, int32_t hist_vertices) {
+  if (!c) return FM_EINVAL;
+  if (hist_vertices < 0) return fail(c, FM_EINVAL, "hist_vertices %d < 0", hist_vertices);
+  c->correct_hist = hist_vertices;
+  return FM_OK;
+}
+
+int fm_correct(fm_ctx* c, int32_t* block_tok, const int32_t* block_len, int32_t* labels_out) {
+  if (!c) return FM_EINVAL;
+  if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
+  if (c->correct_hist <= 0) return fail(c, FM_ESTATE, "correct stage is off: call fm_set_correct before the fm_draft whose block is corrected");
+  if (!block_tok || !block_len) return fail(c, FM_EINVAL, "null block buffer");
+  hipLaunchKernelGGL(k_correct, dim3((c->D.S + 63) / 64), dim3(64), 0, c->stream, c->st, c->D, c->lab_v, c->lab_f, c->correct_hist,
+                     block_tok, block_len, labels_out);
+  HIPCHK(c, hipGetLastError());
+  return FM_OK;
+}
+
 int fm_verify_block(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits, int32_t* accepted) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
@@ -997,6 +1021,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
   int rc = FM_OK;
   for (long step = 0; step < max_steps && !done && rc == FM_OK; step++) {
     rc = c->bf16 ? draft_impl<f16_t>(c, c->gen_tok, c->gen_len, speculative) : draft_impl<float>(c, c->gen_tok, c->gen_len, speculative);
+    if (rc == FM_OK && speculative && c->correct_hist > 0) rc = fm_correct(c, c->gen_tok, c->gen_len, nullptr);
     if (rc == FM_OK)
       rc = c->bf16 ? verify_impl<f16_t>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc)
                    : verify_impl<float>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc);

@@ -367,3 +367,155 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
   }
   if (threadIdx.x == 0) block_len[s] = len;
 }
+
+// ------------------------------------------------------------------------------------------
+// Correct stage (Sec. 3.2): label rows of the point-level features, then the integer correction of a draft block
+// ------------------------------------------------------------------------------------------
+// One wave per point-level feature: softmax of the three label logits W_label f.  Rows 0 .. S*nspv-1 are the
+// point pipeline's SP head outputs (vertex v + k), the rest the face pipeline's vertex-level HF outputs (vertex
+// 3f + j); a row is stored only when its pipeline fired for the sequence, so older rows stay usable like the
+// token distributions do.
+__global__ __launch_bounds__(64) void k_label_rows(Dims D, DraftRows R, const float* __restrict__ spv_out,
+                                                    const float* __restrict__ hfv_out, const float* __restrict__ W,
+                                                    float* __restrict__ lab_v, float* __restrict__ lab_f) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  const float* src;
+  float* dst;
+  if (r < D.S * D.nspv) {
+    const int s = r / D.nspv;
+    if (!R.firev[s]) return;
+    src = spv_out + (long)r * D.d;
+    dst = lab_v + (long)r * 3;
+  } else {
+    const int rr = r - D.S * D.nspv, s = rr / D.nhfv;
+    if (!R.firef[s]) return;
+    src = hfv_out + (long)rr * D.d;
+    dst = lab_f + (long)rr * 3;
+  }
+  float z[3] = {0.f, 0.f, 0.f};
+  for (int i = lane; i < D.d; i += 64) {
+    const float x = src[i];
+    z[0] = fmaf(W[i], x, z[0]);
+    z[1] = fmaf(W[D.d + i], x, z[1]);
+    z[2] = fmaf(W[2 * D.d + i], x, z[2]);
+  }
+#pragma unroll
+  for (int k = 0; k < 3; k++) z[k] = wave_sum(z[k]);
+  if (lane == 0) {
+    const float mx = fmaxf(z[0], fmaxf(z[1], z[2]));
+    const float e0 = expf(z[0] - mx), e1 = expf(z[1] - mx), e2 = expf(z[2] - mx);
+    const float inv = 1.0f / (e0 + e1 + e2);
+    dst[0] = e0 * inv; dst[1] = e1 * inv; dst[2] = e2 * inv;
+  }
+}
+
+#define FM_LABEL_HIST 0
+#define FM_LABEL_NEW 1
+#define FM_LABEL_INTRA 2
+
+// One thread per sequence (a block holds at most 27 tokens, i.e. 9 points): labels of the block's points from the
+// stored rows, the historical / intra-batch moves in ascending vertex order, then the z-y-x re-sort of the faces
+// that consist of draft tokens only.  Integer work on bin coordinates; the main token is never touched.
+// Vertex u owns x_{3u+1..3u+3}; block token i is x_{P+i}.
+__global__ void k_correct(StateDev st, Dims D, const float* __restrict__ lab_v, const float* __restrict__ lab_f,
+                          int hist_vertices, int* __restrict__ block_tok, const int* __restrict__ block_len,
+                          int* __restrict__ labels_out) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= D.S) return;
+  int* tok = block_tok + (long)s * D.Bm;
+  int* lout = labels_out ? labels_out + (long)s * D.Bm : nullptr;
+  if (lout)
+    for (int i = 0; i < D.Bm; i++) lout[i] = -1;
+  if (st.fin[s]) return;
+  const int P = st.P[s];
+  int len = block_len[s];
+  len = min(len, D.Bm);
+  if (len < 4) return;
+  const int u0 = (P + 2) / 3, u1 = (P + len - 4) / 3;
+  if (u1 < u0) return;
+  const int np = u1 - u0 + 1;                    // <= 9
+  int lab[9];
+  bool pt[9];
+  const int basev = st.basev[s], basef = st.basef[s];
+  for (int i = 0; i < np; i++) {
+    const int u = u0 + i;
+    float a[3] = {0.f, 0.f, 0.f};
+    int cnt = 0;
+    const int kv = basev >= 0 ? u - basev / 3 : 0;
+    if (basev >= 0 && kv >= 1 && kv <= D.nspv) {
+      const float* row = lab_v + ((long)s * D.nspv + kv - 1) * 3;
+      a[0] += row[0]; a[1] += row[1]; a[2] += row[2];
+      cnt++;
+    }
+    const int jf = basef >= 0 ? u - basef / 3 : 0;
+    if (basef >= 0 && jf >= 1 && jf <= D.nhfv) {
+      const float* row = lab_f + ((long)s * D.nhfv + jf - 1) * 3;
+      a[0] += row[0]; a[1] += row[1]; a[2] += row[2];
+      cnt++;
+    }
+    int l = FM_LABEL_NEW;
+    if (cnt > 0) {
+      const float inv = 1.0f / (float)cnt;
+      const float m0 = a[0] * inv, m1 = a[1] * inv, m2 = a[2] * inv;
+      l = 0;
+      float best = m0;
+      if (m1 > best) { best = m1; l = 1; }
+      if (m2 > best) { best = m2; l = 2; }
+    }
+    lab[i] = l;
+    if (lout) lout[i] = l;
+    const int* c = tok + 3 * u + 1 - P;
+    pt[i] = c[0] >= 0 && c[0] < D.nbins && c[1] >= 0 && c[1] < D.nbins && c[2] >= 0 && c[2] < D.nbins;
+  }
+  const int* known = st.hist + (long)s * (D.maxtok + 1);     // x_0 .. x_P (the pending main token is x_P)
+  const int nkv = P / 3;
+  const int h0 = max(0, nkv - hist_vertices);
+  for (int i = 0; i < np; i++) {
+    if (!pt[i]) continue;
+    int* c = tok + 3 * (u0 + i) + 1 - P;
+    if (lab[i] == FM_LABEL_HIST) {
+      long best = -1;
+      int bh = -1;
+      bool same = false;
+      for (int h = h0; h < nkv; h++) {
+        const int* k = known + 3 * h + 1;
+        if (!(k[0] < D.nbins && k[1] < D.nbins && k[2] < D.nbins)) continue;
+        const long dz = c[0] - k[0], dy = c[1] - k[1], dx = c[2] - k[2];
+        const long dd = dz * dz + dy * dy + dx * dx;
+        if (dd == 0) { same = true; break; }
+        if (bh < 0 || dd < best) { best = dd; bh = h; }
+      }
+      if (!same && bh >= 0) { c[0] = known[3 * bh + 1]; c[1] = known[3 * bh + 2]; c[2] = known[3 * bh + 3]; }
+    } else if (lab[i] == FM_LABEL_INTRA) {
+      long best = -1;
+      int bw = -1;
+      bool same = false;
+      for (int w = 0; w < np; w++) {
+        if (w == i || !pt[w]) continue;
+        const int* k = tok + 3 * (u0 + w) + 1 - P;
+        const long dz = c[0] - k[0], dy = c[1] - k[1], dx = c[2] - k[2];
+        const long dd = dz * dz + dy * dy + dx * dx;
+        if (dd == 0) { same = true; break; }
+        if (lab[w] == FM_LABEL_NEW && (u0 + w) / 3 != (u0 + i) / 3 && (bw < 0 || dd < best)) { best = dd; bw = w; }
+      }
+      if (!same && bw >= 0) {
+        const int* k = tok + 3 * (u0 + bw) + 1 - P;
+        c[0] = k[0]; c[1] = k[1]; c[2] = k[2];
+      }
+    }
+  }
+  // faces whose nine tokens are all drafts of this block: vertices in ascending (z, y, x) order
+  for (int f = (u0 + 2) / 3; f < (u1 + 1) / 3; f++) {
+    const int i0 = 3 * f - u0;
+    if (!(pt[i0] && pt[i0 + 1] && pt[i0 + 2])) continue;
+    int* c = tok + 3 * (3 * f) + 1 - P;
+    for (int pass = 0; pass < 2; pass++)
+      for (int j = 0; j < 2 - pass; j++) {
+        int* a = c + 3 * j;
+        int* b = a + 3;
+        const bool gt = a[0] != b[0] ? a[0] > b[0] : a[1] != b[1] ? a[1] > b[1] : a[2] > b[2];
+        if (gt)
+          for (int k = 0; k < 3; k++) { const int t = a[k]; a[k] = b[k]; b[k] = t; }
+      }
+  }
+}

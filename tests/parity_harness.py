@@ -12,6 +12,7 @@ import numpy as np
 import torch
 
 import synth_inputs as si
+from oracle import correct as ocr
 from oracle import speculative as osp
 from oracle.hourglass import Model, SeqState, forward_block
 from paper_2511_15618_amd import FlashMesh
@@ -24,12 +25,16 @@ class Report:
         self.max_logit_err = 0.0
         self.token_flips = 0
         self.draft_flips = 0
+        self.label_flips = 0
+        self.points = 0
+        self.corrected_blocks = 0
         self.accepted = []
         self.block_lens = []
 
     def __repr__(self):
         return (f"steps={self.steps} max|dlogit|={self.max_logit_err:.3e} token_flips={self.token_flips} "
-                f"draft_flips={self.draft_flips} mean_acc={np.mean(self.accepted) if self.accepted else 0:.2f}")
+                f"draft_flips={self.draft_flips} mean_acc={np.mean(self.accepted) if self.accepted else 0:.2f}"
+                + (f" points={self.points} label_flips={self.label_flips} corrected_blocks={self.corrected_blocks}" if self.points else ""))
 
 
 def make_pair(cfg, work=np.float64, max_tokens=None):
@@ -45,10 +50,17 @@ def make_pair(cfg, work=np.float64, max_tokens=None):
     return model, fm, states
 
 
-def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work=np.float64, check_logits=True):
-    """Run the decode loop on both sides; returns (Report, device token streams)."""
+def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work=np.float64, check_logits=True,
+             correct_hist=0):
+    """Run the decode loop on both sides; returns (Report, device token streams).
+
+    correct_hist > 0: the correct stage runs between draft and verify on both sides.  The device's labels must be the
+    oracle's except where the oracle's own label distribution separates the two by less than the tolerance; with the
+    device's labels the oracle's integer correction must reproduce the device's corrected block exactly."""
     model, fm, states = make_pair(cfg, work=work)
     fm.set_budget(faces)
+    if correct_hist:
+        fm.set_correct(correct_hist)
     budget = 9 * faces
     if replay is not None:
         fm.set_draft_replay(*replay)
@@ -56,6 +68,7 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
     tok, ln = fm.new_block()
     logits = torch.zeros(S, Bm, V, dtype=torch.float32, device="cuda")
     acc = torch.zeros(S, dtype=torch.int32, device="cuda")
+    labels_dev = torch.zeros(S, Bm, dtype=torch.int32, device="cuda")
     rep = Report()
     nlim = cfg.n_bins if cfg.ban_specials else cfg.vocab
     while True:
@@ -70,9 +83,13 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
             ln[:] = torch.from_numpy((1 - st_dev[:, 4]).astype(np.int32)).cuda()
         else:
             fm.draft(tok, ln)
+        h_pre = tok.cpu().numpy() if correct_hist else None
+        if correct_hist and drafts != "none":
+            fm.correct(tok, ln, labels_dev)
         fm.verify_block(tok, ln, logits, acc)
         torch.cuda.synchronize()
         h_tok, h_len = tok.cpu().numpy(), ln.cpu().numpy()
+        h_lab = labels_dev.cpu().numpy()
         h_logits, h_acc = logits.cpu().numpy(), acc.cpu().numpy()
         fm.commit(acc)
         for s in range(S):
@@ -81,17 +98,38 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
                 assert h_len[s] == 0 and h_acc[s] == 0, (s, h_len[s], h_acc[s])
                 continue
             block_dev = [int(t) for t in h_tok[s, :h_len[s]]]
+            block_pre = [int(t) for t in h_pre[s, :h_len[s]]] if correct_hist else block_dev
             if drafts == "native" and replay is None:
                 merged = []
                 block_ref = osp.draft(model, st, budget, merged)
-                assert len(block_ref) == len(block_dev), (rep.steps, s, block_ref, block_dev)
-                assert block_ref[0] == block_dev[0]
+                assert len(block_ref) == len(block_pre), (rep.steps, s, block_ref, block_pre)
+                assert block_ref[0] == block_pre[0]
                 for i in range(1, len(block_ref)):
-                    if block_ref[i] != block_dev[i]:
+                    if block_ref[i] != block_pre[i]:
                         dist = merged[i - 1]
-                        gap = dist[block_ref[i]] - dist[block_dev[i]]
+                        gap = dist[block_ref[i]] - dist[block_pre[i]]
                         assert gap <= tol, ("draft token beyond tolerance", rep.steps, s, i, gap)
                         rep.draft_flips += 1
+                if correct_hist and len(block_pre) >= 4:
+                    u0, u1 = ocr.draft_vertex_range(st.P, len(block_pre))
+                    ref = ocr.point_labels(st, u0, u1)
+                    labels = {}
+                    for i, u in enumerate(range(u0, u1 + 1)):
+                        lab_ref, dist = ref[u]
+                        lab_dev = int(h_lab[s, i])
+                        rep.points += 1
+                        if lab_dev != lab_ref:
+                            assert dist is not None and 0 <= lab_dev < 3, ("label", rep.steps, s, u, lab_ref, lab_dev)
+                            gap = dist[lab_ref] - dist[lab_dev]
+                            assert gap <= tol, ("label beyond tolerance", rep.steps, s, u, gap)
+                            rep.label_flips += 1
+                        labels[u] = lab_dev
+                    assert all(int(v) == -1 for v in h_lab[s, max(u1 - u0 + 1, 0):])
+                    want = ocr.correct_block(cfg, st.P, block_pre, labels, st.tokens + [st.main], correct_hist)
+                    assert want == block_dev, ("corrected block", rep.steps, s, block_pre, labels, want, block_dev)
+                    rep.corrected_blocks += int(want != block_pre)
+                elif correct_hist:
+                    assert block_dev == block_pre
             else:
                 assert block_dev[0] == st.main and 1 <= len(block_dev) <= min(Bm, budget - st.P)
             lg = forward_block(model, st, block_dev)

@@ -47,6 +47,36 @@ def test_lockstep_small_native_heads(name):
         assert np.array_equal(out2.cpu().numpy(), out)
 
 
+@pytest.mark.parametrize("name", ["t_f32_99", "t_f32_1815", "t_bf16_99", "t_bf16_1815", "t_bf16_99_b1", "t_f32_2727", "t_bf16_c17"])
+def test_lockstep_with_correct_stage(name):
+    """Predict - correct - verify (Sec. 3.2): labels from the label head, the integer correction of every draft block
+    bit for bit, and a stream that the stage leaves untouched."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.TEST_CONFIGS[name]
+    print("case correct", name, flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype], correct_hist=6)
+    print(rep, flush=True)
+    assert all(len(s) == 9 * cfg.faces for s in streams)
+    if cfg.draft_point or cfg.draft_face:
+        assert rep.points > 0 and rep.corrected_blocks > 0
+    # whole-loop entry point with the stage on, and plain sequential decoding: the same stream
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    out, n, st = fm.generate(cfg.faces, True)
+    out = out.cpu().numpy()
+    if rep.token_flips == 0:
+        for s in range(cfg.batch):
+            assert list(out[s, :9 * cfg.faces]) == streams[s]
+    fm.set_correct(0)
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    out2, n2, st2 = fm.generate(cfg.faces, True)
+    assert np.array_equal(out2.cpu().numpy(), out)
+    with pytest.raises(RuntimeError):
+        fm.correct(*fm.new_block())
+
+
 def test_config0_tiny_full_run():
     _need_gpu()
     from parity_harness import lockstep
