@@ -84,6 +84,9 @@ def main():
     ap.add_argument("--window", type=int, default=0,
                     help="sliding-window self-attention: window in coordinate tokens (multiple of 9); with --faces beyond "
                          "the configuration's budget the stream runs past one window over ring K/V caches")
+    ap.add_argument("--correct", type=int, default=0,
+                    help="run the correct stage (label head, vertex-sharing moves, z-y-x re-sort) in every step, with this "
+                         "many historical vertices; random-init labels, so only its cost is meaningful")
     ap.add_argument("--b8-faces", type=int, default=150,
                     help="faces per sequence of the extra batch-8 leg (configs[3], same model as configs[2]); 0 = skip")
     ap.add_argument("--no-cpu", action="store_true")
@@ -112,6 +115,8 @@ def main():
     weights = si.make_weights(cfg, 0)
     fm = FlashMesh(config_struct(cfg))
     fm.load_weights(si.pack_blob(cfg, weights))
+    if args.correct:
+        fm.set_correct(args.correct)
     mems = [si.make_memory(cfg, s) for s in range(cfg.batch)]
     mems_dev = [torch.from_numpy(m).cuda() for m in mems]
 
@@ -245,7 +250,7 @@ def main():
     # batch-8 leg: the same model with 8 independent sequences (configs[3]) on a shortened budget, so that the
     # default run stays within minutes; ragged accepted lengths come from the per-sequence replay draws
     batch8 = None
-    if args.config == 2 and args.b8_faces > 0 and not args.draft and not args.window:
+    if args.config == 2 and args.b8_faces > 0 and not args.draft and not args.window and not args.correct:
         cfg8 = si.CONFIGS[3]
         f8 = min(args.b8_faces, cfg8.faces)
         fm.close()
@@ -307,7 +312,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: d={cfg.d_model}, {cfg.n_layers} blocks, batch {cfg.batch}, "
                                f"{faces} faces ({9 * faces} tokens), block {cfg.block_max}, draft counts Dc={cfg.draft_coord} m={cfg.draft_point} n={cfg.draft_face}"
-                               + (f", sliding window {cfg.window} tokens" if cfg.window else ""),
+                               + (f", sliding window {cfg.window} tokens" if cfg.window else "")
+                               + (f", correct stage on ({args.correct} historical vertices)" if args.correct else ""),
                    "draft_source": f"replay p={REPLAY_P}", "tokens": tokens, "mean_accepted": tokens / max(steps, 1),
                    "accepted_hist": hist, "stream_equals_native_run": same,
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,
