@@ -91,6 +91,8 @@ def main():
                     help="faces per sequence of the extra batch-8 leg (configs[3], same model as configs[2]); 0 = skip")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--gemm-sweep", action="store_true",
+                    help="row sweep (16 .. 4096) of the weight-streaming GEMM kernel on the FFN up projection; prints and exits")
     ap.add_argument("--counter-pass", action="store_true",
                     help="short run for hardware-counter collection: fill the caches to half context with forced "
                          "commits, then one 1 GiB device copy (the calibration kernel) and 5 verify passes")
@@ -117,6 +119,13 @@ def main():
     fm.load_weights(si.pack_blob(cfg, weights))
     if args.correct:
         fm.set_correct(args.correct)
+    if args.gemm_sweep:
+        sweep = [fm.measure_gemm(r) for r in (8, 16, 32, 72, 128, 256, 512, 1024, 2048, 4096)]
+        for e in sweep:
+            e["frac_of_mfma_peak"] = e["TFLOPs"] / MFMA_PEAK_TFLOPS
+            e["weight_GBs"] = 2.0 * cfg.d_model * cfg.ffn_mult * cfg.d_model / (e["ms"] * 1e-3) / 1e9
+        print(json.dumps({"gemm_sweep": f"Y[rows, {cfg.ffn_mult * cfg.d_model}] = gelu(X[rows, {cfg.d_model}] W^T), k_gemm_mfma", "rows": sweep}))
+        return
     mems = [si.make_memory(cfg, s) for s in range(cfg.batch)]
     mems_dev = [torch.from_numpy(m).cuda() for m in mems]
 

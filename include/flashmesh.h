@@ -171,6 +171,12 @@ int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
  * and frees 2 GiB of device memory for the duration of the call.  Synchronises. */
 int fm_measure_peaks(fm_ctx* ctx, double* host_out);
 
+/* Row sweep of the weight-streaming GEMM kernel that the per-operator path uses: times Y[rows, 4 d_model] =
+ * gelu(X[rows, d_model] W1^T) with the FFN up projection of the first block (half-precision contexts only), back to
+ * back on the context's stream.  HOST out[0] = milliseconds per launch, out[1] = TFLOP/s.  Allocates and frees its
+ * operands.  Synchronises. */
+int fm_measure_gemm(fm_ctx* ctx, int32_t rows, double* host_out);
+
 /* Which implementation fm_verify_block runs for this context: 1 = the single persistent kernel (half-precision
  * storage, one sequence, block <= 16), 0 = one launch per operator.  Both compute the same function with the same
  * arithmetic per operator; they cut the key axis of the attention differently, so results agree to rounding, and

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
            "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile",
-           "fm_verify_path", "fm_measure_peaks"]
+           "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm"]
 
 
 class LibraryMissing(RuntimeError):
@@ -65,6 +65,7 @@ def load_library():
     lib.fm_debug_ring.argtypes = [p, i32, p]
     lib.fm_debug_profile.argtypes = [p, p, i32]
     lib.fm_measure_peaks.argtypes = [p, C.POINTER(C.c_double)]
+    lib.fm_measure_gemm.argtypes = [p, i32, C.POINTER(C.c_double)]
     lib.fm_verify_path.argtypes = [p]
     lib.fm_verify_path.restype = i32
     for n in EXPORTS:
@@ -198,6 +199,11 @@ class FlashMesh:
         v = (C.c_double * 3)()
         self._chk(self.lib.fm_measure_peaks(self.h, v), "fm_measure_peaks")
         return {"hbm_read_GBs": v[0], "hbm_copy_GBs": v[1], "mfma_f16_TFLOPs": v[2]}
+
+    def measure_gemm(self, rows: int) -> dict:
+        out = (C.c_double * 2)()
+        self._chk(self.lib.fm_measure_gemm(self.h, rows, out), "fm_measure_gemm")
+        return {"rows": rows, "ms": out[0], "TFLOPs": out[1]}
 
     def verify_path(self) -> int:
         return int(self.lib.fm_verify_path(self.h))

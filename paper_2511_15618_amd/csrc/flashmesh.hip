@@ -1001,6 +1001,40 @@ int fm_measure_peaks(fm_ctx* c, double* host_out) {
   return rc;
 }
 
+int fm_measure_gemm(fm_ctx* c, int32_t rows, double* host_out) {
+  if (!c || !host_out) return FM_EINVAL;
+  if (!c->bf16 || !c->weights_loaded) return fail(c, FM_ESTATE, "GEMM probe needs the half-precision path with weights loaded");
+  if (rows < 1 || rows > 65536) return fail(c, FM_EINVAL, "rows %d outside [1, 65536]", rows);
+  const int d = c->D.d, N = c->ff;
+  const Layer& L = c->stacks[0][0];
+  f16_t *X = nullptr, *Y = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&]() {
+    if (X) (void)hipFree(X);
+    if (Y) (void)hipFree(Y);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+#define PK_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(c, FM_EHIP, "GEMM probe: %s failed", #x); } } while (0)
+  PK_TRY(hipStreamSynchronize(c->stream));
+  PK_TRY(hipMalloc((void**)&X, (size_t)rows * d * 2)); PK_TRY(hipMalloc((void**)&Y, (size_t)rows * N * 2));
+  PK_TRY(hipMemsetAsync(X, 0, (size_t)rows * d * 2, c->stream));
+  PK_TRY(hipEventCreate(&e0)); PK_TRY(hipEventCreate(&e1));
+  // Y[rows, ff] = gelu(X[rows, d] W1^T): the FFN up projection of the first block, half in and out
+  GemmArgs a{X, d, 0, L.w1, 0, Y, N, 0, nullptr, 0, 0, rows, N, d, nullptr, nullptr, 0.f, nullptr, nullptr, 0, nullptr, nullptr, 0, 0, 0};
+  const int reps = rows <= 256 ? 50 : 10;
+  float ms = 0.f;
+  if (!mfma_gemm_launch<f16_t>(c->mres, a, EPI_GELU_T, 1, c->stream)) { cleanup(); return fail(c, FM_EINVAL, "GEMM probe: unsupported shape"); }
+  PK_TRY(hipEventRecord(e0, c->stream));
+  for (int i = 0; i < reps; i++) mfma_gemm_launch<f16_t>(c->mres, a, EPI_GELU_T, 1, c->stream);
+  PK_TRY(hipEventRecord(e1, c->stream)); PK_TRY(hipEventSynchronize(e1)); PK_TRY(hipEventElapsedTime(&ms, e0, e1));
+  host_out[0] = ms / reps;
+  host_out[1] = 2.0 * rows * (double)N * d * reps / (ms * 1e-3) / 1e12;
+#undef PK_TRY
+  cleanup();
+  return FM_OK;
+}
+
 int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_tok, int32_t* out_len, fm_stats* stats) {
   if (!c) return FM_EINVAL;
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
