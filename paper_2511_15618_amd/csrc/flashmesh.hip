@@ -1025,8 +1025,15 @@ int fm_measure_gemm(fm_ctx* c, int32_t rows, double* host_out) {
   const int reps = rows <= 256 ? 50 : 10;
   float ms = 0.f;
   if (!mfma_gemm_launch<f16_t>(c->mres, a, EPI_GELU_T, 1, c->stream)) { cleanup(); return fail(c, FM_EINVAL, "GEMM probe: unsupported shape"); }
+  // FM_GEMM_PROBE_CYCLE = n: successive launches walk the up projections of n different blocks (n x 8 d^2 bytes
+  // of weights), which tells a last-level-cache hit from an L2 hit from HBM
+  std::vector<const void*> ws;
+  for (int st = 0; st < 5; st++) for (auto& Lx : c->stacks[st]) ws.push_back(Lx.w1);
+  int cyc = 1;
+  if (const char* e = getenv("FM_GEMM_PROBE_CYCLE")) cyc = std::max(1, std::min(atoi(e), (int)ws.size()));
+  for (int i = 0; i < cyc; i++) { a.W = ws[i]; mfma_gemm_launch<f16_t>(c->mres, a, EPI_GELU_T, 1, c->stream); }
   PK_TRY(hipEventRecord(e0, c->stream));
-  for (int i = 0; i < reps; i++) mfma_gemm_launch<f16_t>(c->mres, a, EPI_GELU_T, 1, c->stream);
+  for (int i = 0; i < reps; i++) { a.W = ws[i % cyc]; mfma_gemm_launch<f16_t>(c->mres, a, EPI_GELU_T, 1, c->stream); }
   PK_TRY(hipEventRecord(e1, c->stream)); PK_TRY(hipEventSynchronize(e1)); PK_TRY(hipEventElapsedTime(&ms, e0, e1));
   host_out[0] = ms / reps;
   host_out[1] = 2.0 * rows * (double)N * d * reps / (ms * 1e-3) / 1e12;
