@@ -162,6 +162,10 @@ def test_error_paths():
     assert lib.fm_generate(h, cfg.faces, 1, out.data_ptr(), ln.data_ptr(), None) == -2            # not prefilled
     assert lib.fm_set_budget(h, 0) == -1 and lib.fm_set_budget(h, cfg.faces + 1) == -1
     assert lib.fm_verify_block(h, None, ln.data_ptr(), None, acc.data_ptr()) == -1
+    assert lib.fm_correct(h, tok.data_ptr(), ln.data_ptr(), None) == -2                           # stage is off
+    assert lib.fm_set_correct(h, -1) == -1
+    assert lib.fm_set_correct(h, 4) == 0 and lib.fm_correct(h, None, ln.data_ptr(), None) == -1
+    assert lib.fm_set_correct(h, 0) == 0
     # an unprefilled sequence is simply not live; over-long and out-of-range block entries are clipped
     fm.prefill_condition(0, mem)
     tok.fill_(10 ** 6)
