@@ -73,6 +73,27 @@ def counter_traffic(config_index, persistent):
     return None
 
 
+class _Totals:
+    steps = 0
+    tokens = 0
+    ms_total = 0.0
+
+
+def generate_in_stages(fm, faces, what, stage=500):
+    """fm_generate to `faces` faces in stages of `stage` faces (the budget is raised and the loop resumes), with a
+    progress line on stderr after each: a long generation then never looks hung.  Totals over the stages."""
+    tot = _Totals()
+    done = 0
+    while done < faces:
+        done = min(done + stage, faces)
+        out, n, st = fm.generate(done, True)
+        tot.steps += int(st.steps)
+        tot.tokens += int(st.tokens)
+        tot.ms_total += float(st.ms_total)
+        print(f"bench: {what}: {done} / {faces} faces, {tot.steps} steps, {tot.ms_total / 1e3:.1f} s", file=sys.stderr, flush=True)
+    return out, n, tot
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,7 +135,9 @@ def main():
     faces = args.faces or cfg.faces
     if args.window:
         cfg = cfg.replace(window=args.window, faces=max(faces, cfg.faces))
+    print(f"bench: drawing the weights of configs[{args.config}]", file=sys.stderr, flush=True)
     weights = si.make_weights(cfg, 0)
+    print("bench: weights drawn, creating the context", file=sys.stderr, flush=True)
     fm = FlashMesh(config_struct(cfg))
     fm.load_weights(si.pack_blob(cfg, weights))
     if args.correct:
@@ -176,7 +199,7 @@ def main():
     reset()
     fm.set_draft_replay(None, 0, 0.0, 0)
     torch.cuda.synchronize()
-    out, n, st_native = fm.generate(faces, True)
+    out, n, st_native = generate_in_stages(fm, faces, "native heads")
     stream = out.clone()
     n_tokens = int(n.min().item())
 
