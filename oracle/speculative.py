@@ -16,6 +16,7 @@ import numpy as np
 from . import primitives as P
 from .correct import correct_block, draft_vertex_range, label_row, point_labels
 from .hourglass import Model, SeqState, forward_block
+from . import sampling as smp
 
 
 # ---------------------------------------------------------------------------------------
@@ -95,10 +96,12 @@ def _dist(model: Model, h):
     return P.softmax(model.logits(h[None, :]))[0]
 
 
-def draft(model: Model, st: SeqState, budget_tokens: int, merged=None):
+def draft(model: Model, st: SeqState, budget_tokens: int, merged=None, sampling=None, seq=0):
     """Build the next verify block [main, drafts...] from the state left by the last commit.
 
-    If `merged` is a list it receives the averaged distribution behind every draft token."""
+    If `merged` is a list it receives the averaged distribution behind every draft token.
+    sampling = (temperature, seed): the draft tokens are drawn from the averaged distributions
+    (oracle.sampling) instead of their arg max."""
     m, cfg = model, model.cfg
     if st.finished:
         return []
@@ -154,7 +157,11 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None):
         dist = sum(have) / float(len(have))
         if merged is not None:
             merged.append(dist)
-        block.append(pick(dist, cfg))
+        if sampling is None:
+            block.append(pick(dist, cfg))
+        else:
+            n = cfg.n_bins if cfg.ban_specials else cfg.vocab
+            block.append(smp.inverse_cdf(dist[:n], smp.uniform(sampling[1], seq, p, smp.DRAFT)))
         p += 1
     return block
 
@@ -180,6 +187,25 @@ def verify(model: Model, st: SeqState, block):
     logits = forward_block(model, st, block)
     y = [pick(logits[i], model.cfg) for i in range(len(block))]
     return logits, y, accept_length(block, y)
+
+
+def verify_sampled(model: Model, st: SeqState, block, proposals, sampling, seq=0):
+    """Non-greedy verification (oracle.sampling).  proposals[i] is the averaged distribution block[i + 1] was drawn
+    from, or None for a draft that did not come from it.  Returns (logits, y, a) in the shape verify() uses:
+    only y[a - 1], the token emitted after the accepted prefix, is meaningful."""
+    cfg = model.cfg
+    T, seed = sampling
+    n = cfg.n_bins if cfg.ban_specials else cfg.vocab
+    logits = forward_block(model, st, block)
+    B = len(block)
+    ps = [smp.target_row(logits[i], n, T) for i in range(B)]
+    qs = [None if proposals[i] is None else smp.proposal_row(proposals[i], n) for i in range(B - 1)] + [None]
+    us_acc = [smp.uniform(seed, seq, st.P + i + 1, smp.ACCEPT) for i in range(B)]
+    us_res = [smp.uniform(seed, seq, st.P + i + 1, smp.RESAMPLE) for i in range(B)]
+    a, tok = smp.verify_rows(ps, qs, block, us_acc, us_res)
+    y = [-1] * B
+    y[a - 1] = tok
+    return logits, y, a
 
 
 def commit(model: Model, st: SeqState, block, y, a: int):
@@ -209,24 +235,33 @@ def corrected(model: Model, st: SeqState, block, hist_vertices: int):
     return correct_block(model.cfg, st.P, block, labels, st.tokens + [st.main], hist_vertices)
 
 
-def generate(model: Model, mem, faces: int, speculative=True, draft_fn=None, trace=None, correct_hist=0):
+def generate(model: Model, mem, faces: int, speculative=True, draft_fn=None, trace=None, correct_hist=0, sampling=None,
+             seq=0):
     """Greedy generation of up to `faces` faces.  Returns (x_1 .., final state); BOS excluded, the pending main token included.
 
     speculative=False is plain one-token-at-a-time decoding of the same backbone.
     draft_fn(st, budget) overrides the draft source (tests feed adversarial drafts).
-    correct_hist > 0 runs the correct stage on every draft block with that many historical vertices."""
+    correct_hist > 0 runs the correct stage on every draft block with that many historical vertices.
+    sampling = (temperature, seed) switches from greedy decoding to sampled decoding with non-greedy verification."""
     budget = 9 * faces
     st = SeqState(model, mem, budget)
     while not st.finished and st.P < budget:
         if not speculative:
-            block = [st.main]
+            block, merged = [st.main], []
         elif draft_fn is not None:
             block = draft_fn(st, budget)
+            merged = [None] * (len(block) - 1)
         else:
-            block = draft(model, st, budget)
+            merged = []
+            block = draft(model, st, budget, merged, sampling, seq)
         if speculative and correct_hist > 0:
-            block = corrected(model, st, block, correct_hist)
-        _, y, a = verify(model, st, block)
+            fixed = corrected(model, st, block, correct_hist)
+            merged = [m if fixed[i + 1] == block[i + 1] else None for i, m in enumerate(merged)]
+            block = fixed
+        if sampling is None:
+            _, y, a = verify(model, st, block)
+        else:
+            _, y, a = verify_sampled(model, st, block, merged, sampling, seq)
         a = commit(model, st, block, y, a)
         if trace is not None:
             trace.append((st.P - a, list(block), a))

@@ -7,6 +7,7 @@ import pytest
 import synth_inputs as si
 from oracle import primitives as P
 from oracle import correct as oc
+from oracle import sampling as smp
 from oracle import speculative as sp
 from oracle.hourglass import Model, SeqState, forward_block, forward_full
 
@@ -461,3 +462,87 @@ def test_label_rows_are_softmax_of_the_linear_head():
     row = oc.label_row(m, f)
     z = np.array([float(np.dot(m.w["label"][i], f)) for i in range(3)])
     assert np.allclose(row, np.exp(z) / np.exp(z).sum(), atol=1e-14) and abs(row.sum() - 1.0) < 1e-14
+
+
+# -- non-greedy verification (oracle.sampling) ----------------------------------------------------
+def test_inverse_cdf_closed_forms():
+    w = np.array([0.0, 2.0, 0.0, 1.0, 1.0])
+    assert smp.inverse_cdf(w, 0.0) == 1                       # first index with weight
+    assert [smp.inverse_cdf(w, u) for u in (0.49, 0.5, 0.74, 0.75, 0.999999)] == [1, 3, 3, 4, 4]
+    assert smp.inverse_cdf(np.ones(8), 0.37) == 2             # uniform weights: floor(8 u)
+    assert smp.inverse_cdf(np.ones(8) * 1e-30, 0.999) == 7
+    r = np.random.default_rng(0)
+    w = r.random(50)
+    for u in r.random(200):
+        i = smp.inverse_cdf(w, u)
+        assert w[:i].sum() <= u * w.sum() < w[:i + 1].sum() + 1e-12
+
+
+def test_target_row_is_tempered_softmax_and_tends_to_greedy():
+    z = np.array([0.3, -1.0, 2.0, 1.9, 7.0, 0.0])
+    p = smp.target_row(z, 4, 0.5)                               # only the first four tokens are admissible
+    want = np.exp(z[:4] / 0.5)
+    assert np.allclose(p, want / want.sum(), atol=1e-15) and len(p) == 4
+    assert np.argmax(smp.target_row(z, 4, 1e-3)) == 2 and smp.target_row(z, 4, 1e-3)[2] > 1 - 1e-12
+
+
+def test_rejection_rule_special_cases():
+    p = np.array([0.5, 0.3, 0.2, 0.0])
+    # proposal equal to the target: every draft is accepted
+    assert all(smp.accept_draft(p, p, x, u) for x in range(3) for u in (0.0, 0.5, 0.999999))
+    # a draft the target gives no mass is always rejected and the replacement comes from the target itself
+    q = np.array([0.0, 0.0, 0.0, 1.0])
+    assert not smp.accept_draft(p, q, 3, 0.0)
+    assert np.allclose(smp.residual(p, q, 3), p)
+    # general case: acceptance probability min(1, p/q), residual max(p - q, 0)
+    q = np.array([0.1, 0.6, 0.3, 0.0])
+    assert smp.accept_draft(p, q, 0, 0.999999)                                   # p/q = 5
+    assert smp.accept_draft(p, q, 1, 0.49) and not smp.accept_draft(p, q, 1, 0.51)   # p/q = 1/2
+    assert np.allclose(smp.residual(p, q, 1), [0.4, 0.0, 0.0, 0.0])
+    # point-mass proposal: accepted with probability p(x), replacement from p without x
+    assert smp.accept_draft(p, None, 1, 0.29) and not smp.accept_draft(p, None, 1, 0.31)
+    assert np.allclose(smp.residual(p, None, 1), [0.5, 0.0, 0.2, 0.0])
+    # a draft outside the admissible tokens is rejected
+    assert not smp.accept_draft(p, None, 7, 0.0)
+
+
+def test_speculative_sampling_reproduces_the_target_distribution():
+    """The defining property: draw a draft from q, apply the rejection test, and the token that comes out is
+    distributed as the target p, whatever q is (chi-square against p over many draws, two positions deep)."""
+    r = np.random.default_rng(3)
+    V, N = 6, 60000
+    for trial in range(3):
+        p0, p1 = r.dirichlet(np.ones(V)), r.dirichlet(np.ones(V) * 0.5)
+        q0, q1 = r.dirichlet(np.ones(V) * 2.0), r.dirichlet(np.ones(V))
+        if trial == 2:
+            q0 = None                                      # point-mass proposals (a replayed draft)
+        first = np.zeros(V)
+        second_given_accept = np.zeros(V)
+        n_acc = 0
+        for _ in range(N):
+            u = r.random(6)
+            x1 = smp.inverse_cdf(q0, u[0]) if q0 is not None else int(r.integers(0, V))
+            x2 = smp.inverse_cdf(q1, u[1])
+            a, tok = smp.verify_rows([p0, p1, p0], [q0, q1, None], [0, x1, x2], u[2:5], [u[5], r.random(), r.random()])
+            emitted = [x1, x2][:a - 1] + [tok]
+            first[emitted[0]] += 1
+            if a >= 2:
+                n_acc += 1
+                second_given_accept[emitted[1]] += 1
+        chi = ((first - N * p0) ** 2 / (N * p0)).sum()
+        assert chi < 25.0, (trial, chi)                    # 5 degrees of freedom: P(chi2 > 25) ~ 1e-4
+        chi2 = ((second_given_accept - n_acc * p1) ** 2 / (n_acc * p1)).sum()
+        assert chi2 < 25.0, (trial, chi2)
+
+
+def test_sampled_generation_is_keyed_and_tends_to_greedy():
+    cfg, m, mem = _model("t_f32_99")
+    a, _ = sp.generate(m, mem, cfg.faces, True, sampling=(1.0, 5))
+    b, _ = sp.generate(m, mem, cfg.faces, True, sampling=(1.0, 5))
+    c, _ = sp.generate(m, mem, cfg.faces, True, sampling=(1.0, 6))
+    assert a == b and a != c and len(a) == 9 * cfg.faces
+    greedy, _ = sp.generate(m, mem, cfg.faces, True)
+    cold, _ = sp.generate(m, mem, cfg.faces, True, sampling=(1e-4, 5))
+    assert cold == greedy
+    cold_seq, _ = sp.generate(m, mem, cfg.faces, False, sampling=(1e-4, 9))
+    assert cold_seq == greedy
