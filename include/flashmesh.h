@@ -117,6 +117,16 @@ int fm_draft(fm_ctx* ctx, int32_t* block_tok_dev, int32_t* block_len_dev);
 int fm_set_correct(fm_ctx* ctx, int32_t hist_vertices);
 int fm_correct(fm_ctx* ctx, int32_t* block_tok_dev, const int32_t* block_len_dev, int32_t* labels_out_dev);
 
+/* Sampled decoding with non-greedy verification (the supplement's "Integrating the three levels" averages predicted
+ * distributions; Sec. 3.3 evaluates a match test, which is temperature 0 here).  With temperature T > 0: fm_draft draws
+ * every draft token from the averaged draft distribution q over the admissible tokens; fm_verify_block forms
+ * p = softmax(logits / T) per row, accepts draft x while u q(x) < p(x) (a draft that is not the token drawn from q -
+ * replayed, corrected or written by the caller - counts as a proposal with all its mass on it), and the next main token
+ * comes from max(p - q, 0) after the first rejection, from p after a fully accepted block.  The emitted stream is then
+ * distributed like token-by-token sampling from the backbone.  Uniforms are counter based, keyed by (seed, sequence,
+ * absolute position, purpose), so a run is reproducible.  temperature = 0 (the default) is greedy decoding. */
+int fm_set_sampling(fm_ctx* ctx, float temperature, uint64_t seed);
+
 /* Verify stage (Sec. 3.3): one causal backbone forward over each sequence's block at positions
  * P .. P+len-1 against the K/V caches of all three levels.  logits_dev ([batch, block_max, vocab]
  * float32) may be NULL.  accepted_len_dev[seq] = 1 + number of leading drafts equal to the

@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
-           "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile",
+           "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile",
            "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm"]
 
 
@@ -59,6 +59,7 @@ def load_library():
     lib.fm_read_state.argtypes = [p, p]
     lib.fm_set_draft_replay.argtypes = [p, p, i32, i32, C.c_float, C.c_uint64]
     lib.fm_set_budget.argtypes = [p, i32]
+    lib.fm_set_sampling.argtypes = [p, C.c_float, C.c_uint64]
     lib.fm_set_correct.argtypes = [p, i32]
     lib.fm_correct.argtypes = [p, p, p, p]
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
@@ -174,6 +175,9 @@ class FlashMesh:
             self._keep = stream
             self._chk(self.lib.fm_set_draft_replay(self.h, self._ptr(stream), stream.shape[1], n_valid,
                                                    C.c_float(keep_prob), C.c_uint64(seed)), "fm_set_draft_replay")
+
+    def set_sampling(self, temperature: float, seed: int):
+        self._chk(self.lib.fm_set_sampling(self.h, C.c_float(temperature), C.c_uint64(seed)), "fm_set_sampling")
 
     def set_correct(self, hist_vertices: int):
         self._chk(self.lib.fm_set_correct(self.h, hist_vertices), "fm_set_correct")

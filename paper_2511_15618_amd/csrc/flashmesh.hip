@@ -75,6 +75,7 @@ struct fm_ctx {
   HfLevel hfc, hfv;
   float* label_w;     // label head of the correct stage [3][d]
   float *lab_v, *lab_f;   // label distributions of the point pipeline [S][nspv][3] and the face pipeline [S][nhfv][3]
+  Sampling smp;           // sampled decoding (temperature 0 = greedy): proposals kept between draft and verify
   int correct_hist = 0;   // historical vertices the correct stage looks at; 0 = stage off (no label rows are computed)
 
   // state
@@ -277,6 +278,19 @@ void run_stack(fm_ctx* c, int stack, float* tap_ring, int tap_rs) {
   }
 }
 
+// per verify row: the backbone's greedy token (or, with sampled decoding, the rejection test and the resampled token),
+// then the accepted length per sequence
+void choose_and_accept(fm_ctx* c, const float* logits, int32_t* accepted) {
+  const Dims& D = c->D;
+  if (c->smp.temperature > 0.f) {
+    hipLaunchKernelGGL(k_sample_rows, dim3(c->Rc), dim3(256), 0, c->stream, c->st, D, logits, c->smp);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)c->smp.accflag);
+  } else {
+    hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, logits, D.V, D.ban ? D.nbins : D.V, c->st.y);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)nullptr);
+  }
+}
+
 template <typename T>
 int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits_out, int32_t* accepted) {
   const Dims& D = c->D;
@@ -289,8 +303,7 @@ int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, f
     c->pk.logits = lgp;
     c->pk.epoch = ++c->pk_epoch;
     hipLaunchKernelGGL(k_verify_persist, dim3(PK_NWG), dim3(256), c->pk_lds, c->stream, c->pk);
-    hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, lgp, D.V, D.ban ? D.nbins : D.V, c->st.y);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted);
+    choose_and_accept(c, lgp, accepted);
     HIPCHK(c, hipGetLastError());
     return FM_OK;
   }
@@ -320,8 +333,7 @@ int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, f
   // output head, greedy prediction, acceptance
   float* lg = logits_out ? logits_out : c->logits;
   gemm_norm<T>(c, EPI_F32, c->h[0], c->gf, c->lm, lg, D.V, c->Rc, D.V, flag);
-  hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, lg, D.V, D.ban ? D.nbins : D.V, c->st.y);
-  hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted);
+  choose_and_accept(c, lg, accepted);
   HIPCHK(c, hipGetLastError());
   return FM_OK;
 }
@@ -397,7 +409,7 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
     }
   }
   hipLaunchKernelGGL(k_merge, dim3(D.S), dim3(256), 0, c->stream, c->st, D, c->dr, c->dist_c, c->dist_v, c->dist_f,
-                     c->replay, speculative, block_tok, block_len);
+                     c->replay, speculative, block_tok, block_len, c->smp);
   HIPCHK(c, hipGetLastError());
   return FM_OK;
 }
@@ -664,6 +676,9 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &c->dist_c, S * std::max(D.Dc, 1) * D.V));
   TRY(dalloc(c, &c->dist_v, S * std::max(D.nhfc, 1) * D.V)); TRY(dalloc(c, &c->dist_f, S * std::max(D.nhfc, 1) * D.V));
   TRY(dalloc(c, &c->lab_v, S * std::max(D.nspv, 1) * 3)); TRY(dalloc(c, &c->lab_f, S * std::max(D.nhfv, 1) * 3));
+  c->smp = Sampling{0.f, 0ull, nullptr, nullptr, nullptr, nullptr};
+  TRY(dalloc(c, &c->smp.qrow, S * D.Bm * D.V)); TRY(dalloc(c, &c->smp.qsum, S * D.Bm));
+  TRY(dalloc(c, &c->smp.qtok, S * D.Bm)); TRY(dalloc(c, &c->smp.accflag, S * D.Bm));
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
@@ -838,6 +853,14 @@ int fm_draft(fm_ctx* c, int32_t* block_tok, int32_t* block_len) {
   if (!block_tok || !block_len) return fail(c, FM_EINVAL, "null block buffer");
   const int rc = c->bf16 ? draft_impl<f16_t>(c, block_tok, block_len, 1) : draft_impl<float>(c, block_tok, block_len, 1);
   return rc == FM_OK && c->sticky_error ? FM_EINVAL : rc;
+}
+
+int fm_set_sampling(fm_ctx* c, float temperature, uint64_t seed) {
+  if (!c) return FM_EINVAL;
+  if (!(temperature >= 0.f) || temperature > 1e4f) return fail(c, FM_EINVAL, "temperature %g outside [0, 1e4]", (double)temperature);
+  c->smp.temperature = temperature;
+  c->smp.seed = seed;
+  return FM_OK;
 }
 
 int fm_set_correct(fm_ctx* c, int32_t hist_vertices) {

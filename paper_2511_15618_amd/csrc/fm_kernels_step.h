@@ -86,15 +86,17 @@ __global__ __launch_bounds__(256) void k_verify_setup(StateDev st, Dims D, InvFr
   }
 }
 
-// accepted = 1 + number of leading drafts that equal the backbone's greedy prediction
-__global__ void k_accept(StateDev st, Dims D, int* __restrict__ accepted_out) {
+// accepted = 1 + number of leading drafts that equal the backbone's greedy prediction; with sampled decoding
+// (accflag != null) 1 + number of leading drafts that passed the rejection test (flag of row i is about draft i + 1)
+__global__ void k_accept(StateDev st, Dims D, int* __restrict__ accepted_out, const int* __restrict__ accflag) {
   const int s = threadIdx.x;
   if (s >= D.S) return;
   const int len = st.vlen[s];
   int a = 0;
   if (len > 0) {
     a = 1;
-    while (a < len && st.vtok[s * D.Bm + a] == st.y[s * D.Bm + a - 1]) a++;
+    if (accflag) while (a < len && accflag[s * D.Bm + a - 1]) a++;
+    else while (a < len && st.vtok[s * D.Bm + a] == st.y[s * D.Bm + a - 1]) a++;
   }
   st.acc[s] = a;
   if (accepted_out) accepted_out[s] = a;
@@ -160,6 +162,68 @@ __global__ void k_reset_seq(StateDev st, Dims D, int s, int bos) {
   int alive = 0;
   for (int i = 0; i < D.S; i++) alive += st.fin[i] ? 0 : 1;
   st.alive[0] = alive;
+}
+
+
+// ------------------------------------------------------------------------------------------
+// Sampled decoding with non-greedy verification: drafts drawn from the averaged draft distributions, the
+// rejection test of speculative sampling on the backbone's tempered softmax, residual resampling.
+// Uniforms are counter based: (seed, sequence, absolute position of the token decided, purpose).
+// ------------------------------------------------------------------------------------------
+#define FM_U_DRAFT 0
+#define FM_U_ACCEPT 1
+#define FM_U_RESAMPLE 2
+
+struct Sampling {
+  float temperature;            // 0 = greedy decoding
+  unsigned long long seed;
+  float* qrow;                  // [S][Bm][V] averaged draft distribution behind draft index i (unnormalised over the admissible tokens)
+  float* qsum;                  // [S][Bm]    its sum over the admissible tokens
+  int* qtok;                    // [S][Bm]    the token drawn from it (-1: none)
+  int* accflag;                 // [S][Bm]    row i: draft i + 1 passed the rejection test
+};
+
+__device__ __forceinline__ float sample_uniform(unsigned long long seed, int purpose, int seq, int pos);
+
+// Inverse CDF in index order over n weights, by one workgroup of 256 threads: thread t owns the contiguous chunk
+// [t*chunk, (t+1)*chunk); `wf(i)` gives weight i.  Returns the smallest i whose cumulative weight exceeds
+// u * total (the last index with weight if rounding leaves none), the same in every thread.  sh: 258 floats, si: 1 int.
+template <class F>
+__device__ __forceinline__ int block_inverse_cdf(int n, float u, F wf, float* sh, int* si) {
+  const int t = threadIdx.x;
+  const int chunk = (n + 255) / 256;
+  const int i0 = t * chunk, i1 = min(i0 + chunk, n);
+  float local = 0.f;
+  for (int i = i0; i < i1; i++) local += wf(i);
+  sh[t] = local;
+  if (t == 0) *si = -1;
+  __syncthreads();
+  if (t == 0) {
+    float run = 0.f;
+    for (int k = 0; k < 256; k++) { const float v = sh[k]; sh[k] = run; run += v; }
+    sh[256] = run;
+  }
+  __syncthreads();
+  const float thr = u * sh[256];
+  const float excl = sh[t];
+  if (i0 < i1 && excl <= thr && excl + local > thr) {
+    float run = excl;
+    for (int i = i0; i < i1; i++) {
+      run += wf(i);
+      if (run > thr) { *si = i; break; }
+    }
+  }
+  __syncthreads();
+  if (*si < 0 && t == 0) {
+    int last = 0;
+    for (int i = 0; i < n; i++)
+      if (wf(i) > 0.f) last = i;
+    *si = last;
+  }
+  __syncthreads();
+  const int r = *si;
+  __syncthreads();
+  return r;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -299,14 +363,84 @@ __device__ __forceinline__ float replay_uniform(unsigned long long seed, unsigne
   return (float)(z >> 40) * (1.0f / 16777216.0f);
 }
 
+__device__ __forceinline__ float sample_uniform(unsigned long long seed, int purpose, int seq, int pos) {
+  return replay_uniform(seed * 3ull + (unsigned long long)purpose, (unsigned long long)seq, (unsigned long long)pos);
+}
+
+// One workgroup per verify row (sequence s, block index i): the backbone's distribution p = softmax(logits / T) over the
+// admissible tokens, the rejection test for the draft at index i + 1 (u q(x) < p(x); a draft that is not the token
+// drawn from the stored distribution counts as a proposal with all its mass on it), and the token emitted after this
+// row if the accepted prefix ends here: from max(p - q, 0) after a rejection, from p after the last row.
+__global__ __launch_bounds__(256) void k_sample_rows(StateDev st, Dims D, const float* __restrict__ logits, Sampling sm) {
+  __shared__ float sh[260];
+  __shared__ int si;
+  const int row = blockIdx.x, s = row / D.Bm, i = row % D.Bm;
+  const int len = st.vlen[s];
+  if (i >= len) return;
+  const int nlim = D.ban ? D.nbins : D.V;
+  const float* x = logits + (long)row * D.V;
+  const float invT = 1.0f / sm.temperature;
+  // max and sum of exp((x - max) / T)
+  float mx = -INFINITY;
+  for (int j = threadIdx.x; j < nlim; j += 256) mx = fmaxf(mx, x[j]);
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3]));
+  __syncthreads();
+  float sum = 0.f;
+  for (int j = threadIdx.x; j < nlim; j += 256) sum += expf((x[j] - mx) * invT);
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  const float invZp = 1.0f / (sh[0] + sh[1] + sh[2] + sh[3]);
+  __syncthreads();
+  auto pf = [&](int j) { return expf((x[j] - mx) * invT) * invZp; };
+  const int pos = st.P[s] + i + 1;                       // the token this row decides
+  const bool has_draft = i + 1 < len;
+  const int xd = has_draft ? st.vtok[s * D.Bm + i + 1] : -1;
+  const bool fromq = has_draft && xd == sm.qtok[s * D.Bm + i + 1] && xd >= 0 && xd < nlim;
+  const float* q = sm.qrow + ((long)s * D.Bm + i + 1) * D.V;
+  const float invZq = fromq ? 1.0f / sm.qsum[s * D.Bm + i + 1] : 0.f;
+  bool accepted = false;
+  if (has_draft && xd >= 0 && xd < nlim) {
+    const float pa = pf(xd), qa = fromq ? q[xd] * invZq : 1.0f;
+    accepted = sample_uniform(sm.seed, FM_U_ACCEPT, s, pos) * qa < pa;
+  }
+  const float u = sample_uniform(sm.seed, FM_U_RESAMPLE, s, pos);
+  int y;
+  if (!has_draft) {
+    y = block_inverse_cdf(nlim, u, pf, sh, &si);
+  } else {
+    auto wf = [&](int j) { return fromq ? fmaxf(pf(j) - q[j] * invZq, 0.f) : (j == xd ? 0.f : pf(j)); };
+    // all the mass can vanish only if p and q agree everywhere (or p sits on the draft alone): then p itself
+    float tot = 0.f;
+    for (int j = threadIdx.x; j < nlim; j += 256) tot += wf(j);
+    tot = wave_sum(tot);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = tot;
+    __syncthreads();
+    tot = sh[0] + sh[1] + sh[2] + sh[3];
+    __syncthreads();
+    y = tot > 0.f ? block_inverse_cdf(nlim, u, wf, sh, &si) : block_inverse_cdf(nlim, u, pf, sh, &si);
+  }
+  if (threadIdx.x == 0) {
+    st.y[row] = y;
+    sm.accflag[row] = accepted ? 1 : 0;
+  }
+}
+
 // One workgroup per sequence: update the draft bookkeeping, average the distributions that cover
 // each future position, take the greedy token, stop at the first uncovered position.
 __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R, const float* __restrict__ dist_c,
                                                 const float* __restrict__ dist_v, const float* __restrict__ dist_f,
                                                 Replay rp, int speculative, int* __restrict__ block_tok,
-                                                int* __restrict__ block_len) {
+                                                int* __restrict__ block_len, Sampling sm) {
   __shared__ float sv[4];
   __shared__ int si[4];
+  __shared__ float sh[260];
+  __shared__ int sidx;
+  if (sm.temperature > 0.f)
+    for (int i = threadIdx.x; i < D.Bm; i += 256) sm.qtok[blockIdx.x * D.Bm + i] = -1;
   const int s = blockIdx.x;
   int* tok = block_tok + (long)s * D.Bm;
   if (st.fin[s]) {
@@ -342,6 +476,22 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
     if (basef >= 0 && tf >= 3 && tf < D.n) rows[cnt++] = dist_f + ((long)s * D.nhfc + (tf - 3)) * D.V;
     if (cnt == 0) break;
     const float inv = 1.0f / (float)cnt;
+    if (sm.temperature > 0.f) {
+      // sampled decoding: keep the averaged distribution (the proposal the verify pass tests against) and draw from it
+      float* qr = sm.qrow + ((long)s * D.Bm + len) * D.V;
+      for (int i = threadIdx.x; i < nlim; i += 256) {
+        float a = rows[0][i];
+        if (cnt > 1) a += rows[1][i];
+        if (cnt > 2) a += rows[2][i];
+        qr[i] = a * inv;
+      }
+      __syncthreads();
+      const int b = block_inverse_cdf(nlim, sample_uniform(sm.seed, FM_U_DRAFT, s, p), [&](int i) { return qr[i]; }, sh, &sidx);
+      if (threadIdx.x == 0) { tok[len] = b; sm.qtok[s * D.Bm + len] = b; sm.qsum[s * D.Bm + len] = sh[256]; }
+      __syncthreads();
+      len++;
+      continue;
+    }
     float bv = -INFINITY;
     int bi = 0x7fffffff;
     for (int i = threadIdx.x; i < nlim; i += 256) {

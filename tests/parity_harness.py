@@ -13,6 +13,7 @@ import torch
 
 import synth_inputs as si
 from oracle import correct as ocr
+from oracle import sampling as smp
 from oracle import speculative as osp
 from oracle.hourglass import Model, SeqState, forward_block
 from paper_2511_15618_amd import FlashMesh
@@ -50,8 +51,16 @@ def make_pair(cfg, work=np.float64, max_tokens=None):
     return model, fm, states
 
 
+def _cdf_margin(w, u, idx):
+    """How far u is outside the cumulative-weight interval of idx (0 if idx is an exact inverse-CDF answer)."""
+    c = np.cumsum(np.asarray(w, np.float64))
+    c = c / c[-1]
+    lo = c[idx - 1] if idx > 0 else 0.0
+    return max(lo - u, u - c[idx], 0.0)
+
+
 def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work=np.float64, check_logits=True,
-             correct_hist=0):
+             correct_hist=0, sampling=None):
     """Run the decode loop on both sides; returns (Report, device token streams).
 
     correct_hist > 0: the correct stage runs between draft and verify on both sides.  The device's labels must be the
@@ -61,6 +70,11 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
     fm.set_budget(faces)
     if correct_hist:
         fm.set_correct(correct_hist)
+    if sampling is not None:
+        # sampled decoding: every decision (draft draw, rejection test, resampled token) must be the oracle's, or lie
+        # within the tolerance of the boundary that decides it; the oracle is then forced onto the device's decision
+        assert drafts == "native" and replay is None and not correct_hist
+        fm.set_sampling(*sampling)
     budget = 9 * faces
     if replay is not None:
         fm.set_draft_replay(*replay)
@@ -92,6 +106,7 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
         h_lab = labels_dev.cpu().numpy()
         h_logits, h_acc = logits.cpu().numpy(), acc.cpu().numpy()
         fm.commit(acc)
+        main_after = fm.read_state()[:, 3] if sampling is not None else None
         for s in range(S):
             st = states[s]
             if st.finished or st.P >= budget:
@@ -99,6 +114,49 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
                 continue
             block_dev = [int(t) for t in h_tok[s, :h_len[s]]]
             block_pre = [int(t) for t in h_pre[s, :h_len[s]]] if correct_hist else block_dev
+            if sampling is not None:
+                T, seed = sampling
+                merged = []
+                block_ref = osp.draft(model, st, budget, merged, sampling, seq=s)
+                assert len(block_ref) == len(block_dev) and block_ref[0] == block_dev[0], (rep.steps, s, block_ref, block_dev)
+                for i in range(1, len(block_ref)):
+                    if block_ref[i] != block_dev[i]:
+                        gap = _cdf_margin(merged[i - 1][:nlim], smp.uniform(seed, s, st.P + i, smp.DRAFT), block_dev[i])
+                        assert gap <= tol, ("sampled draft beyond tolerance", rep.steps, s, i, gap)
+                        rep.draft_flips += 1
+                lg = forward_block(model, st, block_dev)
+                B = len(block_dev)
+                err = float(np.abs(lg - h_logits[s, :B]).max())
+                rep.max_logit_err = max(rep.max_logit_err, err)
+                assert err <= tol, ("logits beyond tolerance", rep.steps, s, err)
+                ps = [smp.target_row(lg[i], nlim, T) for i in range(B)]
+                qs = [smp.proposal_row(merged[i], nlim) for i in range(B - 1)] + [None]
+                ua = [smp.uniform(seed, s, st.P + i + 1, smp.ACCEPT) for i in range(B)]
+                ur = [smp.uniform(seed, s, st.P + i + 1, smp.RESAMPLE) for i in range(B)]
+                a_ref, _ = smp.verify_rows(ps, qs, block_dev, ua, ur)
+                a = int(h_acc[s])
+                assert 1 <= a <= B
+                if a_ref != a:
+                    k = min(a_ref, a)                  # the first decision that differs is about draft k (row k - 1)
+                    x = block_dev[k]
+                    gap = abs(ua[k - 1] * qs[k - 1][x] - ps[k - 1][x])
+                    assert gap <= tol, ("rejection test beyond tolerance", rep.steps, s, k, gap)
+                    rep.token_flips += 1
+                w = ps[a - 1] if a == B else smp.residual(ps[a - 1], qs[a - 1], block_dev[a])
+                tok_ref, tok_dev = smp.inverse_cdf(w, ur[a - 1]), int(main_after[s])
+                if tok_ref != tok_dev:
+                    assert 0 <= tok_dev < nlim
+                    gap = _cdf_margin(w, ur[a - 1], tok_dev)
+                    assert gap <= tol, ("resampled token beyond tolerance", rep.steps, s, a, gap)
+                    rep.token_flips += 1
+                y = [-1] * B
+                y[a - 1] = tok_dev
+                osp.commit(model, st, block_dev, y, a)
+                if st.P >= budget:
+                    st.finished = True
+                rep.accepted.append(a)
+                rep.block_lens.append(B)
+                continue
             if drafts == "native" and replay is None:
                 merged = []
                 block_ref = osp.draft(model, st, budget, merged)

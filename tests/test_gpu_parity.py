@@ -77,6 +77,41 @@ def test_lockstep_with_correct_stage(name):
         fm.correct(*fm.new_block())
 
 
+@pytest.mark.parametrize("name,temperature", [("t_f32_99", 1.0), ("t_f32_1815", 0.7), ("t_bf16_99", 1.0), ("t_bf16_1815", 1.3),
+                                              ("t_bf16_99_b1", 1.0), ("t_f32_c", 1.0)])
+def test_lockstep_sampled_decoding(name, temperature):
+    """Sampled decoding with non-greedy verification: the drawn drafts, the rejection tests (accepted lengths) and the
+    resampled tokens against the oracle, decision by decision, with the same counter-based uniforms on both sides."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.TEST_CONFIGS[name]
+    print("case sampled", name, flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype], sampling=(temperature, 17))
+    print(rep, flush=True)
+    assert all(len(s) == 9 * cfg.faces for s in streams)
+    # reproducible from the seed through the whole-loop entry point, and different for another seed
+    def run(seed):
+        fm.set_sampling(temperature, seed)
+        for s in range(cfg.batch):
+            fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+        return fm.generate(cfg.faces, True)[0].cpu().numpy()
+    a, b, c = run(17), run(17), run(18)
+    assert np.array_equal(a, b) and not np.array_equal(a, c)
+    if rep.token_flips == 0 and rep.draft_flips == 0:
+        for s in range(cfg.batch):
+            assert list(a[s, :9 * cfg.faces]) == streams[s]
+    # temperature 0 is greedy decoding again
+    fm.set_sampling(0.0, 0)
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    g1 = fm.generate(cfg.faces, True)[0].cpu().numpy()
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    g2 = fm.generate(cfg.faces, False)[0].cpu().numpy()
+    if cfg.dtype == "f32":
+        assert np.array_equal(g1, g2)
+
+
 def test_config0_tiny_full_run():
     _need_gpu()
     from parity_harness import lockstep
