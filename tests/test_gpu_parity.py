@@ -112,6 +112,19 @@ def test_lockstep_sampled_decoding(name, temperature):
         assert np.array_equal(g1, g2)
 
 
+@pytest.mark.parametrize("name", ["t_f32_1815", "t_bf16_99"])
+def test_lockstep_sampled_decoding_with_correct_stage(name):
+    """Tokens the correct stage rewrote are no longer draws from the stored proposal: the rejection test then treats them
+    as proposals with all their mass on one token (accept with probability p(x), resample from p without x)."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.TEST_CONFIGS[name]
+    print("case sampled + correct", name, flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype], sampling=(1.0, 3), correct_hist=6)
+    print(rep, flush=True)
+    assert all(len(s) == 9 * cfg.faces for s in streams) and rep.corrected_blocks > 0
+
+
 def test_config0_tiny_full_run():
     _need_gpu()
     from parity_harness import lockstep
