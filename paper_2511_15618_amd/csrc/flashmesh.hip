@@ -302,7 +302,8 @@ int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, f
     float* lgp = logits_out ? logits_out : c->logits;
     c->pk.logits = lgp;
     c->pk.epoch = ++c->pk_epoch;
-    hipLaunchKernelGGL(k_verify_persist, dim3(PK_NWG), dim3(256), c->pk_lds, c->stream, c->pk);
+    if (c->pk.RS == 32) hipLaunchKernelGGL(k_verify_persist<2>, dim3(PK_NWG), dim3(256), c->pk_lds, c->stream, c->pk);
+    else hipLaunchKernelGGL(k_verify_persist<1>, dim3(PK_NWG), dim3(256), c->pk_lds, c->stream, c->pk);
     choose_and_accept(c, lgp, accepted);
     HIPCHK(c, hipGetLastError());
     return FM_OK;
@@ -596,15 +597,18 @@ int build_persist(fm_ctx* c) {
   const size_t nl = hl.size();
   // GEMM inputs (fp32 residual stream and its half-pair copy, attention outputs, FFN hidden): one region per layer,
   // so that no address is written twice within a launch
-  TRY(dalloc(c, &a.hA, (nl + 1) * 16 * d)); TRY(dalloc(c, &a.hB, nl * 16 * d)); TRY(dalloc(c, &a.hC, nl * 16 * d));
-  for (int i = 0; i < 4; i++) TRY(dalloc(c, &a.hT[i], 16 * d));
-  TRY(dalloc(c, &a.xA, (nl + 1) * 8 * d)); TRY(dalloc(c, &a.xB, nl * 8 * d)); TRY(dalloc(c, &a.xC, nl * 8 * d));
-  TRY(dalloc(c, &a.q, 8 * d)); TRY(dalloc(c, &a.att, nl * 8 * d)); TRY(dalloc(c, &a.q2, 8 * d));
-  TRY(dalloc(c, &a.att2, nl * 8 * d));
-  TRY(dalloc(c, &a.pool, 2 * 8 * d)); TRY(dalloc(c, &a.mid, nl * 8 * c->ff));
-  TRY(dalloc(c, &a.newK, (size_t)D.H * 16 * 32)); TRY(dalloc(c, &a.newV, (size_t)D.H * 16 * 32));
-  TRY(dalloc(c, &a.partS, (size_t)D.H * PK_MAXSPLIT * PK_PART)); TRY(dalloc(c, &a.partX, (size_t)D.H * PK_MAXSPLIT * PK_PART));
-  TRY(dalloc(c, &a.w2part, (d / 16) * 3 * 256));
+  // rows per exchange region: one group of 16, or two when the block is longer than 16 tokens
+  a.RS = D.Bm > 16 ? 32 : 16;
+  const size_t RS = a.RS, RH = RS / 2, RG = RS / 16;
+  TRY(dalloc(c, &a.hA, (nl + 1) * RS * d)); TRY(dalloc(c, &a.hB, nl * RS * d)); TRY(dalloc(c, &a.hC, nl * RS * d));
+  for (int i = 0; i < 4; i++) TRY(dalloc(c, &a.hT[i], RS * d));
+  TRY(dalloc(c, &a.xA, (nl + 1) * RH * d)); TRY(dalloc(c, &a.xB, nl * RH * d)); TRY(dalloc(c, &a.xC, nl * RH * d));
+  TRY(dalloc(c, &a.q, RH * d)); TRY(dalloc(c, &a.att, nl * RH * d)); TRY(dalloc(c, &a.q2, RH * d));
+  TRY(dalloc(c, &a.att2, nl * RH * d));
+  TRY(dalloc(c, &a.pool, 2 * 8 * d)); TRY(dalloc(c, &a.mid, nl * RH * c->ff));
+  TRY(dalloc(c, &a.newK, (size_t)D.H * RS * 32)); TRY(dalloc(c, &a.newV, (size_t)D.H * RS * 32));
+  TRY(dalloc(c, &a.partS, (size_t)D.H * PK_MAXSPLIT * RG * PK_PART)); TRY(dalloc(c, &a.partX, (size_t)D.H * PK_MAXSPLIT * RG * PK_PART));
+  TRY(dalloc(c, &a.w2part, (d / 16) * RG * 3 * 256));
   TRY(dalloc(c, &a.abort_word, 16));
   if (hipMemset(a.abort_word + 1, 0xFF, 4) != hipSuccess) return fail(c, FM_EHIP, "hipMemset failed");
   a.run_flag = c->st.alive;
@@ -622,7 +626,9 @@ int build_persist(fm_ctx* c) {
   int dev = 0, cus = 0, per_cu = 0;
   c->pk_lds = 0;   // the kernel uses static LDS only
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist, 256, c->pk_lds) != hipSuccess || (long)cus * per_cu < PK_NWG) {
+      (a.RS == 32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist<2>, 256, c->pk_lds)
+                  : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist<1>, 256, c->pk_lds)) != hipSuccess ||
+      (long)cus * per_cu < PK_NWG) {
     (void)hipGetLastError();
     c->persist = false;   // fall back to the per-launch path
   }
@@ -766,7 +772,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   {
     const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
     const char* env = getenv("FM_PERSIST");
-    c->persist = c->bf16 && D.S == 1 && D.Bm <= 16 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
+    c->persist = c->bf16 && D.S == 1 && D.Bm <= 32 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
                  !(env && env[0] == '0');
   }
   int rc = build_params(c);

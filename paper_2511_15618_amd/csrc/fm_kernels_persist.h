@@ -1,5 +1,6 @@
-// Persistent verify kernel for the half-precision path with at most 16 rows per hourglass level
-// (one sequence, block <= 16): the whole backbone forward of one verify pass is ONE launch.
+// Persistent verify kernel for the half-precision path, one sequence, blocks of up to 32 tokens: the whole backbone
+// forward of one verify pass is ONE launch.  Rows are handled in groups of 16 (one MFMA row tile): blocks of up to
+// 16 tokens have one group per level, longer ones two at the coordinate level (template parameter QT).
 //
 // Why: at batch 1 a transformer block is ~10 dependent operations of 0.3-1 us of HBM time each; as
 // separate launches every one costs ~4 us.  Here 256 resident workgroups walk a static schedule of
@@ -56,7 +57,8 @@ struct PkArgs {
   Dims D;
   int ff;
   float eps;
-  int R[3];                 // row slots per level (<= 16)
+  int R[3];                 // row slots per level (<= RS)
+  int RS;                   // rows the exchange buffers hold per region: 16, or 32 when the coordinate level has two row groups
   int capb[3], capbM;       // cache capacity in 32-key blocks per level / of the condition memory
   int nsplit[3], nsplitM;   // launch-time split counts (fixed partition of the key axis)
   int win[3];               // sliding window per level (0 = none); the self-attention caches are then rings of capb blocks
@@ -70,16 +72,16 @@ struct PkArgs {
   const float* gf;
   float* logits;
   // exchange buffers (u64 = payload | tag << 32)
-  u64 *hA, *hB, *hC;        // [layers + 1][16][d]: one region per layer, written once per launch
-  u64* hT[4];               // outputs of cpre, vpre, face, vpost  [16][d]
-  u64 *xA, *xB, *xC;        // [layers (+ 1)][16][d/2]: the same activations as hA, hB, hC rounded to half pairs, for the GEMMs
-  u64 *q, *q2;              // [16][d/2] rotated queries of the self- / cross-attention (half pairs)
-  u64 *att, *att2;          // [layers][16][d/2] attention outputs
-  u64* pool;                // [2][16][d/2] pooled groups before the two shortening projections
-  u64* mid;                 // [layers][16][ff/2]
-  u64 *newK, *newV;         // [H][16][32]
-  u64 *partS, *partX;       // [H][PK_MAXSPLIT][PK_PART]
-  u64* w2part;              // [d/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
+  u64 *hA, *hB, *hC;        // [layers + 1][RS][d]: one region per layer, written once per launch
+  u64* hT[4];               // outputs of cpre, vpre, face, vpost  [RS][d]
+  u64 *xA, *xB, *xC;        // [layers (+ 1)][RS][d/2]: the same activations as hA, hB, hC rounded to half pairs, for the GEMMs
+  u64 *q, *q2;              // [RS][d/2] rotated queries of the self- / cross-attention (half pairs)
+  u64 *att, *att2;          // [layers][RS][d/2] attention outputs
+  u64* pool;                // [2][16][d/2] pooled groups before the two shortening projections (coarse rows: at most 9)
+  u64* mid;                 // [layers][RS][ff/2]
+  u64 *newK, *newV;         // [H][RS][32]
+  u64 *partS, *partX;       // [H][PK_MAXSPLIT][RS/16][PK_PART]
+  u64* w2part;              // [d/16][RS/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
   unsigned epoch;
   u64 timeout_ticks;        // bound of every wait (100 MHz wall clock)
   unsigned test_skew;       // test hook: added to the tag the embedding publishes, so that nothing downstream ever arrives
@@ -90,11 +92,12 @@ struct PkArgs {
   u64* prof;                // optional [1 + stages]: earliest start, latest completion per stage (wall clock ticks)
 };
 
+template <int QT>
 struct PkShared {
   f32x4 red[4][64];
   float ssq[4][16];
-  float lo[4][16][65];
-  float lm[4][16], ll[4][16];
+  float lo[4][16 * QT][65];
+  float lm[4][16 * QT], ll[4][16 * QT];
 };
 
 __device__ __forceinline__ u64 pk_ld(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -171,15 +174,18 @@ __device__ __forceinline__ bool pk_fetch(unsigned (&out)[N], int n, bool active,
 // A level transition must not publish anything before the stack below it has finished with the shared
 // exchange buffers, even when its own rows are inactive or only need data of earlier passes: it first
 // waits for row 0 of the stack output from EVERY tile (a tile stores only after its last read).
-__device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, unsigned tag, int stage);
+__device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, unsigned tag, int stage, int rows);
 
 #define PK_TAG(a, l) ((a).epoch * 64u + (unsigned)(l) + 1u)
 
-__device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, unsigned tag, int stage) {
+__device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, unsigned tag, int stage, int rows) {
   unsigned s4[4];
   const int d = a.D.d;
   const int n = (d - (int)threadIdx.x + 255) / 256;     // columns threadIdx.x, +256, ... below d (d <= 1024)
-  return pk_fetch<4>(s4, n, n > 0, tag, [&](int i) { return hT + threadIdx.x + 256 * i; }, a, stage);
+  bool ok = pk_fetch<4>(s4, n, n > 0, tag, [&](int i) { return hT + threadIdx.x + 256 * i; }, a, stage);
+  // a second row group is written by units of its own: their first row (16) as well
+  if (rows > 16) ok = pk_fetch<4>(s4, n, n > 0, tag, [&](int i) { return hT + 16l * d + threadIdx.x + 256 * i; }, a, stage) && ok;
+  return ok;
 }
 
 // phase timing inside the units of one chosen stage (debug): latest time each phase was reached
@@ -194,8 +200,8 @@ __device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, un
 // tagged half pairs, i.e. two 16-byte agent-scope loads.  No LDS staging, no barrier before the multiplication;
 // the tags are checked per lane and the whole set is re-read until complete.
 // ------------------------------------------------------------------------------------------
-template <int ASRC>
-__device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, PkShared& sh, pk_cw_t Wt, int KT, const u64* A,
+template <int ASRC, class SH>
+__device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, SH& sh, pk_cw_t Wt, int KT, const u64* A,
                                              unsigned tagA, pk_cf_t gain, int R, f32x4& result, int stage,
                                              int lda = 0) {
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
@@ -389,8 +395,9 @@ __device__ __forceinline__ void pk_qkv_prefetch(int nt, int d, int R, const int*
     pre.t[i] = part < 2 ? cs[(long)rr * 32 + qd * 8 + (col & 7)] : float2{1.f, 0.f};
   }
 }
+template <int QT>
 __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, const f32x4& c, int nt, unsigned tag, int R,
-                                           const PkQkvPre& pre, int capb) {
+                                           const PkQkvPre& pre, int capb, int row0) {
   const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
   const int d = a.D.d;
   const int part = (nt * 16) / d, cp = (nt * 16) % d;
@@ -413,9 +420,9 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
     const int p = pre.p[i];
     if (r < R) {
       if (part == 0) {
-        if ((lane & 1) == 0) pk_st(a.q + (long)r * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
+        if ((lane & 1) == 0) pk_st(a.q + (long)(row0 + r) * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
       } else {
-        u64* nb = (part == 1 ? a.newK : a.newV) + ((long)hh * 16 + r) * 32;
+        u64* nb = (part == 1 ? a.newK : a.newV) + ((long)hh * (QT * 16) + row0 + r) * 32;
         if ((lane & 1) == 0) pk_st(nb + (dim >> 1), pk_pack(v, w), tag);
         if (p >= 0) {
           const int ps = p % (capb * 32);      // the cache is a ring when a window is set
@@ -429,19 +436,19 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 }
 
 // ------------------------------------------------------------------------------------------
-// Attention over one key range of one head (flash-decoding split), same arithmetic as k_attn_mfma<1>.
-// Keys of this pass (positions >= P0) are taken from the exchange buffers, older keys from the cache.
+// Attention over one key range of one head (flash-decoding split), same arithmetic as k_attn_mfma<QT>: QT tiles of
+// 16 query rows share every K/V block that is loaded.  Keys of this pass (positions >= P0) are taken from the
+// exchange buffers, older keys from the cache.  lim[t]: last key the lane's row of tile t may see (-1: unused slot).
+// Partial results: tile t of (head, split) at part + t * PK_PART.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, const u64* qbuf, int lim, int maxlim, int R,
+template <int QT, class SH>
+__device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64* qbuf, const int (&lim)[QT], int maxlim, int R,
                                              pk_cw_t Kc, pk_cw_t Vc, int capb, int nsplit_cfg, int hh, int split,
                                              bool overlay, int P0, u64* part, unsigned tag, int stage, int window) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int g = lane >> 4, ql = lane & 15;
   const int d = a.D.d;
   const float kScale = 0.125f * 1.4426950408889634f;
-  const bool on = ql < R;
-  // lim: last key this lane's query row may see (-1 for an unused row slot), maxlim: the largest of the block;
-  // both are the same for every layer of a level and come from the caller
   // With a window the cache is a ring of capb blocks (a multiple of four): position p lives in slot p mod (32 capb);
   // seen from the newest visible position, slot j holds lapbase + j if that is <= maxlim, else the position one
   // lap earlier.  Without a window lapbase = 0 and nothing wraps.
@@ -449,7 +456,13 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
   const int ringn = capb * 32;
   const int lapbase = max(maxlim, 0) / ringn * ringn;
   auto held = [&](int slot) { const int k = lapbase + slot; return k > maxlim ? k - ringn : k; };
-  const int first = window > 0 ? max(lim - window + 1, 0) : 0;
+  bool on[QT];
+  int first[QT];
+#pragma unroll
+  for (int t = 0; t < QT; t++) {
+    on[t] = t * 16 + ql < R;
+    first[t] = window > 0 ? max(lim[t] - window + 1, 0) : 0;
+  }
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
   if (split >= nsplit) return true;      // nothing visible in this range: the merge knows the same count
@@ -480,62 +493,73 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
     for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
   }
   // q of this lane: dims g*8..+8 and 32 + g*8..+8 of the head = two runs of four tagged elements = four 16-byte
-  // agent-scope loads, simply repeated until every tag matches (small enough to poll with the data itself)
+  // agent-scope loads per query tile, simply repeated until every tag matches (small enough to poll with the data itself)
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  unsigned qraw[56];
-  const u64* qp = qbuf + (long)(on ? ql : 0) * (d >> 1) + ((hh * 64 + g * 8) >> 1);
+  f16x8 qf0[QT], qf1[QT];
   bool ok = true;
   {
+    const u64* qp[QT];
+#pragma unroll
+    for (int t = 0; t < QT; t++) qp[t] = qbuf + (long)(on[t] ? t * 16 + ql : 0) * (d >> 1) + ((hh * 64 + g * 8) >> 1);
     const u64 t0 = wall_clock64();
     int it = 0;
-    u32x4 qv[4];
+    u32x4 qv[QT][4];
     while (true) {
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        const u64* p = qp + (j >> 1) * 16 + (j & 1) * 2;
-        asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(qv[j]) : "v"(p) : "memory");
-      }
+      for (int t = 0; t < QT; t++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          const u64* p = qp[t] + (j >> 1) * 16 + (j & 1) * 2;
+          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(qv[t][j]) : "v"(p) : "memory");
+        }
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       bool okq = true;
 #pragma unroll
-      for (int j = 0; j < 4; j++) {
-        asm volatile("" : "+v"(qv[j]));
-        okq = okq && qv[j][1] == tag && qv[j][3] == tag;
-      }
+      for (int t = 0; t < QT; t++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+          asm volatile("" : "+v"(qv[t][j]));
+          okq = okq && qv[t][j][1] == tag && qv[t][j][3] == tag;
+        }
       if (__all(okq)) break;
       if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { ok = false; break; }
       __builtin_amdgcn_s_sleep(2);
     }
 #pragma unroll
-    for (int j = 0; j < 4; j++) { qraw[2 * j] = qv[j][0]; qraw[2 * j + 1] = qv[j][2]; }
+    for (int t = 0; t < QT; t++) {
+      u32x4 lo4 = u32x4{qv[t][0][0], qv[t][0][2], qv[t][1][0], qv[t][1][2]};
+      u32x4 hi4 = u32x4{qv[t][2][0], qv[t][2][2], qv[t][3][0], qv[t][3][2]};
+      if (!on[t]) { lo4 = u32x4{0u, 0u, 0u, 0u}; hi4 = lo4; }
+      qf0[t] = __builtin_bit_cast(f16x8, lo4);
+      qf1[t] = __builtin_bit_cast(f16x8, hi4);
+    }
   }
   // rows written by this pass that fall into one of this wave's blocks (at most one block)
+  unsigned raw[48];
   if (bov >= 0) {
-    ok = pk_fetch<48>(*reinterpret_cast<unsigned(*)[48]>(qraw + 8), 48, true, tag, [&](int i) {
+    ok = pk_fetch<48>(raw, 48, true, tag, [&](int i) {
       if (i < 16) {
         const int f = i >> 2;
         int nr = held(bov * 32 + (f >> 1) * 16 + (lane & 15)) - P0;
         nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
-        return (const u64*)(a.newK + ((long)hh * 16 + nr) * 32 + (((f & 1) * 32 + g * 8) >> 1) + (i & 3));
+        return (const u64*)(a.newK + ((long)hh * (QT * 16) + nr) * 32 + (((f & 1) * 32 + g * 8) >> 1) + (i & 3));
       }
       const int j = (i - 16) & 7, dt = (i - 16) >> 3;
       int nr = held(bov * 32 + (j >> 2) * 16 + g * 4 + (j & 3)) - P0;
       nr = nr < 0 ? 0 : (nr >= R ? R - 1 : nr);
-      return (const u64*)(a.newV + ((long)hh * 16 + nr) * 32 + ((dt * 16 + (lane & 15)) >> 1));
+      return (const u64*)(a.newV + ((long)hh * (QT * 16) + nr) * 32 + ((dt * 16 + (lane & 15)) >> 1));
     }, a, stage) && ok;
   }
-  if (!on) {
-#pragma unroll
-    for (int i = 0; i < 8; i++) qraw[i] = 0u;
-  }
-  const unsigned* raw = qraw + 8;
-  const f16x8 qf0 = __builtin_bit_cast(f16x8, (u32x4{qraw[0], qraw[1], qraw[2], qraw[3]}));
-  const f16x8 qf1 = __builtin_bit_cast(f16x8, (u32x4{qraw[4], qraw[5], qraw[6], qraw[7]}));
 
-  float mrun = -INFINITY, lrun = 0.f;
-  f32x4 o[4];
+  float mrun[QT], lrun[QT];
+  f32x4 o[QT][4];
 #pragma unroll
-  for (int dt = 0; dt < 4; dt++) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < QT; t++) {
+    mrun[t] = -INFINITY;
+    lrun[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 4; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   for (int b = b0 + wave; b < b1; b += 4) {
     // the next block of this wave is requested before the current one is multiplied
     f16x8 kn[4], vn[4];
@@ -567,61 +591,67 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
         }
       }
     }
-    f32x4 sT[2];
 #pragma unroll
-    for (int hb = 0; hb < 2; hb++) {
-      f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-      z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2], qf0, z, 0, 0, 0);
-      z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2 + 1], qf1, z, 0, 0, 0);
-      sT[hb] = z;
-    }
-    float mx = -INFINITY;
+    for (int t = 0; t < QT; t++) {
+      f32x4 sT[2];
 #pragma unroll
-    for (int hb = 0; hb < 2; hb++)
-#pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const int key = held(b * 32 + hb * 16 + g * 4 + i);      // absolute position
-        const float v = (key <= lim && key >= first) ? sT[hb][i] * kScale : -INFINITY;
-        sT[hb][i] = v;
-        mx = fmaxf(mx, v);
+      for (int hb = 0; hb < 2; hb++) {
+        f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
+        z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2], qf0[t], z, 0, 0, 0);
+        z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2 + 1], qf1[t], z, 0, 0, 0);
+        sT[hb] = z;
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mnew = fmaxf(mrun, mx);
-    const float msafe = mnew == -INFINITY ? 0.f : mnew;
-    const float alpha = __builtin_amdgcn_exp2f(mrun - msafe);
-    mrun = mnew;
-    f16x8 pf;
-    float psum = 0.f;
+      float mx = -INFINITY;
 #pragma unroll
-    for (int hb = 0; hb < 2; hb++)
+      for (int hb = 0; hb < 2; hb++)
 #pragma unroll
-      for (int i = 0; i < 4; i++) {
-        const float p = __builtin_amdgcn_exp2f(sT[hb][i] - msafe);
-        psum += p;
-        pf[hb * 4 + i] = (f16_t)p;
+        for (int i = 0; i < 4; i++) {
+          const int key = held(b * 32 + hb * 16 + g * 4 + i);      // absolute position
+          const float v = (key <= lim[t] && key >= first[t]) ? sT[hb][i] * kScale : -INFINITY;
+          sT[hb][i] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(mrun[t], mx);
+      const float msafe = mnew == -INFINITY ? 0.f : mnew;
+      const float alpha = __builtin_amdgcn_exp2f(mrun[t] - msafe);
+      mrun[t] = mnew;
+      f16x8 pf;
+      float psum = 0.f;
+#pragma unroll
+      for (int hb = 0; hb < 2; hb++)
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+          const float p = __builtin_amdgcn_exp2f(sT[hb][i] - msafe);
+          psum += p;
+          pf[hb * 4 + i] = (f16_t)p;
+        }
+      lrun[t] = lrun[t] * alpha + psum;
+#pragma unroll
+      for (int dt = 0; dt < 4; dt++) {
+        o[t][dt] *= alpha;
+        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[t][dt], 0, 0, 0);
       }
-    lrun = lrun * alpha + psum;
-#pragma unroll
-    for (int dt = 0; dt < 4; dt++) {
-      o[dt] *= alpha;
-      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[dt], 0, 0, 0);
     }
     if (b + 4 < b1) {
 #pragma unroll
       for (int f = 0; f < 4; f++) { kf[f] = kn[f]; vf[f] = vn[f]; }
     }
   }
-  float l = lrun;
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
-  if (g == 0) { sh.lm[wave][ql] = mrun; sh.ll[wave][ql] = l; }
 #pragma unroll
-  for (int dt = 0; dt < 4; dt++)
+  for (int t = 0; t < QT; t++) {
+    float l = lrun[t];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (g == 0) { sh.lm[wave][t * 16 + ql] = mrun[t]; sh.ll[wave][t * 16 + ql] = l; }
 #pragma unroll
-    for (int i = 0; i < 4; i++) sh.lo[wave][ql][dt * 16 + g * 4 + i] = o[dt][i];
+    for (int dt = 0; dt < 4; dt++)
+#pragma unroll
+      for (int i = 0; i < 4; i++) sh.lo[wave][t * 16 + ql][dt * 16 + g * 4 + i] = o[t][dt][i];
+  }
   if (__syncthreads_or(!ok)) return false;
-  for (int e = threadIdx.x; e < 16 * 64; e += 256) {
+  for (int e = threadIdx.x; e < QT * 16 * 64; e += 256) {
     const int qi = e >> 6, dim = e & 63;
     const float M = fmaxf(fmaxf(sh.lm[0][qi], sh.lm[1][qi]), fmaxf(sh.lm[2][qi], sh.lm[3][qi]));
     const float Ms = M == -INFINITY ? 0.f : M;
@@ -633,8 +663,10 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
       den += sh.ll[w][qi] * f;
     }
     if (qi < R) {
-      pk_stf(part + e, num, tag);
-      if (dim == 0) { pk_stf(part + 16 * 64 + qi, M, tag); pk_stf(part + 16 * 64 + 16 + qi, den, tag); }
+      u64* pt = part + (long)(qi >> 4) * PK_PART;      // the row's tile
+      const int ql16 = qi & 15;
+      pk_stf(pt + ql16 * 64 + dim, num, tag);
+      if (dim == 0) { pk_stf(pt + 16 * 64 + ql16, M, tag); pk_stf(pt + 16 * 64 + 16 + ql16, den, tag); }
     }
   }
   __syncthreads();
@@ -643,13 +675,17 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, PkShared& sh, cons
 
 // merge of the splits of one head (one quarter of its dims per unit) into the half-pair attention output;
 // thread = (row, dim), splits summed in a fixed order
-__device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, int maxlim, int R, int capb, int nsplit_cfg,
+// (rg: the row group, R: its rows; the split count comes from the largest limit of the whole level, as in the units
+// that wrote the partial results)
+template <int QT>
+__device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, int maxlim, int R, int rg, int capb, int nsplit_cfg,
                                               int hh, int dq, const u64* parts, u64* att, unsigned tag, int stage) {
   const int d = a.D.d;
   const int nblk = min((maxlim + 32) >> 5, capb);
   const int per = (capb + nsplit_cfg - 1) / nsplit_cfg;
   const int nsplit = max(1, (nblk + per - 1) / per);
-  const u64* base = parts + (long)hh * PK_MAXSPLIT * PK_PART;
+  const long rec = (long)QT * PK_PART;                 // one (head, split) record: a tile per row group
+  const u64* base = parts + (long)hh * PK_MAXSPLIT * rec + (long)rg * PK_PART;
   const int qi = threadIdx.x >> 4, dim = dq * 16 + (threadIdx.x & 15);
   const bool on = qi < R;
   bool ok = true;
@@ -659,7 +695,7 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, int
     unsigned raw[48];
     const int n = min(16, nsplit - k0);
     ok = pk_fetch<48>(raw, 3 * n, on, tag, [&](int i) {
-      const u64* p = base + (long)(k0 + i / 3) * PK_PART;
+      const u64* p = base + (long)(k0 + i / 3) * rec;
       const int w = i % 3;
       return w == 0 ? p + 16 * 64 + qi : w == 1 ? p + 16 * 64 + 16 + qi : p + qi * 64 + dim;
     }, a, stage) && ok;
@@ -682,7 +718,7 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, int
   }
   const float v = den > 0.f ? num / den : 0.f;
   const float w = __shfl_xor(v, 1, 64);
-  if (on && (dim & 1) == 0) pk_st(att + (long)qi * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
+  if (on && (dim & 1) == 0) pk_st(att + (long)(rg * 16 + qi) * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
   if (__syncthreads_or(!ok)) return false;
   return true;
 }
@@ -699,9 +735,11 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, PkShared& sh, int
     stage++;                                                                                        \
   } while (0)
 
+template <int QT>
 __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   if (*a.run_flag == 0) return;
-  __shared__ PkShared sh;
+  __shared__ PkShared<QT> sh;
+  const int RS = QT * 16, RH = QT * 8;     // rows of an exchange region (= a.RS), and half of it: the row count of a half-pair region in units of d
   const int d = a.D.d, H = a.D.H, ff = a.ff;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   unsigned rr = 0;     // round-robin origin of the current stage (same in every workgroup)
@@ -711,14 +749,21 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
 
   // Per level and the same for all of its layers: the last visible key of this lane's query row in the
   // self-attention (its own position) and in the cross-attention, the block maxima, the first position of the pass.
-  int limS[3], limX[3], maxS[3], maxX[3], firstP[3];
+  // (QT query tiles of 16 rows: tile t holds rows t*16 .. t*16+15 of the level)
+  int limS[3][QT], limX[3][QT], maxS[3], maxX[3], firstP[3];
 #pragma unroll
   for (int lv = 0; lv < 3; lv++) {
     const int ql = threadIdx.x & 15;
-    const bool onl = ql < a.R[lv];
-    limS[lv] = onl ? a.pos[lv][ql] : -1;
-    limX[lv] = onl ? a.limx[lv][ql] : -1;
-    int ms = limS[lv], mx = limX[lv], fp = limS[lv] >= 0 ? limS[lv] : 0x3fffffff;
+    int ms = -1, mx = -1, fp = 0x3fffffff;
+#pragma unroll
+    for (int t = 0; t < QT; t++) {
+      const bool onl = t * 16 + ql < a.R[lv];
+      limS[lv][t] = onl ? a.pos[lv][t * 16 + ql] : -1;
+      limX[lv][t] = onl ? a.limx[lv][t * 16 + ql] : -1;
+      ms = max(ms, limS[lv][t]);
+      mx = max(mx, limX[lv][t]);
+      if (limS[lv][t] >= 0) fp = min(fp, limS[lv][t]);
+    }
 #pragma unroll
     for (int o = 1; o < 16; o <<= 1) {
       ms = max(ms, __shfl_xor(ms, o, 64));
@@ -751,118 +796,132 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       const int* pos = a.pos[lev];
       const int capb = a.capb[lev];
       // this layer's own regions of the exchange buffers
-      u64* const hA_l = a.hA + (long)l * 16 * d;
-      u64* const hA_n = a.hA + (long)(l + 1) * 16 * d;
-      u64* const hB_l = a.hB + (long)l * 16 * d;
-      u64* const hC_l = a.hC + (long)l * 16 * d;
-      u64* const xA_l = a.xA + (long)l * 8 * d;
-      u64* const xA_n = a.xA + (long)(l + 1) * 8 * d;
-      u64* const xB_l = a.xB + (long)l * 8 * d;
-      u64* const xC_l = a.xC + (long)l * 8 * d;
-      u64* const att_l = a.att + (long)l * 8 * d;
-      u64* const att2_l = a.att2 + (long)l * 8 * d;
-      u64* const mid_l = a.mid + (long)l * 8 * ff;
+      u64* const hA_l = a.hA + (long)l * RS * d;
+      u64* const hA_n = a.hA + (long)(l + 1) * RS * d;
+      u64* const hB_l = a.hB + (long)l * RS * d;
+      u64* const hC_l = a.hC + (long)l * RS * d;
+      u64* const xA_l = a.xA + (long)l * RH * d;
+      u64* const xA_n = a.xA + (long)(l + 1) * RH * d;
+      u64* const xB_l = a.xB + (long)l * RH * d;
+      u64* const xC_l = a.xC + (long)l * RH * d;
+      u64* const att_l = a.att + (long)l * RH * d;
+      u64* const att2_l = a.att2 + (long)l * RH * d;
+      u64* const mid_l = a.mid + (long)l * RH * ff;
+      // GEMM and merge units take the rows in groups of 16: unit = (tile, row group); a group's rows are contiguous
+      // in every exchange buffer, so a unit is the one-group code on offset pointers
+      const int RG = QT == 1 ? 1 : (R + 15) >> 4;      // a compile-time 1 for blocks of up to 16 tokens
+      const long hd = d >> 1;
       // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append)
-      PK_MINE(3 * d / 16) {
+      PK_MINE(3 * d / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
         PkQkvPre pre;
-        if (wave == 0) pk_qkv_prefetch(u, d, R, pos, a.cs[lev], pre);
-        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)u * (d / 32) * 512, d / 32, xA_l, tag, L.g1, R, c, stage)) return;
-        if (wave == 0) pk_epi_qkv(a, L, c, u, tag, R, pre, capb);
+        if (wave == 0) pk_qkv_prefetch(nt, d, Rl, pos + row0, a.cs[lev] + (long)row0 * 32, pre);
+        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)nt * (d / 32) * 512, d / 32, xA_l + row0 * hd, tag, L.g1, Rl, c, stage)) return;
+        if (wave == 0) pk_epi_qkv<QT>(a, L, c, nt, tag, Rl, pre, capb, row0);
         __syncthreads();
       }
-      PK_NEXT(3 * d / 16);
+      PK_NEXT(3 * d / 16 * RG);
       // ---- self-attention splits
       {
         const int ns = a.nsplit[lev];
         const int P0 = firstP[lev];
         PK_MINE(H * ns) {
           const int hh = u / ns, sp = u % ns;
-          if (!pk_attn_unit(a, sh, a.q, limS[lev], maxS[lev], R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
-                            a.partS + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage, a.win[lev])) return;
+          if (!pk_attn_unit<QT>(a, sh, a.q, limS[lev], maxS[lev], R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
+                                a.partS + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, a.win[lev])) return;
         }
         PK_NEXT(H * ns);
-        PK_MINE(4 * H) {
-          if (!pk_merge_unit(a, sh, maxS[lev], R, capb, ns, u >> 2, u & 3, a.partS, att_l, tag, stage)) return;
+        PK_MINE(4 * H * RG) {
+          const int v = u / RG, rg = u % RG;
+          if (!pk_merge_unit<QT>(a, maxS[lev], min(16, R - rg * 16), rg, capb, ns, v >> 2, v & 3, a.partS, att_l, tag, stage)) return;
         }
-        PK_NEXT(4 * H);
+        PK_NEXT(4 * H * RG);
       }
       // ---- Wo + residual -> hB (tap: the layer input is what the draft heads of this level start from)
-      PK_MINE(d / 16) {
+      PK_MINE(d / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
         unsigned old[4];
         int prow[4];
         bool okr = true;
-        if (wave == 0) okr = pk_res_prefetch(a, u, hA_l, tag, R, pos, old, prow, stage);
-        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)u * (d / 32) * 512, d / 32, att_l, tag, nullptr, R, c, stage)) return;
+        if (wave == 0) okr = pk_res_prefetch(a, nt, hA_l + (long)row0 * d, tag, Rl, pos + row0, old, prow, stage);
+        if (!pk_gemm_tile<0>(a, sh, L.wo + (long)nt * (d / 32) * 512, d / 32, att_l + row0 * hd, tag, nullptr, Rl, c, stage)) return;
         if (wave == 0 && okr)
-          pk_epi_residual(a, c, u, old, hB_l, xB_l, tag, R, prow, L.tap ? a.tap[lev] : nullptr, nullptr, lev == 0 ? 32 : lev == 1 ? 16 : 8);
+          pk_epi_residual(a, c, nt, old, hB_l + (long)row0 * d, xB_l + row0 * hd, tag, Rl, prow, L.tap ? a.tap[lev] : nullptr, nullptr,
+                          lev == 0 ? 32 : lev == 1 ? 16 : 8);
         if (__syncthreads_or(!okr)) return;
       }
-      PK_NEXT(d / 16);
+      PK_NEXT(d / 16 * RG);
       // ---- cross-attention query (norm2 on the fly)
-      PK_MINE(d / 16) {
+      PK_MINE(d / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)u * (d / 32) * 512, d / 32, xB_l, tag, L.g2, R, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, u, a.q2, d >> 1, tag, R, false);
+        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)nt * (d / 32) * 512, d / 32, xB_l + row0 * hd, tag, L.g2, Rl, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, nt, a.q2 + row0 * hd, d >> 1, tag, Rl, false);
         __syncthreads();
       }
-      PK_NEXT(d / 16);
+      PK_NEXT(d / 16 * RG);
       // ---- cross-attention over the condition memory
       {
         const int ns = a.nsplitM;
         PK_MINE(H * ns) {
           const int hh = u / ns, sp = u % ns;
-          if (!pk_attn_unit(a, sh, a.q2, limX[lev], maxX[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
-                            a.partX + ((long)hh * PK_MAXSPLIT + sp) * PK_PART, tag, stage, 0)) return;
+          if (!pk_attn_unit<QT>(a, sh, a.q2, limX[lev], maxX[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
+                                a.partX + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, 0)) return;
         }
         PK_NEXT(H * ns);
-        PK_MINE(4 * H) {
-          if (!pk_merge_unit(a, sh, maxX[lev], R, a.capbM, ns, u >> 2, u & 3, a.partX, att2_l, tag, stage)) return;
+        PK_MINE(4 * H * RG) {
+          const int v = u / RG, rg = u % RG;
+          if (!pk_merge_unit<QT>(a, maxX[lev], min(16, R - rg * 16), rg, a.capbM, ns, v >> 2, v & 3, a.partX, att2_l, tag, stage)) return;
         }
-        PK_NEXT(4 * H);
+        PK_NEXT(4 * H * RG);
       }
       // ---- cross output projection + residual -> hC
-      PK_MINE(d / 16) {
+      PK_MINE(d / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
         unsigned old[4];
         int prow[4];
         bool okr = true;
-        if (wave == 0) okr = pk_res_prefetch(a, u, hB_l, tag, R, pos, old, prow, stage);
-        if (!pk_gemm_tile<0>(a, sh, L.co + (long)u * (d / 32) * 512, d / 32, att2_l, tag, nullptr, R, c, stage)) return;
-        if (wave == 0 && okr) pk_epi_residual(a, c, u, old, hC_l, xC_l, tag, R, prow, nullptr, nullptr, 8);
+        if (wave == 0) okr = pk_res_prefetch(a, nt, hB_l + (long)row0 * d, tag, Rl, pos + row0, old, prow, stage);
+        if (!pk_gemm_tile<0>(a, sh, L.co + (long)nt * (d / 32) * 512, d / 32, att2_l + row0 * hd, tag, nullptr, Rl, c, stage)) return;
+        if (wave == 0 && okr) pk_epi_residual(a, c, nt, old, hC_l + (long)row0 * d, xC_l + row0 * hd, tag, Rl, prow, nullptr, nullptr, 8);
         if (__syncthreads_or(!okr)) return;
       }
-      PK_NEXT(d / 16);
+      PK_NEXT(d / 16 * RG);
       // ---- FFN up (norm3 on the fly, GELU)
-      PK_MINE(ff / 16) {
+      PK_MINE(ff / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
-        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)u * (d / 32) * 512, d / 32, xC_l, tag, L.g3, R, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, u, mid_l, ff >> 1, tag, R, true);
+        if (!pk_gemm_tile<1>(a, sh, L.w1 + (long)nt * (d / 32) * 512, d / 32, xC_l + row0 * hd, tag, L.g3, Rl, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, nt, mid_l + (long)row0 * (ff >> 1), ff >> 1, tag, Rl, true);
         __syncthreads();
       }
-      PK_NEXT(ff / 16);
+      PK_NEXT(ff / 16 * RG);
       // ---- FFN down + residual -> next layer input, or the stack output (+ its ring for later passes).
       // K = ff is four times longer than in the other GEMMs, so a tile is computed by four units, one per
       // K-quarter; quarters 1..3 hand their partial tile to quarter 0, which adds them in a fixed order.
-      PK_MINE(4 * (d / 16)) {
-        const int nt = u >> 2, kq = u & 3;
+      PK_MINE(4 * (d / 16) * RG) {
+        const int uv = u / RG, rg = u % RG, row0 = rg * 16, Rl = min(16, R - row0);
+        const int nt = uv >> 2, kq = uv & 3;
         const int KTq = ff / 128;                       // fragments of one K-quarter
+        u64* const w2p = a.w2part + ((long)nt * RG + rg) * 3 * 256;
         f32x4 c;
         unsigned old[4];
         int prow[4];
         bool okr = true;
-        if (wave == 0 && kq == 0) okr = pk_res_prefetch(a, nt, hC_l, tag, R, pos, old, prow, stage);
-        if (!pk_gemm_tile<0>(a, sh, L.w2 + ((long)nt * (ff / 32) + (long)kq * KTq) * 512, KTq, mid_l + (long)kq * (ff / 8), tag,
-                             nullptr, R, c, stage, ff >> 1)) return;
+        if (wave == 0 && kq == 0) okr = pk_res_prefetch(a, nt, hC_l + (long)row0 * d, tag, Rl, pos + row0, old, prow, stage);
+        if (!pk_gemm_tile<0>(a, sh, L.w2 + ((long)nt * (ff / 32) + (long)kq * KTq) * 512, KTq,
+                             mid_l + (long)row0 * (ff >> 1) + (long)kq * (ff / 8), tag, nullptr, Rl, c, stage, ff >> 1)) return;
         if (wave == 0) {
           const int lane = threadIdx.x & 63;
           if (kq > 0) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) pk_stf(a.w2part + ((long)nt * 3 + (kq - 1)) * 256 + i * 64 + lane, c[i], tag);
+            for (int i = 0; i < 4; i++) pk_stf(w2p + (long)(kq - 1) * 256 + i * 64 + lane, c[i], tag);
           } else {
             unsigned pr[12];
-            okr = pk_fetch<12>(pr, 12, true, tag, [&](int i) { return a.w2part + ((long)nt * 3 + (i >> 2)) * 256 + (i & 3) * 64 + lane; },
+            okr = pk_fetch<12>(pr, 12, true, tag, [&](int i) { return w2p + (long)(i >> 2) * 256 + (i & 3) * 64 + lane; },
                                a, stage) && okr;
             if (okr) {
 #pragma unroll
@@ -879,13 +938,14 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
                 ring = st == 0 ? a.ring_hc : st == 1 ? a.ring_hv : st == 2 ? a.ring_yf : a.ring_yv;
                 rs = st == 0 ? 32 : st == 2 ? 8 : 16;
               }
-              pk_epi_residual(a, c, nt, old, dst, xdst, PK_TAG(a, l + 1), R, prow, nullptr, ring, rs);
+              pk_epi_residual(a, c, nt, old, dst + (long)row0 * d, xdst ? xdst + row0 * hd : nullptr, PK_TAG(a, l + 1), Rl, prow,
+                              nullptr, ring, rs);
             }
           }
         }
         if (__syncthreads_or(!okr)) return;
       }
-      PK_NEXT(4 * (d / 16));
+      PK_NEXT(4 * (d / 16) * RG);
     }
     // ---- level transition after stack st; everything it produces carries the tag of the next layer
     const int ln = a.first[st] + a.count[st];
@@ -900,7 +960,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       for (int r = 0; r < Rf_; r++) if (a.pos[fl][r] >= 0) F0 = min(F0, a.pos[fl][r]);
       PK_MINE(Rc_) {
         const int j = a.pos[cl][u];
-        bool ok = pk_wait_stack(a, a.hT[st], tagn, stage);
+        bool ok = pk_wait_stack(a, a.hT[st], tagn, stage, QT == 1 ? 16 : Rf_);
         for (int i0 = 0; i0 < d; i0 += 512) {
           const int i = i0 + 2 * threadIdx.x;       // two adjacent columns per thread
           float s0 = 0.f, s1 = 0.f;
@@ -932,8 +992,8 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
           for (int i = 0; i < 4; i++) {
             const float w = __shfl_xor(c[i], 1, 64);
             if (g * 4 + i < Rc_) {
-              pk_stf(a.hA + (long)ln * 16 * d + (long)(g * 4 + i) * d + n, c[i], tagn);
-              if ((lane & 1) == 0) pk_st(a.xA + (long)ln * 8 * d + (long)(g * 4 + i) * (d >> 1) + (n >> 1), pk_pack(c[i], w), tagn);
+              pk_stf(a.hA + (long)ln * RS * d + (long)(g * 4 + i) * d + n, c[i], tagn);
+              if ((lane & 1) == 0) pk_st(a.xA + (long)ln * RH * d + (long)(g * 4 + i) * (d >> 1) + (n >> 1), pk_pack(c[i], w), tagn);
             }
           }
         }
@@ -952,7 +1012,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         const int p = a.pos[fl][u];
         int slot = -1;
         if (p >= 0) for (int r = 0; r < Rc_; r++) if (a.pos[cl][r] == p / 3) slot = r;
-        bool ok = pk_wait_stack(a, a.hT[st], tagn, stage);
+        bool ok = pk_wait_stack(a, a.hT[st], tagn, stage, QT == 1 ? 16 : Rc_);
         for (int i = threadIdx.x; i < d; i += 256) {
           unsigned r0[1], r1[1];
           ok = pk_fetch<1>(r0, 1, true, tag_skip, [&](int) { return skip + (long)u * d + i; }, a, stage) && ok;
@@ -965,9 +1025,9 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
               v += ring[(long)((p / 3) & (rs - 1)) * d + i];
             }
           }
-          pk_stf(a.hA + (long)ln * 16 * d + (long)u * d + i, v, tagn);
+          pk_stf(a.hA + (long)ln * RS * d + (long)u * d + i, v, tagn);
           const float w = __shfl_xor(v, 1, 64);
-          if ((i & 1) == 0) pk_st(a.xA + (long)ln * 8 * d + (long)u * (d >> 1) + (i >> 1), pk_pack(v, w), tagn);
+          if ((i & 1) == 0) pk_st(a.xA + (long)ln * RH * d + (long)u * (d >> 1) + (i >> 1), pk_pack(v, w), tagn);
         }
         if (__syncthreads_or(!ok)) return;
       }
@@ -977,15 +1037,17 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   // ---- output head: final norm on the fly, logits to plain memory (later launches read them)
   {
     const int l = a.n_layers, R = a.R[0];
-    const int NT = (a.D.V + 15) / 16;
-    PK_MINE(NT) {
+    const int NT = (a.D.V + 15) / 16, RG = QT == 1 ? 1 : (R + 15) >> 4;
+    PK_MINE(NT * RG) {
+      const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
       f32x4 c;
-      if (!pk_gemm_tile<1>(a, sh, (pk_cw_t)a.lm + (long)u * (d / 32) * 512, d / 32, a.xA + (long)l * 8 * d, PK_TAG(a, l), (pk_cf_t)a.gf, R, c, stage)) return;
+      if (!pk_gemm_tile<1>(a, sh, (pk_cw_t)a.lm + (long)nt * (d / 32) * 512, d / 32, a.xA + (long)l * RH * d + (long)row0 * (d >> 1),
+                           PK_TAG(a, l), (pk_cf_t)a.gf, Rl, c, stage)) return;
       if (wave == 0) {
-        const int lane = threadIdx.x & 63, g = lane >> 4, n = u * 16 + (lane & 15);
+        const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
 #pragma unroll
         for (int i = 0; i < 4; i++)
-          if (g * 4 + i < R && n < a.D.V) a.logits[(long)(g * 4 + i) * a.D.V + n] = c[i];
+          if (g * 4 + i < Rl && n < a.D.V) a.logits[(long)(row0 + g * 4 + i) * a.D.V + n] = c[i];
       }
       __syncthreads();
     }

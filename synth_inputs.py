@@ -111,6 +111,10 @@ TEST_CONFIGS = {
     "t_f32_2727": Config("t_f32_2727", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 12, 2, 27, 27),
     "t_bf16_c17": Config("t_bf16_c17", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 2, 8, 17, 0, 0),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
+    # blocks longer than 16 tokens at one sequence (two row groups at the coordinate level of the single-launch verify kernel)
+    "t_bf16_1815_b1": Config("t_bf16_1815_b1", 256, 4, 64, 2, 1, 2, 2, 3, 100, "bf16", 1, 30, 2, 15, 18),
+    "t_bf16_2727_b1": Config("t_bf16_2727_b1", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 24, 2, 27, 27),
+    "t_bf16_1815_b1_w72": Config("t_bf16_1815_b1_w72", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 150, 2, 15, 18, window=72),
     # sliding window: streams long enough that the K/V rings (multiples of 128 positions) wrap at all three levels
     "t_f32_99_w36": Config("t_f32_99_w36", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 150, 2, 9, 9, window=36),
     "t_bf16_99_w36": Config("t_bf16_99_w36", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 3, 150, 2, 9, 9, window=36),

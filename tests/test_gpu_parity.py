@@ -19,7 +19,8 @@ def _need_gpu():
 
 @pytest.mark.parametrize("name", ["t_f32_c", "t_f32_99", "t_f32_1815", "t_bf16_99", "t_bf16_1815", "t_bf16_99_b1", "t_bf16_99_b1w",
                                   "t_f32_1818", "t_bf16_1812", "t_bf16_279", "t_f32_2727", "t_bf16_c17",
-                                  "t_f32_99_w36", "t_bf16_99_w36", "t_bf16_99_b1_w36", "t_bf16_1815_w72"])
+                                  "t_f32_99_w36", "t_bf16_99_w36", "t_bf16_99_b1_w36", "t_bf16_1815_w72",
+                                  "t_bf16_1815_b1", "t_bf16_2727_b1", "t_bf16_1815_b1_w72"])
 def test_lockstep_small_native_heads(name):
     _need_gpu()
     from parity_harness import lockstep
@@ -28,6 +29,8 @@ def test_lockstep_small_native_heads(name):
     rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype])
     print(rep, flush=True)
     assert all(len(s) == 9 * cfg.faces for s in streams)
+    if name.endswith("_b1") or "_b1_" in name or name.endswith("_b1w"):
+        assert fm.verify_path() == 1          # one sequence in half precision: the single-launch verify kernel
     # the device's own whole-loop entry point must emit the same streams
     for s in range(cfg.batch):
         fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
