@@ -188,7 +188,7 @@ int fm_measure_peaks(fm_ctx* ctx, double* host_out);
 int fm_measure_gemm(fm_ctx* ctx, int32_t rows, double* host_out);
 
 /* Which implementation fm_verify_block runs for this context: 1 = the single persistent kernel (half-precision
- * storage, one sequence, block <= 16), 0 = one launch per operator.  Both compute the same function with the same
+ * storage, one sequence, block <= 32), 0 = one launch per operator.  Both compute the same function with the same
  * arithmetic per operator; they cut the key axis of the attention differently, so results agree to rounding, and
  * each is bit-reproducible in itself. */
 int32_t fm_verify_path(const fm_ctx* ctx);

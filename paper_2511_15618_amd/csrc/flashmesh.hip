@@ -104,7 +104,7 @@ struct fm_ctx {
   std::vector<int> len_bound;   // host upper bound on each sequence's committed coordinate length
   long commits = 0;             // fm_commit calls so far
   bool sticky_error = false;    // a launch wrapper refused its arguments (message in err); reported by the entry point
-  // persistent verify kernel (one sequence, block <= 16, half-precision path)
+  // persistent verify kernel (one sequence, block <= 32, half-precision path)
   bool persist;
   PkArgs pk;
   PrefillLayer* pf_layers = nullptr;   // per-block table of the tiled prefill GEMM (null: per-block launches)
