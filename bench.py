@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--faces", type=int, default=0, help="override the face budget (0 = the configuration's)")
     ap.add_argument("--draft", default="", help="override the draft counts: Dc,m,n (coordinate heads, point tokens, face tokens)")
+    ap.add_argument("--batch", type=int, default=0, help="override the number of sequences of the configuration")
     ap.add_argument("--window", type=int, default=0,
                     help="sliding-window self-attention: window in coordinate tokens (multiple of 9); with --faces beyond "
                          "the configuration's budget the stream runs past one window over ring K/V caches")
@@ -132,6 +133,8 @@ def main():
     if args.draft:
         dc, m, n = (int(v) for v in args.draft.split(","))
         cfg = cfg.replace(draft_coord=dc, draft_point=m, draft_face=n)
+    if args.batch:
+        cfg = cfg.replace(batch=args.batch)
     faces = args.faces or cfg.faces
     if args.window:
         cfg = cfg.replace(window=args.window, faces=max(faces, cfg.faces))
@@ -355,7 +358,7 @@ def main():
                    "measured_on_this_gpu": measured, "batch8": batch8},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": counter_traffic(args.config, persistent) if (faces == si.CONFIGS[args.config].faces and not args.window and not args.draft) else None,
+                     "traffic": counter_traffic(args.config, persistent) if (faces == si.CONFIGS[args.config].faces and not args.window and not args.draft and not args.batch) else None,
                      "algorithmic_bytes": bytes_mid, "ms": ms_verify,
                      "frac_of_measured_read_rate": achieved / measured["hbm_read_GBs"]},
     }
