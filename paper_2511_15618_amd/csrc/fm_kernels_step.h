@@ -435,8 +435,6 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
                                                 const float* __restrict__ dist_v, const float* __restrict__ dist_f,
                                                 Replay rp, int speculative, int* __restrict__ block_tok,
                                                 int* __restrict__ block_len, Sampling sm) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
   __shared__ float sh[260];
   __shared__ int sidx;
   if (sm.temperature > 0.f)
@@ -465,8 +463,8 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
   }
   const int nlim = D.ban ? D.nbins : D.V;
   int len = 1;
-  for (int p = spos + 2; len < D.Bm && p < budget; p++) {
-    const float* rows[3];
+  // the averaged distributions behind draft index idx (position spos + 1 + idx), if any level covers it
+  auto rows_of = [&](int p, const float* (&rows)[3]) {
     int cnt = 0;
     const int kc = p - (basec + 2);
     if (kc >= 0 && kc < D.Dc) rows[cnt++] = dist_c + ((long)s * D.Dc + kc) * D.V;
@@ -474,10 +472,15 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
     if (basev >= 0 && tv >= 3 && tv < D.m) rows[cnt++] = dist_v + ((long)s * D.nhfc + (tv - 3)) * D.V;
     const int tf = p - 1 - basef;
     if (basef >= 0 && tf >= 3 && tf < D.n) rows[cnt++] = dist_f + ((long)s * D.nhfc + (tf - 3)) * D.V;
-    if (cnt == 0) break;
-    const float inv = 1.0f / (float)cnt;
-    if (sm.temperature > 0.f) {
-      // sampled decoding: keep the averaged distribution (the proposal the verify pass tests against) and draw from it
+    return cnt;
+  };
+  if (sm.temperature > 0.f) {
+    // sampled decoding: keep the averaged distribution (the proposal the verify pass tests against) and draw from it
+    for (int p = spos + 2; len < D.Bm && p < budget; p++) {
+      const float* rows[3];
+      const int cnt = rows_of(p, rows);
+      if (cnt == 0) break;
+      const float inv = 1.0f / (float)cnt;
       float* qr = sm.qrow + ((long)s * D.Bm + len) * D.V;
       for (int i = threadIdx.x; i < nlim; i += 256) {
         float a = rows[0][i];
@@ -490,30 +493,54 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
       if (threadIdx.x == 0) { tok[len] = b; sm.qtok[s * D.Bm + len] = b; sm.qsum[s * D.Bm + len] = sh[256]; }
       __syncthreads();
       len++;
-      continue;
     }
-    float bv = -INFINITY;
-    int bi = 0x7fffffff;
-    for (int i = threadIdx.x; i < nlim; i += 256) {
-      float a = rows[0][i];
-      if (cnt > 1) a += rows[1][i];
-      if (cnt > 2) a += rows[2][i];
-      argmax_merge(bv, bi, a * inv, i);
+  } else {
+    // greedy: one wave per draft index, all indices at once; the block then ends at the first index nothing covers
+    __shared__ int stok[32];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int idx = 1 + wave; idx < D.Bm; idx += 4) {
+      const float* rows[3];
+      const int cnt = rows_of(spos + 1 + idx, rows);
+      int bi = -1;
+      if (cnt > 0) {
+        const float inv = 1.0f / (float)cnt;
+        float bv = -INFINITY;
+        bi = 0x7fffffff;
+        for (int i = lane; i < nlim; i += 64) {
+          float a = rows[0][i];
+          if (cnt > 1) a += rows[1][i];
+          if (cnt > 2) a += rows[2][i];
+          argmax_merge(bv, bi, a * inv, i);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+          const float ov = __shfl_xor(bv, o, 64);
+          const int oi = __shfl_xor(bi, o, 64);
+          argmax_merge(bv, bi, ov, oi);
+        }
+      }
+      if (lane == 0) stok[idx] = bi;
     }
-    const int b = block_argmax(bv, bi, sv, si);
-    if (threadIdx.x == 0) tok[len] = b;
-    len++;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      while (len < D.Bm && spos + 1 + len < budget && stok[len] >= 0) { tok[len] = stok[len]; len++; }
+      stok[0] = len;
+    }
+    __syncthreads();
+    len = stok[0];
   }
   if (rp.stream) {
     // synthetic draft source: the known continuation, each token kept with probability `keep`
-    len = 1;
-    for (int p = P + 1; len < D.Bm && p < budget && p <= rp.n_valid; p++, len++) {
-      if (threadIdx.x == 0) {
-        const int truth = rp.stream[(long)s * rp.stride + p - 1];
-        const bool keep = replay_uniform(rp.seed, (unsigned long long)s, (unsigned long long)p) < rp.keep;
-        tok[len] = keep ? truth : (truth + 1) % D.nbins;
-      }
+    int n = min(D.Bm - 1, min(budget - 1 - P, rp.n_valid - P));
+    n = max(n, 0);
+    const int t = threadIdx.x;
+    if (t >= 1 && t <= n) {
+      const int p = P + t;
+      const int truth = rp.stream[(long)s * rp.stride + p - 1];
+      const bool keep = replay_uniform(rp.seed, (unsigned long long)s, (unsigned long long)p) < rp.keep;
+      tok[t] = keep ? truth : (truth + 1) % D.nbins;
     }
+    len = 1 + n;
   }
   if (threadIdx.x == 0) block_len[s] = len;
 }
