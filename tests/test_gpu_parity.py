@@ -128,6 +128,19 @@ def test_lockstep_sampled_decoding_with_correct_stage(name):
     assert all(len(s) == 9 * cfg.faces for s in streams) and rep.corrected_blocks > 0
 
 
+@pytest.mark.parametrize("name", ["t_bf16_99_w36", "t_bf16_1815_b1_w72"])
+def test_lockstep_everything_on(name):
+    """Sliding window, correct stage and sampled decoding together, on both verify paths (three sequences per operator,
+    one sequence with 18-token blocks in the single-launch kernel)."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.TEST_CONFIGS[name].replace(faces=60)
+    print("case everything", name, flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype], sampling=(0.9, 21), correct_hist=9)
+    print(rep, flush=True)
+    assert all(len(s) == 9 * cfg.faces for s in streams)
+
+
 def test_config0_tiny_full_run():
     _need_gpu()
     from parity_harness import lockstep
