@@ -409,7 +409,7 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
                          c->dist_f);
     }
   }
-  hipLaunchKernelGGL(k_merge, dim3(D.S), dim3(256), 0, c->stream, c->st, D, c->dr, c->dist_c, c->dist_v, c->dist_f,
+  hipLaunchKernelGGL(k_merge, dim3(D.S), dim3(1024), 0, c->stream, c->st, D, c->dr, c->dist_c, c->dist_v, c->dist_f,
                      c->replay, speculative, block_tok, block_len, c->smp);
   HIPCHK(c, hipGetLastError());
   return FM_OK;

@@ -185,14 +185,15 @@ struct Sampling {
 
 __device__ __forceinline__ float sample_uniform(unsigned long long seed, int purpose, int seq, int pos);
 
-// Inverse CDF in index order over n weights, by one workgroup of 256 threads: thread t owns the contiguous chunk
-// [t*chunk, (t+1)*chunk); `wf(i)` gives weight i.  Returns the smallest i whose cumulative weight exceeds
-// u * total (the last index with weight if rounding leaves none), the same in every thread.  sh: 258 floats, si: 1 int.
+// Inverse CDF in index order over n weights, by one workgroup of up to 1024 threads: thread t owns the contiguous
+// chunk [t*chunk, (t+1)*chunk); `wf(i)` gives weight i.  Returns the smallest i whose cumulative weight exceeds
+// u * total (the last index with weight if rounding leaves none), the same in every thread.  sh: blockDim + 2 floats
+// (the total is left in sh[blockDim]), si: 1 int.
 template <class F>
 __device__ __forceinline__ int block_inverse_cdf(int n, float u, F wf, float* sh, int* si) {
-  const int t = threadIdx.x;
-  const int chunk = (n + 255) / 256;
-  const int i0 = t * chunk, i1 = min(i0 + chunk, n);
+  const int t = threadIdx.x, nt = blockDim.x;
+  const int chunk = (n + nt - 1) / nt;
+  const int i0 = min(t * chunk, n), i1 = min(i0 + chunk, n);
   float local = 0.f;
   for (int i = i0; i < i1; i++) local += wf(i);
   sh[t] = local;
@@ -200,11 +201,11 @@ __device__ __forceinline__ int block_inverse_cdf(int n, float u, F wf, float* sh
   __syncthreads();
   if (t == 0) {
     float run = 0.f;
-    for (int k = 0; k < 256; k++) { const float v = sh[k]; sh[k] = run; run += v; }
-    sh[256] = run;
+    for (int k = 0; k < nt; k++) { const float v = sh[k]; sh[k] = run; run += v; }
+    sh[nt] = run;
   }
   __syncthreads();
-  const float thr = u * sh[256];
+  const float thr = u * sh[nt];
   const float excl = sh[t];
   if (i0 < i1 && excl <= thr && excl + local > thr) {
     float run = excl;
@@ -431,14 +432,14 @@ __global__ __launch_bounds__(256) void k_sample_rows(StateDev st, Dims D, const 
 
 // One workgroup per sequence: update the draft bookkeeping, average the distributions that cover
 // each future position, take the greedy token, stop at the first uncovered position.
-__global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R, const float* __restrict__ dist_c,
+__global__ __launch_bounds__(1024) void k_merge(StateDev st, Dims D, DraftRows R, const float* __restrict__ dist_c,
                                                 const float* __restrict__ dist_v, const float* __restrict__ dist_f,
                                                 Replay rp, int speculative, int* __restrict__ block_tok,
                                                 int* __restrict__ block_len, Sampling sm) {
-  __shared__ float sh[260];
+  __shared__ float sh[1026];
   __shared__ int sidx;
   if (sm.temperature > 0.f)
-    for (int i = threadIdx.x; i < D.Bm; i += 256) sm.qtok[blockIdx.x * D.Bm + i] = -1;
+    for (int i = threadIdx.x; i < D.Bm; i += blockDim.x) sm.qtok[blockIdx.x * D.Bm + i] = -1;
   const int s = blockIdx.x;
   int* tok = block_tok + (long)s * D.Bm;
   if (st.fin[s]) {
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
       if (cnt == 0) break;
       const float inv = 1.0f / (float)cnt;
       float* qr = sm.qrow + ((long)s * D.Bm + len) * D.V;
-      for (int i = threadIdx.x; i < nlim; i += 256) {
+      for (int i = threadIdx.x; i < nlim; i += blockDim.x) {
         float a = rows[0][i];
         if (cnt > 1) a += rows[1][i];
         if (cnt > 2) a += rows[2][i];
@@ -490,7 +491,7 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
       }
       __syncthreads();
       const int b = block_inverse_cdf(nlim, sample_uniform(sm.seed, FM_U_DRAFT, s, p), [&](int i) { return qr[i]; }, sh, &sidx);
-      if (threadIdx.x == 0) { tok[len] = b; sm.qtok[s * D.Bm + len] = b; sm.qsum[s * D.Bm + len] = sh[256]; }
+      if (threadIdx.x == 0) { tok[len] = b; sm.qtok[s * D.Bm + len] = b; sm.qsum[s * D.Bm + len] = sh[blockDim.x]; }
       __syncthreads();
       len++;
     }
@@ -498,7 +499,7 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
     // greedy: one wave per draft index, all indices at once; the block then ends at the first index nothing covers
     __shared__ int stok[32];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int idx = 1 + wave; idx < D.Bm; idx += 4) {
+    for (int idx = 1 + wave; idx < D.Bm; idx += (int)(blockDim.x >> 6)) {
       const float* rows[3];
       const int cnt = rows_of(spos + 1 + idx, rows);
       int bi = -1;
@@ -506,11 +507,22 @@ __global__ __launch_bounds__(256) void k_merge(StateDev st, Dims D, DraftRows R,
         const float inv = 1.0f / (float)cnt;
         float bv = -INFINITY;
         bi = 0x7fffffff;
-        for (int i = lane; i < nlim; i += 64) {
-          float a = rows[0][i];
-          if (cnt > 1) a += rows[1][i];
-          if (cnt > 2) a += rows[2][i];
-          argmax_merge(bv, bi, a * inv, i);
+        // four strides of the vocabulary per step, all loads of a step in flight together
+        for (int i0 = lane; i0 < nlim; i0 += 256) {
+          float a[4];
+#pragma unroll
+          for (int k = 0; k < 4; k++) {
+            const int i = i0 + 64 * k;
+            a[k] = 0.f;
+            if (i < nlim) {
+              a[k] = rows[0][i];
+              if (cnt > 1) a[k] += rows[1][i];
+              if (cnt > 2) a[k] += rows[2][i];
+            }
+          }
+#pragma unroll
+          for (int k = 0; k < 4; k++)
+            if (i0 + 64 * k < nlim) argmax_merge(bv, bi, a[k] * inv, i0 + 64 * k);
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
