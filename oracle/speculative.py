@@ -5,9 +5,10 @@ supplement's "Three-Level Speculative Decoding", "Integrating the three levels"
 and optimisation rules (A)/(B), and the verify mechanism of Sec. 3.3.  Greedy
 only.  Where the paper is silent the reading taken is stated at the function.
 
-parity unpinned: the numerical values of the SP/HF draft heads are pinned only
-by wiring special cases (zeroed projections) and by the model-free schedule;
-the paper prints no worked numbers for them.
+Pins of the SP/HF draft heads (the paper prints no worked numbers for them): wiring special
+cases (zeroed projections), a closed form of the whole chain under uniform self-attention
+(zero query projection), the query side (norm gain, W_q, rotary position of the query) by
+rotary retrieval of one key, and the model-free schedule against the supplement's 9-9 example.
 """
 from __future__ import annotations
 

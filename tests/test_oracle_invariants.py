@@ -369,6 +369,109 @@ def test_sp_and_hf_residual_wiring():
         assert np.allclose(st.rows["f"][tgt], want_f, atol=1e-12)
 
 
+def test_sp_and_hf_closed_form_with_uniform_self_attention():
+    """With a zero query projection every visible key gets the same weight, so the self-attention of an SP head
+    (Eq. 1) or HF block (Eq. 3-6) is the mean of the cached values; the rest of the chain is then written out here
+    step by step with plain loops (cross-attention scores, softmax, tanh-GELU) and must match."""
+    cfg, m, mem = _model("t_f32_99", faces=3)
+    st = SeqState(m, mem, 27)
+    toks = _tokens(cfg, 14)
+    forward_block(m, st, toks[:13])
+    st.P = 13
+    s, d, H = 12, cfg.d_model, cfg.n_heads
+    r = np.random.default_rng(4)
+    pfx = "cpost.%d." % (cfg.l_cpost - 1)                    # the last layer of the coordinate level
+    # --- SP head 1 of the coordinate level
+    m.w["sp.c.1.wq"] = np.zeros((d, d))
+    h_s = r.standard_normal(d)
+    got = sp.sp_head(m, st, "c", 1, h_s, s)
+    vmean = st.V[pfx][:s + 1].mean(axis=0).reshape(d)        # uniform weights over keys 0..s, heads side by side
+    a = m.w["sp.c.1.wo"] @ vmean
+    q2 = (m.w["sp.c.1.cq"] @ a).reshape(H, 64)
+    Km, Vm = st.Kmem[pfx], st.Vmem[pfx]                       # [M, H, 64]
+    c = np.zeros((H, 64))
+    for h in range(H):
+        sc = np.array([np.dot(q2[h], Km[j, h]) / 8.0 for j in range(Km.shape[0])])
+        w = np.exp(sc - sc.max())
+        w /= w.sum()
+        for j in range(Km.shape[0]):
+            c[h] += w[j] * Vm[j, h]
+    want = m.w["sp.c.1.lin"] @ (m.w["sp.c.1.co"] @ c.reshape(d)) + h_s
+    assert np.allclose(got, want, atol=1e-10)
+    # --- HF block of coordinate offset t = 3: keys 0..limit, FFN with tanh-GELU, residual on the upsampled feature
+    m.w["hf.c.3.wq"] = np.zeros((d, d))
+    h_up = r.standard_normal(d)
+    limit = 9
+    got = sp.hf_block(m, st, "c", 3, h_up, limit + 3, limit)
+    vmean = st.V[pfx][:limit + 1].mean(axis=0).reshape(d)
+    z = m.w["hf.c.3.w1"] @ vmean
+    gelu = 0.5 * z * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3)))
+    want = h_up + m.w["hf.c.3.w2"] @ gelu
+    assert np.allclose(got, want, atol=1e-10)
+    # the visible range matters: one key fewer changes the result
+    assert not np.allclose(sp.hf_block(m, st, "c", 3, h_up, limit + 3, limit - 1), want, atol=1e-6)
+
+
+def test_sp_and_hf_query_side_by_rotary_retrieval():
+    """The query side of the heads (norm gain, W_q, rotary position of the query).  Keys are set to one vector rotated
+    to their positions; a query that is a large multiple of the same vector rotated to position q scores
+    big * sum_i |u_i|^2 cos((q - j) theta_i) against key j, so the softmax collapses onto one key that the test can
+    name: j = s for an SP head (its query stands at s), and for an HF block with all the energy in the first rotary
+    pair (theta = 1) and q = limit + 3 the key at distance 6 (cos 6 = 0.96 beats distances 3, 4, 5, 7 ... 12), which is
+    not the key a query standing at `limit` would pick."""
+    cfg, m, mem = _model("t_f32_99", faces=3)
+    st = SeqState(m, mem, 27)
+    toks = _tokens(cfg, 14)
+    forward_block(m, st, toks[:13])
+    st.P = 13
+    s, d, H = 12, cfg.d_model, cfg.n_heads
+    r = np.random.default_rng(8)
+    pfx = "cpost.%d." % (cfg.l_cpost - 1)
+
+    def rest_of_sp(a_heads, h_s):
+        a = m.w["sp.c.1.wo"] @ a_heads.reshape(d)
+        q2 = (m.w["sp.c.1.cq"] @ a).reshape(H, 64)
+        Km, Vm = st.Kmem[pfx], st.Vmem[pfx]
+        c = np.zeros((H, 64))
+        for h in range(H):
+            sc = np.array([np.dot(q2[h], Km[j, h]) / 8.0 for j in range(Km.shape[0])])
+            w = np.exp(sc - sc.max())
+            c[h] = (w[:, None] * Vm[:, h]).sum(axis=0) / w.sum()
+        return m.w["sp.c.1.lin"] @ (m.w["sp.c.1.co"] @ c.reshape(d)) + h_s
+
+    # --- SP head: the query stands at s, so it retrieves the value cached at s
+    u = r.standard_normal((H, 64))
+    for j in range(s + 1):
+        st.K[pfx][j] = P.rope(u[None], [j], cfg.rope_base)[0]
+    h_s = r.standard_normal(d)
+    g = 1.0 + 0.3 * r.standard_normal(d)
+    m.w["sp.c.1.g"] = g
+    n = P.rmsnorm(h_s[None], g, cfg.rms_eps)[0]
+    m.w["sp.c.1.wq"] = 60.0 * np.outer(u.reshape(d), n) / np.dot(n, n)         # W_q n = 60 u
+    got = sp.sp_head(m, st, "c", 1, h_s, s)
+    assert np.allclose(got, rest_of_sp(st.V[pfx][s], h_s), atol=1e-9)
+    assert not np.allclose(got, rest_of_sp(st.V[pfx][s - 1], h_s), atol=1e-6)
+    # --- HF block: the query stands at the slot it predicts for (limit + 3), not at the last visible key
+    u1 = np.zeros((H, 64))
+    u1[:, 0] = 1.0
+    limit, pos = 9, 12
+    for j in range(limit + 1):
+        st.K[pfx][j] = P.rope(u1[None], [j], cfg.rope_base)[0]
+    h_up = r.standard_normal(d)
+    g = 1.0 + 0.3 * r.standard_normal(d)
+    m.w["hf.c.3.g"] = g
+    n = P.rmsnorm(h_up[None], g, cfg.rms_eps)[0]
+    m.w["hf.c.3.wq"] = 16000.0 * np.outer(u1.reshape(d), n) / np.dot(n, n)
+    got = sp.hf_block(m, st, "c", 3, h_up, pos, limit)
+
+    def rest_of_hf(v_heads):
+        z = m.w["hf.c.3.w1"] @ v_heads.reshape(d)
+        return h_up + m.w["hf.c.3.w2"] @ (0.5 * z * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3))))
+
+    assert np.allclose(got, rest_of_hf(st.V[pfx][pos - 6]), atol=1e-9)
+    assert not np.allclose(got, rest_of_hf(st.V[pfx][limit]), atol=1e-6)
+
+
 # -- correct stage (Sec. 3.2) ---------------------------------------------------------------
 def _correct_cases():
     for line in open(os.path.join(GOLD, "correct_cases.txt")):
