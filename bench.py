@@ -73,6 +73,91 @@ def counter_traffic(config_index, persistent):
     return None
 
 
+def forced_fill(fm, cfg, torch, target, seed=7):
+    """Bring every sequence to `target` committed tokens without a greedy stream: whole blocks of seeded random
+    coordinate tokens are verified (which writes their K/V rows) and committed by force (the caller owns the
+    accepted lengths it hands to fm_commit).  Deterministic: the same call leaves the same state every time."""
+    tok, ln = fm.new_block()
+    acc = torch.zeros(cfg.batch, dtype=torch.int32, device="cuda")
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    fm.set_draft_replay(None, 0, 0.0, 0)
+    fm.set_budget(target // 9)
+    while True:
+        for _ in range(50):
+            fm.draft(tok, ln)
+            tok[:, 1:] = torch.randint(0, cfg.n_bins, (cfg.batch, cfg.block_max - 1), generator=gen,
+                                       device="cuda", dtype=torch.int32)
+            ln[:] = torch.where(ln > 0, torch.full_like(ln, cfg.block_max), ln)
+            fm.verify_block(tok, ln, None, acc)
+            fm.commit(ln)
+        if int(fm.read_state()[:, 4].min()) == 1:      # every sequence has reached the budget
+            return
+
+
+def time_verify(fm, torch, tok, ln, acc, iters):
+    """Average duration of fm_verify_block on the block in (tok, ln), HIP events on the library's stream."""
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        fm.verify_block(tok, ln, None, acc)
+    ev0.record(fm.stream)
+    for _ in range(iters):
+        fm.verify_block(tok, ln, None, acc)
+    ev1.record(fm.stream)
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) / iters
+
+
+def half_context_leg(fm, cfg, torch, mems_dev, faces, steps, warmup, cont_faces=60):
+    """The decode step at half context for a configuration whose whole generation does not fit a default run
+    (several sequences): forced fill to faces/2, a short native continuation to learn the greedy stream from there,
+    the identical fill again, then `warmup` untimed and `steps` timed steps of draft -> verify -> commit with the
+    replay draft source (p = REPLAY_P) on that continuation, and the verify pass alone for the roofline."""
+    half = 9 * (faces // 2)
+    cont = min(cont_faces, faces - faces // 2)
+
+    def fill():
+        for q in range(cfg.batch):
+            fm.prefill_condition(q, mems_dev[q])
+        forced_fill(fm, cfg, torch, half)
+    fill()
+    out, n, _ = fm.generate(faces // 2 + cont, True)        # native heads from the filled state
+    stream, nt = out.clone(), int(n.min().item())
+    fill()
+    fm.set_draft_replay(stream, nt, REPLAY_P, REPLAY_SEED)
+    fm.set_budget(faces // 2 + cont)
+    tok, ln = fm.new_block()
+    acc = torch.zeros(cfg.batch, dtype=torch.int32, device="cuda")
+    for _ in range(warmup):
+        fm.draft(tok, ln)
+        fm.verify_block(tok, ln, None, acc)
+        fm.commit(acc)
+    torch.cuda.synchronize()
+    p0 = fm.read_state()[:, 0].sum()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(fm.stream)
+    for _ in range(steps):
+        fm.draft(tok, ln)
+        fm.verify_block(tok, ln, None, acc)
+        fm.commit(acc)
+    ev1.record(fm.stream)
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1)
+    state = fm.read_state()
+    tokens = int(state[:, 0].sum() - p0)
+    assert int(state[:, 4].max()) == 0, "the continuation was too short for the timed steps"
+    fm.draft(tok, ln)
+    nbytes = fm.verify_bytes()
+    ms_verify = time_verify(fm, torch, tok, ln, acc, 10)
+    gbs = nbytes / (ms_verify * 1e-3) / 1e9
+    return {"tokens_per_s": tokens / ms * 1e3, "ms_per_step": ms / steps, "steps": steps, "tokens": tokens,
+            "mean_accepted_per_sequence": tokens / steps / cfg.batch,
+            "context_tokens_per_sequence": [int(v) for v in state[:, 0]],
+            "roofline": {"bound": "hbm", "kernel": "verify pass at half context (all launches of fm_verify_block)" if fm.verify_path() == 0
+                         else "k_verify_persist at half context (fm_verify_block)",
+                         "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                         "traffic": None, "algorithmic_bytes": nbytes, "ms": ms_verify}}
+
+
 class _Totals:
     steps = 0
     tokens = 0
@@ -109,8 +194,8 @@ def main():
     ap.add_argument("--correct", type=int, default=0,
                     help="run the correct stage (label head, vertex-sharing moves, z-y-x re-sort) in every step, with this "
                          "many historical vertices; random-init labels, so only its cost is meaningful")
-    ap.add_argument("--b8-faces", type=int, default=150,
-                    help="faces per sequence of the extra batch-8 leg (configs[3], same model as configs[2]); 0 = skip")
+    ap.add_argument("--b8-steps", type=int, default=200,
+                    help="timed steps of the extra batch-8 leg (configs[3] at its full size, at half context); 0 = skip")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--gemm-sweep", action="store_true",
@@ -163,18 +248,10 @@ def main():
         # The K/V caches only need the right length for the byte counters, not a greedy stream: commit whole
         # blocks of arbitrary coordinate tokens (the caller owns the accepted lengths it hands to fm_commit).
         reset()
+        forced_fill(fm, cfg, torch, 9 * (faces // 2))
         fm.set_budget(faces)
         tok, ln = fm.new_block()
         acc = torch.zeros(cfg.batch, dtype=torch.int32, device="cuda")
-        gen = torch.Generator(device="cuda").manual_seed(7)
-        target = 9 * (faces // 2)
-        while int(fm.read_state()[:, 0].min()) < target:
-            for _ in range(50):
-                fm.draft(tok, ln)
-                tok[:, 1:] = torch.randint(0, cfg.n_bins, (cfg.batch, cfg.block_max - 1), generator=gen,
-                                           device="cuda", dtype=torch.int32)
-                fm.verify_block(tok, ln, None, acc)
-                fm.commit(ln)
         fm.draft(tok, ln)
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
@@ -186,6 +263,30 @@ def main():
         print(json.dumps({"counter_pass": True, "context_tokens": int(fm.read_state()[0, 0]),
                           "verify_algorithmic_bytes": fm.verify_bytes(), "copy_bytes_each_way": 1 << 30,
                           "verify_path": fm.verify_path()}))
+        return
+
+    if cfg.batch > 1:
+        # several sequences: the whole generation does not fit a default run, so the step is timed at half context
+        steps = args.steps if args.steps > 0 else 200
+        leg = half_context_leg(fm, cfg, torch, mems_dev, faces, steps, args.warmup)
+        measured = fm.measure_peaks()
+        leg["roofline"]["frac_of_measured_read_rate"] = leg["roofline"]["achieved"] / measured["hbm_read_GBs"]
+        result = {
+            "metric": f"mesh tokens/sec, batch {cfg.batch} (replay drafts p={REPLAY_P}, all heads executed)",
+            "value": leg["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+            "ms_per_step": leg["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f16 (bf16-valued weights held as half, fp32 accumulate)", "data": "synthetic",
+            "config": {"workload": f"configs[{args.config}] {cfg.name}: d={cfg.d_model}, {cfg.n_layers} blocks, batch {cfg.batch}, "
+                                   f"{faces} faces per sequence, block {cfg.block_max}, timed at half context "
+                                   f"({9 * (faces // 2)} tokens per sequence, reached by forced commits)",
+                       "draft_source": f"replay p={REPLAY_P}", "tokens": leg["tokens"],
+                       "mean_accepted_per_sequence": leg["mean_accepted_per_sequence"],
+                       "context_tokens_per_sequence": leg["context_tokens_per_sequence"], "measured_on_this_gpu": measured},
+            "roofline": leg["roofline"],
+        }
+        if not args.no_cpu:
+            result["cpu_baseline"] = cpu_baseline(cfg, weights, mems[0], args.cpu_seconds)
+        print(json.dumps(result))
         return
 
     # warm-up: W untimed steps through the step-wise entry points
@@ -211,10 +312,22 @@ def main():
     fm.set_draft_replay(stream, n_tokens, REPLAY_P, REPLAY_SEED)
     torch.cuda.synchronize()
     t0 = time.time()
+    context = None
     if args.steps > 0:
+        # K timed steps at half context: the replay source at p = 1 decodes the first half of the stream, then the
+        # timed steps run with the headline acceptance level
         ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fm.set_draft_replay(stream, n_tokens, 1.0, 0)
+        fm.generate(max(faces // 2, 1), True)
+        fm.set_draft_replay(stream, n_tokens, REPLAY_P, REPLAY_SEED)
         fm.set_budget(faces)
+        for _ in range(args.warmup):
+            fm.draft(tok, ln)
+            fm.verify_block(tok, ln, None, acc)
+            fm.commit(acc)
+        torch.cuda.synchronize()
         p0 = fm.read_state()[:, 0].sum()
+        context = int(p0)
         ev0.record()
         for _ in range(args.steps):
             fm.draft(tok, ln)
@@ -231,7 +344,11 @@ def main():
         ms, steps, tokens = st.ms_total, int(st.steps), int(st.tokens)
         same = bool((out2 == stream).all().item())
     wall = time.time() - t0
-    hist = None if args.steps > 0 else [int(v) for v in st.acc_hist[: cfg.block_max + 1]]
+    hist = None if args.steps > 0 else st.hist()[: cfg.block_max + 1]
+    levels = None if args.steps > 0 else {
+        "coordinate_only_steps": sum(st.hist(0)), "point_level_steps": sum(st.hist(1)), "face_level_steps": sum(st.hist(2)),
+        "point_acc": st.mean_verified_drafts(1), "face_acc": st.mean_verified_drafts(2),
+        "ms_draft": st.ms_draft, "ms_verify": st.ms_verify, "ms_commit": st.ms_commit, "phase_samples": int(st.phase_samples)}
 
     # 3) plain one-token-per-step decoding of the same backbone on a prefix (the sequential baseline)
     reset()
@@ -262,16 +379,8 @@ def main():
     fm.set_budget(faces)
     fm.draft(tok, ln)
     bytes_mid = fm.verify_bytes()
-    iters = 20
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(3):
-        fm.verify_block(tok, ln, None, acc)
-    ev0.record(fm.stream)
-    for _ in range(iters):
-        fm.verify_block(tok, ln, None, acc)
-    ev1.record(fm.stream)
-    torch.cuda.synchronize()
-    ms_verify = ev0.elapsed_time(ev1) / iters
+    context_roofline = int(fm.read_state()[0, 0])
+    ms_verify = time_verify(fm, torch, tok, ln, acc, 20)
     achieved = bytes_mid / (ms_verify * 1e-3) / 1e9
     if fm.verify_path() == 1:
         kernel = ("k_verify_persist (whole backbone forward of the block in one launch) at half context; the timed "
@@ -282,53 +391,21 @@ def main():
     measured = fm.measure_peaks()
     persistent = fm.verify_path() == 1
 
-    # batch-8 leg: the same model with 8 independent sequences (configs[3]) on a shortened budget, so that the
-    # default run stays within minutes; ragged accepted lengths come from the per-sequence replay draws
+    # batch-8 leg: the same model with 8 independent sequences (configs[3]) at its full 2000 faces per sequence, timed
+    # at half context (forced fill, see half_context_leg); ragged accepted lengths come from the per-sequence replay draws
     batch8 = None
-    if args.config == 2 and args.b8_faces > 0 and not args.draft and not args.window and not args.correct:
+    if args.config == 2 and args.b8_steps > 0 and not args.draft and not args.window and not args.correct and not args.faces:
         cfg8 = si.CONFIGS[3]
-        f8 = min(args.b8_faces, cfg8.faces)
         fm.close()
         torch.cuda.empty_cache()
+        print("bench: batch-8 leg", file=sys.stderr, flush=True)
         fm8 = FlashMesh(config_struct(cfg8))
         fm8.load_weights(si.pack_blob(cfg8, weights))
         mems8 = [torch.from_numpy(si.make_memory(cfg8, q)).cuda() for q in range(cfg8.batch)]
-
-        def reset8():
-            for q in range(cfg8.batch):
-                fm8.prefill_condition(q, mems8[q])
-
-        reset8()
-        fm8.set_draft_replay(None, 0, 0.0, 0)
-        out8, n8, _ = fm8.generate(f8, True)
-        stream8, nt8 = out8.clone(), int(n8.min().item())
-        reset8()
-        fm8.set_draft_replay(stream8, nt8, REPLAY_P, REPLAY_SEED)
-        out8b, _, st8 = fm8.generate(f8, True)
-        same8 = bool((out8b == stream8).all().item())
-        reset8()
-        fm8.set_draft_replay(stream8, nt8, 1.0, 0)
-        fm8.generate(max(f8 // 2, 1), True)
-        fm8.set_budget(f8)
-        tok8, ln8 = fm8.new_block()
-        acc8 = torch.zeros(cfg8.batch, dtype=torch.int32, device="cuda")
-        fm8.draft(tok8, ln8)
-        b8_bytes = fm8.verify_bytes()
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for _ in range(3):
-            fm8.verify_block(tok8, ln8, None, acc8)
-        ev0.record(fm8.stream)
-        for _ in range(10):
-            fm8.verify_block(tok8, ln8, None, acc8)
-        ev1.record(fm8.stream)
-        torch.cuda.synchronize()
-        ms8 = ev0.elapsed_time(ev1) / 10
-        batch8 = {"workload": f"configs[3] {cfg8.name}: batch {cfg8.batch}, {f8} faces per sequence, block {cfg8.block_max}",
-                  "tokens_per_s": st8.tokens / st8.ms_total * 1e3, "ms_per_step": st8.ms_total / max(int(st8.steps), 1),
-                  "mean_accepted_per_sequence": st8.tokens / max(int(st8.steps), 1) / cfg8.batch,
-                  "stream_equals_native_run": same8, "verify_ms_at_half_context": ms8,
-                  "verify_algorithmic_bytes": b8_bytes, "verify_GBs": b8_bytes / (ms8 * 1e-3) / 1e9,
-                  "verify_frac_of_hbm_peak": b8_bytes / (ms8 * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        batch8 = half_context_leg(fm8, cfg8, torch, mems8, cfg8.faces, args.b8_steps, 5)
+        batch8["workload"] = (f"configs[3] {cfg8.name}: batch {cfg8.batch}, {cfg8.faces} faces per sequence, block {cfg8.block_max}, "
+                              f"{args.b8_steps} steps timed at half context (reached by forced commits)")
+        batch8["roofline"]["frac_of_measured_read_rate"] = batch8["roofline"]["achieved"] / measured["hbm_read_GBs"]
         fm8.close()
         torch.cuda.empty_cache()
 
@@ -348,9 +425,10 @@ def main():
         "config": {"workload": f"configs[{args.config}] {cfg.name}: d={cfg.d_model}, {cfg.n_layers} blocks, batch {cfg.batch}, "
                                f"{faces} faces ({9 * faces} tokens), block {cfg.block_max}, draft counts Dc={cfg.draft_coord} m={cfg.draft_point} n={cfg.draft_face}"
                                + (f", sliding window {cfg.window} tokens" if cfg.window else "")
-                               + (f", correct stage on ({args.correct} historical vertices)" if args.correct else ""),
+                               + (f", correct stage on ({args.correct} historical vertices)" if args.correct else "")
+                               + (f"; {steps} steps timed at half context ({context} tokens committed, reached with replay p=1)" if context is not None else "; whole generation timed"),
                    "draft_source": f"replay p={REPLAY_P}", "tokens": tokens, "mean_accepted": tokens / max(steps, 1),
-                   "accepted_hist": hist, "stream_equals_native_run": same,
+                   "accepted_hist": hist, "per_level": levels, "stream_equals_native_run": same,
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,
                    "native_heads_ms_per_step": st_native.ms_total / max(st_native.steps, 1),
                    "sequential_tokens_per_s": st_seq.tokens / st_seq.ms_total * 1e3,
@@ -359,7 +437,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": counter_traffic(args.config, persistent) if (faces == si.CONFIGS[args.config].faces and not args.window and not args.draft and not args.batch) else None,
-                     "algorithmic_bytes": bytes_mid, "ms": ms_verify,
+                     "traffic_source": "committed counter profile profiles/k_verify_persist_config2_b1_hbm_counters.txt (two rocprofv3 --pmc runs of bench.py --counter-pass at half context), not a counter of this run",
+                     "context_tokens": context_roofline, "algorithmic_bytes": bytes_mid, "ms": ms_verify,
                      "frac_of_measured_read_rate": achieved / measured["hbm_read_GBs"]},
     }
     if not args.no_cpu:

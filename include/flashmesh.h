@@ -68,8 +68,15 @@ typedef struct {
 typedef struct {
   int64_t steps;             /* decode steps run by fm_generate                                   */
   int64_t tokens;            /* tokens emitted over all sequences (BOS excluded)                  */
-  int64_t acc_hist[32];      /* histogram of accepted lengths per (step, live sequence)           */
+  int64_t acc_hist[3][32];   /* histograms of accepted lengths (main token included) per (step, live sequence), by what the
+                                block carried: [0] coordinate-level drafts only, [1] a fresh point-level prediction, [2] a
+                                fresh face-level prediction.  Their sum is the histogram of all steps; the mean of
+                                (length - 1) over [2] / [1] is the number of correctly verified tokens per draft prediction
+                                at the face / point level (Sec. 5.4, Table "draft_num": Face-Acc, Point-Acc)                */
   double ms_total;           /* device time of the whole loop, hipEvent                            */
+  double ms_draft, ms_verify, ms_commit; /* device time of the draft (+ correct), verify and commit phases of one step: mean
+                                over the phase_samples steps that carried event marks (one step in 32)                      */
+  int64_t phase_samples;
 } fm_stats;
 
 /* Create a context for `cfg` bound to `hip_stream` (a hipStream_t; NULL = the null stream).
@@ -131,11 +138,18 @@ int fm_set_sampling(fm_ctx* ctx, float temperature, uint64_t seed);
  * P .. P+len-1 against the K/V caches of all three levels.  logits_dev ([batch, block_max, vocab]
  * float32) may be NULL.  accepted_len_dev[seq] = 1 + number of leading drafts equal to the
  * backbone's own greedy prediction (0 for an empty block).  Committed state is not changed;
- * calling it twice with the same block gives the same result. */
+ * calling it twice with the same block gives the same result.
+ * One sequence in half precision runs as a single launch of 256 workgroups that wait for each other's results and
+ * must therefore all be resident: the library checks at fm_create that the kernel fits once per compute unit, but it
+ * cannot see other work on the GPU.  A kernel of another stream or process that occupies compute units while a pass
+ * runs can make a bounded wait (200 ms) expire.  Such a pass writes accepted_len_dev = 0 for every sequence, fm_commit
+ * of it changes nothing, the next synchronising call (fm_read_state, fm_verify_bytes, fm_generate) returns FM_EHIP with
+ * the diagnosis once, and from then on the context runs one launch per operator (fm_verify_path() = 0), so the caller
+ * can simply draft and verify again. */
 int fm_verify_block(fm_ctx* ctx, const int32_t* block_tok_dev, const int32_t* block_len_dev,
                     float* logits_dev, int32_t* accepted_len_dev);
 
-/* Commit the first accepted_len_dev[seq] (1..len) tokens of the last verified block: advances the
+/* Commit the first accepted_len_dev[seq] (1..len; 0 = leave the sequence as it is) tokens of the last verified block: advances the
  * committed lengths at all three levels (K/V rollback is implicit: rows past them are scratch), and
  * makes the backbone's prediction after the last accepted token the next main token. */
 int fm_commit(fm_ctx* ctx, const int32_t* accepted_len_dev);
@@ -175,6 +189,15 @@ int fm_debug_profile(fm_ctx* ctx, uint64_t* host_out, int32_t n);
  * 4/5/6 tapped features of the coordinate (32) / vertex (16) / face (8) level.  Entry = position mod ring size.
  * Synchronises. */
 int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
+
+/* Draft-stage buffers of the last fm_draft for element-wise parity checks.  which = -1 / -2 switches the keeping of the
+ * averaged draft distributions on / off (greedy decoding does not need them and skips the stores by default; sampled
+ * decoding always keeps them).  which = 0: HOST out [batch][block_max][vocab] float32, row i of a sequence = the
+ * averaged distribution behind draft index i (supplement "Integrating the three levels"; entries at or above the
+ * admissible token count and rows at or above the block length are unspecified).  which = 1 / 2: the label
+ * distributions of the point pipeline [batch][max(m/3 - 1, 1)][3] / of the face pipeline [batch][max(n/3 - 1, 1)][3]
+ * (Sec. 3.2; rows of pipelines that have not fired hold older values).  Synchronises. */
+int fm_debug_draft(fm_ctx* ctx, int32_t which, float* host_out);
 
 /* What this GPU sustains, for reporting next to the published peaks: HOST out[0] = streaming read GB/s, out[1] =
  * streaming copy GB/s (read + write bytes), out[2] = register-only MFMA loop TFLOP/s (fp16, 32x32x16).  Allocates

@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
-           "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile",
+           "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile", "fm_debug_draft",
            "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm"]
 
 
@@ -27,7 +27,20 @@ class FmConfig(C.Structure):
 
 
 class FmStats(C.Structure):
-    _fields_ = [("steps", C.c_int64), ("tokens", C.c_int64), ("acc_hist", C.c_int64 * 32), ("ms_total", C.c_double)]
+    _fields_ = [("steps", C.c_int64), ("tokens", C.c_int64), ("acc_hist", (C.c_int64 * 32) * 3), ("ms_total", C.c_double),
+                ("ms_draft", C.c_double), ("ms_verify", C.c_double), ("ms_commit", C.c_double), ("phase_samples", C.c_int64)]
+
+    def hist(self, kind=None):
+        """Accepted-length histogram as a list of 32 counts: kind 0 / 1 / 2 = coordinate-only / point-level / face-level
+        steps, None = all steps."""
+        kinds = (0, 1, 2) if kind is None else (kind,)
+        return [sum(int(self.acc_hist[k][i]) for k in kinds) for i in range(32)]
+
+    def mean_verified_drafts(self, kind):
+        """Mean number of accepted draft tokens per step of that kind (the paper's Point-Acc for 1, Face-Acc for 2)."""
+        h = self.hist(kind)
+        n = sum(h)
+        return sum((i - 1) * v for i, v in enumerate(h) if i > 0) / n if n else float("nan")
 
 
 _lib = None
@@ -64,6 +77,7 @@ def load_library():
     lib.fm_correct.argtypes = [p, p, p, p]
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_debug_ring.argtypes = [p, i32, p]
+    lib.fm_debug_draft.argtypes = [p, i32, p]
     lib.fm_debug_profile.argtypes = [p, p, i32]
     lib.fm_measure_peaks.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_measure_gemm.argtypes = [p, i32, C.POINTER(C.c_double)]
@@ -192,6 +206,21 @@ class FlashMesh:
         size = (32, 16, 8, 16, 32, 16, 8)[which]
         out = np.zeros((self.batch, size, self.cfgs.d_model), np.float32)
         self._chk(self.lib.fm_debug_ring(self.h, which, C.c_void_p(out.ctypes.data)), "fm_debug_ring")
+        return out
+
+    def keep_draft_rows(self, on: bool = True):
+        self._chk(self.lib.fm_debug_draft(self.h, -1 if on else -2, None), "fm_debug_draft")
+
+    def debug_draft(self, which: int) -> np.ndarray:
+        cfgs = self.cfgs
+        if which == 0:
+            shape = (self.batch, self.block_max, self.vocab)
+        elif which == 1:
+            shape = (self.batch, max(cfgs.draft_point // 3 - 1, 1), 3)
+        else:
+            shape = (self.batch, max(cfgs.draft_face // 3 - 1, 1), 3)
+        out = np.zeros(shape, np.float32)
+        self._chk(self.lib.fm_debug_draft(self.h, which, C.c_void_p(out.ctypes.data)), "fm_debug_draft")
         return out
 
     def debug_profile(self, n: int = 1024) -> np.ndarray:

@@ -106,6 +106,7 @@ struct fm_ctx {
   bool sticky_error = false;    // a launch wrapper refused its arguments (message in err); reported by the entry point
   // persistent verify kernel (one sequence, block <= 32, half-precision path)
   bool persist;
+  int persist_failures = 0;   // times the single-launch kernel gave up (the context then left that path)
   PkArgs pk;
   PrefillLayer* pf_layers = nullptr;   // per-block table of the tiled prefill GEMM (null: per-block launches)
   int pf_n = 0;
@@ -278,16 +279,20 @@ void run_stack(fm_ctx* c, int stack, float* tap_ring, int tap_rs) {
   }
 }
 
+// Word that the single-launch verify kernel raises when one of its bounded waits gave up (null on the per-operator
+// path): the acceptance and commit kernels then report 0 accepted tokens and change nothing.
+const unsigned* pass_failed(const fm_ctx* c) { return c->persist ? c->pk.abort_word : nullptr; }
+
 // per verify row: the backbone's greedy token (or, with sampled decoding, the rejection test and the resampled token),
 // then the accepted length per sequence
 void choose_and_accept(fm_ctx* c, const float* logits, int32_t* accepted) {
   const Dims& D = c->D;
   if (c->smp.temperature > 0.f) {
     hipLaunchKernelGGL(k_sample_rows, dim3(c->Rc), dim3(256), 0, c->stream, c->st, D, logits, c->smp);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)c->smp.accflag);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)c->smp.accflag, pass_failed(c));
   } else {
     hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, logits, D.V, D.ban ? D.nbins : D.V, c->st.y);
-    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)nullptr);
+    hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)nullptr, pass_failed(c));
   }
 }
 
@@ -416,13 +421,13 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
 }
 
 template <typename T>
-int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
+int prefill_impl(fm_ctx* c, int seq, const float* mem_dev, void* stage_area) {
   const Dims& D = c->D;
   const int d = D.d;
   // condition memory in the storage type (dmid is large enough: M*d <= checked at create)
   if (std::is_same<T, f16_t>::value && c->pf_layers) {
     // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
-    f16_t* Xt = (f16_t*)c->stage;
+    f16_t* Xt = (f16_t*)stage_area;
     hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
     hipLaunchKernelGGL(k_prefill_kv, dim3(512), dim3(256), 0, c->stream,
                        (const f16_t*)Xt, (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M, c->pf_n);
@@ -430,8 +435,8 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
     HIPCHK(c, hipGetLastError());
     return FM_OK;
   }
-  T* memT = (T*)c->stage;  // reuse staging area: [M*d] T followed by fp32 [M][2d]
-  float* kv = c->stage + (size_t)D.M * d;
+  T* memT = (T*)stage_area;  // [M*d] T followed by fp32 [M][2d]
+  float* kv = (float*)((unsigned char*)stage_area + (size_t)D.M * d * sizeof(T));
   hipLaunchKernelGGL((k_convert<T>), dim3(512), dim3(256), 0, c->stream, mem_dev, memT, (long)D.M * d);
   for (int st = 0; st < 5; st++)
     for (auto& L : c->stacks[st]) {
@@ -449,16 +454,22 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev) {
   return FM_OK;
 }
 
-// After a synchronisation: did the persistent kernel give up waiting (it never hangs, it reports)?
+// After a synchronisation: did the single-launch verify kernel give up waiting (it never hangs, it reports)?
+// If so the passes enqueued since then have accepted nothing and committed nothing (k_accept / k_commit look at the
+// same word), so the decode state is that of the last good commit.  The failure is reported once with its diagnosis,
+// the words are re-armed, and the context continues on the per-operator path, which shares weights, caches and rings.
 int check_persist(fm_ctx* c) {
   if (!c->persist) return FM_OK;
   unsigned w[9] = {0};
   HIPCHK(c, hipMemcpy(w, c->pk.abort_word, sizeof w, hipMemcpyDeviceToHost));
-  if (w[0])
-    return fail(c, FM_EHIP, "persistent verify kernel timed out: earliest stuck stage %u; first missing element: stage %u "
-                "workgroup %u thread %u index %u expected tag %u saw %u (epoch %u)", w[1], w[5], w[6], w[7], w[8], w[3], w[4],
-                c->pk_epoch);
-  return FM_OK;
+  if (!w[0]) return FM_OK;
+  const unsigned rearm[9] = {0u, 0xFFFFFFFFu, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+  HIPCHK(c, hipMemcpy(c->pk.abort_word, rearm, sizeof rearm, hipMemcpyHostToDevice));
+  c->persist = false;
+  c->persist_failures++;
+  return fail(c, FM_EHIP, "persistent verify kernel timed out: earliest stuck stage %u; first missing element: stage %u "
+              "workgroup %u thread %u index %u expected tag %u saw %u (epoch %u); passes since then accepted nothing, the "
+              "context continues with one launch per operator", w[1], w[5], w[6], w[7], w[8], w[3], w[4], c->pk_epoch);
 }
 
 // Build the parameter tables and the list of (blob range -> device destination) in manifest order.
@@ -644,7 +655,7 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &st.basec, S)); TRY(dalloc(c, &st.basev, S)); TRY(dalloc(c, &st.basef, S));
   TRY(dalloc(c, &st.vlen, S)); TRY(dalloc(c, &st.vtok, S * D.Bm)); TRY(dalloc(c, &st.y, S * D.Bm)); TRY(dalloc(c, &st.acc, S));
   TRY(dalloc(c, &st.hist, S * (D.maxtok + 1))); TRY(dalloc(c, &st.budget, 1)); TRY(dalloc(c, &st.alive, 1));
-  TRY(dalloc(c, &st.acc_hist, 32)); TRY(dalloc(c, &st.counters, 2));
+  TRY(dalloc(c, &st.acc_hist, 3 * 32)); TRY(dalloc(c, &st.counters, 2)); TRY(dalloc(c, &st.kind, S));
   TRY(dalloc(c, &c->ring_hc, S * RS_C * d)); TRY(dalloc(c, &c->tap_c, S * RS_C * d));
   TRY(dalloc(c, &c->ring_hv, S * RS_V * d)); TRY(dalloc(c, &c->ring_yv, S * RS_V * d)); TRY(dalloc(c, &c->tap_v, S * RS_V * d));
   TRY(dalloc(c, &c->ring_yf, S * RS_F * d)); TRY(dalloc(c, &c->tap_f, S * RS_F * d));
@@ -682,7 +693,7 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &c->dist_c, S * std::max(D.Dc, 1) * D.V));
   TRY(dalloc(c, &c->dist_v, S * std::max(D.nhfc, 1) * D.V)); TRY(dalloc(c, &c->dist_f, S * std::max(D.nhfc, 1) * D.V));
   TRY(dalloc(c, &c->lab_v, S * std::max(D.nspv, 1) * 3)); TRY(dalloc(c, &c->lab_f, S * std::max(D.nhfv, 1) * 3));
-  c->smp = Sampling{0.f, 0ull, nullptr, nullptr, nullptr, nullptr};
+  c->smp = Sampling{0.f, 0ull, nullptr, nullptr, nullptr, nullptr, 0};
   TRY(dalloc(c, &c->smp.qrow, S * D.Bm * D.V)); TRY(dalloc(c, &c->smp.qsum, S * D.Bm));
   TRY(dalloc(c, &c->smp.qtok, S * D.Bm)); TRY(dalloc(c, &c->smp.accflag, S * D.Bm));
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
@@ -848,7 +859,7 @@ int fm_prefill_condition(fm_ctx* c, int32_t seq, const float* mem_dev) {
   if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
   if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range [0,%d)", seq, c->D.S);
   if (!mem_dev) return fail(c, FM_EINVAL, "null condition memory");
-  int rc = c->bf16 ? prefill_impl<f16_t>(c, seq, mem_dev) : prefill_impl<float>(c, seq, mem_dev);
+  int rc = c->bf16 ? prefill_impl<f16_t>(c, seq, mem_dev, c->stage) : prefill_impl<float>(c, seq, mem_dev, c->stage);
   if (rc == FM_OK) { c->prefilled[seq] = true; c->len_bound[seq] = 0; }
   return rc;
 }
@@ -899,7 +910,7 @@ int fm_verify_block(fm_ctx* c, const int32_t* block_tok, const int32_t* block_le
 int fm_commit(fm_ctx* c, const int32_t* accepted) {
   if (!c) return FM_EINVAL;
   if (!accepted) return fail(c, FM_EINVAL, "null accepted buffer");
-  hipLaunchKernelGGL(k_commit, dim3(1), dim3(64), 0, c->stream, c->st, c->D, accepted);
+  hipLaunchKernelGGL(k_commit, dim3(1), dim3(64), 0, c->stream, c->st, c->D, accepted, pass_failed(c));
   HIPCHK(c, hipGetLastError());
   for (int s = 0; s < c->D.S; s++) c->len_bound[s] = std::min(c->len_bound[s] + c->D.Bm, c->D.maxtok);
   c->commits++;
@@ -951,6 +962,19 @@ int fm_debug_profile(fm_ctx* c, uint64_t* host_out, int32_t n) {
   std::vector<unsigned long long> init(1024, 0ull);
   init[0] = ~0ull;
   HIPCHK(c, hipMemcpy(c->pk.prof, init.data(), 1024 * 8, hipMemcpyHostToDevice));   // re-arm
+  return FM_OK;
+}
+
+int fm_debug_draft(fm_ctx* c, int32_t which, float* host_out) {
+  if (!c) return FM_EINVAL;
+  const Dims& D = c->D;
+  if (which == -1 || which == -2) { c->smp.keep_rows = which == -1 ? 1 : 0; return FM_OK; }
+  if (!host_out) return fail(c, FM_EINVAL, "null output");
+  const float* src = which == 0 ? c->smp.qrow : which == 1 ? c->lab_v : which == 2 ? c->lab_f : nullptr;
+  if (!src) return fail(c, FM_EINVAL, "draft buffer %d out of range", which);
+  const size_t n = which == 0 ? (size_t)D.S * D.Bm * D.V : which == 1 ? (size_t)D.S * std::max(D.nspv, 1) * 3 : (size_t)D.S * std::max(D.nhfv, 1) * 3;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  HIPCHK(c, hipMemcpy(host_out, src, n * sizeof(float), hipMemcpyDeviceToHost));
   return FM_OK;
 }
 
@@ -1079,68 +1103,108 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
     if (!c->prefilled[s]) return fail(c, FM_ESTATE, "sequence %d has no condition memory", s);
   TRY(fm_set_budget(c, max_faces));
   const Dims& D = c->D;
-  HIPCHK(c, hipMemsetAsync(c->st.acc_hist, 0, 32 * sizeof(unsigned long long), c->stream));
+  // events: whole loop, lagged flag copy, and the four phase marks of a sampled step; destroyed on every way out
+  enum { E_BEGIN, E_END, E_FLAG, E_P0, E_P1, E_P2, E_P3, E_COUNT };
+  struct Events {
+    hipEvent_t e[E_COUNT] = {};
+    ~Events() { for (hipEvent_t x : e) if (x) (void)hipEventDestroy(x); }
+  } ev;
+  for (int i = 0; i < E_COUNT; i++) HIPCHK(c, hipEventCreate(&ev.e[i]));
+  HIPCHK(c, hipMemsetAsync(c->st.acc_hist, 0, 3 * 32 * sizeof(unsigned long long), c->stream));
   HIPCHK(c, hipMemsetAsync(c->st.counters, 0, 2 * sizeof(unsigned long long), c->stream));
-  hipEvent_t e0, e1, eflag;
-  HIPCHK(c, hipEventCreate(&e0)); HIPCHK(c, hipEventCreate(&e1)); HIPCHK(c, hipEventCreate(&eflag));
-  HIPCHK(c, hipEventRecord(e0, c->stream));
-  const long max_steps = 9L * max_faces + 1;
+  HIPCHK(c, hipEventRecord(ev.e[E_BEGIN], c->stream));
+  const long max_steps = 9L * max_faces + 1 + 128;     // + the steps a failed pass of the single-launch kernel may void
   const int check_every = 32;
-  bool pending = false, done = false;
-  long commits_at_copy = 0;
+  bool pending = false, done = false, phase_pending = false;
+  long commits_at_copy = 0, phase_samples = 0;
+  double ms_phase[3] = {0.0, 0.0, 0.0};
+  auto take_phases = [&]() -> int {
+    float a = 0.f, b = 0.f, d = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&a, ev.e[E_P0], ev.e[E_P1]));
+    HIPCHK(c, hipEventElapsedTime(&b, ev.e[E_P1], ev.e[E_P2]));
+    HIPCHK(c, hipEventElapsedTime(&d, ev.e[E_P2], ev.e[E_P3]));
+    ms_phase[0] += a; ms_phase[1] += b; ms_phase[2] += d;
+    phase_samples++;
+    phase_pending = false;
+    return FM_OK;
+  };
   int rc = FM_OK;
   for (long step = 0; step < max_steps && !done && rc == FM_OK; step++) {
+    // one step per interval carries the phase marks, once the marks of the previous sample have been read
+    bool sample = step % check_every == 1;
+    if (sample && phase_pending) {
+      if (hipEventQuery(ev.e[E_P3]) == hipSuccess) TRY(take_phases());
+      else { (void)hipGetLastError(); sample = false; }
+    }
+    if (sample) HIPCHK(c, hipEventRecord(ev.e[E_P0], c->stream));
     rc = c->bf16 ? draft_impl<f16_t>(c, c->gen_tok, c->gen_len, speculative) : draft_impl<float>(c, c->gen_tok, c->gen_len, speculative);
     if (rc == FM_OK && speculative && c->correct_hist > 0) rc = fm_correct(c, c->gen_tok, c->gen_len, nullptr);
+    if (rc == FM_OK && sample) HIPCHK(c, hipEventRecord(ev.e[E_P1], c->stream));
     if (rc == FM_OK)
       rc = c->bf16 ? verify_impl<f16_t>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc)
                    : verify_impl<float>(c, c->gen_tok, c->gen_len, nullptr, c->gen_acc);
+    if (rc == FM_OK && sample) HIPCHK(c, hipEventRecord(ev.e[E_P2], c->stream));
     if (rc == FM_OK) rc = fm_commit(c, c->gen_acc);
+    if (rc == FM_OK && sample) { HIPCHK(c, hipEventRecord(ev.e[E_P3], c->stream)); phase_pending = true; }
     if (rc == FM_OK && c->sticky_error) rc = FM_EINVAL;
     if (rc != FM_OK) break;
     if ((step + 1) % check_every == 0) {
       // look at the flag copied one interval ago, then queue the next copy: the device never waits for the host
       if (pending) {
-        HIPCHK(c, hipEventSynchronize(eflag));
+        HIPCHK(c, hipEventSynchronize(ev.e[E_FLAG]));
         if (c->host_flag[0] == 0) done = true;
         // the lengths of one interval ago bound today's: every commit since then added at most block_max
         const long since = c->commits - commits_at_copy;
         for (int s = 0; s < D.S; s++)
           c->len_bound[s] = (int)std::min<long>(c->len_bound[s], c->host_flag[16 + s] + since * D.Bm);
+        if (c->host_flag[1] != 0) {
+          // the single-launch verify kernel gave up in some pass of the last interval: nothing was accepted or
+          // committed since, so the loop simply goes on with one launch per operator (message kept in fm_last_error)
+          HIPCHK(c, hipStreamSynchronize(c->stream));
+          (void)check_persist(c);
+          pending = false;
+          continue;
+        }
       }
       if (!done) {
         HIPCHK(c, hipMemcpyAsync(c->host_flag, c->st.alive, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+        if (c->persist)
+          HIPCHK(c, hipMemcpyAsync(c->host_flag + 1, c->pk.abort_word, sizeof(int), hipMemcpyDeviceToHost, c->stream));
+        else
+          c->host_flag[1] = 0;
         HIPCHK(c, hipMemcpyAsync(c->host_flag + 16, c->st.P, sizeof(int) * (size_t)D.S, hipMemcpyDeviceToHost, c->stream));
         commits_at_copy = c->commits;
-        HIPCHK(c, hipEventRecord(eflag, c->stream));
+        HIPCHK(c, hipEventRecord(ev.e[E_FLAG], c->stream));
         pending = true;
       }
     }
   }
-  if (rc == FM_OK) {
-    HIPCHK(c, hipEventRecord(e1, c->stream));
-    // outputs: x_1 .. x_P per sequence
-    for (int s = 0; s < D.S; s++)
-      HIPCHK(c, hipMemcpyAsync(out_tok + (size_t)s * D.maxtok, c->st.hist + (size_t)s * (D.maxtok + 1) + 1, (size_t)D.maxtok * 4,
-                               hipMemcpyDeviceToDevice, c->stream));
-    HIPCHK(c, hipMemcpyAsync(out_len, c->st.P, (size_t)D.S * 4, hipMemcpyDeviceToDevice, c->stream));
-    HIPCHK(c, hipStreamSynchronize(c->stream));
-    TRY(check_persist(c));
-    if (stats) {
-      unsigned long long cnt[2], hist[32];
-      HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));
-      HIPCHK(c, hipMemcpy(hist, c->st.acc_hist, sizeof hist, hipMemcpyDeviceToHost));
-      float ms = 0.f;
-      HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
-      stats->tokens = (int64_t)cnt[1];
-      stats->steps = 0;
-      for (int i = 0; i < 32; i++) { stats->acc_hist[i] = (int64_t)hist[i]; }
-      stats->steps = (int64_t)cnt[0];
-      stats->ms_total = ms;
-    }
+  if (rc != FM_OK) return rc;
+  HIPCHK(c, hipEventRecord(ev.e[E_END], c->stream));
+  // outputs: x_1 .. x_P per sequence
+  for (int s = 0; s < D.S; s++)
+    HIPCHK(c, hipMemcpyAsync(out_tok + (size_t)s * D.maxtok, c->st.hist + (size_t)s * (D.maxtok + 1) + 1, (size_t)D.maxtok * 4,
+                             hipMemcpyDeviceToDevice, c->stream));
+  HIPCHK(c, hipMemcpyAsync(out_len, c->st.P, (size_t)D.S * 4, hipMemcpyDeviceToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  TRY(check_persist(c));      // a failure in the very last interval: reported, the caller may call again
+  if (phase_pending) TRY(take_phases());
+  if (stats) {
+    unsigned long long cnt[2], hist[3 * 32];
+    HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(hist, c->st.acc_hist, sizeof hist, hipMemcpyDeviceToHost));
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, ev.e[E_BEGIN], ev.e[E_END]));
+    stats->steps = (int64_t)cnt[0];
+    stats->tokens = (int64_t)cnt[1];
+    for (int k = 0; k < 3; k++)
+      for (int i = 0; i < 32; i++) stats->acc_hist[k][i] = (int64_t)hist[k * 32 + i];
+    stats->ms_total = ms;
+    const double n = phase_samples > 0 ? (double)phase_samples : 1.0;
+    stats->ms_draft = ms_phase[0] / n; stats->ms_verify = ms_phase[1] / n; stats->ms_commit = ms_phase[2] / n;
+    stats->phase_samples = phase_samples;
   }
-  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); (void)hipEventDestroy(eflag);
-  return rc;
+  return FM_OK;
 }
 
 }  // extern "C"

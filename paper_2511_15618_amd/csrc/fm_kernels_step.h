@@ -24,8 +24,10 @@ struct StateDev {
   int* hist;          // [S][maxtok + 1], hist[p] = x_p
   int* budget;        // [1]
   int* alive;         // [1] unfinished sequences; doubles as the run flag of the step
-  unsigned long long* acc_hist;  // [32]
+  unsigned long long* acc_hist;  // [3][32]: accepted lengths of steps whose block carried coordinate-level drafts only /
+                                 // a fresh point-level prediction / a fresh face-level prediction
   unsigned long long* counters;  // [0] steps, [1] tokens
+  int* kind;                     // [S] which of the three the block built by the last draft was
 };
 
 __device__ __forceinline__ int eff_block_len(const StateDev& st, const Dims& D, int s, const int* block_len) {
@@ -88,12 +90,14 @@ __global__ __launch_bounds__(256) void k_verify_setup(StateDev st, Dims D, InvFr
 
 // accepted = 1 + number of leading drafts that equal the backbone's greedy prediction; with sampled decoding
 // (accflag != null) 1 + number of leading drafts that passed the rejection test (flag of row i is about draft i + 1)
-__global__ void k_accept(StateDev st, Dims D, int* __restrict__ accepted_out, const int* __restrict__ accflag) {
+// (failed != null and *failed != 0: the forward pass gave up and its logits mean nothing; every accepted length is 0)
+__global__ void k_accept(StateDev st, Dims D, int* __restrict__ accepted_out, const int* __restrict__ accflag,
+                         const unsigned* __restrict__ failed) {
   const int s = threadIdx.x;
   if (s >= D.S) return;
   const int len = st.vlen[s];
   int a = 0;
-  if (len > 0) {
+  if (len > 0 && !(failed && *failed)) {
     a = 1;
     if (accflag) while (a < len && accflag[s * D.Bm + a - 1]) a++;
     else while (a < len && st.vtok[s * D.Bm + a] == st.y[s * D.Bm + a - 1]) a++;
@@ -102,17 +106,19 @@ __global__ void k_accept(StateDev st, Dims D, int* __restrict__ accepted_out, co
   if (accepted_out) accepted_out[s] = a;
 }
 
-__global__ void k_commit(StateDev st, Dims D, const int* __restrict__ accepted) {
+// An accepted length of 0 (a pass that did not complete) leaves the sequence as it is.
+__global__ void k_commit(StateDev st, Dims D, const int* __restrict__ accepted, const unsigned* __restrict__ failed) {
   const int s = threadIdx.x;
   __shared__ int any_live;
+  if (failed && *failed) return;
   if (s == 0) any_live = 0;
   __syncthreads();
   if (s < D.S) {
     const int len = st.vlen[s];
-    if (len > 0) {
+    if (len > 0 && accepted[s] > 0) {
       any_live = 1;
       int a = accepted[s];
-      a = max(1, min(a, len));
+      a = min(a, len);
       for (int i = 1; i < a; i++)
         if (st.vtok[s * D.Bm + i] == D.eos) { a = i; break; }   // an accepted EOS draft is not fed: it becomes the main token
       int P = st.P[s];
@@ -125,7 +131,7 @@ __global__ void k_commit(StateDev st, Dims D, const int* __restrict__ accepted) 
       st.main[s] = mainTok;
       st.fin[s] = (mainTok == D.eos || P >= st.budget[0]) ? 1 : 0;
       st.vlen[s] = 0;
-      atomicAdd(&st.acc_hist[min(a, 31)], 1ull);
+      atomicAdd(&st.acc_hist[min(max(st.kind[s], 0), 2) * 32 + min(a, 31)], 1ull);
       atomicAdd(&st.counters[1], (unsigned long long)a);
     }
   }
@@ -181,6 +187,7 @@ struct Sampling {
   float* qsum;                  // [S][Bm]    its sum over the admissible tokens
   int* qtok;                    // [S][Bm]    the token drawn from it (-1: none)
   int* accflag;                 // [S][Bm]    row i: draft i + 1 passed the rejection test
+  int keep_rows;                // test hook: greedy decoding also leaves the averaged rows in qrow (read by fm_debug_draft)
 };
 
 __device__ __forceinline__ float sample_uniform(unsigned long long seed, int purpose, int seq, int pos);
@@ -449,7 +456,7 @@ __global__ __launch_bounds__(1024) void k_merge(StateDev st, Dims D, DraftRows R
   const int P = st.P[s], budget = st.budget[0];
   if (threadIdx.x == 0) tok[0] = st.main[s];
   if (P == 0 || !speculative) {
-    if (threadIdx.x == 0) block_len[s] = 1;
+    if (threadIdx.x == 0) { block_len[s] = 1; st.kind[s] = 0; }
     return;
   }
   const int spos = P - 1;
@@ -461,6 +468,7 @@ __global__ __launch_bounds__(1024) void k_merge(StateDev st, Dims D, DraftRows R
     st.basec[s] = basec; st.basev[s] = basev; st.basef[s] = basef;
     if (R.firev[s]) st.firedv[s] = spos / 3;
     if (R.firef[s]) st.firedf[s] = spos / 9;
+    st.kind[s] = R.firef[s] ? 2 : R.firev[s] ? 1 : 0;
   }
   const int nlim = D.ban ? D.nbins : D.V;
   int len = 1;
@@ -522,7 +530,10 @@ __global__ __launch_bounds__(1024) void k_merge(StateDev st, Dims D, DraftRows R
           }
 #pragma unroll
           for (int k = 0; k < 4; k++)
-            if (i0 + 64 * k < nlim) argmax_merge(bv, bi, a[k] * inv, i0 + 64 * k);
+            if (i0 + 64 * k < nlim) {
+              argmax_merge(bv, bi, a[k] * inv, i0 + 64 * k);
+              if (sm.keep_rows) sm.qrow[((long)s * D.Bm + idx) * D.V + i0 + 64 * k] = a[k] * inv;
+            }
         }
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {

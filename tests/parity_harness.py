@@ -5,6 +5,15 @@ draft block, the verify logits (max-abs), the greedy predictions, the accepted l
 committed lengths.  Where a token differs, the oracle's own scores decide: if the margin between
 its choice and the device's choice is below the tolerance the flip is allowed and the oracle is
 forced onto the device's token; anything else is a failure.
+
+Tolerances.  `tol` is the bar on logits (max-abs).  Everything that is decided by a softmax of logits is judged in
+log space, where that bar carries over without reference to the size of the probabilities: if every logit of a row is
+within tol of the oracle's, every probability of its softmax is within a factor exp(+-2 tol) (numerator and normaliser
+each move by at most exp(+-tol)), and so is a mean of such rows.  Hence: averaged draft distributions and label rows
+are compared element by element as |log p_dev - log p_ref| <= 2 tol; a differing greedy draft token or label is allowed
+only if the oracle's own log-probabilities of the two candidates are within 2 tol; a differing rejection decision only
+if |log(u q(x)) - log p(x)| <= 4 tol; a differing inverse-CDF draw only if u lies inside the interval that the
+cumulative weight boundaries of the chosen index can reach when every weight moves by its bound.
 """
 from __future__ import annotations
 
@@ -31,14 +40,21 @@ class Report:
         self.corrected_blocks = 0
         self.accepted = []
         self.block_lens = []
+        self.max_dist_logerr = 0.0      # averaged draft distributions, |log p_dev - log p_ref|
+        self.max_dist_abserr = 0.0      # the same rows, |p_dev - p_ref|
+        self.dist_rows = 0
+        self.max_label_logerr = 0.0
+        self.label_rows = 0
 
     def __repr__(self):
         return (f"steps={self.steps} max|dlogit|={self.max_logit_err:.3e} token_flips={self.token_flips} "
                 f"draft_flips={self.draft_flips} mean_acc={np.mean(self.accepted) if self.accepted else 0:.2f}"
+                + (f" dist_rows={self.dist_rows} max|dlog q|={self.max_dist_logerr:.2e} max|dq|={self.max_dist_abserr:.2e}" if self.dist_rows else "")
+                + (f" label_rows={self.label_rows} max|dlog label|={self.max_label_logerr:.2e}" if self.label_rows else "")
                 + (f" points={self.points} label_flips={self.label_flips} corrected_blocks={self.corrected_blocks}" if self.points else ""))
 
 
-def make_pair(cfg, work=np.float64, max_tokens=None):
+def make_pair(cfg, work=np.float64, max_tokens=None, prefill="prefill_condition"):
     w = si.make_weights(cfg, 0)
     model = Model(cfg, w, work=work)
     fm = FlashMesh(config_struct(cfg, max_tokens=max_tokens))
@@ -46,28 +62,68 @@ def make_pair(cfg, work=np.float64, max_tokens=None):
     fm.load_weights(si.pack_blob(cfg, w))
     mems = [si.make_memory(cfg, s) for s in range(cfg.batch)]
     for s, m in enumerate(mems):
-        fm.prefill_condition(s, torch.from_numpy(m).cuda())
+        getattr(fm, prefill)(s, torch.from_numpy(m).cuda())
     states = [SeqState(model, mems[s], max_tokens or cfg.max_tokens) for s in range(cfg.batch)]
     return model, fm, states
 
 
-def _cdf_margin(w, u, idx):
-    """How far u is outside the cumulative-weight interval of idx (0 if idx is an exact inverse-CDF answer)."""
-    c = np.cumsum(np.asarray(w, np.float64))
-    c = c / c[-1]
-    lo = c[idx - 1] if idx > 0 else 0.0
-    return max(lo - u, u - c[idx], 0.0)
+def _log_err(dev, ref):
+    """max |log dev - log ref| over the entries the oracle gives real mass (the rest must be negligible on the device too)."""
+    dev, ref = np.asarray(dev, np.float64), np.asarray(ref, np.float64)
+    big = ref > 1e-25
+    assert np.all(dev[~big] < 1e-20), "mass where the oracle has none"
+    return float(np.abs(np.log(np.maximum(dev[big], 1e-300)) - np.log(ref[big])).max())
+
+
+def _cdf_draw_possible(w, err, u, idx) -> bool:
+    """Can the inverse CDF over weights within +-err of w (index order, normalised by their own sum) return idx for u?"""
+    w, err = np.asarray(w, np.float64), np.asarray(err, np.float64)
+    cw, ce = np.cumsum(w), np.cumsum(err)
+
+    def reach(k):        # (lowest, highest) value the normalised cumulative weight through index k can take
+        if k < 0:
+            return 0.0, 0.0
+        A, EA, B, EB = cw[k], ce[k], cw[-1] - cw[k], ce[-1] - ce[k]
+        a_lo, a_hi, b_lo, b_hi = max(A - EA, 0.0), A + EA, max(B - EB, 0.0), B + EB
+        lo = a_lo / (a_lo + b_hi) if a_lo + b_hi > 0 else 0.0
+        hi = a_hi / (a_hi + b_lo) if a_hi + b_lo > 0 else 1.0
+        return lo, hi
+    return reach(idx - 1)[0] <= u < reach(idx)[1] or (u >= reach(idx)[1] and idx == len(w) - 1)
+
+
+def _check_dist_rows(rep, dev_rows, merged, nlim, tol, cfg):
+    """Averaged draft distribution behind every draft index: device row i against the oracle's, element by element."""
+    for i, ref in enumerate(merged, start=1):
+        dev = dev_rows[i, :nlim]
+        rep.max_dist_logerr = max(rep.max_dist_logerr, _log_err(dev, ref[:nlim]))
+        rep.max_dist_abserr = max(rep.max_dist_abserr, float(np.abs(dev - ref[:nlim]).max()))
+        rep.dist_rows += 1
+    assert rep.max_dist_logerr <= 2.0 * tol, ("draft distribution beyond tolerance", rep.steps, rep.max_dist_logerr)
+    if cfg.dtype == "f32":
+        assert rep.max_dist_abserr <= 1e-5, ("draft distribution beyond 1e-5", rep.steps, rep.max_dist_abserr)
+
+
+def _check_label_rows(rep, cfg, st, lab_v, lab_f, tol):
+    """Label distributions the two pipelines hold (Sec. 3.2): point pipeline row k - 1 is vertex v + k of its last
+    firing at vertex token v, face pipeline row j - 1 is vertex 3f + j of its last firing at face token f."""
+    for rows, dev, first in ((st.labels["v"], lab_v, st.fired_v), (st.labels["f"], lab_f, 3 * st.fired_f)):
+        for u, ref in rows.items():
+            rep.max_label_logerr = max(rep.max_label_logerr, _log_err(dev[u - first - 1], ref))
+            rep.label_rows += 1
+    assert rep.max_label_logerr <= 2.0 * tol, ("label distribution beyond tolerance", rep.steps, rep.max_label_logerr)
 
 
 def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work=np.float64, check_logits=True,
-             correct_hist=0, sampling=None):
+             correct_hist=0, sampling=None, pair=None, prefill="prefill_condition"):
     """Run the decode loop on both sides; returns (Report, device token streams).
 
     correct_hist > 0: the correct stage runs between draft and verify on both sides.  The device's labels must be the
     oracle's except where the oracle's own label distribution separates the two by less than the tolerance; with the
     device's labels the oracle's integer correction must reproduce the device's corrected block exactly."""
-    model, fm, states = make_pair(cfg, work=work)
+    model, fm, states = pair if pair is not None else make_pair(cfg, work=work, prefill=prefill)      # pair: a run that is already under way
     fm.set_budget(faces)
+    fm.keep_draft_rows(drafts == "native" and replay is None)
+    rel = float(np.expm1(2.0 * tol))          # relative bound on every probability that comes out of a softmax
     if correct_hist:
         fm.set_correct(correct_hist)
     if sampling is not None:
@@ -99,6 +155,9 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
             ln[:] = torch.from_numpy((1 - st_dev[:, 4]).astype(np.int32)).cuda()
         else:
             fm.draft(tok, ln)
+        native = drafts == "native" and replay is None
+        h_dist = fm.debug_draft(0) if native else None                  # averaged draft distributions [S, Bm, V]
+        h_labv, h_labf = (fm.debug_draft(1), fm.debug_draft(2)) if native and correct_hist else (None, None)
         h_pre = tok.cpu().numpy() if correct_hist else None
         if correct_hist and drafts != "none":
             fm.correct(tok, ln, labels_dev)
@@ -121,10 +180,12 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
                 merged = []
                 block_ref = osp.draft(model, st, budget, merged, sampling, seq=s)
                 assert len(block_ref) == len(block_dev) and block_ref[0] == block_dev[0], (rep.steps, s, block_ref, block_dev)
+                _check_dist_rows(rep, h_dist[s], merged, nlim, tol, cfg)
                 for i in range(1, len(block_ref)):
                     if block_ref[i] != block_pre[i]:
-                        gap = _cdf_margin(merged[i - 1][:nlim], smp.uniform(seed, s, st.P + i, smp.DRAFT), block_pre[i])
-                        assert gap <= tol, ("sampled draft beyond tolerance", rep.steps, s, i, gap)
+                        w = merged[i - 1][:nlim]
+                        assert _cdf_draw_possible(w, rel * w, smp.uniform(seed, s, st.P + i, smp.DRAFT), block_pre[i]), \
+                            ("sampled draft beyond tolerance", rep.steps, s, i)
                         rep.draft_flips += 1
                 changed = [i for i in range(1, len(block_dev)) if block_dev[i] != block_pre[i]]
                 rep.corrected_blocks += int(bool(changed))
@@ -143,15 +204,17 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
                 if a_ref != a:
                     k = min(a_ref, a)                  # the first decision that differs is about draft k (row k - 1)
                     x = block_dev[k]
-                    gap = abs(ua[k - 1] * (1.0 if qs[k - 1] is None else qs[k - 1][x]) - (ps[k - 1][x] if x < nlim else 0.0))
-                    assert gap <= tol, ("rejection test beyond tolerance", rep.steps, s, k, gap)
+                    assert x < nlim
+                    gap = abs(np.log(ua[k - 1] * (1.0 if qs[k - 1] is None else qs[k - 1][x])) - np.log(ps[k - 1][x]))
+                    assert gap <= 4.0 * tol, ("rejection test beyond tolerance", rep.steps, s, k, gap)
                     rep.token_flips += 1
                 w = ps[a - 1] if a == B else smp.residual(ps[a - 1], qs[a - 1], block_dev[a])
                 tok_ref, tok_dev = smp.inverse_cdf(w, ur[a - 1]), int(main_after[s])
                 if tok_ref != tok_dev:
                     assert 0 <= tok_dev < nlim
-                    gap = _cdf_margin(w, ur[a - 1], tok_dev)
-                    assert gap <= tol, ("resampled token beyond tolerance", rep.steps, s, a, gap)
+                    qa = None if a == B else qs[a - 1]
+                    err = rel * (ps[a - 1] + (qa if qa is not None else 0.0))
+                    assert _cdf_draw_possible(w, err, ur[a - 1], tok_dev), ("resampled token beyond tolerance", rep.steps, s, a)
                     rep.token_flips += 1
                 y = [-1] * B
                 y[a - 1] = tok_dev
@@ -166,12 +229,15 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
                 block_ref = osp.draft(model, st, budget, merged)
                 assert len(block_ref) == len(block_pre), (rep.steps, s, block_ref, block_pre)
                 assert block_ref[0] == block_pre[0]
+                _check_dist_rows(rep, h_dist[s], merged, nlim, tol, cfg)
                 for i in range(1, len(block_ref)):
                     if block_ref[i] != block_pre[i]:
                         dist = merged[i - 1]
-                        gap = dist[block_ref[i]] - dist[block_pre[i]]
-                        assert gap <= tol, ("draft token beyond tolerance", rep.steps, s, i, gap)
+                        gap = np.log(dist[block_ref[i]]) - np.log(dist[block_pre[i]])
+                        assert gap <= 2.0 * tol, ("draft token beyond tolerance", rep.steps, s, i, gap)
                         rep.draft_flips += 1
+                if correct_hist:
+                    _check_label_rows(rep, cfg, st, h_labv[s], h_labf[s], tol)
                 if correct_hist and len(block_pre) >= 4:
                     u0, u1 = ocr.draft_vertex_range(st.P, len(block_pre))
                     ref = ocr.point_labels(st, u0, u1)
@@ -182,8 +248,8 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
                         rep.points += 1
                         if lab_dev != lab_ref:
                             assert dist is not None and 0 <= lab_dev < 3, ("label", rep.steps, s, u, lab_ref, lab_dev)
-                            gap = dist[lab_ref] - dist[lab_dev]
-                            assert gap <= tol, ("label beyond tolerance", rep.steps, s, u, gap)
+                            gap = np.log(dist[lab_ref]) - np.log(dist[lab_dev])
+                            assert gap <= 2.0 * tol, ("label beyond tolerance", rep.steps, s, u, gap)
                             rep.label_flips += 1
                         labels[u] = lab_dev
                     assert all(int(v) == -1 for v in h_lab[s, max(u1 - u0 + 1, 0):])

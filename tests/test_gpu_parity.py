@@ -163,7 +163,6 @@ def test_config3_shape_short_lockstep():
     assert rep.steps == 5 and len(rep.accepted) == 5 * cfg.batch
 
 
-@pytest.mark.skipif(os.environ.get("FM_LONG") != "1", reason="tens of GB of host memory and minutes of CPU oracle time; set FM_LONG=1")
 def test_config4_shape_short_lockstep():
     """configs[4] at its real widths (d=1536, 48 blocks, 4 sequences, block 18) for a few lock-step steps."""
     _need_gpu()
