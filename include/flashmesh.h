@@ -63,6 +63,8 @@ typedef struct {
                            of the coordinate level sees keys [p-W+1, p], the vertex and face levels W/3 and W/9
                            of their own positions, the K/V caches are rings of W + block_max + 2 positions (rounded
                            up to 128) and max_tokens only bounds the length of the emitted stream                 */
+  int32_t rules_off;    /* schedule rules of the supplement's "Optimizations" to switch OFF (0 = the paper's final schedule):
+                           bit 0 = rule (A): the point level then also fires at face split nodes                       */
 } fm_config;
 
 typedef struct {

@@ -28,10 +28,11 @@ def coord_targets(s: int, Dc: int):
     return [s + 1 + d for d in range(1, Dc + 1)]
 
 
-def point_fires(s: int, fired_v: int, m: int) -> bool:
-    """Point level fires once per vertex token v = floor(s/3), except where the face level does (rule A)."""
+def point_fires(s: int, fired_v: int, m: int, rule_a: bool = True) -> bool:
+    """Point level fires once per vertex token v = floor(s/3), except where the face level does (rule A; with the
+    rule switched off it fires there as well and both levels cover the same positions)."""
     v = s // 3
-    return m > 0 and s >= 0 and v % 3 != 0 and fired_v != v
+    return m > 0 and s >= 0 and (v % 3 != 0 or not rule_a) and fired_v != v
 
 
 def face_fires(s: int, fired_f: int, n: int) -> bool:
@@ -119,7 +120,7 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None, sampling=
 
     # point level: SP heads on the vertex feature, repeat x3 (Eq. 2, no skip exists for a future
     # token), one coordinate-level HF block per offset
-    if point_fires(s, st.fired_v, mm):
+    if point_fires(s, st.fired_v, mm, bool(getattr(cfg, "rule_a", 1))):
         v = s // 3
         rows = {}
         labels = {}

@@ -23,7 +23,7 @@ class FmConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "d_model", "n_heads", "ffn_mult", "n_bins", "l_cpre", "l_cpost", "l_vpre", "l_vpost", "l_face", "mem_len",
         "dtype", "max_batch", "max_tokens", "draft_coord", "draft_point", "draft_face", "hf_ffn_mult",
-        "ban_specials")] + [("rope_base", C.c_float), ("rms_eps", C.c_float), ("window", C.c_int32)]
+        "ban_specials")] + [("rope_base", C.c_float), ("rms_eps", C.c_float), ("window", C.c_int32), ("rules_off", C.c_int32)]
 
 
 class FmStats(C.Structure):
@@ -99,7 +99,7 @@ def config_struct(cfg, max_batch=None, max_tokens=None) -> FmConfig:
         max_batch=max_batch or cfg.batch, max_tokens=max_tokens or cfg.max_tokens,
         draft_coord=cfg.draft_coord, draft_point=cfg.draft_point, draft_face=cfg.draft_face,
         hf_ffn_mult=cfg.hf_ffn_mult, ban_specials=cfg.ban_specials, rope_base=cfg.rope_base, rms_eps=cfg.rms_eps,
-        window=getattr(cfg, "window", 0))
+        window=getattr(cfg, "window", 0), rules_off=0 if getattr(cfg, "rule_a", 1) else 1)
 
 
 class FlashMesh:

@@ -30,6 +30,8 @@ struct Layer {
   float *g1, *g2, *g3;
   void *wqkv, *wo, *cq, *ckv, *co, *w1, *w2;  // storage type T, [out, in]
   void* wqkv_rp;                               // persistent path: q/k tiles hold whole rotary pairs
+  void* wcqo;                                  // persistent path: cq diag(g2) wo (tiled), folded at load time
+  size_t off_wo, off_cq;                       // where wo and cq start in the weight blob
   void *Kc, *Vc;                               // [S][H][cap][64]
   void *Km, *Vm;                               // [S][H][M][64]
   int level;                                   // 0 coordinate, 1 vertex, 2 face
@@ -506,9 +508,12 @@ int build_params(fm_ctx* c) {
       } else {
         lin(L.wqkv, 3 * d, d);   // wq, wk, wv are consecutive in the blob
       }
+      L.off_wo = off;
       lin(L.wo, d, d);
       item(L.g2, d, true);
+      L.off_cq = off;
       lin(L.cq, d, d);
+      if (c->persist) TRY(dalloc_t(c, &L.wcqo, d * d));
       lin(L.ckv, 2 * d, d);    // ck, cv consecutive
       lin(L.co, d, d);
       item(L.g3, d, true);
@@ -573,7 +578,7 @@ int build_persist(fm_ctx* c) {
       PkLayer p{};
       p.g1 = (pk_cf_t)L.g1; p.g2 = (pk_cf_t)L.g2; p.g3 = (pk_cf_t)L.g3;
       p.wqkv = (pk_cw_t)L.wqkv_rp; p.wo = (pk_cw_t)L.wo; p.cq = (pk_cw_t)L.cq; p.co = (pk_cw_t)L.co;
-      p.w1 = (pk_cw_t)L.w1; p.w2 = (pk_cw_t)L.w2;
+      p.w1 = (pk_cw_t)L.w1; p.w2 = (pk_cw_t)L.w2; p.wcqo = (pk_cw_t)L.wcqo;
       p.Kc = (pk_w_t)L.Kc; p.Vc = (pk_w_t)L.Vc; p.Km = (pk_cw_t)L.Km; p.Vm = (pk_cw_t)L.Vm;
       p.level = L.level;
       p.last = i + 1 == c->stacks[st].size();
@@ -620,6 +625,7 @@ int build_persist(fm_ctx* c) {
   TRY(dalloc(c, &a.newK, (size_t)D.H * RS * 32)); TRY(dalloc(c, &a.newV, (size_t)D.H * RS * 32));
   TRY(dalloc(c, &a.partS, (size_t)D.H * PK_MAXSPLIT * RG * PK_PART)); TRY(dalloc(c, &a.partX, (size_t)D.H * PK_MAXSPLIT * RG * PK_PART));
   TRY(dalloc(c, &a.w2part, (d / 16) * RG * 3 * 256));
+  TRY(dalloc(c, &a.ssqB, nl * (d / 16) * RS));
   TRY(dalloc(c, &a.abort_word, 16));
   if (hipMemset(a.abort_word + 1, 0xFF, 4) != hipSuccess) return fail(c, FM_EHIP, "hipMemset failed");
   a.run_flag = c->st.alive;
@@ -631,11 +637,29 @@ int build_persist(fm_ctx* c) {
   // test hooks for the bounded waits: a shorter bound, and an embedding that publishes under the wrong tag
   a.timeout_ticks = PK_TIMEOUT_TICKS;
   a.test_skew = 0;
+  a.two_phase = 0;
+  if (const char* e = getenv("FM_PK_TWO_PHASE")) a.two_phase = atoi(e);
+  a.xcd_local = 1;
+  if (const char* e = getenv("FM_PK_XCD_LOCAL")) a.xcd_local = atoi(e);
   if (const char* e = getenv("FM_PK_TIMEOUT_TICKS")) a.timeout_ticks = strtoull(e, nullptr, 10);
   if (const char* e = getenv("FM_PK_TEST_SKEW")) a.test_skew = (unsigned)atoi(e);
+  // dynamic LDS: K/V blocks that the attention units stage before their queries arrive, 8 KiB per block and wave.
+  // As many as fit next to the kernel's static LDS on a 160 KiB compute unit, at most 4 (a range of 16 blocks per
+  // unit, i.e. half of the longest configured context at 16 ranges per head).
+  int blocks = a.RS == 32 ? 3 : 4;
+  if (const char* e = getenv("FM_PK_KV_LDS")) blocks = std::max(0, std::min(atoi(e), blocks));
+  while (blocks > 0) {
+    const int bytes = blocks * 4 * 8192;
+    const hipError_t e = a.RS == 32 ? hipFuncSetAttribute((const void*)k_verify_persist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)
+                                    : hipFuncSetAttribute((const void*)k_verify_persist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) break;
+    (void)hipGetLastError();
+    blocks--;
+  }
+  a.kv_lds_blocks = blocks;
+  c->pk_lds = (size_t)blocks * 4 * 8192;
   // all 256 workgroups must be resident at once: they wait for each other's results
   int dev = 0, cus = 0, per_cu = 0;
-  c->pk_lds = 0;   // the kernel uses static LDS only
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
       (a.RS == 32 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist<2>, 256, c->pk_lds)
                   : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_verify_persist<1>, 256, c->pk_lds)) != hipSuccess ||
@@ -745,6 +769,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   if (Bm > 27) return FM_EINVAL;  // rings hold 32 coordinate positions: block + 2 carried rows
   if (!(g.rope_base > 1.f) || !(g.rms_eps > 0.f)) return FM_EINVAL;
   if (g.window < 0 || g.window % 9 != 0) return FM_EINVAL;
+  if (g.rules_off & ~1) return FM_EINVAL;
 
   fm_ctx* c = new (std::nothrow) fm_ctx();
   if (!c) return FM_ENOMEM;
@@ -771,6 +796,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   D.Dc = g.draft_coord; D.m = g.draft_point; D.n = g.draft_face;
   D.nspv = std::max(D.m / 3 - 1, 0); D.nspf = std::max(D.n / 9 - 1, 0);
   D.nhfc = std::max(std::max(D.m, D.n) - 3, 0); D.nhfv = std::max(D.n / 3 - 1, 0);
+  D.ruleA = (g.rules_off & 1) ? 0 : 1;
   D.nbins = g.n_bins; D.ban = g.ban_specials ? 1 : 0; D.eos = g.n_bins + 1; D.pad = g.n_bins + 2;
   c->Vpad = (D.V + 63) / 64 * 64;
   c->Rc = D.S * D.Bm; c->Rv = D.S * D.VB; c->Rf = D.S * D.FB;
@@ -850,6 +876,25 @@ int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
     }
   }
   HIPCHK(c, hipGetLastError());
+  if (c->bf16 && c->stacks[0].size() && c->stacks[0][0].wcqo) {
+    // single-launch verify kernel: the cross-attention query projection folded into the output projection before it,
+    // W = cq diag(g2) wo per block, multiplied in fp32 from the blob's values and then tiled like any other weight
+    const size_t d = c->D.d;
+    float* tmp = nullptr;
+    if (hipMalloc((void**)&tmp, 3 * d * d * sizeof(float)) != hipSuccess) { (void)hipGetLastError(); return fail(c, FM_ENOMEM, "hipMalloc of the folding buffers failed"); }
+    int rc = FM_OK;
+    for (int st = 0; st < 5 && rc == FM_OK; st++)
+      for (Layer& L : c->stacks[st]) {
+        if (hipMemcpyAsync(tmp, blob + L.off_cq, d * d * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+            hipMemcpyAsync(tmp + d * d, blob + L.off_wo, d * d * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess) { rc = fail(c, FM_EHIP, "weight copy failed"); break; }
+        hipLaunchKernelGGL(k_fold_projections, dim3((unsigned)(d / 16), (unsigned)(d / 16)), dim3(16, 16), 0, c->stream, tmp, L.g2, tmp + d * d, tmp + 2 * d * d, (int)d);
+        hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, tmp + 2 * d * d, (f16_t*)L.wcqo, (int)d, (int)d, (int)d, 0);
+        if (hipStreamSynchronize(c->stream) != hipSuccess) { rc = fail(c, FM_EHIP, "weight folding failed"); break; }   // the blob ranges and tmp are reused
+      }
+    (void)hipFree(tmp);
+    TRY(rc);
+    HIPCHK(c, hipGetLastError());
+  }
   c->weights_loaded = true;
   return FM_OK;
 }

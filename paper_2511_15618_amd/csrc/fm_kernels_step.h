@@ -16,6 +16,7 @@ struct Dims {
   int nspv, nspf;        // SP heads at the point / face level
   int nhfc, nhfv;        // HF parameter sets at the coordinate / vertex level
   int nbins, ban, eos, pad;
+  int ruleA;             // rule (A) of the supplement: no point-level prediction at a face split node
 };
 
 struct StateDev {
@@ -277,7 +278,7 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
     const bool alive = !st.fin[s] && P > 0;
     const int spos = P - 1;
     const int v = alive ? spos / 3 : 0, f = alive ? spos / 9 : 0;
-    const bool firev = alive && D.m > 0 && (v % 3) != 0 && st.firedv[s] != v;
+    const bool firev = alive && D.m > 0 && ((v % 3) != 0 || !D.ruleA) && st.firedv[s] != v;
     const bool firef = alive && D.n > 0 && st.firedf[s] != f;
     if (threadIdx.x == 0) {
       R.alive[s] = alive; R.firev[s] = firev; R.firef[s] = firef;

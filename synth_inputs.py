@@ -47,6 +47,7 @@ class Config:
     rope_base: float = 10000.0
     rms_eps: float = 1e-6
     window: int = 0       # self-attention window in coordinate tokens (multiple of 9); 0 = the whole context
+    rule_a: int = 1       # supplement "Optimizations", rule (A): no point-level prediction where a face-level one fires
 
     @property
     def vocab(self) -> int:
@@ -110,6 +111,10 @@ TEST_CONFIGS = {
     "t_bf16_279": Config("t_bf16_279", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 27),
     "t_f32_2727": Config("t_f32_2727", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 12, 2, 27, 27),
     "t_bf16_c17": Config("t_bf16_c17", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 2, 8, 17, 0, 0),
+    # rule (A) of the supplement switched off: the point level also fires at face split nodes (three levels overlap there)
+    "t_f32_99_noA": Config("t_f32_99_noA", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 6, 2, 9, 9, rule_a=0),
+    "t_bf16_1815_noA": Config("t_bf16_1815_noA", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18, rule_a=0),
+    "t_bf16_99_b1_noA": Config("t_bf16_99_b1_noA", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9, rule_a=0),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
     # blocks longer than 16 tokens at one sequence (two row groups at the coordinate level of the single-launch verify kernel)
     "t_bf16_1815_b1": Config("t_bf16_1815_b1", 256, 4, 64, 2, 1, 2, 2, 3, 100, "bf16", 1, 30, 2, 15, 18),

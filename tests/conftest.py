@@ -15,3 +15,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def repo_root():
     return ROOT
+
+
+@pytest.fixture
+def say(capsys):
+    """Progress lines of long tests, written past pytest's capture so that a run that is watched from outside (a GPU
+    box kills a command that prints nothing for minutes) sees them while the test is still running."""
+    def _say(*a):
+        with capsys.disabled():
+            print(*a, flush=True)
+    return _say

@@ -29,6 +29,14 @@ from paper_2511_15618_amd import FlashMesh
 from paper_2511_15618_amd.binding import config_struct
 
 
+PROGRESS = None      # optional callable: long set-ups report where they are (tests point it at the `say` fixture)
+
+
+def _progress(*a):
+    if PROGRESS is not None:
+        PROGRESS(*a)
+
+
 class Report:
     def __init__(self):
         self.steps = 0
@@ -56,14 +64,19 @@ class Report:
 
 def make_pair(cfg, work=np.float64, max_tokens=None, prefill="prefill_condition"):
     w = si.make_weights(cfg, 0)
+    _progress("  weights drawn")
     model = Model(cfg, w, work=work)
     fm = FlashMesh(config_struct(cfg, max_tokens=max_tokens))
     assert fm.blob_elems() == si.blob_size(cfg)
     fm.load_weights(si.pack_blob(cfg, w))
+    _progress("  weights loaded")
     mems = [si.make_memory(cfg, s) for s in range(cfg.batch)]
     for s, m in enumerate(mems):
         getattr(fm, prefill)(s, torch.from_numpy(m).cuda())
-    states = [SeqState(model, mems[s], max_tokens or cfg.max_tokens) for s in range(cfg.batch)]
+    states = []
+    for s in range(cfg.batch):
+        states.append(SeqState(model, mems[s], max_tokens or cfg.max_tokens))
+        _progress("  oracle state", s)
     return model, fm, states
 
 
@@ -170,6 +183,8 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
         main_after = fm.read_state()[:, 3] if sampling is not None else None
         for s in range(S):
             st = states[s]
+            if st is None:             # a sequence the oracle does not follow
+                continue
             if st.finished or st.P >= budget:
                 assert h_len[s] == 0 and h_acc[s] == 0, (s, h_len[s], h_acc[s])
                 continue
@@ -282,10 +297,13 @@ def lockstep(cfg, faces, tol, max_steps=None, drafts="native", replay=None, work
             rep.accepted.append(a)
             rep.block_lens.append(B)
         rep.steps += 1
+        _progress("  lock-step", rep.steps)
         st_dev = fm.read_state()
         for s in range(S):
             st = states[s]
+            if st is None:
+                continue
             assert tuple(st_dev[s, :4]) == (st.P, (st.P + 2) // 3, (st.P + 8) // 9, st.main), (rep.steps, s, st_dev[s], st.P, st.main)
             assert bool(st_dev[s, 4]) == bool(st.finished)
-    streams = [st.tokens[1:] + [st.main] for st in states]
+    streams = [None if st is None else st.tokens[1:] + [st.main] for st in states]
     return rep, streams, fm

@@ -20,7 +20,8 @@ def _need_gpu():
 @pytest.mark.parametrize("name", ["t_f32_c", "t_f32_99", "t_f32_1815", "t_bf16_99", "t_bf16_1815", "t_bf16_99_b1", "t_bf16_99_b1w",
                                   "t_f32_1818", "t_bf16_1812", "t_bf16_279", "t_f32_2727", "t_bf16_c17",
                                   "t_f32_99_w36", "t_bf16_99_w36", "t_bf16_99_b1_w36", "t_bf16_1815_w72",
-                                  "t_bf16_1815_b1", "t_bf16_2727_b1", "t_bf16_1815_b1_w72"])
+                                  "t_bf16_1815_b1", "t_bf16_2727_b1", "t_bf16_1815_b1_w72",
+                                  "t_f32_99_noA", "t_bf16_1815_noA", "t_bf16_99_b1_noA"])
 def test_lockstep_small_native_heads(name):
     _need_gpu()
     from parity_harness import lockstep
@@ -151,24 +152,30 @@ def test_config0_tiny_full_run():
     assert len(streams[0]) == 90
 
 
-def test_config3_shape_short_lockstep():
+def test_config3_shape_short_lockstep(say):
     """configs[3] at its real widths (d=1024, 40 blocks, 8 sequences with ragged progress) for a few steps of
     lock-step decoding: draft blocks, logits, greedy tokens, accepted and committed lengths."""
     _need_gpu()
     from parity_harness import lockstep
+    import parity_harness
+    parity_harness.PROGRESS = say
     cfg = si.CONFIGS[3].replace(faces=40)
     print("case config3 short", flush=True)
     rep, streams, fm = lockstep(cfg, cfg.faces, TOL["bf16"], max_steps=5)
+    parity_harness.PROGRESS = None
     print(rep, flush=True)
     assert rep.steps == 5 and len(rep.accepted) == 5 * cfg.batch
 
 
-def test_config4_shape_short_lockstep():
+def test_config4_shape_short_lockstep(say):
     """configs[4] at its real widths (d=1536, 48 blocks, 4 sequences, block 18) for a few lock-step steps."""
     _need_gpu()
     from parity_harness import lockstep
+    import parity_harness
+    parity_harness.PROGRESS = say
     cfg = si.CONFIGS[4].replace(faces=40)
     print("case config4 short", flush=True)
     rep, streams, fm = lockstep(cfg, cfg.faces, TOL["bf16"], max_steps=4)
+    parity_harness.PROGRESS = None
     print(rep, flush=True)
     assert rep.steps == 4 and len(rep.accepted) == 4 * cfg.batch

@@ -336,6 +336,29 @@ def test_step_totals_and_rules():
         assert fired_v_at == [s for s in sorted(rec) if s % 3 == 0 and s % 9 != 0]
 
 
+def test_rule_a_switched_off_lets_the_point_level_fire_at_face_nodes():
+    """Supplement "Optimizations": rule (A) drops the point-level prediction where a face-level one fires.  With the
+    rule off both fire at a face split node and cover the same positions; everything else is unchanged, and the
+    emitted stream is the backbone's either way."""
+    cfg, m, mem = _model("t_f32_99", faces=8, rule_a=0)
+    rec = _walk(cfg, m, mem, 40)
+    n, mm = cfg.draft_face, cfg.draft_point
+    for s in sorted(rec):
+        main = s + 1
+        if s % 3 == 0:
+            assert rec[s]["v"] == list(range(main + 3, main + mm))           # also where s % 9 == 0
+        if s % 9 == 0:
+            assert rec[s]["f"] == list(range(main + 3, main + n))
+            assert sorted(set(rec[s]["v"]) & set(rec[s]["f"])) == list(range(main + 3, main + min(n, mm)))
+        assert rec[s]["c"] == [main + 1, main + 2]
+    cfg_on, m_on, _ = _model("t_f32_99", faces=8)
+    rec_on = _walk(cfg_on, m_on, mem, 40)
+    assert all(rec_on[s]["len"] == rec[s]["len"] for s in rec)                # the face level already covered the block
+    a, _ = sp.generate(m, mem, 4, speculative=True)
+    b, _ = sp.generate(m_on, mem, 4, speculative=False)
+    assert a == b
+
+
 # -- T7: residual wiring of the draft heads ------------------------------------------------------
 def test_sp_and_hf_residual_wiring():
     cfg, m, mem = _model("t_f32_99", faces=3)
