@@ -103,6 +103,16 @@ int fm_load_weights(fm_ctx* ctx, const float* host_blob, size_t n_floats);
  * and reset of the sequence to x_0 = BOS with empty caches. */
 int fm_prefill_condition(fm_ctx* ctx, int32_t seq, const float* mem_dev);
 
+/* fm_prefill_condition for callers that must not touch an allocator while they run (a serving loop that re-conditions
+ * a sequence between requests, code under HIP graph capture, harnesses that forbid hipMalloc): the same kernels and the
+ * same result, but the staging area of the call (the condition memory re-ordered for the matrix units, or, on the fp32
+ * path, its converted copy and one block's K/V rows) lives in a 16 MiB device array that is part of the library image
+ * instead of memory owned by the context.  The call allocates and frees nothing.  FM_EINVAL with a message when the
+ * configuration needs more staging than 16 MiB (mem_len * d_model * 2 bytes in half precision with mem_len and d_model
+ * multiples of 256, else mem_len * d_model * (element size + 8)).  Every GPU holds one such array for all contexts on
+ * it: calls that overlap in time on one GPU (different streams or contexts) race on it; calls on one stream are safe. */
+int fm_prefill_condition_static(fm_ctx* ctx, int32_t seq, const float* mem_dev);
+
 /* Predict stage (Sec. 3.1, supplement "Three-Level Speculative Decoding"): from the features tapped
  * at the last committed position run the coordinate-level SP heads, and the point / face pipelines
  * (SP heads, draft upsample Eq. 2, HF blocks Eq. 3-6) where a split node was crossed (rules (A) and

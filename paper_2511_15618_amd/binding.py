@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
-           "fm_prefill_condition", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
+           "fm_prefill_condition", "fm_prefill_condition_static", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
            "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile", "fm_debug_draft",
            "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm"]
 
@@ -65,6 +65,7 @@ def load_library():
     lib.fm_blob_elems.restype = i64
     lib.fm_load_weights.argtypes = [p, p, C.c_size_t]
     lib.fm_prefill_condition.argtypes = [p, i32, p]
+    lib.fm_prefill_condition_static.argtypes = [p, i32, p]
     lib.fm_draft.argtypes = [p, p, p]
     lib.fm_verify_block.argtypes = [p, p, p, p, p]
     lib.fm_commit.argtypes = [p, p]
@@ -151,6 +152,11 @@ class FlashMesh:
         assert mem.is_cuda and mem.dtype == self.torch.float32 and mem.is_contiguous()
         assert tuple(mem.shape) == (self.cfgs.mem_len, self.cfgs.d_model)
         self._chk(self.lib.fm_prefill_condition(self.h, seq, self._ptr(mem)), "fm_prefill_condition")
+
+    def prefill_condition_static(self, seq: int, mem):
+        assert mem.is_cuda and mem.dtype == self.torch.float32 and mem.is_contiguous()
+        assert tuple(mem.shape) == (self.cfgs.mem_len, self.cfgs.d_model)
+        self._chk(self.lib.fm_prefill_condition_static(self.h, seq, self._ptr(mem)), "fm_prefill_condition_static")
 
     def new_block(self):
         t = self.torch

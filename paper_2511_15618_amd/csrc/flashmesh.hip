@@ -8,6 +8,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <cstdlib>
 #include <string>
 #include <type_traits>
@@ -19,6 +20,12 @@
 #include "fm_kernels_mfma.h"
 #include "fm_kernels_persist.h"
 #include "fm_kernels_prefill.h"
+
+// Staging area of fm_prefill_condition_static: a file-scope device array instead of memory owned by a context, so that
+// the call touches no allocator.  Every GPU the library runs on holds its own copy at its own address; the host-side
+// name below is only a handle for hipGetSymbolAddress and is never passed to a kernel or a copy.
+#define FM_STATIC_SCRATCH_BYTES (16u << 20)
+static __device__ __align__(256) unsigned char scratch[FM_STATIC_SCRATCH_BYTES];
 
 #define RS_C 32  // ring sizes (positions kept per sequence) at the coordinate / vertex / face level
 #define RS_V 16
@@ -49,6 +56,10 @@ struct HfLevel {
 };
 
 struct LoadItem { size_t blob_off, n; void* dst; bool f32; int N, K, perm; };  // N, K > 0: linear weight [N, K]
+
+// device address of `scratch` on each GPU, looked up once per device (at the first fm_create on it)
+std::mutex g_scratch_mu;
+void* g_scratch_addr[64] = {};
 
 }  // namespace
 
@@ -93,6 +104,7 @@ struct fm_ctx {
   MfmaRes mres;       // workspaces of the MFMA kernels (half-precision path)
   float* stage;       // staging for weight conversion / prefill GEMM output
   size_t stage_elems;
+  unsigned char* static_scratch = nullptr;   // this GPU's copy of the file-scope staging array
   // draft scratch
   DraftRows dr;
   DraftBufs db;
@@ -420,6 +432,14 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
                      c->replay, speculative, block_tok, block_len, c->smp);
   HIPCHK(c, hipGetLastError());
   return FM_OK;
+}
+
+// staging bytes a prefill call needs: the memory in fragment order (tiled GEMM), or the memory in the storage type
+// followed by the fp32 K/V rows of one block
+size_t prefill_stage_bytes(const fm_ctx* c) {
+  const size_t M = c->D.M, d = c->D.d;
+  if (c->bf16 && c->pf_layers) return M * d * sizeof(f16_t);
+  return M * d * c->esz + M * 2 * d * sizeof(float);
 }
 
 template <typename T>
@@ -815,6 +835,21 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   int rc = build_params(c);
   if (rc == FM_OK) rc = build_buffers(c);
   if (rc == FM_OK) {
+    // this GPU's copy of the static staging array: address looked up once per device, with that device current
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) rc = fail(c, FM_EHIP, "hipGetDevice failed");
+    else {
+      std::lock_guard<std::mutex> lk(g_scratch_mu);
+      if (!g_scratch_addr[dev]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) rc = fail(c, FM_EHIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+        else g_scratch_addr[dev] = p;
+      }
+      c->static_scratch = (unsigned char*)g_scratch_addr[dev];
+    }
+  }
+  if (rc == FM_OK) {
     const int budget = g.max_tokens;
     if (hipMemcpy(c->st.budget, &budget, sizeof(int), hipMemcpyHostToDevice) != hipSuccess) rc = FM_EHIP;
     // all sequences start finished until they are prefilled
@@ -905,6 +940,21 @@ int fm_prefill_condition(fm_ctx* c, int32_t seq, const float* mem_dev) {
   if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range [0,%d)", seq, c->D.S);
   if (!mem_dev) return fail(c, FM_EINVAL, "null condition memory");
   int rc = c->bf16 ? prefill_impl<f16_t>(c, seq, mem_dev, c->stage) : prefill_impl<float>(c, seq, mem_dev, c->stage);
+  if (rc == FM_OK) { c->prefilled[seq] = true; c->len_bound[seq] = 0; }
+  return rc;
+}
+
+int fm_prefill_condition_static(fm_ctx* c, int32_t seq, const float* mem_dev) {
+  if (!c) return FM_EINVAL;
+  if (!c->weights_loaded) return fail(c, FM_ESTATE, "weights not loaded");
+  if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range [0,%d)", seq, c->D.S);
+  if (!mem_dev) return fail(c, FM_EINVAL, "null condition memory");
+  if (!c->static_scratch) return fail(c, FM_ESTATE, "no static staging area on this device");
+  const size_t need = prefill_stage_bytes(c);
+  if (need > FM_STATIC_SCRATCH_BYTES)
+    return fail(c, FM_EINVAL, "condition memory of %d x %d needs %zu staging bytes, the static area holds %u: use fm_prefill_condition",
+                c->D.M, c->D.d, need, (unsigned)FM_STATIC_SCRATCH_BYTES);
+  int rc = c->bf16 ? prefill_impl<f16_t>(c, seq, mem_dev, c->static_scratch) : prefill_impl<float>(c, seq, mem_dev, c->static_scratch);
   if (rc == FM_OK) { c->prefilled[seq] = true; c->len_bound[seq] = 0; }
   return rc;
 }
