@@ -37,8 +37,6 @@ struct Layer {
   float *g1, *g2, *g3;
   void *wqkv, *wo, *cq, *ckv, *co, *w1, *w2;  // storage type T, [out, in]
   void* wqkv_rp;                               // persistent path: q/k tiles hold whole rotary pairs
-  void* wcqo;                                  // persistent path: cq diag(g2) wo (tiled), folded at load time
-  size_t off_wo, off_cq;                       // where wo and cq start in the weight blob
   void *Kc, *Vc;                               // [S][H][cap][64]
   void *Km, *Vm;                               // [S][H][M][64]
   int level;                                   // 0 coordinate, 1 vertex, 2 face
@@ -528,12 +526,9 @@ int build_params(fm_ctx* c) {
       } else {
         lin(L.wqkv, 3 * d, d);   // wq, wk, wv are consecutive in the blob
       }
-      L.off_wo = off;
       lin(L.wo, d, d);
       item(L.g2, d, true);
-      L.off_cq = off;
       lin(L.cq, d, d);
-      if (c->persist) TRY(dalloc_t(c, &L.wcqo, d * d));
       lin(L.ckv, 2 * d, d);    // ck, cv consecutive
       lin(L.co, d, d);
       item(L.g3, d, true);
@@ -598,7 +593,7 @@ int build_persist(fm_ctx* c) {
       PkLayer p{};
       p.g1 = (pk_cf_t)L.g1; p.g2 = (pk_cf_t)L.g2; p.g3 = (pk_cf_t)L.g3;
       p.wqkv = (pk_cw_t)L.wqkv_rp; p.wo = (pk_cw_t)L.wo; p.cq = (pk_cw_t)L.cq; p.co = (pk_cw_t)L.co;
-      p.w1 = (pk_cw_t)L.w1; p.w2 = (pk_cw_t)L.w2; p.wcqo = (pk_cw_t)L.wcqo;
+      p.w1 = (pk_cw_t)L.w1; p.w2 = (pk_cw_t)L.w2;
       p.Kc = (pk_w_t)L.Kc; p.Vc = (pk_w_t)L.Vc; p.Km = (pk_cw_t)L.Km; p.Vm = (pk_cw_t)L.Vm;
       p.level = L.level;
       p.last = i + 1 == c->stacks[st].size();
@@ -645,7 +640,6 @@ int build_persist(fm_ctx* c) {
   TRY(dalloc(c, &a.newK, (size_t)D.H * RS * 32)); TRY(dalloc(c, &a.newV, (size_t)D.H * RS * 32));
   TRY(dalloc(c, &a.partS, (size_t)D.H * PK_MAXSPLIT * RG * PK_PART)); TRY(dalloc(c, &a.partX, (size_t)D.H * PK_MAXSPLIT * RG * PK_PART));
   TRY(dalloc(c, &a.w2part, (d / 16) * RG * 3 * 256));
-  TRY(dalloc(c, &a.ssqB, nl * (d / 16) * RS));
   TRY(dalloc(c, &a.abort_word, 16));
   if (hipMemset(a.abort_word + 1, 0xFF, 4) != hipSuccess) return fail(c, FM_EHIP, "hipMemset failed");
   a.run_flag = c->st.alive;
@@ -911,25 +905,6 @@ int fm_load_weights(fm_ctx* c, const float* blob, size_t n_floats) {
     }
   }
   HIPCHK(c, hipGetLastError());
-  if (c->bf16 && c->stacks[0].size() && c->stacks[0][0].wcqo) {
-    // single-launch verify kernel: the cross-attention query projection folded into the output projection before it,
-    // W = cq diag(g2) wo per block, multiplied in fp32 from the blob's values and then tiled like any other weight
-    const size_t d = c->D.d;
-    float* tmp = nullptr;
-    if (hipMalloc((void**)&tmp, 3 * d * d * sizeof(float)) != hipSuccess) { (void)hipGetLastError(); return fail(c, FM_ENOMEM, "hipMalloc of the folding buffers failed"); }
-    int rc = FM_OK;
-    for (int st = 0; st < 5 && rc == FM_OK; st++)
-      for (Layer& L : c->stacks[st]) {
-        if (hipMemcpyAsync(tmp, blob + L.off_cq, d * d * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
-            hipMemcpyAsync(tmp + d * d, blob + L.off_wo, d * d * 4, hipMemcpyHostToDevice, c->stream) != hipSuccess) { rc = fail(c, FM_EHIP, "weight copy failed"); break; }
-        hipLaunchKernelGGL(k_fold_projections, dim3((unsigned)(d / 16), (unsigned)(d / 16)), dim3(16, 16), 0, c->stream, tmp, L.g2, tmp + d * d, tmp + 2 * d * d, (int)d);
-        hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, tmp + 2 * d * d, (f16_t*)L.wcqo, (int)d, (int)d, (int)d, 0);
-        if (hipStreamSynchronize(c->stream) != hipSuccess) { rc = fail(c, FM_EHIP, "weight folding failed"); break; }   // the blob ranges and tmp are reused
-      }
-    (void)hipFree(tmp);
-    TRY(rc);
-    HIPCHK(c, hipGetLastError());
-  }
   c->weights_loaded = true;
   return FM_OK;
 }

@@ -117,25 +117,6 @@ __global__ void k_tile_weight(const float* __restrict__ src, f16_t* __restrict__
   }
 }
 
-// C[n][k] = sum_j A[n][j] g[j] B[j][k] for square fp32 matrices of width d (a multiple of 16): the product of two
-// projections with the gain of the norm between them, used once per block at load time.  16 x 16 tile per workgroup.
-__global__ __launch_bounds__(256) void k_fold_projections(const float* __restrict__ A, const float* __restrict__ g,
-                                                          const float* __restrict__ B, float* __restrict__ C, int d) {
-  __shared__ float sa[16][17], sb[16][17];
-  const int tx = threadIdx.x, ty = threadIdx.y;
-  const int n = blockIdx.y * 16 + ty, k = blockIdx.x * 16 + tx;
-  float acc = 0.f;
-  for (int j0 = 0; j0 < d; j0 += 16) {
-    sa[ty][tx] = A[(long)n * d + j0 + tx] * g[j0 + tx];
-    sb[ty][tx] = B[(long)(j0 + ty) * d + k];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 16; j++) acc = fmaf(sa[ty][j], sb[j][tx], acc);
-    __syncthreads();
-  }
-  C[(long)n * d + k] = acc;
-}
-
 // ------------------------------------------------------------------------------------------
 // GEMM
 // ------------------------------------------------------------------------------------------

@@ -43,7 +43,6 @@ typedef const PK_GLOBAL float* pk_cf_t;     // gains
 struct PkLayer {
   pk_cf_t g1, g2, g3;
   pk_cw_t wqkv, wo, cq, co, w1, w2;   // tiled; wqkv with rotary pairs inside one tile
-  pk_cw_t wcqo;                       // cq diag(g2) wo, tiled: the cross-attention query taken straight from the attention output
   pk_w_t Kc, Vc;
   pk_cw_t Km, Vm;
   int level;      // 0 coordinate, 1 vertex, 2 face
@@ -83,7 +82,6 @@ struct PkArgs {
   u64* mid;                 // [layers][RS][ff/2]
   u64 *newK, *newV;         // [H][RS][32]
   u64 *partS, *partX;       // [H][PK_MAXSPLIT][RS/16][PK_PART]
-  u64* ssqB;                // [layers][d/16][RS]: per output tile of Wo, the sum of squares of its 16 columns of hB per row
   u64* w2part;              // [d/16][RS/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
   unsigned epoch;
   u64 timeout_ticks;        // bound of every wait (100 MHz wall clock)
@@ -145,16 +143,18 @@ template <int N, class F>
 __device__ __forceinline__ bool pk_fetch(unsigned (&out)[N], int n, bool active, unsigned tag, F addr, const PkArgs& a, int stage) {
   const u64 t0 = wall_clock64();
   int it = 0;
-  // phase 1 (optional): watch one element per lane until it shows up (cheap while the producers are still far away)
-  if (N > 1 && a.two_phase) {
+  // (a.two_phase: watch one element per lane first; otherwise the full read comes first and the watching only starts
+  // after a read that came back incomplete)
+  auto watch = [&]() -> bool {
     while (true) {
       bool ok = true;
       if (active && n > 0) ok = (unsigned)(pk_ld(addr(0)) >> 32) == tag;
-      if (__all(ok)) break;
+      if (__all(ok)) return true;
       if ((++it & 7) == 0 && pk_expired(a, t0, stage)) return false;
       __builtin_amdgcn_s_sleep(4);
     }
-  }
+  };
+  if (N > 1 && a.two_phase && !watch()) return false;
   // phase 2: read everything, again until complete
   while (true) {
     // all loads are issued back to back (the compiler keeps agent-scope loads in program order and would
@@ -183,7 +183,8 @@ __device__ __forceinline__ bool pk_fetch(unsigned (&out)[N], int n, bool active,
       }
       return false;
     }
-    __builtin_amdgcn_s_sleep(2);
+    if (N > 1) { if (!watch()) return false; }
+    else __builtin_amdgcn_s_sleep(2);
   }
 }
 
@@ -210,8 +211,7 @@ __device__ __forceinline__ bool pk_wait_stack(const PkArgs& a, const u64* hT, un
 // ------------------------------------------------------------------------------------------
 // GEMM tile: C[16 rows x 16 cols] = A[16 x K] * W_tile^T, four waves split K (K <= 1024), result in wave 0.
 // A is a half-pair exchange buffer [16][K/2].  ASRC 1: the rows are RMS-normalised (gain g) on the fly; they are
-// the half-rounded copy that the producers of the fp32 residual stream write next to it.  ASRC 2: the rows are only
-// multiplied by the gain (the caller owns the 1/rms factor).
+// the half-rounded copy that the producers of the fp32 residual stream write next to it.
 // Every wave takes the MFMA A-fragments of its K-quarter straight from the exchange buffer: lane (r, g) of
 // fragment f needs the 8 consecutive values k0 = f*32 + g*8 .. +8 of row r, which are 32 contiguous bytes of
 // tagged half pairs, i.e. two 16-byte agent-scope loads.  No LDS staging, no barrier before the multiplication;
@@ -236,8 +236,8 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, SH& sh, pk_cw_t Wt
 #pragma unroll
   for (int f = 0; f < 8; f++)
     if (f < FW) wf[f] = *(const PK_GLOBAL f16x8*)(Wt + ((long)(wave * FW + f) * 64 + lane) * 8);
-  f32x4 gl[ASRC >= 1 ? 16 : 1];
-  if (ASRC >= 1) {
+  f32x4 gl[ASRC == 1 ? 16 : 1];
+  if (ASRC == 1) {
 #pragma unroll
     for (int f = 0; f < 8; f++)
       if (f < FW) {
@@ -252,48 +252,50 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, SH& sh, pk_cw_t Wt
   const u64 t0 = wall_clock64();
   int it = 0;
   bool good = true;
-  // phase 1: one cheap load per lane until it shows the tag.  Lane l watches fragment l/8, its first or second
-  // half (a producer tile owns half a fragment row), in one of the last four rows.
-  if (a.two_phase) {
-    const int fs = min(lane >> 3, FW - 1), hs = (lane >> 2) & 1, rs = max(R - 1 - (lane & 3), 0);
-    const u64* sent = Aw + (long)rs * lda + fs * EF + hs * (EF / 2);
-    PK_MARK(0);
-    while (true) {
-      const bool ok = (unsigned)(pk_ld(sent) >> 32) == tagA;
-      if (__all(ok)) break;
-      if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
-      __builtin_amdgcn_s_sleep(4);
-    }
+  // The full fragment read is its own validity check, so a unit whose input is already there pays one round trip.
+  // When a read comes back incomplete the wave falls back to watching one element per lane (lane l: fragment l/8, its
+  // first or second half - a producer tile owns half a fragment row - in one of the last four rows) and reads the
+  // fragments again once those show the tag: waiting costs the memory system 64 small loads per round, not 32 KiB.
+  const int fs_ = min(lane >> 3, FW - 1), hs_ = (lane >> 2) & 1, rs_ = max(R - 1 - (lane & 3), 0);
+#define PK_WATCH(AW)                                                                                          \
+  {                                                                                                           \
+    const u64* sent = (AW) + (long)rs_ * lda + fs_ * EF + hs_ * (EF / 2);                                     \
+    while (good) {                                                                                            \
+      const bool okw = (unsigned)(pk_ld(sent) >> 32) == tagA;                                                 \
+      if (__all(okw)) break;                                                                                  \
+      if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { good = false; break; }                               \
+      __builtin_amdgcn_s_sleep(4);                                                                            \
+    }                                                                                                         \
   }
+  if (a.two_phase) PK_WATCH(Aw)
   PK_MARK(1);
   // phase 2: the fragments (inline asm loads: the wait is explicit, and every destination is passed through
   // an empty asm afterwards to pin its uses behind the wait)
   u32x4 v[8 * NL];
-  while (good) {
-#pragma unroll
-    for (int f = 0; f < 8; f++) {
-#pragma unroll
-      for (int j = 0; j < NL; j++) {
-        v[f * NL + j] = u32x4{tagA, tagA, tagA, tagA};
-        if (f < FW && on) {
-          const u64* p = mine + f * EF + 2 * j;
-          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[f * NL + j]) : "v"(p) : "memory");
-        }
-      }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    bool ok = true;
-#pragma unroll
-    for (int i = 0; i < 8 * NL; i++) {
-      asm volatile("" : "+v"(v[i]));
-      ok = ok && v[i][1] == tagA && v[i][3] == tagA;      // unused slots were preset to the tag
-    }
-    if (__all(ok)) break;
-    if ((++it & 3) == 0 && pk_expired(a, t0, stage)) { good = false; break; }
-    __builtin_amdgcn_s_sleep(2);
+#define PK_FETCH_FRAGS(MINE, AW)                                                                              \
+  while (good) {                                                                                              \
+    _Pragma("unroll") for (int f = 0; f < 8; f++) {                                                           \
+      _Pragma("unroll") for (int j = 0; j < NL; j++) {                                                        \
+        v[f * NL + j] = u32x4{tagA, tagA, tagA, tagA};                                                        \
+        if (f < FW && on) {                                                                                   \
+          const u64* p = (MINE) + f * EF + 2 * j;                                                             \
+          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[f * NL + j]) : "v"(p) : "memory");      \
+        }                                                                                                     \
+      }                                                                                                       \
+    }                                                                                                         \
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");                                                          \
+    bool ok = true;                                                                                           \
+    _Pragma("unroll") for (int i = 0; i < 8 * NL; i++) {                                                      \
+      asm volatile("" : "+v"(v[i]));                                                                          \
+      ok = ok && v[i][1] == tagA && v[i][3] == tagA;      /* unused slots were preset to the tag */           \
+    }                                                                                                         \
+    if (__all(ok)) break;                                                                                     \
+    if ((++it & 3) == 0 && pk_expired(a, t0, stage)) { good = false; break; }                                 \
+    PK_WATCH(AW)                                                                                              \
   }
+  PK_FETCH_FRAGS(mine, Aw)
   PK_MARK(2);
-  if (ASRC >= 1) {
+  if (ASRC == 1) {
     // RMSNorm without a barrier in front of the multiplication: the MFMA runs on half(x * gain) and the per-row
     // factor 1/rms, a scalar per output row, is applied to the accumulated tile afterwards.  Row sums of
     // squares: this lane's 8*FW values, then the four k-groups of the wave; the four waves meet in LDS below.
@@ -314,11 +316,9 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, SH& sh, pk_cw_t Wt
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, wf[f], acc, 0, 0, 0);
       }
     }
-    if (ASRC == 1) {
-      ss += __shfl_xor(ss, 16, 64);
-      ss += __shfl_xor(ss, 32, 64);
-      if (g == 0) sh.ssq[wave][r] = ss;
-    }
+    ss += __shfl_xor(ss, 16, 64);
+    ss += __shfl_xor(ss, 32, 64);
+    if (g == 0) sh.ssq[wave][r] = ss;
   } else {
 #pragma unroll
     for (int f = 0; f < 8; f++) {
@@ -329,6 +329,8 @@ __device__ __forceinline__ bool pk_gemm_tile(const PkArgs& a, SH& sh, pk_cw_t Wt
       }
     }
   }
+#undef PK_FETCH_FRAGS
+#undef PK_WATCH
   sh.red[wave][lane] = acc;
   if (__syncthreads_or(!good)) return false;
   PK_MARK(3);
@@ -360,7 +362,7 @@ __device__ __forceinline__ bool pk_res_prefetch(const PkArgs& a, int nt, const u
 
 __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c, int nt, const unsigned (&old)[4],
                                                 u64* hout, u64* xout, unsigned tag_out, int R, const int (&prow)[4],
-                                                float* tap_ring, float* out_ring, int ring_size, u64* ssq_out = nullptr) {
+                                                float* tap_ring, float* out_ring, int ring_size) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
   const int d = a.D.d;
 #pragma unroll
@@ -379,12 +381,6 @@ __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c,
         if (tap_ring) tap_ring[(long)(p & (ring_size - 1)) * d + n] = ho;
         if (out_ring) out_ring[(long)(p & (ring_size - 1)) * d + n] = v;
       }
-    }
-    if (ssq_out) {          // sum of squares of this tile's 16 columns of row r (all 16 lanes of the row take part)
-      const float ho = __uint_as_float(old[i]);
-      float q = r < R ? (ho + c[i]) * (ho + c[i]) : 0.f;
-      q += __shfl_xor(q, 1, 64); q += __shfl_xor(q, 2, 64); q += __shfl_xor(q, 4, 64); q += __shfl_xor(q, 8, 64);
-      if ((lane & 15) == 0 && r < R) pk_stf(ssq_out + r, q, tag_out);
     }
   }
 }
@@ -470,7 +466,7 @@ template <int QT, class SH>
 __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64* qbuf, const int (&lim)[QT], int maxlim, int R,
                                              pk_cw_t Kc, pk_cw_t Vc, int capb, int nsplit_cfg, int hh, int split,
                                              bool overlay, int P0, u64* part, unsigned tag, int stage, int window,
-                                             PK_LDS unsigned char* kvlds, const u64* ssq = nullptr, float eps = 0.f) {
+                                             PK_LDS unsigned char* kvlds) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int g = lane >> 4, ql = lane & 15;
   const int d = a.D.d;
@@ -577,27 +573,6 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
       qf1[t] = __builtin_bit_cast(f16x8, hi4);
     }
   }
-  // cross-attention: the queries arrive without the 1/rms factor of their norm; it is put together here from the sums
-  // of squares that the d/16 output tiles of the preceding projection published (lane (row, g) adds tiles g, g + 4, ...)
-  float qscale[QT];
-#pragma unroll
-  for (int t = 0; t < QT; t++) qscale[t] = kScale;
-  if (ssq) {
-    const int NT = d >> 4, RSq = QT * 16;
-#pragma unroll
-    for (int t = 0; t < QT; t++) {
-      unsigned part16[16];
-      const int row = on[t] ? t * 16 + ql : 0;
-      const int n = (NT - g + 3) >> 2;                   // tiles g, g + 4, ... below NT (NT <= 64)
-      ok = pk_fetch<16>(part16, n, true, tag, [&](int i) { return ssq + (long)(g + 4 * i) * RSq + row; }, a, stage) && ok;
-      float tot = 0.f;
-#pragma unroll
-      for (int i = 0; i < 16; i++) if (i < n) tot += __uint_as_float(part16[i]);
-      tot += __shfl_xor(tot, 16, 64);
-      tot += __shfl_xor(tot, 32, 64);
-      qscale[t] = kScale / sqrtf(tot / (float)d + eps);
-    }
-  }
   // rows written by this pass that fall into one of this wave's blocks (at most one block)
   unsigned raw[48];
   if (bov >= 0) {
@@ -681,7 +656,7 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
 #pragma unroll
         for (int i = 0; i < 4; i++) {
           const int key = held(b * 32 + hb * 16 + g * 4 + i);      // absolute position
-          const float v = (key <= lim[t] && key >= first[t]) ? sT[hb][i] * qscale[t] : -INFINITY;
+          const float v = (key <= lim[t] && key >= first[t]) ? sT[hb][i] * kScale : -INFINITY;
           sT[hb][i] = v;
           mx = fmaxf(mx, v);
         }
@@ -934,10 +909,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         }
         PK_NEXT(PK_GROUPED_SLOTS(H, 4 * RG));
       }
-      // ---- Wo + residual -> hB (tap: the layer input is what the draft heads of this level start from).  Each tile also
-      // publishes the sum of squares of its 16 columns of hB per row: the cross-attention units put the 1/rms of norm2
-      // together from them.
-      u64* const ssq_l = a.ssqB + (long)l * (d / 16) * RS;
+      // ---- Wo + residual -> hB (tap: the layer input is what the draft heads of this level start from)
       PK_MINE(d / 16 * RG) {
         const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
@@ -947,25 +919,19 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         if (wave == 0) okr = pk_res_prefetch(a, nt, hA_l + (long)row0 * d, tag, Rl, pos + row0, old, prow, stage);
         if (!pk_gemm_tile<0>(a, sh, L.wo + (long)nt * (d / 32) * 512, d / 32, att_l + row0 * hd, tag, nullptr, Rl, c, stage)) return;
         if (wave == 0 && okr)
-          pk_epi_residual(a, c, nt, old, hB_l + (long)row0 * d, nullptr, tag, Rl, prow, L.tap ? a.tap[lev] : nullptr, nullptr,
-                          lev == 0 ? 32 : lev == 1 ? 16 : 8, ssq_l + (long)nt * RS + row0);
+          pk_epi_residual(a, c, nt, old, hB_l + (long)row0 * d, xB_l + row0 * hd, tag, Rl, prow, L.tap ? a.tap[lev] : nullptr, nullptr,
+                          lev == 0 ? 32 : lev == 1 ? 16 : 8);
         if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16 * RG);
-      // ---- cross-attention query, in the same round as Wo instead of after it.  With hB = hA + att Wo^T the product
-      // (hB * g2) cq^T splits into (hA * g2) cq^T, whose operands exist since the layer began and which is multiplied
-      // while the attention output is still on its way, and att (cq diag(g2) Wo)^T with the matrix folded at load
-      // time.  The 1/rms factor of norm2 is a scalar per row: the cross-attention units apply it to the scores.
-      // The 4 tiles of a head form a group.
+      // ---- cross-attention query (norm2 on the fly): the 4 tiles of a head form a group
       PK_MINE_GROUPED(H, 4 * RG) {
         const int hh = PK_GROUP(4 * RG), k = PK_UNIT(4 * RG);
         if (hh >= H) continue;
         const int nt = hh * 4 + k / RG, row0 = (k % RG) * 16, Rl = min(16, R - row0);
-        f32x4 c1, c2;
-        if (!pk_gemm_tile<2>(a, sh, L.cq + (long)nt * (d / 32) * 512, d / 32, xA_l + row0 * hd, tag, L.g2, Rl, c1, stage)) return;
-        __syncthreads();          // wave 0 has taken the first sum out of LDS
-        if (!pk_gemm_tile<0>(a, sh, L.wcqo + (long)nt * (d / 32) * 512, d / 32, att_l + row0 * hd, tag, nullptr, Rl, c2, stage)) return;
-        if (wave == 0) pk_epi_half(c1 + c2, nt, a.q2 + row0 * hd, d >> 1, tag, Rl, false, a.xcd_local);
+        f32x4 c;
+        if (!pk_gemm_tile<1>(a, sh, L.cq + (long)nt * (d / 32) * 512, d / 32, xB_l + row0 * hd, tag, L.g2, Rl, c, stage)) return;
+        if (wave == 0) pk_epi_half(c, nt, a.q2 + row0 * hd, d >> 1, tag, Rl, false, a.xcd_local);
         __syncthreads();
       }
       PK_NEXT(PK_GROUPED_SLOTS(H, 4 * RG));
@@ -976,7 +942,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
           const int hh = PK_GROUP(ns), sp = PK_UNIT(ns);
           if (hh >= H) continue;
           if (!pk_attn_unit<QT>(a, sh, a.q2, limX[lev], maxX[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
-                                a.partX + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, 0, pk_kvlds, ssq_l, a.eps)) return;
+                                a.partX + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, 0, pk_kvlds)) return;
         }
         PK_NEXT(PK_GROUPED_SLOTS(H, ns));
         PK_MINE_GROUPED(H, 4 * RG) {
