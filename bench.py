@@ -107,13 +107,14 @@ def time_verify(fm, torch, tok, ln, acc, iters):
     return ev0.elapsed_time(ev1) / iters
 
 
-def half_context_leg(fm, cfg, torch, mems_dev, faces, steps, warmup, cont_faces=60):
+def half_context_leg(fm, cfg, torch, mems_dev, faces, steps, warmup):
     """The decode step at half context for a configuration whose whole generation does not fit a default run
     (several sequences): forced fill to faces/2, a short native continuation to learn the greedy stream from there,
     the identical fill again, then `warmup` untimed and `steps` timed steps of draft -> verify -> commit with the
     replay draft source (p = REPLAY_P) on that continuation, and the verify pass alone for the roofline."""
     half = 9 * (faces // 2)
-    cont = min(cont_faces, faces - faces // 2)
+    # the continuation must outlast the warm-up and timed steps even if every block is accepted whole
+    cont = min((steps + warmup) * cfg.block_max // 9 + 3, faces - faces // 2)
 
     def fill():
         for q in range(cfg.batch):
@@ -194,7 +195,7 @@ def main():
     ap.add_argument("--correct", type=int, default=0,
                     help="run the correct stage (label head, vertex-sharing moves, z-y-x re-sort) in every step, with this "
                          "many historical vertices; random-init labels, so only its cost is meaningful")
-    ap.add_argument("--b8-steps", type=int, default=200,
+    ap.add_argument("--b8-steps", type=int, default=100,
                     help="timed steps of the extra batch-8 leg (configs[3] at its full size, at half context); 0 = skip")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -267,7 +268,7 @@ def main():
 
     if cfg.batch > 1:
         # several sequences: the whole generation does not fit a default run, so the step is timed at half context
-        steps = args.steps if args.steps > 0 else 200
+        steps = args.steps if args.steps > 0 else 100
         leg = half_context_leg(fm, cfg, torch, mems_dev, faces, steps, args.warmup)
         measured = fm.measure_peaks()
         leg["roofline"]["frac_of_measured_read_rate"] = leg["roofline"]["achieved"] / measured["hbm_read_GBs"]

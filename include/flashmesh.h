@@ -64,7 +64,10 @@ typedef struct {
                            of their own positions, the K/V caches are rings of W + block_max + 2 positions (rounded
                            up to 128) and max_tokens only bounds the length of the emitted stream                 */
   int32_t rules_off;    /* schedule rules of the supplement's "Optimizations" to switch OFF (0 = the paper's final schedule):
-                           bit 0 = rule (A): the point level then also fires at face split nodes                       */
+                           bit 0 = rule (A): the point level then also fires at face split nodes;
+                           bit 1 = rule (B): the point and face levels then also predict their first three tokens (HF sets for
+                           the coordinate offsets 0..2 and the vertex offset 0 join the blob), which are averaged with the
+                           coordinate level's                                                                            */
 } fm_config;
 
 typedef struct {
@@ -208,7 +211,8 @@ int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
  * averaged distribution behind draft index i (supplement "Integrating the three levels"; entries at or above the
  * admissible token count and rows at or above the block length are unspecified).  which = 1 / 2: the label
  * distributions of the point pipeline [batch][max(m/3 - 1, 1)][3] / of the face pipeline [batch][max(n/3 - 1, 1)][3]
- * (Sec. 3.2; rows of pipelines that have not fired hold older values).  Synchronises. */
+ * (Sec. 3.2; rows of pipelines that have not fired hold older values; with rule (B) off the face pipeline has n/3 rows).
+ * Synchronises. */
 int fm_debug_draft(fm_ctx* ctx, int32_t which, float* host_out);
 
 /* What this GPU sustains, for reporting next to the published peaks: HOST out[0] = streaming read GB/s, out[1] =

@@ -40,13 +40,13 @@ def face_fires(s: int, fired_f: int, n: int) -> bool:
     return n > 0 and s >= 0 and fired_f != f
 
 
-def point_targets(v: int, m: int):
-    """Offsets t = 3 .. m-1 from the split node 3v predict x_{3v+t+1} (rule B drops t = 0..2)."""
-    return [3 * v + t + 1 for t in range(3, m)]
+def point_targets(v: int, m: int, rule_b: bool = True):
+    """Offsets t = 3 .. m-1 from the split node 3v predict x_{3v+t+1} (rule B drops t = 0..2; with the rule off they stay)."""
+    return [3 * v + t + 1 for t in range(3 if rule_b else 0, m)]
 
 
-def face_targets(f: int, n: int):
-    return [9 * f + t + 1 for t in range(3, n)]
+def face_targets(f: int, n: int, rule_b: bool = True):
+    return [9 * f + t + 1 for t in range(3 if rule_b else 0, n)]
 
 
 # ---------------------------------------------------------------------------------------
@@ -111,6 +111,7 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None, sampling=
     if s < 0:
         return [st.main]
     Dc, mm, nn = cfg.draft_coord, cfg.draft_point, cfg.draft_face
+    rule_b = bool(getattr(cfg, "rule_b", 1))
 
     # coordinate level: every position (supplement, "Coordinate-level speculative decoding")
     rows = {}
@@ -124,9 +125,11 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None, sampling=
         v = s // 3
         rows = {}
         labels = {}
-        for k in range(1, mm // 3):
-            u = sp_head(m, st, "v", k, st.tap["v"][v], v)
-            labels[v + k] = label_row(m, u)          # point-level feature of vertex v + k (Sec. 3.2)
+        for k in range(1 if rule_b else 0, mm // 3):
+            # k = 0 (rule (B) off): the current vertex, whose feature is the tapped one itself
+            u = sp_head(m, st, "v", k, st.tap["v"][v], v) if k else st.tap["v"][v]
+            if k:
+                labels[v + k] = label_row(m, u)      # point-level feature of vertex v + k (Sec. 3.2)
             for t in (3 * k, 3 * k + 1, 3 * k + 2):
                 rows[3 * v + t + 1] = _dist(m, hf_block(m, st, "c", t, u, 3 * v + t, 3 * v))
         st.rows["v"] = rows
@@ -140,7 +143,7 @@ def draft(model: Model, st: SeqState, budget_tokens: int, merged=None, sampling=
         g = [st.y_f[f]] + [sp_head(m, st, "f", k, st.tap["f"][f], f) for k in range(1, nn // 9)]
         rows = {}
         labels = {}
-        for j in range(1, nn // 3):
+        for j in range(1 if rule_b else 0, nn // 3):
             hv = hf_block(m, st, "v", j, g[j // 3], 3 * f + j, 3 * f)
             labels[3 * f + j] = label_row(m, hv)     # point-level feature of vertex 3f + j
             for t in (3 * j, 3 * j + 1, 3 * j + 2):

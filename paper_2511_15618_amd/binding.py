@@ -100,7 +100,7 @@ def config_struct(cfg, max_batch=None, max_tokens=None) -> FmConfig:
         max_batch=max_batch or cfg.batch, max_tokens=max_tokens or cfg.max_tokens,
         draft_coord=cfg.draft_coord, draft_point=cfg.draft_point, draft_face=cfg.draft_face,
         hf_ffn_mult=cfg.hf_ffn_mult, ban_specials=cfg.ban_specials, rope_base=cfg.rope_base, rms_eps=cfg.rms_eps,
-        window=getattr(cfg, "window", 0), rules_off=0 if getattr(cfg, "rule_a", 1) else 1)
+        window=getattr(cfg, "window", 0), rules_off=(0 if getattr(cfg, "rule_a", 1) else 1) | (0 if getattr(cfg, "rule_b", 1) else 2))
 
 
 class FlashMesh:
@@ -224,7 +224,7 @@ class FlashMesh:
         elif which == 1:
             shape = (self.batch, max(cfgs.draft_point // 3 - 1, 1), 3)
         else:
-            shape = (self.batch, max(cfgs.draft_face // 3 - 1, 1), 3)
+            shape = (self.batch, max(cfgs.draft_face // 3 - (0 if cfgs.rules_off & 2 else 1), 1), 3)
         out = np.zeros(shape, np.float32)
         self._chk(self.lib.fm_debug_draft(self.h, which, C.c_void_p(out.ctypes.data)), "fm_debug_draft")
         return out

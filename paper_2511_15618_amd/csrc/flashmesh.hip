@@ -653,25 +653,9 @@ int build_persist(fm_ctx* c) {
   a.test_skew = 0;
   a.two_phase = 0;
   if (const char* e = getenv("FM_PK_TWO_PHASE")) a.two_phase = atoi(e);
-  a.xcd_local = 1;
-  if (const char* e = getenv("FM_PK_XCD_LOCAL")) a.xcd_local = atoi(e);
   if (const char* e = getenv("FM_PK_TIMEOUT_TICKS")) a.timeout_ticks = strtoull(e, nullptr, 10);
   if (const char* e = getenv("FM_PK_TEST_SKEW")) a.test_skew = (unsigned)atoi(e);
-  // dynamic LDS: K/V blocks that the attention units stage before their queries arrive, 8 KiB per block and wave.
-  // As many as fit next to the kernel's static LDS on a 160 KiB compute unit, at most 4 (a range of 16 blocks per
-  // unit, i.e. half of the longest configured context at 16 ranges per head).
-  int blocks = a.RS == 32 ? 3 : 4;
-  if (const char* e = getenv("FM_PK_KV_LDS")) blocks = std::max(0, std::min(atoi(e), blocks));
-  while (blocks > 0) {
-    const int bytes = blocks * 4 * 8192;
-    const hipError_t e = a.RS == 32 ? hipFuncSetAttribute((const void*)k_verify_persist<2>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)
-                                    : hipFuncSetAttribute((const void*)k_verify_persist<1>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
-    if (e == hipSuccess) break;
-    (void)hipGetLastError();
-    blocks--;
-  }
-  a.kv_lds_blocks = blocks;
-  c->pk_lds = (size_t)blocks * 4 * 8192;
+  c->pk_lds = 0;   // the kernel uses static LDS only
   // all 256 workgroups must be resident at once: they wait for each other's results
   int dev = 0, cus = 0, per_cu = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
@@ -778,12 +762,12 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   if (g.max_batch < 1 || g.max_batch > 64 || g.max_tokens < 9 || g.max_tokens % 9 != 0) return FM_EINVAL;
   if (g.draft_coord < 0 || g.draft_point < 0 || g.draft_face < 0) return FM_EINVAL;
   if (g.draft_point % 3 != 0 || g.draft_face % 9 != 0) return FM_EINVAL;
-  if ((g.draft_point > 0 || g.draft_face > 0) && g.draft_coord < 2) return FM_EINVAL;  // rule (B) leaves 3 tokens to the coordinate level
+  if ((g.draft_point > 0 || g.draft_face > 0) && g.draft_coord < 2 && !(g.rules_off & 2)) return FM_EINVAL;  // rule (B) leaves 3 tokens to the coordinate level
   const int Bm = std::max(std::max(1 + g.draft_coord, g.draft_point), std::max(g.draft_face, 1));
   if (Bm > 27) return FM_EINVAL;  // rings hold 32 coordinate positions: block + 2 carried rows
   if (!(g.rope_base > 1.f) || !(g.rms_eps > 0.f)) return FM_EINVAL;
   if (g.window < 0 || g.window % 9 != 0) return FM_EINVAL;
-  if (g.rules_off & ~1) return FM_EINVAL;
+  if (g.rules_off & ~3) return FM_EINVAL;
 
   fm_ctx* c = new (std::nothrow) fm_ctx();
   if (!c) return FM_ENOMEM;
@@ -809,7 +793,8 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   }
   D.Dc = g.draft_coord; D.m = g.draft_point; D.n = g.draft_face;
   D.nspv = std::max(D.m / 3 - 1, 0); D.nspf = std::max(D.n / 9 - 1, 0);
-  D.nhfc = std::max(std::max(D.m, D.n) - 3, 0); D.nhfv = std::max(D.n / 3 - 1, 0);
+  D.t0 = (g.rules_off & 2) ? 0 : 3; D.j0 = (g.rules_off & 2) ? 0 : 1;
+  D.nhfc = std::max(std::max(D.m, D.n) - D.t0, 0); D.nhfv = std::max(D.n / 3 - D.j0, 0);
   D.ruleA = (g.rules_off & 1) ? 0 : 1;
   D.nbins = g.n_bins; D.ban = g.ban_specials ? 1 : 0; D.eos = g.n_bins + 1; D.pad = g.n_bins + 2;
   c->Vpad = (D.V + 63) / 64 * 64;

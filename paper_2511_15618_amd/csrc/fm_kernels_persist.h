@@ -35,7 +35,6 @@ typedef unsigned long long u64;
 // which count against the LDS counter as well: every wait for an LDS read would then also wait for the weight
 // or cache loads in flight.  The table therefore holds pointers that are typed as global.
 #define PK_GLOBAL __attribute__((address_space(1)))
-#define PK_LDS __attribute__((address_space(3)))
 typedef const PK_GLOBAL f16_t* pk_cw_t;     // weights, condition-memory caches
 typedef PK_GLOBAL f16_t* pk_w_t;            // self-attention caches (appended to by this kernel)
 typedef const PK_GLOBAL float* pk_cf_t;     // gains
@@ -85,9 +84,6 @@ struct PkArgs {
   u64* w2part;              // [d/16][RS/16][3][256]: partial tiles of the K-quarters 1..3 of the FFN down projection
   unsigned epoch;
   u64 timeout_ticks;        // bound of every wait (100 MHz wall clock)
-  int xcd_local;            // hand-offs between units of one group (a head, the K-quarters of a tile) use ordinary stores:
-                            // the units of a group run on one XCD (workgroup w on XCD w % 8, checked at the start)
-  int kv_lds_blocks;        // K/V blocks per wave that an attention unit stages in (dynamic) LDS before its queries arrive
   int two_phase;            // waits first watch one element per lane and only then read everything (0: the full read is the poll)
   unsigned test_skew;       // test hook: added to the tag the embedding publishes, so that nothing downstream ever arrives
   unsigned* abort_word;     // [0] abort flag, [1] earliest stage that gave up, [2] claim, [3..8] expected tag, tag seen,
@@ -106,19 +102,10 @@ struct PkShared {
 };
 
 __device__ __forceinline__ u64 pk_ld(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-// local = true: an ordinary store, which stops in the L2 of the writer's XCD.  Only for elements whose every reader runs
-// on that same XCD (agent-scope loads look the line up there first): such a hand-off skips the trip through the fabric.
-__device__ __forceinline__ void pk_st(u64* p, unsigned payload, unsigned tag, bool local = false) {
-  const u64 v = ((u64)tag << 32) | payload;
-  if (local) *p = v;
-  else __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ void pk_st(u64* p, unsigned payload, unsigned tag) {
+  __hip_atomic_store(p, ((u64)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ void pk_stf(u64* p, float v, unsigned tag, bool local = false) { pk_st(p, __float_as_uint(v), tag, local); }
-__device__ __forceinline__ unsigned pk_xcc_id() {
-  unsigned v;
-  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(v));
-  return v;
-}
+__device__ __forceinline__ void pk_stf(u64* p, float v, unsigned tag) { pk_st(p, __float_as_uint(v), tag); }
 __device__ __forceinline__ unsigned pk_pack(float lo, float hi) {
   const f16_t a = (f16_t)lo, b = (f16_t)hi;
   return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
@@ -386,7 +373,7 @@ __device__ __forceinline__ void pk_epi_residual(const PkArgs& a, const f32x4& c,
 }
 
 // half-pair epilogue (wave 0): dst[r][n/2] = (c[n], c[n+1]) as halves, optional GELU
-__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu, bool local = false) {
+__device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, int ld2, unsigned tag, int R, bool gelu) {
   const int lane = threadIdx.x & 63, g = lane >> 4, n = nt * 16 + (lane & 15);
 #pragma unroll
   for (int i = 0; i < 4; i++) {
@@ -394,7 +381,7 @@ __device__ __forceinline__ void pk_epi_half(const f32x4& c, int nt, u64* dst, in
     const float w = __shfl_xor(v, 1, 64);
     const int r = g * 4 + i;
     if ((lane & 1) == 0 && r < R) {
-      pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag, local);
+      pk_st(dst + (long)r * ld2 + (n >> 1), pk_pack(v, w), tag);
     }
   }
 }
@@ -418,7 +405,7 @@ __device__ __forceinline__ void pk_qkv_prefetch(int nt, int d, int R, const int*
 }
 template <int QT>
 __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, const f32x4& c, int nt, unsigned tag, int R,
-                                           const PkQkvPre& pre, int capb, int row0, bool local) {
+                                           const PkQkvPre& pre, int capb, int row0) {
   const int lane = threadIdx.x & 63, g = lane >> 4, col = lane & 15;
   const int d = a.D.d;
   const int part = (nt * 16) / d, cp = (nt * 16) % d;
@@ -441,10 +428,10 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
     const int p = pre.p[i];
     if (r < R) {
       if (part == 0) {
-        if ((lane & 1) == 0) pk_st(a.q + (long)(row0 + r) * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag, local);
+        if ((lane & 1) == 0) pk_st(a.q + (long)(row0 + r) * (d >> 1) + ((hh * 64 + dim) >> 1), pk_pack(v, w), tag);
       } else {
         u64* nb = (part == 1 ? a.newK : a.newV) + ((long)hh * (QT * 16) + row0 + r) * 32;
-        if ((lane & 1) == 0) pk_st(nb + (dim >> 1), pk_pack(v, w), tag, local);
+        if ((lane & 1) == 0) pk_st(nb + (dim >> 1), pk_pack(v, w), tag);
         if (p >= 0) {
           const int ps = p % (capb * 32);      // the cache is a ring when a window is set
           const long base = (long)hh * capb * 2048;
@@ -465,8 +452,7 @@ __device__ __forceinline__ void pk_epi_qkv(const PkArgs& a, const PkLayer& L, co
 template <int QT, class SH>
 __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64* qbuf, const int (&lim)[QT], int maxlim, int R,
                                              pk_cw_t Kc, pk_cw_t Vc, int capb, int nsplit_cfg, int hh, int split,
-                                             bool overlay, int P0, u64* part, unsigned tag, int stage, int window,
-                                             PK_LDS unsigned char* kvlds) {
+                                             bool overlay, int P0, u64* part, unsigned tag, int stage, int window) {
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int g = lane >> 4, ql = lane & 15;
   const int d = a.D.d;
@@ -502,34 +488,17 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
       if (b >= b0 + wave && b < b1 && ((b - b0 - wave) & 3) == 0) bov = b;
     }
   }
-  // The K/V blocks of this wave (b0 + wave, + 4, ...) depend on nothing from this pass: they are requested before the
-  // wait for q.  The first `nbl` of them go straight from global memory into this wave's own LDS region (8 KiB per
-  // block: the K block, then the V block, both verbatim, so a fragment is lane * 16 bytes into its KiB as in global
-  // memory); the one after those goes into registers, and later ones follow one at a time while the loop multiplies.
+  // the first K/V block of this wave depends on nothing from this pass: request it before waiting for q
   pk_cw_t Kb = Kc + (long)hh * capb * 2048;
   pk_cw_t Vb = Vc + (long)hh * capb * 2048;
-  const int nwb = b0 + wave < b1 ? (b1 - b0 - wave + 3) >> 2 : 0;      // blocks of this wave
-  const int nbl = min(nwb, a.kv_lds_blocks);
-  PK_LDS unsigned char* const kvw = kvlds + wave * a.kv_lds_blocks * 8192;
-  for (int i = 0; i < nbl; i++) {
-    const long blk = (long)(b0 + wave + 4 * i) * 2048;
+  f16x8 kf[4], vf[4];
+  if (b0 + wave < b1) {
+    pk_cw_t kp = Kb + (long)(b0 + wave) * 2048 + lane * 8;
+    pk_cw_t vp = Vb + (long)(b0 + wave) * 2048 + (lane & 15) * 32 + g * 8;
 #pragma unroll
-    for (int f = 0; f < 4; f++) {
-      __builtin_amdgcn_global_load_lds(Kb + blk + f * 512 + lane * 8, (PK_LDS void*)(kvw + i * 8192 + f * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(Vb + blk + f * 512 + lane * 8, (PK_LDS void*)(kvw + i * 8192 + 4096 + f * 1024), 16, 0, 0);
-    }
-  }
-  f16x8 kf[4], vf[4], kn[4], vn[4];
+    for (int f = 0; f < 4; f++) kf[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
 #pragma unroll
-  for (int f = 0; f < 4; f++) { kf[f] = f16x8{}; vf[f] = f16x8{}; kn[f] = f16x8{}; vn[f] = f16x8{}; }
-  const int br = b0 + wave + 4 * nbl;          // first block that comes through registers
-  if (br < b1) {
-    pk_cw_t kp = Kb + (long)br * 2048 + lane * 8;
-    pk_cw_t vp = Vb + (long)br * 2048 + (lane & 15) * 32 + g * 8;
-#pragma unroll
-    for (int f = 0; f < 4; f++) kn[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
-#pragma unroll
-    for (int dt = 0; dt < 4; dt++) vn[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
+    for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
   }
   // q of this lane: dims g*8..+8 and 32 + g*8..+8 of the head = two runs of four tagged elements = four 16-byte
   // agent-scope loads per query tile, simply repeated until every tag matches (small enough to poll with the data itself)
@@ -562,7 +531,6 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
         }
       if (__all(okq)) break;
       if ((++it & 7) == 0 && pk_expired(a, t0, stage)) { ok = false; break; }
-      __builtin_amdgcn_s_sleep(2);
     }
 #pragma unroll
     for (int t = 0; t < QT; t++) {
@@ -599,26 +567,16 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
 #pragma unroll
     for (int dt = 0; dt < 4; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  for (int b = b0 + wave, bi = 0; b < b1; b += 4, bi++) {
-    if (bi < nbl) {
-      // from this wave's LDS region (complete: the wait for q drained every outstanding load of the wave)
-      const PK_LDS unsigned char* kb = kvw + bi * 8192;
+  for (int b = b0 + wave; b < b1; b += 4) {
+    // the next block of this wave is requested before the current one is multiplied
+    f16x8 kn[4], vn[4];
+    if (b + 4 < b1) {
+      pk_cw_t kp = Kb + (long)(b + 4) * 2048 + lane * 8;
+      pk_cw_t vp = Vb + (long)(b + 4) * 2048 + (lane & 15) * 32 + g * 8;
 #pragma unroll
-      for (int f = 0; f < 4; f++) kf[f] = *(const PK_LDS f16x8*)(kb + f * 1024 + lane * 16);
+      for (int f = 0; f < 4; f++) kn[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++) vf[dt] = *(const PK_LDS f16x8*)(kb + 4096 + dt * 1024 + (lane & 15) * 64 + g * 16);
-    } else {
-      // from registers: the block requested one iteration (or the prologue) ago; the next one goes out at once
-#pragma unroll
-      for (int f = 0; f < 4; f++) { kf[f] = kn[f]; vf[f] = vn[f]; }
-      if (b + 4 < b1) {
-        pk_cw_t kp = Kb + (long)(b + 4) * 2048 + lane * 8;
-        pk_cw_t vp = Vb + (long)(b + 4) * 2048 + (lane & 15) * 32 + g * 8;
-#pragma unroll
-        for (int f = 0; f < 4; f++) kn[f] = *(const PK_GLOBAL f16x8*)(kp + f * 512);
-#pragma unroll
-        for (int dt = 0; dt < 4; dt++) vn[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
-      }
+      for (int dt = 0; dt < 4; dt++) vn[dt] = *(const PK_GLOBAL f16x8*)(vp + dt * 512);
     }
     if (b == bov) {
 #pragma unroll
@@ -683,6 +641,10 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
         o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[t][dt], 0, 0, 0);
       }
     }
+    if (b + 4 < b1) {
+#pragma unroll
+      for (int f = 0; f < 4; f++) { kf[f] = kn[f]; vf[f] = vn[f]; }
+    }
   }
 #pragma unroll
   for (int t = 0; t < QT; t++) {
@@ -710,8 +672,8 @@ __device__ __forceinline__ bool pk_attn_unit(const PkArgs& a, SH& sh, const u64*
     if (qi < R) {
       u64* pt = part + (long)(qi >> 4) * PK_PART;      // the row's tile
       const int ql16 = qi & 15;
-      pk_stf(pt + ql16 * 64 + dim, num, tag, a.xcd_local);
-      if (dim == 0) { pk_stf(pt + 16 * 64 + ql16, M, tag, a.xcd_local); pk_stf(pt + 16 * 64 + 16 + ql16, den, tag, a.xcd_local); }
+      pk_stf(pt + ql16 * 64 + dim, num, tag);
+      if (dim == 0) { pk_stf(pt + 16 * 64 + ql16, M, tag); pk_stf(pt + 16 * 64 + 16 + ql16, den, tag); }
     }
   }
   __syncthreads();
@@ -772,16 +734,6 @@ __device__ __forceinline__ bool pk_merge_unit(const PkArgs& a, int maxlim, int R
 // The kernel
 // ------------------------------------------------------------------------------------------
 #define PK_MINE(units) for (int u = (int)((blockIdx.x + PK_NWG - (rr % PK_NWG)) % PK_NWG); u < (units) && (worked = true); u += PK_NWG)
-// Units that hand results to each other only inside a group (the tiles, key ranges and merges of one head; the K-quarters
-// of one tile) are dealt so that group g runs on XCD g % 8: workgroup w sits on XCD w % 8, and row w / 8 of that XCD
-// takes the slots row, row + 32, ... of its groups (slot = group / 8 * UPG + unit of the group); the rows rotate from
-// stage to stage like the plain dealing does.  Inside the loop: PK_GROUP(UPG) and PK_UNIT(UPG).
-#define PK_MINE_GROUPED(G, UPG)                                                                                \
-  for (int s_ = (int)(((blockIdx.x >> 3) + 32u - ((rr >> 3) & 31u)) & 31u), sl_ = (((G) + 7) >> 3) * (UPG);   \
-       s_ < sl_ && (worked = true); s_ += 32)
-#define PK_GROUP(UPG) ((int)(blockIdx.x & 7) + 8 * (s_ / (UPG)))
-#define PK_UNIT(UPG) (s_ % (UPG))
-#define PK_GROUPED_SLOTS(G, UPG) (8 * ((((G) + 7) >> 3) * (UPG)))
 #define PK_NEXT(units)                                                                              \
   do {                                                                                              \
     if (a.prof && worked && threadIdx.x == 0) atomicMax(a.prof + 1 + stage, (u64)wall_clock64());   \
@@ -794,8 +746,6 @@ template <int QT>
 __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   if (*a.run_flag == 0) return;
   __shared__ PkShared<QT> sh;
-  extern __shared__ __attribute__((aligned(16))) unsigned char pk_kvlds_[];      // 4 waves x kv_lds_blocks x 8 KiB
-  PK_LDS unsigned char* const pk_kvlds = (PK_LDS unsigned char*)pk_kvlds_;
   const int RS = QT * 16, RH = QT * 8;     // rows of an exchange region (= a.RS), and half of it: the row count of a half-pair region in units of d
   const int d = a.D.d, H = a.D.H, ff = a.ff;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -803,11 +753,6 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
   int stage = 0;
   bool worked = false;
   if (a.prof && threadIdx.x == 0) atomicMin(a.prof, (u64)wall_clock64());
-  if (a.xcd_local && threadIdx.x == 0 && pk_xcc_id() != (blockIdx.x & 7u)) {
-    // the ordinary-store hand-offs assume workgroup w on XCD w % 8: give up the pass (the host then leaves this path)
-    __hip_atomic_store(a.abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    atomicMin(a.abort_word + 1, 9999u);
-  }
 
   // Per level and the same for all of its layers: the last visible key of this lane's query row in the
   // self-attention (its own position) and in the cross-attention, the block maxima, the first position of the pass.
@@ -873,41 +818,32 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // in every exchange buffer, so a unit is the one-group code on offset pointers
       const int RG = QT == 1 ? 1 : (R + 15) >> 4;      // a compile-time 1 for blocks of up to 16 tokens
       const long hd = d >> 1;
-      // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append): the 12 tiles of a head form a group
-      {
-        const int UPG = 12 * RG;
-        PK_MINE_GROUPED(H, UPG) {
-          const int hh = PK_GROUP(UPG), k = PK_UNIT(UPG);
-          if (hh >= H) continue;
-          const int j = k / RG, row0 = (k % RG) * 16, Rl = min(16, R - row0);
-          const int nt = (j >> 2) * (d / 16) + hh * 4 + (j & 3);      // part (q, k, v), head, quarter of the head
-          f32x4 c;
-          PkQkvPre pre;
-          if (wave == 0) pk_qkv_prefetch(nt, d, Rl, pos + row0, a.cs[lev] + (long)row0 * 32, pre);
-          if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)nt * (d / 32) * 512, d / 32, xA_l + row0 * hd, tag, L.g1, Rl, c, stage)) return;
-          if (wave == 0) pk_epi_qkv<QT>(a, L, c, nt, tag, Rl, pre, capb, row0, a.xcd_local);
-          __syncthreads();
-        }
-        PK_NEXT(PK_GROUPED_SLOTS(H, UPG));
+      // ---- QKV (norm1 on the fly, rotary, q / new K,V out, cache append)
+      PK_MINE(3 * d / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
+        f32x4 c;
+        PkQkvPre pre;
+        if (wave == 0) pk_qkv_prefetch(nt, d, Rl, pos + row0, a.cs[lev] + (long)row0 * 32, pre);
+        if (!pk_gemm_tile<1>(a, sh, L.wqkv + (long)nt * (d / 32) * 512, d / 32, xA_l + row0 * hd, tag, L.g1, Rl, c, stage)) return;
+        if (wave == 0) pk_epi_qkv<QT>(a, L, c, nt, tag, Rl, pre, capb, row0);
+        __syncthreads();
       }
+      PK_NEXT(3 * d / 16 * RG);
       // ---- self-attention splits
       {
         const int ns = a.nsplit[lev];
         const int P0 = firstP[lev];
-        PK_MINE_GROUPED(H, ns) {
-          const int hh = PK_GROUP(ns), sp = PK_UNIT(ns);
-          if (hh >= H) continue;
+        PK_MINE(H * ns) {
+          const int hh = u / ns, sp = u % ns;
           if (!pk_attn_unit<QT>(a, sh, a.q, limS[lev], maxS[lev], R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
-                                a.partS + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, a.win[lev], pk_kvlds)) return;
+                                a.partS + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, a.win[lev])) return;
         }
-        PK_NEXT(PK_GROUPED_SLOTS(H, ns));
-        PK_MINE_GROUPED(H, 4 * RG) {
-          const int hh = PK_GROUP(4 * RG), k = PK_UNIT(4 * RG);
-          if (hh >= H) continue;
-          const int dq = k / RG, rg = k % RG;
-          if (!pk_merge_unit<QT>(a, maxS[lev], min(16, R - rg * 16), rg, capb, ns, hh, dq, a.partS, att_l, tag, stage)) return;
+        PK_NEXT(H * ns);
+        PK_MINE(4 * H * RG) {
+          const int v = u / RG, rg = u % RG;
+          if (!pk_merge_unit<QT>(a, maxS[lev], min(16, R - rg * 16), rg, capb, ns, v >> 2, v & 3, a.partS, att_l, tag, stage)) return;
         }
-        PK_NEXT(PK_GROUPED_SLOTS(H, 4 * RG));
+        PK_NEXT(4 * H * RG);
       }
       // ---- Wo + residual -> hB (tap: the layer input is what the draft heads of this level start from)
       PK_MINE(d / 16 * RG) {
@@ -924,34 +860,29 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         if (__syncthreads_or(!okr)) return;
       }
       PK_NEXT(d / 16 * RG);
-      // ---- cross-attention query (norm2 on the fly): the 4 tiles of a head form a group
-      PK_MINE_GROUPED(H, 4 * RG) {
-        const int hh = PK_GROUP(4 * RG), k = PK_UNIT(4 * RG);
-        if (hh >= H) continue;
-        const int nt = hh * 4 + k / RG, row0 = (k % RG) * 16, Rl = min(16, R - row0);
+      // ---- cross-attention query (norm2 on the fly)
+      PK_MINE(d / 16 * RG) {
+        const int nt = u / RG, row0 = (u % RG) * 16, Rl = min(16, R - row0);
         f32x4 c;
         if (!pk_gemm_tile<1>(a, sh, L.cq + (long)nt * (d / 32) * 512, d / 32, xB_l + row0 * hd, tag, L.g2, Rl, c, stage)) return;
-        if (wave == 0) pk_epi_half(c, nt, a.q2 + row0 * hd, d >> 1, tag, Rl, false, a.xcd_local);
+        if (wave == 0) pk_epi_half(c, nt, a.q2 + row0 * hd, d >> 1, tag, Rl, false);
         __syncthreads();
       }
-      PK_NEXT(PK_GROUPED_SLOTS(H, 4 * RG));
+      PK_NEXT(d / 16 * RG);
       // ---- cross-attention over the condition memory
       {
         const int ns = a.nsplitM;
-        PK_MINE_GROUPED(H, ns) {
-          const int hh = PK_GROUP(ns), sp = PK_UNIT(ns);
-          if (hh >= H) continue;
+        PK_MINE(H * ns) {
+          const int hh = u / ns, sp = u % ns;
           if (!pk_attn_unit<QT>(a, sh, a.q2, limX[lev], maxX[lev], R, L.Km, L.Vm, a.capbM, ns, hh, sp, false, 0,
-                                a.partX + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, 0, pk_kvlds)) return;
+                                a.partX + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, 0)) return;
         }
-        PK_NEXT(PK_GROUPED_SLOTS(H, ns));
-        PK_MINE_GROUPED(H, 4 * RG) {
-          const int hh = PK_GROUP(4 * RG), k = PK_UNIT(4 * RG);
-          if (hh >= H) continue;
-          const int dq = k / RG, rg = k % RG;
-          if (!pk_merge_unit<QT>(a, maxX[lev], min(16, R - rg * 16), rg, a.capbM, ns, hh, dq, a.partX, att2_l, tag, stage)) return;
+        PK_NEXT(H * ns);
+        PK_MINE(4 * H * RG) {
+          const int v = u / RG, rg = u % RG;
+          if (!pk_merge_unit<QT>(a, maxX[lev], min(16, R - rg * 16), rg, a.capbM, ns, v >> 2, v & 3, a.partX, att2_l, tag, stage)) return;
         }
-        PK_NEXT(PK_GROUPED_SLOTS(H, 4 * RG));
+        PK_NEXT(4 * H * RG);
       }
       // ---- cross output projection + residual -> hC
       PK_MINE(d / 16 * RG) {
@@ -978,10 +909,9 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
       // ---- FFN down + residual -> next layer input, or the stack output (+ its ring for later passes).
       // K = ff is four times longer than in the other GEMMs, so a tile is computed by four units, one per
       // K-quarter; quarters 1..3 hand their partial tile to quarter 0, which adds them in a fixed order.
-      PK_MINE_GROUPED(d / 16, 4 * RG) {
-        const int nt = PK_GROUP(4 * RG), k = PK_UNIT(4 * RG);
-        if (nt >= d / 16) continue;
-        const int kq = k / RG, rg = k % RG, row0 = rg * 16, Rl = min(16, R - row0);
+      PK_MINE(4 * (d / 16) * RG) {
+        const int uv = u / RG, rg = u % RG, row0 = rg * 16, Rl = min(16, R - row0);
+        const int nt = uv >> 2, kq = uv & 3;
         const int KTq = ff / 128;                       // fragments of one K-quarter
         u64* const w2p = a.w2part + ((long)nt * RG + rg) * 3 * 256;
         f32x4 c;
@@ -995,7 +925,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
           const int lane = threadIdx.x & 63;
           if (kq > 0) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) pk_stf(w2p + (long)(kq - 1) * 256 + i * 64 + lane, c[i], tag, a.xcd_local);
+            for (int i = 0; i < 4; i++) pk_stf(w2p + (long)(kq - 1) * 256 + i * 64 + lane, c[i], tag);
           } else {
             unsigned pr[12];
             okr = pk_fetch<12>(pr, 12, true, tag, [&](int i) { return w2p + (long)(i >> 2) * 256 + (i & 3) * 64 + lane; },
@@ -1022,7 +952,7 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         }
         if (__syncthreads_or(!okr)) return;
       }
-      PK_NEXT(PK_GROUPED_SLOTS(d / 16, 4 * RG));
+      PK_NEXT(4 * (d / 16) * RG);
     }
     // ---- level transition after stack st; everything it produces carries the tag of the next layer
     const int ln = a.first[st] + a.count[st];

@@ -17,6 +17,8 @@ struct Dims {
   int nhfc, nhfv;        // HF parameter sets at the coordinate / vertex level
   int nbins, ban, eos, pad;
   int ruleA;             // rule (A) of the supplement: no point-level prediction at a face split node
+  int t0, j0;            // rule (B): first coordinate offset (3, or 0 with the rule off) and first vertex offset (1 / 0)
+                         // that own an HF parameter set; offsets below them are left to the coordinate level
 };
 
 struct StateDev {
@@ -296,23 +298,24 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
     for (int k = grp; k < D.nspv; k += 8) set_row(R, 1, s * D.nspv + k, tapv, v, firev ? v : -1, D.M, inv, lane32);
     // set 2: face SP heads on the face tap of f
     for (int k = grp; k < D.nspf; k += 8) set_row(R, 2, s * D.nspf + k, tapf, f, firef ? f : -1, D.M, inv, lane32);
-    // set 3: vertex-level HF, vertex offsets j = 1..n/3-1 from vertex token 3f; input = face feature j/3
+    // set 3: vertex-level HF, vertex offsets j = j0..n/3-1 from vertex token 3f; input = face feature j/3
     for (int q = grp; q < D.nhfv; q += 8) {
-      const int j = q + 1;
+      const int j = q + D.j0;
       const float* src = (j < 3) ? yf : B.spf_out + ((long)s * D.nspf + (j / 3 - 1)) * d;
       set_row(R, 3, s * D.nhfv + q, src, 3 * f + j, firef ? 3 * f : -1, D.M, inv, lane32);
     }
-    // set 4: coordinate-level HF, offsets t = 3..; pipe 0 = point pipeline, pipe 1 = face pipeline
+    // set 4: coordinate-level HF, offsets t = t0..; pipe 0 = point pipeline, pipe 1 = face pipeline
     for (int q = grp; q < 2 * D.nhfc; q += 8) {
-      const int pipe = q / D.nhfc, t = q % D.nhfc + 3;
+      const int pipe = q / D.nhfc, t = q % D.nhfc + D.t0;
       const int r = s * 2 * D.nhfc + q;
       if (pipe == 0) {
         const bool on = firev && t < D.m;
-        const float* src = B.spv_out + ((long)s * max(D.nspv, 1) + min(t / 3 - 1, max(D.nspv - 1, 0))) * d;
+        // offsets 0..2 (rule (B) off) belong to the current vertex: its own feature; later ones to the SP head outputs
+        const float* src = t < 3 ? tapv : B.spv_out + ((long)s * max(D.nspv, 1) + min(t / 3 - 1, max(D.nspv - 1, 0))) * d;
         set_row(R, 4, r, src, 3 * v + t, on ? 3 * v : -1, D.M, inv, lane32);
       } else {
         const bool on = firef && t < D.n;
-        const float* src = B.hfv_out + ((long)s * max(D.nhfv, 1) + min(t / 3 - 1, max(D.nhfv - 1, 0))) * d;
+        const float* src = B.hfv_out + ((long)s * max(D.nhfv, 1) + min(max(t / 3 - D.j0, 0), max(D.nhfv - 1, 0))) * d;
         set_row(R, 4, r, src, 9 * f + t, on ? 9 * f : -1, D.M, inv, lane32);
       }
     }
@@ -332,9 +335,9 @@ __global__ __launch_bounds__(256) void k_dist_store(const float* __restrict__ lo
   } else {
     const int rr = r - D.S * D.Dc;
     const int s = rr / (2 * D.nhfc), q = rr % (2 * D.nhfc);
-    const int pipe = q / D.nhfc, t = q % D.nhfc + 3;
-    if (pipe == 0 && R.firev[s] && t < D.m) dst = dist_v + ((long)s * D.nhfc + (t - 3)) * D.V;
-    if (pipe == 1 && R.firef[s] && t < D.n) dst = dist_f + ((long)s * D.nhfc + (t - 3)) * D.V;
+    const int pipe = q / D.nhfc, t = q % D.nhfc + D.t0;
+    if (pipe == 0 && R.firev[s] && t < D.m) dst = dist_v + ((long)s * D.nhfc + (t - D.t0)) * D.V;
+    if (pipe == 1 && R.firef[s] && t < D.n) dst = dist_f + ((long)s * D.nhfc + (t - D.t0)) * D.V;
   }
   if (!dst) return;
   const float* x = logits + (long)r * D.V;
@@ -479,9 +482,9 @@ __global__ __launch_bounds__(1024) void k_merge(StateDev st, Dims D, DraftRows R
     const int kc = p - (basec + 2);
     if (kc >= 0 && kc < D.Dc) rows[cnt++] = dist_c + ((long)s * D.Dc + kc) * D.V;
     const int tv = p - 1 - basev;
-    if (basev >= 0 && tv >= 3 && tv < D.m) rows[cnt++] = dist_v + ((long)s * D.nhfc + (tv - 3)) * D.V;
+    if (basev >= 0 && tv >= D.t0 && tv < D.m) rows[cnt++] = dist_v + ((long)s * D.nhfc + (tv - D.t0)) * D.V;
     const int tf = p - 1 - basef;
-    if (basef >= 0 && tf >= 3 && tf < D.n) rows[cnt++] = dist_f + ((long)s * D.nhfc + (tf - 3)) * D.V;
+    if (basef >= 0 && tf >= D.t0 && tf < D.n) rows[cnt++] = dist_f + ((long)s * D.nhfc + (tf - D.t0)) * D.V;
     return cnt;
   };
   if (sm.temperature > 0.f) {
@@ -649,8 +652,8 @@ __global__ void k_correct(StateDev st, Dims D, const float* __restrict__ lab_v, 
       cnt++;
     }
     const int jf = basef >= 0 ? u - basef / 3 : 0;
-    if (basef >= 0 && jf >= 1 && jf <= D.nhfv) {
-      const float* row = lab_f + ((long)s * D.nhfv + jf - 1) * 3;
+    if (basef >= 0 && jf >= D.j0 && jf < D.j0 + D.nhfv) {
+      const float* row = lab_f + ((long)s * D.nhfv + jf - D.j0) * 3;
       a[0] += row[0]; a[1] += row[1]; a[2] += row[2];
       cnt++;
     }

@@ -48,6 +48,7 @@ class Config:
     rms_eps: float = 1e-6
     window: int = 0       # self-attention window in coordinate tokens (multiple of 9); 0 = the whole context
     rule_a: int = 1       # supplement "Optimizations", rule (A): no point-level prediction where a face-level one fires
+    rule_b: int = 1       # rule (B): the point / face levels leave their first three tokens to the coordinate level
 
     @property
     def vocab(self) -> int:
@@ -114,6 +115,10 @@ TEST_CONFIGS = {
     # rule (A) of the supplement switched off: the point level also fires at face split nodes (three levels overlap there)
     "t_f32_99_noA": Config("t_f32_99_noA", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 6, 2, 9, 9, rule_a=0),
     "t_bf16_1815_noA": Config("t_bf16_1815_noA", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18, rule_a=0),
+    # rule (B) off as well: HF sets for the first three coordinate offsets and the vertex offset 0
+    "t_f32_99_noB": Config("t_f32_99_noB", 128, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 6, 2, 9, 9, rule_b=0),
+    "t_bf16_1815_noAB": Config("t_bf16_1815_noAB", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18, rule_a=0, rule_b=0),
+    "t_bf16_99_b1_noB": Config("t_bf16_99_b1_noB", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9, rule_b=0),
     "t_bf16_99_b1_noA": Config("t_bf16_99_b1_noA", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9, rule_a=0),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
     # blocks longer than 16 tokens at one sequence (two row groups at the coordinate level of the single-launch verify kernel)
@@ -143,13 +148,13 @@ def sp_head_counts(cfg: Config) -> dict:
 
 
 def hf_coord_offsets(cfg: Config) -> range:
-    """Coordinate offsets t that own an HF parameter set (offsets 0..2 are left to the coordinate level)."""
-    return range(3, max(cfg.draft_point, cfg.draft_face))
+    """Coordinate offsets t that own an HF parameter set (under rule (B) offsets 0..2 are left to the coordinate level)."""
+    return range(3 if cfg.rule_b else 0, max(cfg.draft_point, cfg.draft_face))
 
 
 def hf_vertex_offsets(cfg: Config) -> range:
     """Vertex offsets j (from the face split node) that own a vertex-level HF parameter set."""
-    return range(1, cfg.draft_face // 3) if cfg.draft_face else range(0)
+    return range(1 if cfg.rule_b else 0, cfg.draft_face // 3) if cfg.draft_face else range(0)
 
 
 def manifest(cfg: Config):

@@ -119,9 +119,10 @@ def _check_dist_rows(rep, dev_rows, merged, nlim, tol, cfg):
 def _check_label_rows(rep, cfg, st, lab_v, lab_f, tol):
     """Label distributions the two pipelines hold (Sec. 3.2): point pipeline row k - 1 is vertex v + k of its last
     firing at vertex token v, face pipeline row j - 1 is vertex 3f + j of its last firing at face token f."""
-    for rows, dev, first in ((st.labels["v"], lab_v, st.fired_v), (st.labels["f"], lab_f, 3 * st.fired_f)):
+    j0 = 1 if getattr(cfg, "rule_b", 1) else 0       # first vertex offset of the face pipeline that owns a row
+    for rows, dev, first in ((st.labels["v"], lab_v, st.fired_v + 1), (st.labels["f"], lab_f, 3 * st.fired_f + j0)):
         for u, ref in rows.items():
-            rep.max_label_logerr = max(rep.max_label_logerr, _log_err(dev[u - first - 1], ref))
+            rep.max_label_logerr = max(rep.max_label_logerr, _log_err(dev[u - first], ref))
             rep.label_rows += 1
     assert rep.max_label_logerr <= 2.0 * tol, ("label distribution beyond tolerance", rep.steps, rep.max_label_logerr)
 

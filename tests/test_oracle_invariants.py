@@ -359,6 +359,35 @@ def test_rule_a_switched_off_lets_the_point_level_fire_at_face_nodes():
     assert a == b
 
 
+def test_rule_b_switched_off_keeps_the_first_three_tokens_of_the_upper_levels():
+    """Supplement "Optimizations": rule (B) drops the first three tokens of a point- or face-level prediction because the
+    coordinate level predicts them anyway.  With the rule off the upper levels keep them (offset 0 is the main token's
+    own slot and is never asked for), so the two coordinate-level positions are covered twice and the block length stays."""
+    cfg, m, mem = _model("t_f32_99", draft_face=0, faces=4, rule_b=0)
+    rec = _walk(cfg, m, mem, 18)
+    for s in (3, 6, 12, 15):                                   # point split nodes (face level off, as in the 9-9 example)
+        main = s + 1
+        assert rec[s]["v"] == list(range(main, main + cfg.draft_point))
+        assert rec[s]["c"] == [main + 1, main + 2] and rec[s]["len"] == 9
+        assert sorted(set(rec[s]["c"]) & set(rec[s]["v"])) == [main + 1, main + 2]
+        if s + 1 in rec:                                       # one position later: one token shorter, both fresh rows doubled
+            assert rec[s + 1]["len"] == 8
+            assert sorted(set(rec[s + 1]["c"]) & set(rec[s + 1]["v"])) == [main + 2, main + 3]
+    cfg, m, mem = _model("t_f32_1815", faces=6, rule_a=0, rule_b=0)
+    rec = _walk(cfg, m, mem, 30)
+    for s in sorted(rec):
+        main = s + 1
+        if s % 9 == 0:
+            assert rec[s]["f"] == list(range(main, main + cfg.draft_face)) and rec[s]["len"] == 18
+        if s % 3 == 0:
+            assert rec[s]["v"] == list(range(main, main + cfg.draft_point))
+    a, _ = sp.generate(m, mem, 4, speculative=True)
+    b, _ = sp.generate(m, mem, 4, speculative=False)
+    assert a == b
+    assert sp.point_targets(2, 9, rule_b=False) == list(range(7, 16)) and sp.point_targets(2, 9) == list(range(10, 16))
+    assert sp.face_targets(1, 9, rule_b=False) == list(range(10, 19)) and sp.face_targets(1, 9) == list(range(13, 19))
+
+
 # -- T7: residual wiring of the draft heads ------------------------------------------------------
 def test_sp_and_hf_residual_wiring():
     cfg, m, mem = _model("t_f32_99", faces=3)
