@@ -62,7 +62,7 @@ class Model:
         return x @ self.w[name].T
 
     def heads(self, x):
-        return x.reshape(x.shape[0], self.H, P.HEAD_DIM)
+        return x.reshape(x.shape[0], self.H, self.d // self.H)
 
     def qkv(self, pfx, h, pos):
         """Pre-norm, projections and rotary position for self-attention."""
@@ -174,8 +174,8 @@ class SeqState:
             cap = self.caps[LEVEL_OF[st]]
             for i in range(m.layers[st]):
                 pfx = f"{st}.{i}."
-                self.K[pfx] = z(cap, m.H, P.HEAD_DIM)
-                self.V[pfx] = z(cap, m.H, P.HEAD_DIM)
+                self.K[pfx] = z(cap, m.H, m.d // m.H)
+                self.V[pfx] = z(cap, m.H, m.d // m.H)
                 self.Kmem[pfx], self.Vmem[pfx] = m.mem_kv(pfx, mem)
         self.h_c = z(cap_c, m.d)   # coordinate pre-stack outputs (pool input, skip)
         self.h_v = z(cap_v, m.d)   # vertex pre-stack outputs

@@ -14,7 +14,7 @@ from __future__ import annotations
 
 import numpy as np
 
-HEAD_DIM = 64
+HEAD_DIM = 64      # head width of the five benchmark configurations; every function below takes the width from its operands
 
 
 def bf16_round(x):
@@ -43,10 +43,11 @@ def softmax(x):
 
 
 def rope(x, pos, base):
-    """Rotary position embedding on [rows, heads, 64] with half-split pairing (i, i+32).
+    """Rotary position embedding on [rows, heads, hd] with half-split pairing (i, i + hd/2).
 
-    Pair i is rotated by the angle pos * base**(-i/32)."""
-    half = HEAD_DIM // 2
+    Pair i is rotated by the angle pos * base**(-i/(hd/2)); hd = 64 in the benchmark configurations, 96 / 128 in the
+    paper's own model shapes (Sec. 5.1)."""
+    half = x.shape[-1] // 2
     pos = np.asarray(pos, dtype=np.float64)
     inv = base ** (-np.arange(half, dtype=np.float64) / half)
     ang = pos[:, None] * inv[None, :]                     # [rows, 32], always float64
@@ -59,13 +60,13 @@ def rope(x, pos, base):
 def attend(q, K, V, limit, window=0):
     """Scaled dot-product attention, one query row at a time over keys [first, limit[row]].
 
-    q [rows, H, 64]; K, V [L, H, 64]; limit[row] is the last visible key (inclusive).
+    q [rows, H, hd]; K, V [L, H, hd]; limit[row] is the last visible key (inclusive).
     window = 0: first = 0.  window = W > 0 (sliding window, Sec. 5.1 "window size"): a row sees the
     W keys that end at its limit, first = max(0, limit[row] - W + 1).
-    Scores are scaled by 1/sqrt(64); softmax in the working precision."""
-    rows, H, _ = q.shape
+    Scores are scaled by 1/sqrt(hd); softmax in the working precision."""
+    rows, H, hd = q.shape
     out = np.zeros_like(q)
-    scale = 1.0 / np.sqrt(HEAD_DIM)
+    scale = 1.0 / np.sqrt(hd)
     lim = np.asarray(limit)
     if rows and np.all(lim == lim[0]):
         # all rows see the same keys: one batched product per head
@@ -87,9 +88,9 @@ def attend_causal(q, K, V, first_pos, window=0):
 
     Same result as attend(q, K, V, first_pos + arange(rows), window) but with one masked
     matrix product per head, for long teacher-forced blocks."""
-    rows, H, _ = q.shape
+    rows, H, hd = q.shape
     n = first_pos + rows
-    scale = 1.0 / np.sqrt(HEAD_DIM)
+    scale = 1.0 / np.sqrt(hd)
     s = np.matmul(q.transpose(1, 0, 2), K[:n].transpose(1, 2, 0)) * scale        # [H, rows, n]
     kk = np.arange(n)[None, :]
     rr = (first_pos + np.arange(rows))[:, None]

@@ -201,8 +201,10 @@ void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, co
   if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, window, c->stream)) return;
   // the plain kernel reads row-major caches: only the fp32 path has those
   if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "attention: unsupported row set (%d rows, %d per sequence)", rows, RPS); c->sticky_error = true; return; }
-  hipLaunchKernelGGL((k_attn_simple<T>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS,
-                     (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag, window);
+#define FM_ATTN(HDV) hipLaunchKernelGGL((k_attn_simple<T, HDV>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS, \
+                                        (const T*)Kc, (const T*)Vc, seq_stride, cap, (T*)out, c->D.H, flag, window)
+  if (c->D.hd == 64) FM_ATTN(64); else if (c->D.hd == 96) FM_ATTN(96); else FM_ATTN(128);
+#undef FM_ATTN
 }
 
 template <typename T>
@@ -236,14 +238,17 @@ void rope_append(fm_ctx* c, const float* qkv, long ldq, const float2* cs, const 
   if (std::is_same<T, f16_t>::value)
     hipLaunchKernelGGL(k_rope_append_h, dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (f16_t*)q, (f16_t*)Kc,
                        (f16_t*)Vc, c->D.H, (cap + 31) / 32, flag);
-  else
-    hipLaunchKernelGGL((k_rope_append<float>), dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (float*)q,
-                       (float*)Kc, (float*)Vc, c->D.H, cap, flag);
+  else {
+#define FM_ROPE(HDV) hipLaunchKernelGGL((k_rope_append<float, HDV>), dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (float*)q, \
+                                        (float*)Kc, (float*)Vc, c->D.H, cap, flag)
+    if (c->D.hd == 64) FM_ROPE(64); else if (c->D.hd == 96) FM_ROPE(96); else FM_ROPE(128);
+#undef FM_ROPE
+  }
 }
 
 // elements of one (sequence) slice of a K or V cache with `cap` key positions
 size_t cache_seq_elems(const fm_ctx* c, int cap) {
-  return c->bf16 ? (size_t)c->D.H * ((cap + 31) / 32) * 2048 : (size_t)c->D.H * cap * FM_HD;
+  return c->bf16 ? (size_t)c->D.H * ((cap + 31) / 32) * 2048 : (size_t)c->D.H * cap * c->D.hd;
 }
 
 // one transformer block on the row set of `level` (Sec. 3.1: self-attention, cross-attention to c, FFN)
@@ -466,8 +471,11 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev, void* stage_area) {
       if (std::is_same<T, f16_t>::value)
         hipLaunchKernelGGL(k_mem_kv_store_h, dim3(D.M), dim3(256), 0, c->stream, kv, (f16_t*)Km, (f16_t*)Vm, D.H, D.M,
                            (D.M + 31) / 32);
-      else
-        hipLaunchKernelGGL((k_mem_kv_store<float>), dim3(D.M), dim3(256), 0, c->stream, kv, (float*)Km, (float*)Vm, D.H, D.M);
+      else {
+#define FM_MEMKV(HDV) hipLaunchKernelGGL((k_mem_kv_store<float, HDV>), dim3(D.M), dim3(256), 0, c->stream, kv, (float*)Km, (float*)Vm, D.H, D.M)
+        if (D.hd == 64) FM_MEMKV(64); else if (D.hd == 96) FM_MEMKV(96); else FM_MEMKV(128);
+#undef FM_MEMKV
+      }
     }
   hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
   HIPCHK(c, hipGetLastError());
@@ -684,7 +692,7 @@ int build_buffers(fm_ctx* c) {
   const size_t rows[3] = {(size_t)c->Rc, (size_t)c->Rv, (size_t)c->Rf};
   for (int l = 0; l < 3; l++) {
     TRY(dalloc(c, &c->pos[l], rows[l])); TRY(dalloc(c, &c->limx[l], rows[l]));
-    TRY(dalloc(c, &c->cs[l], rows[l] * 32)); TRY(dalloc(c, &c->h[l], rows[l] * d));
+    TRY(dalloc(c, &c->cs[l], rows[l] * 64)); TRY(dalloc(c, &c->h[l], rows[l] * d));
   }
   TRY(dalloc_t(c, &c->xn, rows[0] * d)); TRY(dalloc_t(c, &c->qT, rows[0] * d)); TRY(dalloc_t(c, &c->attT, rows[0] * d));
   TRY(dalloc_t(c, &c->mid, rows[0] * c->ff));
@@ -702,7 +710,7 @@ int build_buffers(fm_ctx* c) {
     maxset = std::max(maxset, nset[i]);
     TRY(dalloc(c, (const float***)&c->dr.src[i], nset[i])); TRY(dalloc(c, &c->dr.pos[i], nset[i]));
     TRY(dalloc(c, &c->dr.lim[i], nset[i])); TRY(dalloc(c, &c->dr.limx[i], nset[i]));
-    TRY(dalloc(c, &c->dr.cs[i], nset[i] * 32));
+    TRY(dalloc(c, &c->dr.cs[i], nset[i] * 64));
   }
   TRY(dalloc(c, &c->dr.alive, S)); TRY(dalloc(c, &c->dr.firev, S)); TRY(dalloc(c, &c->dr.firef, S)); TRY(dalloc(c, &c->dr.flags, 4));
   TRY(dalloc(c, &c->spv_out, nset[1] * d)); TRY(dalloc(c, &c->spf_out, nset[2] * d)); TRY(dalloc(c, &c->hfv_out, nset[3] * d));
@@ -755,7 +763,9 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   if (!cfg || !out) return FM_EINVAL;
   *out = nullptr;
   const fm_config& g = *cfg;
-  if (g.d_model <= 0 || g.n_heads <= 0 || g.d_model != g.n_heads * FM_HD) return FM_EINVAL;
+  if (g.d_model <= 0 || g.n_heads <= 0 || g.d_model % g.n_heads != 0) return FM_EINVAL;
+  const int hd = g.d_model / g.n_heads;          // 64; 96 and 128 (the paper's own widths) in fp32 storage only
+  if (hd != 64 && !((hd == 96 || hd == 128) && g.dtype == FM_DTYPE_F32)) return FM_EINVAL;
   if (g.ffn_mult < 1 || g.hf_ffn_mult < 1 || g.n_bins < 1 || g.mem_len < 1) return FM_EINVAL;
   if (g.l_cpre < 1 || g.l_cpost < 1 || g.l_vpre < 1 || g.l_vpost < 1 || g.l_face < 1) return FM_EINVAL;
   if (g.dtype != FM_DTYPE_F32 && g.dtype != FM_DTYPE_BF16) return FM_EINVAL;
@@ -778,7 +788,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   c->ff = g.ffn_mult * g.d_model;
   c->hff = g.hf_ffn_mult * g.d_model;
   Dims& D = c->D;
-  D.d = g.d_model; D.H = g.n_heads; D.V = g.n_bins + 3; D.S = g.max_batch; D.Bm = Bm;
+  D.d = g.d_model; D.H = g.n_heads; D.hd = hd; D.V = g.n_bins + 3; D.S = g.max_batch; D.Bm = Bm;
   D.VB = (Bm + 2) / 3; D.FB = (Bm + 8) / 9; D.M = g.mem_len;
   D.maxtok = g.max_tokens;
   D.capc = g.max_tokens; D.capv = (g.max_tokens + 2) / 3 + 1; D.capf = (g.max_tokens + 8) / 9 + 1;
@@ -799,7 +809,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   D.nbins = g.n_bins; D.ban = g.ban_specials ? 1 : 0; D.eos = g.n_bins + 1; D.pad = g.n_bins + 2;
   c->Vpad = (D.V + 63) / 64 * 64;
   c->Rc = D.S * D.Bm; c->Rv = D.S * D.VB; c->Rf = D.S * D.FB;
-  for (int i = 0; i < 32; i++) c->inv.v[i] = std::pow((double)g.rope_base, -(double)i / 32.0);
+  for (int i = 0; i < 64; i++) c->inv.v[i] = std::pow((double)g.rope_base, -(double)i / (hd / 2.0));
   c->weights_loaded = false;
   c->prefilled.assign(D.S, false);
   c->len_bound.assign(D.S, D.maxtok);

@@ -117,44 +117,45 @@ __global__ void k_embed(const int* __restrict__ tok, const int* __restrict__ pos
 }
 
 // ------------------------------------------------------------------------------------------
-// Rotary position + K/V append.  qkv fp32 [R][3d] -> q (T) [R][d]; K/V caches [S][H][cap][64].
-// cs[r][i] = (cos, sin) of pos * base^(-i/32), i < 32; pair (i, i+32).
+// Rotary position + K/V append.  qkv fp32 [R][3d] -> q (T) [R][d]; K/V caches [S][H][cap][HD].
+// cs[r][i] = (cos, sin) of pos * base^(-i/(HD/2)), i < HD/2; pair (i, i + HD/2).
 // ------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int HD>
 __global__ void k_rope_append(const float* __restrict__ qkv, long ldq, const float2* __restrict__ cs,
                               const int* __restrict__ pos, int RPS, T* __restrict__ q, T* __restrict__ Kc,
                               T* __restrict__ Vc, int H, int cap, const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
+  constexpr int HP = HD / 2;
   const int r = blockIdx.x;
   const int p = pos[r];
-  const int d = H * FM_HD;
+  const int d = H * HD;
   const int s = r / RPS;
-  for (int idx = threadIdx.x; idx < H * 32; idx += blockDim.x) {
-    const int hh = idx >> 5, i = idx & 31;
-    const float2 c = cs[(long)r * 32 + i];
+  for (int idx = threadIdx.x; idx < H * HP; idx += blockDim.x) {
+    const int hh = idx / HP, i = idx % HP;
+    const float2 c = cs[(long)r * HP + i];
     const float* row = qkv + (long)r * ldq;
-    const float qa = row[hh * 64 + i], qb = row[hh * 64 + 32 + i];
-    Store<T>::st(q + (long)r * d + hh * 64 + i, qa * c.x - qb * c.y);
-    Store<T>::st(q + (long)r * d + hh * 64 + 32 + i, qb * c.x + qa * c.y);
+    const float qa = row[hh * HD + i], qb = row[hh * HD + HP + i];
+    Store<T>::st(q + (long)r * d + hh * HD + i, qa * c.x - qb * c.y);
+    Store<T>::st(q + (long)r * d + hh * HD + HP + i, qb * c.x + qa * c.y);
     if (Kc && p >= 0) {
-      const float ka = row[d + hh * 64 + i], kb = row[d + hh * 64 + 32 + i];
-      const long o = (((long)s * H + hh) * cap + p % cap) * FM_HD;     // the cache is a ring when a window is set
+      const float ka = row[d + hh * HD + i], kb = row[d + hh * HD + HP + i];
+      const long o = (((long)s * H + hh) * cap + p % cap) * HD;     // the cache is a ring when a window is set
       Store<T>::st(Kc + o + i, ka * c.x - kb * c.y);
-      Store<T>::st(Kc + o + 32 + i, kb * c.x + ka * c.y);
-      Store<T>::st(Vc + o + i, row[2 * d + hh * 64 + i]);
-      Store<T>::st(Vc + o + 32 + i, row[2 * d + hh * 64 + 32 + i]);
+      Store<T>::st(Kc + o + HP + i, kb * c.x + ka * c.y);
+      Store<T>::st(Vc + o + i, row[2 * d + hh * HD + i]);
+      Store<T>::st(Vc + o + HP + i, row[2 * d + hh * HD + HP + i]);
     }
   }
 }
 
-// Condition-memory keys/values: kv fp32 [M][2d] -> caches [H][M][64] of one sequence (no rotary).
-template <typename T>
+// Condition-memory keys/values: kv fp32 [M][2d] -> caches [H][M][HD] of one sequence (no rotary).
+template <typename T, int HD>
 __global__ void k_mem_kv_store(const float* __restrict__ kv, T* __restrict__ Kc, T* __restrict__ Vc, int H, int M) {
   const int m = blockIdx.x;
-  const int d = H * FM_HD;
+  const int d = H * HD;
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    const int hh = i >> 6, e = i & 63;
-    const long o = ((long)hh * M + m) * FM_HD + e;
+    const int hh = i / HD, e = i % HD;
+    const long o = ((long)hh * M + m) * HD + e;
     Store<T>::st(Kc + o, kv[(long)m * 2 * d + i]);
     Store<T>::st(Vc + o, kv[(long)m * 2 * d + d + i]);
   }
@@ -167,65 +168,66 @@ __global__ void k_convert(const float* __restrict__ src, T* __restrict__ dst, lo
 }
 
 // ------------------------------------------------------------------------------------------
-// Attention, one workgroup per (row, head): softmax(q K^T / 8) V over keys [0, limit[row]].
+// Attention, one workgroup per (row, head): softmax(q K^T / sqrt(HD)) V over keys [0, limit[row]].
 // Threads stride over the keys with a private online softmax and merge at the end.
-// Caches: [S][H][cap][64] (seq_stride = H*cap*64; 0 for a cache shared by every sequence).
+// Caches: [S][H][cap][HD] (seq_stride = H*cap*HD; 0 for a cache shared by every sequence).
 // ------------------------------------------------------------------------------------------
-template <typename T>
+template <typename T, int HD>
 __global__ __launch_bounds__(256) void k_attn_simple(const T* __restrict__ q, const int* __restrict__ limit, int RPS,
                                                       const T* __restrict__ Kc, const T* __restrict__ Vc, long seq_stride,
                                                       int cap, T* __restrict__ out, int H, const int* run_flag, int window) {
   if (run_flag && *run_flag == 0) return;
   const int r = blockIdx.x, hh = blockIdx.y;
-  const int d = H * FM_HD;
+  const int d = H * HD;
   const int lim = limit[r];
-  T* o = out + (long)r * d + hh * FM_HD;
+  const float kScale = HD == 64 ? 0.125f : 1.0f / sqrtf((float)HD);
+  T* o = out + (long)r * d + hh * HD;
   if (lim < 0) {
-    if (threadIdx.x < FM_HD) Store<T>::st(o + threadIdx.x, 0.f);
+    if (threadIdx.x < HD) Store<T>::st(o + threadIdx.x, 0.f);
     return;
   }
   const int s = r / RPS;
-  const T* K = Kc + (long)s * seq_stride + (long)hh * cap * FM_HD;
-  const T* V = Vc + (long)s * seq_stride + (long)hh * cap * FM_HD;
-  float qv[FM_HD];
+  const T* K = Kc + (long)s * seq_stride + (long)hh * cap * HD;
+  const T* V = Vc + (long)s * seq_stride + (long)hh * cap * HD;
+  float qv[HD];
 #pragma unroll
-  for (int i = 0; i < FM_HD; i += 8) Store<T>::ld8(q + (long)r * d + hh * FM_HD + i, qv + i);
-  float m = -INFINITY, l = 0.f, acc[FM_HD];
+  for (int i = 0; i < HD; i += 8) Store<T>::ld8(q + (long)r * d + hh * HD + i, qv + i);
+  float m = -INFINITY, l = 0.f, acc[HD];
 #pragma unroll
-  for (int i = 0; i < FM_HD; i++) acc[i] = 0.f;
+  for (int i = 0; i < HD; i++) acc[i] = 0.f;
   // window > 0: keys lim - window + 1 .. lim, stored at slot (position mod cap)
   const int first = window > 0 ? max(lim - window + 1, 0) : 0;
   for (int ka = first + threadIdx.x; ka <= lim; ka += 256) {
     const int j = window > 0 ? ka % cap : ka;
-    float kv[FM_HD];
+    float kv[HD];
 #pragma unroll
-    for (int i = 0; i < FM_HD; i += 8) Store<T>::ld8(K + (long)j * FM_HD + i, kv + i);
+    for (int i = 0; i < HD; i += 8) Store<T>::ld8(K + (long)j * HD + i, kv + i);
     float sc = 0.f;
 #pragma unroll
-    for (int i = 0; i < FM_HD; i++) sc = fmaf(qv[i], kv[i], sc);
-    sc *= 0.125f;
+    for (int i = 0; i < HD; i++) sc = fmaf(qv[i], kv[i], sc);
+    sc *= kScale;
     const float mn = fmaxf(m, sc);
     const float a = __expf(m - mn), p = __expf(sc - mn);
 #pragma unroll
-    for (int i = 0; i < FM_HD; i += 8) Store<T>::ld8(V + (long)j * FM_HD + i, kv + i);
+    for (int i = 0; i < HD; i += 8) Store<T>::ld8(V + (long)j * HD + i, kv + i);
     l = l * a + p;
 #pragma unroll
-    for (int i = 0; i < FM_HD; i++) acc[i] = acc[i] * a + p * kv[i];
+    for (int i = 0; i < HD; i++) acc[i] = acc[i] * a + p * kv[i];
     m = mn;
   }
-  __shared__ float sm[4], sl[4], so[4][FM_HD];
+  __shared__ float sm[4], sl[4], so[4][HD];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const float wm = wave_max(m);
   const float f = (m == -INFINITY) ? 0.f : __expf(m - wm);
   l = wave_sum(l * f);
 #pragma unroll
-  for (int i = 0; i < FM_HD; i++) {
+  for (int i = 0; i < HD; i++) {
     float v = wave_sum(acc[i] * f);
     if (lane == 0) so[wave][i] = v;
   }
   if (lane == 0) { sm[wave] = wm; sl[wave] = l; }
   __syncthreads();
-  if (threadIdx.x < FM_HD) {
+  if (threadIdx.x < HD) {
     const float gm = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
     float num = 0.f, den = 0.f;
 #pragma unroll

@@ -5,10 +5,11 @@
 #include "fm_device.h"
 #include "fm_kernels_basic.h"
 
-struct InvFreq { double v[32]; };  // base^(-i/32), computed in double on the host
+struct InvFreq { double v[64]; };  // base^(-i/(hd/2)) for the hd/2 rotary pairs of a head, computed in double on the host
 
 struct Dims {
   int d, H, V, S, Bm, VB, FB, M;
+  int hd;                // head width d / H: 64 (both storage types), 96 or 128 (fp32 storage only)
   int capc, capv, capf;  // K/V cache slots per level (rings when a window is set)
   int maxtok;            // longest stream (positions 1 .. maxtok)
   int wc, wv, wf;        // attention window per level in its own positions, 0 = unbounded
@@ -74,19 +75,20 @@ __global__ __launch_bounds__(256) void k_verify_setup(StateDev st, Dims D, InvFr
     limx_f[idx] = on ? D.M - 1 : -1;
   }
   __syncthreads();
-  for (int idx = tid; idx < D.S * D.Bm * 32; idx += 256) {
-    const int p = pos_c[idx >> 5];
-    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx & 31];
+  const int np = D.hd >> 1;      // rotary pairs per head
+  for (int idx = tid; idx < D.S * D.Bm * np; idx += 256) {
+    const int p = pos_c[idx / np];
+    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx % np];
     cs_c[idx] = make_float2((float)cos(a), (float)sin(a));
   }
-  for (int idx = tid; idx < D.S * D.VB * 32; idx += 256) {
-    const int p = pos_v[idx >> 5];
-    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx & 31];
+  for (int idx = tid; idx < D.S * D.VB * np; idx += 256) {
+    const int p = pos_v[idx / np];
+    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx % np];
     cs_v[idx] = make_float2((float)cos(a), (float)sin(a));
   }
-  for (int idx = tid; idx < D.S * D.FB * 32; idx += 256) {
-    const int p = pos_f[idx >> 5];
-    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx & 31];
+  for (int idx = tid; idx < D.S * D.FB * np; idx += 256) {
+    const int p = pos_f[idx / np];
+    const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx % np];
     cs_f[idx] = make_float2((float)cos(a), (float)sin(a));
   }
 }
@@ -257,15 +259,17 @@ struct DraftBufs {
 };
 
 __device__ __forceinline__ void set_row(const DraftRows& R, int set, int r, const float* src, int pos, int lim, int M,
-                                        const InvFreq& inv, int lane32) {
+                                        const InvFreq& inv, int lane32, int np = 32) {
   if (lane32 == 0) {
     R.src[set][r] = src;
     R.pos[set][r] = lim >= 0 ? pos : -1;
     R.lim[set][r] = lim;
     R.limx[set][r] = lim >= 0 ? M - 1 : -1;
   }
-  const double a = (lim >= 0 ? (double)pos : 0.0) * inv.v[lane32];
-  R.cs[set][(long)r * 32 + lane32] = make_float2((float)cos(a), (float)sin(a));
+  for (int i = lane32; i < np; i += 32) {        // np = rotary pairs per head
+    const double a = (lim >= 0 ? (double)pos : 0.0) * inv.v[i];
+    R.cs[set][(long)r * np + i] = make_float2((float)cos(a), (float)sin(a));
+  }
 }
 
 // one workgroup, 32 threads per row at a time
@@ -293,16 +297,16 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
     const float* tapf = B.tap_f + ((long)s * 8 + (f & 7)) * d;
     const float* yf = B.ring_yf + ((long)s * 8 + (f & 7)) * d;
     // set 0: coordinate SP heads k = 1..Dc on the coordinate tap at s
-    for (int k = grp; k < D.Dc; k += 8) set_row(R, 0, s * D.Dc + k, tapc, spos, alive ? spos : -1, D.M, inv, lane32);
+    for (int k = grp; k < D.Dc; k += 8) set_row(R, 0, s * D.Dc + k, tapc, spos, alive ? spos : -1, D.M, inv, lane32, D.hd >> 1);
     // set 1: point SP heads on the vertex tap of v
-    for (int k = grp; k < D.nspv; k += 8) set_row(R, 1, s * D.nspv + k, tapv, v, firev ? v : -1, D.M, inv, lane32);
+    for (int k = grp; k < D.nspv; k += 8) set_row(R, 1, s * D.nspv + k, tapv, v, firev ? v : -1, D.M, inv, lane32, D.hd >> 1);
     // set 2: face SP heads on the face tap of f
-    for (int k = grp; k < D.nspf; k += 8) set_row(R, 2, s * D.nspf + k, tapf, f, firef ? f : -1, D.M, inv, lane32);
+    for (int k = grp; k < D.nspf; k += 8) set_row(R, 2, s * D.nspf + k, tapf, f, firef ? f : -1, D.M, inv, lane32, D.hd >> 1);
     // set 3: vertex-level HF, vertex offsets j = j0..n/3-1 from vertex token 3f; input = face feature j/3
     for (int q = grp; q < D.nhfv; q += 8) {
       const int j = q + D.j0;
       const float* src = (j < 3) ? yf : B.spf_out + ((long)s * D.nspf + (j / 3 - 1)) * d;
-      set_row(R, 3, s * D.nhfv + q, src, 3 * f + j, firef ? 3 * f : -1, D.M, inv, lane32);
+      set_row(R, 3, s * D.nhfv + q, src, 3 * f + j, firef ? 3 * f : -1, D.M, inv, lane32, D.hd >> 1);
     }
     // set 4: coordinate-level HF, offsets t = t0..; pipe 0 = point pipeline, pipe 1 = face pipeline
     for (int q = grp; q < 2 * D.nhfc; q += 8) {
@@ -312,11 +316,11 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
         const bool on = firev && t < D.m;
         // offsets 0..2 (rule (B) off) belong to the current vertex: its own feature; later ones to the SP head outputs
         const float* src = t < 3 ? tapv : B.spv_out + ((long)s * max(D.nspv, 1) + min(t / 3 - 1, max(D.nspv - 1, 0))) * d;
-        set_row(R, 4, r, src, 3 * v + t, on ? 3 * v : -1, D.M, inv, lane32);
+        set_row(R, 4, r, src, 3 * v + t, on ? 3 * v : -1, D.M, inv, lane32, D.hd >> 1);
       } else {
         const bool on = firef && t < D.n;
         const float* src = B.hfv_out + ((long)s * max(D.nhfv, 1) + min(max(t / 3 - D.j0, 0), max(D.nhfv - 1, 0))) * d;
-        set_row(R, 4, r, src, 9 * f + t, on ? 9 * f : -1, D.M, inv, lane32);
+        set_row(R, 4, r, src, 9 * f + t, on ? 9 * f : -1, D.M, inv, lane32, D.hd >> 1);
       }
     }
   }

@@ -22,7 +22,8 @@ def _need_gpu():
                                   "t_f32_99_w36", "t_bf16_99_w36", "t_bf16_99_b1_w36", "t_bf16_1815_w72",
                                   "t_bf16_1815_b1", "t_bf16_2727_b1", "t_bf16_1815_b1_w72",
                                   "t_f32_99_noA", "t_bf16_1815_noA", "t_bf16_99_b1_noA",
-                                  "t_f32_99_noB", "t_bf16_1815_noAB", "t_bf16_99_b1_noB"])
+                                  "t_f32_99_noB", "t_bf16_1815_noAB", "t_bf16_99_b1_noB",
+                                  "t_f32_hd96", "t_f32_hd128"])
 def test_lockstep_small_native_heads(name):
     _need_gpu()
     from parity_harness import lockstep
@@ -53,7 +54,7 @@ def test_lockstep_small_native_heads(name):
 
 
 @pytest.mark.parametrize("name", ["t_f32_99", "t_f32_1815", "t_bf16_99", "t_bf16_1815", "t_bf16_99_b1", "t_f32_2727", "t_bf16_c17",
-                                  "t_bf16_1815_noAB"])
+                                  "t_bf16_1815_noAB", "t_f32_hd96"])
 def test_lockstep_with_correct_stage(name):
     """Predict - correct - verify (Sec. 3.2): labels from the label head, the integer correction of every draft block
     bit for bit, and a stream that the stage leaves untouched."""

@@ -27,7 +27,7 @@ def _tokens(cfg, n, seed=3):
 
 
 # -- T1: incremental decoding equals full-sequence recompute ------------------------------
-@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99"])
+@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99", "t_f32_hd96", "t_f32_hd128"])
 def test_incremental_equals_full(name):
     cfg, m, mem = _model(name)
     T = 64
@@ -195,7 +195,7 @@ def test_single_block_is_textbook_attention():
 
 
 # -- T4: speculative greedy == sequential greedy -------------------------------------------------
-@pytest.mark.parametrize("name", ["t_f32_c", "t_f32_99", "t_f32_1815", "t_bf16_99"])
+@pytest.mark.parametrize("name", ["t_f32_c", "t_f32_99", "t_f32_1815", "t_bf16_99", "t_f32_hd96"])
 def test_speculative_equals_sequential_native_heads(name):
     cfg, m, mem = _model(name)
     seq, st0 = sp.generate(m, mem, cfg.faces, speculative=False)

@@ -1,6 +1,8 @@
 """Pins for the oracle's primitives: closed forms, brute force, and independent library routines."""
 import os
 
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -172,3 +174,29 @@ def test_shorten_upsample_brute_force(T):
     # causality of the pair: coarse row floor(i/3) only pools fine rows <= i
     for i in range(T):
         assert 3 * (i // 3) <= i
+
+
+@pytest.mark.parametrize("hd", [64, 96, 128])
+def test_rope_and_attention_take_the_head_width_from_their_operands(hd):
+    """Head widths of the paper's own models (Sec. 5.1: 96 and 128): pair i of a head turns by pos * base^(-i / (hd/2)),
+    scores are scaled by 1/sqrt(hd)."""
+    rng = np.random.default_rng(hd)
+    x = rng.standard_normal((3, 2, hd))
+    pos = np.array([0, 5, 1234])
+    y = P.rope(x, pos, 10000.0)
+    assert np.allclose(y[0], x[0])                                         # position 0: identity
+    for i in (0, 1, hd // 2 - 1):
+        ang = pos[2] * 10000.0 ** (-i / (hd / 2))
+        a, b = x[2, 1, i], x[2, 1, i + hd // 2]
+        assert abs(y[2, 1, i] - (a * math.cos(ang) - b * math.sin(ang))) < 1e-9
+        assert abs(y[2, 1, i + hd // 2] - (b * math.cos(ang) + a * math.sin(ang))) < 1e-9
+    assert np.allclose(np.linalg.norm(y, axis=-1), np.linalg.norm(x, axis=-1))
+    q, K, V = rng.standard_normal((2, 2, hd)), rng.standard_normal((7, 2, hd)), rng.standard_normal((7, 2, hd))
+    out = P.attend(q, K, V, [3, 6])
+    for r, lim in enumerate((3, 6)):
+        for h in range(2):
+            sc = np.array([q[r, h] @ K[j, h] for j in range(lim + 1)]) / math.sqrt(hd)
+            w = np.exp(sc - sc.max())
+            w /= w.sum()
+            assert np.allclose(out[r, h], sum(w[j] * V[j, h] for j in range(lim + 1)))
+    assert np.allclose(P.attend_causal(q, K, V, 5), P.attend(q, K, V, [5, 6]))
