@@ -201,6 +201,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--gemm-sweep", action="store_true",
                     help="row sweep (16 .. 4096) of the weight-streaming GEMM kernel on the FFN up projection; prints and exits")
+    ap.add_argument("--exchange-probe", action="store_true",
+                    help="cost of one dependent all-to-all hand-off between resident workgroups (the step the single-launch "
+                         "verify kernel repeats ~10 times per block), by workgroup count and volume; prints and exits")
     ap.add_argument("--counter-pass", action="store_true",
                     help="short run for hardware-counter collection: fill the caches to half context with forced "
                          "commits, then one 1 GiB device copy (the calibration kernel) and 5 verify passes")
@@ -231,6 +234,15 @@ def main():
     fm.load_weights(si.pack_blob(cfg, weights))
     if args.correct:
         fm.set_correct(args.correct)
+    if args.exchange_probe:
+        rows = []
+        for wgs in (256, 128, 64):
+            for nbytes in (4096, 12288, 36864):
+                rows.append({"workgroups": wgs, "bytes": nbytes, "us_per_round": fm.measure_exchange(wgs, nbytes)})
+        rows.append({"workgroups": 2, "pingpong": True, "us_per_round_trip": fm.measure_exchange(2, 4096, True)})
+        print(json.dumps({"exchange_probe": "dependent all-to-all hand-offs between resident workgroups: tagged 8-byte elements, "
+                                            "agent-scope stores, agent-scope loads repeated until every tag matches", "rows": rows}))
+        return
     if args.gemm_sweep:
         sweep = [fm.measure_gemm(r) for r in (8, 16, 32, 72, 128, 256, 512, 1024, 2048, 4096)]
         for e in sweep:

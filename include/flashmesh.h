@@ -221,6 +221,14 @@ int fm_debug_draft(fm_ctx* ctx, int32_t which, float* host_out);
  * and frees 2 GiB of device memory for the duration of the call.  Synchronises. */
 int fm_measure_peaks(fm_ctx* ctx, double* host_out);
 
+/* Cost of one dependent all-to-all hand-off between resident workgroups, the step that the single-launch verify kernel
+ * repeats about ten times per transformer block: 2000 rounds in which each of `workgroups` (2..256) workgroups publishes
+ * its share of `bytes` (tagged 8-byte elements, agent-scope stores) and then reads all of them (agent-scope loads,
+ * repeated until every tag matches), nothing else.  pingpong != 0: one element each way between two workgroups instead.
+ * HOST out[0] = microseconds per round.  Allocates and frees its buffers; every wait in the kernel is bounded.
+ * Synchronises. */
+int fm_measure_exchange(fm_ctx* ctx, int32_t workgroups, int32_t bytes, int32_t pingpong, double* host_out);
+
 /* Row sweep of the weight-streaming GEMM kernel that the per-operator path uses: times Y[rows, 4 d_model] =
  * gelu(X[rows, d_model] W1^T) with the FFN up projection of the first block (half-precision contexts only), back to
  * back on the context's stream.  HOST out[0] = milliseconds per launch, out[1] = TFLOP/s.  Allocates and frees its

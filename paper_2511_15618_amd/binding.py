@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_prefill_condition_static", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
            "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile", "fm_debug_draft",
-           "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm"]
+           "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm", "fm_measure_exchange"]
 
 
 class LibraryMissing(RuntimeError):
@@ -82,6 +82,7 @@ def load_library():
     lib.fm_debug_profile.argtypes = [p, p, i32]
     lib.fm_measure_peaks.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_measure_gemm.argtypes = [p, i32, C.POINTER(C.c_double)]
+    lib.fm_measure_exchange.argtypes = [p, i32, i32, i32, C.POINTER(C.c_double)]
     lib.fm_verify_path.argtypes = [p]
     lib.fm_verify_path.restype = i32
     for n in EXPORTS:
@@ -243,6 +244,12 @@ class FlashMesh:
         out = (C.c_double * 2)()
         self._chk(self.lib.fm_measure_gemm(self.h, rows, out), "fm_measure_gemm")
         return {"rows": rows, "ms": out[0], "TFLOPs": out[1]}
+
+    def measure_exchange(self, workgroups: int, nbytes: int, pingpong: bool = False) -> float:
+        """Microseconds per dependent all-to-all hand-off between `workgroups` resident workgroups."""
+        out = C.c_double()
+        self._chk(self.lib.fm_measure_exchange(self.h, workgroups, nbytes, 1 if pingpong else 0, C.byref(out)), "fm_measure_exchange")
+        return out.value
 
     def verify_path(self) -> int:
         return int(self.lib.fm_verify_path(self.h))

@@ -1119,6 +1119,41 @@ int fm_measure_peaks(fm_ctx* c, double* host_out) {
   return rc;
 }
 
+int fm_measure_exchange(fm_ctx* c, int32_t workgroups, int32_t bytes, int32_t pingpong, double* host_out) {
+  if (!c || !host_out) return FM_EINVAL;
+  if (workgroups < 2 || workgroups > 256 || bytes < workgroups * 8 || bytes > 49152 || bytes % (workgroups * 16) != 0)
+    return fail(c, FM_EINVAL, "exchange probe: 2..256 workgroups, bytes a multiple of 16 per workgroup, at most 49152");
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_probe_exchange, 256, 0) != hipSuccess || (long)cus * per_cu < workgroups) {
+    (void)hipGetLastError();
+    return fail(c, FM_ESTATE, "exchange probe: %d workgroups cannot be resident together on this device", workgroups);
+  }
+  const int vol = bytes / 8, nstage = 2000;
+  unsigned long long *buf = nullptr, *ticks = nullptr;
+  unsigned* words = nullptr;
+  auto cleanup = [&]() {
+    if (buf) (void)hipFree(buf);
+    if (ticks) (void)hipFree(ticks);
+    if (words) (void)hipFree(words);
+  };
+#define PK_TRY(x) do { if ((x) != hipSuccess) { (void)hipGetLastError(); cleanup(); return fail(c, FM_EHIP, "exchange probe: %s failed", #x); } } while (0)
+  PK_TRY(hipStreamSynchronize(c->stream));
+  PK_TRY(hipMalloc((void**)&buf, (size_t)3 * vol * 8)); PK_TRY(hipMalloc((void**)&ticks, 16)); PK_TRY(hipMalloc((void**)&words, 256));
+  PK_TRY(hipMemsetAsync(buf, 0, (size_t)3 * vol * 8, c->stream)); PK_TRY(hipMemsetAsync(ticks, 0, 16, c->stream));
+  PK_TRY(hipMemsetAsync(words, 0, 256, c->stream));
+  hipLaunchKernelGGL(k_probe_exchange, dim3(workgroups), dim3(256), 0, c->stream, buf, words, words + 32, ticks, vol, nstage, pingpong ? 1 : 0);
+  PK_TRY(hipStreamSynchronize(c->stream));
+  unsigned long long t[2] = {0, 0};
+  unsigned ab = 0;
+  PK_TRY(hipMemcpy(t, ticks, 16, hipMemcpyDeviceToHost)); PK_TRY(hipMemcpy(&ab, words + 32, 4, hipMemcpyDeviceToHost));
+#undef PK_TRY
+  cleanup();
+  if (ab) return fail(c, FM_EHIP, "exchange probe: a bounded wait expired");
+  host_out[0] = (double)(t[1] - t[0]) * 0.01 / nstage;       // microseconds per round (100 MHz wall clock)
+  return FM_OK;
+}
+
 int fm_measure_gemm(fm_ctx* c, int32_t rows, double* host_out) {
   if (!c || !host_out) return FM_EINVAL;
   if (!c->bf16 || !c->weights_loaded) return fail(c, FM_ESTATE, "GEMM probe needs the half-precision path with weights loaded");

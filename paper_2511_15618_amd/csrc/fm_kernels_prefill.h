@@ -193,3 +193,70 @@ __global__ __launch_bounds__(256) void k_probe_mfma(float* __restrict__ sink, in
     for (int j = 0; j < 16; j++) s += acc[i][j];
   sink[blockIdx.x * 256 + threadIdx.x] = s;
 }
+
+// ------------------------------------------------------------------------------------------
+// Probe of the hand-off that the single-launch verify kernel is made of: `nstage` dependent rounds in which every one
+// of the resident workgroups publishes its slice of a vector of tagged 8-byte elements (agent-scope stores) and then
+// reads the whole vector (16-byte agent-scope loads, repeated until every tag matches) - one all-to-all hand-off per
+// round, with no arithmetic between the rounds.  mode 1: a ping-pong between workgroups 0 and 1 instead (one element
+// each way per round).  Every wait is bounded; *abort_word != 0 afterwards means a wait expired.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_probe_exchange(unsigned long long* buf, unsigned* arrive, unsigned* abort_word,
+                                                        unsigned long long* ticks, int vol, int nstage, int mode) {
+  typedef unsigned long long u64;
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const int nwg = gridDim.x;
+  auto expired = [&](u64 t0) -> bool {
+    if (__hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return true;
+    if (wall_clock64() - t0 > 20000000ull) { __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); return true; }
+    return false;
+  };
+  // all workgroups resident before the clock starts
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  {
+    const u64 t0 = wall_clock64();
+    while (true) {
+      const unsigned n = __hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (__syncthreads_and(n == (unsigned)nwg)) break;
+      if (__syncthreads_or(expired(t0))) return;
+    }
+  }
+  const u64 tstart = wall_clock64();
+  const int per = vol / nwg, n16 = vol / 2;
+  for (int t = 1; t <= nstage; t++) {
+    u64* g = buf + (long)(t % 3) * vol;
+    if (mode == 1) {
+      if (blockIdx.x > 1) break;
+      if (threadIdx.x == 0) {
+        u64* mine = g + blockIdx.x * 64;
+        u64* other = g + (1 - blockIdx.x) * 64;
+        const u64 t0 = wall_clock64();
+        if (blockIdx.x == 0) __hip_atomic_store(mine, (u64)t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        while (__hip_atomic_load(other, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != (u64)t) if (expired(t0)) return;
+        if (blockIdx.x == 1) __hip_atomic_store(mine, (u64)t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      continue;
+    }
+    if ((int)threadIdx.x < per)
+      __hip_atomic_store(g + blockIdx.x * per + threadIdx.x, ((u64)t << 32) | (unsigned)(blockIdx.x * per + threadIdx.x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const u64 t0 = wall_clock64();
+    int it = 0;
+    while (true) {
+      u32x4 v[12];
+#pragma unroll
+      for (int j = 0; j < 12; j++)
+        if (256 * j < n16) {        // uniform guard, clamped address (n16 <= 3072)
+          const u64* p = g + 2 * (long)min((int)threadIdx.x + 256 * j, n16 - 1);
+          asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v[j]) : "v"(p) : "memory");
+        }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      bool ok = true;
+#pragma unroll
+      for (int j = 0; j < 12; j++)
+        if (256 * j < n16) { asm volatile("" : "+v"(v[j])); ok = ok && v[j][1] == (unsigned)t && v[j][3] == (unsigned)t; }
+      if (__syncthreads_and(ok)) break;
+      if ((++it & 3) == 0 && __syncthreads_or(expired(t0))) return;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) { ticks[0] = tstart; ticks[1] = wall_clock64(); }
+}
