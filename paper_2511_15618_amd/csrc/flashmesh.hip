@@ -121,7 +121,7 @@ struct fm_ctx {
   int persist_failures = 0;   // times the single-launch kernel gave up (the context then left that path)
   PkArgs pk;
   PrefillLayer* pf_layers = nullptr;   // per-block table of the tiled prefill GEMM (null: per-block launches)
-  int pf_n = 0;
+  int pf_n = 0, pf_grid = 0;           // blocks in the table; workgroups of its launch (one per compute unit, multiple of 8)
   unsigned pk_epoch;
   size_t pk_lds;           // dynamic LDS of the persistent kernel (none at present)
   double weight_bytes;
@@ -454,7 +454,7 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev, void* stage_area) {
     // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
     f16_t* Xt = (f16_t*)stage_area;
     hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
-    hipLaunchKernelGGL(k_prefill_kv, dim3(512), dim3(256), 0, c->stream,
+    hipLaunchKernelGGL(k_prefill_kv, dim3(c->pf_grid), dim3(256), PF_LDS_BYTES, c->stream,
                        (const f16_t*)Xt, (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M, c->pf_n);
     hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
     HIPCHK(c, hipGetLastError());
@@ -746,6 +746,12 @@ int build_buffers(fm_ctx* c) {
       c->pf_layers = (PrefillLayer*)raw;
       HIPCHK(c, hipMemcpy(c->pf_layers, tab.data(), tab.size() * sizeof(PrefillLayer), hipMemcpyHostToDevice));
       c->pf_n = (int)tab.size();
+      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS_BYTES));
+      hipDeviceProp_t prop;
+      int dev = 0;
+      HIPCHK(c, hipGetDevice(&dev));
+      HIPCHK(c, hipGetDeviceProperties(&prop, dev));
+      c->pf_grid = std::max(8, prop.multiProcessorCount / 8 * 8);
     }
   }
   if (hipHostMalloc((void**)&c->host_flag, 64 + sizeof(int) * (size_t)c->D.S) != hipSuccess) return fail(c, FM_ENOMEM, "hipHostMalloc failed");
