@@ -83,6 +83,8 @@ struct fm_ctx {
   void *short_cv, *short_vf, *lm;
   float* gf;
   SpLevel sp[3];
+  SpLevel sp_all;          // the heads of all three levels as one group list, in memory order point, face, coordinate
+  bool sp_merged = false;  // one sequence, half path: the three SP chains run as one chain of grouped launches
   HfLevel hfc, hfv;
   float* label_w;     // label head of the correct stage [3][d]
   float *lab_v, *lab_f;   // label distributions of the point pipeline [S][nspv][3] and the face pipeline [S][nhfv][3]
@@ -382,6 +384,45 @@ void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level,
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.lin, dd, out, ldo, gso, c->dkeep, (long)G * d, d, D.S, d, d, G, flag);
 }
 
+// The SP chains (Eq. 1) of all three levels of one sequence as one chain of grouped launches (half path): the row set is
+// the point-, face- and coordinate-level rows behind each other, every GEMM is grouped over all heads, and the two
+// attention launches take one cache per level.  Same arithmetic per row as run_sp.  Rows of a level that does not fire
+// in this step carry limit -1 (no keys) and produce values nobody reads.
+void run_sp_all(fm_ctx* c, const int* flag) {
+  typedef f16_t T;
+  const Dims& D = c->D;
+  const SpLevel& A = c->sp_all;
+  const int d = D.d, G = A.cnt;
+  if (G == 0) return;
+  const long dd = (long)d * d, ld = (long)G * d;
+  const int nrow[3] = {D.nspv, D.nspf, D.Dc}, lev[3] = {1, 2, 0}, set[3] = {1, 2, 0};
+  const Layer* last[3] = {&c->stacks[3].back(), &c->stacks[2].back(), &c->stacks[4].back()};
+  rmsnorm<T>(c, nullptr, c->dr.src[1], A.g, G, c->dxn, c->dkeep, G, flag);
+  gemm<T>(c, EPI_F32, c->dxn, ld, d, A.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
+  rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[1], c->dr.pos[1], G, G, c->dq, nullptr, nullptr, 32, flag);
+  AttnLevelHost lv[3];
+  long off = 0;
+  for (int z = 0; z < 3; z++) {
+    const int cap = level_cap(c, lev[z]);
+    lv[z] = AttnLevelHost{(const f16_t*)c->dq + off * d, c->dr.lim[set[z]], nrow[z], last[z]->Kc, last[z]->Vc, cap,
+                          (f16_t*)c->datt + off * d, false, level_key_bound(c, lev[z]), level_window(c, lev[z])};
+    off += nrow[z];
+  }
+  if (!mfma_attn_launch_levels(c->mres, lv, D.H, flag, c->stream)) { fail(c, FM_EINVAL, "merged SP attention: unsupported row sets"); c->sticky_error = true; return; }
+  gemm<T>(c, EPI_T, c->datt, ld, d, A.wo, dd, c->dxn, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
+  gemm<T>(c, EPI_T, c->dxn, ld, d, A.cq, dd, c->dq, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
+  off = 0;
+  for (int z = 0; z < 3; z++) {
+    lv[z] = AttnLevelHost{(const f16_t*)c->dq + off * d, c->dr.limx[set[z]], nrow[z], last[z]->Km, last[z]->Vm, D.M,
+                          (f16_t*)c->datt + off * d, true, 1 << 30, 0};
+    off += nrow[z];
+  }
+  if (!mfma_attn_launch_levels(c->mres, lv, D.H, flag, c->stream)) { fail(c, FM_EINVAL, "merged SP cross-attention: unsupported row sets"); c->sticky_error = true; return; }
+  gemm<T>(c, EPI_T, c->datt, ld, d, A.co, dd, c->dxn, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
+  // outputs: point, face, coordinate rows behind each other = spv_out, spf_out, first rows of the output head's input
+  gemm<T>(c, EPI_F32, c->dxn, ld, d, A.lin, dd, c->spv_out, ld, d, c->dkeep, ld, d, 1, d, d, G, flag);
+}
+
 // HF block chain (Eq. 3-6) for row set `set`: `per_seq` rows per sequence, `G` parameter sets, `mult`
 // consecutive row groups of G sharing the sets (mult = 2 for the coordinate level: point and face pipelines)
 template <typename T>
@@ -413,12 +454,16 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
     const Layer& lastv = c->stacks[3].back();
     const Layer& lastf = c->stacks[2].back();
     const int nLM = D.S * (D.Dc + 2 * D.nhfc);
-    // coordinate level: SP heads straight to the output head
-    run_sp<T>(c, 0, c->sp[0], lastc, 0, c->dh, (long)D.Dc * d, d, f_alive);
-    // point level: SP heads on the vertex feature; their outputs feed the coordinate HF rows of pipe 0
-    run_sp<T>(c, 1, c->sp[1], lastv, 1, c->spv_out, (long)D.nspv * d, d, f_v);
-    // face level: SP heads on the face feature, vertex-level HF, then coordinate HF rows of pipe 1
-    run_sp<T>(c, 2, c->sp[2], lastf, 2, c->spf_out, (long)D.nspf * d, d, f_f);
+    if (std::is_same<T, f16_t>::value && c->sp_merged) {
+      run_sp_all(c, f_alive);
+    } else {
+      // coordinate level: SP heads straight to the output head
+      run_sp<T>(c, 0, c->sp[0], lastc, 0, c->dh, (long)D.Dc * d, d, f_alive);
+      // point level: SP heads on the vertex feature; their outputs feed the coordinate HF rows of pipe 0
+      run_sp<T>(c, 1, c->sp[1], lastv, 1, c->spv_out, (long)D.nspv * d, d, f_v);
+      // face level: SP heads on the face feature, vertex-level HF, then coordinate HF rows of pipe 1
+      run_sp<T>(c, 2, c->sp[2], lastf, 2, c->spf_out, (long)D.nspf * d, d, f_f);
+    }
     run_hf<T>(c, 3, c->hfv, 1, lastv, 1, c->hfv_out, f_f);
     if (c->correct_hist > 0 && D.nspv + D.nhfv > 0)     // label rows of the point-level features (Sec. 3.2)
       hipLaunchKernelGGL(k_label_rows, dim3(D.S * (D.nspv + D.nhfv)), dim3(64), 0, c->stream, D, c->dr, c->spv_out, c->hfv_out,
@@ -550,13 +595,27 @@ int build_params(fm_ctx* c) {
   TRY(dalloc(c, &c->gf, d)); item(c->gf, d, true);
   TRY(dalloc_t(c, &c->lm, (size_t)c->Vpad * d)); lin(c->lm, V, d);
   const int spcnt[3] = {D.Dc, D.nspv, D.nspf};
+  // The heads of the three levels lie behind each other in device memory (point, face, coordinate: the order of the
+  // merged row set), so that one grouped launch can serve all of them; the blob keeps its own order.
+  {
+    SpLevel& A = c->sp_all;
+    A.cnt = D.Dc + D.nspv + D.nspf;
+    const size_t n = A.cnt;
+    TRY(dalloc(c, &A.g, n * d));
+    TRY(dalloc_t(c, &A.wq, n * d * d)); TRY(dalloc_t(c, &A.wo, n * d * d)); TRY(dalloc_t(c, &A.cq, n * d * d));
+    TRY(dalloc_t(c, &A.co, n * d * d)); TRY(dalloc_t(c, &A.lin, n * d * d));
+    const size_t first[3] = {(size_t)D.nspv + D.nspf, 0, (size_t)D.nspv};
+    for (int l = 0; l < 3; l++) {
+      SpLevel& s = c->sp[l];
+      s.g = A.g + first[l] * d;
+      s.wq = at(A.wq, first[l] * d * d); s.wo = at(A.wo, first[l] * d * d); s.cq = at(A.cq, first[l] * d * d);
+      s.co = at(A.co, first[l] * d * d); s.lin = at(A.lin, first[l] * d * d);
+    }
+  }
   for (int l = 0; l < 3; l++) {
     SpLevel& s = c->sp[l];
     s.cnt = spcnt[l];
     const size_t n = s.cnt;
-    TRY(dalloc(c, &s.g, n * d));
-    TRY(dalloc_t(c, &s.wq, n * d * d)); TRY(dalloc_t(c, &s.wo, n * d * d)); TRY(dalloc_t(c, &s.cq, n * d * d));
-    TRY(dalloc_t(c, &s.co, n * d * d)); TRY(dalloc_t(c, &s.lin, n * d * d));
     for (size_t k = 0; k < n; k++) {
       item(s.g + k * d, d, true);
       lin(at(s.wq, k * d * d), d, d); lin(at(s.wo, k * d * d), d, d);
@@ -706,16 +765,33 @@ int build_buffers(fm_ctx* c) {
   // draft rows
   const size_t nset[5] = {S * D.Dc, S * D.nspv, S * D.nspf, S * D.nhfv, S * 2 * D.nhfc};
   size_t maxset = 1;
-  for (int i = 0; i < 5; i++) {
+  for (int i = 3; i < 5; i++) {
     maxset = std::max(maxset, nset[i]);
     TRY(dalloc(c, (const float***)&c->dr.src[i], nset[i])); TRY(dalloc(c, &c->dr.pos[i], nset[i]));
     TRY(dalloc(c, &c->dr.lim[i], nset[i])); TRY(dalloc(c, &c->dr.limx[i], nset[i]));
     TRY(dalloc(c, &c->dr.cs[i], nset[i] * 64));
   }
+  {
+    // the tables of the three SP row sets lie behind each other (point, face, coordinate), as the heads do
+    const size_t nsp = nset[0] + nset[1] + nset[2], np = (size_t)D.hd / 2;
+    maxset = std::max(maxset, nsp);
+    const float** src; int *pos, *lim, *limx; float2* cs;
+    TRY(dalloc(c, (const float***)&src, nsp)); TRY(dalloc(c, &pos, nsp)); TRY(dalloc(c, &lim, nsp)); TRY(dalloc(c, &limx, nsp));
+    TRY(dalloc(c, &cs, nsp * 64));
+    const size_t first[3] = {nset[1] + nset[2], 0, nset[1]};
+    for (int i = 0; i < 3; i++) {
+      c->dr.src[i] = src + first[i]; c->dr.pos[i] = pos + first[i]; c->dr.lim[i] = lim + first[i];
+      c->dr.limx[i] = limx + first[i]; c->dr.cs[i] = cs + first[i] * np;
+    }
+  }
   TRY(dalloc(c, &c->dr.alive, S)); TRY(dalloc(c, &c->dr.firev, S)); TRY(dalloc(c, &c->dr.firef, S)); TRY(dalloc(c, &c->dr.flags, 4));
-  TRY(dalloc(c, &c->spv_out, nset[1] * d)); TRY(dalloc(c, &c->spf_out, nset[2] * d)); TRY(dalloc(c, &c->hfv_out, nset[3] * d));
+  TRY(dalloc(c, &c->hfv_out, nset[3] * d));
   const size_t nLM = S * (D.Dc + 2 * D.nhfc);
-  TRY(dalloc(c, &c->dh, nLM * d)); TRY(dalloc(c, &c->dlogits, nLM * D.V));
+  // outputs of the SP heads: point, face, then the rows of the output head (coordinate SP heads first, HF rows behind)
+  TRY(dalloc(c, &c->spv_out, (nset[1] + nset[2] + nLM) * d));
+  c->spf_out = c->spv_out + nset[1] * d;
+  c->dh = c->spf_out + nset[2] * d;
+  TRY(dalloc(c, &c->dlogits, nLM * D.V));
   const size_t rmax = std::max(maxset, nLM);
   TRY(dalloc(c, &c->dkeep, rmax * d)); TRY(dalloc(c, &c->dtmp, rmax * d));
   TRY(dalloc_t(c, &c->dxn, rmax * d)); TRY(dalloc_t(c, &c->dq, rmax * d)); TRY(dalloc_t(c, &c->datt, rmax * d));
@@ -732,9 +808,11 @@ int build_buffers(fm_ctx* c) {
   c->mres = MfmaRes{nullptr, nullptr, 0, 0};
   if (const char* e = getenv("FM_GEMM_WAVES")) c->mres.gemm_waves = atoi(e);   // measurement switch: 4, 8 or 16
   if (c->bf16) {
-    c->mres.attn_ws_floats = mfma_attn_ws_floats(D.S, D.H);
+    c->mres.attn_ws_floats = mfma_attn_ws_floats(std::max(D.S, 3), D.H);       // 3: the merged SP launch has three row sets
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
-    TRY(dalloc(c, &c->mres.attn_counters, (size_t)D.S * D.H));
+    TRY(dalloc(c, &c->mres.attn_counters, (size_t)std::max(D.S, 3) * D.H));
+    const char* spm = getenv("FM_SP_MERGED");      // "0": one chain of launches per level, as with several sequences
+    c->sp_merged = D.S == 1 && D.Dc <= 16 && D.nspv <= 16 && D.nspf <= 16 && !(spm && spm[0] == '0');
     // tiled prefill GEMM: whole 256 x 128 output tiles only (keys x dims for V, dims x keys for K)
     const char* pt = getenv("FM_PREFILL_TILED");     // "0" forces the per-block GEMM + scatter launches
     if (D.M % 256 == 0 && d % 256 == 0 && !(pt && pt[0] == '0')) {

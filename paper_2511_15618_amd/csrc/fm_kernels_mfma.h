@@ -455,13 +455,13 @@ __device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float*
 }
 
 // Workspace per (sequence, head): [nsplit][QT*16*64 unnormalised O | QT*16 running max (log2 units) | QT*16 sums]
+// (the body of the launch; `split`, `hh`, `s` = key range, head and sequence of this workgroup)
 template <int QT>
-__global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS, int RS,
-                                                    const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
-                                                    long seq_stride, int capb, f16_t* __restrict__ out, int H,
-                                                    float* __restrict__ ws, unsigned* __restrict__ counters,
-                                                    int nsplit_cfg, int defer_merge, const int* run_flag, int window) {
-  if (run_flag && *run_flag == 0) return;
+__device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS, int RS,
+                                               const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
+                                               long seq_stride, int capb, f16_t* __restrict__ out, int H,
+                                               float* __restrict__ ws, unsigned* __restrict__ counters,
+                                               int nsplit_cfg, int defer_merge, int window, int split, int hh, int s) {
   constexpr int NQ = QT * 16;
   constexpr int PSZ = NQ * 64 + 2 * NQ;
   __shared__ float lo[4][NQ][65];
@@ -469,7 +469,6 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   __shared__ AttnMergeShared<QT> ms;
   __shared__ int s_last;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int split = blockIdx.x, hh = blockIdx.y, s = blockIdx.z;
   const int d = H * FM_HD;
   const int g = lane >> 4, ql = lane & 15;
   const float kScale = 0.125f * 1.4426950408889634f;   // 1/sqrt(64) * log2(e)
@@ -640,17 +639,51 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
   attn_merge<QT, true>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * FM_HD, d);
 }
 
+template <int QT>
+__global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS, int RS,
+                                                    const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
+                                                    long seq_stride, int capb, f16_t* __restrict__ out, int H,
+                                                    float* __restrict__ ws, unsigned* __restrict__ counters,
+                                                    int nsplit_cfg, int defer_merge, const int* run_flag, int window) {
+  if (run_flag && *run_flag == 0) return;
+  attn_mfma_core<QT>(q, limit, RPS, RS, Kc, Vc, seq_stride, capb, out, H, ws, counters, nsplit_cfg, defer_merge, window,
+                     blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Up to three row sets of one sequence, each attending to a cache of its own (the SP heads of the three levels read the
+// coordinate-, point- and face-level caches of the last blocks, Eq. 1), in one launch: blockIdx.z picks the set.
+// Workspace and counters of set z start at z * H * FM_ATTN_MAX_SPLIT * (32*64+64) floats and z * H counters.
+struct AttnLevel {
+  const f16_t* q;
+  const int* limit;
+  int RPS;                 // rows (0: the set is empty)
+  const f16_t *Kc, *Vc;
+  int capb;
+  f16_t* out;
+  int nsplit_cfg, window;
+};
+struct AttnLevels { AttnLevel lv[3]; };
+
+__global__ __launch_bounds__(256) void k_attn_mfma_levels(AttnLevels L, int H, float* __restrict__ ws,
+                                                           unsigned* __restrict__ counters, int defer_merge,
+                                                           const int* run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  const int z = blockIdx.z;
+  const AttnLevel A = z == 0 ? L.lv[0] : z == 1 ? L.lv[1] : L.lv[2];
+  if (A.RPS == 0 || (int)blockIdx.x >= A.nsplit_cfg) return;
+  attn_mfma_core<1>(A.q, A.limit, A.RPS, A.RPS, A.Kc, A.Vc, 0L, A.capb, A.out, H,
+                    ws + (size_t)z * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), counters + z * H, A.nsplit_cfg, defer_merge,
+                    A.window, blockIdx.x, blockIdx.y, 0);
+}
+
 // Second launch of the deferred form: one workgroup per (head, sequence) derives the split count exactly as the
 // first launch did and merges; (sequence, head) pairs that fitted one split were already written there.
 template <int QT>
-__global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limit, int RPS, int RS, int capb, int nsplit_cfg,
-                                                     f16_t* __restrict__ out, int H, const float* __restrict__ ws,
-                                                     const int* run_flag) {
-  if (run_flag && *run_flag == 0) return;
+__device__ __forceinline__ void attn_merge_core(const int* __restrict__ limit, int RPS, int RS, int capb, int nsplit_cfg,
+                                                f16_t* __restrict__ out, int H, const float* __restrict__ ws, int hh, int s) {
   constexpr int NQ = QT * 16;
   constexpr int PSZ = NQ * 64 + 2 * NQ;
   __shared__ AttnMergeShared<QT> ms;
-  const int hh = blockIdx.x, s = blockIdx.y;
   const int d = H * FM_HD;
   int maxlim = -1;
   for (int qi = 0; qi < RPS; qi++) maxlim = max(maxlim, limit[(long)s * RS + qi]);
@@ -660,6 +693,24 @@ __global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limi
   if (nsplit == 1) return;
   const long sh = (long)s * H + hh;
   attn_merge<QT, false>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * FM_HD, d);
+}
+
+template <int QT>
+__global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limit, int RPS, int RS, int capb, int nsplit_cfg,
+                                                     f16_t* __restrict__ out, int H, const float* __restrict__ ws,
+                                                     const int* run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  attn_merge_core<QT>(limit, RPS, RS, capb, nsplit_cfg, out, H, ws, blockIdx.x, blockIdx.y);
+}
+
+__global__ __launch_bounds__(256) void k_attn_merge_levels(AttnLevels L, int H, const float* __restrict__ ws,
+                                                            const int* run_flag) {
+  if (run_flag && *run_flag == 0) return;
+  const int z = blockIdx.y;
+  const AttnLevel A = z == 0 ? L.lv[0] : z == 1 ? L.lv[1] : L.lv[2];
+  if (A.RPS == 0) return;
+  attn_merge_core<1>(A.limit, A.RPS, A.RPS, A.capb, A.nsplit_cfg, A.out, H,
+                     ws + (size_t)z * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), blockIdx.x, 0);
 }
 
 inline size_t mfma_attn_ws_floats(int S, int H) {
@@ -716,5 +767,42 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
       if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
     }
   }
+  return true;
+}
+
+// One launch (plus the merge launch) for up to three row sets of one sequence, each with its own cache.
+// `dense`, `key_bound`, `window` per set as in mfma_attn_launch.  Returns false if a set does not fit one q-tile.
+struct AttnLevelHost {
+  const void* q; const int* limit; int rows; const void *Kc, *Vc; int cap; void* out; bool dense; int key_bound, window;
+};
+inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv)[3], int H, const int* flag, hipStream_t st) {
+  AttnLevels L{};
+  int gx = 1;
+  long total = 0;
+  for (int z = 0; z < 3; z++) {
+    const AttnLevelHost& h = lv[z];
+    AttnLevel& A = L.lv[z];
+    A = AttnLevel{(const f16_t*)h.q, h.limit, h.rows, (const f16_t*)h.Kc, (const f16_t*)h.Vc, (h.cap + 31) / 32, (f16_t*)h.out, 1, h.window};
+    if (h.rows == 0) continue;
+    if (h.rows > 16) return false;
+    if (h.window > 0 && (h.cap % 32 != 0 || h.window > h.cap)) return false;
+    // the same partition of the key axis as mfma_attn_launch makes for one sequence
+    int nsplit = A.capb / 8;
+    nsplit = nsplit < 1 ? 1 : nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
+    if (h.dense) {
+      const int want = 768 / H > 0 ? 768 / H : 1;
+      nsplit = nsplit > want ? want : nsplit;
+    }
+    A.nsplit_cfg = nsplit;
+    const int per = (A.capb + nsplit - 1) / nsplit;
+    const int bound_blocks = ((h.key_bound < h.cap ? h.key_bound : h.cap) + 31) / 32;
+    int launched = (bound_blocks + per - 1) / per;
+    launched = launched < 1 ? 1 : launched > nsplit ? nsplit : launched;
+    gx = launched > gx ? launched : gx;
+    total += (long)launched * H;
+  }
+  const int defer = (gx > 1 && total > 256) ? 1 : 0;
+  hipLaunchKernelGGL(k_attn_mfma_levels, dim3(gx, H, 3), dim3(256), 0, st, L, H, res.attn_ws, res.attn_counters, defer, flag);
+  if (defer) hipLaunchKernelGGL(k_attn_merge_levels, dim3(H, 3), dim3(256), 0, st, L, H, res.attn_ws, flag);
   return true;
 }
