@@ -42,8 +42,9 @@ extern "C" {
 
 typedef struct fm_ctx fm_ctx; /* opaque, owned by the library */
 
-/* Plain-old-data configuration, copied by fm_create.  head_dim = d_model / n_heads must be 64, or 96 / 128 (the widths of the
- * paper's own models, Sec. 5.1) with FM_DTYPE_F32: the half-precision kernels are built for 64.
+/* Plain-old-data configuration, copied by fm_create.  head_dim = d_model / n_heads must be 64, 96 or 128 (96 and 128 are the
+ * widths of the paper's own models, Sec. 5.1; they run one launch per operator in either storage type - the single-launch
+ * verify kernel and the fused projection epilogue are written for 64-wide heads).
  * vocabulary = n_bins + 3 with BOS = n_bins, EOS = n_bins + 1, PAD = n_bins + 2. */
 typedef struct {
   int32_t d_model, n_heads, ffn_mult, n_bins;

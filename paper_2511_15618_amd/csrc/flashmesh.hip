@@ -200,7 +200,7 @@ template <typename T>
 void attention(fm_ctx* c, const void* q, const int* limit, int rows, int RPS, const void* Kc, const void* Vc,
                long seq_stride, int cap, void* out, const int* flag, bool dense = false, int key_bound = 1 << 30,
                int window = 0) {
-  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, window, c->stream)) return;
+  if (mfma_attn_launch<T>(c->mres, q, limit, rows, RPS, Kc, Vc, seq_stride, cap, out, c->D.H, flag, dense, key_bound, window, c->stream, c->D.hd)) return;
   // the plain kernel reads row-major caches: only the fp32 path has those
   if (!std::is_same<T, float>::value) { fail(c, FM_EINVAL, "attention: unsupported row set (%d rows, %d per sequence)", rows, RPS); c->sticky_error = true; return; }
 #define FM_ATTN(HDV) hipLaunchKernelGGL((k_attn_simple<T, HDV>), dim3(rows, c->D.H), dim3(256), 0, c->stream, (const T*)q, limit, RPS, \
@@ -237,10 +237,12 @@ void gemm_norm(fm_ctx* c, int epi, const float* h, const float* gain, const void
 template <typename T>
 void rope_append(fm_ctx* c, const float* qkv, long ldq, const float2* cs, const int* pos, int rows, int RPS, void* q,
                  void* Kc, void* Vc, int cap, const int* flag) {
-  if (std::is_same<T, f16_t>::value)
-    hipLaunchKernelGGL(k_rope_append_h, dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (f16_t*)q, (f16_t*)Kc,
-                       (f16_t*)Vc, c->D.H, (cap + 31) / 32, flag);
-  else {
+  if (std::is_same<T, f16_t>::value) {
+#define FM_ROPEH(HDV) hipLaunchKernelGGL((k_rope_append_h<HDV>), dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (f16_t*)q, \
+                                         (f16_t*)Kc, (f16_t*)Vc, c->D.H, (cap + 31) / 32, flag)
+    if (c->D.hd == 64) FM_ROPEH(64); else if (c->D.hd == 96) FM_ROPEH(96); else FM_ROPEH(128);
+#undef FM_ROPEH
+  } else {
 #define FM_ROPE(HDV) hipLaunchKernelGGL((k_rope_append<float, HDV>), dim3(rows), dim3(256), 0, c->stream, qkv, ldq, cs, pos, RPS, (float*)q, \
                                         (float*)Kc, (float*)Vc, c->D.H, cap, flag)
     if (c->D.hd == 64) FM_ROPE(64); else if (c->D.hd == 96) FM_ROPE(96); else FM_ROPE(128);
@@ -250,7 +252,7 @@ void rope_append(fm_ctx* c, const float* qkv, long ldq, const float2* cs, const 
 
 // elements of one (sequence) slice of a K or V cache with `cap` key positions
 size_t cache_seq_elems(const fm_ctx* c, int cap) {
-  return c->bf16 ? (size_t)c->D.H * ((cap + 31) / 32) * 2048 : (size_t)c->D.H * cap * c->D.hd;
+  return c->bf16 ? (size_t)c->D.H * ((cap + 31) / 32) * 32 * c->D.hd : (size_t)c->D.H * cap * c->D.hd;
 }
 
 // one transformer block on the row set of `level` (Sec. 3.1: self-attention, cross-attention to c, FFN)
@@ -262,8 +264,9 @@ void run_block(fm_ctx* c, const Layer& L, int level) {
   const int cap = level_cap(c, level);
   float* h = c->h[level];
   const int* flag = c->st.alive;
-  if (std::is_same<T, f16_t>::value) {
-    // norm1, fused q,k,v projection, rotary, q out and cache append in one launch
+  if (std::is_same<T, f16_t>::value && D.hd == 64) {
+    // norm1, fused q,k,v projection, rotary, q out and cache append in one launch (written for 64-wide heads; the
+    // wider heads of the paper's own shapes take the two launches below)
     GemmArgs a{h, d, 0, L.wqkv, 0, c->qT, d, 0, nullptr, 0, 0, rows, 3 * d, d, flag, L.g1, c->cfg.rms_eps,
                c->cs[level], c->pos[level], RPS, L.Kc, L.Vc, (long)cache_seq_elems(c, cap), (cap + 31) / 32, D.H};
     if (!mfma_gemm_launch<T>(c->mres, a, EPI_QKV, 1, c->stream)) { fail(c, FM_EINVAL, "qkv: unsupported shape"); c->sticky_error = true; }
@@ -499,8 +502,10 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev, void* stage_area) {
     // memory -> MFMA fragment order (the same tiling as a weight matrix), then one launch for all blocks
     f16_t* Xt = (f16_t*)stage_area;
     hipLaunchKernelGGL(k_tile_weight, dim3(1024), dim3(256), 0, c->stream, mem_dev, Xt, D.M, d, D.M, 0);
-    hipLaunchKernelGGL(k_prefill_kv, dim3(c->pf_grid), dim3(256), PF_LDS_BYTES, c->stream,
-                       (const f16_t*)Xt, (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M, c->pf_n);
+#define FM_PREFILL(HDV) hipLaunchKernelGGL((k_prefill_kv<HDV>), dim3(c->pf_grid), dim3(256), PF_LDS_BYTES, c->stream, (const f16_t*)Xt, \
+                                           (const PrefillLayer*)c->pf_layers, (long)((size_t)seq * cache_seq_elems(c, D.M)), d / 32, d, D.M, c->pf_n)
+    if (D.hd == 64) FM_PREFILL(64); else if (D.hd == 96) FM_PREFILL(96); else FM_PREFILL(128);
+#undef FM_PREFILL
     hipLaunchKernelGGL(k_reset_seq, dim3(1), dim3(64), 0, c->stream, c->st, D, seq, D.nbins);
     HIPCHK(c, hipGetLastError());
     return FM_OK;
@@ -513,10 +518,12 @@ int prefill_impl(fm_ctx* c, int seq, const float* mem_dev, void* stage_area) {
       gemm<T>(c, EPI_F32, memT, d, 0, L.ckv, 0, kv, 2 * d, 0, nullptr, 0, 0, D.M, 2 * d, d, 1, nullptr);
       T* Km = (T*)L.Km + (size_t)seq * cache_seq_elems(c, D.M);
       T* Vm = (T*)L.Vm + (size_t)seq * cache_seq_elems(c, D.M);
-      if (std::is_same<T, f16_t>::value)
-        hipLaunchKernelGGL(k_mem_kv_store_h, dim3(D.M), dim3(256), 0, c->stream, kv, (f16_t*)Km, (f16_t*)Vm, D.H, D.M,
-                           (D.M + 31) / 32);
-      else {
+      if (std::is_same<T, f16_t>::value) {
+#define FM_MEMKVH(HDV) hipLaunchKernelGGL((k_mem_kv_store_h<HDV>), dim3(D.M), dim3(256), 0, c->stream, kv, (f16_t*)Km, (f16_t*)Vm, D.H, D.M, \
+                                          (D.M + 31) / 32)
+        if (D.hd == 64) FM_MEMKVH(64); else if (D.hd == 96) FM_MEMKVH(96); else FM_MEMKVH(128);
+#undef FM_MEMKVH
+      } else {
 #define FM_MEMKV(HDV) hipLaunchKernelGGL((k_mem_kv_store<float, HDV>), dim3(D.M), dim3(256), 0, c->stream, kv, (float*)Km, (float*)Vm, D.H, D.M)
         if (D.hd == 64) FM_MEMKV(64); else if (D.hd == 96) FM_MEMKV(96); else FM_MEMKV(128);
 #undef FM_MEMKV
@@ -570,7 +577,7 @@ int build_params(fm_ctx* c) {
       TRY(dalloc_t(c, &L.Kc, D.S * cache_seq_elems(c, cap))); TRY(dalloc_t(c, &L.Vc, D.S * cache_seq_elems(c, cap)));
       TRY(dalloc_t(c, &L.Km, D.S * cache_seq_elems(c, D.M))); TRY(dalloc_t(c, &L.Vm, D.S * cache_seq_elems(c, D.M)));
       item(L.g1, d, true);
-      if (c->bf16) {
+      if (c->bf16 && D.hd == 64) {
         // half path: the q and k tiles of the fused projection hold whole rotary pairs (both verify paths apply
         // the rotation in the GEMM epilogue), so only the permuted tiling is kept
         c->items.push_back({off, 3 * d * d, L.wqkv, false, (int)(3 * d), (int)d, (int)d});
@@ -808,11 +815,11 @@ int build_buffers(fm_ctx* c) {
   c->mres = MfmaRes{nullptr, nullptr, 0, 0};
   if (const char* e = getenv("FM_GEMM_WAVES")) c->mres.gemm_waves = atoi(e);   // measurement switch: 4, 8 or 16
   if (c->bf16) {
-    c->mres.attn_ws_floats = mfma_attn_ws_floats(std::max(D.S, 3), D.H);       // 3: the merged SP launch has three row sets
+    c->mres.attn_ws_floats = mfma_attn_ws_floats(std::max(D.S, 3), D.H, D.hd);       // 3: the merged SP launch has three row sets
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
     TRY(dalloc(c, &c->mres.attn_counters, (size_t)std::max(D.S, 3) * D.H));
     const char* spm = getenv("FM_SP_MERGED");      // "0": one chain of launches per level, as with several sequences
-    c->sp_merged = D.S == 1 && D.Dc <= 16 && D.nspv <= 16 && D.nspf <= 16 && !(spm && spm[0] == '0');
+    c->sp_merged = D.hd == 64 && D.S == 1 && D.Dc <= 16 && D.nspv <= 16 && D.nspf <= 16 && !(spm && spm[0] == '0');
     // tiled prefill GEMM: whole 256 x 128 output tiles only (keys x dims for V, dims x keys for K)
     const char* pt = getenv("FM_PREFILL_TILED");     // "0" forces the per-block GEMM + scatter launches
     if (D.M % 256 == 0 && d % 256 == 0 && !(pt && pt[0] == '0')) {
@@ -824,7 +831,9 @@ int build_buffers(fm_ctx* c) {
       c->pf_layers = (PrefillLayer*)raw;
       HIPCHK(c, hipMemcpy(c->pf_layers, tab.data(), tab.size() * sizeof(PrefillLayer), hipMemcpyHostToDevice));
       c->pf_n = (int)tab.size();
-      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS_BYTES));
+      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv<64>, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS_BYTES));
+      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv<96>, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS_BYTES));
+      HIPCHK(c, hipFuncSetAttribute((const void*)k_prefill_kv<128>, hipFuncAttributeMaxDynamicSharedMemorySize, PF_LDS_BYTES));
       hipDeviceProp_t prop;
       int dev = 0;
       HIPCHK(c, hipGetDevice(&dev));
@@ -848,8 +857,8 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   *out = nullptr;
   const fm_config& g = *cfg;
   if (g.d_model <= 0 || g.n_heads <= 0 || g.d_model % g.n_heads != 0) return FM_EINVAL;
-  const int hd = g.d_model / g.n_heads;          // 64; 96 and 128 (the paper's own widths) in fp32 storage only
-  if (hd != 64 && !((hd == 96 || hd == 128) && g.dtype == FM_DTYPE_F32)) return FM_EINVAL;
+  const int hd = g.d_model / g.n_heads;          // 64, or the paper's own widths 96 and 128
+  if (hd != 64 && hd != 96 && hd != 128) return FM_EINVAL;
   if (g.ffn_mult < 1 || g.hf_ffn_mult < 1 || g.n_bins < 1 || g.mem_len < 1) return FM_EINVAL;
   if (g.l_cpre < 1 || g.l_cpost < 1 || g.l_vpre < 1 || g.l_vpost < 1 || g.l_face < 1) return FM_EINVAL;
   if (g.dtype != FM_DTYPE_F32 && g.dtype != FM_DTYPE_BF16) return FM_EINVAL;
@@ -902,7 +911,7 @@ int fm_create(const fm_config* cfg, void* hip_stream, fm_ctx** out) {
   {
     const int nl = g.l_cpre + g.l_cpost + g.l_vpre + g.l_vpost + g.l_face;
     const char* env = getenv("FM_PERSIST");
-    c->persist = c->bf16 && D.S == 1 && D.Bm <= 32 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
+    c->persist = c->bf16 && D.hd == 64 && D.S == 1 && D.Bm <= 32 && D.d % 128 == 0 && D.d <= 1024 && c->ff % 512 == 0 && nl < 62 &&
                  !(env && env[0] == '0');
   }
   int rc = build_params(c);

@@ -37,59 +37,65 @@ __device__ __forceinline__ void publish_fence() { __builtin_amdgcn_fence(__ATOMI
 #define FM_ATTN_MAX_SPLIT 64
 
 // ------------------------------------------------------------------------------------------
-// Cache layouts of the half-precision path (one 32-key block = 2048 halves = 4 KiB per head)
+// Cache layouts of the half-precision path: one 32-key block of a head = 32 HD halves (4 KiB for the 64-wide heads
+// of the benchmark configurations; HD = 96 and 128 are the paper's own model shapes)
 // ------------------------------------------------------------------------------------------
-// K: four A-fragments per block, fragment f = (key/16)*2 + dim/32, lane = key%16 + 16*((dim%32)/8)
+// K: HD/16 A-fragments per block, fragment f = (key/16)*(HD/32) + dim/32, lane = key%16 + 16*((dim%32)/8)
+template <int HD = 64>
 __device__ __forceinline__ long kblk_off(int key, int dim) {
   const int r = key & 31;
-  const int f = (r >> 4) * 2 + (dim >> 5);
+  const int f = (r >> 4) * (HD / 32) + (dim >> 5);
   const int lane = (r & 15) + 16 * ((dim & 31) >> 3);
-  return (long)(key >> 5) * 2048 + (f * 64 + lane) * 8 + (dim & 7);
+  return (long)(key >> 5) * (32 * HD) + (f * 64 + lane) * 8 + (dim & 7);
 }
 // V: transposed inside the block, [dim][slot]; slot order matches the C-layout of the score tile so
 // that the probabilities never leave registers: key r -> g = (r%16)/4, slot = g*8 + (r/16)*4 + r%4
+template <int HD = 64>
 __device__ __forceinline__ long vblk_off(int key, int dim) {
   const int r = key & 31;
   const int slot = ((r & 15) >> 2) * 8 + (r >> 4) * 4 + (r & 3);
-  return (long)(key >> 5) * 2048 + dim * 32 + slot;
+  return (long)(key >> 5) * (32 * HD) + dim * 32 + slot;
 }
 
 // rotary + append for the half-precision caches (same contract as k_rope_append)
+template <int HD>
 __global__ void k_rope_append_h(const float* __restrict__ qkv, long ldq, const float2* __restrict__ cs,
                                 const int* __restrict__ pos, int RPS, f16_t* __restrict__ q, f16_t* __restrict__ Kc,
                                 f16_t* __restrict__ Vc, int H, int capb, const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
+  constexpr int NP = HD / 2;                                  // rotary pairs per head: dims i and i + NP
   const int r = blockIdx.x;
   const int p = pos[r] >= 0 ? pos[r] % (capb * 32) : -1;     // the cache is a ring when a window is set
-  const int d = H * FM_HD;
+  const int d = H * HD;
   const int s = r / RPS;
-  for (int idx = threadIdx.x; idx < H * 32; idx += blockDim.x) {
-    const int hh = idx >> 5, i = idx & 31;
-    const float2 c = cs[(long)r * 32 + i];
+  for (int idx = threadIdx.x; idx < H * NP; idx += blockDim.x) {
+    const int hh = idx / NP, i = idx % NP;
+    const float2 c = cs[(long)r * NP + i];
     const float* row = qkv + (long)r * ldq;
-    const float qa = row[hh * 64 + i], qb = row[hh * 64 + 32 + i];
-    q[(long)r * d + hh * 64 + i] = (f16_t)(qa * c.x - qb * c.y);
-    q[(long)r * d + hh * 64 + 32 + i] = (f16_t)(qb * c.x + qa * c.y);
+    const float qa = row[hh * HD + i], qb = row[hh * HD + NP + i];
+    q[(long)r * d + hh * HD + i] = (f16_t)(qa * c.x - qb * c.y);
+    q[(long)r * d + hh * HD + NP + i] = (f16_t)(qb * c.x + qa * c.y);
     if (Kc && p >= 0) {
-      const float ka = row[d + hh * 64 + i], kb = row[d + hh * 64 + 32 + i];
-      const long base = ((long)s * H + hh) * capb * 2048;
-      Kc[base + kblk_off(p, i)] = (f16_t)(ka * c.x - kb * c.y);
-      Kc[base + kblk_off(p, i + 32)] = (f16_t)(kb * c.x + ka * c.y);
-      Vc[base + vblk_off(p, i)] = (f16_t)row[2 * d + hh * 64 + i];
-      Vc[base + vblk_off(p, i + 32)] = (f16_t)row[2 * d + hh * 64 + 32 + i];
+      const float ka = row[d + hh * HD + i], kb = row[d + hh * HD + NP + i];
+      const long base = ((long)s * H + hh) * capb * (32 * HD);
+      Kc[base + kblk_off<HD>(p, i)] = (f16_t)(ka * c.x - kb * c.y);
+      Kc[base + kblk_off<HD>(p, i + NP)] = (f16_t)(kb * c.x + ka * c.y);
+      Vc[base + vblk_off<HD>(p, i)] = (f16_t)row[2 * d + hh * HD + i];
+      Vc[base + vblk_off<HD>(p, i + NP)] = (f16_t)row[2 * d + hh * HD + NP + i];
     }
   }
 }
 
+template <int HD>
 __global__ void k_mem_kv_store_h(const float* __restrict__ kv, f16_t* __restrict__ Kc, f16_t* __restrict__ Vc, int H,
                                  int M, int capb) {
   const int m = blockIdx.x;
-  const int d = H * FM_HD;
+  const int d = H * HD;
   for (int i = threadIdx.x; i < d; i += blockDim.x) {
-    const int hh = i >> 6, e = i & 63;
-    const long base = (long)hh * capb * 2048;
-    Kc[base + kblk_off(m, e)] = (f16_t)kv[(long)m * 2 * d + i];
-    Vc[base + vblk_off(m, e)] = (f16_t)kv[(long)m * 2 * d + d + i];
+    const int hh = i / HD, e = i % HD;
+    const long base = (long)hh * capb * (32 * HD);
+    Kc[base + kblk_off<HD>(m, e)] = (f16_t)kv[(long)m * 2 * d + i];
+    Vc[base + vblk_off<HD>(m, e)] = (f16_t)kv[(long)m * 2 * d + d + i];
   }
 }
 
@@ -381,10 +387,10 @@ struct AttnMergeShared {
   float cf[FM_ATTN_MAX_SPLIT][QT * 16], cl[FM_ATTN_MAX_SPLIT][QT * 16], cden[QT * 16];
 };
 
-template <int QT, bool AGENT>
+template <int QT, bool AGENT, int HD = 64>
 __device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float* base, int nsplit, int RPS, f16_t* orow0, int d) {
   constexpr int NQ = QT * 16;
-  constexpr int PSZ = NQ * 64 + 2 * NQ;
+  constexpr int PSZ = NQ * HD + 2 * NQ;
   typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
   for (int e0 = 0; e0 < nsplit * NQ; e0 += 256 * 4) {
     float tm[4], tl[4];
@@ -393,7 +399,7 @@ __device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float*
       const int e = e0 + j * 256 + threadIdx.x;
       tm[j] = tl[j] = 0.f;
       if (e < nsplit * NQ) {
-        const float* pp = base + (long)(e / NQ) * PSZ + NQ * 64 + (e % NQ);
+        const float* pp = base + (long)(e / NQ) * PSZ + NQ * HD + (e % NQ);
         tm[j] = AGENT ? ld_agent(pp) : *pp;
         tl[j] = AGENT ? ld_agent(pp + NQ) : pp[NQ];
       }
@@ -420,8 +426,8 @@ __device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float*
   }
   __syncthreads();
   // numerators: 16-byte loads (four dims of one query row), eight splits in flight per thread
-  for (int v4 = threadIdx.x; v4 < NQ * 16; v4 += 256) {
-    const int e = v4 * 4, qi = e >> 6, dim = e & 63;
+  for (int v4 = threadIdx.x; v4 < NQ * (HD / 4); v4 += 256) {
+    const int e = v4 * 4, qi = e / HD, dim = e % HD;
     float num[4] = {0.f, 0.f, 0.f, 0.f};
     for (int c0 = 0; c0 < nsplit; c0 += 8) {
       u32x4 v[8];
@@ -454,28 +460,29 @@ __device__ __forceinline__ void attn_merge(AttnMergeShared<QT>& ms, const float*
   }
 }
 
-// Workspace per (sequence, head): [nsplit][QT*16*64 unnormalised O | QT*16 running max (log2 units) | QT*16 sums]
+// Workspace per (sequence, head): [nsplit][QT*16*HD unnormalised O | QT*16 running max (log2 units) | QT*16 sums]
 // (the body of the launch; `split`, `hh`, `s` = key range, head and sequence of this workgroup)
-template <int QT>
+template <int QT, int HD = 64>
 __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS, int RS,
                                                const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
                                                long seq_stride, int capb, f16_t* __restrict__ out, int H,
                                                float* __restrict__ ws, unsigned* __restrict__ counters,
                                                int nsplit_cfg, int defer_merge, int window, int split, int hh, int s) {
   constexpr int NQ = QT * 16;
-  constexpr int PSZ = NQ * 64 + 2 * NQ;
-  __shared__ float lo[4][NQ][65];
+  constexpr int PSZ = NQ * HD + 2 * NQ;
+  constexpr int KC = HD / 32, DT = HD / 16;     // 32-dim chunks of a key row, 16-dim tiles of the output
+  __shared__ float lo[4][NQ][HD + 1];
   __shared__ float lm[4][NQ], ll[4][NQ];
   __shared__ AttnMergeShared<QT> ms;
   __shared__ int s_last;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int d = H * FM_HD;
+  const int d = H * HD;
   const int g = lane >> 4, ql = lane & 15;
-  const float kScale = 0.125f * 1.4426950408889634f;   // 1/sqrt(64) * log2(e)
+  const float kScale = (HD == 64 ? 0.125f : 1.0f / sqrtf((float)HD)) * 1.4426950408889634f;   // 1/sqrt(HD) * log2(e)
 
   // this lane's query rows (one per q-tile), their visibility limits and B-operand fragments
   int lim[QT], first[QT];
-  f16x8 qf[QT][2];
+  f16x8 qf[QT][KC];
   int maxlim = -1;
 #pragma unroll
   for (int t = 0; t < QT; t++) {
@@ -485,9 +492,9 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
     lim[t] = on ? limit[row] : -1;
     first[t] = window > 0 ? max(lim[t] - window + 1, 0) : 0;     // sliding window: keys first .. lim
     maxlim = max(maxlim, lim[t]);
-    const f16_t* qp = q + row * d + hh * FM_HD + g * 8;
-    qf[t][0] = *reinterpret_cast<const f16x8*>(qp);
-    qf[t][1] = *reinterpret_cast<const f16x8*>(qp + 32);
+    const f16_t* qp = q + row * d + hh * HD + g * 8;
+#pragma unroll
+    for (int kc = 0; kc < KC; kc++) qf[t][kc] = *reinterpret_cast<const f16x8*>(qp + kc * 32);
   }
 #pragma unroll
   for (int o = 1; o < 16; o <<= 1) maxlim = max(maxlim, __shfl_xor(maxlim, o, 64));
@@ -509,35 +516,36 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
   const int b0 = split * per, b1 = min(b0 + per, nblk);
 
   float mrun[QT], lrun[QT];
-  f32x4 o[QT][4];
+  f32x4 o[QT][DT];
 #pragma unroll
   for (int t = 0; t < QT; t++) {
     mrun[t] = -INFINITY;
     lrun[t] = 0.f;
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int dt = 0; dt < DT; dt++) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
-  const f16_t* Kb = Kc + (long)s * seq_stride + (long)hh * capb * 2048;
-  const f16_t* Vb = Vc + (long)s * seq_stride + (long)hh * capb * 2048;
+  constexpr int BLK = 32 * HD;                 // halves per 32-key block of a head
+  const f16_t* Kb = Kc + (long)s * seq_stride + (long)hh * capb * BLK;
+  const f16_t* Vb = Vc + (long)s * seq_stride + (long)hh * capb * BLK;
   // the next block of this wave is requested before the current one is multiplied
-  f16x8 kf[4], vf[4];
+  f16x8 kf[2 * KC], vf[DT];
   if (b0 + wave < b1) {
-    const f16_t* kp = Kb + (long)(b0 + wave) * 2048 + lane * 8;
-    const f16_t* vp = Vb + (long)(b0 + wave) * 2048 + (lane & 15) * 32 + g * 8;
+    const f16_t* kp = Kb + (long)(b0 + wave) * BLK + lane * 8;
+    const f16_t* vp = Vb + (long)(b0 + wave) * BLK + (lane & 15) * 32 + g * 8;
 #pragma unroll
-    for (int f = 0; f < 4; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
+    for (int f = 0; f < 2 * KC; f++) kf[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+    for (int dt = 0; dt < DT; dt++) vf[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
   }
   for (int b = b0 + wave; b < b1; b += 4) {
-    f16x8 kn[4], vn[4];
+    f16x8 kn[2 * KC], vn[DT];
     if (b + 4 < b1) {
-      const f16_t* kp = Kb + (long)(b + 4) * 2048 + lane * 8;
-      const f16_t* vp = Vb + (long)(b + 4) * 2048 + (lane & 15) * 32 + g * 8;
+      const f16_t* kp = Kb + (long)(b + 4) * BLK + lane * 8;
+      const f16_t* vp = Vb + (long)(b + 4) * BLK + (lane & 15) * 32 + g * 8;
 #pragma unroll
-      for (int f = 0; f < 4; f++) kn[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
+      for (int f = 0; f < 2 * KC; f++) kn[f] = *reinterpret_cast<const f16x8*>(kp + f * 512);
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++) vn[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
+      for (int dt = 0; dt < DT; dt++) vn[dt] = *reinterpret_cast<const f16x8*>(vp + dt * 512);
     }
 #pragma unroll
     for (int t = 0; t < QT; t++) {
@@ -546,8 +554,8 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
 #pragma unroll
       for (int hb = 0; hb < 2; hb++) {
         f32x4 z = f32x4{0.f, 0.f, 0.f, 0.f};
-        z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2], qf[t][0], z, 0, 0, 0);
-        z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * 2 + 1], qf[t][1], z, 0, 0, 0);
+#pragma unroll
+        for (int kc = 0; kc < KC; kc++) z = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf[hb * KC + kc], qf[t][kc], z, 0, 0, 0);
         sT[hb] = z;
       }
       float mx = -INFINITY;
@@ -579,14 +587,16 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
         }
       lrun[t] = lrun[t] * alpha + psum;
 #pragma unroll
-      for (int dt = 0; dt < 4; dt++) {
+      for (int dt = 0; dt < DT; dt++) {
         o[t][dt] *= alpha;
         o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf[dt], pf, o[t][dt], 0, 0, 0);   // O^T[dim][q]
       }
     }
     if (b + 4 < b1) {
 #pragma unroll
-      for (int f = 0; f < 4; f++) { kf[f] = kn[f]; vf[f] = vn[f]; }
+      for (int f = 0; f < 2 * KC; f++) kf[f] = kn[f];
+#pragma unroll
+      for (int dt = 0; dt < DT; dt++) vf[dt] = vn[dt];
     }
   }
   // combine the four waves of the workgroup
@@ -597,15 +607,15 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
     l += __shfl_xor(l, 32, 64);
     if (g == 0) { lm[wave][t * 16 + ql] = mrun[t]; ll[wave][t * 16 + ql] = l; }
 #pragma unroll
-    for (int dt = 0; dt < 4; dt++)
+    for (int dt = 0; dt < DT; dt++)
 #pragma unroll
       for (int i = 0; i < 4; i++) lo[wave][t * 16 + ql][dt * 16 + g * 4 + i] = o[t][dt][i];
   }
   __syncthreads();
   const long sh = (long)s * H + hh;
   float* part = ws + (sh * nsplit_cfg + split) * PSZ;   // slots are laid out for the configured split count
-  for (int e = threadIdx.x; e < NQ * 64; e += 256) {
-    const int qi = e >> 6, dim = e & 63;
+  for (int e = threadIdx.x; e < NQ * HD; e += 256) {
+    const int qi = e / HD, dim = e % HD;
     const float M = fmaxf(fmaxf(lm[0][qi], lm[1][qi]), fmaxf(lm[2][qi], lm[3][qi]));
     const float Ms = M == -INFINITY ? 0.f : M;
     float num = 0.f, den = 0.f;
@@ -616,13 +626,13 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
       den += ll[w][qi] * f;
     }
     if (nsplit == 1) {
-      if (qi < RPS) out[((long)s * RS + qi) * d + hh * FM_HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
+      if (qi < RPS) out[((long)s * RS + qi) * d + hh * HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
     } else if (defer_merge) {
       part[e] = num;
-      if (dim == 0) { part[NQ * 64 + qi] = M; part[NQ * 64 + NQ + qi] = den; }
+      if (dim == 0) { part[NQ * HD + qi] = M; part[NQ * HD + NQ + qi] = den; }
     } else {
       st_agent(part + e, num);
-      if (dim == 0) { st_agent(part + NQ * 64 + qi, M); st_agent(part + NQ * 64 + NQ + qi, den); }
+      if (dim == 0) { st_agent(part + NQ * HD + qi, M); st_agent(part + NQ * HD + NQ + qi, den); }
     }
   }
   if (nsplit == 1 || defer_merge) return;     // deferred: k_attn_merge runs behind this launch
@@ -636,17 +646,17 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
   __syncthreads();
   if (!s_last) return;
   // last workgroup of this (sequence, head)
-  attn_merge<QT, true>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * FM_HD, d);
+  attn_merge<QT, true, HD>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * HD, d);
 }
 
-template <int QT>
+template <int QT, int HD>
 __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, const int* __restrict__ limit, int RPS, int RS,
                                                     const f16_t* __restrict__ Kc, const f16_t* __restrict__ Vc,
                                                     long seq_stride, int capb, f16_t* __restrict__ out, int H,
                                                     float* __restrict__ ws, unsigned* __restrict__ counters,
                                                     int nsplit_cfg, int defer_merge, const int* run_flag, int window) {
   if (run_flag && *run_flag == 0) return;
-  attn_mfma_core<QT>(q, limit, RPS, RS, Kc, Vc, seq_stride, capb, out, H, ws, counters, nsplit_cfg, defer_merge, window,
+  attn_mfma_core<QT, HD>(q, limit, RPS, RS, Kc, Vc, seq_stride, capb, out, H, ws, counters, nsplit_cfg, defer_merge, window,
                      blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
@@ -678,13 +688,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma_levels(AttnLevels L, int H, f
 
 // Second launch of the deferred form: one workgroup per (head, sequence) derives the split count exactly as the
 // first launch did and merges; (sequence, head) pairs that fitted one split were already written there.
-template <int QT>
+template <int QT, int HD = 64>
 __device__ __forceinline__ void attn_merge_core(const int* __restrict__ limit, int RPS, int RS, int capb, int nsplit_cfg,
                                                 f16_t* __restrict__ out, int H, const float* __restrict__ ws, int hh, int s) {
   constexpr int NQ = QT * 16;
-  constexpr int PSZ = NQ * 64 + 2 * NQ;
+  constexpr int PSZ = NQ * HD + 2 * NQ;
   __shared__ AttnMergeShared<QT> ms;
-  const int d = H * FM_HD;
+  const int d = H * HD;
   int maxlim = -1;
   for (int qi = 0; qi < RPS; qi++) maxlim = max(maxlim, limit[(long)s * RS + qi]);
   const int nblk = min((maxlim + 32) >> 5, capb);
@@ -692,15 +702,15 @@ __device__ __forceinline__ void attn_merge_core(const int* __restrict__ limit, i
   const int nsplit = max(1, (nblk + per - 1) / per);
   if (nsplit == 1) return;
   const long sh = (long)s * H + hh;
-  attn_merge<QT, false>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * FM_HD, d);
+  attn_merge<QT, false, HD>(ms, ws + sh * nsplit_cfg * PSZ, nsplit, RPS, out + (long)s * RS * d + hh * HD, d);
 }
 
-template <int QT>
+template <int QT, int HD>
 __global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limit, int RPS, int RS, int capb, int nsplit_cfg,
                                                      f16_t* __restrict__ out, int H, const float* __restrict__ ws,
                                                      const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
-  attn_merge_core<QT>(limit, RPS, RS, capb, nsplit_cfg, out, H, ws, blockIdx.x, blockIdx.y);
+  attn_merge_core<QT, HD>(limit, RPS, RS, capb, nsplit_cfg, out, H, ws, blockIdx.x, blockIdx.y);
 }
 
 __global__ __launch_bounds__(256) void k_attn_merge_levels(AttnLevels L, int H, const float* __restrict__ ws,
@@ -713,20 +723,21 @@ __global__ __launch_bounds__(256) void k_attn_merge_levels(AttnLevels L, int H, 
                      ws + (size_t)z * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), blockIdx.x, 0);
 }
 
-inline size_t mfma_attn_ws_floats(int S, int H) {
-  return (size_t)S * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64);
+inline size_t mfma_attn_ws_floats(int S, int H, int hd = 64) {
+  return (size_t)S * H * FM_ATTN_MAX_SPLIT * (32 * std::max(hd, 64) + 64);
 }
 
 template <typename T>
 bool mfma_attn_launch(const MfmaRes&, const void*, const int*, int, int, const void*, const void*, long, int, void*, int,
-                      const int*, bool, int, int, hipStream_t) { return false; }
+                      const int*, bool, int, int, hipStream_t, int = 64) { return false; }
 
 // `cap` = key capacity of the cache (positions); caches are laid out in 32-key blocks
 template <>
 inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int* limit, int rows, int RPS, const void* Kc,
                                     const void* Vc, long seq_stride, int cap, void* out, int H, const int* flag,
-                                    bool dense, int key_bound, int window, hipStream_t st) {
+                                    bool dense, int key_bound, int window, hipStream_t st, int hd) {
   if (RPS < 1 || rows % RPS != 0) return false;
+  if (hd != 64 && hd != 96 && hd != 128) return false;
   if (window > 0 && (cap % 32 != 0 || window > cap)) return false;     // a ring is a whole number of blocks
   const int S = rows / RPS;
   const int capb = (cap + 31) / 32;
@@ -750,23 +761,27 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
   // write-back, and those queue up per XCD).  Then the partials go out as plain stores and a second, tiny
   // launch merges them; the arithmetic is the same either way.
   const int defer = (launched > 1 && (long)launched * H * S > 256) ? 1 : 0;
-  // at most 32 query rows of a sequence per launch; longer row sets go out in chunks
-  const int d = H * FM_HD;
-  for (int r0 = 0; r0 < RPS; r0 += 32) {
-    const int rc = RPS - r0 < 32 ? RPS - r0 : 32;
+  // at most 32 query rows of a sequence per launch (16 for the wide heads, whose partial tiles would not fit the
+  // LDS of a 32-row launch); longer row sets go out in chunks
+  const int d = H * hd;
+  const int chunk = hd == 64 ? 32 : 16;
+#define FM_ATTN_GO(QTV, HDV)                                                                                       \
+  {                                                                                                                \
+    hipLaunchKernelGGL((k_attn_mfma<QTV, HDV>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc, \
+                       seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag, window);     \
+    if (defer) hipLaunchKernelGGL((k_attn_merge<QTV, HDV>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag); \
+  }
+  for (int r0 = 0; r0 < RPS; r0 += chunk) {
+    const int rc = RPS - r0 < chunk ? RPS - r0 : chunk;
     const f16_t* qc = (const f16_t*)q + (long)r0 * d;
     const int* lc = limit + r0;
     f16_t* oc = (f16_t*)out + (long)r0 * d;
-    if (rc <= 16) {
-      hipLaunchKernelGGL((k_attn_mfma<1>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc,
-                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag, window);
-      if (defer) hipLaunchKernelGGL((k_attn_merge<1>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
-    } else {
-      hipLaunchKernelGGL((k_attn_mfma<2>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc,
-                         seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag, window);
-      if (defer) hipLaunchKernelGGL((k_attn_merge<2>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag);
-    }
+    if (hd == 96) FM_ATTN_GO(1, 96)
+    else if (hd == 128) FM_ATTN_GO(1, 128)
+    else if (rc <= 16) FM_ATTN_GO(1, 64)
+    else FM_ATTN_GO(2, 64)
   }
+#undef FM_ATTN_GO
   return true;
 }
 

@@ -35,7 +35,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 #define PF_WAIT_VM(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14))
 
 // Launch: gridDim.x a multiple of 8 (one workgroup per compute unit), 256 threads, PF_LDS_BYTES of dynamic LDS.
-// Needs M % 256 == 0, d % 256 == 0 (whole tiles) and KT = d / 32.
+// Needs M % 256 == 0, d % 256 == 0 (whole tiles), KT = d / 32 and HD (the head width, a multiple of 32) dividing d.
+template <int HD>
 __global__ __launch_bounds__(256, 1) void k_prefill_kv(const f16_t* __restrict__ Xt, const PrefillLayer* __restrict__ layers,
                                                        long seq_off, int KT, int d, int M, int n_layers) {
   extern __shared__ pf_u32x4 pf_smem[];
@@ -183,13 +184,13 @@ __global__ __launch_bounds__(256, 1) void k_prefill_kv(const f16_t* __restrict__
             // rows = keys, column = dim.  Keys r..r+3 and r+16..r+19 of a block sit next to each other in the V
             // layout: runs j/4 = q and q+2 make one 16-byte store
             const int row0 = a0 + wm * 128 + x * 32 + hl4;
-            f16_t* base = L.Vm + seq_off + (long)(col >> 6) * capb * 2048;
+            f16_t* base = L.Vm + seq_off + (long)(col / HD) * capb * (32 * HD);
 #pragma unroll
             for (int q = 0; q < 2; q++) {
               f16x8o o;
 #pragma unroll
               for (int i = 0; i < 4; i++) { o[i] = (f16_t)acc[x][w][q * 4 + i]; o[4 + i] = (f16_t)acc[x][w][(q + 2) * 4 + i]; }
-              *(__attribute__((address_space(1))) f16x8o*)(base + vblk_off(row0 + q * 8, col & 63)) = o;
+              *(__attribute__((address_space(1))) f16x8o*)(base + vblk_off<HD>(row0 + q * 8, col % HD)) = o;
             }
           } else {
             // rows = dims, column = key.  Lanes l and l+32 hold dims 0-3 and 4-7 of the same 8-dim run of a key, which
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(256, 1) void k_prefill_kv(const f16_t* __restrict__
               const auto s1 = __builtin_amdgcn_permlane32_swap(l2[1], h2[1], false, false);
               const pf_u32x4 o = {s0[0], s1[0], s0[1], s1[1]};
               const int e0 = a0 + wm * 128 + x * 32 + (2 * qp + (lane >> 5)) * 8;   // first dim of the run this lane stores
-              *(__attribute__((address_space(1))) pf_u32x4*)(L.Km + seq_off + (long)(e0 >> 6) * capb * 2048 + kblk_off(col, e0 & 63)) = o;
+              *(__attribute__((address_space(1))) pf_u32x4*)(L.Km + seq_off + (long)(e0 / HD) * capb * (32 * HD) + kblk_off<HD>(col, e0 % HD)) = o;
             }
           }
 #pragma unroll

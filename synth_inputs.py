@@ -120,10 +120,14 @@ TEST_CONFIGS = {
     "t_bf16_1815_noAB": Config("t_bf16_1815_noAB", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18, rule_a=0, rule_b=0),
     "t_bf16_99_b1_noB": Config("t_bf16_99_b1_noB", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9, rule_b=0),
     # head widths of the paper's own models (Sec. 5.1: d = 768 / 1536 / 2048 with 8 / 16 heads, i.e. 96 and 128 per head;
-    # 4-8-12 and 4-10-18 blocks per level), scaled down in width and depth; fp32 storage (the half-precision kernels are
-    # built for a head width of 64)
+    # 4-8-12 and 4-10-18 blocks per level), scaled down in width and depth, in both storage types; the last two keep
+    # the paper's d = 768 with 8 heads, and 8 heads of 128, at a few blocks, with a condition memory of whole GEMM tiles
     "t_f32_hd96": Config("t_f32_hd96", 192, 2, 32, 1, 2, 1, 2, 2, 24, "f32", 2, 6, 2, 9, 9),
     "t_f32_hd128": Config("t_f32_hd128", 256, 2, 32, 2, 2, 3, 2, 3, 24, "f32", 1, 6, 2, 15, 18),
+    "t_bf16_hd96": Config("t_bf16_hd96", 192, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 2, 8, 2, 9, 9),
+    "t_bf16_hd128": Config("t_bf16_hd128", 256, 2, 32, 2, 2, 3, 2, 3, 40, "bf16", 1, 8, 2, 15, 18),
+    "t_bf16_d768_h8": Config("t_bf16_d768_h8", 768, 8, 128, 1, 1, 1, 1, 2, 256, "bf16", 2, 6, 2, 9, 9),
+    "t_bf16_d1024_h8": Config("t_bf16_d1024_h8", 1024, 8, 128, 1, 1, 1, 1, 1, 256, "bf16", 1, 5, 2, 15, 18),
     "t_bf16_99_b1_noA": Config("t_bf16_99_b1_noA", 128, 2, 32, 1, 2, 1, 2, 2, 40, "bf16", 1, 12, 2, 9, 9, rule_a=0),
     "t_bf16_1815": Config("t_bf16_1815", 192, 3, 64, 1, 2, 2, 2, 2, 72, "bf16", 2, 14, 2, 15, 18),
     # blocks longer than 16 tokens at one sequence (two row groups at the coordinate level of the single-launch verify kernel)

@@ -47,7 +47,6 @@ def test_config_struct_matches_header_layout():
     dict(d_model=100), dict(n_heads=3), dict(dtype=7), dict(max_batch=0), dict(max_batch=65), dict(max_tokens=10),
     dict(draft_point=4), dict(draft_face=12), dict(draft_coord=1), dict(draft_face=36), dict(l_face=0),
     dict(mem_len=0), dict(rope_base=1.0), dict(rms_eps=0.0), dict(window=-9), dict(window=10), dict(rules_off=4),
-    dict(d_model=192, dtype=1),      # head width 96 is fp32-only
     dict(d_model=160),               # head width 80
 ])
 def test_create_rejects_bad_config_without_touching_the_device(lib, bad):

@@ -23,7 +23,7 @@ def _need_gpu():
                                   "t_bf16_1815_b1", "t_bf16_2727_b1", "t_bf16_1815_b1_w72",
                                   "t_f32_99_noA", "t_bf16_1815_noA", "t_bf16_99_b1_noA",
                                   "t_f32_99_noB", "t_bf16_1815_noAB", "t_bf16_99_b1_noB",
-                                  "t_f32_hd96", "t_f32_hd128"])
+                                  "t_f32_hd96", "t_f32_hd128", "t_bf16_hd96", "t_bf16_hd128"])
 def test_lockstep_small_native_heads(name):
     _need_gpu()
     from parity_harness import lockstep
@@ -54,7 +54,7 @@ def test_lockstep_small_native_heads(name):
 
 
 @pytest.mark.parametrize("name", ["t_f32_99", "t_f32_1815", "t_bf16_99", "t_bf16_1815", "t_bf16_99_b1", "t_f32_2727", "t_bf16_c17",
-                                  "t_bf16_1815_noAB", "t_f32_hd96"])
+                                  "t_bf16_1815_noAB", "t_f32_hd96", "t_bf16_hd96"])
 def test_lockstep_with_correct_stage(name):
     """Predict - correct - verify (Sec. 3.2): labels from the label head, the integer correction of every draft block
     bit for bit, and a stream that the stage leaves untouched."""
@@ -143,6 +143,30 @@ def test_lockstep_everything_on(name):
     rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype], sampling=(0.9, 21), correct_hist=9)
     print(rep, flush=True)
     assert all(len(s) == 9 * cfg.faces for s in streams)
+
+
+@pytest.mark.parametrize("name", ["t_bf16_d768_h8", "t_bf16_d1024_h8"])
+def test_paper_head_widths_half_precision(name, say):
+    """Head widths 96 and 128 (the paper's own shapes, Sec. 5.1: d = 768 with 8 heads; 16 heads of 128 scaled to 8) on the
+    half-precision path: tiled prefill GEMM into the wide-head cache layouts, MFMA attention, draft heads - every step of
+    the generation in lock-step."""
+    _need_gpu()
+    from parity_harness import lockstep
+    import parity_harness
+    parity_harness.PROGRESS = say
+    cfg = si.TEST_CONFIGS[name]
+    print("case paper head width", name, flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL["bf16"])
+    parity_harness.PROGRESS = None
+    print(rep, flush=True)
+    assert all(len(s) == 9 * cfg.faces for s in streams)
+    assert fm.verify_path() == 0              # the single-launch kernel is written for 64-wide heads
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    out = fm.generate(cfg.faces, True)[0].cpu().numpy()
+    if rep.token_flips == 0:
+        for s in range(cfg.batch):
+            assert list(out[s, :9 * cfg.faces]) == streams[s]
 
 
 def test_config0_tiny_full_run():
