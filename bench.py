@@ -189,6 +189,10 @@ def main():
     ap.add_argument("--faces", type=int, default=0, help="override the face budget (0 = the configuration's)")
     ap.add_argument("--draft", default="", help="override the draft counts: Dc,m,n (coordinate heads, point tokens, face tokens)")
     ap.add_argument("--batch", type=int, default=0, help="override the number of sequences of the configuration")
+    ap.add_argument("--model", default="",
+                    help="override width and depth: d,H,c,v,f = d_model, heads, blocks at the coordinate / point / face level "
+                         "(c and v split evenly before and after the coarser level), e.g. 1536,16,4,8,12 for the paper's "
+                         "model with 96-wide heads; head widths other than 64 run one launch per operator")
     ap.add_argument("--window", type=int, default=0,
                     help="sliding-window self-attention: window in coordinate tokens (multiple of 9); with --faces beyond "
                          "the configuration's budget the stream runs past one window over ring K/V caches")
@@ -224,6 +228,10 @@ def main():
         cfg = cfg.replace(draft_coord=dc, draft_point=m, draft_face=n)
     if args.batch:
         cfg = cfg.replace(batch=args.batch)
+    if args.model:
+        dm, nh, lc, lv, lf = (int(v) for v in args.model.split(","))
+        cfg = cfg.replace(name=f"{cfg.name} with model {args.model}", d_model=dm, n_heads=nh, l_cpre=lc // 2, l_cpost=lc - lc // 2,
+                          l_vpre=lv // 2, l_vpost=lv - lv // 2, l_face=lf)
     faces = args.faces or cfg.faces
     if args.window:
         cfg = cfg.replace(window=args.window, faces=max(faces, cfg.faces))
@@ -260,7 +268,8 @@ def main():
     if args.counter_pass:
         # The K/V caches only need the right length for the byte counters, not a greedy stream: commit whole
         # blocks of arbitrary coordinate tokens (the caller owns the accepted lengths it hands to fm_commit).
-        reset()
+        for _ in range(4):                          # the prefill kernel several times: its counters are read off the last call
+            reset()
         forced_fill(fm, cfg, torch, 9 * (faces // 2))
         fm.set_budget(faces)
         tok, ln = fm.new_block()
@@ -452,7 +461,7 @@ def main():
                    "measured_on_this_gpu": measured, "batch8": batch8},
         "roofline": {"bound": "hbm", "kernel": kernel,
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": counter_traffic(args.config, persistent) if (faces == si.CONFIGS[args.config].faces and not args.window and not args.draft and not args.batch) else None,
+                     "traffic": counter_traffic(args.config, persistent) if (faces == si.CONFIGS[args.config].faces and not args.window and not args.draft and not args.batch and not args.model) else None,
                      "traffic_source": "committed counter profile profiles/k_verify_persist_config2_b1_hbm_counters.txt (two rocprofv3 --pmc runs of bench.py --counter-pass at half context), not a counter of this run",
                      "context_tokens": context_roofline, "algorithmic_bytes": bytes_mid, "ms": ms_verify,
                      "frac_of_measured_read_rate": achieved / measured["hbm_read_GBs"]},
