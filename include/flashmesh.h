@@ -217,6 +217,13 @@ int fm_debug_ring(fm_ctx* ctx, int32_t which, float* host_out);
  * Synchronises. */
 int fm_debug_draft(fm_ctx* ctx, int32_t which, float* host_out);
 
+/* Cross-attention keys and values of the condition memory as fm_prefill_condition left them (Sec. 3.1: K_mem = W_k c,
+ * V_mem = W_v c), for element-wise parity checks: HOST k_out and v_out, each [mem_len][d_model] float32 in plain row-major
+ * order (the library undoes its blocked cache layouts), for sequence `seq` and transformer block `block`, blocks counted
+ * through the stacks in the order coordinate-pre, point-pre, face, point-post, coordinate-post.  Synchronises.
+ * FM_EINVAL for an index out of range, FM_ESTATE if the sequence has not been prefilled. */
+int fm_debug_mem_kv(fm_ctx* ctx, int32_t seq, int32_t block, float* host_k, float* host_v);
+
 /* What this GPU sustains, for reporting next to the published peaks: HOST out[0] = streaming read GB/s, out[1] =
  * streaming copy GB/s (read + write bytes), out[2] = register-only MFMA loop TFLOP/s (fp16, 32x32x16).  Allocates
  * and frees 2 GiB of device memory for the duration of the call.  Synchronises. */

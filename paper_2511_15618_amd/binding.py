@@ -11,7 +11,7 @@ LIB_PATH = os.path.join(HERE, "libflashmesh.so")
 
 EXPORTS = ["fm_create", "fm_destroy", "fm_last_error", "fm_block_max", "fm_blob_elems", "fm_load_weights",
            "fm_prefill_condition", "fm_prefill_condition_static", "fm_draft", "fm_verify_block", "fm_commit", "fm_generate", "fm_read_state",
-           "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile", "fm_debug_draft",
+           "fm_set_draft_replay", "fm_set_budget", "fm_set_correct", "fm_correct", "fm_set_sampling", "fm_verify_bytes", "fm_debug_ring", "fm_debug_profile", "fm_debug_draft", "fm_debug_mem_kv",
            "fm_verify_path", "fm_measure_peaks", "fm_measure_gemm", "fm_measure_exchange"]
 
 
@@ -79,6 +79,7 @@ def load_library():
     lib.fm_verify_bytes.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_debug_ring.argtypes = [p, i32, p]
     lib.fm_debug_draft.argtypes = [p, i32, p]
+    lib.fm_debug_mem_kv.argtypes = [p, i32, i32, p, p]
     lib.fm_debug_profile.argtypes = [p, p, i32]
     lib.fm_measure_peaks.argtypes = [p, C.POINTER(C.c_double)]
     lib.fm_measure_gemm.argtypes = [p, i32, C.POINTER(C.c_double)]
@@ -229,6 +230,12 @@ class FlashMesh:
         out = np.zeros(shape, np.float32)
         self._chk(self.lib.fm_debug_draft(self.h, which, C.c_void_p(out.ctypes.data)), "fm_debug_draft")
         return out
+
+    def debug_mem_kv(self, seq: int, block: int):
+        k = np.zeros((self.cfgs.mem_len, self.cfgs.d_model), np.float32)
+        v = np.zeros_like(k)
+        self._chk(self.lib.fm_debug_mem_kv(self.h, seq, block, C.c_void_p(k.ctypes.data), C.c_void_p(v.ctypes.data)), "fm_debug_mem_kv")
+        return k, v
 
     def debug_profile(self, n: int = 1024) -> np.ndarray:
         out = np.zeros(n, np.uint64)

@@ -1146,6 +1146,44 @@ int fm_debug_ring(fm_ctx* c, int32_t which, float* host_out) {
   return FM_OK;
 }
 
+int fm_debug_mem_kv(fm_ctx* c, int32_t seq, int32_t block, float* host_k, float* host_v) {
+  if (!c || !host_k || !host_v) return FM_EINVAL;
+  if (seq < 0 || seq >= c->D.S) return fail(c, FM_EINVAL, "sequence %d out of range", seq);
+  if (!c->prefilled[seq]) return fail(c, FM_ESTATE, "sequence %d has no condition memory", seq);
+  const Layer* L = nullptr;
+  int left = block;
+  for (int st = 0; st < 5 && !L && left >= 0; st++) {
+    if (left < (int)c->stacks[st].size()) L = &c->stacks[st][left];
+    else left -= (int)c->stacks[st].size();
+  }
+  if (block < 0 || !L) return fail(c, FM_EINVAL, "block %d out of range", block);
+  const Dims& D = c->D;
+  const size_t n = cache_seq_elems(c, D.M);
+  std::vector<unsigned char> raw(n * c->esz);
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  for (int kv = 0; kv < 2; kv++) {
+    const unsigned char* src = (const unsigned char*)(kv ? L->Vm : L->Km) + (size_t)seq * n * c->esz;
+    HIPCHK(c, hipMemcpy(raw.data(), src, raw.size(), hipMemcpyDeviceToHost));
+    float* out = kv ? host_v : host_k;
+    const int hd = D.hd, capb = (D.M + 31) / 32;
+    for (int m = 0; m < D.M; m++)
+      for (int i = 0; i < D.d; i++) {
+        const int hh = i / hd, e = i % hd;
+        if (c->bf16) {
+          // the blocked layouts of the half path: 32-key blocks of a head; K in MFMA fragment order, V as [dim][key slot]
+          const int r = m & 31;
+          size_t o = ((size_t)hh * capb + (m >> 5)) * 32 * hd;
+          if (kv == 0) o += (size_t)((((r >> 4) * (hd / 32) + (e >> 5)) * 64 + (r & 15) + 16 * ((e & 31) >> 3)) * 8 + (e & 7));
+          else o += (size_t)e * 32 + ((r & 15) >> 2) * 8 + (r >> 4) * 4 + (r & 3);
+          out[(size_t)m * D.d + i] = (float)((const f16_t*)raw.data())[o];
+        } else {
+          out[(size_t)m * D.d + i] = ((const float*)raw.data())[((size_t)hh * D.M + m) * hd + e];
+        }
+      }
+  }
+  return FM_OK;
+}
+
 int fm_verify_bytes(fm_ctx* c, double* host_bytes) {
   if (!c || !host_bytes) return FM_EINVAL;
   const int S = c->D.S;

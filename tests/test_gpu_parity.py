@@ -206,3 +206,45 @@ def test_config4_shape_short_lockstep(say):
     parity_harness.PROGRESS = None
     print(rep, flush=True)
     assert rep.steps == 4 and len(rep.accepted) == 4 * cfg.batch
+
+
+@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99", "t_bf16_hd96", "t_bf16_d768_h8", "t_bf16_d1024_h8", "config1"])
+def test_condition_kv_element_by_element(name):
+    """fm_prefill_condition against the definition K_mem = W_k c, V_mem = W_v c (Sec. 3.1), every element of every block:
+    the per-block launches (small memories), the tiled matrix-unit kernel (memories of whole 256-row tiles) in all three
+    head widths, and the fp32 path.  Tolerance from the arithmetic: the memory is rounded to half once (2^-11 relative per
+    element, the weights are exact), products are summed in fp32, and the result is rounded to half once more."""
+    _need_gpu()
+    from oracle.hourglass import Model
+    from paper_2511_15618_amd import FlashMesh
+    from paper_2511_15618_amd.binding import config_struct
+    cfg = si.CONFIGS[1].replace(faces=10) if name == "config1" else si.TEST_CONFIGS[name]
+    print("case condition K/V", name, flush=True)
+    w = si.make_weights(cfg, 0)
+    model = Model(cfg, w)
+    fm = FlashMesh(config_struct(cfg))
+    fm.load_weights(si.pack_blob(cfg, w))
+    half = cfg.dtype == "bf16"
+    u_in, u_acc = (2.0 ** -11, 2.0 ** -24) if half else (0.0, 2.0 ** -24)
+    worst = 0.0
+    for s in range(cfg.batch):
+        mem = si.make_memory(cfg, s)
+        fm.prefill_condition(s, torch.from_numpy(mem).cuda())
+        b = 0
+        for st in ("cpre", "vpre", "face", "vpost", "cpost"):
+            for i in range(model.layers[st]):
+                pfx = f"{st}.{i}."
+                K, V = model.mem_kv(pfx, mem)                      # [M, H, hd] float64
+                dk, dv = fm.debug_mem_kv(s, b)
+                for ref, dev, wn in ((K, dk, "ck"), (V, dv, "cv")):
+                    ref = ref.reshape(cfg.mem_len, cfg.d_model)
+                    mag = np.abs(np.asarray(mem, np.float64)) @ np.abs(model.w[pfx + wn]).T      # sum of |w_k c_k| per element
+                    bound = 1.05 * ((u_in + (cfg.d_model + 2) * u_acc) * mag + (u_in if half else u_acc) * np.abs(ref)) + 1e-30
+                    err = np.abs(dev.astype(np.float64) - ref)
+                    worst = max(worst, float((err / bound).max()))
+                    assert (err <= bound).all(), (name, s, pfx, wn, float(err.max()), float((err / bound).max()))
+                b += 1
+    print(f"condition K/V {name}: worst error / bound = {worst:.3f}", flush=True)
+    assert 0.0 < worst <= 1.0
+    with pytest.raises(RuntimeError):
+        fm.debug_mem_kv(0, b)
