@@ -812,8 +812,9 @@ int build_buffers(fm_ctx* c) {
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
-  c->mres = MfmaRes{nullptr, nullptr, 0, 0};
+  c->mres = MfmaRes{nullptr, nullptr, 0, 0, 0};
   if (const char* e = getenv("FM_GEMM_WAVES")) c->mres.gemm_waves = atoi(e);   // measurement switch: 4, 8 or 16
+  if (const char* e = getenv("FM_GEMM_MT_CAP")) c->mres.gemm_mt_cap = atoi(e); // measurement switch: up to 2, 3, 5 or 8 row tiles per workgroup
   if (c->bf16) {
     c->mres.attn_ws_floats = mfma_attn_ws_floats(std::max(D.S, 3), D.H, D.hd);       // 3: the merged SP launch has three row sets
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));

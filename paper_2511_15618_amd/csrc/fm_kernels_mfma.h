@@ -322,6 +322,7 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
   unsigned* attn_counters;
   size_t attn_ws_floats;
   int gemm_waves;     // 0 = choose per launch; 4, 8, 16 = forced (measurement switch)
+  int gemm_mt_cap;    // 0 = default (below); 2, 3, 5, 8 = one workgroup covers up to that many 16-row tiles (measurement switch)
 };
 
 template <int MT, bool NORM, int NW>
@@ -354,7 +355,16 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   if (a.K % 32 != 0 || a.M < 1) return false;
   const int KT = a.K / 32, Npad = (a.N + 15) / 16 * 16, NT = Npad / 16;
   const int mtiles = (a.M + 15) / 16;
-  const int MT = mtiles <= 1 ? 1 : mtiles <= 2 ? 2 : mtiles <= 3 ? 3 : mtiles <= 5 ? 5 : 8;
+  // Row tiles per workgroup.  Up to 128 rows (every launch of a decode step) a workgroup takes one 16-row tile and the
+  // row tiles of a column tile go to different workgroups: the weight tile is then fetched once from HBM and again from
+  // L2, but each workgroup reads a fifth of the activations at 72 rows and five times as many workgroups pull on the
+  // weights (measured: -5 % per verify pass on 8 sequences at d = 1024, -7 % on 4 sequences at d = 1536).  Taller
+  // problems (the per-block prefill GEMM) keep 128 rows per workgroup.
+  int MT = mtiles <= 8 ? 1 : 8;
+  if (res.gemm_mt_cap > 1) {
+    MT = mtiles <= 1 ? 1 : mtiles <= 2 ? 2 : mtiles <= 3 ? 3 : mtiles <= 5 ? 5 : 8;
+    if (MT > res.gemm_mt_cap) MT = res.gemm_mt_cap >= 8 ? 8 : res.gemm_mt_cap >= 5 ? 5 : res.gemm_mt_cap;
+  }
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
   // waves per workgroup: enough for about 2048 waves in the launch, at least two K fragments per wave, and the
   // partial tiles of all waves within the static LDS limit
