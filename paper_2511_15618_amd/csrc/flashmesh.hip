@@ -322,7 +322,7 @@ template <typename T>
 int verify_impl(fm_ctx* c, const int32_t* block_tok, const int32_t* block_len, float* logits_out, int32_t* accepted) {
   const Dims& D = c->D;
   const int d = D.d;
-  hipLaunchKernelGGL(k_verify_setup, dim3(1), dim3(256), 0, c->stream, c->st, D, c->inv, block_tok, block_len,
+  hipLaunchKernelGGL(k_verify_setup, dim3(std::min(16, (D.S * D.Bm * (D.hd / 2) + 255) / 256)), dim3(256), 0, c->stream, c->st, D, c->inv, block_tok, block_len,
                      c->pos[0], c->pos[1], c->pos[2], c->limx[0], c->limx[1], c->limx[2], c->cs[0], c->cs[1], c->cs[2]);
   if (c->persist) {
     // the whole backbone forward in one launch (see fm_kernels_persist.h), then greedy choice and acceptance
@@ -451,7 +451,7 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
   const Dims& D = c->D;
   const int d = D.d;
   if (speculative) {
-    hipLaunchKernelGGL(k_draft_setup, dim3(1), dim3(256), 0, c->stream, c->st, D, c->inv, c->dr, c->db);
+    hipLaunchKernelGGL(k_draft_setup, dim3(D.S), dim3(256), 0, c->stream, c->st, D, c->inv, c->dr, c->db);
     const int *f_alive = c->dr.flags, *f_v = c->dr.flags + 1, *f_f = c->dr.flags + 2;
     const Layer& lastc = c->stacks[4].back();
     const Layer& lastv = c->stacks[3].back();

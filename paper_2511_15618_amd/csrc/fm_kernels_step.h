@@ -42,52 +42,62 @@ __device__ __forceinline__ int eff_block_len(const StateDev& st, const Dims& D, 
   return max(len, 0);
 }
 
+// (any number of workgroups: every entry is computed from the committed state alone)
 __global__ __launch_bounds__(256) void k_verify_setup(StateDev st, Dims D, InvFreq inv, const int* __restrict__ block_tok,
                                                        const int* __restrict__ block_len, int* pos_c, int* pos_v, int* pos_f,
                                                        int* limx_c, int* limx_v, int* limx_f, float2* cs_c, float2* cs_v,
                                                        float2* cs_f) {
-  const int tid = threadIdx.x;
-  for (int idx = tid; idx < D.S * D.Bm; idx += 256) {
+  const int tid = blockIdx.x * 256 + threadIdx.x, nth = gridDim.x * 256;
+  // position of row idx of a level, -1 for a row the block does not reach
+  auto row_c = [&](int idx) {
     const int s = idx / D.Bm, i = idx % D.Bm;
-    const int len = eff_block_len(st, D, s, block_len);
-    const bool on = i < len;
-    pos_c[idx] = on ? st.P[s] + i : -1;
-    limx_c[idx] = on ? D.M - 1 : -1;
-    int t = on ? block_tok[idx] : D.pad;
-    if (t < 0 || t >= D.V) t = D.pad;
-    st.vtok[idx] = t;
-    if (i == 0) st.vlen[s] = len;
-  }
-  for (int idx = tid; idx < D.S * D.VB; idx += 256) {
+    return i < eff_block_len(st, D, s, block_len) ? st.P[s] + i : -1;
+  };
+  auto row_v = [&](int idx) {
     const int s = idx / D.VB, k = idx % D.VB;
     const int len = eff_block_len(st, D, s, block_len), P = st.P[s];
     const int j = (P + 2) / 3 + k;
-    const bool on = 3 * j < P + len;
-    pos_v[idx] = on ? j : -1;
-    limx_v[idx] = on ? D.M - 1 : -1;
-  }
-  for (int idx = tid; idx < D.S * D.FB; idx += 256) {
+    return 3 * j < P + len ? j : -1;
+  };
+  auto row_f = [&](int idx) {
     const int s = idx / D.FB, k = idx % D.FB;
     const int len = eff_block_len(st, D, s, block_len), P = st.P[s];
     const int f = (P + 8) / 9 + k;
-    const bool on = 9 * f < P + len;
-    pos_f[idx] = on ? f : -1;
-    limx_f[idx] = on ? D.M - 1 : -1;
+    return 9 * f < P + len ? f : -1;
+  };
+  for (int idx = tid; idx < D.S * D.Bm; idx += nth) {
+    const int s = idx / D.Bm, i = idx % D.Bm;
+    const int p = row_c(idx);
+    pos_c[idx] = p;
+    limx_c[idx] = p >= 0 ? D.M - 1 : -1;
+    int t = p >= 0 ? block_tok[idx] : D.pad;
+    if (t < 0 || t >= D.V) t = D.pad;
+    st.vtok[idx] = t;
+    if (i == 0) st.vlen[s] = eff_block_len(st, D, s, block_len);
   }
-  __syncthreads();
+  for (int idx = tid; idx < D.S * D.VB; idx += nth) {
+    const int p = row_v(idx);
+    pos_v[idx] = p;
+    limx_v[idx] = p >= 0 ? D.M - 1 : -1;
+  }
+  for (int idx = tid; idx < D.S * D.FB; idx += nth) {
+    const int p = row_f(idx);
+    pos_f[idx] = p;
+    limx_f[idx] = p >= 0 ? D.M - 1 : -1;
+  }
   const int np = D.hd >> 1;      // rotary pairs per head
-  for (int idx = tid; idx < D.S * D.Bm * np; idx += 256) {
-    const int p = pos_c[idx / np];
+  for (int idx = tid; idx < D.S * D.Bm * np; idx += nth) {
+    const int p = row_c(idx / np);
     const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx % np];
     cs_c[idx] = make_float2((float)cos(a), (float)sin(a));
   }
-  for (int idx = tid; idx < D.S * D.VB * np; idx += 256) {
-    const int p = pos_v[idx / np];
+  for (int idx = tid; idx < D.S * D.VB * np; idx += nth) {
+    const int p = row_v(idx / np);
     const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx % np];
     cs_v[idx] = make_float2((float)cos(a), (float)sin(a));
   }
-  for (int idx = tid; idx < D.S * D.FB * np; idx += 256) {
-    const int p = pos_f[idx / np];
+  for (int idx = tid; idx < D.S * D.FB * np; idx += nth) {
+    const int p = row_f(idx / np);
     const double a = (p < 0 ? 0.0 : (double)p) * inv.v[idx % np];
     cs_f[idx] = make_float2((float)cos(a), (float)sin(a));
   }
@@ -272,26 +282,40 @@ __device__ __forceinline__ void set_row(const DraftRows& R, int set, int r, cons
   }
 }
 
-// one workgroup, 32 threads per row at a time
+// One workgroup per sequence, 32 threads per row at a time.  The three launch flags (any sequence alive / firing at the
+// point level / at the face level) depend on the committed state only, so every workgroup could derive them; workgroup 0
+// does, for all sequences, and writes them.
 __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFreq inv, DraftRows R, DraftBufs B) {
   const int lane32 = threadIdx.x & 31, grp = threadIdx.x >> 5;  // 8 groups of 32
-  __shared__ int f_any[3];
-  if (threadIdx.x < 3) f_any[threadIdx.x] = 0;
-  __syncthreads();
   const int d = D.d;
-  for (int s = 0; s < D.S; s++) {
+  auto predicates = [&](int s, bool& alive, bool& firev, bool& firef, int& spos, int& v, int& f) {
     const int P = st.P[s];
-    const bool alive = !st.fin[s] && P > 0;
-    const int spos = P - 1;
-    const int v = alive ? spos / 3 : 0, f = alive ? spos / 9 : 0;
-    const bool firev = alive && D.m > 0 && ((v % 3) != 0 || !D.ruleA) && st.firedv[s] != v;
-    const bool firef = alive && D.n > 0 && st.firedf[s] != f;
-    if (threadIdx.x == 0) {
-      R.alive[s] = alive; R.firev[s] = firev; R.firef[s] = firef;
-      if (alive) f_any[0] = 1;
-      if (firev) f_any[1] = 1;
-      if (firef) f_any[2] = 1;
+    alive = !st.fin[s] && P > 0;
+    spos = P - 1;
+    v = alive ? spos / 3 : 0;
+    f = alive ? spos / 9 : 0;
+    firev = alive && D.m > 0 && ((v % 3) != 0 || !D.ruleA) && st.firedv[s] != v;
+    firef = alive && D.n > 0 && st.firedf[s] != f;
+  };
+  if (blockIdx.x == 0) {
+    __shared__ int f_any[3];
+    if (threadIdx.x < 3) f_any[threadIdx.x] = 0;
+    __syncthreads();
+    for (int s = threadIdx.x; s < D.S; s += blockDim.x) {
+      bool alive, firev, firef; int spos, v, f;
+      predicates(s, alive, firev, firef, spos, v, f);
+      if (alive) atomicOr(&f_any[0], 1);
+      if (firev) atomicOr(&f_any[1], 1);
+      if (firef) atomicOr(&f_any[2], 1);
     }
+    __syncthreads();
+    if (threadIdx.x < 3) R.flags[threadIdx.x] = f_any[threadIdx.x];
+  }
+  {
+    const int s = blockIdx.x;
+    bool alive, firev, firef; int spos, v, f;
+    predicates(s, alive, firev, firef, spos, v, f);
+    if (threadIdx.x == 0) { R.alive[s] = alive; R.firev[s] = firev; R.firef[s] = firef; }
     const float* tapc = B.tap_c + ((long)s * 32 + (spos & 31)) * d;
     const float* tapv = B.tap_v + ((long)s * 16 + (v & 15)) * d;
     const float* tapf = B.tap_f + ((long)s * 8 + (f & 7)) * d;
@@ -324,8 +348,6 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
       }
     }
   }
-  __syncthreads();
-  if (threadIdx.x < 3) R.flags[threadIdx.x] = f_any[threadIdx.x];
 }
 
 // softmax of one LM row of the draft heads into the distribution store of its level
