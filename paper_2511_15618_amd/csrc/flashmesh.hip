@@ -84,7 +84,8 @@ struct fm_ctx {
   float* gf;
   SpLevel sp[3];
   SpLevel sp_all;          // the heads of all three levels as one group list, in memory order point, face, coordinate
-  bool sp_merged = false;  // one sequence, half path: the three SP chains run as one chain of grouped launches
+  bool sp_merged = false;  // half path, 64-wide heads: the three SP chains run as one chain of grouped launches
+  const float** lm_src = nullptr;   // rows of the output head's input: coordinate SP head outputs, then coordinate HF outputs
   HfLevel hfc, hfv;
   float* label_w;     // label head of the correct stage [3][d]
   float *lab_v, *lab_f;   // label distributions of the point pipeline [S][nspv][3] and the face pipeline [S][nhfv][3]
@@ -387,43 +388,45 @@ void run_sp(fm_ctx* c, int set, const SpLevel& sp, const Layer& last, int level,
   gemm<T>(c, EPI_F32, c->dxn, (long)G * d, d, sp.lin, dd, out, ldo, gso, c->dkeep, (long)G * d, d, D.S, d, d, G, flag);
 }
 
-// The SP chains (Eq. 1) of all three levels of one sequence as one chain of grouped launches (half path): the row set is
-// the point-, face- and coordinate-level rows behind each other, every GEMM is grouped over all heads, and the two
-// attention launches take one cache per level.  Same arithmetic per row as run_sp.  Rows of a level that does not fire
-// in this step carry limit -1 (no keys) and produce values nobody reads.
+// The SP chains (Eq. 1) of all three levels as one chain of grouped launches (half path): the row set is, per sequence,
+// the point-, face- and coordinate-level rows behind each other, every GEMM is grouped over all heads (S rows per head),
+// and the two attention launches take one cache per level.  Same arithmetic per row as run_sp.  Rows of a level that
+// does not fire in this step carry limit -1 (no keys) and produce values nobody reads.
 void run_sp_all(fm_ctx* c, const int* flag) {
   typedef f16_t T;
   const Dims& D = c->D;
   const SpLevel& A = c->sp_all;
-  const int d = D.d, G = A.cnt;
+  const int d = D.d, G = A.cnt, S = D.S, rows = S * G;
   if (G == 0) return;
   const long dd = (long)d * d, ld = (long)G * d;
   const int nrow[3] = {D.nspv, D.nspf, D.Dc}, lev[3] = {1, 2, 0}, set[3] = {1, 2, 0};
   const Layer* last[3] = {&c->stacks[3].back(), &c->stacks[2].back(), &c->stacks[4].back()};
-  rmsnorm<T>(c, nullptr, c->dr.src[1], A.g, G, c->dxn, c->dkeep, G, flag);
-  gemm<T>(c, EPI_F32, c->dxn, ld, d, A.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
-  rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[1], c->dr.pos[1], G, G, c->dq, nullptr, nullptr, 32, flag);
+  rmsnorm<T>(c, nullptr, c->dr.src[1], A.g, G, c->dxn, c->dkeep, rows, flag);
+  gemm<T>(c, EPI_F32, c->dxn, ld, d, A.wq, dd, c->dtmp, ld, d, nullptr, 0, 0, S, d, d, G, flag);
+  rope_append<T>(c, c->dtmp, (long)d, c->dr.cs[1], c->dr.pos[1], rows, G, c->dq, nullptr, nullptr, 32, flag);
   AttnLevelHost lv[3];
   long off = 0;
   for (int z = 0; z < 3; z++) {
     const int cap = level_cap(c, lev[z]);
-    lv[z] = AttnLevelHost{(const f16_t*)c->dq + off * d, c->dr.lim[set[z]], nrow[z], last[z]->Kc, last[z]->Vc, cap,
-                          (f16_t*)c->datt + off * d, false, level_key_bound(c, lev[z]), level_window(c, lev[z])};
+    lv[z] = AttnLevelHost{(const f16_t*)c->dq + off * d, c->dr.lim[set[z]], nrow[z], last[z]->Kc, last[z]->Vc,
+                          (long)cache_seq_elems(c, cap), cap, (f16_t*)c->datt + off * d, false, level_key_bound(c, lev[z]),
+                          level_window(c, lev[z])};
     off += nrow[z];
   }
-  if (!mfma_attn_launch_levels(c->mres, lv, D.H, flag, c->stream)) { fail(c, FM_EINVAL, "merged SP attention: unsupported row sets"); c->sticky_error = true; return; }
-  gemm<T>(c, EPI_T, c->datt, ld, d, A.wo, dd, c->dxn, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
-  gemm<T>(c, EPI_T, c->dxn, ld, d, A.cq, dd, c->dq, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
+  if (!mfma_attn_launch_levels(c->mres, lv, S, G, D.H, flag, c->stream)) { fail(c, FM_EINVAL, "merged SP attention: unsupported row sets"); c->sticky_error = true; return; }
+  gemm<T>(c, EPI_T, c->datt, ld, d, A.wo, dd, c->dxn, ld, d, nullptr, 0, 0, S, d, d, G, flag);
+  gemm<T>(c, EPI_T, c->dxn, ld, d, A.cq, dd, c->dq, ld, d, nullptr, 0, 0, S, d, d, G, flag);
   off = 0;
   for (int z = 0; z < 3; z++) {
-    lv[z] = AttnLevelHost{(const f16_t*)c->dq + off * d, c->dr.limx[set[z]], nrow[z], last[z]->Km, last[z]->Vm, D.M,
-                          (f16_t*)c->datt + off * d, true, 1 << 30, 0};
+    lv[z] = AttnLevelHost{(const f16_t*)c->dq + off * d, c->dr.limx[set[z]], nrow[z], last[z]->Km, last[z]->Vm,
+                          (long)cache_seq_elems(c, D.M), D.M, (f16_t*)c->datt + off * d, true, 1 << 30, 0};
     off += nrow[z];
   }
-  if (!mfma_attn_launch_levels(c->mres, lv, D.H, flag, c->stream)) { fail(c, FM_EINVAL, "merged SP cross-attention: unsupported row sets"); c->sticky_error = true; return; }
-  gemm<T>(c, EPI_T, c->datt, ld, d, A.co, dd, c->dxn, ld, d, nullptr, 0, 0, 1, d, d, G, flag);
-  // outputs: point, face, coordinate rows behind each other = spv_out, spf_out, first rows of the output head's input
-  gemm<T>(c, EPI_F32, c->dxn, ld, d, A.lin, dd, c->spv_out, ld, d, c->dkeep, ld, d, 1, d, d, G, flag);
+  if (!mfma_attn_launch_levels(c->mres, lv, S, G, D.H, flag, c->stream)) { fail(c, FM_EINVAL, "merged SP cross-attention: unsupported row sets"); c->sticky_error = true; return; }
+  gemm<T>(c, EPI_T, c->datt, ld, d, A.co, dd, c->dxn, ld, d, nullptr, 0, 0, S, d, d, G, flag);
+  // outputs: per sequence the point, face and coordinate rows behind each other (spv_out, spf_out and the rows the output
+  // head's pointer table names)
+  gemm<T>(c, EPI_F32, c->dxn, ld, d, A.lin, dd, c->spv_out, ld, d, c->dkeep, ld, d, S, d, d, G, flag);
 }
 
 // HF block chain (Eq. 3-6) for row set `set`: `per_seq` rows per sequence, `G` parameter sets, `mult`
@@ -469,11 +472,11 @@ int draft_impl(fm_ctx* c, int32_t* block_tok, int32_t* block_len, int speculativ
     }
     run_hf<T>(c, 3, c->hfv, 1, lastv, 1, c->hfv_out, f_f);
     if (c->correct_hist > 0 && D.nspv + D.nhfv > 0)     // label rows of the point-level features (Sec. 3.2)
-      hipLaunchKernelGGL(k_label_rows, dim3(D.S * (D.nspv + D.nhfv)), dim3(64), 0, c->stream, D, c->dr, c->spv_out, c->hfv_out,
+      hipLaunchKernelGGL(k_label_rows, dim3(D.S * (D.nspv + D.nhfv)), dim3(64), 0, c->stream, D, c->dr, c->spv_out, c->db.spv_rs, c->hfv_out,
                          c->label_w, c->lab_v, c->lab_f);
     run_hf<T>(c, 4, c->hfc, 2, lastc, 0, c->dh + (long)D.S * D.Dc * d, f_alive);
     if (nLM > 0) {
-      rmsnorm<T>(c, c->dh, nullptr, c->gf, 0, c->dxn, nullptr, nLM, f_alive);
+      rmsnorm<T>(c, nullptr, c->lm_src, c->gf, 0, c->dxn, nullptr, nLM, f_alive);
       gemm<T>(c, EPI_F32, c->dxn, d, 0, c->lm, 0, c->dlogits, D.V, 0, nullptr, 0, 0, nLM, D.V, d, 1, f_alive);
       hipLaunchKernelGGL(k_dist_store, dim3(nLM), dim3(256), 0, c->stream, c->dlogits, D, c->dr, c->dist_c, c->dist_v,
                          c->dist_f);
@@ -778,26 +781,53 @@ int build_buffers(fm_ctx* c) {
     TRY(dalloc(c, &c->dr.lim[i], nset[i])); TRY(dalloc(c, &c->dr.limx[i], nset[i]));
     TRY(dalloc(c, &c->dr.cs[i], nset[i] * 64));
   }
+  const char* spm = getenv("FM_SP_MERGED");      // "0": one chain of launches per level
+  c->sp_merged = c->bf16 && D.hd == 64 && D.Dc <= 16 && D.nspv <= 16 && D.nspf <= 16 && !(spm && spm[0] == '0');
+  const int G_all = D.Dc + D.nspv + D.nspf;
   {
-    // the tables of the three SP row sets lie behind each other (point, face, coordinate), as the heads do
+    // One table for the three SP row sets.  Merged chain: rows [sequence][point heads | face heads | coordinate heads],
+    // as the heads lie in memory, so that a grouped launch over all heads sees S rows per head with one stride.
+    // Otherwise the three sets behind each other, each [sequence][head].
     const size_t nsp = nset[0] + nset[1] + nset[2], np = (size_t)D.hd / 2;
     maxset = std::max(maxset, nsp);
     const float** src; int *pos, *lim, *limx; float2* cs;
     TRY(dalloc(c, (const float***)&src, nsp)); TRY(dalloc(c, &pos, nsp)); TRY(dalloc(c, &lim, nsp)); TRY(dalloc(c, &limx, nsp));
     TRY(dalloc(c, &cs, nsp * 64));
-    const size_t first[3] = {nset[1] + nset[2], 0, nset[1]};
+    const size_t first_m[3] = {(size_t)D.nspv + D.nspf, 0, (size_t)D.nspv}, first_s[3] = {nset[1] + nset[2], 0, nset[1]};
+    const int cnt[5] = {D.Dc, D.nspv, D.nspf, D.nhfv, 2 * D.nhfc};
+    for (int i = 0; i < 5; i++) c->dr.rs[i] = cnt[i];
     for (int i = 0; i < 3; i++) {
-      c->dr.src[i] = src + first[i]; c->dr.pos[i] = pos + first[i]; c->dr.lim[i] = lim + first[i];
-      c->dr.limx[i] = limx + first[i]; c->dr.cs[i] = cs + first[i] * np;
+      const size_t first = c->sp_merged ? first_m[i] : first_s[i];
+      if (c->sp_merged) c->dr.rs[i] = G_all;
+      c->dr.src[i] = src + first; c->dr.pos[i] = pos + first; c->dr.lim[i] = lim + first;
+      c->dr.limx[i] = limx + first; c->dr.cs[i] = cs + first * np;
     }
   }
   TRY(dalloc(c, &c->dr.alive, S)); TRY(dalloc(c, &c->dr.firev, S)); TRY(dalloc(c, &c->dr.firef, S)); TRY(dalloc(c, &c->dr.flags, 4));
   TRY(dalloc(c, &c->hfv_out, nset[3] * d));
   const size_t nLM = S * (D.Dc + 2 * D.nhfc);
-  // outputs of the SP heads: point, face, then the rows of the output head (coordinate SP heads first, HF rows behind)
-  TRY(dalloc(c, &c->spv_out, (nset[1] + nset[2] + nLM) * d));
-  c->spf_out = c->spv_out + nset[1] * d;
-  c->dh = c->spf_out + nset[2] * d;
+  // Outputs of the SP heads.  Merged chain: one buffer [sequence][point | face | coordinate heads][d]; otherwise one
+  // buffer per level, the coordinate level's being the first rows of the output head's input.  The output head reads its
+  // rows (coordinate SP heads of every sequence, then the coordinate HF rows) through a pointer table either way.
+  TRY(dalloc(c, &c->dh, nLM * d));
+  int spv_rs = std::max(D.nspv, 1), spf_rs = D.nspf;
+  if (c->sp_merged) {
+    TRY(dalloc(c, &c->spv_out, (size_t)S * std::max(G_all, 1) * d));
+    c->spf_out = c->spv_out + (size_t)D.nspv * d;
+    spv_rs = spf_rs = G_all;
+  } else {
+    TRY(dalloc(c, &c->spv_out, nset[1] * d));
+    TRY(dalloc(c, &c->spf_out, nset[2] * d));
+  }
+  {
+    std::vector<const float*> tab(std::max<size_t>(nLM, 1));
+    for (size_t i = 0; i < nLM; i++) {
+      if (c->sp_merged && i < S * (size_t)D.Dc) tab[i] = c->spv_out + ((i / D.Dc) * G_all + D.nspv + D.nspf + i % D.Dc) * d;
+      else tab[i] = c->dh + i * d;
+    }
+    TRY(dalloc(c, (const float***)&c->lm_src, tab.size()));
+    HIPCHK(c, hipMemcpy(c->lm_src, tab.data(), tab.size() * sizeof(float*), hipMemcpyHostToDevice));
+  }
   TRY(dalloc(c, &c->dlogits, nLM * D.V));
   const size_t rmax = std::max(maxset, nLM);
   TRY(dalloc(c, &c->dkeep, rmax * d)); TRY(dalloc(c, &c->dtmp, rmax * d));
@@ -809,18 +839,17 @@ int build_buffers(fm_ctx* c) {
   c->smp = Sampling{0.f, 0ull, nullptr, nullptr, nullptr, nullptr, 0};
   TRY(dalloc(c, &c->smp.qrow, S * D.Bm * D.V)); TRY(dalloc(c, &c->smp.qsum, S * D.Bm));
   TRY(dalloc(c, &c->smp.qtok, S * D.Bm)); TRY(dalloc(c, &c->smp.accflag, S * D.Bm));
-  c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out};
+  c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out, spv_rs, spf_rs};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
   c->mres = MfmaRes{nullptr, nullptr, 0, 0, 0};
   if (const char* e = getenv("FM_GEMM_WAVES")) c->mres.gemm_waves = atoi(e);   // measurement switch: 4, 8 or 16
   if (const char* e = getenv("FM_GEMM_MT_CAP")) c->mres.gemm_mt_cap = atoi(e); // measurement switch: up to 2, 3, 5 or 8 row tiles per workgroup
   if (c->bf16) {
-    c->mres.attn_ws_floats = mfma_attn_ws_floats(std::max(D.S, 3), D.H, D.hd);       // 3: the merged SP launch has three row sets
+    c->mres.attn_ws_floats = mfma_attn_ws_floats(3 * D.S, D.H, D.hd);       // 3: the merged SP launch has three row sets per sequence
     TRY(dalloc(c, &c->mres.attn_ws, c->mres.attn_ws_floats, false));
-    TRY(dalloc(c, &c->mres.attn_counters, (size_t)std::max(D.S, 3) * D.H));
-    const char* spm = getenv("FM_SP_MERGED");      // "0": one chain of launches per level, as with several sequences
-    c->sp_merged = D.hd == 64 && D.S == 1 && D.Dc <= 16 && D.nspv <= 16 && D.nspf <= 16 && !(spm && spm[0] == '0');
+    TRY(dalloc(c, &c->mres.attn_counters, (size_t)3 * D.S * D.H));
+
     // tiled prefill GEMM: whole 256 x 128 output tiles only (keys x dims for V, dims x keys for K)
     const char* pt = getenv("FM_PREFILL_TILED");     // "0" forces the per-block GEMM + scatter launches
     if (D.M % 256 == 0 && d % 256 == 0 && !(pt && pt[0] == '0')) {

@@ -670,30 +670,31 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const f16_t* __restrict__ q, 
                      blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
-// Up to three row sets of one sequence, each attending to a cache of its own (the SP heads of the three levels read the
-// coordinate-, point- and face-level caches of the last blocks, Eq. 1), in one launch: blockIdx.z picks the set.
-// Workspace and counters of set z start at z * H * FM_ATTN_MAX_SPLIT * (32*64+64) floats and z * H counters.
+// Up to three row sets per sequence, each attending to a cache of its own (the SP heads of the three levels read the
+// coordinate-, point- and face-level caches of the last blocks, Eq. 1), in one launch: blockIdx.z = set * S + sequence.
+// Workspace and counters of set z start at z * S * H * FM_ATTN_MAX_SPLIT * (32*64+64) floats and z * S * H counters.
 struct AttnLevel {
   const f16_t* q;
   const int* limit;
-  int RPS;                 // rows (0: the set is empty)
+  int RPS;                 // rows of the set per sequence (0: the set is empty)
   const f16_t *Kc, *Vc;
+  long seq_stride;         // elements between the caches of two sequences
   int capb;
   f16_t* out;
   int nsplit_cfg, window;
 };
-struct AttnLevels { AttnLevel lv[3]; };
+struct AttnLevels { AttnLevel lv[3]; int S, RS; };   // sequences; rows per sequence in the q / limit / out buffers
 
 __global__ __launch_bounds__(256) void k_attn_mfma_levels(AttnLevels L, int H, float* __restrict__ ws,
                                                            unsigned* __restrict__ counters, int defer_merge,
                                                            const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
-  const int z = blockIdx.z;
+  const int z = blockIdx.z / L.S, sq = blockIdx.z % L.S;
   const AttnLevel A = z == 0 ? L.lv[0] : z == 1 ? L.lv[1] : L.lv[2];
   if (A.RPS == 0 || (int)blockIdx.x >= A.nsplit_cfg) return;
-  attn_mfma_core<1>(A.q, A.limit, A.RPS, A.RPS, A.Kc, A.Vc, 0L, A.capb, A.out, H,
-                    ws + (size_t)z * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), counters + z * H, A.nsplit_cfg, defer_merge,
-                    A.window, blockIdx.x, blockIdx.y, 0);
+  attn_mfma_core<1>(A.q, A.limit, A.RPS, L.RS, A.Kc, A.Vc, A.seq_stride, A.capb, A.out, H,
+                    ws + (size_t)z * L.S * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), counters + z * L.S * H, A.nsplit_cfg,
+                    defer_merge, A.window, blockIdx.x, blockIdx.y, sq);
 }
 
 // Second launch of the deferred form: one workgroup per (head, sequence) derives the split count exactly as the
@@ -726,11 +727,11 @@ __global__ __launch_bounds__(256) void k_attn_merge(const int* __restrict__ limi
 __global__ __launch_bounds__(256) void k_attn_merge_levels(AttnLevels L, int H, const float* __restrict__ ws,
                                                             const int* run_flag) {
   if (run_flag && *run_flag == 0) return;
-  const int z = blockIdx.y;
+  const int z = blockIdx.y / L.S, sq = blockIdx.y % L.S;
   const AttnLevel A = z == 0 ? L.lv[0] : z == 1 ? L.lv[1] : L.lv[2];
   if (A.RPS == 0) return;
-  attn_merge_core<1>(A.limit, A.RPS, A.RPS, A.capb, A.nsplit_cfg, A.out, H,
-                     ws + (size_t)z * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), blockIdx.x, 0);
+  attn_merge_core<1>(A.limit, A.RPS, L.RS, A.capb, A.nsplit_cfg, A.out, H,
+                     ws + (size_t)z * L.S * H * FM_ATTN_MAX_SPLIT * (32 * 64 + 64), blockIdx.x, sq);
 }
 
 inline size_t mfma_attn_ws_floats(int S, int H, int hd = 64) {
@@ -797,17 +798,21 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
 
 // One launch (plus the merge launch) for up to three row sets of one sequence, each with its own cache.
 // `dense`, `key_bound`, `window` per set as in mfma_attn_launch.  Returns false if a set does not fit one q-tile.
+// `rows` = rows of the set per sequence; q, limit and out point at the set's first row of sequence 0 in buffers with RS
+// rows per sequence; S sequences.
 struct AttnLevelHost {
-  const void* q; const int* limit; int rows; const void *Kc, *Vc; int cap; void* out; bool dense; int key_bound, window;
+  const void* q; const int* limit; int rows; const void *Kc, *Vc; long seq_stride; int cap; void* out; bool dense; int key_bound, window;
 };
-inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv)[3], int H, const int* flag, hipStream_t st) {
+inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv)[3], int S, int RS, int H, const int* flag,
+                                    hipStream_t st) {
   AttnLevels L{};
+  L.S = S; L.RS = RS;
   int gx = 1;
   long total = 0;
   for (int z = 0; z < 3; z++) {
     const AttnLevelHost& h = lv[z];
     AttnLevel& A = L.lv[z];
-    A = AttnLevel{(const f16_t*)h.q, h.limit, h.rows, (const f16_t*)h.Kc, (const f16_t*)h.Vc, (h.cap + 31) / 32, (f16_t*)h.out, 1, h.window};
+    A = AttnLevel{(const f16_t*)h.q, h.limit, h.rows, (const f16_t*)h.Kc, (const f16_t*)h.Vc, h.seq_stride, (h.cap + 31) / 32, (f16_t*)h.out, 1, h.window};
     if (h.rows == 0) continue;
     if (h.rows > 16) return false;
     if (h.window > 0 && (h.cap % 32 != 0 || h.window > h.cap)) return false;
@@ -815,7 +820,7 @@ inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv
     int nsplit = A.capb / 8;
     nsplit = nsplit < 1 ? 1 : nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
     if (h.dense) {
-      const int want = 768 / H > 0 ? 768 / H : 1;
+      const int want = 768 / (H * S) > 0 ? 768 / (H * S) : 1;
       nsplit = nsplit > want ? want : nsplit;
     }
     A.nsplit_cfg = nsplit;
@@ -824,10 +829,10 @@ inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv
     int launched = (bound_blocks + per - 1) / per;
     launched = launched < 1 ? 1 : launched > nsplit ? nsplit : launched;
     gx = launched > gx ? launched : gx;
-    total += (long)launched * H;
+    total += (long)launched * H * S;
   }
   const int defer = (gx > 1 && total > 256) ? 1 : 0;
-  hipLaunchKernelGGL(k_attn_mfma_levels, dim3(gx, H, 3), dim3(256), 0, st, L, H, res.attn_ws, res.attn_counters, defer, flag);
-  if (defer) hipLaunchKernelGGL(k_attn_merge_levels, dim3(H, 3), dim3(256), 0, st, L, H, res.attn_ws, flag);
+  hipLaunchKernelGGL(k_attn_mfma_levels, dim3(gx, H, 3 * S), dim3(256), 0, st, L, H, res.attn_ws, res.attn_counters, defer, flag);
+  if (defer) hipLaunchKernelGGL(k_attn_merge_levels, dim3(H, 3 * S), dim3(256), 0, st, L, H, res.attn_ws, flag);
   return true;
 }

@@ -261,11 +261,15 @@ struct DraftRows {
   float2* cs[5];
   int *alive, *firev, *firef;   // [S]
   int* flags;                   // [0] any alive with P > 0, [1] any point firing, [2] any face firing
+  int rs[5];                    // rows per sequence in the tables of a set: row (sequence s, head k) = s * rs + k.  The
+                                // set's own head count, or for the three SP sets the head count of all three together
+                                // when their tables are one table (point, face, coordinate heads behind each other)
 };
 
 struct DraftBufs {
   const float *tap_c, *tap_v, *tap_f, *ring_yf;   // rings
   const float *spv_out, *spf_out, *hfv_out;        // head outputs feeding the HF blocks
+  int spv_rs, spf_rs;                               // rows per sequence in spv_out / spf_out (as DraftRows::rs)
 };
 
 __device__ __forceinline__ void set_row(const DraftRows& R, int set, int r, const float* src, int pos, int lim, int M,
@@ -321,15 +325,15 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
     const float* tapf = B.tap_f + ((long)s * 8 + (f & 7)) * d;
     const float* yf = B.ring_yf + ((long)s * 8 + (f & 7)) * d;
     // set 0: coordinate SP heads k = 1..Dc on the coordinate tap at s
-    for (int k = grp; k < D.Dc; k += 8) set_row(R, 0, s * D.Dc + k, tapc, spos, alive ? spos : -1, D.M, inv, lane32, D.hd >> 1);
+    for (int k = grp; k < D.Dc; k += 8) set_row(R, 0, s * R.rs[0] + k, tapc, spos, alive ? spos : -1, D.M, inv, lane32, D.hd >> 1);
     // set 1: point SP heads on the vertex tap of v
-    for (int k = grp; k < D.nspv; k += 8) set_row(R, 1, s * D.nspv + k, tapv, v, firev ? v : -1, D.M, inv, lane32, D.hd >> 1);
+    for (int k = grp; k < D.nspv; k += 8) set_row(R, 1, s * R.rs[1] + k, tapv, v, firev ? v : -1, D.M, inv, lane32, D.hd >> 1);
     // set 2: face SP heads on the face tap of f
-    for (int k = grp; k < D.nspf; k += 8) set_row(R, 2, s * D.nspf + k, tapf, f, firef ? f : -1, D.M, inv, lane32, D.hd >> 1);
+    for (int k = grp; k < D.nspf; k += 8) set_row(R, 2, s * R.rs[2] + k, tapf, f, firef ? f : -1, D.M, inv, lane32, D.hd >> 1);
     // set 3: vertex-level HF, vertex offsets j = j0..n/3-1 from vertex token 3f; input = face feature j/3
     for (int q = grp; q < D.nhfv; q += 8) {
       const int j = q + D.j0;
-      const float* src = (j < 3) ? yf : B.spf_out + ((long)s * D.nspf + (j / 3 - 1)) * d;
+      const float* src = (j < 3) ? yf : B.spf_out + ((long)s * B.spf_rs + (j / 3 - 1)) * d;
       set_row(R, 3, s * D.nhfv + q, src, 3 * f + j, firef ? 3 * f : -1, D.M, inv, lane32, D.hd >> 1);
     }
     // set 4: coordinate-level HF, offsets t = t0..; pipe 0 = point pipeline, pipe 1 = face pipeline
@@ -339,7 +343,7 @@ __global__ __launch_bounds__(256) void k_draft_setup(StateDev st, Dims D, InvFre
       if (pipe == 0) {
         const bool on = firev && t < D.m;
         // offsets 0..2 (rule (B) off) belong to the current vertex: its own feature; later ones to the SP head outputs
-        const float* src = t < 3 ? tapv : B.spv_out + ((long)s * max(D.nspv, 1) + min(t / 3 - 1, max(D.nspv - 1, 0))) * d;
+        const float* src = t < 3 ? tapv : B.spv_out + ((long)s * B.spv_rs + min(t / 3 - 1, max(D.nspv - 1, 0))) * d;
         set_row(R, 4, r, src, 3 * v + t, on ? 3 * v : -1, D.M, inv, lane32, D.hd >> 1);
       } else {
         const bool on = firef && t < D.n;
@@ -605,16 +609,16 @@ __global__ __launch_bounds__(1024) void k_merge(StateDev st, Dims D, DraftRows R
 // point pipeline's SP head outputs (vertex v + k), the rest the face pipeline's vertex-level HF outputs (vertex
 // 3f + j); a row is stored only when its pipeline fired for the sequence, so older rows stay usable like the
 // token distributions do.
-__global__ __launch_bounds__(64) void k_label_rows(Dims D, DraftRows R, const float* __restrict__ spv_out,
+__global__ __launch_bounds__(64) void k_label_rows(Dims D, DraftRows R, const float* __restrict__ spv_out, int spv_rs,
                                                     const float* __restrict__ hfv_out, const float* __restrict__ W,
                                                     float* __restrict__ lab_v, float* __restrict__ lab_f) {
   const int r = blockIdx.x, lane = threadIdx.x;
   const float* src;
   float* dst;
   if (r < D.S * D.nspv) {
-    const int s = r / D.nspv;
+    const int s = r / D.nspv, k = r % D.nspv;
     if (!R.firev[s]) return;
-    src = spv_out + (long)r * D.d;
+    src = spv_out + ((long)s * spv_rs + k) * D.d;      // spv_rs rows per sequence in the SP output buffer
     dst = lab_v + (long)r * 3;
   } else {
     const int rr = r - D.S * D.nspv, s = rr / D.nhfv;
