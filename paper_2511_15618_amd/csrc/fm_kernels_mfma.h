@@ -139,11 +139,13 @@ struct GemmSplit {
 // round instead of two)
 // NW waves per workgroup (4, 8 or 16) split K: launches with few column tiles (N = d gives 64 to 96 of them)
 // take more waves per workgroup so that enough loads are in flight and each wave's K walk stays short.
-template <int MT, int EPI, bool NORM, int NW>
+// NC column tiles of 16 per workgroup (1 or 2): with two, an activation fragment loaded (and normalised) once feeds two
+// MFMAs, which halves what the wide projections (N >= 2048) pull out of L2 for their activations.
+template <int MT, int EPI, bool NORM, int NW, int NC = 1>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs a, GemmSplit sp) {
   if (a.run_flag && *a.run_flag == 0) return;
-  static_assert(NW * MT <= 60, "partial tiles of all waves must fit the static LDS limit");
-  __shared__ f32x4 red[NW][MT][64];
+  static_assert(NW * MT * NC <= 60, "partial tiles of all waves must fit the static LDS limit");
+  __shared__ f32x4 red[NW][MT * NC][64];
   __shared__ float sq[NORM ? NW : 1][MT][16];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int nt = blockIdx.x;
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
   const int KT = a.K / 32;
   typedef typename std::conditional<NORM, float, f16_t>::type XT;
   const XT* X = (const XT*)a.X + (long)g * a.gsx;
-  const f16_t* W = (const f16_t*)a.W + (long)g * a.gsw + ((long)nt * KT) * 512;
+  const f16_t* W = (const f16_t*)a.W + (long)g * a.gsw + ((long)nt * NC * KT) * 512;   // column tile c of this workgroup: + c * KT * 512
   const int m0 = mb * MT * 16;
   // A-fragment row pointers (rows past M are clamped: computed, never stored)
   const XT* xrow[MT];
@@ -162,10 +164,14 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
     m = m < a.M ? m : a.M - 1;
     xrow[mt] = X + (long)m * a.ldx + (lane >> 4) * 8;
   }
-  f32x4 acc[MT];
+  f32x4 acc[MT][NC];
   float ss[MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; mt++) { acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f}; ss[mt] = 0.f; }
+  for (int mt = 0; mt < MT; mt++) {
+    ss[mt] = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; c++) acc[mt][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
   const int kt0 = wave * sp.kt_per_wave;
   const int kt1 = min(kt0 + sp.kt_per_wave, KT);
 
@@ -174,17 +180,18 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
   constexpr int U4 = NORM ? (MT <= 2 ? 4 : MT <= 5 ? 2 : 1) : (MT <= 2 ? 8 : MT <= 5 ? 4 : 2);
   constexpr int U = NW == 16 ? (U4 >= 4 ? U4 / 4 : 1) : NW == 8 ? (U4 >= 2 ? U4 / 2 : 1) : U4;
   struct AFrag { typename std::conditional<NORM, f32x4, f16x8>::type lo; f32x4 hi; };   // hi only used when NORM
-  f16x8 bc[U];
+  f16x8 bc[NC][U];
   AFrag ac[MT][U];
   f32x4 gc[NORM ? U : 1][2];
   const int nk = kt1 - kt0;
   auto kmap = [&](int i) { return kt0 + i; };
-  auto load_chunk = [&](f16x8 (&b)[U], AFrag (&af)[MT][U], f32x4 (&gg)[NORM ? U : 1][2], int i0) {
+  auto load_chunk = [&](f16x8 (&b)[NC][U], AFrag (&af)[MT][U], f32x4 (&gg)[NORM ? U : 1][2], int i0) {
 #pragma unroll
     for (int u = 0; u < U; u++) {
       if (i0 + u < nk) {
         const int kt = kmap(i0 + u);
-        b[u] = *reinterpret_cast<const f16x8*>(W + ((long)kt * 64 + lane) * 8);
+#pragma unroll
+        for (int c = 0; c < NC; c++) b[c][u] = *reinterpret_cast<const f16x8*>(W + ((long)(c * KT + kt) * 64 + lane) * 8);
         if constexpr (NORM) {
           const float* gp = a.gain + kt * 32 + (lane >> 4) * 8;
           gg[u][0] = *reinterpret_cast<const f32x4*>(gp);
@@ -204,7 +211,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
   };
   load_chunk(bc, ac, gc, 0);
   for (int i0 = 0; i0 < nk; i0 += U) {
-    f16x8 bn[U];
+    f16x8 bn[NC][U];
     AFrag an[MT][U];
     f32x4 gn[NORM ? U : 1][2];
     load_chunk(bn, an, gn, i0 + U);
@@ -225,13 +232,15 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
           } else {
             av = ac[mt][u].lo;
           }
-          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bc[u], acc[mt], 0, 0, 0);
+#pragma unroll
+          for (int c = 0; c < NC; c++) acc[mt][c] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, bc[c][u], acc[mt][c], 0, 0, 0);
         }
       }
     }
 #pragma unroll
     for (int u = 0; u < U; u++) {
-      bc[u] = bn[u];
+#pragma unroll
+      for (int c = 0; c < NC; c++) bc[c][u] = bn[c][u];
       if constexpr (NORM) { gc[u][0] = gn[u][0]; gc[u][1] = gn[u][1]; }
 #pragma unroll
       for (int mt = 0; mt < MT; mt++) ac[mt][u] = an[mt][u];
@@ -240,7 +249,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
   // reduce the K-slices of the waves through LDS, in wave order
 #pragma unroll
   for (int mt = 0; mt < MT; mt++) {
-    red[wave][mt][lane] = acc[mt];
+#pragma unroll
+    for (int c = 0; c < NC; c++) red[wave][mt * NC + c][lane] = acc[mt][c];
     if constexpr (NORM) {
       float t = ss[mt];
       t += __shfl_xor(t, 16, 64);
@@ -249,11 +259,12 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
     }
   }
   __syncthreads();
-  const int n = nt * 16 + (lane & 15);
-  for (int mt = wave; mt < MT; mt += NW) {
-    f32x4 v = red[0][mt][lane];
+  for (int t = wave; t < MT * NC; t += NW) {
+    const int mt = t / NC, ntc = nt * NC + t % NC;     // row tile and column tile of this result tile
+    const int n = ntc * 16 + (lane & 15);
+    f32x4 v = red[0][t][lane];
 #pragma unroll
-    for (int w = 1; w < NW; w++) v += red[w][mt][lane];
+    for (int w = 1; w < NW; w++) v += red[w][t][lane];
     if constexpr (NORM) {
 #pragma unroll
       for (int i = 0; i < 4; i++) {
@@ -268,7 +279,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void k_gemm_mfma(GemmArgs
       // tile nt of the fused projection: part 0/1/2 = q/k/v, head hh, and for q and k the rotary pairs
       // qd*8 .. +8 (columns 0..7 = first halves, 8..15 = second halves), for v the dims qd*16 .. +16
       const int d = a.H * FM_HD, col = lane & 15;
-      const int part = (nt * 16) / d, cp = (nt * 16) % d;
+      const int part = (ntc * 16) / d, cp = (ntc * 16) % d;
       const int hh = cp >> 6, qd = (cp & 63) >> 4;
 #pragma unroll
       for (int i = 0; i < 4; i++) {
@@ -323,28 +334,36 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
   size_t attn_ws_floats;
   int gemm_waves;     // 0 = choose per launch; 4, 8, 16 = forced (measurement switch)
   int gemm_mt_cap;    // 0 = default (below); 2, 3, 5, 8 = one workgroup covers up to that many 16-row tiles (measurement switch)
+  int gemm_nc;        // 0 = two column tiles per workgroup for the wide projections; 1 = one everywhere, 2 = two everywhere (measurement switches)
 };
 
-template <int MT, bool NORM, int NW>
+template <int MT, bool NORM, int NW, int NC>
 void gemm_mfma_dispatch3(const GemmArgs& a, const GemmSplit& sp, int epi, dim3 grid, hipStream_t st) {
   if (epi == EPI_QKV) {
-    if constexpr (NORM) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_QKV, true, NW>), grid, dim3(NW * 64), 0, st, a, sp);
+    if constexpr (NORM) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_QKV, true, NW, NC>), grid, dim3(NW * 64), 0, st, a, sp);
     return;
   }
-  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32, NORM, NW>), grid, dim3(NW * 64), 0, st, a, sp);
-  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T, NORM, NW>), grid, dim3(NW * 64), 0, st, a, sp);
-  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T, NORM, NW>), grid, dim3(NW * 64), 0, st, a, sp);
+  if (epi == EPI_F32) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_F32, NORM, NW, NC>), grid, dim3(NW * 64), 0, st, a, sp);
+  else if (epi == EPI_GELU_T) hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_GELU_T, NORM, NW, NC>), grid, dim3(NW * 64), 0, st, a, sp);
+  else hipLaunchKernelGGL((k_gemm_mfma<MT, EPI_T, NORM, NW, NC>), grid, dim3(NW * 64), 0, st, a, sp);
 }
-template <int MT, bool NORM>
+template <int MT, bool NORM, int NC>
 void gemm_mfma_dispatch2(const GemmArgs& a, const GemmSplit& sp, int nw, int epi, dim3 grid, hipStream_t st) {
-  if constexpr (MT <= 3) { if (nw == 16) { gemm_mfma_dispatch3<MT, NORM, 16>(a, sp, epi, grid, st); return; } }
-  if constexpr (MT <= 5) { if (nw >= 8) { gemm_mfma_dispatch3<MT, NORM, 8>(a, sp, epi, grid, st); return; } }
-  gemm_mfma_dispatch3<MT, NORM, 4>(a, sp, epi, grid, st);
+  if constexpr (MT <= 3) { if (nw == 16) { gemm_mfma_dispatch3<MT, NORM, 16, NC>(a, sp, epi, grid, st); return; } }
+  if constexpr (MT <= 5) { if (nw >= 8) { gemm_mfma_dispatch3<MT, NORM, 8, NC>(a, sp, epi, grid, st); return; } }
+  gemm_mfma_dispatch3<MT, NORM, 4, NC>(a, sp, epi, grid, st);
 }
 template <int MT>
-void gemm_mfma_dispatch(const GemmArgs& a, const GemmSplit& sp, int nw, int epi, dim3 grid, hipStream_t st) {
-  if (a.gain) gemm_mfma_dispatch2<MT, true>(a, sp, nw, epi, grid, st);
-  else gemm_mfma_dispatch2<MT, false>(a, sp, nw, epi, grid, st);
+void gemm_mfma_dispatch(const GemmArgs& a, const GemmSplit& sp, int nw, int epi, int nc, dim3 grid, hipStream_t st) {
+  if constexpr (MT == 1) {
+    if (nc == 2) {
+      if (a.gain) gemm_mfma_dispatch2<1, true, 2>(a, sp, nw, epi, grid, st);
+      else gemm_mfma_dispatch2<1, false, 2>(a, sp, nw, epi, grid, st);
+      return;
+    }
+  }
+  if (a.gain) gemm_mfma_dispatch2<MT, true, 1>(a, sp, nw, epi, grid, st);
+  else gemm_mfma_dispatch2<MT, false, 1>(a, sp, nw, epi, grid, st);
 }
 
 template <typename T>
@@ -368,19 +387,22 @@ inline bool mfma_gemm_launch<f16_t>(const MfmaRes& res, const GemmArgs& a, int e
   const int nmb = (a.M + MT * 16 - 1) / (MT * 16);
   // waves per workgroup: enough for about 2048 waves in the launch, at least two K fragments per wave, and the
   // partial tiles of all waves within the static LDS limit
-  const long wgs = (long)NT * groups * nmb;
+  // two column tiles per workgroup for the wide projections (q,k,v, FFN up, output head) when rows are split 16 per
+  // workgroup: FM_GEMM_NC=1 switches it off (measurement)
+  const int nc = (MT == 1 && NT >= (res.gemm_nc == 2 ? 2 : 128) && NT % 2 == 0 && res.gemm_nc != 1) ? 2 : 1;   // gemm_nc == 2: every even launch (measurement)
+  const long wgs = (long)(NT / nc) * groups * nmb;
   const int nw_max = MT <= 3 ? 16 : MT <= 5 ? 8 : 4;
   int nw = 4;
   while (nw < nw_max && wgs * nw < 2048 && KT / (nw * 2) >= 2) nw *= 2;
   if (res.gemm_waves == 4 || res.gemm_waves == 8 || res.gemm_waves == 16) nw = res.gemm_waves < nw_max ? res.gemm_waves : nw_max;
   GemmSplit sp{(KT + nw - 1) / nw};   // the waves of a workgroup split K
-  dim3 grid(NT, 1, groups * nmb);
+  dim3 grid(NT / nc, 1, groups * nmb);
   switch (MT) {
-    case 1: gemm_mfma_dispatch<1>(a, sp, nw, epi, grid, st); break;
-    case 2: gemm_mfma_dispatch<2>(a, sp, nw, epi, grid, st); break;
-    case 3: gemm_mfma_dispatch<3>(a, sp, nw, epi, grid, st); break;
-    case 5: gemm_mfma_dispatch<5>(a, sp, nw, epi, grid, st); break;
-    default: gemm_mfma_dispatch<8>(a, sp, nw, epi, grid, st); break;
+    case 1: gemm_mfma_dispatch<1>(a, sp, nw, epi, nc, grid, st); break;
+    case 2: gemm_mfma_dispatch<2>(a, sp, nw, epi, nc, grid, st); break;
+    case 3: gemm_mfma_dispatch<3>(a, sp, nw, epi, nc, grid, st); break;
+    case 5: gemm_mfma_dispatch<5>(a, sp, nw, epi, nc, grid, st); break;
+    default: gemm_mfma_dispatch<8>(a, sp, nw, epi, nc, grid, st); break;
   }
   return true;
 }
