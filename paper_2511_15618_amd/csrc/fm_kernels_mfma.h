@@ -334,6 +334,8 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
   size_t attn_ws_floats;
   int gemm_waves;     // 0 = choose per launch; 4, 8, 16 = forced (measurement switch)
   int gemm_mt_cap;    // 0 = default (below); 2, 3, 5, 8 = one workgroup covers up to that many 16-row tiles (measurement switch)
+  int attn_wgs;       // key ranges of a growing cache: as few as give about this many workgroups per launch (768 by default,
+                      // as for the condition memory); 0 = ranges as short as 8 blocks whatever the batch (measurement switch)
   int gemm_nc;        // 0 = two column tiles per workgroup for the wide projections; 1 = one everywhere, 2 = two everywhere (measurement switches)
 };
 
@@ -774,14 +776,16 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
   if (window > 0 && (cap % 32 != 0 || window > cap)) return false;     // a ring is a whole number of blocks
   const int S = rows / RPS;
   const int capb = (cap + 31) / 32;
-  // The key axis is cut into fixed ranges of at least 8 blocks (two per wave).  A growing cache is far below
-  // its capacity most of the time, so its ranges stay that short (up to 64 of them); a cache that is always
-  // full (`dense`: the condition memory) gets as few ranges as fill the chip in one round of workgroups.
+  // The key axis is cut into fixed ranges of at least 8 blocks (two per wave), at most 64 of them, and no more than
+  // give about 768 workgroups per launch (three per compute unit: measured best between 256 and 3072 for 8 x 16 and
+  // 4 x 24 (sequence, head) pairs; with fewer pairs the ranges stay short).  The ranges depend on the capacity, the
+  // head count and the batch size only, never on how far a sequence has grown.
   int nsplit = capb / 8;
   nsplit = nsplit < 1 ? 1 : nsplit;
   nsplit = nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
-  if (dense) {
-    const int want = 768 / (H * S) > 0 ? 768 / (H * S) : 1;
+  if (dense || res.attn_wgs > 0) {
+    const int target = dense ? 768 : res.attn_wgs;
+    const int want = target / (H * S) > 0 ? target / (H * S) : 1;
     nsplit = nsplit > want ? want : nsplit;
   }
   // `key_bound` is the host's upper bound on the visible keys: ranges past it hold nothing and are not launched
@@ -841,8 +845,9 @@ inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv
     // the same partition of the key axis as mfma_attn_launch makes for one sequence
     int nsplit = A.capb / 8;
     nsplit = nsplit < 1 ? 1 : nsplit > FM_ATTN_MAX_SPLIT ? FM_ATTN_MAX_SPLIT : nsplit;
-    if (h.dense) {
-      const int want = 768 / (H * S) > 0 ? 768 / (H * S) : 1;
+    if (h.dense || res.attn_wgs > 0) {
+      const int target = h.dense ? 768 : res.attn_wgs;
+      const int want = target / (H * S) > 0 ? target / (H * S) : 1;
       nsplit = nsplit > want ? want : nsplit;
     }
     A.nsplit_cfg = nsplit;
