@@ -842,7 +842,8 @@ int build_buffers(fm_ctx* c) {
   c->db = DraftBufs{c->tap_c, c->tap_v, c->tap_f, c->ring_yf, c->spv_out, c->spf_out, c->hfv_out, spv_rs, spf_rs};
   TRY(dalloc(c, &c->gen_tok, S * D.Bm)); TRY(dalloc(c, &c->gen_len, S)); TRY(dalloc(c, &c->gen_acc, S));
   if (c->persist) TRY(build_persist(c));
-  c->mres = MfmaRes{nullptr, nullptr, 0, 0, 0, 768, 0};
+  c->mres = MfmaRes{nullptr, nullptr, 0, 0, 0, 768, 0, 0};
+  if (const char* e = getenv("FM_ATTN_MERGE")) c->mres.attn_merge = atoi(e);   // measurement switch, see MfmaRes
   if (const char* e = getenv("FM_ATTN_WGS")) c->mres.attn_wgs = atoi(e);       // measurement switch: workgroups per self-attention launch
   if (const char* e = getenv("FM_GEMM_NC")) c->mres.gemm_nc = atoi(e);         // measurement switch: 1 = one column tile per workgroup
   if (const char* e = getenv("FM_GEMM_WAVES")) c->mres.gemm_waves = atoi(e);   // measurement switch: 4, 8 or 16

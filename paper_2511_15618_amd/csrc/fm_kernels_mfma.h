@@ -336,6 +336,7 @@ struct MfmaRes {      // per-context resources of the MFMA kernels
   int gemm_mt_cap;    // 0 = default (below); 2, 3, 5, 8 = one workgroup covers up to that many 16-row tiles (measurement switch)
   int attn_wgs;       // key ranges of a growing cache: as few as give about this many workgroups per launch (768 by default,
                       // as for the condition memory); 0 = ranges as short as 8 blocks whatever the batch (measurement switch)
+  int attn_merge;     // 2 = the last workgroup of a (sequence, head) always merges, publication without an L2 write-back (measurement)
   int gemm_nc;        // 0 = two column tiles per workgroup for the wide projections; 1 = one everywhere, 2 = two everywhere (measurement switches)
 };
 
@@ -661,7 +662,7 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
     }
     if (nsplit == 1) {
       if (qi < RPS) out[((long)s * RS + qi) * d + hh * HD + dim] = (f16_t)(den > 0.f ? num / den : 0.f);
-    } else if (defer_merge) {
+    } else if (defer_merge == 1) {
       part[e] = num;
       if (dim == 0) { part[NQ * HD + qi] = M; part[NQ * HD + NQ + qi] = den; }
     } else {
@@ -669,8 +670,15 @@ __device__ __forceinline__ void attn_mfma_core(const f16_t* __restrict__ q, cons
       if (dim == 0) { st_agent(part + NQ * HD + qi, M); st_agent(part + NQ * HD + NQ + qi, den); }
     }
   }
-  if (nsplit == 1 || defer_merge) return;     // deferred: k_attn_merge runs behind this launch
-  publish_fence();
+  if (nsplit == 1 || defer_merge == 1) return;     // deferred: k_attn_merge runs behind this launch
+  if (defer_merge == 2) {
+    // The partials went out as agent-scope stores (written through, not left in this die's L2), so they are visible to
+    // the other dies once the stores have completed: wait for that instead of writing the whole L2 back.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+  } else {
+    publish_fence();
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     const unsigned old = __hip_atomic_fetch_add(&counters[sh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -797,7 +805,7 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
   // With many workgroups the in-kernel merge loses: every workgroup pays an agent-scope release fence (an L2
   // write-back, and those queue up per XCD).  Then the partials go out as plain stores and a second, tiny
   // launch merges them; the arithmetic is the same either way.
-  const int defer = (launched > 1 && (long)launched * H * S > 256) ? 1 : 0;
+  const int defer = res.attn_merge == 2 ? 2 : (launched > 1 && (long)launched * H * S > 256) ? 1 : 0;
   // at most 32 query rows of a sequence per launch (16 for the wide heads, whose partial tiles would not fit the
   // LDS of a 32-row launch); longer row sets go out in chunks
   const int d = H * hd;
@@ -806,7 +814,7 @@ inline bool mfma_attn_launch<f16_t>(const MfmaRes& res, const void* q, const int
   {                                                                                                                \
     hipLaunchKernelGGL((k_attn_mfma<QTV, HDV>), grid, dim3(256), 0, st, qc, lc, rc, RPS, (const f16_t*)Kc, (const f16_t*)Vc, \
                        seq_stride, capb, oc, H, res.attn_ws, res.attn_counters, nsplit, defer, flag, window);     \
-    if (defer) hipLaunchKernelGGL((k_attn_merge<QTV, HDV>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag); \
+    if (defer == 1) hipLaunchKernelGGL((k_attn_merge<QTV, HDV>), dim3(H, S), dim3(256), 0, st, lc, rc, RPS, capb, nsplit, oc, H, res.attn_ws, flag); \
   }
   for (int r0 = 0; r0 < RPS; r0 += chunk) {
     const int rc = RPS - r0 < chunk ? RPS - r0 : chunk;
@@ -858,8 +866,8 @@ inline bool mfma_attn_launch_levels(const MfmaRes& res, const AttnLevelHost (&lv
     gx = launched > gx ? launched : gx;
     total += (long)launched * H * S;
   }
-  const int defer = (gx > 1 && total > 256) ? 1 : 0;
+  const int defer = res.attn_merge == 2 ? 2 : (gx > 1 && total > 256) ? 1 : 0;
   hipLaunchKernelGGL(k_attn_mfma_levels, dim3(gx, H, 3 * S), dim3(256), 0, st, L, H, res.attn_ws, res.attn_counters, defer, flag);
-  if (defer) hipLaunchKernelGGL(k_attn_merge_levels, dim3(H, 3 * S), dim3(256), 0, st, L, H, res.attn_ws, flag);
+  if (defer == 1) hipLaunchKernelGGL(k_attn_merge_levels, dim3(H, 3 * S), dim3(256), 0, st, L, H, res.attn_ws, flag);
   return true;
 }
