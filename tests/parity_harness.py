@@ -62,8 +62,10 @@ class Report:
                 + (f" points={self.points} label_flips={self.label_flips} corrected_blocks={self.corrected_blocks}" if self.points else ""))
 
 
-def make_pair(cfg, work=np.float64, max_tokens=None, prefill="prefill_condition"):
+def make_pair(cfg, work=np.float64, max_tokens=None, prefill="prefill_condition", edit_weights=None):
     w = si.make_weights(cfg, 0)
+    if edit_weights is not None:          # the same edited weights go to both sides
+        edit_weights(w)
     _progress("  weights drawn")
     model = Model(cfg, w, work=work)
     fm = FlashMesh(config_struct(cfg, max_tokens=max_tokens))

@@ -248,3 +248,34 @@ def test_condition_kv_element_by_element(name):
     assert 0.0 < worst <= 1.0
     with pytest.raises(RuntimeError):
         fm.debug_mem_kv(0, b)
+
+
+@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99", "t_bf16_99_b1"])
+def test_lockstep_eos_ends_sequences(name):
+    """The degenerate end of a mesh: with the special tokens admitted (ban_specials = 0) the random-init backbone emits
+    EOS somewhere in most sequences, which finishes that sequence at once (the rest of its block is dropped) while the
+    others go on; blocks, accepted lengths, committed state and finished flags in lock-step with the oracle, and the
+    whole-loop entry point ends every stream at the same token."""
+    _need_gpu()
+    from parity_harness import lockstep, make_pair
+    cfg = si.TEST_CONFIGS[name].replace(ban_specials=0, faces=16)
+    print("case eos", name, flush=True)
+    eos_row = cfg.n_bins + 1
+
+    def louder_eos(w):                                # a power of two: the row stays bf16-valued
+        w["lm"][eos_row] = 2.0 * w["lm"][eos_row]
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype], pair=make_pair(cfg, edit_weights=louder_eos))
+    print(rep, [len(s) for s in streams], flush=True)
+    eos = cfg.n_bins + 1
+    ended = [s for s in streams if s and s[-1] == eos and len(s) < 9 * cfg.faces]
+    for s in streams:
+        assert eos not in s[:-1]                      # nothing is generated behind an EOS
+        assert len(s) == 9 * cfg.faces or s[-1] == eos
+    assert ended, "no sequence met an EOS"
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    out, n, st = fm.generate(cfg.faces, True)
+    out, n = out.cpu().numpy(), n.cpu().numpy()
+    if rep.token_flips == 0:
+        for s in range(cfg.batch):
+            assert list(out[s, :n[s]]) == streams[s]
