@@ -279,3 +279,24 @@ def test_lockstep_eos_ends_sequences(name):
     if rep.token_flips == 0:
         for s in range(cfg.batch):
             assert list(out[s, :n[s]]) == streams[s]
+
+
+@pytest.mark.parametrize("name", ["t_bf16_99", "t_f32_99"])
+def test_lockstep_at_the_largest_batch(name):
+    """64 sequences, the most fm_create accepts: every per-sequence table, flag and counter at its full length."""
+    _need_gpu()
+    from parity_harness import lockstep
+    cfg = si.TEST_CONFIGS[name].replace(batch=64, faces=3)
+    print("case batch 64", name, flush=True)
+    rep, streams, fm = lockstep(cfg, cfg.faces, TOL[cfg.dtype])
+    print(rep, flush=True)
+    assert len(streams) == 64 and all(len(s) == 27 for s in streams)
+    assert len({tuple(s) for s in streams}) > 32          # the sequences are conditioned on different memories
+    for s in range(cfg.batch):
+        fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+    out, n, st = fm.generate(cfg.faces, True)
+    assert st.tokens == 27 * 64
+    if rep.token_flips == 0:
+        out = out.cpu().numpy()
+        for s in range(64):
+            assert list(out[s, :27]) == streams[s]
