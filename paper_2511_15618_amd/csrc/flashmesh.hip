@@ -689,7 +689,8 @@ int build_persist(fm_ctx* c) {
   const int caps[3] = {D.capc, D.capv, D.capf};
   for (int l = 0; l < 3; l++) {
     a.capb[l] = (caps[l] + 31) / 32;
-    int ns = PK_NWG / D.H;                       // about one attention unit per workgroup (32 per head measured slower: the merge grows)
+    int ns = PK_NWG / D.H;                       // about one attention unit per workgroup
+    if (const char* e = getenv("FM_PK_NSPLIT")) ns = std::max(1, atoi(e));       // measurement switch: key ranges per head
     ns = std::min(ns, std::max(1, a.capb[l] / 2));
     a.nsplit[l] = std::max(1, std::min(ns, PK_MAXSPLIT));
     a.pos[l] = c->pos[l]; a.limx[l] = c->limx[l]; a.cs[l] = c->cs[l];

@@ -834,7 +834,9 @@ __global__ __launch_bounds__(256) void k_verify_persist(PkArgs a) {
         const int ns = a.nsplit[lev];
         const int P0 = firstP[lev];
         PK_MINE(H * ns) {
-          const int hh = u / ns, sp = u % ns;
+          // range-major: the ranges that hold keys come first, so that with more ranges than a workgroup can take at once
+          // the non-empty ones still spread over all workgroups
+          const int hh = u % H, sp = u / H;
           if (!pk_attn_unit<QT>(a, sh, a.q, limS[lev], maxS[lev], R, L.Kc, L.Vc, capb, ns, hh, sp, true, P0,
                                 a.partS + ((long)hh * PK_MAXSPLIT + sp) * (RS >> 4) * PK_PART, tag, stage, a.win[lev])) return;
         }
