@@ -454,6 +454,7 @@ def main():
                                + (f"; {steps} steps timed at half context ({context} tokens committed, reached with replay p=1)" if context is not None else "; whole generation timed"),
                    "draft_source": f"replay p={REPLAY_P}", "tokens": tokens, "mean_accepted": tokens / max(steps, 1),
                    "accepted_hist": hist, "per_level": levels, "stream_equals_native_run": same,
+                   "nonfinite_logit_rows": int(st_native.nonfinite_rows),
                    "native_heads_tokens_per_s": st_native.tokens / st_native.ms_total * 1e3,
                    "native_heads_ms_per_step": st_native.ms_total / max(st_native.steps, 1),
                    "sequential_tokens_per_s": st_seq.tokens / st_seq.ms_total * 1e3,

@@ -84,6 +84,8 @@ typedef struct {
   double ms_draft, ms_verify, ms_commit; /* device time of the draft (+ correct), verify and commit phases of one step: mean
                                 over the phase_samples steps that carried event marks (one step in 32)                      */
   int64_t phase_samples;
+  int64_t nonfinite_rows;    /* verify rows whose logits held an infinity or a NaN (0 in a healthy run): with FM_DTYPE_BF16
+                                activations, K/V and GEMM inputs are IEEE half, which overflows beyond 65504 without a trap */
 } fm_stats;
 
 /* Create a context for `cfg` bound to `hip_stream` (a hipStream_t; NULL = the null stream).

@@ -28,7 +28,8 @@ class FmConfig(C.Structure):
 
 class FmStats(C.Structure):
     _fields_ = [("steps", C.c_int64), ("tokens", C.c_int64), ("acc_hist", (C.c_int64 * 32) * 3), ("ms_total", C.c_double),
-                ("ms_draft", C.c_double), ("ms_verify", C.c_double), ("ms_commit", C.c_double), ("phase_samples", C.c_int64)]
+                ("ms_draft", C.c_double), ("ms_verify", C.c_double), ("ms_commit", C.c_double), ("phase_samples", C.c_int64),
+                ("nonfinite_rows", C.c_int64)]
 
     def hist(self, kind=None):
         """Accepted-length histogram as a list of 32 counts: kind 0 / 1 / 2 = coordinate-only / point-level / face-level

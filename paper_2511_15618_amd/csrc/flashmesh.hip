@@ -314,7 +314,7 @@ void choose_and_accept(fm_ctx* c, const float* logits, int32_t* accepted) {
     hipLaunchKernelGGL(k_sample_rows, dim3(c->Rc), dim3(256), 0, c->stream, c->st, D, logits, c->smp);
     hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)c->smp.accflag, pass_failed(c));
   } else {
-    hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, logits, D.V, D.ban ? D.nbins : D.V, c->st.y);
+    hipLaunchKernelGGL(k_argmax_rows, dim3(c->Rc), dim3(256), 0, c->stream, logits, D.V, D.ban ? D.nbins : D.V, c->st.y, c->st.counters + 2);
     hipLaunchKernelGGL(k_accept, dim3(1), dim3(64), 0, c->stream, c->st, D, accepted, (const int*)nullptr, pass_failed(c));
   }
 }
@@ -755,7 +755,7 @@ int build_buffers(fm_ctx* c) {
   TRY(dalloc(c, &st.basec, S)); TRY(dalloc(c, &st.basev, S)); TRY(dalloc(c, &st.basef, S));
   TRY(dalloc(c, &st.vlen, S)); TRY(dalloc(c, &st.vtok, S * D.Bm)); TRY(dalloc(c, &st.y, S * D.Bm)); TRY(dalloc(c, &st.acc, S));
   TRY(dalloc(c, &st.hist, S * (D.maxtok + 1))); TRY(dalloc(c, &st.budget, 1)); TRY(dalloc(c, &st.alive, 1));
-  TRY(dalloc(c, &st.acc_hist, 3 * 32)); TRY(dalloc(c, &st.counters, 2)); TRY(dalloc(c, &st.kind, S));
+  TRY(dalloc(c, &st.acc_hist, 3 * 32)); TRY(dalloc(c, &st.counters, 3)); TRY(dalloc(c, &st.kind, S));
   TRY(dalloc(c, &c->ring_hc, S * RS_C * d)); TRY(dalloc(c, &c->tap_c, S * RS_C * d));
   TRY(dalloc(c, &c->ring_hv, S * RS_V * d)); TRY(dalloc(c, &c->ring_yv, S * RS_V * d)); TRY(dalloc(c, &c->tap_v, S * RS_V * d));
   TRY(dalloc(c, &c->ring_yf, S * RS_F * d)); TRY(dalloc(c, &c->tap_f, S * RS_F * d));
@@ -1376,7 +1376,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
   } ev;
   for (int i = 0; i < E_COUNT; i++) HIPCHK(c, hipEventCreate(&ev.e[i]));
   HIPCHK(c, hipMemsetAsync(c->st.acc_hist, 0, 3 * 32 * sizeof(unsigned long long), c->stream));
-  HIPCHK(c, hipMemsetAsync(c->st.counters, 0, 2 * sizeof(unsigned long long), c->stream));
+  HIPCHK(c, hipMemsetAsync(c->st.counters, 0, 3 * sizeof(unsigned long long), c->stream));
   HIPCHK(c, hipEventRecord(ev.e[E_BEGIN], c->stream));
   const long max_steps = 9L * max_faces + 1 + 128;     // + the steps a failed pass of the single-launch kernel may void
   const int check_every = 32;
@@ -1455,7 +1455,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
   TRY(check_persist(c));      // a failure in the very last interval: reported, the caller may call again
   if (phase_pending) TRY(take_phases());
   if (stats) {
-    unsigned long long cnt[2], hist[3 * 32];
+    unsigned long long cnt[3], hist[3 * 32];
     HIPCHK(c, hipMemcpy(cnt, c->st.counters, sizeof cnt, hipMemcpyDeviceToHost));
     HIPCHK(c, hipMemcpy(hist, c->st.acc_hist, sizeof hist, hipMemcpyDeviceToHost));
     float ms = 0.f;
@@ -1468,6 +1468,7 @@ int fm_generate(fm_ctx* c, int32_t max_faces, int32_t speculative, int32_t* out_
     const double n = phase_samples > 0 ? (double)phase_samples : 1.0;
     stats->ms_draft = ms_phase[0] / n; stats->ms_verify = ms_phase[1] / n; stats->ms_commit = ms_phase[2] / n;
     stats->phase_samples = phase_samples;
+    stats->nonfinite_rows = (int64_t)cnt[2];
   }
   return FM_OK;
 }

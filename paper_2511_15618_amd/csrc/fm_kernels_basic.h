@@ -299,13 +299,25 @@ __device__ __forceinline__ int block_argmax(float bv, int bi, float* sv, int* si
   return bi;
 }
 
-__global__ __launch_bounds__(256) void k_argmax_rows(const float* __restrict__ logits, int V, int nlim, int* __restrict__ y) {
+// `nonfinite` (may be null): counts the rows whose admissible logits hold an infinity or a NaN - half-precision
+// activations beyond 65504 overflow silently on the way, and this is where it shows
+__global__ __launch_bounds__(256) void k_argmax_rows(const float* __restrict__ logits, int V, int nlim, int* __restrict__ y,
+                                                      unsigned long long* __restrict__ nonfinite) {
   __shared__ float sv[4];
   __shared__ int si[4];
   const float* x = logits + (long)blockIdx.x * V;
   float bv = -INFINITY;
   int bi = 0x7fffffff;
-  for (int i = threadIdx.x; i < nlim; i += 256) argmax_merge(bv, bi, x[i], i);
+  int bad = 0;
+  for (int i = threadIdx.x; i < nlim; i += 256) {
+    const float v = x[i];
+    bad |= !(fabsf(v) <= 3.0e38f);
+    argmax_merge(bv, bi, v, i);
+  }
+  bad = __syncthreads_or(bad);
   const int b = block_argmax(bv, bi, sv, si);
-  if (threadIdx.x == 0) y[blockIdx.x] = b;
+  if (threadIdx.x == 0) {
+    y[blockIdx.x] = b;
+    if (bad && nonfinite) atomicAdd(nonfinite, 1ull);
+  }
 }

@@ -30,7 +30,7 @@ struct StateDev {
   int* alive;         // [1] unfinished sequences; doubles as the run flag of the step
   unsigned long long* acc_hist;  // [3][32]: accepted lengths of steps whose block carried coordinate-level drafts only /
                                  // a fresh point-level prediction / a fresh face-level prediction
-  unsigned long long* counters;  // [0] steps, [1] tokens
+  unsigned long long* counters;  // [0] steps, [1] tokens, [2] verify rows with a non-finite logit
   int* kind;                     // [S] which of the three the block built by the last draft was
 };
 
@@ -432,10 +432,12 @@ __global__ __launch_bounds__(256) void k_sample_rows(StateDev st, Dims D, const 
   __syncthreads();
   float sum = 0.f;
   for (int j = threadIdx.x; j < nlim; j += 256) sum += expf((x[j] - mx) * invT);
+  // an infinity or a NaN among the logits shows in the sum (inf - inf, or NaN itself)
   sum = wave_sum(sum);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = sum;
   __syncthreads();
   const float invZp = 1.0f / (sh[0] + sh[1] + sh[2] + sh[3]);
+  if (threadIdx.x == 0 && !(fabsf(invZp) <= 3.0e38f && fabsf(mx) <= 3.0e38f)) atomicAdd(st.counters + 2, 1ull);
   __syncthreads();
   auto pf = [&](int j) { return expf((x[j] - mx) * invT) * invZp; };
   const int pos = st.P[s] + i + 1;                       // the token this row decides

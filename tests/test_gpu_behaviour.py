@@ -431,3 +431,27 @@ def test_config3_real_widths_at_context(say):
     parity_harness.PROGRESS = None
     print(rep, "fill flips", flips, flush=True)
     assert rep.steps == 4 and len(rep.accepted) == 4 * 2 and len(set(rep.accepted)) > 1
+
+
+@pytest.mark.parametrize("name", ["t_bf16_99", "t_bf16_99_b1"])
+def test_half_precision_overflow_is_counted(name):
+    """Activations of the half-precision path beyond 65504 become infinities without a trap.  A run with an outlier weight
+    (one FFN up projection scaled by 2^24, still bf16-valued) must say so: fm_stats.nonfinite_rows counts the verify rows
+    whose logits were not finite; a healthy run counts none.  Both verify paths."""
+    _need_gpu()
+    from paper_2511_15618_amd import FlashMesh
+    from paper_2511_15618_amd.binding import config_struct
+    cfg = si.TEST_CONFIGS[name]
+    counts = []
+    for scale in (1.0, 2.0 ** 24):
+        w = si.make_weights(cfg, 0)
+        w["cpre.0.w1"] = w["cpre.0.w1"] * scale
+        fm = FlashMesh(config_struct(cfg))
+        fm.load_weights(si.pack_blob(cfg, w))
+        for s in range(cfg.batch):
+            fm.prefill_condition(s, torch.from_numpy(si.make_memory(cfg, s)).cuda())
+        out, n, st = fm.generate(4, True)
+        counts.append(int(st.nonfinite_rows))
+        assert int(n.min()) == 36                     # the loop still ends at the budget
+    print("non-finite rows: healthy", counts[0], "with the outlier", counts[1], flush=True)
+    assert counts[0] == 0 and counts[1] > 0
