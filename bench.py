@@ -163,6 +163,7 @@ class _Totals:
     steps = 0
     tokens = 0
     ms_total = 0.0
+    nonfinite_rows = 0
 
 
 def generate_in_stages(fm, faces, what, stage=500):
@@ -176,6 +177,7 @@ def generate_in_stages(fm, faces, what, stage=500):
         tot.steps += int(st.steps)
         tot.tokens += int(st.tokens)
         tot.ms_total += float(st.ms_total)
+        tot.nonfinite_rows += int(st.nonfinite_rows)
         print(f"bench: {what}: {done} / {faces} faces, {tot.steps} steps, {tot.ms_total / 1e3:.1f} s", file=sys.stderr, flush=True)
     return out, n, tot
 

@@ -9,7 +9,7 @@
 // and MFMA cost, which is what holds the logits inside the stated tolerance.
 typedef _Float16 f16_t;
 
-#define FM_HD 64          // head dimension (all supported configurations)
+#define FM_HD 64          // head width the single-launch verify kernel and the fused q,k,v epilogue are written for
 #define FM_WAVE 64
 
 template <typename T> struct Store;
