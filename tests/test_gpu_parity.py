@@ -208,7 +208,7 @@ def test_config4_shape_short_lockstep(say):
     assert rep.steps == 4 and len(rep.accepted) == 4 * cfg.batch
 
 
-@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99", "t_bf16_hd96", "t_bf16_d768_h8", "t_bf16_d1024_h8", "config1"])
+@pytest.mark.parametrize("name", ["t_f32_99", "t_bf16_99", "t_bf16_hd96", "t_bf16_d768_h8", "t_bf16_d1024_h8", "config1", "config2"])
 def test_condition_kv_element_by_element(name):
     """fm_prefill_condition against the definition K_mem = W_k c, V_mem = W_v c (Sec. 3.1), every element of every block:
     the per-block launches (small memories), the tiled matrix-unit kernel (memories of whole 256-row tiles) in all three
@@ -218,7 +218,10 @@ def test_condition_kv_element_by_element(name):
     from oracle.hourglass import Model
     from paper_2511_15618_amd import FlashMesh
     from paper_2511_15618_amd.binding import config_struct
-    cfg = si.CONFIGS[1].replace(faces=10) if name == "config1" else si.TEST_CONFIGS[name]
+    cfg = si.CONFIGS[int(name[-1])].replace(faces=10) if name.startswith("config") else si.TEST_CONFIGS[name]
+    # configs[2] is the shape the prefill figure of the benchmark is measured on (4096 x 1024 memory, 40 blocks): every
+    # element of the first and last block of each stack (the float64 reference of all 40 would take minutes)
+    only = {0, 3, 4, 11, 12, 27, 28, 35, 36, 39} if name == "config2" else None
     print("case condition K/V", name, flush=True)
     w = si.make_weights(cfg, 0)
     model = Model(cfg, w)
@@ -234,6 +237,9 @@ def test_condition_kv_element_by_element(name):
         for st in ("cpre", "vpre", "face", "vpost", "cpost"):
             for i in range(model.layers[st]):
                 pfx = f"{st}.{i}."
+                if only is not None and b not in only:
+                    b += 1
+                    continue
                 K, V = model.mem_kv(pfx, mem)                      # [M, H, hd] float64
                 dk, dv = fm.debug_mem_kv(s, b)
                 for ref, dev, wn in ((K, dk, "ck"), (V, dv, "cv")):
